@@ -1,0 +1,205 @@
+/*
+ * umas.h - C ABI of libumas: the model-local worker step of UnityMAS-O on one gfx950 GPU.
+ *
+ * Four calls follow the paper's statement of the problem (logical roles V, the
+ * agent-to-model map phi: V -> M, trajectories with reward signals at role, turn and
+ * trajectory level, model-local buffers B_i and PPO-style per-model updates):
+ *
+ *   umas_assign_token_rewards  reward composition, routing through phi, placement on tokens
+ *   umas_advantages            GAE as a masked, segmented reverse scan
+ *   umas_policy_logprobs       LM-head scoring: log-prob of the taken token, logsumexp, entropy
+ *   umas_ppo_loss_fwd_bwd      scoring + clipped surrogate + backward to hidden states and weights
+ *
+ * Conventions
+ *   - THIN metadata (graph, reward scalars) are HOST pointers, caller-owned, read during the
+ *     call only (the paper's controller keeps exactly this: role ids, routing ids, reward
+ *     metadata).  FAT tensors (masks, rewards per token, hidden states, weights, outputs,
+ *     workspace) are DEVICE pointers, caller-allocated; the library owns no memory.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default
+ *     stream).  No call synchronises with the device, except umas_assign_token_rewards, which
+ *     copies the thin host arrays to the device and waits for those copies (not for its
+ *     kernels) so that the caller may free them on return.  Results, including loss
+ *     statistics, stay on the device.
+ *   - Every call returns a umas_status.  Argument errors are found on the host before any
+ *     launch, leave outputs untouched and set a thread-local message (umas_last_error).
+ *   - Workspace sizes come from the umas_*_workspace_bytes queries; workspace must be
+ *     256-byte aligned.  Passing less than the required size returns UMAS_EWORKSPACE.
+ *   - One GPU, one process; calls on different streams may run concurrently only with
+ *     disjoint outputs and workspaces.
+ */
+#ifndef UMAS_H
+#define UMAS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  UMAS_OK = 0,
+  UMAS_EINVAL = -1,     /* NULL required pointer, value out of range, malformed graph */
+  UMAS_ESHAPE = -2,     /* size not supported (d not a multiple of 8 for bf16, too many models, ...) */
+  UMAS_EDTYPE = -3,     /* unknown umas_dtype */
+  UMAS_EWORKSPACE = -4, /* workspace NULL, misaligned or too small */
+  UMAS_EHIP = -5        /* a HIP runtime call failed (message carries hipGetErrorString) */
+} umas_status;
+
+typedef enum { UMAS_F32 = 0, UMAS_BF16 = 1 } umas_dtype;
+
+enum { UMAS_PLACE_LAST = 0, UMAS_PLACE_ALL = 1 };
+enum { UMAS_SEG_TURN = 0, UMAS_SEG_TRAJ = 1 };
+enum { UMAS_MAX_MODELS = 8, UMAS_MAX_ROLES = 64 };
+
+/* Message of the last failing call on this thread; static storage, never freed by the caller. */
+const char* umas_last_error(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Thin inputs (HOST pointers).
+ * The executed workflow of every trajectory in its linearised view (s_0,k_1,a_1,...,k_T,a_T)
+ * (Section "Workflow Graphs and Execution"): turn = one role invocation, turns of a trajectory
+ * are consecutive and in linearised order, tokens of a turn are consecutive in the global
+ * token order.  The predecessor CSR carries the control-flow record C of the trajectory; it is
+ * validated (same trajectory, earlier turn) and not used by the arithmetic, which follows the
+ * linearised order as the paper's objective does.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t n_roles;              /* |V| <= UMAS_MAX_ROLES */
+  int32_t n_models;             /* |M| <= UMAS_MAX_MODELS */
+  int32_t n_traj;
+  int32_t n_turns;
+  int64_t n_tokens;
+  const int32_t* role_to_model; /* [n_roles]    phi (Section "Agent--LLM Mapping") */
+  const int32_t* traj_turn_off; /* [n_traj+1]   CSR: turns of trajectory b */
+  const int32_t* turn_role;     /* [n_turns]    active role k_t of each turn */
+  const int64_t* turn_tok_off;  /* [n_turns+1]  CSR: tokens of turn u in the global token order */
+  const int32_t* turn_pred_off; /* [n_turns+1]  CSR of predecessor turns, or NULL = chain */
+  const int32_t* turn_pred;     /* [turn_pred_off[n_turns]] global turn ids, or NULL */
+  const int32_t* traj_group;    /* [n_traj] group id >= 0 for reward normalisation, or NULL = none */
+} umas_graph;
+
+/* Reward scalars at the three levels of the reward interface and the optional weights of
+ * r_v = lam_node r_node + lam_turn r_turn + lam_traj r_traj (Section "Agent-Specific Reward
+ * Interface").  NULL level = 0, NULL weight = 1.  With traj_group the trajectory-level
+ * reward is z-scored inside each group first: (R - mean) / (population std + norm_eps). */
+typedef struct {
+  const float* role_reward;     /* [n_traj*n_roles] one scalar per (trajectory, role), or NULL */
+  const float* turn_reward;     /* [n_turns]        one scalar per invocation, or NULL */
+  const float* traj_reward;     /* [n_traj]         one scalar per trajectory, or NULL */
+  const float* w_role;          /* [n_roles] or NULL */
+  const float* w_turn;          /* [n_roles] or NULL */
+  const float* w_traj;          /* [n_roles] or NULL */
+  int32_t place_mode;           /* UMAS_PLACE_LAST: last mask=1 token of the turn; UMAS_PLACE_ALL: every mask=1 token */
+  float norm_eps;               /* > 0 */
+} umas_rewards;
+
+/* ------------------------------------------------------------------------------------------
+ * Model-local streams (DEVICE pointers, caller-allocated, all written by
+ * umas_assign_token_rewards).  Stream m is the buffer B_m of the model-local worker group
+ * (Section "Model-Local Buffers"): tokens of all turns with phi(role) = m, turns in ascending
+ * global id, streams stored back to back.  "model-local order" below means this order.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int64_t* model_tok_off;     /* [n_models+1]  stream m = positions [off[m], off[m+1]) */
+  int64_t* perm;              /* [n_tokens]    model-local position -> global token index */
+  int32_t* tok_turn;          /* [n_tokens]    global turn id of each token */
+  int32_t* tok_role;          /* [n_tokens]    role id (kept under sharing for role-level reporting) */
+  uint8_t* tok_mask;          /* [n_tokens]    mask gathered into model-local order */
+  float*   tok_reward;        /* [n_tokens]    reward placed on tokens */
+  int64_t* turn_seg_off;      /* [n_turns+1]   token offsets of the turn segments, grouped by model */
+  int32_t* seg_turn;          /* [n_turns]     global turn id of turn segment s */
+  int32_t* model_turn_off;    /* [n_models+1]  turn segments of model m */
+  int64_t* traj_seg_off;      /* [n_turns+1]   token offsets of trajectory runs (maximal runs of one
+                                               trajectory inside a stream); entries past the count are n_tokens */
+  int32_t* model_trajrun_off; /* [n_models+1]  trajectory runs of model m; [n_models] = their number */
+  int32_t* rowsel;            /* [n_tokens]    per model, ascending stream-relative positions with mask=1 */
+  int64_t* model_rowsel_off;  /* [n_models+1]  rowsel of model m = [off[m], off[m+1]) */
+  float*   turn_scalar;       /* [n_turns]     composed reward of each turn, global turn order */
+  int32_t* turn_step;         /* [n_turns]     1-based position of the turn inside its trajectory */
+} umas_streams;
+
+/* Bytes of workspace umas_assign_token_rewards needs for this graph. */
+size_t umas_assign_workspace_bytes(const umas_graph* graph);
+
+/* Steps a1-a3: compose per-turn rewards, normalise, route through phi, place on tokens
+ * (Sections "Agent-Specific Reward Interface", "Model-Local Buffers", paragraphs "Reward
+ * assembly and commitment" and "Batch construction").
+ *   tok_mask_global  DEVICE uint8 [n_tokens], global token order, 1 = action token
+ *   out              HOST struct of DEVICE pointers, all non-NULL
+ * Errors (nothing launched): NULL pointers, non-monotone CSR, role or phi out of range,
+ * predecessor outside the trajectory or not earlier, negative group id, bad place_mode. */
+umas_status umas_assign_token_rewards(const umas_graph* graph, const umas_rewards* rewards,
+                                      const uint8_t* tok_mask_global, const umas_streams* out,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+size_t umas_advantages_workspace_bytes(int64_t n_tokens);
+
+/* Step a4: A_t = sum_l (gamma lam)^l delta_{t+l}, delta_t = r_t + gamma V(s_{t+1}) - V(s_t)
+ * (paragraph "Advantage computation and policy evaluation") as a masked, segmented reverse
+ * scan over the model-local streams.  Segments: turns (UMAS_SEG_TURN) or trajectory runs
+ * (UMAS_SEG_TRAJ); V and A past a segment end are 0; mask=0 tokens are skipped by the
+ * recurrence and output 0.  In UMAS_SEG_TRAJ the carried state is multiplied by
+ * gamma_turn^(step difference) when the scan crosses a turn boundary, which reproduces the
+ * objective's gamma^(t-1) discount over role invocations.
+ *   value  DEVICE float [n_tokens] in model-local order, or NULL (= 0)
+ *   adv, ret  DEVICE float [n_tokens]; ret = adv + value at mask=1 tokens */
+umas_status umas_advantages(const umas_streams* streams, int64_t n_tokens, int32_t n_turns,
+                            const float* value, float gamma, float lam, float gamma_turn,
+                            int32_t seg_mode, float* adv, float* ret,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+size_t umas_policy_logprobs_workspace_bytes(int64_t n_sel, int32_t d, int32_t V, umas_dtype dtype);
+
+/* Step a5: for each selected row i, z = W h_i (float accumulate), lse = log sum_v exp z_v,
+ * logp = z[ids[i]] - lse, entropy = lse - sum_v softmax(z)_v z_v ("old log probabilities",
+ * paragraph "Advantage computation and policy evaluation").  Logits are never written out.
+ *   H       DEVICE [n_rows, d] row-major, dtype;  W  DEVICE [V, d] row-major, dtype
+ *   ids     DEVICE int32 [n_rows]; a row whose id is outside [0,V) gets logp = entropy = 0
+ *   rowsel  DEVICE int32 [n_sel] ascending rows to score, or NULL with n_sel = n_rows (all)
+ *   logp, lse, entropy  DEVICE float [n_rows]; rows not selected are set to 0; entropy may be NULL
+ * bf16 needs d % 8 == 0. */
+umas_status umas_policy_logprobs(const void* H, const void* W, umas_dtype dtype, int64_t n_rows,
+                                 int32_t d, int32_t V, const int32_t* ids, const int32_t* rowsel,
+                                 int64_t n_sel, float* logp, float* lse, float* entropy,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Row 0: the model's totals; rows 1..n_roles: the same numbers over the rows of one role. */
+typedef struct {
+  float loss;              /* mean over scored rows of max(-A ratio, -A clip(ratio, 1-eps, 1+eps)) */
+  float clip_frac;         /* share of scored rows whose clipped term is strictly larger */
+  float entropy_mean;
+  float approx_kl;         /* mean of logp_old - logp */
+  int64_t n_scored;        /* rows in the mean (selected rows; rows with invalid ids add 0 to the sums) */
+  int64_t n_invalid_ids;   /* selected rows whose token id is outside [0,V) */
+} umas_loss_stats;
+
+/* Smallest workspace the call accepts and the size at which it runs in the fewest passes. */
+size_t umas_ppo_loss_workspace_bytes_min(int64_t n_sel, int32_t d, int32_t V, umas_dtype dtype, int32_t n_roles);
+size_t umas_ppo_loss_workspace_bytes(int64_t n_sel, int32_t d, int32_t V, umas_dtype dtype, int32_t n_roles);
+
+/* Steps a5-a7 for one model's stream (each worker group updates its own model, paragraph
+ * "Model-specific updates and synchronization"): scoring as above, then the single-clip PPO
+ * surrogate (PPO-style loop after Schulman et al. 2017) with the token mean over the n_sel
+ * selected rows as loss, then the backward through the LM head:
+ *   ratio = exp(logp - logp_old); L = max(-A ratio, -A clip(ratio, 1-eps, 1+eps))
+ *   g = dloss/dlogp;  dz_iv = g_i (1[v = ids[i]] - softmax(z_i)_v);  dH = dz W;  dW = dz^T H
+ *   logp_old, adv  DEVICE float [n_rows]
+ *   tok_role       DEVICE int32 [n_rows] or NULL with n_roles = 0
+ *   stats          DEVICE umas_loss_stats [1 + n_roles]
+ *   logp_new       DEVICE float [n_rows] or NULL
+ *   dH             DEVICE [n_rows, d] in the dtype of H; rows not selected are set to 0
+ *   dW             DEVICE float [V, d]; accumulate_dW = 0 overwrites, 1 adds
+ * clip_eps must lie in (0,1).  entropy_coef must be 0 (the entropy bonus is not built). */
+umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_dtype dtype, int64_t n_rows,
+                                  int32_t d, int32_t V, const int32_t* ids, const int32_t* rowsel,
+                                  int64_t n_sel, const float* logp_old, const float* adv,
+                                  const int32_t* tok_role, int32_t n_roles, float clip_eps,
+                                  float entropy_coef, int32_t accumulate_dW, umas_loss_stats* stats,
+                                  float* logp_new, void* dH, float* dW,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UMAS_H */

@@ -1,0 +1,266 @@
+"""ctypes binding of libumas.so (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch
+
+PLACE_LAST, PLACE_ALL = 0, 1
+SEG_TURN, SEG_TRAJ = 0, 1
+UMAS_F32, UMAS_BF16 = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+class UmasError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libumas status {code}: {message}")
+        self.code = code
+
+
+class _Graph(C.Structure):
+    _fields_ = [("n_roles", C.c_int32), ("n_models", C.c_int32), ("n_traj", C.c_int32), ("n_turns", C.c_int32),
+                ("n_tokens", C.c_int64), ("role_to_model", C.c_void_p), ("traj_turn_off", C.c_void_p),
+                ("turn_role", C.c_void_p), ("turn_tok_off", C.c_void_p), ("turn_pred_off", C.c_void_p),
+                ("turn_pred", C.c_void_p), ("traj_group", C.c_void_p)]
+
+
+class _Rewards(C.Structure):
+    _fields_ = [("role_reward", C.c_void_p), ("turn_reward", C.c_void_p), ("traj_reward", C.c_void_p),
+                ("w_role", C.c_void_p), ("w_turn", C.c_void_p), ("w_traj", C.c_void_p),
+                ("place_mode", C.c_int32), ("norm_eps", C.c_float)]
+
+
+_STREAM_FIELDS = ["model_tok_off", "perm", "tok_turn", "tok_role", "tok_mask", "tok_reward", "turn_seg_off",
+                  "seg_turn", "model_turn_off", "traj_seg_off", "model_trajrun_off", "rowsel",
+                  "model_rowsel_off", "turn_scalar", "turn_step"]
+
+
+class _Streams(C.Structure):
+    _fields_ = [(name, C.c_void_p) for name in _STREAM_FIELDS]
+
+
+STATS_DTYPE = np.dtype([("loss", "<f4"), ("clip_frac", "<f4"), ("entropy_mean", "<f4"), ("approx_kl", "<f4"),
+                        ("n_scored", "<i8"), ("n_invalid_ids", "<i8")])
+
+
+@dataclass
+class Streams:
+    """Device tensors written by umas_assign_token_rewards (model-local order)."""
+    n_tokens: int
+    n_turns: int
+    n_models: int
+    model_tok_off: torch.Tensor
+    perm: torch.Tensor
+    tok_turn: torch.Tensor
+    tok_role: torch.Tensor
+    tok_mask: torch.Tensor
+    tok_reward: torch.Tensor
+    turn_seg_off: torch.Tensor
+    seg_turn: torch.Tensor
+    model_turn_off: torch.Tensor
+    traj_seg_off: torch.Tensor
+    model_trajrun_off: torch.Tensor
+    rowsel: torch.Tensor
+    model_rowsel_off: torch.Tensor
+    turn_scalar: torch.Tensor
+    turn_step: torch.Tensor
+
+    def _c(self) -> _Streams:
+        s = _Streams()
+        for name in _STREAM_FIELDS:
+            setattr(s, name, getattr(self, name).data_ptr())
+        return s
+
+
+_LIB = None
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libumas.so")
+
+
+def load_library():
+    """Load libumas.so built in-tree; there is no fallback when it is missing."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(path)
+    lib.umas_last_error.restype = C.c_char_p
+    for name in ("umas_assign_workspace_bytes", "umas_advantages_workspace_bytes",
+                 "umas_policy_logprobs_workspace_bytes", "umas_ppo_loss_workspace_bytes",
+                 "umas_ppo_loss_workspace_bytes_min"):
+        getattr(lib, name).restype = C.c_size_t
+    lib.umas_assign_workspace_bytes.argtypes = [C.c_void_p]
+    lib.umas_advantages_workspace_bytes.argtypes = [C.c_int64]
+    lib.umas_policy_logprobs_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int]
+    lib.umas_ppo_loss_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int, C.c_int32]
+    lib.umas_ppo_loss_workspace_bytes_min.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int, C.c_int32]
+    lib.umas_assign_token_rewards.restype = C.c_int
+    lib.umas_assign_token_rewards.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_size_t, C.c_void_p]
+    lib.umas_advantages.restype = C.c_int
+    lib.umas_advantages.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_float, C.c_float, C.c_float,
+                                    C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.umas_policy_logprobs.restype = C.c_int
+    lib.umas_policy_logprobs.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int32, C.c_int32,
+                                         C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.umas_ppo_loss_fwd_bwd.restype = C.c_int
+    lib.umas_ppo_loss_fwd_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int32, C.c_int32,
+                                          C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_int32, C.c_float, C.c_float, C.c_int32, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    _LIB = lib
+    return lib
+
+
+def _check(lib, status: int):
+    if status != 0:
+        raise UmasError(status, lib.umas_last_error().decode())
+
+
+def _host(arr, dtype):
+    """Contiguous host array of the ABI's type, or None; returns (array kept alive, pointer)."""
+    if arr is None:
+        return None, None
+    a = np.ascontiguousarray(arr, dtype=dtype)
+    return a, a.ctypes.data
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return UMAS_F32
+    if t.dtype == torch.bfloat16:
+        return UMAS_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def umas_assign_token_rewards(*, n_roles, n_models, role_to_model, traj_turn_off, turn_role, turn_tok_off,
+                              tok_mask_global: torch.Tensor, turn_pred_off=None, turn_pred=None, traj_group=None,
+                              role_reward=None, turn_reward=None, traj_reward=None, w_role=None, w_turn=None,
+                              w_traj=None, place_mode=PLACE_LAST, norm_eps=1e-6) -> Streams:
+    lib = load_library()
+    keep = []
+
+    def h(a, dt):
+        arr, p = _host(a, dt)
+        keep.append(arr)
+        return p
+
+    traj_turn_off = np.asarray(traj_turn_off)
+    turn_tok_off = np.asarray(turn_tok_off)
+    n_traj, n_turns = len(traj_turn_off) - 1, len(turn_tok_off) - 1
+    n_tokens = int(tok_mask_global.numel())
+    g = _Graph(n_roles, n_models, n_traj, n_turns, n_tokens, h(role_to_model, np.int32), h(traj_turn_off, np.int32),
+               h(turn_role, np.int32), h(turn_tok_off, np.int64), h(turn_pred_off, np.int32), h(turn_pred, np.int32),
+               h(traj_group, np.int32))
+    r = _Rewards(h(role_reward, np.float32), h(turn_reward, np.float32), h(traj_reward, np.float32),
+                 h(w_role, np.float32), h(w_turn, np.float32), h(w_traj, np.float32), place_mode, norm_eps)
+    dev = tok_mask_global.device
+    i64 = dict(dtype=torch.int64, device=dev)
+    i32 = dict(dtype=torch.int32, device=dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    out = Streams(
+        n_tokens=n_tokens, n_turns=n_turns, n_models=n_models,
+        model_tok_off=torch.empty(n_models + 1, **i64), perm=torch.empty(n_tokens, **i64),
+        tok_turn=torch.empty(n_tokens, **i32), tok_role=torch.empty(n_tokens, **i32),
+        tok_mask=torch.empty(n_tokens, dtype=torch.uint8, device=dev), tok_reward=torch.empty(n_tokens, **f32),
+        turn_seg_off=torch.empty(n_turns + 1, **i64), seg_turn=torch.empty(max(n_turns, 1), **i32),
+        model_turn_off=torch.empty(n_models + 1, **i32), traj_seg_off=torch.empty(n_turns + 1, **i64),
+        model_trajrun_off=torch.empty(n_models + 1, **i32), rowsel=torch.empty(max(n_tokens, 1), **i32),
+        model_rowsel_off=torch.empty(n_models + 1, **i64), turn_scalar=torch.empty(max(n_turns, 1), **f32),
+        turn_step=torch.empty(max(n_turns, 1), **i32))
+    ws = _workspace(lib.umas_assign_workspace_bytes(C.addressof(g)), dev)
+    cs = out._c()
+    _check(lib, lib.umas_assign_token_rewards(C.addressof(g), C.addressof(r), _ptr(tok_mask_global), C.addressof(cs),
+                                              ws.data_ptr(), ws.numel(), _stream()))
+    return out
+
+
+def umas_advantages(streams: Streams, value: Optional[torch.Tensor], gamma, lam, gamma_turn=1.0, seg_mode=SEG_TURN):
+    lib = load_library()
+    dev = streams.tok_reward.device
+    adv = torch.empty(streams.n_tokens, dtype=torch.float32, device=dev)
+    ret = torch.empty(streams.n_tokens, dtype=torch.float32, device=dev)
+    ws = _workspace(lib.umas_advantages_workspace_bytes(streams.n_tokens), dev)
+    cs = streams._c()
+    _check(lib, lib.umas_advantages(C.addressof(cs), streams.n_tokens, streams.n_turns, _ptr(value), gamma, lam,
+                                    gamma_turn, seg_mode, adv.data_ptr(), ret.data_ptr(), ws.data_ptr(), ws.numel(),
+                                    _stream()))
+    return adv, ret
+
+
+def umas_policy_logprobs(H: torch.Tensor, W: torch.Tensor, ids: torch.Tensor, rowsel: Optional[torch.Tensor] = None,
+                         want_entropy=True, workspace: Optional[torch.Tensor] = None):
+    lib = load_library()
+    n_rows, d = H.shape
+    V = W.shape[0]
+    n_sel = n_rows if rowsel is None else int(rowsel.numel())
+    dt = _dtype_code(H)
+    dev = H.device
+    logp = torch.empty(n_rows, dtype=torch.float32, device=dev)
+    lse = torch.empty(n_rows, dtype=torch.float32, device=dev)
+    ent = torch.empty(n_rows, dtype=torch.float32, device=dev) if want_entropy else None
+    ws = workspace if workspace is not None else _workspace(lib.umas_policy_logprobs_workspace_bytes(n_sel, d, V, dt), dev)
+    _check(lib, lib.umas_policy_logprobs(H.data_ptr(), W.data_ptr(), dt, n_rows, d, V, ids.data_ptr(), _ptr(rowsel),
+                                         n_sel, logp.data_ptr(), lse.data_ptr(), _ptr(ent), ws.data_ptr(), ws.numel(),
+                                         _stream()))
+    return logp, lse, ent
+
+
+def ppo_workspace_bytes(n_sel, d, V, dtype: torch.dtype, n_roles, minimum=False) -> int:
+    lib = load_library()
+    code = UMAS_BF16 if dtype == torch.bfloat16 else UMAS_F32
+    f = lib.umas_ppo_loss_workspace_bytes_min if minimum else lib.umas_ppo_loss_workspace_bytes
+    return int(f(n_sel, d, V, code, n_roles))
+
+
+def umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv, tok_role, n_roles, clip_eps, *, entropy_coef=0.0,
+                          accumulate_dW=False, dW=None, dH=None, logp_new=None, stats=None, workspace=None):
+    lib = load_library()
+    n_rows, d = H.shape
+    V = W.shape[0]
+    n_sel = n_rows if rowsel is None else int(rowsel.numel())
+    dt = _dtype_code(H)
+    dev = H.device
+    if dW is None:
+        dW = torch.empty((V, d), dtype=torch.float32, device=dev)
+    if dH is None:
+        dH = torch.empty_like(H)
+    if logp_new is None:
+        logp_new = torch.empty(n_rows, dtype=torch.float32, device=dev)
+    if stats is None:
+        stats = torch.empty((1 + n_roles) * STATS_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+    ws = workspace if workspace is not None else _workspace(
+        lib.umas_ppo_loss_workspace_bytes(n_sel, d, V, dt, n_roles), dev)
+    _check(lib, lib.umas_ppo_loss_fwd_bwd(H.data_ptr(), W.data_ptr(), dt, n_rows, d, V, ids.data_ptr(), _ptr(rowsel),
+                                          n_sel, logp_old.data_ptr(), adv.data_ptr(), _ptr(tok_role), n_roles,
+                                          clip_eps, entropy_coef, 1 if accumulate_dW else 0, stats.data_ptr(),
+                                          logp_new.data_ptr(), dH.data_ptr(), dW.data_ptr(), ws.data_ptr(), ws.numel(),
+                                          _stream()))
+    return stats, logp_new, dH, dW
+
+
+def read_stats(stats: torch.Tensor) -> np.ndarray:
+    """Copy the device umas_loss_stats array to a numpy structured array (synchronises)."""
+    return stats.cpu().numpy().view(STATS_DTYPE)

@@ -1,0 +1,134 @@
+// Shared host/device helpers of libumas: error reporting, workspace carving, wave and
+// block primitives for 64-wide wavefronts.  gfx950 only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "../../include/umas.h"
+
+namespace umas {
+
+umas_status fail(umas_status code, const char* fmt, ...);
+
+#define UMAS_HIP(expr)                                                                 \
+  do {                                                                                 \
+    hipError_t e__ = (expr);                                                           \
+    if (e__ != hipSuccess)                                                             \
+      return ::umas::fail(UMAS_EHIP, "%s failed: %s", #expr, hipGetErrorString(e__)); \
+  } while (0)
+
+#define UMAS_LAUNCHED(name)                                                                  \
+  do {                                                                                       \
+    hipError_t e__ = hipGetLastError();                                                      \
+    if (e__ != hipSuccess)                                                                   \
+      return ::umas::fail(UMAS_EHIP, "launch of %s failed: %s", name, hipGetErrorString(e__)); \
+  } while (0)
+
+#define UMAS_REQUIRE(cond, code, ...) \
+  do {                                \
+    if (!(cond)) return ::umas::fail(code, __VA_ARGS__); \
+  } while (0)
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
+
+// Carves 256-byte aligned arrays out of a caller-provided workspace; with base == nullptr it
+// only measures.
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base(static_cast<char*>(b)) {}
+  template <typename T>
+  T* take(size_t n) {
+    size_t bytes = align_up(n * sizeof(T));
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+inline unsigned cdiv(size_t a, size_t b) { return static_cast<unsigned>((a + b - 1) / b); }
+
+// ------------------------------------------------------------------ device primitives
+constexpr int kWave = 64;
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+template <typename T>
+__device__ __forceinline__ T wave_max(T v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    T t = __shfl_xor(v, o, kWave);
+    v = t > v ? t : v;
+  }
+  return v;
+}
+template <typename T>
+__device__ __forceinline__ T wave_incl_scan(T v) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    T t = __shfl_up(v, o, kWave);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+
+// Exclusive prefix sum over the threads of a block (blockDim.x a multiple of 64, at most 1024).
+// `smem` holds at least 17 values of T.  Returns the exclusive prefix; *total gets the block sum.
+template <typename T>
+__device__ __forceinline__ T block_excl_scan(T v, T* smem, T* total) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int nwave = blockDim.x / kWave;
+  T incl = wave_incl_scan(v);
+  __syncthreads();  // smem may still be read from a previous use
+  if (lane == kWave - 1) smem[wave] = incl;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    T run = 0;
+    for (int w = 0; w < nwave; ++w) {
+      T t = smem[w];
+      smem[w] = run;
+      run += t;
+    }
+    smem[16] = run;
+  }
+  __syncthreads();
+  *total = smem[16];
+  return incl - v + smem[wave];
+}
+
+template <typename T>
+__device__ __forceinline__ T block_sum(T v, T* smem) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int nwave = blockDim.x / kWave;
+  v = wave_sum(v);
+  __syncthreads();
+  if (lane == 0) smem[wave] = v;
+  __syncthreads();
+  T r = 0;
+  for (int w = 0; w < nwave; ++w) r += smem[w];
+  return r;
+}
+
+// Largest j in [0, n] with off[j] <= x, for ascending off[0..n] and off[0] <= x.
+template <typename T>
+__device__ __forceinline__ int last_le(const T* __restrict__ off, int n, T x) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (off[mid] <= x) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+}  // namespace umas

@@ -1,0 +1,777 @@
+// LM-head scoring, the clipped PPO surrogate and the backward through the LM head.
+//
+// Scoring ("old log probabilities", paragraph "Advantage computation and policy evaluation"):
+// for every selected row z = W h, lse = log sum exp z, logp = z[y] - lse, entropy = lse -
+// sum softmax(z) z.  The bf16 path computes 256x256 logit tiles with MFMA and reduces each tile
+// to per-row (max, sum exp, sum exp*z, taken logit) in registers; logits never leave the chip.
+// Update (paragraph "Model-specific updates and synchronization", PPO after Schulman et al.
+// 2017): ratio = exp(logp - logp_old), L = max(-A ratio, -A clip(ratio)), g = dL/dlogp, then
+// dz = g (onehot - softmax) is recomputed tile by tile from H, W and lse, rounded to bf16 into a
+// bounded chunk buffer in both orientations, and dH = dz W, dW = dz^T H run as MFMA GEMMs.
+// The float32 path is a plain, unblocked implementation for small shapes.
+#include <math.h>
+
+#include "umas_common.h"
+#include "umas_mfma.h"
+
+namespace umas {
+namespace {
+
+using Cfg = TileCfg<256, 256, 2, 2>;
+constexpr int kGM = 4, kGN = 8;          // tile group resident on one XCD
+constexpr int kRowBlock = 256;
+constexpr float kNegInf = -INFINITY;
+
+__device__ __forceinline__ uint16_t f2bf(float x) {
+  return __builtin_bit_cast(uint16_t, static_cast<__bf16>(x));
+}
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+
+// Online-softmax partial: m = max z, s = sum exp(z - m), t = sum exp(z - m) z.
+struct Part {
+  float m, s, t;
+};
+__device__ __forceinline__ Part part_merge(Part x, Part y) {
+  if (x.m == kNegInf) return y;
+  if (y.m == kNegInf) return x;
+  const float M = fmaxf(x.m, y.m);
+  const float ex = __expf(x.m - M), ey = __expf(y.m - M);
+  return Part{M, x.s * ex + y.s * ey, x.t * ex + y.t * ey};
+}
+
+// ------------------------------------------------------------------ small helpers
+__global__ void k_fill_f32(float* __restrict__ p, int64_t n, float v) {
+  int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+__global__ void k_fill_u32(uint32_t* __restrict__ p, int64_t n, uint32_t v) {
+  int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+
+hipError_t fill_bytes_zero(void* p, size_t bytes, hipStream_t st) {
+  // bytes is a multiple of 4 for every buffer cleared here
+  const int64_t n = static_cast<int64_t>(bytes / 4);
+  if (n == 0) return hipSuccess;
+  const unsigned grid = static_cast<unsigned>(n / 256 + 1 < 65536 ? n / 256 + 1 : 65536);
+  hipLaunchKernelGGL(k_fill_u32, dim3(grid), dim3(256), 0, st, static_cast<uint32_t*>(p), n, 0u);
+  return hipGetLastError();
+}
+
+// out[c, r] = in[row(r), c] for r < n_r (row(r) = rowsel[r] or r), zero for n_r <= r < ld_out;
+// bf16 elements, in is [*, n_c] row-major, out is [n_c, ld_out].
+__global__ void k_transpose_bf16(const uint16_t* __restrict__ in, int64_t n_c, const int32_t* __restrict__ rowsel,
+                                 int64_t n_r, uint16_t* __restrict__ out, int64_t ld_out) {
+  __shared__ uint16_t tile[64][66];
+  const int64_t r0 = static_cast<int64_t>(blockIdx.x) * 64, c0 = static_cast<int64_t>(blockIdx.y) * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;   // 256 threads: 4 rows per pass
+  for (int i = ty; i < 64; i += 4) {
+    const int64_t r = r0 + i, c = c0 + tx;
+    uint16_t v = 0;
+    if (r < n_r && c < n_c) {
+      const int64_t src = rowsel ? rowsel[r] : r;
+      v = in[src * n_c + c];
+    }
+    tile[i][tx] = v;
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int64_t c = c0 + i, r = r0 + tx;
+    if (c < n_c && r < ld_out) out[c * ld_out + r] = tile[tx][i];
+  }
+}
+
+// ------------------------------------------------------------------ bf16: logit tiles -> partials
+// A = W (vocabulary rows on the M side, so one lane sees many vocabulary entries of one token),
+// B = selected rows of H.  partial[tile_m][n] = (m, s, t, taken logit or 0).
+__global__ void __launch_bounds__(Cfg::T)
+k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
+              const int32_t* __restrict__ rowsel, int64_t n_sel, const int32_t* __restrict__ ids,
+              int tiles_m, int tiles_n, float4* __restrict__ partial, int64_t n_pad) {
+  using C = Cfg;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * C::STAGE];
+  int tile_m, tile_n;
+  if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
+  const int m0 = tile_m * C::BM;
+  const int64_t n0 = static_cast<int64_t>(tile_n) * C::BN;
+  const uint16_t* pa[C::NA];
+  const uint16_t* pb[C::NB];
+  const int kofs = slot_kofs();
+#pragma unroll
+  for (int i = 0; i < C::NA; ++i) {
+    const int v = m0 + slot_row<C>(i);
+    pa[i] = v < V ? W + static_cast<int64_t>(v) * d + kofs : nullptr;
+  }
+#pragma unroll
+  for (int i = 0; i < C::NB; ++i) {
+    const int64_t n = n0 + slot_row<C>(i);
+    pb[i] = n < n_sel ? H + static_cast<int64_t>(rowsel ? rowsel[n] : n) * d + kofs : nullptr;
+  }
+  floatx16 acc[C::TM][C::TN];
+#pragma unroll
+  for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < C::TN; ++tn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
+  mfma_mainloop<C>(pa, pb, d, lds, acc);
+
+  // epilogue: the tile buffers are free now
+  float* s_part = reinterpret_cast<float*>(lds);          // [WM][BN][3]
+  float* s_zy = s_part + C::WM * C::BN * 3;               // [BN]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / C::WN;
+  if (threadIdx.x < C::BN) s_zy[threadIdx.x] = 0.f;
+  __syncthreads();
+  const int vbase = m0 + wm * C::WTM + (lane >> 5) * 4;   // vocabulary id of element (tm=0, r=0)
+  const bool tail = m0 + C::BM > V;
+#pragma unroll
+  for (int tn = 0; tn < C::TN; ++tn) {
+    const int col = acc_col<C>(tn);
+    const int64_t n = n0 + col;
+    float m = kNegInf;
+#pragma unroll
+    for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        if (tail && vbase + tm * 32 + (r >> 2) * 8 + (r & 3) >= V) acc[tm][tn][r] = kNegInf;
+        m = fmaxf(m, acc[tm][tn][r]);
+      }
+    float s = 0.f, t = 0.f;
+    if (m != kNegInf) {
+#pragma unroll
+      for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float z = acc[tm][tn][r];
+          const float e = __expf(z - m);
+          s += e;
+          t += (z == kNegInf) ? 0.f : e * z;
+        }
+    }
+    Part p{m, s, t};
+    Part q{__shfl_xor(p.m, 32, kWave), __shfl_xor(p.s, 32, kWave), __shfl_xor(p.t, 32, kWave)};
+    p = part_merge(p, q);
+    if (lane < 32) {
+      float* dst = s_part + (wm * C::BN + col) * 3;
+      dst[0] = p.m; dst[1] = p.s; dst[2] = p.t;
+    }
+    if (n < n_sel) {
+      const int y = ids[rowsel ? rowsel[n] : n];
+      const int rel = y - vbase;                           // offset from this lane's first element
+      if (y >= 0 && y < V && rel >= 0 && rel < C::WTM && ((rel >> 2) & 1) == 0) {
+        float zy = 0.f;
+#pragma unroll
+        for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (tm * 32 + (r >> 2) * 8 + (r & 3) == rel) zy = acc[tm][tn][r];
+        s_zy[col] = zy;
+      }
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < C::BN) {
+    const int col = threadIdx.x;
+    Part p{kNegInf, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < C::WM; ++w) {
+      const float* src = s_part + (w * C::BN + col) * 3;
+      p = part_merge(p, Part{src[0], src[1], src[2]});
+    }
+    if (n0 + col < n_pad) partial[static_cast<int64_t>(tile_m) * n_pad + n0 + col] = make_float4(p.m, p.s, p.t, s_zy[col]);
+  }
+}
+
+// Merge the per-tile partials of each selected row; compact results and optional scatter.
+__global__ void k_score_finalize(const float4* __restrict__ partial, int tiles_m, int64_t n_pad, int64_t n_sel,
+                                 const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
+                                 float* __restrict__ logp_c, float* __restrict__ lse_c, float* __restrict__ ent_c,
+                                 float* __restrict__ logp, float* __restrict__ lse, float* __restrict__ entropy) {
+  const int64_t n = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (n >= n_sel) return;
+  Part p{kNegInf, 0.f, 0.f};
+  float zy = 0.f;
+  for (int tm = 0; tm < tiles_m; ++tm) {
+    const float4 q = partial[static_cast<int64_t>(tm) * n_pad + n];
+    p = part_merge(p, Part{q.x, q.y, q.z});
+    zy += q.w;
+  }
+  const int64_t row = rowsel ? rowsel[n] : n;
+  const int y = ids[row];
+  const bool ok = y >= 0 && y < V;
+  const float l = p.m + logf(p.s);
+  const float lp = ok ? zy - l : 0.f;
+  const float en = ok ? l - p.t / p.s : 0.f;
+  if (logp_c) { logp_c[n] = lp; lse_c[n] = l; ent_c[n] = en; }
+  if (logp) logp[row] = lp;
+  if (lse) lse[row] = l;
+  if (entropy) entropy[row] = en;
+}
+
+// ------------------------------------------------------------------ float32: plain scoring
+// One block per selected row; every thread walks vocabulary entries v = tid, tid + T, ...
+__global__ void __launch_bounds__(256)
+k_score_f32(const float* __restrict__ W, const float* __restrict__ H, int d, int V,
+            const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids,
+            float* __restrict__ logp_c, float* __restrict__ lse_c, float* __restrict__ ent_c,
+            float* __restrict__ logp, float* __restrict__ lse, float* __restrict__ entropy) {
+  extern __shared__ float s_h[];   // [d] + 3*4 scratch
+  __shared__ float s_m[4], s_s[4], s_t[4], s_zy;
+  const int64_t n = blockIdx.x;
+  const int64_t row = rowsel ? rowsel[n] : n;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) s_h[k] = H[row * d + k];
+  if (threadIdx.x == 0) s_zy = 0.f;
+  __syncthreads();
+  const int y = ids[row];
+  Part p{kNegInf, 0.f, 0.f};
+  for (int v = threadIdx.x; v < V; v += blockDim.x) {
+    const float* w = W + static_cast<int64_t>(v) * d;
+    float z = 0.f;
+    for (int k = 0; k < d; ++k) z = fmaf(s_h[k], w[k], z);
+    if (v == y) s_zy = z;
+    p = part_merge(p, Part{z, 1.f, z});
+  }
+  // merge over the block: lanes, then wavefronts
+  for (int o = 32; o > 0; o >>= 1) {
+    Part q{__shfl_xor(p.m, o, kWave), __shfl_xor(p.s, o, kWave), __shfl_xor(p.t, o, kWave)};
+    p = part_merge(p, q);
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) { s_m[wave] = p.m; s_s[wave] = p.s; s_t[wave] = p.t; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    Part a{kNegInf, 0.f, 0.f};
+    for (int w = 0; w < 4; ++w) a = part_merge(a, Part{s_m[w], s_s[w], s_t[w]});
+    const bool ok = y >= 0 && y < V;
+    const float l = a.m + logf(a.s);
+    const float lp = ok ? s_zy - l : 0.f;
+    const float en = ok ? l - a.t / a.s : 0.f;
+    if (logp_c) { logp_c[n] = lp; lse_c[n] = l; ent_c[n] = en; }
+    if (logp) logp[row] = lp;
+    if (lse) lse[row] = l;
+    if (entropy) entropy[row] = en;
+  }
+}
+
+// ------------------------------------------------------------------ clipped surrogate
+// Per selected row: loss term and g = dloss/dlogp; per block sums of (L, clipped, entropy,
+// logp_old - logp, rows, invalid ids) for the model and for each role, in float64.
+constexpr int kStat = 6;
+__global__ void __launch_bounds__(kRowBlock)
+k_ppo_rows(int64_t n_sel, const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
+           const float* __restrict__ logp_c, const float* __restrict__ ent_c, const float* __restrict__ logp_old,
+           const float* __restrict__ adv, const int32_t* __restrict__ tok_role, int n_roles, float clip_eps,
+           float* __restrict__ g_c, double* __restrict__ blk_stats) {
+  extern __shared__ double s_acc[];   // [(1+n_roles) * kStat]
+  const int nacc = (1 + n_roles) * kStat;
+  for (int i = threadIdx.x; i < nacc; i += blockDim.x) s_acc[i] = 0.0;
+  __syncthreads();
+  const int64_t n = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (n < n_sel) {
+    const int64_t row = rowsel ? rowsel[n] : n;
+    const int y = ids[row];
+    const bool ok = y >= 0 && y < V;
+    float L = 0.f, g = 0.f, clipped = 0.f, en = 0.f, kl = 0.f;
+    if (ok) {
+      const float lp = logp_c[n], lo = logp_old[row], A = adv[row];
+      const float ratio = __expf(lp - lo);
+      const float u = -A * ratio;
+      const float c = -A * fminf(fmaxf(ratio, 1.f - clip_eps), 1.f + clip_eps);
+      const bool unclipped = u >= c;
+      L = unclipped ? u : c;
+      g = unclipped ? u / static_cast<float>(n_sel) : 0.f;
+      clipped = unclipped ? 0.f : 1.f;
+      en = ent_c[n];
+      kl = lo - lp;
+    }
+    g_c[n] = g;
+    const int role = (tok_role && n_roles > 0) ? tok_role[row] : -1;
+    for (int pass = 0; pass < 2; ++pass) {
+      if (pass == 1 && (role < 0 || role >= n_roles)) break;
+      double* a = s_acc + (pass == 0 ? 0 : (1 + role) * kStat);
+      atomicAdd(a + 0, static_cast<double>(L));
+      atomicAdd(a + 1, static_cast<double>(clipped));
+      atomicAdd(a + 2, static_cast<double>(en));
+      atomicAdd(a + 3, static_cast<double>(kl));
+      atomicAdd(a + 4, 1.0);
+      atomicAdd(a + 5, ok ? 0.0 : 1.0);
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < nacc; i += blockDim.x) blk_stats[static_cast<int64_t>(blockIdx.x) * nacc + i] = s_acc[i];
+}
+
+__global__ void __launch_bounds__(256)
+k_ppo_stats(int nblk, int n_roles, const double* __restrict__ blk_stats, umas_loss_stats* __restrict__ stats) {
+  __shared__ double smem[32];
+  const int nacc = (1 + n_roles) * kStat;
+  for (int k = 0; k <= n_roles; ++k) {
+    double sum[kStat];
+    for (int j = 0; j < kStat; ++j) {
+      double v = 0.0;
+      for (int b = threadIdx.x; b < nblk; b += blockDim.x) v += blk_stats[static_cast<int64_t>(b) * nacc + k * kStat + j];
+      sum[j] = block_sum<double>(v, smem);
+    }
+    if (threadIdx.x == 0) {
+      const double cnt = sum[4];
+      umas_loss_stats s;
+      s.loss = cnt > 0 ? static_cast<float>(sum[0] / cnt) : 0.f;
+      s.clip_frac = cnt > 0 ? static_cast<float>(sum[1] / cnt) : 0.f;
+      s.entropy_mean = cnt > 0 ? static_cast<float>(sum[2] / cnt) : 0.f;
+      s.approx_kl = cnt > 0 ? static_cast<float>(sum[3] / cnt) : 0.f;
+      s.n_scored = static_cast<int64_t>(cnt);
+      s.n_invalid_ids = static_cast<int64_t>(sum[5]);
+      stats[k] = s;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ bf16: dz tiles into the chunk buffer
+// Same tile product as k_score_tiles; epilogue forms dz = g (onehot - exp(z - lse)) and writes it as
+// bf16 to dZ [mcp, Vp] and dZt [Vp, mcp].  Rows past the chunk and vocabulary ids past V get 0.
+__global__ void __launch_bounds__(Cfg::T)
+k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
+           const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc, const int32_t* __restrict__ ids,
+           const float* __restrict__ lse_c, const float* __restrict__ g_c, int tiles_m, int tiles_n,
+           uint16_t* __restrict__ dZ, uint16_t* __restrict__ dZt, int64_t Vp, int64_t mcp) {
+  using C = Cfg;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * C::STAGE];
+  int tile_m, tile_n;
+  if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
+  const int m0 = tile_m * C::BM;
+  const int64_t n0 = static_cast<int64_t>(tile_n) * C::BN;   // chunk-relative
+  const uint16_t* pa[C::NA];
+  const uint16_t* pb[C::NB];
+  const int kofs = slot_kofs();
+#pragma unroll
+  for (int i = 0; i < C::NA; ++i) {
+    const int v = m0 + slot_row<C>(i);
+    pa[i] = v < V ? W + static_cast<int64_t>(v) * d + kofs : nullptr;
+  }
+#pragma unroll
+  for (int i = 0; i < C::NB; ++i) {
+    const int64_t n = n0 + slot_row<C>(i);
+    pb[i] = n < mc ? H + static_cast<int64_t>(rowsel ? rowsel[c0 + n] : c0 + n) * d + kofs : nullptr;
+  }
+  floatx16 acc[C::TM][C::TN];
+#pragma unroll
+  for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < C::TN; ++tn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
+  mfma_mainloop<C>(pa, pb, d, lds, acc);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / C::WN;
+  const int vbase = m0 + wm * C::WTM + (lane >> 5) * 4;
+#pragma unroll
+  for (int tn = 0; tn < C::TN; ++tn) {
+    const int64_t n = n0 + acc_col<C>(tn);
+    float l = 0.f, g = 0.f;
+    int rel = -1;
+    const bool live = n < mc;
+    if (live) {
+      l = lse_c[c0 + n];
+      g = g_c[c0 + n];
+      rel = ids[rowsel ? rowsel[c0 + n] : c0 + n] - vbase;
+    }
+#pragma unroll
+    for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int e0 = tm * 32 + q * 8;          // element offset of r = 4q from this lane's base
+        const int v0 = vbase + e0;
+        uint16_t o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float dz = 0.f;
+          if (live && v0 + j < V) {
+            const float p = __expf(acc[tm][tn][q * 4 + j] - l);
+            dz = (e0 + j == rel) ? g * (1.f - p) : -g * p;
+          }
+          o[j] = f2bf(dz);
+        }
+        if (n < mcp && v0 < Vp) {
+          uint2 pk;
+          pk.x = static_cast<uint32_t>(o[0]) | (static_cast<uint32_t>(o[1]) << 16);
+          pk.y = static_cast<uint32_t>(o[2]) | (static_cast<uint32_t>(o[3]) << 16);
+          *reinterpret_cast<uint2*>(dZ + n * Vp + v0) = pk;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) dZt[static_cast<int64_t>(v0 + j) * mcp + n] = o[j];
+        }
+      }
+  }
+}
+
+// ------------------------------------------------------------------ bf16: C = A B^T with K-contiguous operands
+// EPI 0: dH[rowsel[c0 + m], j] = bf16(C[m, j]) for m < mc  (A = dZ [mcp, Vp], B = Wt [d, Vp])
+// EPI 1: dW[v, j] (+)= C[v, j]                              (A = dZt [Vp, mcp], B = Ht [d, mcp])
+template <int EPI>
+__global__ void __launch_bounds__(Cfg::T)
+k_gemm_tn(const uint16_t* __restrict__ A, int64_t lda, int64_t m_rows, const uint16_t* __restrict__ B, int64_t ldb,
+          int n_rows, int K, int tiles_m, int tiles_n, void* __restrict__ out, int64_t ld_out,
+          const int32_t* __restrict__ rowsel, int64_t c0, int64_t m_valid, int accumulate) {
+  using C = Cfg;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * C::STAGE];
+  int tile_m, tile_n;
+  if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
+  const int64_t m0 = static_cast<int64_t>(tile_m) * C::BM;
+  const int n0 = tile_n * C::BN;
+  const uint16_t* pa[C::NA];
+  const uint16_t* pb[C::NB];
+  const int kofs = slot_kofs();
+#pragma unroll
+  for (int i = 0; i < C::NA; ++i) {
+    const int64_t m = m0 + slot_row<C>(i);
+    pa[i] = m < m_rows ? A + m * lda + kofs : nullptr;
+  }
+#pragma unroll
+  for (int i = 0; i < C::NB; ++i) {
+    const int n = n0 + slot_row<C>(i);
+    pb[i] = n < n_rows ? B + static_cast<int64_t>(n) * ldb + kofs : nullptr;
+  }
+  floatx16 acc[C::TM][C::TN];
+#pragma unroll
+  for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < C::TN; ++tn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
+  mfma_mainloop<C>(pa, pb, K, lds, acc);
+#pragma unroll
+  for (int tn = 0; tn < C::TN; ++tn) {
+    const int j = n0 + acc_col<C>(tn);
+    if (j >= n_rows) continue;
+#pragma unroll
+    for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t m = m0 + acc_row<C>(tm, r);
+        if (m >= m_valid) continue;
+        if (EPI == 0) {
+          const int64_t row = rowsel ? rowsel[c0 + m] : c0 + m;
+          static_cast<uint16_t*>(out)[row * ld_out + j] = f2bf(acc[tm][tn][r]);
+        } else {
+          float* dst = static_cast<float*>(out) + m * ld_out + j;
+          *dst = accumulate ? *dst + acc[tm][tn][r] : acc[tm][tn][r];
+        }
+      }
+  }
+}
+
+// ------------------------------------------------------------------ float32: plain backward
+// dz[n, v] = g (onehot - exp(z - lse)) for a chunk of selected rows, z recomputed with the same
+// sequential dot product as the forward pass.
+__global__ void __launch_bounds__(256)
+k_dz_f32(const float* __restrict__ W, const float* __restrict__ H, int d, int V, const int32_t* __restrict__ rowsel,
+         int64_t c0, const int32_t* __restrict__ ids, const float* __restrict__ lse_c, const float* __restrict__ g_c,
+         float* __restrict__ dz) {
+  extern __shared__ float s_h[];
+  const int64_t n = blockIdx.x;
+  const int64_t row = rowsel ? rowsel[c0 + n] : c0 + n;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) s_h[k] = H[row * d + k];
+  __syncthreads();
+  const int y = ids[row];
+  const float l = lse_c[c0 + n], g = g_c[c0 + n];
+  for (int v = threadIdx.x; v < V; v += blockDim.x) {
+    const float* w = W + static_cast<int64_t>(v) * d;
+    float z = 0.f;
+    for (int k = 0; k < d; ++k) z = fmaf(s_h[k], w[k], z);
+    const float p = expf(z - l);
+    dz[n * V + v] = (v == y) ? g * (1.f - p) : -g * p;
+  }
+}
+// dH[row, j] = sum_v dz[n, v] W[v, j]
+__global__ void __launch_bounds__(256)
+k_dh_f32(const float* __restrict__ dz, const float* __restrict__ W, int d, int V, const int32_t* __restrict__ rowsel,
+         int64_t c0, float* __restrict__ dH) {
+  const int64_t n = blockIdx.x;
+  const int64_t row = rowsel ? rowsel[c0 + n] : c0 + n;
+  for (int j = threadIdx.x; j < d; j += blockDim.x) {
+    float s = 0.f;
+    for (int v = 0; v < V; ++v) s = fmaf(dz[n * V + v], W[static_cast<int64_t>(v) * d + j], s);
+    dH[row * d + j] = s;
+  }
+}
+// dW[v, j] (+)= sum_n dz[n, v] H[row(n), j]
+__global__ void __launch_bounds__(256)
+k_dw_f32(const float* __restrict__ dz, const float* __restrict__ H, int d, int V, const int32_t* __restrict__ rowsel,
+         int64_t c0, int64_t mc, int accumulate, float* __restrict__ dW) {
+  const int v = blockIdx.x;
+  for (int j = threadIdx.x; j < d; j += blockDim.x) {
+    float s = 0.f;
+    for (int64_t n = 0; n < mc; ++n) {
+      const int64_t row = rowsel ? rowsel[c0 + n] : c0 + n;
+      s = fmaf(dz[n * V + v], H[row * d + j], s);
+    }
+    float* dst = dW + static_cast<int64_t>(v) * d + j;
+    *dst = accumulate ? *dst + s : s;
+  }
+}
+
+// ------------------------------------------------------------------ host side
+constexpr int64_t kF32ChunkRows = 4096;
+constexpr int64_t kMaxChunkRows = 1 << 17;
+
+int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+struct ScoreWs {
+  float4* partial;   // [tiles_m][n_pad]
+  float* logp_c;
+  float* lse_c;
+  float* ent_c;
+};
+size_t carve_score(Carver& c, ScoreWs& w, int64_t n_sel, int V, umas_dtype dt, bool compact) {
+  const int64_t n_pad = round_up(n_sel > 0 ? n_sel : 1, Cfg::BN);
+  const int64_t tiles_m = (V + Cfg::BM - 1) / Cfg::BM;
+  w.partial = dt == UMAS_BF16 ? c.take<float4>(static_cast<size_t>(tiles_m) * n_pad) : nullptr;
+  w.logp_c = w.lse_c = w.ent_c = nullptr;
+  if (compact) {
+    w.logp_c = c.take<float>(n_pad);
+    w.lse_c = c.take<float>(n_pad);
+    w.ent_c = c.take<float>(n_pad);
+  }
+  return c.off;
+}
+
+struct PpoWs {
+  ScoreWs score;
+  float* g_c;
+  double* blk_stats;
+  uint16_t* Wt;      // bf16 [d][Vp]
+  char* chunk;       // rest of the workspace
+  size_t fixed_bytes;
+};
+// bytes one chunk of mc rows needs
+size_t chunk_bytes(int64_t mc, int d, int V, umas_dtype dt) {
+  if (dt == UMAS_F32) return align_up(static_cast<size_t>(mc) * V * sizeof(float));
+  const int64_t Vp = round_up(V, 256), mcp = round_up(mc, 256);
+  return align_up(static_cast<size_t>(mcp) * Vp * 2) * 2 + align_up(static_cast<size_t>(d) * mcp * 2);
+}
+size_t carve_ppo(Carver& c, PpoWs& w, int64_t n_sel, int d, int V, umas_dtype dt, int n_roles) {
+  carve_score(c, w.score, n_sel, V, dt, true);
+  const int64_t n_pad = round_up(n_sel > 0 ? n_sel : 1, Cfg::BN);
+  w.g_c = c.take<float>(n_pad);
+  w.blk_stats = c.take<double>(static_cast<size_t>(cdiv(n_pad, kRowBlock)) * (1 + n_roles) * kStat);
+  w.Wt = dt == UMAS_BF16 ? c.take<uint16_t>(static_cast<size_t>(d) * round_up(V, 256)) : nullptr;
+  w.chunk = c.base ? c.base + c.off : nullptr;
+  w.fixed_bytes = c.off;
+  return c.off;
+}
+
+umas_status check_model_args(const void* H, const void* W, umas_dtype dt, int64_t n_rows, int d, int V,
+                             const int32_t* ids, const int32_t* rowsel, int64_t n_sel) {
+  UMAS_REQUIRE(dt == UMAS_F32 || dt == UMAS_BF16, UMAS_EDTYPE, "dtype=%d is neither F32 nor BF16", static_cast<int>(dt));
+  UMAS_REQUIRE(n_rows >= 0 && n_sel >= 0, UMAS_EINVAL, "negative row count");
+  UMAS_REQUIRE(d >= 1 && V >= 1, UMAS_ESHAPE, "d=%d and V=%d must be positive", d, V);
+  UMAS_REQUIRE(dt != UMAS_BF16 || d % 8 == 0, UMAS_ESHAPE, "bf16 needs d %% 8 == 0 (d=%d)", d);
+  UMAS_REQUIRE(dt != UMAS_F32 || d <= 8192, UMAS_ESHAPE, "the float32 path supports d <= 8192 (d=%d)", d);
+  UMAS_REQUIRE(rowsel || n_sel == n_rows, UMAS_EINVAL, "rowsel is NULL but n_sel != n_rows");
+  UMAS_REQUIRE(n_sel <= n_rows, UMAS_EINVAL, "n_sel=%lld exceeds n_rows=%lld", static_cast<long long>(n_sel),
+               static_cast<long long>(n_rows));
+  UMAS_REQUIRE((H && ids) || n_rows == 0, UMAS_EINVAL, "H and ids must not be NULL");
+  UMAS_REQUIRE(W, UMAS_EINVAL, "W must not be NULL");
+  UMAS_REQUIRE(reinterpret_cast<uintptr_t>(H) % 16 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0, UMAS_EINVAL,
+               "H and W must be 16-byte aligned");
+  return UMAS_OK;
+}
+
+umas_status check_ws(void* ws, size_t have, size_t need) {
+  UMAS_REQUIRE(ws && reinterpret_cast<uintptr_t>(ws) % kAlign == 0 && have >= need, UMAS_EWORKSPACE,
+               "workspace must be 256-byte aligned and hold %zu bytes (got %zu)", need, have);
+  return UMAS_OK;
+}
+
+// Forward scoring of the selected rows into compact arrays and/or scattered outputs.
+umas_status run_score(const void* H, const void* W, umas_dtype dt, int d, int V, const int32_t* ids,
+                      const int32_t* rowsel, int64_t n_sel, const ScoreWs& w, float* logp, float* lse,
+                      float* entropy, hipStream_t st) {
+  if (n_sel == 0) return UMAS_OK;
+  if (dt == UMAS_BF16) {
+    const int tiles_m = (V + Cfg::BM - 1) / Cfg::BM;
+    const int tiles_n = static_cast<int>((n_sel + Cfg::BN - 1) / Cfg::BN);
+    const int64_t n_pad = round_up(n_sel, Cfg::BN);
+    hipLaunchKernelGGL(k_score_tiles, dim3(tile_grid<kGM, kGN>(tiles_m, tiles_n)), dim3(Cfg::T), 0, st,
+                       static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), d, V, rowsel, n_sel, ids,
+                       tiles_m, tiles_n, w.partial, n_pad);
+    UMAS_LAUNCHED("k_score_tiles");
+    hipLaunchKernelGGL(k_score_finalize, dim3(cdiv(n_sel, 256)), dim3(256), 0, st, w.partial, tiles_m, n_pad, n_sel,
+                       rowsel, ids, V, w.logp_c, w.lse_c, w.ent_c, logp, lse, entropy);
+    UMAS_LAUNCHED("k_score_finalize");
+  } else {
+    hipLaunchKernelGGL(k_score_f32, dim3(static_cast<unsigned>(n_sel)), dim3(256), d * sizeof(float), st,
+                       static_cast<const float*>(W), static_cast<const float*>(H), d, V, rowsel, ids, w.logp_c,
+                       w.lse_c, w.ent_c, logp, lse, entropy);
+    UMAS_LAUNCHED("k_score_f32");
+  }
+  return UMAS_OK;
+}
+
+}  // namespace
+}  // namespace umas
+
+using namespace umas;
+
+extern "C" size_t umas_policy_logprobs_workspace_bytes(int64_t n_sel, int32_t d, int32_t V, umas_dtype dtype) {
+  (void)d;
+  if (n_sel < 0 || V < 1) return 0;
+  Carver c(nullptr);
+  ScoreWs w;
+  const size_t b = carve_score(c, w, n_sel, V, dtype, false);
+  return b > 0 ? b : kAlign;
+}
+
+extern "C" umas_status umas_policy_logprobs(const void* H, const void* W, umas_dtype dtype, int64_t n_rows, int32_t d,
+                                            int32_t V, const int32_t* ids, const int32_t* rowsel, int64_t n_sel,
+                                            float* logp, float* lse, float* entropy, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream) {
+  umas_status s = check_model_args(H, W, dtype, n_rows, d, V, ids, rowsel, n_sel);
+  if (s != UMAS_OK) return s;
+  UMAS_REQUIRE((logp && lse) || n_rows == 0, UMAS_EINVAL, "logp and lse must not be NULL");
+  UMAS_REQUIRE(n_sel < (1LL << 31), UMAS_ESHAPE, "at most 2^31-1 selected rows");
+  s = check_ws(workspace, workspace_bytes, umas_policy_logprobs_workspace_bytes(n_sel, d, V, dtype));
+  if (s != UMAS_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (rowsel && n_rows > 0) {
+    UMAS_HIP(fill_bytes_zero(logp, n_rows * sizeof(float), st));
+    UMAS_HIP(fill_bytes_zero(lse, n_rows * sizeof(float), st));
+    if (entropy) UMAS_HIP(fill_bytes_zero(entropy, n_rows * sizeof(float), st));
+  }
+  Carver c(workspace);
+  ScoreWs w;
+  carve_score(c, w, n_sel, V, dtype, false);
+  return run_score(H, W, dtype, d, V, ids, rowsel, n_sel, w, logp, lse, entropy, st);
+}
+
+extern "C" size_t umas_ppo_loss_workspace_bytes_min(int64_t n_sel, int32_t d, int32_t V, umas_dtype dtype,
+                                                    int32_t n_roles) {
+  if (n_sel < 0 || d < 1 || V < 1 || n_roles < 0) return 0;
+  Carver c(nullptr);
+  PpoWs w;
+  carve_ppo(c, w, n_sel, d, V, dtype, n_roles);
+  const int64_t mc = n_sel < 256 ? (n_sel > 0 ? n_sel : 1) : 256;
+  return c.off + chunk_bytes(mc, d, V, dtype);
+}
+
+extern "C" size_t umas_ppo_loss_workspace_bytes(int64_t n_sel, int32_t d, int32_t V, umas_dtype dtype,
+                                                int32_t n_roles) {
+  if (n_sel < 0 || d < 1 || V < 1 || n_roles < 0) return 0;
+  Carver c(nullptr);
+  PpoWs w;
+  carve_ppo(c, w, n_sel, d, V, dtype, n_roles);
+  int64_t mc = n_sel > 0 ? n_sel : 1;
+  const int64_t cap = dtype == UMAS_F32 ? kF32ChunkRows : kMaxChunkRows;
+  if (mc > cap) {
+    const int64_t nchunk = (mc + cap - 1) / cap;
+    mc = round_up((mc + nchunk - 1) / nchunk, 256);
+  }
+  return c.off + chunk_bytes(mc, d, V, dtype);
+}
+
+extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_dtype dtype, int64_t n_rows, int32_t d,
+                                             int32_t V, const int32_t* ids, const int32_t* rowsel, int64_t n_sel,
+                                             const float* logp_old, const float* adv, const int32_t* tok_role,
+                                             int32_t n_roles, float clip_eps, float entropy_coef,
+                                             int32_t accumulate_dW, umas_loss_stats* stats, float* logp_new, void* dH,
+                                             float* dW, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  umas_status s = check_model_args(H, W, dtype, n_rows, d, V, ids, rowsel, n_sel);
+  if (s != UMAS_OK) return s;
+  UMAS_REQUIRE((logp_old && adv && dH) || n_rows == 0, UMAS_EINVAL, "logp_old, adv and dH must not be NULL");
+  UMAS_REQUIRE(stats && dW, UMAS_EINVAL, "stats and dW must not be NULL");
+  UMAS_REQUIRE(n_roles >= 0 && n_roles <= UMAS_MAX_ROLES, UMAS_ESHAPE, "n_roles=%d outside [0,%d]", n_roles, UMAS_MAX_ROLES);
+  UMAS_REQUIRE(tok_role || n_roles == 0, UMAS_EINVAL, "tok_role is NULL but n_roles > 0");
+  UMAS_REQUIRE(clip_eps > 0.f && clip_eps < 1.f, UMAS_EINVAL, "clip_eps=%g outside (0,1)", static_cast<double>(clip_eps));
+  UMAS_REQUIRE(entropy_coef == 0.f, UMAS_EINVAL, "entropy_coef must be 0: the entropy bonus is not built");
+  UMAS_REQUIRE(n_sel < (1LL << 31), UMAS_ESHAPE, "at most 2^31-1 selected rows");
+  s = check_ws(workspace, workspace_bytes, umas_ppo_loss_workspace_bytes_min(n_sel, d, V, dtype, n_roles));
+  if (s != UMAS_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const size_t esz = dtype == UMAS_BF16 ? 2 : 4;
+  Carver c(workspace);
+  PpoWs w;
+  carve_ppo(c, w, n_sel, d, V, dtype, n_roles);
+
+  if (rowsel && n_rows > 0) {
+    if (logp_new) UMAS_HIP(fill_bytes_zero(logp_new, n_rows * sizeof(float), st));
+    UMAS_HIP(fill_bytes_zero(dH, static_cast<size_t>(n_rows) * d * esz, st));
+  }
+  if (!accumulate_dW && n_sel == 0) UMAS_HIP(fill_bytes_zero(dW, static_cast<size_t>(V) * d * sizeof(float), st));
+
+  // forward scoring and the surrogate
+  s = run_score(H, W, dtype, d, V, ids, rowsel, n_sel, w.score, logp_new, nullptr, nullptr, st);
+  if (s != UMAS_OK) return s;
+  const int nblk = cdiv(n_sel > 0 ? n_sel : 1, kRowBlock);
+  hipLaunchKernelGGL(k_ppo_rows, dim3(nblk), dim3(kRowBlock), (1 + n_roles) * kStat * sizeof(double), st, n_sel, rowsel,
+                     ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv, tok_role, n_roles, clip_eps, w.g_c,
+                     w.blk_stats);
+  UMAS_LAUNCHED("k_ppo_rows");
+  hipLaunchKernelGGL(k_ppo_stats, dim3(1), dim3(256), 0, st, nblk, n_roles, w.blk_stats, stats);
+  UMAS_LAUNCHED("k_ppo_stats");
+  if (n_sel == 0) return UMAS_OK;
+
+  // backward in chunks of selected rows sized to the workspace
+  const size_t room = workspace_bytes - w.fixed_bytes;
+  int64_t mc = n_sel;
+  const int64_t cap = dtype == UMAS_F32 ? kF32ChunkRows : kMaxChunkRows;
+  if (mc > cap) mc = cap;
+  while (mc > 256 && chunk_bytes(mc, d, V, dtype) > room) mc = round_up(mc / 2, 256);
+  if (mc > 256) {   // balance the chunks
+    const int64_t nchunk = (n_sel + mc - 1) / mc;
+    const int64_t even = round_up((n_sel + nchunk - 1) / nchunk, 256);
+    if (even < mc) mc = even;
+  }
+  UMAS_REQUIRE(chunk_bytes(mc < n_sel ? mc : n_sel, d, V, dtype) <= room, UMAS_EWORKSPACE,
+               "workspace cannot hold one chunk of %lld rows", static_cast<long long>(mc));
+
+  if (dtype == UMAS_F32) {
+    float* dz = reinterpret_cast<float*>(w.chunk);
+    for (int64_t c0 = 0; c0 < n_sel; c0 += mc) {
+      const int64_t rows = n_sel - c0 < mc ? n_sel - c0 : mc;
+      hipLaunchKernelGGL(k_dz_f32, dim3(static_cast<unsigned>(rows)), dim3(256), d * sizeof(float), st,
+                         static_cast<const float*>(W), static_cast<const float*>(H), d, V, rowsel, c0, ids,
+                         w.score.lse_c, w.g_c, dz);
+      UMAS_LAUNCHED("k_dz_f32");
+      hipLaunchKernelGGL(k_dh_f32, dim3(static_cast<unsigned>(rows)), dim3(256), 0, st, dz,
+                         static_cast<const float*>(W), d, V, rowsel, c0, static_cast<float*>(dH));
+      UMAS_LAUNCHED("k_dh_f32");
+      hipLaunchKernelGGL(k_dw_f32, dim3(static_cast<unsigned>(V)), dim3(256), 0, st, dz, static_cast<const float*>(H),
+                         d, V, rowsel, c0, rows, (accumulate_dW || c0 > 0) ? 1 : 0, dW);
+      UMAS_LAUNCHED("k_dw_f32");
+    }
+    return UMAS_OK;
+  }
+
+  const int64_t Vp = round_up(V, 256);
+  const uint16_t* Wb = static_cast<const uint16_t*>(W);
+  const uint16_t* Hb = static_cast<const uint16_t*>(H);
+  hipLaunchKernelGGL(k_transpose_bf16, dim3(cdiv(Vp, 64), cdiv(d, 64)), dim3(256), 0, st, Wb, static_cast<int64_t>(d),
+                     static_cast<const int32_t*>(nullptr), static_cast<int64_t>(V), w.Wt, Vp);
+  UMAS_LAUNCHED("k_transpose_bf16");
+  for (int64_t c0 = 0; c0 < n_sel; c0 += mc) {
+    const int64_t rows = n_sel - c0 < mc ? n_sel - c0 : mc;
+    const int64_t mcp = round_up(rows, 256);
+    uint16_t* dZ = reinterpret_cast<uint16_t*>(w.chunk);
+    uint16_t* dZt = reinterpret_cast<uint16_t*>(w.chunk + align_up(static_cast<size_t>(mcp) * Vp * 2));
+    uint16_t* Ht = reinterpret_cast<uint16_t*>(w.chunk + 2 * align_up(static_cast<size_t>(mcp) * Vp * 2));
+    hipLaunchKernelGGL(k_transpose_bf16, dim3(cdiv(mcp, 64), cdiv(d, 64)), dim3(256), 0, st, Hb, static_cast<int64_t>(d),
+                       rowsel ? rowsel + c0 : nullptr, rows, Ht, mcp);
+    UMAS_LAUNCHED("k_transpose_bf16");
+    const int tiles_v = static_cast<int>(Vp / 256), tiles_r = static_cast<int>(mcp / 256), tiles_d = (d + 255) / 256;
+    hipLaunchKernelGGL(k_dz_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r)), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel,
+                       c0, rows, ids, w.score.lse_c, w.g_c, tiles_v, tiles_r, dZ, dZt, Vp, mcp);
+    UMAS_LAUNCHED("k_dz_tiles");
+    hipLaunchKernelGGL(k_gemm_tn<0>, dim3(tile_grid<kGM, kGN>(tiles_r, tiles_d)), dim3(Cfg::T), 0, st, dZ, Vp, mcp, w.Wt,
+                       Vp, d, static_cast<int>(Vp), tiles_r, tiles_d, dH, static_cast<int64_t>(d), rowsel, c0, rows, 0);
+    UMAS_LAUNCHED("k_gemm_tn<dH>");
+    hipLaunchKernelGGL(k_gemm_tn<1>, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_d)), dim3(Cfg::T), 0, st, dZt, mcp, Vp, Ht,
+                       mcp, d, static_cast<int>(mcp), tiles_v, tiles_d, dW, static_cast<int64_t>(d),
+                       static_cast<const int32_t*>(nullptr), static_cast<int64_t>(0), static_cast<int64_t>(V),
+                       (accumulate_dW || c0 > 0) ? 1 : 0);
+    UMAS_LAUNCHED("k_gemm_tn<dW>");
+  }
+  return UMAS_OK;
+}

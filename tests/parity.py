@@ -1,0 +1,179 @@
+"""Parity harness: runs one workload through libumas on the GPU and through the CPU oracle.
+
+Both sides read the same seeded arrays from `workloads`; neither sees the other's results.
+Used by the `-m gpu` tests and by the smoke check.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import workloads as wl
+from oracle import umas_oracle as orc
+import paper_2605_26646_amd as umas
+
+INT_FIELDS = ["model_tok_off", "perm", "tok_turn", "tok_role", "tok_mask", "turn_seg_off", "seg_turn",
+              "model_turn_off", "model_trajrun_off", "model_rowsel_off"]
+
+
+def close(x, o, tol, what):
+    """|x-o| <= tol*max(|o|, rms(o)) element-wise and ||x-o|| <= tol*||o|| (float64 reference o)."""
+    x = np.asarray(x, dtype=np.float64)
+    o = np.asarray(o, dtype=np.float64)
+    assert x.shape == o.shape, f"{what}: shape {x.shape} vs {o.shape}"
+    if o.size == 0:
+        return 0.0
+    assert np.isfinite(x).all(), f"{what}: non-finite values"
+    rms = np.sqrt(np.mean(o * o))
+    err = np.abs(x - o)
+    bound = tol * np.maximum(np.abs(o), rms)
+    worst = float((err / np.maximum(bound, 1e-300)).max()) if rms > 0 else float(err.max() > 0)
+    assert (err <= bound + 1e-30).all(), f"{what}: element-wise error {worst:.3g} x tolerance {tol}"
+    nrm = np.linalg.norm(o)
+    rel = float(np.linalg.norm(x - o) / nrm) if nrm > 0 else float(np.linalg.norm(x - o))
+    assert rel <= tol, f"{what}: norm-wise error {rel:.3g} > {tol}"
+    return rel
+
+
+def to_dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def oracle_front(w: wl.Workload, place_mode=None, seg_mode=None, gamma_turn=None, gamma=None, lam=None,
+                 zero_value=False):
+    """Oracle steps a1-a4 on workload w."""
+    place_mode = w.place_mode if place_mode is None else place_mode
+    seg_mode = w.seg_mode if seg_mode is None else seg_mode
+    gamma_turn = w.gamma_turn if gamma_turn is None else gamma_turn
+    gamma = w.gamma if gamma is None else gamma
+    lam = w.lam if lam is None else lam
+    norm = None if w.traj_reward is None else orc.group_normalise(w.traj_reward, w.traj_group, w.norm_eps)
+    rho = orc.compose_rewards(w.traj_turn_off, w.turn_role, w.n_roles, w.role_reward, w.turn_reward, norm,
+                              w.w_role, w.w_turn, w.w_traj)
+    st = orc.route(w.n_models, w.role_to_model, w.traj_turn_off, w.turn_role, w.turn_tok_off, w.tok_mask)
+    r = orc.place_rewards(st, rho, place_mode)
+    value = None if (w.value is None or zero_value) else w.value
+    adv, ret = orc.advantages(st, w.traj_turn_off, r, value, gamma, lam, gamma_turn, seg_mode)
+    return rho, st, r, adv, ret
+
+
+def gpu_front(w: wl.Workload, place_mode=None, seg_mode=None, gamma_turn=None, gamma=None, lam=None,
+              zero_value=False):
+    place_mode = w.place_mode if place_mode is None else place_mode
+    seg_mode = w.seg_mode if seg_mode is None else seg_mode
+    gamma_turn = w.gamma_turn if gamma_turn is None else gamma_turn
+    gamma = w.gamma if gamma is None else gamma
+    lam = w.lam if lam is None else lam
+    mask = to_dev(w.tok_mask)
+    s = umas.umas_assign_token_rewards(
+        n_roles=w.n_roles, n_models=w.n_models, role_to_model=w.role_to_model, traj_turn_off=w.traj_turn_off,
+        turn_role=w.turn_role, turn_tok_off=w.turn_tok_off, tok_mask_global=mask, turn_pred_off=w.turn_pred_off,
+        turn_pred=w.turn_pred, traj_group=w.traj_group, role_reward=w.role_reward, turn_reward=w.turn_reward,
+        traj_reward=w.traj_reward, w_role=w.w_role, w_turn=w.w_turn, w_traj=w.w_traj, place_mode=place_mode,
+        norm_eps=w.norm_eps)
+    value = None if (w.value is None or zero_value) else to_dev(w.value)
+    adv, ret = umas.umas_advantages(s, value, gamma, lam, gamma_turn, seg_mode)
+    return s, adv, ret
+
+
+def check_front(w: wl.Workload, s, adv, ret, rho, st, r, adv_o, ret_o, tol=1e-5):
+    """Routing, masks and placement bit-exact; composed rewards and advantages within tol."""
+    for f in INT_FIELDS:
+        got = getattr(s, f).cpu().numpy()
+        assert np.array_equal(got, st[f]), f"{f} differs from the oracle"
+    n_runs = int(st["model_trajrun_off"][-1])
+    got_runs = s.traj_seg_off.cpu().numpy()
+    assert np.array_equal(got_runs[:n_runs + 1], st["traj_seg_off"]), "traj_seg_off differs"
+    assert (got_runs[n_runs + 1:] == w.n_tokens).all()
+    n_scored = int(st["model_rowsel_off"][-1])
+    assert np.array_equal(s.rowsel.cpu().numpy()[:n_scored], st["rowsel"]), "rowsel differs"
+    if w.n_turns:
+        step = np.concatenate([np.arange(1, n + 1) for n in np.diff(w.traj_turn_off)]) if w.n_traj else np.zeros(0)
+        assert np.array_equal(s.turn_step.cpu().numpy()[:w.n_turns], step)
+    ts = s.turn_scalar.cpu().numpy()[:w.n_turns]
+    if w.traj_group is None:
+        assert np.array_equal(ts.view(np.uint32), rho.view(np.uint32)), "composed turn rewards are not bit-exact"
+    else:
+        close(ts, rho, tol, "turn_scalar")
+    # placement copies the composed scalar: same positions as the oracle, values bitwise from turn_scalar
+    tr = s.tok_reward.cpu().numpy()
+    assert np.array_equal(tr != 0, r != 0), "reward positions differ"
+    tok_turn = st["tok_turn"]
+    nz = np.nonzero(r)[0]
+    assert np.array_equal(tr[nz].view(np.uint32), ts[tok_turn[nz]].view(np.uint32)), "placed values are not copies"
+    close(adv.cpu().numpy(), adv_o, tol, "advantages")
+    close(ret.cpu().numpy(), ret_o, tol, "returns")
+
+
+def run_model_parity(w: wl.Workload, m: int, s, adv_gpu, st, adv_o, noise_scale=1.0, ratio_one=False, verbose=False,
+                     workspace_bytes=None):
+    """Steps a5-a7 for model m: GPU chain on GPU advantages, oracle chain on oracle advantages."""
+    spec = w.models[m]
+    t = w.model_tensors(m)
+    tdt = torch.float32 if spec.dtype == "f32" else torch.bfloat16
+    tol_logp, tol = (1e-5, 1e-5) if spec.dtype == "f32" else (2e-2, 1e-2)
+    a, e = int(st["model_tok_off"][m]), int(st["model_tok_off"][m + 1])
+    ra, re = int(st["model_rowsel_off"][m]), int(st["model_rowsel_off"][m + 1])
+    rowsel_o = st["rowsel"][ra:re]
+    H, W, ids = to_dev(t["H"], tdt), to_dev(t["W"], tdt), to_dev(t["ids"])
+    rowsel = s.rowsel[ra:re]
+    # a5
+    logp, lse, ent = umas.umas_policy_logprobs(H, W, ids, rowsel)
+    logp_o, lse_o, ent_o = orc.score(t["H"], t["W"], t["ids"], rowsel_o)
+    if spec.dtype == "f32":
+        close(logp.cpu().numpy(), logp_o, tol_logp, "logp")
+        close(lse.cpu().numpy(), lse_o, tol_logp, "lse")
+        close(ent.cpu().numpy(), ent_o, tol_logp, "entropy")
+    else:
+        for name, x, o in (("logp", logp, logp_o), ("lse", lse, lse_o), ("entropy", ent, ent_o)):
+            err = np.abs(x.cpu().numpy().astype(np.float64) - o).max() if len(o) else 0.0
+            assert err <= tol_logp, f"{name}: max abs error {err:.3g} > {tol_logp}"
+    # old log-probs: the oracle's current log-probs plus the generator's noise (an input to both sides)
+    logp_old = logp_o.copy() if ratio_one else logp_o + noise_scale * t["noise"].astype(np.float64)
+    logp_old32 = logp_old.astype(np.float32)
+    role_o = st["tok_role"][a:e]
+    stats_o, g_o = orc.ppo_loss(logp_o, logp_old32, adv_o[a:e], ent_o, rowsel_o, role_o, w.n_roles, w.clip_eps)
+    dH_o, dW_o = orc.lm_head_backward(t["H"], t["W"], t["ids"], lse_o, g_o, rowsel_o)
+    ws = None
+    if workspace_bytes is not None:
+        ws = torch.empty(workspace_bytes, dtype=torch.uint8, device="cuda")
+    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(
+        H, W, ids, rowsel, to_dev(logp_old32), adv_gpu[a:e].contiguous(), s.tok_role[a:e].contiguous(), w.n_roles,
+        w.clip_eps, workspace=ws)
+    torch.cuda.synchronize()
+    sg = umas.read_stats(stats)
+    for k in range(1 + w.n_roles):
+        assert int(sg["n_scored"][k]) == int(stats_o[k, 4]), f"n_scored[{k}]"
+        assert int(sg["n_invalid_ids"][k]) == 0
+        for j, name in enumerate(("loss", "clip_frac", "entropy_mean", "approx_kl")):
+            o = stats_o[k, j]
+            scale = max(abs(o), abs(stats_o[0, j]), 1e-3 if name != "approx_kl" else 1e-2)
+            lim = tol * scale if name != "clip_frac" else max(tol * scale, 2.0 / max(stats_o[k, 4], 1))
+            assert abs(float(sg[name][k]) - o) <= lim, f"{name}[{k}]: {float(sg[name][k])} vs {o}"
+    if spec.dtype == "f32":
+        close(logp_new.cpu().numpy(), logp_o, tol_logp, "logp_new")
+    else:
+        assert np.abs(logp_new.cpu().numpy() - logp_o).max(initial=0) <= tol_logp
+    rel_h = close(dH.float().cpu().numpy(), dH_o, tol, "dH")
+    rel_w = close(dW.cpu().numpy(), dW_o, tol, "dW")
+    if verbose:
+        print(f"  model {m}: rows={e - a} scored={re - ra} d={spec.d} V={spec.V} {spec.dtype} "
+              f"loss={float(sg['loss'][0]):+.6f} (oracle {stats_o[0, 0]:+.6f}) clip_frac={float(sg['clip_frac'][0]):.4f} "
+              f"dH rel {rel_h:.2e} dW rel {rel_w:.2e}", flush=True)
+    return stats_o, sg
+
+
+def run_config_parity(cfg: int, verbose=False, noise_std=0.05, ratio_one=False, workspace_bytes=None, **overrides):
+    w = wl.make_workload(cfg, noise_std=noise_std, **overrides)
+    if verbose:
+        print(f"{w.name}: traj={w.n_traj} turns={w.n_turns} tokens={w.n_tokens} models={w.n_models}", flush=True)
+    rho, st, r, adv_o, ret_o = oracle_front(w)
+    s, adv, ret = gpu_front(w)
+    check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+    for m in range(w.n_models):
+        run_model_parity(w, m, s, adv, st, adv_o, ratio_one=ratio_one, verbose=verbose,
+                         workspace_bytes=workspace_bytes)
+    return w

@@ -1,0 +1,106 @@
+"""The C-ABI library loads, exports every declared symbol, and rejects bad arguments on the host (no GPU)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2605_26646_amd as umas
+    if not os.path.exists(umas.lib_path()):
+        import __graft_entry__ as g
+        g.build()
+    return umas.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "umas.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(umas_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"umas_assign_token_rewards", "umas_advantages", "umas_policy_logprobs",
+            "umas_ppo_loss_fwd_bwd", "umas_last_error"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_layouts_match_the_header():
+    from paper_2605_26646_amd import binding as b
+    assert C.sizeof(b._Graph) == 4 * 4 + 8 + 7 * 8
+    assert C.sizeof(b._Rewards) == 6 * 8 + 8
+    assert C.sizeof(b._Streams) == 15 * 8
+    assert b.STATS_DTYPE.itemsize == 32
+
+
+def test_workspace_queries(lib):
+    assert lib.umas_advantages_workspace_bytes(0) > 0
+    assert lib.umas_advantages_workspace_bytes(10 ** 6) >= (10 ** 6 // 4096) * 20
+    small = lib.umas_ppo_loss_workspace_bytes_min(39000, 2048, 151936, 1, 3)
+    full = lib.umas_ppo_loss_workspace_bytes(39000, 2048, 151936, 1, 3)
+    assert 0 < small < full
+    assert lib.umas_policy_logprobs_workspace_bytes(1000, 64, 512, 0) > 0
+
+
+def graph(**kw):
+    from paper_2605_26646_amd import binding as b
+    base = dict(n_roles=2, n_models=2, role_to_model=[0, 1], traj_turn_off=[0, 2], turn_role=[0, 1],
+                turn_tok_off=[0, 3, 5], turn_pred_off=None, turn_pred=None, traj_group=None)
+    base.update(kw)
+    keep = []
+
+    def h(a, dt):
+        if a is None:
+            return None
+        arr = np.ascontiguousarray(a, dtype=dt)
+        keep.append(arr)
+        return arr.ctypes.data
+
+    g = b._Graph(base["n_roles"], base["n_models"], len(base["traj_turn_off"]) - 1, len(base["turn_tok_off"]) - 1,
+                 int(base["turn_tok_off"][-1]), h(base["role_to_model"], np.int32), h(base["traj_turn_off"], np.int32),
+                 h(base["turn_role"], np.int32), h(base["turn_tok_off"], np.int64), h(base["turn_pred_off"], np.int32),
+                 h(base["turn_pred"], np.int32), h(base["traj_group"], np.int32))
+    return g, keep
+
+
+@pytest.mark.parametrize("kw,code,needle", [
+    (dict(role_to_model=[0, 2]), -1, "role_to_model"),
+    (dict(turn_role=[0, 5]), -1, "turn_role"),
+    (dict(turn_tok_off=[0, 4, 3]), -1, "turn_tok_off"),
+    (dict(traj_turn_off=[0, 1]), -1, "traj_turn_off"),
+    (dict(n_models=9, role_to_model=[0, 1]), -2, "n_models"),
+    (dict(turn_pred_off=[0, 0, 1], turn_pred=[1]), -1, "predecessor"),
+    (dict(traj_group=[-1]), -1, "traj_group"),
+])
+def test_malformed_graphs_are_rejected_before_any_launch(lib, kw, code, needle):
+    from paper_2605_26646_amd import binding as b
+    g, keep = graph(**kw)
+    r = b._Rewards(None, None, None, None, None, None, 0, 1e-6)
+    s = b._Streams(*([1] * 15))          # non-NULL dummies: validation fails before they are used
+    status = lib.umas_assign_token_rewards(C.addressof(g), C.addressof(r), 1, C.addressof(s), 256, 1 << 20, None)
+    assert status == code
+    assert needle in lib.umas_last_error().decode()
+
+
+def test_bad_scalar_arguments(lib):
+    assert lib.umas_policy_logprobs(256, 256, 7, 4, 8, 8, 256, None, 4, 256, 256, None, 256, 1 << 20, None) == -3
+    assert lib.umas_policy_logprobs(256, 256, 1, 4, 12, 8, 256, None, 4, 256, 256, None, 256, 1 << 20, None) == -2
+    assert "d % 8" in lib.umas_last_error().decode()
+    # clip_eps outside (0,1)
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 1.5, 0.0, 0, 256, None,
+                                   256, 256, 256, 1 << 30, None)
+    assert st == -1 and "clip_eps" in lib.umas_last_error().decode()
+    # workspace too small
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0, 256, None,
+                                   256, 256, 256, 16, None)
+    assert st == -4
+    from paper_2605_26646_amd import binding as b
+    s = b._Streams(*([1] * 15))
+    assert lib.umas_advantages(C.addressof(s), 10, 1, None, 1.0, 1.0, 1.0, 3, 256, 256, 256, 1 << 20, None) == -1

@@ -1,0 +1,181 @@
+"""GPU parity: libumas (through the C ABI) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import umas_oracle as orc
+import paper_2605_26646_amd as umas
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+# Scaled-down model shapes: several 256-wide vocabulary and row tiles with ragged tails, several
+# 64-wide K steps with a ragged tail (d = 200 is a multiple of 8 but not of 64).
+SMALL_BF16 = [(200, 1000, "bf16")]
+SMALL_TWO = [(128, 700, "bf16"), (200, 1000, "bf16")]
+
+
+def test_cfg0_full_size_fp32():
+    P.run_config_parity(0, verbose=True)
+
+
+def test_cfg0_clip_stress_and_ratio_one():
+    P.run_config_parity(0, verbose=True, noise_std=0.25)
+    P.run_config_parity(0, verbose=True, ratio_one=True)
+
+
+def test_cfg1_scaled_group_normalised_padding():
+    P.run_config_parity(1, verbose=True, n_traj=16, tokens_per_turn=40, models=SMALL_BF16)
+
+
+def test_cfg1_scaled_clip_stress():
+    P.run_config_parity(1, verbose=True, n_traj=16, tokens_per_turn=40, models=SMALL_BF16, noise_std=0.25)
+
+
+def test_cfg2_scaled_interior_masks_turn_rewards():
+    P.run_config_parity(2, verbose=True, n_traj=8, tokens_per_turn=48, models=SMALL_BF16)
+
+
+def test_cfg3_scaled_two_models():
+    P.run_config_parity(3, verbose=True, n_traj=6, tokens_per_turn=24, models=SMALL_TWO)
+
+
+def test_cfg4_scaled_long_turns_both_segment_modes():
+    w = P.run_config_parity(4, verbose=True, n_traj=4, tokens_per_turn=192, models=SMALL_BF16)
+    for seg_mode, gamma_turn in ((orc.SEG_TRAJ, 1.0), (orc.SEG_TRAJ, 0.9)):
+        rho, st, r, adv_o, ret_o = P.oracle_front(w, seg_mode=seg_mode, gamma_turn=gamma_turn)
+        s, adv, ret = P.gpu_front(w, seg_mode=seg_mode, gamma_turn=gamma_turn)
+        P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+
+
+def test_backward_in_several_chunks_matches():
+    # the smallest workspace the call accepts forces 256-row chunks and dW accumulation across them
+    w = wl.make_workload(1, n_traj=16, tokens_per_turn=40, models=SMALL_BF16)
+    n_sel = int(w.tok_mask.sum())
+    nbytes = umas.ppo_workspace_bytes(n_sel, 200, 1000, torch.bfloat16, w.n_roles, minimum=True)
+    P.run_config_parity(1, verbose=True, n_traj=16, tokens_per_turn=40, models=SMALL_BF16, workspace_bytes=nbytes)
+    w0 = wl.make_workload(0)
+    nbytes = umas.ppo_workspace_bytes(768, 64, 512, torch.float32, 3, minimum=True)
+    P.run_config_parity(0, workspace_bytes=nbytes)
+
+
+@pytest.mark.parametrize("cfg,kw", [(1, dict(n_traj=4096)), (4, dict(n_traj=64, tokens_per_turn=4096)),
+                                    (2, dict(n_traj=512))])
+def test_front_end_full_and_replicated_sizes(cfg, kw):
+    """Routing, placement and scans at full and batch-replicated sizes, compared in full."""
+    w = wl.make_workload(cfg, **kw)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w)
+    s, adv, ret = P.gpu_front(w)
+    P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+
+
+@pytest.mark.parametrize("variant", ["suffix_sum", "place_all", "traj_decay", "weights"])
+def test_scan_and_placement_variants(variant):
+    w = wl.make_workload(2, n_traj=24, tokens_per_turn=100)
+    kw = {}
+    if variant == "suffix_sum":
+        kw = dict(gamma=1.0, lam=1.0, zero_value=True)
+    elif variant == "place_all":
+        kw = dict(place_mode=orc.PLACE_ALL)
+    elif variant == "traj_decay":
+        kw = dict(seg_mode=orc.SEG_TRAJ, gamma_turn=0.8, gamma=1.0, lam=1.0, zero_value=True)
+    elif variant == "weights":
+        w.w_role = np.array([0.5, 2.0, 1.5], np.float32)
+        w.w_turn = np.array([1.25, 0.75, 3.0], np.float32)
+        w.w_traj = np.array([0.3, 0.7, 1.1], np.float32)
+        w.role_reward = np.random.default_rng(1).normal(size=w.n_traj * w.n_roles).astype(np.float32)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w, **kw)
+    s, adv, ret = P.gpu_front(w, **kw)
+    P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+    if variant == "suffix_sum":
+        # last-token and all-token placement agree at every valid token when gamma = lam = 1, V = 0 ... for
+        # the token that carries the reward; the suffix sum at a turn's first valid token is the turn reward
+        first_valid = [int(np.nonzero(st["tok_mask"][a:e])[0][0]) + a for a, e in
+                       zip(st["turn_seg_off"][:-1], st["turn_seg_off"][1:]) if st["tok_mask"][a:e].any()]
+        turns = st["tok_turn"][first_valid]
+        assert np.allclose(adv.cpu().numpy()[first_valid], rho[turns], rtol=1e-6, atol=1e-7)
+
+
+def test_degenerate_graphs():
+    # empty turns, an all-masked turn, an empty trajectory, a model that receives nothing
+    turn_len = np.array([5, 0, 3, 7, 0, 2], np.int64)
+    w = wl.make_workload(0)
+    w.n_traj, w.n_turns, w.n_roles, w.n_models = 4, 6, 3, 3
+    w.traj_turn_off = np.array([0, 2, 2, 5, 6], np.int32)
+    w.turn_role = np.array([0, 1, 1, 0, 0, 1], np.int32)
+    w.role_to_model = np.array([2, 0, 1], np.int32)          # model 1 serves only role 2, which never runs
+    w.turn_tok_off = np.concatenate([[0], np.cumsum(turn_len)]).astype(np.int64)
+    w.n_tokens = int(w.turn_tok_off[-1])
+    w.turn_pred_off, w.turn_pred = None, None
+    w.tok_mask = np.ones(w.n_tokens, np.uint8)
+    w.tok_mask[5:8] = 0                                       # turn 2 entirely masked
+    w.tok_mask[14] = 0
+    rng = np.random.default_rng(3)
+    w.traj_reward = rng.normal(size=4).astype(np.float32)
+    w.role_reward = rng.normal(size=12).astype(np.float32)
+    w.turn_reward = rng.normal(size=6).astype(np.float32)
+    w.value = rng.normal(size=w.n_tokens).astype(np.float32)
+    for seg_mode in (orc.SEG_TURN, orc.SEG_TRAJ):
+        rho, st, r, adv_o, ret_o = P.oracle_front(w, seg_mode=seg_mode, gamma_turn=0.7)
+        s, adv, ret = P.gpu_front(w, seg_mode=seg_mode, gamma_turn=0.7)
+        P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+
+
+def test_empty_workload_and_empty_selection():
+    s = umas.umas_assign_token_rewards(n_roles=1, n_models=1, role_to_model=[0], traj_turn_off=[0], turn_role=[],
+                                       turn_tok_off=[0], tok_mask_global=torch.empty(0, dtype=torch.uint8, device="cuda"))
+    adv, ret = umas.umas_advantages(s, None, 1.0, 1.0)
+    torch.cuda.synchronize()
+    assert s.model_tok_off.tolist() == [0, 0] and s.model_rowsel_off.tolist() == [0, 0] and adv.numel() == 0
+    # no selected rows: zero statistics, zero gradients
+    H = torch.randn(8, 64, device="cuda").bfloat16()
+    W = torch.randn(300, 64, device="cuda").bfloat16()
+    ids = torch.zeros(8, dtype=torch.int32, device="cuda")
+    rowsel = torch.empty(0, dtype=torch.int32, device="cuda")
+    z = torch.zeros(8, device="cuda")
+    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, z, z, None, 0, 0.2)
+    torch.cuda.synchronize()
+    sg = umas.read_stats(stats)
+    assert sg["n_scored"][0] == 0 and sg["loss"][0] == 0
+    assert not dH.float().abs().sum().item() and not dW.abs().sum().item() and not logp_new.abs().sum().item()
+
+
+def test_invalid_token_ids_are_counted_and_ignored():
+    w = wl.make_workload(1, n_traj=2, tokens_per_turn=40, models=[(64, 300, "bf16")])
+    t = w.model_tensors(0)
+    n = len(t["ids"])
+    ids_bad = t["ids"].copy()
+    bad = np.array([3, 17, 100])
+    ids_bad[bad] = [300, -1, 10 ** 6]
+    H, W = P.to_dev(t["H"], torch.bfloat16), P.to_dev(t["W"], torch.bfloat16)
+    logp, lse, ent = umas.umas_policy_logprobs(H, W, P.to_dev(ids_bad))
+    good = np.setdiff1d(np.arange(n), bad)
+    logp_o, lse_o, ent_o = orc.score(t["H"], t["W"], t["ids"], good.astype(np.int32))
+    assert np.abs(logp.cpu().numpy() - logp_o).max() <= 2e-2 and (logp.cpu().numpy()[bad] == 0).all()
+    adv = np.random.default_rng(0).normal(size=n).astype(np.float32)
+    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(H, W, P.to_dev(ids_bad), None, P.to_dev(logp_o.astype(np.float32)),
+                                                        P.to_dev(adv), None, 0, 0.2)
+    sg = umas.read_stats(stats)
+    assert sg["n_invalid_ids"][0] == 3 and sg["n_scored"][0] == n
+    assert not dH.float().cpu().numpy()[bad].any()
+    # the oracle with those rows' gradient forced to 0 and the mean still over n rows
+    st_o, g_o = orc.ppo_loss(logp_o, logp_o.astype(np.float32), adv, ent_o, good.astype(np.int32), np.zeros(n, np.int32), 0, 0.2)
+    g_o *= len(good) / n
+    dH_o, dW_o = orc.lm_head_backward(t["H"], t["W"], t["ids"], lse_o, g_o, good.astype(np.int32))
+    P.close(dH.float().cpu().numpy(), dH_o, 1e-2, "dH")
+    P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW")
+
+
+def test_accumulate_dw_adds_to_existing_gradient():
+    w = wl.make_workload(1, n_traj=2, tokens_per_turn=40, models=[(64, 300, "bf16")])
+    t = w.model_tensors(0)
+    n = len(t["ids"])
+    H, W, ids = P.to_dev(t["H"], torch.bfloat16), P.to_dev(t["W"], torch.bfloat16), P.to_dev(t["ids"])
+    adv = P.to_dev(np.random.default_rng(0).normal(size=n).astype(np.float32))
+    logp, _, _ = umas.umas_policy_logprobs(H, W, ids)
+    _, _, _, dW1 = umas.umas_ppo_loss_fwd_bwd(H, W, ids, None, logp, adv, None, 0, 0.2)
+    dW2 = dW1.clone()
+    umas.umas_ppo_loss_fwd_bwd(H, W, ids, None, logp, adv, None, 0, 0.2, accumulate_dW=True, dW=dW2)
+    torch.cuda.synchronize()
+    assert torch.allclose(dW2, 2 * dW1, rtol=1e-6, atol=0)
