@@ -73,11 +73,21 @@ class Streams:
     def _c(self) -> _Streams:
         s = _Streams()
         for name in _STREAM_FIELDS:
-            setattr(s, name, getattr(self, name).data_ptr())
+            t = getattr(self, name)
+            # an empty tensor has no storage; the ABI wants non-NULL pointers even for size 0
+            setattr(s, name, t.data_ptr() or _dummy(t.device).data_ptr())
         return s
 
 
 _LIB = None
+_DUMMY = {}
+
+
+def _dummy(device) -> torch.Tensor:
+    key = str(device)
+    if key not in _DUMMY:
+        _DUMMY[key] = torch.zeros(256, dtype=torch.uint8, device=device)
+    return _DUMMY[key]
 
 
 def lib_path() -> str:
@@ -139,6 +149,16 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else t.data_ptr()
 
 
+def _sel_ptr(rowsel: Optional[torch.Tensor]):
+    """Pointer of a row selection; an empty selection still needs a non-NULL pointer (NULL means all rows)."""
+    if rowsel is None:
+        return None, None
+    if rowsel.numel() == 0:
+        dummy = torch.zeros(1, dtype=torch.int32, device=rowsel.device)
+        return dummy, dummy.data_ptr()
+    return rowsel, rowsel.data_ptr()
+
+
 def _stream():
     return torch.cuda.current_stream().cuda_stream
 
@@ -192,7 +212,7 @@ def umas_assign_token_rewards(*, n_roles, n_models, role_to_model, traj_turn_off
         turn_step=torch.empty(max(n_turns, 1), **i32))
     ws = _workspace(lib.umas_assign_workspace_bytes(C.addressof(g)), dev)
     cs = out._c()
-    _check(lib, lib.umas_assign_token_rewards(C.addressof(g), C.addressof(r), _ptr(tok_mask_global), C.addressof(cs),
+    _check(lib, lib.umas_assign_token_rewards(C.addressof(g), C.addressof(r), _ptr(tok_mask_global) or _dummy(dev).data_ptr(), C.addressof(cs),
                                               ws.data_ptr(), ws.numel(), _stream()))
     return out
 
@@ -222,7 +242,8 @@ def umas_policy_logprobs(H: torch.Tensor, W: torch.Tensor, ids: torch.Tensor, ro
     lse = torch.empty(n_rows, dtype=torch.float32, device=dev)
     ent = torch.empty(n_rows, dtype=torch.float32, device=dev) if want_entropy else None
     ws = workspace if workspace is not None else _workspace(lib.umas_policy_logprobs_workspace_bytes(n_sel, d, V, dt), dev)
-    _check(lib, lib.umas_policy_logprobs(H.data_ptr(), W.data_ptr(), dt, n_rows, d, V, ids.data_ptr(), _ptr(rowsel),
+    _keep, sel = _sel_ptr(rowsel)
+    _check(lib, lib.umas_policy_logprobs(H.data_ptr(), W.data_ptr(), dt, n_rows, d, V, ids.data_ptr(), sel,
                                          n_sel, logp.data_ptr(), lse.data_ptr(), _ptr(ent), ws.data_ptr(), ws.numel(),
                                          _stream()))
     return logp, lse, ent
@@ -253,7 +274,8 @@ def umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv, tok_role, n_roles, c
         stats = torch.empty((1 + n_roles) * STATS_DTYPE.itemsize, dtype=torch.uint8, device=dev)
     ws = workspace if workspace is not None else _workspace(
         lib.umas_ppo_loss_workspace_bytes(n_sel, d, V, dt, n_roles), dev)
-    _check(lib, lib.umas_ppo_loss_fwd_bwd(H.data_ptr(), W.data_ptr(), dt, n_rows, d, V, ids.data_ptr(), _ptr(rowsel),
+    _keep, sel = _sel_ptr(rowsel)
+    _check(lib, lib.umas_ppo_loss_fwd_bwd(H.data_ptr(), W.data_ptr(), dt, n_rows, d, V, ids.data_ptr(), sel,
                                           n_sel, logp_old.data_ptr(), adv.data_ptr(), _ptr(tok_role), n_roles,
                                           clip_eps, entropy_coef, 1 if accumulate_dW else 0, stats.data_ptr(),
                                           logp_new.data_ptr(), dH.data_ptr(), dW.data_ptr(), ws.data_ptr(), ws.numel(),

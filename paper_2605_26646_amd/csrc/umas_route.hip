@@ -117,8 +117,14 @@ __global__ void k_turn_meta(int n_traj, int n_turns, int n_roles, const int32_t*
   const float wr = w_role ? w_role[v] : 1.0f;
   const float wt = w_turn ? w_turn[v] : 1.0f;
   const float wj = w_traj ? w_traj[v] : 1.0f;
-  // (node + turn) + traj with every product and sum rounded on its own: no fused multiply-add
-  turn_scalar[u] = __fadd_rn(__fadd_rn(__fmul_rn(wr, rr), __fmul_rn(wt, rt)), __fmul_rn(wj, rj));
+  // (node + turn) + traj with every product and sum rounded on its own: contraction into fused
+  // multiply-adds is switched off for this expression so that the result is reproducible bit for bit
+  {
+#pragma clang fp contract(off)
+    const float pr = wr * rr, pt = wt * rt, pj = wj * rj;
+    const float s1 = pr + pt;
+    turn_scalar[u] = s1 + pj;
+  }
 }
 
 // Per block of turns and per model: number of turns and of tokens routed to that model.

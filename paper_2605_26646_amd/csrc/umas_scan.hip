@@ -247,7 +247,7 @@ extern "C" umas_status umas_advantages(const umas_streams* s, int64_t n_tokens, 
                seg_mode);
   UMAS_REQUIRE(s->tok_reward && s->tok_mask && s->turn_seg_off && s->traj_seg_off && s->tok_turn && s->turn_step,
                UMAS_EINVAL, "streams lacks tok_reward, tok_mask, turn_seg_off, traj_seg_off, tok_turn or turn_step");
-  UMAS_REQUIRE(adv && ret, UMAS_EINVAL, "adv and ret must not be NULL");
+  UMAS_REQUIRE((adv && ret) || n_tokens == 0, UMAS_EINVAL, "adv and ret must not be NULL");
   UMAS_REQUIRE(gamma == gamma && lam == lam && gamma_turn == gamma_turn, UMAS_EINVAL, "gamma, lam, gamma_turn must be numbers");
   const size_t need = umas_advantages_workspace_bytes(n_tokens);
   UMAS_REQUIRE(workspace && reinterpret_cast<uintptr_t>(workspace) % kAlign == 0 && workspace_bytes >= need,

@@ -6,8 +6,9 @@
 // to per-row (max, sum exp, sum exp*z, taken logit) in registers; logits never leave the chip.
 // Update (paragraph "Model-specific updates and synchronization", PPO after Schulman et al.
 // 2017): ratio = exp(logp - logp_old), L = max(-A ratio, -A clip(ratio)), g = dL/dlogp, then
-// dz = g (onehot - softmax) is recomputed tile by tile from H, W and lse, rounded to bf16 into a
-// bounded chunk buffer in both orientations, and dH = dz W, dW = dz^T H run as MFMA GEMMs.
+// the dense part of dz = g (onehot - softmax) is recomputed tile by tile from H, W and lse, rounded
+// to bf16 into a bounded chunk buffer in both orientations, and dH = dz W, dW = dz^T H run as MFMA
+// GEMMs; the one-hot part (one term per row) is added in float32.
 // The float32 path is a plain, unblocked implementation for small shapes.
 #include <math.h>
 
@@ -330,11 +331,13 @@ k_ppo_stats(int nblk, int n_roles, const double* __restrict__ blk_stats, umas_lo
 }
 
 // ------------------------------------------------------------------ bf16: dz tiles into the chunk buffer
-// Same tile product as k_score_tiles; epilogue forms dz = g (onehot - exp(z - lse)) and writes it as
-// bf16 to dZ [mcp, Vp] and dZt [Vp, mcp].  Rows past the chunk and vocabulary ids past V get 0.
+// Same tile product as k_score_tiles; the epilogue forms the dense part of dz = g (onehot - softmax),
+// -g exp(z - lse), and writes it as bf16 to dZ [mcp, Vp] and dZt [Vp, mcp].  Rows past the chunk and
+// vocabulary ids past V get 0.  The one-hot part g at v = y is a single term per row and is added in
+// float32 where dH and dW are written, so that it never meets the bf16 rounding of the dense part.
 __global__ void __launch_bounds__(Cfg::T)
 k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
-           const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc, const int32_t* __restrict__ ids,
+           const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc,
            const float* __restrict__ lse_c, const float* __restrict__ g_c, int tiles_m, int tiles_n,
            uint16_t* __restrict__ dZ, uint16_t* __restrict__ dZt, int64_t Vp, int64_t mcp) {
   using C = Cfg;
@@ -372,12 +375,10 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
   for (int tn = 0; tn < C::TN; ++tn) {
     const int64_t n = n0 + acc_col<C>(tn);
     float l = 0.f, g = 0.f;
-    int rel = -1;
     const bool live = n < mc;
     if (live) {
       l = lse_c[c0 + n];
       g = g_c[c0 + n];
-      rel = ids[rowsel ? rowsel[c0 + n] : c0 + n] - vbase;
     }
 #pragma unroll
     for (int tm = 0; tm < C::TM; ++tm)
@@ -390,8 +391,7 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
         for (int j = 0; j < 4; ++j) {
           float dz = 0.f;
           if (live && v0 + j < V) {
-            const float p = __expf(acc[tm][tn][q * 4 + j] - l);
-            dz = (e0 + j == rel) ? g * (1.f - p) : -g * p;
+            dz = -g * __expf(acc[tm][tn][q * 4 + j] - l);
           }
           o[j] = f2bf(dz);
         }
@@ -408,13 +408,14 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
 }
 
 // ------------------------------------------------------------------ bf16: C = A B^T with K-contiguous operands
-// EPI 0: dH[rowsel[c0 + m], j] = bf16(C[m, j]) for m < mc  (A = dZ [mcp, Vp], B = Wt [d, Vp])
+// EPI 0: dH[rowsel[c0 + m], j] = bf16(C[m, j] + g[m] W[y[m], j]) for m < mc  (A = dZ [mcp, Vp], B = Wt [d, Vp])
 // EPI 1: dW[v, j] (+)= C[v, j]                              (A = dZt [Vp, mcp], B = Ht [d, mcp])
 template <int EPI>
 __global__ void __launch_bounds__(Cfg::T)
 k_gemm_tn(const uint16_t* __restrict__ A, int64_t lda, int64_t m_rows, const uint16_t* __restrict__ B, int64_t ldb,
           int n_rows, int K, int tiles_m, int tiles_n, void* __restrict__ out, int64_t ld_out,
-          const int32_t* __restrict__ rowsel, int64_t c0, int64_t m_valid, int accumulate) {
+          const int32_t* __restrict__ rowsel, int64_t c0, int64_t m_valid, int accumulate,
+          const uint16_t* __restrict__ W, const int32_t* __restrict__ ids, const float* __restrict__ g_c) {
   using C = Cfg;
   __shared__ __attribute__((aligned(16))) uint16_t lds[2 * C::STAGE];
   int tile_m, tile_n;
@@ -454,13 +455,32 @@ k_gemm_tn(const uint16_t* __restrict__ A, int64_t lda, int64_t m_rows, const uin
         if (m >= m_valid) continue;
         if (EPI == 0) {
           const int64_t row = rowsel ? rowsel[c0 + m] : c0 + m;
-          static_cast<uint16_t*>(out)[row * ld_out + j] = f2bf(acc[tm][tn][r]);
+          const float g = g_c[c0 + m];
+          float v = acc[tm][tn][r];
+          if (g != 0.f) v += g * bf2f(W[static_cast<int64_t>(ids[row]) * ld_out + j]);   // g = 0 for invalid ids
+          static_cast<uint16_t*>(out)[row * ld_out + j] = f2bf(v);
         } else {
           float* dst = static_cast<float*>(out) + m * ld_out + j;
           *dst = accumulate ? *dst + acc[tm][tn][r] : acc[tm][tn][r];
         }
       }
   }
+}
+
+// One-hot part of dW: dW[y_n, :] += g_n h_n for every selected row, in float32.  Rows that took the
+// same token add into the same dW row, hence atomics; one wavefront per row.
+__global__ void __launch_bounds__(256)
+k_dw_onehot(const uint16_t* __restrict__ H, int d, const int32_t* __restrict__ rowsel, int64_t n_sel,
+            const int32_t* __restrict__ ids, const float* __restrict__ g_c, float* __restrict__ dW) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n = static_cast<int64_t>(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (n >= n_sel) return;
+  const float g = g_c[n];
+  if (g == 0.f) return;                      // clipped rows, zero advantage, invalid ids
+  const int64_t row = rowsel ? rowsel[n] : n;
+  const uint16_t* h = H + row * d;
+  float* dst = dW + static_cast<int64_t>(ids[row]) * d;
+  for (int j = lane; j < d; j += kWave) unsafeAtomicAdd(dst + j, g * bf2f(h[j]));
 }
 
 // ------------------------------------------------------------------ float32: plain backward
@@ -762,16 +782,20 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     UMAS_LAUNCHED("k_transpose_bf16");
     const int tiles_v = static_cast<int>(Vp / 256), tiles_r = static_cast<int>(mcp / 256), tiles_d = (d + 255) / 256;
     hipLaunchKernelGGL(k_dz_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r)), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel,
-                       c0, rows, ids, w.score.lse_c, w.g_c, tiles_v, tiles_r, dZ, dZt, Vp, mcp);
+                       c0, rows, w.score.lse_c, w.g_c, tiles_v, tiles_r, dZ, dZt, Vp, mcp);
     UMAS_LAUNCHED("k_dz_tiles");
     hipLaunchKernelGGL(k_gemm_tn<0>, dim3(tile_grid<kGM, kGN>(tiles_r, tiles_d)), dim3(Cfg::T), 0, st, dZ, Vp, mcp, w.Wt,
-                       Vp, d, static_cast<int>(Vp), tiles_r, tiles_d, dH, static_cast<int64_t>(d), rowsel, c0, rows, 0);
+                       Vp, d, static_cast<int>(Vp), tiles_r, tiles_d, dH, static_cast<int64_t>(d), rowsel, c0, rows, 0, Wb, ids,
+                       w.g_c);
     UMAS_LAUNCHED("k_gemm_tn<dH>");
     hipLaunchKernelGGL(k_gemm_tn<1>, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_d)), dim3(Cfg::T), 0, st, dZt, mcp, Vp, Ht,
                        mcp, d, static_cast<int>(mcp), tiles_v, tiles_d, dW, static_cast<int64_t>(d),
                        static_cast<const int32_t*>(nullptr), static_cast<int64_t>(0), static_cast<int64_t>(V),
-                       (accumulate_dW || c0 > 0) ? 1 : 0);
+                       (accumulate_dW || c0 > 0) ? 1 : 0, static_cast<const uint16_t*>(nullptr),
+                       static_cast<const int32_t*>(nullptr), static_cast<const float*>(nullptr));
     UMAS_LAUNCHED("k_gemm_tn<dW>");
   }
+  hipLaunchKernelGGL(k_dw_onehot, dim3(cdiv(n_sel, 4)), dim3(256), 0, st, Hb, d, rowsel, n_sel, ids, w.g_c, dW);
+  UMAS_LAUNCHED("k_dw_onehot");
   return UMAS_OK;
 }

@@ -178,4 +178,5 @@ def test_accumulate_dw_adds_to_existing_gradient():
     dW2 = dW1.clone()
     umas.umas_ppo_loss_fwd_bwd(H, W, ids, None, logp, adv, None, 0, 0.2, accumulate_dW=True, dW=dW2)
     torch.cuda.synchronize()
-    assert torch.allclose(dW2, 2 * dW1, rtol=1e-6, atol=0)
+    # float atomics add the one-hot rows in any order: equal up to float32 rounding of the sums
+    assert torch.allclose(dW2, 2 * dW1, rtol=1e-5, atol=1e-6 * dW1.abs().max().item())
