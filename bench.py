@@ -1,0 +1,191 @@
+"""Benchmark of the model-local worker step on one MI355X.
+
+A step is one pass of the whole hot path over one batch of the Qwen2.5-3B-shaped pipeline
+workload (configuration 1: d=2048, V=151936, 64 trajectories x 3 roles x 256 tokens, bf16):
+umas_assign_token_rewards -> umas_advantages -> umas_ppo_loss_fwd_bwd (scoring, clipped
+surrogate, backward to hidden states and LM-head weights).  All inputs are resident in HBM
+before the timed region.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0
+
+
+def cpu_baseline(w, t, sample_rows):
+    """The oracle's scoring + surrogate + backward on the first `sample_rows` rows, host cores only."""
+    from oracle import umas_oracle as orc
+    n = sample_rows
+    H, ids = t["H"][:n], t["ids"][:n]
+    t0 = time.perf_counter()
+    logp, lse, ent = orc.score(H, t["W"], ids)
+    logp_old = (logp + t["noise"][:n]).astype(np.float32)
+    adv = np.ones(n)
+    stats, g = orc.ppo_loss(logp, logp_old, adv, ent, None, np.zeros(n, np.int32), 0, w.clip_eps)
+    orc.lm_head_backward(H, t["W"], ids, lse, g)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": n / dt, "unit": "scored tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {n} rows of the same workload (same W), scoring+loss+backward in float64, {dt:.1f} s"}
+
+
+def hbm_kernels(umas, wl, torch, cfg, n_traj, iters=5):
+    """Reward/routing and scan kernels on a batch-replicated instance: achieved GB/s on algorithmic bytes."""
+    w = wl.make_workload(cfg, n_traj=n_traj)
+    mask = torch.from_numpy(w.tok_mask).cuda()
+    value = None if w.value is None else torch.from_numpy(w.value).cuda()
+    kw = dict(n_roles=w.n_roles, n_models=w.n_models, role_to_model=w.role_to_model, traj_turn_off=w.traj_turn_off,
+              turn_role=w.turn_role, turn_tok_off=w.turn_tok_off, tok_mask_global=mask, traj_group=w.traj_group,
+              role_reward=w.role_reward, turn_reward=w.turn_reward, traj_reward=w.traj_reward, place_mode=w.place_mode)
+    for _ in range(2):
+        s = umas.umas_assign_token_rewards(**kw)
+        umas.umas_advantages(s, value, w.gamma, w.lam, w.gamma_turn, w.seg_mode)
+    torch.cuda.synchronize()
+    umas.profile_enable(True)
+    for _ in range(iters):
+        s = umas.umas_assign_token_rewards(**kw)
+        umas.umas_advantages(s, value, w.gamma, w.lam, w.gamma_turn, w.seg_mode)
+    torch.cuda.synchronize()
+    prof = umas.profile_read()
+    umas.profile_enable(False)
+    N = w.n_tokens
+    scored = int(w.tok_mask.sum())
+    scan_ms = sum(prof[k][0] for k in prof if k.startswith("k_scan")) / iters
+    route_names = [k for k in prof if not k.startswith("k_scan")]
+    route_ms = sum(prof[k][0] for k in route_names) / iters
+    scan_bytes = (17 if value is not None else 13) * N
+    route_bytes = (1 + 8 + 4 + 4 + 1 + 4) * N + 4 * scored
+    return {"workload": f"{w.name} x{n_traj} trajectories", "tokens": N,
+            "scan": {"ms": scan_ms, "algorithmic_bytes": scan_bytes, "GBps": scan_bytes / scan_ms / 1e6,
+                     "frac_of_hbm_peak": scan_bytes / scan_ms / 1e6 / PEAK_HBM_GBPS},
+            "route_place": {"ms": route_ms, "algorithmic_bytes": route_bytes, "GBps": route_bytes / route_ms / 1e6,
+                            "frac_of_hbm_peak": route_bytes / route_ms / 1e6 / PEAK_HBM_GBPS},
+            "kernels_ms": {k: v[0] / iters for k, v in prof.items()}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--cpu-rows", type=int, default=192, help="rows of the CPU-oracle baseline sample (0 = skip)")
+    ap.add_argument("--no-hbm", action="store_true", help="skip the batch-replicated reward/scan measurement")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no collectives or sharding; run with --gpus 1")
+
+    import torch
+    import workloads as wl
+    import paper_2605_26646_amd as umas
+    umas.load_library()          # fails loudly when the HIP library is missing
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    dev = torch.device("cuda:0")
+
+    w = wl.make_workload(1)
+    spec = w.models[0]
+    t = w.model_tensors(0)
+    H = torch.from_numpy(t["H"]).to(dev).bfloat16()
+    W = torch.from_numpy(t["W"]).to(dev).bfloat16()
+    ids = torch.from_numpy(t["ids"]).to(dev)
+    mask = torch.from_numpy(w.tok_mask).to(dev)
+    noise = torch.from_numpy(t["noise"]).to(dev)
+    kw = dict(n_roles=w.n_roles, n_models=w.n_models, role_to_model=w.role_to_model, traj_turn_off=w.traj_turn_off,
+              turn_role=w.turn_role, turn_tok_off=w.turn_tok_off, tok_mask_global=mask, turn_pred_off=w.turn_pred_off,
+              turn_pred=w.turn_pred, traj_group=w.traj_group, traj_reward=w.traj_reward, place_mode=w.place_mode)
+
+    # set-up outside the timed region: routing once to learn the selection size, old log-probs, buffers
+    s = umas.umas_assign_token_rewards(**kw)
+    torch.cuda.synchronize()
+    n_sel = int(s.model_rowsel_off[1].item())
+    rowsel = s.rowsel[:n_sel]
+    t0 = time.perf_counter()
+    logp, _, _ = umas.umas_policy_logprobs(H, W, ids, rowsel)
+    torch.cuda.synchronize()
+    logprobs_ms = None
+    for _ in range(2):
+        t0 = time.perf_counter()
+        logp, _, _ = umas.umas_policy_logprobs(H, W, ids, rowsel)
+        torch.cuda.synchronize()
+        logprobs_ms = (time.perf_counter() - t0) * 1e3
+    logp_old = logp + noise * mask.float()
+    ws = torch.empty(umas.ppo_workspace_bytes(n_sel, spec.d, spec.V, torch.bfloat16, w.n_roles), dtype=torch.uint8,
+                     device=dev)
+    dW = torch.empty((spec.V, spec.d), dtype=torch.float32, device=dev)
+    dH = torch.empty_like(H)
+    logp_new = torch.empty(w.n_tokens, dtype=torch.float32, device=dev)
+    stats = torch.empty((1 + w.n_roles) * 32, dtype=torch.uint8, device=dev)
+
+    def step():
+        st = umas.umas_assign_token_rewards(**kw)
+        adv, _ = umas.umas_advantages(st, None, w.gamma, w.lam, w.gamma_turn, w.seg_mode)
+        umas.umas_ppo_loss_fwd_bwd(H, W, ids, st.rowsel[:n_sel], logp_old, adv, st.tok_role, w.n_roles, w.clip_eps,
+                                   dW=dW, dH=dH, logp_new=logp_new, stats=stats, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    umas.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = umas.profile_read()
+    umas.profile_enable(False)
+    ms_per_step = elapsed * 1e3 / args.steps
+    loss = float(umas.read_stats(stats)["loss"][0])
+
+    # dominant kernel: the one with the largest summed time; every MFMA kernel does 2*V*d flop per row
+    per_launch = {k: v[0] / v[1] for k, v in prof.items()}
+    per_step = {k: v[0] / args.steps for k, v in prof.items()}
+    dom = max(per_step, key=per_step.get)
+    launches_per_step = prof[dom][1] / args.steps
+    rows_per_launch = n_sel / launches_per_step
+    flop_per_launch = 2.0 * spec.V * spec.d * rows_per_launch
+    achieved = flop_per_launch / (per_launch[dom] * 1e-3) / 1e12
+    algorithmic = 6.0 * spec.V * spec.d * n_sel
+    out = {
+        "metric": "scored tokens/sec, PPO loss fwd+bwd (3B-shape, V=151936) + % bf16 MFMA peak",
+        "value": n_sel / (ms_per_step * 1e-3), "unit": "scored tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg1 Qwen2.5-3B-shaped pipeline: d=2048 V=151936, 64 traj x 3 roles x 256 tokens",
+                   "tokens": w.n_tokens, "scored_tokens": n_sel, "step": "assign_token_rewards + advantages + ppo_loss_fwd_bwd"},
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "flop_per_launch": flop_per_launch, "ms_per_launch": per_launch[dom]},
+        "whole_step": {"algorithmic_tflops": algorithmic / (ms_per_step * 1e-3) / 1e12,
+                       "frac_of_bf16_peak_algorithmic_6Vd": algorithmic / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                       "frac_of_bf16_peak_executed_8Vd": algorithmic * 8 / 6 / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+        "kernels_ms_per_step": per_step,
+        "policy_logprobs_ms": logprobs_ms,
+        "loss": loss,
+    }
+    if not args.no_hbm:
+        del ws, dW, dH
+        torch.cuda.empty_cache()
+        out["hbm_kernels"] = [hbm_kernels(umas, wl, torch, 4, 8192), hbm_kernels(umas, wl, torch, 1, 131072)]
+    if args.cpu_rows > 0:
+        out["cpu_baseline"] = cpu_baseline(w, t, args.cpu_rows)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

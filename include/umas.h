@@ -199,6 +199,16 @@ umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_dtype dtype
                                   float* logp_new, void* dH, float* dW,
                                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Kernel timing aid for benchmarks (not part of the method).  While enabled, every kernel launch
+ * of the library is followed by a HIP event on its stream and the time between consecutive events
+ * of one call is booked to the kernel launched in between.  umas_profile_enable(on) discards earlier
+ * records.  umas_profile_read waits for the recorded events and returns, per kernel name in order of
+ * first launch, the summed milliseconds and the number of launches: names is HOST char [cap][32],
+ * total_ms HOST float [cap], launches HOST int32 [cap]; returns the number of names or -1 on a HIP
+ * error.  Not thread-safe; meant for a single benchmarking thread. */
+umas_status umas_profile_enable(int32_t on);
+int32_t umas_profile_read(char* names, float* total_ms, int32_t* launches, int32_t cap);
+
 #ifdef __cplusplus
 }
 #endif

@@ -8,6 +8,6 @@ PyTorch supplies device memory and the current stream, nothing else.
 from .binding import (  # noqa: F401
     UmasError, Streams, lib_path, load_library,
     umas_assign_token_rewards, umas_advantages, umas_policy_logprobs, umas_ppo_loss_fwd_bwd,
-    ppo_workspace_bytes, read_stats,
+    ppo_workspace_bytes, read_stats, profile_enable, profile_read,
     PLACE_LAST, PLACE_ALL, SEG_TURN, SEG_TRAJ,
 )

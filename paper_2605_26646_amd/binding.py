@@ -286,3 +286,28 @@ def umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv, tok_role, n_roles, c
 def read_stats(stats: torch.Tensor) -> np.ndarray:
     """Copy the device umas_loss_stats array to a numpy structured array (synchronises)."""
     return stats.cpu().numpy().view(STATS_DTYPE)
+
+
+def profile_enable(on: bool) -> None:
+    """Switch the library's per-kernel event timing on (discarding earlier records) or off."""
+    lib = load_library()
+    lib.umas_profile_enable.restype = C.c_int
+    lib.umas_profile_enable.argtypes = [C.c_int32]
+    _check(lib, lib.umas_profile_enable(1 if on else 0))
+
+
+def profile_read(cap: int = 64) -> dict:
+    """{kernel name: (total milliseconds, launches)} since profile_enable(True); synchronises."""
+    lib = load_library()
+    lib.umas_profile_read.restype = C.c_int32
+    lib.umas_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
+    names = C.create_string_buffer(32 * cap)
+    ms = (C.c_float * cap)()
+    cnt = (C.c_int32 * cap)()
+    n = lib.umas_profile_read(names, ms, cnt, cap)
+    if n < 0:
+        raise UmasError(-5, "umas_profile_read failed")
+    out = {}
+    for i in range(n):
+        out[names.raw[32 * i:32 * i + 32].split(b"\0")[0].decode()] = (float(ms[i]), int(cnt[i]))
+    return out

@@ -13,6 +13,11 @@ namespace umas {
 
 umas_status fail(umas_status code, const char* fmt, ...);
 
+// Kernel timing aid (umas_profile_enable / umas_profile_read).
+extern bool g_prof_on;
+void prof_mark(hipStream_t st);                     // opens an interval at the start of an API call
+void prof_kernel(const char* name, hipStream_t st); // closes the interval of the kernel just launched
+
 #define UMAS_HIP(expr)                                                                 \
   do {                                                                                 \
     hipError_t e__ = (expr);                                                           \
@@ -20,11 +25,14 @@ umas_status fail(umas_status code, const char* fmt, ...);
       return ::umas::fail(UMAS_EHIP, "%s failed: %s", #expr, hipGetErrorString(e__)); \
   } while (0)
 
+// After every kernel launch: check the launch and, when kernel timing is on, close the kernel's
+// interval with an event on its stream `st` (intervals open at prof_mark or at the previous launch).
 #define UMAS_LAUNCHED(name)                                                                  \
   do {                                                                                       \
     hipError_t e__ = hipGetLastError();                                                      \
     if (e__ != hipSuccess)                                                                   \
       return ::umas::fail(UMAS_EHIP, "launch of %s failed: %s", name, hipGetErrorString(e__)); \
+    if (::umas::g_prof_on) ::umas::prof_kernel(name, st);                                    \
   } while (0)
 
 #define UMAS_REQUIRE(cond, code, ...) \

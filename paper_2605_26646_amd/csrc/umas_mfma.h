@@ -40,7 +40,9 @@ template <class C>
 __device__ __forceinline__ int slot_row(int i) { return (threadIdx.x >> 3) + i * C::ROWS_PER_PASS; }
 __device__ __forceinline__ int slot_kofs() { return (threadIdx.x & 7) * 8; }
 
-// pa[i] / pb[i]: address of (row of slot i, k = slot_kofs()) or nullptr for a row outside the matrix.
+// pa[i] / pb[i]: address of (row of slot i, k = slot_kofs()); always a readable row: callers clamp rows
+// outside the matrix to a valid one and ignore the results that come from them.  Only the K tail
+// (K not a multiple of 64) is zero-filled, because every output depends on it.
 template <class C>
 __device__ __forceinline__ void mfma_mainloop(const uint16_t* const (&pa)[C::NA], const uint16_t* const (&pb)[C::NB],
                                               int K, uint16_t* lds, floatx16 (&acc)[C::TM][C::TN]) {
@@ -48,15 +50,31 @@ __device__ __forceinline__ void mfma_mainloop(const uint16_t* const (&pa)[C::NA]
   const int wm = wave / C::WN, wn = wave % C::WN;
   const int kofs = slot_kofs();
   uint4 ra[C::NA], rb[C::NB];
-  const uint4 zero = make_uint4(0, 0, 0, 0);
+  const int nk = (K + C::BK - 1) / C::BK;
+  const bool ktail = (K % C::BK) != 0;
 
   auto gload = [&](int kt) {
     const int k = kt * C::BK;
-    const bool kin = k + kofs < K;
+    if (ktail && kt == nk - 1) {
+      // clamp the address into the row and drop what lies past K
+      const bool kin = k + kofs < K;
+      const int kk = kin ? k : 0;
 #pragma unroll
-    for (int i = 0; i < C::NA; ++i) ra[i] = (pa[i] && kin) ? *reinterpret_cast<const uint4*>(pa[i] + k) : zero;
+      for (int i = 0; i < C::NA; ++i) {
+        uint4 v = *reinterpret_cast<const uint4*>(pa[i] + kk);
+        ra[i] = make_uint4(kin ? v.x : 0u, kin ? v.y : 0u, kin ? v.z : 0u, kin ? v.w : 0u);
+      }
 #pragma unroll
-    for (int i = 0; i < C::NB; ++i) rb[i] = (pb[i] && kin) ? *reinterpret_cast<const uint4*>(pb[i] + k) : zero;
+      for (int i = 0; i < C::NB; ++i) {
+        uint4 v = *reinterpret_cast<const uint4*>(pb[i] + kk);
+        rb[i] = make_uint4(kin ? v.x : 0u, kin ? v.y : 0u, kin ? v.z : 0u, kin ? v.w : 0u);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < C::NA; ++i) ra[i] = *reinterpret_cast<const uint4*>(pa[i] + k);
+#pragma unroll
+      for (int i = 0; i < C::NB; ++i) rb[i] = *reinterpret_cast<const uint4*>(pb[i] + k);
+    }
   };
   auto swrite = [&](int stage) {
     uint16_t* sa = lds + stage * C::STAGE;
@@ -84,7 +102,6 @@ __device__ __forceinline__ void mfma_mainloop(const uint16_t* const (&pa)[C::NA]
     }
   };
 
-  const int nk = (K + C::BK - 1) / C::BK;
   gload(0);
   swrite(0);
   __syncthreads();

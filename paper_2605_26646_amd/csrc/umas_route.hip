@@ -429,6 +429,7 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
                UMAS_EWORKSPACE, "workspace must be 256-byte aligned and hold %zu bytes (got %zu)", need,
                workspace_bytes);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  prof_mark(st);
   const int R = g->n_roles, K = g->n_models, B = g->n_traj, U = g->n_turns;
   const int64_t N = g->n_tokens;
   Carver c(workspace);
@@ -466,6 +467,7 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
   }
   // the host arrays are only promised for the duration of the call: wait until the copies have read them
   UMAS_HIP(hipStreamSynchronize(st));
+  prof_mark(st);
 
   const float* traj_r = r->traj_reward ? w.traj_reward : nullptr;
   if (n_groups > 0) {

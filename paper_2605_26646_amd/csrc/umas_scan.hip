@@ -255,6 +255,7 @@ extern "C" umas_status umas_advantages(const umas_streams* s, int64_t n_tokens, 
                workspace_bytes);
   if (n_tokens == 0) return UMAS_OK;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  prof_mark(st);
   const int nblk = cdiv(n_tokens, kTile);
   Carver c(workspace);
   Aff* blk_fold = c.take<Aff>(nblk);

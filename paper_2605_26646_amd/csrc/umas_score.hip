@@ -58,7 +58,9 @@ hipError_t fill_bytes_zero(void* p, size_t bytes, hipStream_t st) {
   if (n == 0) return hipSuccess;
   const unsigned grid = static_cast<unsigned>(n / 256 + 1 < 65536 ? n / 256 + 1 : 65536);
   hipLaunchKernelGGL(k_fill_u32, dim3(grid), dim3(256), 0, st, static_cast<uint32_t*>(p), n, 0u);
-  return hipGetLastError();
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess && g_prof_on) prof_kernel("k_fill_u32", st);
+  return e;
 }
 
 // out[c, r] = in[row(r), c] for r < n_r (row(r) = rowsel[r] or r), zero for n_r <= r < ld_out;
@@ -102,13 +104,13 @@ k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, in
   const int kofs = slot_kofs();
 #pragma unroll
   for (int i = 0; i < C::NA; ++i) {
-    const int v = m0 + slot_row<C>(i);
-    pa[i] = v < V ? W + static_cast<int64_t>(v) * d + kofs : nullptr;
+    const int v = min(m0 + slot_row<C>(i), V - 1);                  // rows past V: results are masked below
+    pa[i] = W + static_cast<int64_t>(v) * d + kofs;
   }
 #pragma unroll
   for (int i = 0; i < C::NB; ++i) {
-    const int64_t n = n0 + slot_row<C>(i);
-    pb[i] = n < n_sel ? H + static_cast<int64_t>(rowsel ? rowsel[n] : n) * d + kofs : nullptr;
+    const int64_t n = min(n0 + slot_row<C>(i), n_sel - 1);          // rows past n_sel: results are never read
+    pb[i] = H + static_cast<int64_t>(rowsel ? rowsel[n] : n) * d + kofs;
   }
   floatx16 acc[C::TM][C::TN];
 #pragma unroll
@@ -351,13 +353,13 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
   const int kofs = slot_kofs();
 #pragma unroll
   for (int i = 0; i < C::NA; ++i) {
-    const int v = m0 + slot_row<C>(i);
-    pa[i] = v < V ? W + static_cast<int64_t>(v) * d + kofs : nullptr;
+    const int v = min(m0 + slot_row<C>(i), V - 1);                  // rows past V are written as 0 below
+    pa[i] = W + static_cast<int64_t>(v) * d + kofs;
   }
 #pragma unroll
   for (int i = 0; i < C::NB; ++i) {
-    const int64_t n = n0 + slot_row<C>(i);
-    pb[i] = n < mc ? H + static_cast<int64_t>(rowsel ? rowsel[c0 + n] : c0 + n) * d + kofs : nullptr;
+    const int64_t n = min(n0 + slot_row<C>(i), mc - 1);             // rows past the chunk are written as 0 below
+    pb[i] = H + static_cast<int64_t>(rowsel ? rowsel[c0 + n] : c0 + n) * d + kofs;
   }
   floatx16 acc[C::TM][C::TN];
 #pragma unroll
@@ -427,13 +429,13 @@ k_gemm_tn(const uint16_t* __restrict__ A, int64_t lda, int64_t m_rows, const uin
   const int kofs = slot_kofs();
 #pragma unroll
   for (int i = 0; i < C::NA; ++i) {
-    const int64_t m = m0 + slot_row<C>(i);
-    pa[i] = m < m_rows ? A + m * lda + kofs : nullptr;
+    const int64_t m = min(m0 + slot_row<C>(i), m_rows - 1);         // clamped rows are not stored below
+    pa[i] = A + m * lda + kofs;
   }
 #pragma unroll
   for (int i = 0; i < C::NB; ++i) {
-    const int n = n0 + slot_row<C>(i);
-    pb[i] = n < n_rows ? B + static_cast<int64_t>(n) * ldb + kofs : nullptr;
+    const int n = min(n0 + slot_row<C>(i), n_rows - 1);
+    pb[i] = B + static_cast<int64_t>(n) * ldb + kofs;
   }
   floatx16 acc[C::TM][C::TN];
 #pragma unroll
@@ -656,6 +658,7 @@ extern "C" umas_status umas_policy_logprobs(const void* H, const void* W, umas_d
   s = check_ws(workspace, workspace_bytes, umas_policy_logprobs_workspace_bytes(n_sel, d, V, dtype));
   if (s != UMAS_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  prof_mark(st);
   if (rowsel && n_rows > 0) {
     UMAS_HIP(fill_bytes_zero(logp, n_rows * sizeof(float), st));
     UMAS_HIP(fill_bytes_zero(lse, n_rows * sizeof(float), st));
@@ -710,6 +713,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
   s = check_ws(workspace, workspace_bytes, umas_ppo_loss_workspace_bytes_min(n_sel, d, V, dtype, n_roles));
   if (s != UMAS_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  prof_mark(st);
   const size_t esz = dtype == UMAS_BF16 ? 2 : 4;
   Carver c(workspace);
   PpoWs w;
@@ -787,13 +791,13 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     hipLaunchKernelGGL(k_gemm_tn<0>, dim3(tile_grid<kGM, kGN>(tiles_r, tiles_d)), dim3(Cfg::T), 0, st, dZ, Vp, mcp, w.Wt,
                        Vp, d, static_cast<int>(Vp), tiles_r, tiles_d, dH, static_cast<int64_t>(d), rowsel, c0, rows, 0, Wb, ids,
                        w.g_c);
-    UMAS_LAUNCHED("k_gemm_tn<dH>");
+    UMAS_LAUNCHED("k_gemm_tn_dH");
     hipLaunchKernelGGL(k_gemm_tn<1>, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_d)), dim3(Cfg::T), 0, st, dZt, mcp, Vp, Ht,
                        mcp, d, static_cast<int>(mcp), tiles_v, tiles_d, dW, static_cast<int64_t>(d),
                        static_cast<const int32_t*>(nullptr), static_cast<int64_t>(0), static_cast<int64_t>(V),
                        (accumulate_dW || c0 > 0) ? 1 : 0, static_cast<const uint16_t*>(nullptr),
                        static_cast<const int32_t*>(nullptr), static_cast<const float*>(nullptr));
-    UMAS_LAUNCHED("k_gemm_tn<dW>");
+    UMAS_LAUNCHED("k_gemm_tn_dW");
   }
   hipLaunchKernelGGL(k_dw_onehot, dim3(cdiv(n_sel, 4)), dim3(256), 0, st, Hb, d, rowsel, n_sel, ids, w.g_c, dW);
   UMAS_LAUNCHED("k_dw_onehot");

@@ -102,23 +102,25 @@ class Workload:
         """
         spec = self.models[m]
         n = self.model_ntok[m] if rows is None else min(rows, self.model_ntok[m])
-        rng_h = np.random.default_rng([self.seed, 1000 + m])
-        rng_w = np.random.default_rng([self.seed, 2000 + m])
         rng_i = np.random.default_rng([self.seed, 3000 + m])
         rng_n = np.random.default_rng([self.seed, 4000 + m])
-        H = np.empty((n, spec.d), dtype=np.float32)
-        step = max(1, (1 << 24) // spec.d)
-        for r0 in range(0, n, step):
-            blk = rng_h.standard_normal((min(step, n - r0), spec.d), dtype=np.float32)
-            rms = np.sqrt(np.mean(blk * blk, axis=1, dtype=np.float32), dtype=np.float32)
-            H[r0:r0 + blk.shape[0]] = blk / rms[:, None]
-        W = np.empty((spec.V, spec.d), dtype=np.float32)
-        for r0 in range(0, spec.V, step):
-            r1 = min(spec.V, r0 + step)
-            W[r0:r1] = rng_w.standard_normal((r1 - r0, spec.d), dtype=np.float32) * np.float32(0.02)
-        if spec.dtype == "bf16":
-            H = round_to_bf16(H)
-            W = round_to_bf16(W)
+        bf16 = spec.dtype == "bf16"
+
+        def h_block(out, blk, r0, r1):
+            g = np.random.default_rng([self.seed, 1000 + m, blk])
+            x = g.standard_normal((r1 - r0, spec.d), dtype=np.float32)
+            rms = np.sqrt(np.mean(x * x, axis=1, dtype=np.float32), dtype=np.float32)
+            x /= rms[:, None]
+            out[r0:r1] = round_to_bf16(x) if bf16 else x
+
+        def w_block(out, blk, r0, r1):
+            g = np.random.default_rng([self.seed, 2000 + m, blk])
+            x = g.standard_normal((r1 - r0, spec.d), dtype=np.float32)
+            x *= np.float32(0.02)
+            out[r0:r1] = round_to_bf16(x) if bf16 else x
+
+        H = _fill_blocks(n, spec.d, h_block)
+        W = _fill_blocks(spec.V, spec.d, w_block)
         k = np.arange(1, spec.V + 1, dtype=np.float64)
         cdf = np.cumsum(k ** -1.1)
         cdf /= cdf[-1]
@@ -126,6 +128,20 @@ class Workload:
         ids = np.minimum(ids, spec.V - 1).astype(np.int32)
         noise = (rng_n.standard_normal(n) * self.noise_std).astype(np.float32)
         return {"H": H, "W": W, "ids": ids, "noise": noise}
+
+
+def _fill_blocks(n_rows: int, n_cols: int, fill) -> np.ndarray:
+    """Float32 [n_rows, n_cols] filled block by block; every block of rows draws from a stream of
+    its own, so the result does not depend on how many threads fill it."""
+    from concurrent.futures import ThreadPoolExecutor
+    import os
+    out = np.empty((n_rows, n_cols), dtype=np.float32)
+    step = max(1, (1 << 22) // max(n_cols, 1))
+    jobs = [(b, r0, min(n_rows, r0 + step)) for b, r0 in enumerate(range(0, n_rows, step))]
+    workers = max(1, min(16, os.cpu_count() or 1, len(jobs)))
+    with ThreadPoolExecutor(workers) as ex:
+        list(ex.map(lambda j: fill(out, *j), jobs))
+    return out
 
 
 def _chain_preds(traj_turn_off: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
