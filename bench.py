@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--cpu-rows", type=int, default=192, help="rows of the CPU-oracle baseline sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the CPU-oracle baseline sample (0 = skip)")
     ap.add_argument("--no-hbm", action="store_true", help="skip the batch-replicated reward/scan measurement")
     args = ap.parse_args()
     if args.gpus != 1:
