@@ -114,6 +114,114 @@ __device__ __forceinline__ void mfma_mainloop(const uint16_t* const (&pa)[C::NA]
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Fast main loop for K % 64 == 0: tiles go from global memory straight into LDS
+// (buffer_load_dwordx4 ... lds: no staging registers, no ds_write), fragments are read one 16-wide
+// K-slice ahead of the MFMAs that consume them.
+//
+// LDS layout: rows of 128 bytes without padding; the 16-byte chunk c of row r sits in slot
+// c ^ ((r >> 1) & 7), which spreads the fragment reads of 16 consecutive rows over all banks.
+// One wavefront-wide load instruction fills 8 consecutive rows (1 KB); lane l of it fills slot l & 7
+// of row l >> 3, so it fetches chunk (l & 7) ^ ((row >> 1) & 7) of that row from global memory.
+//
+// Operands are addressed as raw buffers: a wave-uniform base (the caller picks it so that every
+// byte offset of the tile fits 32 bits) plus one 32-bit byte offset per load slot.
+template <class C>
+struct DirectCfg {
+  static constexpr int ROWB = 128;                                 // bytes per LDS row
+  static constexpr int STAGEB = (C::BM + C::BN) * ROWB;            // bytes per stage
+  static constexpr int LDS_BYTES = 2 * STAGEB;
+};
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0xFFFFFFFF, 0x00020000);
+}
+
+// K offset (in elements) of the chunk this thread fetches for all of its slots.
+__device__ __forceinline__ int direct_kofs() {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  return 8 * ((lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7));
+}
+
+// oa[i] / ob[i]: byte offset from the operand's base of (row of slot i, k = direct_kofs()); rows outside
+// the matrix are clamped to a valid row by the caller, which ignores what comes out of them.
+template <class C>
+__device__ __forceinline__ void mfma_mainloop_direct(__amdgpu_buffer_rsrc_t ra, const uint32_t (&oa)[C::NA],
+                                                     __amdgpu_buffer_rsrc_t rb, const uint32_t (&ob)[C::NB], int K,
+                                                     uint16_t* lds, floatx16 (&acc)[C::TM][C::TN]) {
+  using D = DirectCfg<C>;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / C::WN, wn = wave % C::WN;
+  char* base = reinterpret_cast<char*>(lds);
+  const int nk = K / C::BK;
+
+  // slot i of this wavefront fills rows [i*ROWS_PER_PASS + wave*8, +8) of the A (or B) area; the
+  // loads of one K-step are issued in BK/16 parts, one part under each K-slice's MFMAs
+  constexpr int kParts = C::BK / 16;
+  static_assert(C::NA % kParts == 0 && C::NB % kParts == 0, "load slots split evenly over the K-slices");
+  auto gload_part = [&](int kt, int stage, int part) {
+    const int kbytes = kt * C::BK * 2;
+    char* sa = base + stage * D::STAGEB + wave * 8 * D::ROWB;
+    char* sb = sa + C::BM * D::ROWB;
+#pragma unroll
+    for (int i = part * (C::NA / kParts); i < (part + 1) * (C::NA / kParts); ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, reinterpret_cast<uint32_t*>(sa + i * C::ROWS_PER_PASS * D::ROWB), 16,
+                                               oa[i], kbytes, 0, 0);
+#pragma unroll
+    for (int i = part * (C::NB / kParts); i < (part + 1) * (C::NB / kParts); ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, reinterpret_cast<uint32_t*>(sb + i * C::ROWS_PER_PASS * D::ROWB), 16,
+                                               ob[i], kbytes, 0, 0);
+  };
+
+  // byte offsets of this lane's fragment chunk for the four K-slices of a stage
+  const int sw = (lane >> 1) & 7;
+  int coff[C::BK / 16];
+#pragma unroll
+  for (int kk = 0; kk < C::BK / 16; ++kk) coff[kk] = ((kk * 2 + (lane >> 5)) ^ sw) * 16;
+  const int arow = (wm * C::WTM + (lane & 31)) * D::ROWB;
+  const int brow = (C::BM + wn * C::WTN + (lane & 31)) * D::ROWB;
+
+  bf16x8 af[2][C::TM], bfr[2][C::TN];
+  auto fload = [&](int buf, int stage, int kk) {
+    const char* sa = base + stage * D::STAGEB + arow + coff[kk];
+    const char* sb = base + stage * D::STAGEB + brow + coff[kk];
+#pragma unroll
+    for (int tm = 0; tm < C::TM; ++tm) af[buf][tm] = *reinterpret_cast<const bf16x8*>(sa + tm * 32 * D::ROWB);
+#pragma unroll
+    for (int tn = 0; tn < C::TN; ++tn) bfr[buf][tn] = *reinterpret_cast<const bf16x8*>(sb + tn * 32 * D::ROWB);
+  };
+
+#pragma unroll
+  for (int part = 0; part < kParts; ++part) gload_part(0, 0, part);
+  __syncthreads();
+  fload(0, 0, 0);
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    // The other stage was last read before the barrier that ended the previous step.  In the last
+    // step the loads repeat the final tile, which nobody uses, to keep the loop branch-free.
+    const int kn = kt + 1 < nk ? kt + 1 : kt;
+#pragma unroll
+    for (int kk = 0; kk < kParts; ++kk) {
+      // Memory phase: a quarter of the next tile's global->LDS loads and the fragment reads of the
+      // next K-slice.  Compute phase: the MFMAs of this slice, whose fragments were requested one
+      // phase earlier.  The fences keep the two phases in this order so that every read has a whole
+      // compute phase to land.
+      gload_part(kn, cur ^ 1, kk);
+      if (kk + 1 < kParts) fload((kk + 1) & 1, cur, kk + 1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < C::TN; ++tn)
+          acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][tm], bfr[kk & 1][tn], acc[tm][tn], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
+    fload(0, cur ^ 1, 0);
+  }
+}
+
 // Position of accumulator element (tm, tn, r) inside the workgroup tile.
 template <class C>
 __device__ __forceinline__ int acc_row(int tm, int r) {

@@ -86,6 +86,45 @@ __global__ void k_transpose_bf16(const uint16_t* __restrict__ in, int64_t n_c, c
   }
 }
 
+// Logit tile Z[v, n] = W[m0 + v, :] . H[row(n0 + n), :] for a 256x256 block of (vocabulary, selected rows),
+// row(n) = rowsel[sel0 + n] or sel0 + n.  Rows past V and past n_lim are clamped to valid ones; the
+// callers mask what comes out of them.
+template <class C>
+__device__ __forceinline__ void logit_tile(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
+                                           const int32_t* __restrict__ rowsel, int64_t sel0, int64_t n_lim, int m0,
+                                           int64_t n0, uint16_t* lds, floatx16 (&acc)[C::TM][C::TN]) {
+#pragma unroll
+  for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < C::TN; ++tn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
+  if (d % C::BK == 0) {
+    const uint32_t kofs = direct_kofs();
+    uint32_t oa[C::NA], ob[C::NB];
+#pragma unroll
+    for (int i = 0; i < C::NA; ++i) oa[i] = (static_cast<uint32_t>(min(slot_row<C>(i), V - 1 - m0)) * d + kofs) * 2u;
+#pragma unroll
+    for (int i = 0; i < C::NB; ++i) {
+      const int64_t n = sel0 + min(n0 + slot_row<C>(i), n_lim - 1);
+      ob[i] = (static_cast<uint32_t>(rowsel ? rowsel[n] : n) * d + kofs) * 2u;   // host checks n_rows*d*2 < 2^32
+    }
+    mfma_mainloop_direct<C>(make_rsrc(W + static_cast<int64_t>(m0) * d), oa, make_rsrc(H), ob, d, lds, acc);
+  } else {
+    const int kofs = slot_kofs();
+    const uint16_t* pa[C::NA];
+    const uint16_t* pb[C::NB];
+#pragma unroll
+    for (int i = 0; i < C::NA; ++i) pa[i] = W + static_cast<int64_t>(min(m0 + slot_row<C>(i), V - 1)) * d + kofs;
+#pragma unroll
+    for (int i = 0; i < C::NB; ++i) {
+      const int64_t n = sel0 + min(n0 + slot_row<C>(i), n_lim - 1);
+      pb[i] = H + static_cast<int64_t>(rowsel ? rowsel[n] : n) * d + kofs;
+    }
+    mfma_mainloop<C>(pa, pb, d, lds, acc);
+  }
+}
+
 // ------------------------------------------------------------------ bf16: logit tiles -> partials
 // A = W (vocabulary rows on the M side, so one lane sees many vocabulary entries of one token),
 // B = selected rows of H.  partial[tile_m][n] = (m, s, t, taken logit or 0).
@@ -99,27 +138,8 @@ k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, in
   if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
   const int m0 = tile_m * C::BM;
   const int64_t n0 = static_cast<int64_t>(tile_n) * C::BN;
-  const uint16_t* pa[C::NA];
-  const uint16_t* pb[C::NB];
-  const int kofs = slot_kofs();
-#pragma unroll
-  for (int i = 0; i < C::NA; ++i) {
-    const int v = min(m0 + slot_row<C>(i), V - 1);                  // rows past V: results are masked below
-    pa[i] = W + static_cast<int64_t>(v) * d + kofs;
-  }
-#pragma unroll
-  for (int i = 0; i < C::NB; ++i) {
-    const int64_t n = min(n0 + slot_row<C>(i), n_sel - 1);          // rows past n_sel: results are never read
-    pb[i] = H + static_cast<int64_t>(rowsel ? rowsel[n] : n) * d + kofs;
-  }
   floatx16 acc[C::TM][C::TN];
-#pragma unroll
-  for (int tm = 0; tm < C::TM; ++tm)
-#pragma unroll
-    for (int tn = 0; tn < C::TN; ++tn)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
-  mfma_mainloop<C>(pa, pb, d, lds, acc);
+  logit_tile<C>(W, H, d, V, rowsel, 0, n_sel, m0, n0, lds, acc);
 
   // epilogue: the tile buffers are free now
   float* s_part = reinterpret_cast<float*>(lds);          // [WM][BN][3]
@@ -348,27 +368,8 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
   if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
   const int m0 = tile_m * C::BM;
   const int64_t n0 = static_cast<int64_t>(tile_n) * C::BN;   // chunk-relative
-  const uint16_t* pa[C::NA];
-  const uint16_t* pb[C::NB];
-  const int kofs = slot_kofs();
-#pragma unroll
-  for (int i = 0; i < C::NA; ++i) {
-    const int v = min(m0 + slot_row<C>(i), V - 1);                  // rows past V are written as 0 below
-    pa[i] = W + static_cast<int64_t>(v) * d + kofs;
-  }
-#pragma unroll
-  for (int i = 0; i < C::NB; ++i) {
-    const int64_t n = min(n0 + slot_row<C>(i), mc - 1);             // rows past the chunk are written as 0 below
-    pb[i] = H + static_cast<int64_t>(rowsel ? rowsel[c0 + n] : c0 + n) * d + kofs;
-  }
   floatx16 acc[C::TM][C::TN];
-#pragma unroll
-  for (int tm = 0; tm < C::TM; ++tm)
-#pragma unroll
-    for (int tn = 0; tn < C::TN; ++tn)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
-  mfma_mainloop<C>(pa, pb, d, lds, acc);
+  logit_tile<C>(W, H, d, V, rowsel, c0, mc, m0, n0, lds, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN;
@@ -413,30 +414,25 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
 // EPI 0: dH[rowsel[c0 + m], j] = bf16(C[m, j] + g[m] W[y[m], j]) for m < mc  (A = dZ [mcp, Vp], B = Wt [d, Vp])
 // EPI 1: dW[v, j] (+)= C[v, j]                              (A = dZt [Vp, mcp], B = Ht [d, mcp])
 template <int EPI>
-__global__ void __launch_bounds__(Cfg::T)
-k_gemm_tn(const uint16_t* __restrict__ A, int64_t lda, int64_t m_rows, const uint16_t* __restrict__ B, int64_t ldb,
+__device__ __forceinline__ void
+gemm_tn_body(const uint16_t* __restrict__ A, int64_t lda, int64_t m_rows, const uint16_t* __restrict__ B, int64_t ldb,
           int n_rows, int K, int tiles_m, int tiles_n, void* __restrict__ out, int64_t ld_out,
           const int32_t* __restrict__ rowsel, int64_t c0, int64_t m_valid, int accumulate,
-          const uint16_t* __restrict__ W, const int32_t* __restrict__ ids, const float* __restrict__ g_c) {
+          const uint16_t* __restrict__ W, const int32_t* __restrict__ ids, const float* __restrict__ g_c,
+          uint16_t* lds) {
   using C = Cfg;
-  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * C::STAGE];
   int tile_m, tile_n;
   if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
   const int64_t m0 = static_cast<int64_t>(tile_m) * C::BM;
   const int n0 = tile_n * C::BN;
-  const uint16_t* pa[C::NA];
-  const uint16_t* pb[C::NB];
-  const int kofs = slot_kofs();
+  const uint32_t kofs = direct_kofs();                              // K is a multiple of 256 here
+  uint32_t oa[C::NA], ob[C::NB];
 #pragma unroll
-  for (int i = 0; i < C::NA; ++i) {
-    const int64_t m = min(m0 + slot_row<C>(i), m_rows - 1);         // clamped rows are not stored below
-    pa[i] = A + m * lda + kofs;
-  }
+  for (int i = 0; i < C::NA; ++i)                                   // clamped rows are not stored below
+    oa[i] = (static_cast<uint32_t>(min(static_cast<int64_t>(slot_row<C>(i)), m_rows - 1 - m0)) * static_cast<uint32_t>(lda) + kofs) * 2u;
 #pragma unroll
-  for (int i = 0; i < C::NB; ++i) {
-    const int n = min(n0 + slot_row<C>(i), n_rows - 1);
-    pb[i] = B + static_cast<int64_t>(n) * ldb + kofs;
-  }
+  for (int i = 0; i < C::NB; ++i)
+    ob[i] = (static_cast<uint32_t>(min(slot_row<C>(i), n_rows - 1 - n0)) * static_cast<uint32_t>(ldb) + kofs) * 2u;
   floatx16 acc[C::TM][C::TN];
 #pragma unroll
   for (int tm = 0; tm < C::TM; ++tm)
@@ -444,7 +440,7 @@ k_gemm_tn(const uint16_t* __restrict__ A, int64_t lda, int64_t m_rows, const uin
     for (int tn = 0; tn < C::TN; ++tn)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
-  mfma_mainloop<C>(pa, pb, K, lds, acc);
+  mfma_mainloop_direct<C>(make_rsrc(A + m0 * lda), oa, make_rsrc(B + static_cast<int64_t>(n0) * ldb), ob, K, lds, acc);
 #pragma unroll
   for (int tn = 0; tn < C::TN; ++tn) {
     const int j = n0 + acc_col<C>(tn);
@@ -467,6 +463,23 @@ k_gemm_tn(const uint16_t* __restrict__ A, int64_t lda, int64_t m_rows, const uin
         }
       }
   }
+}
+
+// (kernel templates whose bodies use buffer resources do not get their host stubs emitted: two plain kernels)
+__global__ void __launch_bounds__(Cfg::T)
+k_gemm_dh(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uint16_t* __restrict__ Wt, int d, int tiles_m,
+          int tiles_n, uint16_t* __restrict__ dH, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
+          const uint16_t* __restrict__ W, const int32_t* __restrict__ ids, const float* __restrict__ g_c) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[DirectCfg<Cfg>::LDS_BYTES / 2];
+  gemm_tn_body<0>(dZ, Vp, mcp, Wt, Vp, d, static_cast<int>(Vp), tiles_m, tiles_n, dH, d, rowsel, c0, rows, 0, W, ids, g_c,
+                  lds);
+}
+__global__ void __launch_bounds__(Cfg::T)
+k_gemm_dw(const uint16_t* __restrict__ dZt, int64_t mcp, int64_t Vp, const uint16_t* __restrict__ Ht, int d, int V,
+          int tiles_m, int tiles_n, float* __restrict__ dW, int accumulate) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[DirectCfg<Cfg>::LDS_BYTES / 2];
+  gemm_tn_body<1>(dZt, mcp, Vp, Ht, mcp, d, static_cast<int>(mcp), tiles_m, tiles_n, dW, d, nullptr, 0, V, accumulate,
+                  nullptr, nullptr, nullptr, lds);
 }
 
 // One-hot part of dW: dW[y_n, :] += g_n h_n for every selected row, in float32.  Rows that took the
@@ -592,6 +605,9 @@ umas_status check_model_args(const void* H, const void* W, umas_dtype dt, int64_
   UMAS_REQUIRE(d >= 1 && V >= 1, UMAS_ESHAPE, "d=%d and V=%d must be positive", d, V);
   UMAS_REQUIRE(dt != UMAS_BF16 || d % 8 == 0, UMAS_ESHAPE, "bf16 needs d %% 8 == 0 (d=%d)", d);
   UMAS_REQUIRE(dt != UMAS_F32 || d <= 8192, UMAS_ESHAPE, "the float32 path supports d <= 8192 (d=%d)", d);
+  UMAS_REQUIRE(dt != UMAS_BF16 || static_cast<uint64_t>(n_rows) * d * 2 < (1ull << 32), UMAS_ESHAPE,
+               "bf16 H must be smaller than 4 GiB (32-bit buffer offsets): n_rows=%lld d=%d",
+               static_cast<long long>(n_rows), d);
   UMAS_REQUIRE(rowsel || n_sel == n_rows, UMAS_EINVAL, "rowsel is NULL but n_sel != n_rows");
   UMAS_REQUIRE(n_sel <= n_rows, UMAS_EINVAL, "n_sel=%lld exceeds n_rows=%lld", static_cast<long long>(n_sel),
                static_cast<long long>(n_rows));
@@ -788,16 +804,12 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     hipLaunchKernelGGL(k_dz_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r)), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel,
                        c0, rows, w.score.lse_c, w.g_c, tiles_v, tiles_r, dZ, dZt, Vp, mcp);
     UMAS_LAUNCHED("k_dz_tiles");
-    hipLaunchKernelGGL(k_gemm_tn<0>, dim3(tile_grid<kGM, kGN>(tiles_r, tiles_d)), dim3(Cfg::T), 0, st, dZ, Vp, mcp, w.Wt,
-                       Vp, d, static_cast<int>(Vp), tiles_r, tiles_d, dH, static_cast<int64_t>(d), rowsel, c0, rows, 0, Wb, ids,
-                       w.g_c);
-    UMAS_LAUNCHED("k_gemm_tn_dH");
-    hipLaunchKernelGGL(k_gemm_tn<1>, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_d)), dim3(Cfg::T), 0, st, dZt, mcp, Vp, Ht,
-                       mcp, d, static_cast<int>(mcp), tiles_v, tiles_d, dW, static_cast<int64_t>(d),
-                       static_cast<const int32_t*>(nullptr), static_cast<int64_t>(0), static_cast<int64_t>(V),
-                       (accumulate_dW || c0 > 0) ? 1 : 0, static_cast<const uint16_t*>(nullptr),
-                       static_cast<const int32_t*>(nullptr), static_cast<const float*>(nullptr));
-    UMAS_LAUNCHED("k_gemm_tn_dW");
+    hipLaunchKernelGGL(k_gemm_dh, dim3(tile_grid<kGM, kGN>(tiles_r, tiles_d)), dim3(Cfg::T), 0, st, dZ, Vp, mcp, w.Wt, d,
+                       tiles_r, tiles_d, static_cast<uint16_t*>(dH), rowsel, c0, rows, Wb, ids, w.g_c);
+    UMAS_LAUNCHED("k_gemm_dh");
+    hipLaunchKernelGGL(k_gemm_dw, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_d)), dim3(Cfg::T), 0, st, dZt, mcp, Vp, Ht, d, V,
+                       tiles_v, tiles_d, dW, (accumulate_dW || c0 > 0) ? 1 : 0);
+    UMAS_LAUNCHED("k_gemm_dw");
   }
   hipLaunchKernelGGL(k_dw_onehot, dim3(cdiv(n_sel, 4)), dim3(256), 0, st, Hb, d, rowsel, n_sel, ids, w.g_c, dW);
   UMAS_LAUNCHED("k_dw_onehot");
