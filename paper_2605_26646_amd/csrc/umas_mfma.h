@@ -126,6 +126,9 @@ __device__ __forceinline__ void mfma_mainloop(const uint16_t* const (&pa)[C::NA]
 //
 // Operands are addressed as raw buffers: a wave-uniform base (the caller picks it so that every
 // byte offset of the tile fits 32 bits) plus one 32-bit byte offset per load slot.
+#ifndef UMAS_LOAD_PARTS
+#define UMAS_LOAD_PARTS 2
+#endif
 template <class C>
 struct DirectCfg {
   static constexpr int ROWB = 128;                                 // bytes per LDS row
@@ -159,6 +162,7 @@ __device__ __forceinline__ void mfma_mainloop_direct(__amdgpu_buffer_rsrc_t ra, 
   // slot i of this wavefront fills rows [i*ROWS_PER_PASS + wave*8, +8) of the A (or B) area; the
   // loads of one K-step are issued in BK/16 parts, one part under each K-slice's MFMAs
   constexpr int kParts = C::BK / 16;
+  constexpr int kLoadParts = UMAS_LOAD_PARTS;   // the loads are issued under the first kLoadParts K-slices
   static_assert(C::NA % kParts == 0 && C::NB % kParts == 0, "load slots split evenly over the K-slices");
   auto gload_part = [&](int kt, int stage, int part) {
     const int kbytes = kt * C::BK * 2;
@@ -196,6 +200,7 @@ __device__ __forceinline__ void mfma_mainloop_direct(__amdgpu_buffer_rsrc_t ra, 
   for (int part = 0; part < kParts; ++part) gload_part(0, 0, part);
   __syncthreads();
   fload(0, 0, 0);
+  __builtin_amdgcn_sched_barrier(0);
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
     // The other stage was last read before the barrier that ended the previous step.  In the last
@@ -207,18 +212,30 @@ __device__ __forceinline__ void mfma_mainloop_direct(__amdgpu_buffer_rsrc_t ra, 
       // next K-slice.  Compute phase: the MFMAs of this slice, whose fragments were requested one
       // phase earlier.  The fences keep the two phases in this order so that every read has a whole
       // compute phase to land.
-      gload_part(kn, cur ^ 1, kk);
+      if (kk < kLoadParts) {
+#pragma unroll
+        for (int part = kk * (kParts / kLoadParts); part < (kk + 1) * (kParts / kLoadParts); ++part)
+          gload_part(kn, cur ^ 1, part);
+      }
       if (kk + 1 < kParts) fload((kk + 1) & 1, cur, kk + 1);
-      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int tm = 0; tm < C::TM; ++tm)
 #pragma unroll
         for (int tn = 0; tn < C::TN; ++tn)
           acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][tm], bfr[kk & 1][tn], acc[tm][tn], 0, 0, 0);
+      // inside the slice: one memory instruction after each MFMA, so that their issue hides under the
+      // matrix pipe (the reads and loads here feed later slices, never this one)
+#pragma unroll
+      for (int i = 0; i < C::TM * C::TN; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (kk + 1 < kParts && i < C::TM + C::TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        else if (kk < kLoadParts) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
     fload(0, cur ^ 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 

@@ -374,38 +374,41 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN;
   const int vbase = m0 + wm * C::WTM + (lane >> 5) * 4;
+  const bool tail = m0 + C::BM > V;
+  const int t = lane & 3;                       // position in the quad of lanes holding 4 consecutive rows n
+  const uint32_t sel = (t & 1) ? 0x07060302u : 0x05040100u;   // v_perm_b32: 0-3 = bytes of src1, 4-7 = bytes of src0
 #pragma unroll
   for (int tn = 0; tn < C::TN; ++tn) {
     const int64_t n = n0 + acc_col<C>(tn);
-    float l = 0.f, g = 0.f;
-    const bool live = n < mc;
-    if (live) {
-      l = lse_c[c0 + n];
-      g = g_c[c0 + n];
+    float l2 = 0.f, g = 0.f;                    // rows past the chunk: g = 0 and a finite exponent, so dz = 0
+    if (n < mc) {
+      l2 = lse_c[c0 + n] * 1.44269504088896341f;
+      g = -g_c[c0 + n];
     }
 #pragma unroll
     for (int tm = 0; tm < C::TM; ++tm)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int e0 = tm * 32 + q * 8;          // element offset of r = 4q from this lane's base
-        const int v0 = vbase + e0;
-        uint16_t o[4];
+        const int v0 = vbase + tm * 32 + q * 8;  // this lane holds vocabulary entries v0..v0+3 of row n
+        float dz[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          float dz = 0.f;
-          if (live && v0 + j < V) {
-            dz = -g * __expf(acc[tm][tn][q * 4 + j] - l);
-          }
-          o[j] = f2bf(dz);
+          dz[j] = g * exp2f(fmaf(acc[tm][tn][q * 4 + j], 1.44269504088896341f, -l2));
+          if (tail && v0 + j >= V) dz[j] = 0.f;
         }
-        if (n < mcp && v0 < Vp) {
-          uint2 pk;
-          pk.x = static_cast<uint32_t>(o[0]) | (static_cast<uint32_t>(o[1]) << 16);
-          pk.y = static_cast<uint32_t>(o[2]) | (static_cast<uint32_t>(o[3]) << 16);
-          *reinterpret_cast<uint2*>(dZ + n * Vp + v0) = pk;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) dZt[static_cast<int64_t>(v0 + j) * mcp + n] = o[j];
-        }
+        const uint32_t p01 = static_cast<uint32_t>(f2bf(dz[0])) | (static_cast<uint32_t>(f2bf(dz[1])) << 16);
+        const uint32_t p23 = static_cast<uint32_t>(f2bf(dz[2])) | (static_cast<uint32_t>(f2bf(dz[3])) << 16);
+        *reinterpret_cast<uint2*>(dZ + n * Vp + v0) = make_uint2(p01, p23);
+        // 4x4 transpose over the quad: afterwards lane t holds entry v0+t of rows n-t .. n-t+3
+        const uint32_t send = t < 2 ? p23 : p01;
+        const uint32_t recv = __builtin_amdgcn_update_dpp(0u, send, 0x4E, 0xF, 0xF, false);   // lane ^ 2
+        const uint32_t a = t < 2 ? p01 : recv, b = t < 2 ? recv : p23;
+        const uint32_t ax = __builtin_amdgcn_update_dpp(0u, a, 0xB1, 0xF, 0xF, false);        // lane ^ 1
+        const uint32_t bx = __builtin_amdgcn_update_dpp(0u, b, 0xB1, 0xF, 0xF, false);
+        // even lanes take the low halves (own, neighbour), odd lanes the high halves (neighbour, own)
+        const uint32_t o0 = __builtin_amdgcn_perm((t & 1) ? a : ax, (t & 1) ? ax : a, sel);
+        const uint32_t o1 = __builtin_amdgcn_perm((t & 1) ? b : bx, (t & 1) ? bx : b, sel);
+        *reinterpret_cast<uint2*>(dZt + static_cast<int64_t>(v0 + t) * mcp + (n - t)) = make_uint2(o0, o1);
       }
   }
 }
