@@ -115,128 +115,152 @@ __device__ __forceinline__ void mfma_mainloop(const uint16_t* const (&pa)[C::NA]
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fast main loop for K % 64 == 0: tiles go from global memory straight into LDS
-// (buffer_load_dwordx4 ... lds: no staging registers, no ds_write), fragments are read one 16-wide
-// K-slice ahead of the MFMAs that consume them.
+// Fast main loop for K % 64 == 0.
 //
-// LDS layout: rows of 128 bytes without padding; the 16-byte chunk c of row r sits in slot
-// c ^ ((r >> 1) & 7), which spreads the fragment reads of 16 consecutive rows over all banks.
-// One wavefront-wide load instruction fills 8 consecutive rows (1 KB); lane l of it fills slot l & 7
-// of row l >> 3, so it fetches chunk (l & 7) ^ ((row >> 1) & 7) of that row from global memory.
+// K is walked in sub-steps of 32.  Tiles go from global memory straight into a ring of S LDS stages
+// (buffer_load_dwordx4 ... lds: no staging registers, no ds_write), S - 2 sub-steps ahead of their
+// use, so that a load may miss in L2 without stalling the workgroup.  Fragments are read one 16-wide
+// K-slice ahead of the MFMAs that consume them.  Per sub-step j (stage j % S):
+//   slice 0: MFMAs on slice 0 | read the fragments of slice 1
+//   wait until this wavefront's loads of sub-step j+1 have landed, workgroup barrier
+//   slice 1: MFMAs on slice 1 | issue the loads of sub-step j+S-1 into the stage of sub-step j-1
+//                             | read the fragments of slice 0 of sub-step j+1
+// The barrier in the middle orders everything: a stage is last read (slice 1 fragments) before the
+// barrier of its own sub-step, and refilled only after the barrier of the next one.
+//
+// LDS layout of a stage: A rows then B rows, 64 bytes per row (32 bf16), no padding; the 16-byte chunk
+// c of row r sits in slot c ^ ((r >> 2) & 3), which spreads the fragment reads of 16 consecutive rows
+// over all banks.  One wavefront-wide load fills 16 consecutive rows (1 KB): lane l fills slot l & 3
+// of row l >> 2, i.e. fetches chunk (l & 3) ^ ((l >> 4) & 3) of that row.
 //
 // Operands are addressed as raw buffers: a wave-uniform base (the caller picks it so that every
 // byte offset of the tile fits 32 bits) plus one 32-bit byte offset per load slot.
-#ifndef UMAS_LOAD_PARTS
-#define UMAS_LOAD_PARTS 2
-#endif
-template <class C>
-struct DirectCfg {
-  static constexpr int ROWB = 128;                                 // bytes per LDS row
+template <class C, int S_ = 4>
+struct RingCfg {
+  static constexpr int S = S_;                                     // stages
+  static constexpr int BK = 32;                                    // K per sub-step
+  static constexpr int ROWB = 64;                                  // bytes per LDS row
   static constexpr int STAGEB = (C::BM + C::BN) * ROWB;            // bytes per stage
-  static constexpr int LDS_BYTES = 2 * STAGEB;
+  static constexpr int LDS_BYTES = S * STAGEB;
+  static constexpr int NA = C::BM * 4 / C::T, NB = C::BN * 4 / C::T;   // 16-byte loads per thread per sub-step
+  static constexpr int ROWS_PER_PASS = C::T / 4;
+  static_assert(C::T % 64 == 0 && (C::BM * 4) % C::T == 0 && (C::BN * 4) % C::T == 0, "load slots divide evenly");
 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0xFFFFFFFF, 0x00020000);
 }
 
-// K offset (in elements) of the chunk this thread fetches for all of its slots.
-__device__ __forceinline__ int direct_kofs() {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  return 8 * ((lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7));
+// Tile row that load slot i of this thread fetches, and the K offset (in elements) of its chunk.
+template <class C>
+__device__ __forceinline__ int ring_row(int i) { return i * (C::T / 4) + (threadIdx.x >> 2); }
+__device__ __forceinline__ int ring_kofs() {
+  const int lane = threadIdx.x & 63;
+  return 8 * ((lane & 3) ^ ((lane >> 4) & 3));
 }
 
-// oa[i] / ob[i]: byte offset from the operand's base of (row of slot i, k = direct_kofs()); rows outside
+// s_waitcnt that only waits for the vector-memory counter to drop to n (gfx9 encoding).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt has 6 bits");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// oa[i] / ob[i]: byte offset from the operand's base of (row ring_row(i), k = ring_kofs()); rows outside
 // the matrix are clamped to a valid row by the caller, which ignores what comes out of them.
-template <class C>
-__device__ __forceinline__ void mfma_mainloop_direct(__amdgpu_buffer_rsrc_t ra, const uint32_t (&oa)[C::NA],
-                                                     __amdgpu_buffer_rsrc_t rb, const uint32_t (&ob)[C::NB], int K,
-                                                     uint16_t* lds, floatx16 (&acc)[C::TM][C::TN]) {
-  using D = DirectCfg<C>;
+template <class C, int S>
+__device__ __forceinline__ void mfma_mainloop_ring(__amdgpu_buffer_rsrc_t ra, const uint32_t (&oa)[RingCfg<C, S>::NA],
+                                                   __amdgpu_buffer_rsrc_t rb, const uint32_t (&ob)[RingCfg<C, S>::NB],
+                                                   int K, uint16_t* lds, floatx16 (&acc)[C::TM][C::TN]) {
+  using R = RingCfg<C, S>;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / C::WN, wn = wave % C::WN;
   char* base = reinterpret_cast<char*>(lds);
-  const int nk = K / C::BK;
+  const int nsub = K / R::BK;
+  constexpr int kLoads = R::NA + R::NB;                   // load instructions per wavefront per sub-step
 
-  // slot i of this wavefront fills rows [i*ROWS_PER_PASS + wave*8, +8) of the A (or B) area; the
-  // loads of one K-step are issued in BK/16 parts, one part under each K-slice's MFMAs
-  constexpr int kParts = C::BK / 16;
-  constexpr int kLoadParts = UMAS_LOAD_PARTS;   // the loads are issued under the first kLoadParts K-slices
-  static_assert(C::NA % kParts == 0 && C::NB % kParts == 0, "load slots split evenly over the K-slices");
-  auto gload_part = [&](int kt, int stage, int part) {
-    const int kbytes = kt * C::BK * 2;
-    char* sa = base + stage * D::STAGEB + wave * 8 * D::ROWB;
-    char* sb = sa + C::BM * D::ROWB;
+  auto gload = [&](int sub, int stage) {
+    const int kbytes = sub * R::BK * 2;
+    char* sa = base + stage * R::STAGEB + wave * 16 * R::ROWB;
+    char* sb = sa + C::BM * R::ROWB;
 #pragma unroll
-    for (int i = part * (C::NA / kParts); i < (part + 1) * (C::NA / kParts); ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, reinterpret_cast<uint32_t*>(sa + i * C::ROWS_PER_PASS * D::ROWB), 16,
+    for (int i = 0; i < R::NA; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, reinterpret_cast<uint32_t*>(sa + i * R::ROWS_PER_PASS * R::ROWB), 16,
                                                oa[i], kbytes, 0, 0);
 #pragma unroll
-    for (int i = part * (C::NB / kParts); i < (part + 1) * (C::NB / kParts); ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, reinterpret_cast<uint32_t*>(sb + i * C::ROWS_PER_PASS * D::ROWB), 16,
+    for (int i = 0; i < R::NB; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, reinterpret_cast<uint32_t*>(sb + i * R::ROWS_PER_PASS * R::ROWB), 16,
                                                ob[i], kbytes, 0, 0);
   };
 
-  // byte offsets of this lane's fragment chunk for the four K-slices of a stage
-  const int sw = (lane >> 1) & 7;
-  int coff[C::BK / 16];
-#pragma unroll
-  for (int kk = 0; kk < C::BK / 16; ++kk) coff[kk] = ((kk * 2 + (lane >> 5)) ^ sw) * 16;
-  const int arow = (wm * C::WTM + (lane & 31)) * D::ROWB;
-  const int brow = (C::BM + wn * C::WTN + (lane & 31)) * D::ROWB;
+  // byte offsets of this lane's fragment chunk for the two K-slices of a stage
+  const int sw = (lane >> 2) & 3;
+  const int coff0 = ((lane >> 5) ^ sw) * 16, coff1 = ((2 + (lane >> 5)) ^ sw) * 16;
+  const int arow = (wm * C::WTM + (lane & 31)) * R::ROWB;
+  const int brow = (C::BM + wn * C::WTN + (lane & 31)) * R::ROWB;
 
   bf16x8 af[2][C::TM], bfr[2][C::TN];
-  auto fload = [&](int buf, int stage, int kk) {
-    const char* sa = base + stage * D::STAGEB + arow + coff[kk];
-    const char* sb = base + stage * D::STAGEB + brow + coff[kk];
+  auto fload = [&](int buf, int stage, int coff) {
+    const char* sa = base + stage * R::STAGEB + arow + coff;
+    const char* sb = base + stage * R::STAGEB + brow + coff;
 #pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm) af[buf][tm] = *reinterpret_cast<const bf16x8*>(sa + tm * 32 * D::ROWB);
+    for (int tm = 0; tm < C::TM; ++tm) af[buf][tm] = *reinterpret_cast<const bf16x8*>(sa + tm * 32 * R::ROWB);
 #pragma unroll
-    for (int tn = 0; tn < C::TN; ++tn) bfr[buf][tn] = *reinterpret_cast<const bf16x8*>(sb + tn * 32 * D::ROWB);
+    for (int tn = 0; tn < C::TN; ++tn) bfr[buf][tn] = *reinterpret_cast<const bf16x8*>(sb + tn * 32 * R::ROWB);
+  };
+  auto mfmas = [&](int buf) {
+#pragma unroll
+    for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < C::TN; ++tn)
+        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][tm], bfr[buf][tn], acc[tm][tn], 0, 0, 0);
+  };
+  // memory instructions are spread behind the MFMAs of a slice, so that their issue hides under the
+  // matrix pipe
+  auto interleave = [&](int n_ds, int n_vm) {
+#pragma unroll
+    for (int i = 0; i < C::TM * C::TN; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (i < n_ds) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (i < n_vm) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
   };
 
+  // prologue: sub-steps 0 .. S-2 in flight, sub-step 0 landed
 #pragma unroll
-  for (int part = 0; part < kParts; ++part) gload_part(0, 0, part);
-  __syncthreads();
-  fload(0, 0, 0);
+  for (int p = 0; p < S - 1; ++p) gload(p < nsub ? p : nsub - 1, p);
+  wait_vmcnt<(S - 2) * kLoads>();
+  __builtin_amdgcn_s_barrier();
+  fload(0, 0, coff0);
   __builtin_amdgcn_sched_barrier(0);
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    // The other stage was last read before the barrier that ended the previous step.  In the last
-    // step the loads repeat the final tile, which nobody uses, to keep the loop branch-free.
-    const int kn = kt + 1 < nk ? kt + 1 : kt;
-#pragma unroll
-    for (int kk = 0; kk < kParts; ++kk) {
-      // Memory phase: a quarter of the next tile's global->LDS loads and the fragment reads of the
-      // next K-slice.  Compute phase: the MFMAs of this slice, whose fragments were requested one
-      // phase earlier.  The fences keep the two phases in this order so that every read has a whole
-      // compute phase to land.
-      if (kk < kLoadParts) {
-#pragma unroll
-        for (int part = kk * (kParts / kLoadParts); part < (kk + 1) * (kParts / kLoadParts); ++part)
-          gload_part(kn, cur ^ 1, part);
-      }
-      if (kk + 1 < kParts) fload((kk + 1) & 1, cur, kk + 1);
-#pragma unroll
-      for (int tm = 0; tm < C::TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < C::TN; ++tn)
-          acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][tm], bfr[kk & 1][tn], acc[tm][tn], 0, 0, 0);
-      // inside the slice: one memory instruction after each MFMA, so that their issue hides under the
-      // matrix pipe (the reads and loads here feed later slices, never this one)
-#pragma unroll
-      for (int i = 0; i < C::TM * C::TN; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (kk + 1 < kParts && i < C::TM + C::TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        else if (kk < kLoadParts) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    __syncthreads();
-    fload(0, cur ^ 1, 0);
+
+  int stage = 0;                                           // j % S
+  for (int j = 0; j < nsub; ++j) {
+    const int stage_next = stage + 1 == S ? 0 : stage + 1;
+    const int stage_prev = stage == 0 ? S - 1 : stage - 1;
+    // slice 0
+    fload(1, stage, coff1);
+    mfmas(0);
+    interleave(C::TM + C::TN, 0);
     __builtin_amdgcn_sched_barrier(0);
+    // loads of sub-step j+1 were issued S-2 sub-steps ago; everything younger may stay in flight
+    wait_vmcnt<(S - 3) * kLoads>();
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    // slice 1; past the end of K the loads repeat the last sub-step (nobody reads them) so that the
+    // in-flight count stays what the waits above assume
+    const int sub_load = j + S - 1 < nsub ? j + S - 1 : nsub - 1;
+    gload(sub_load, stage_prev);
+    fload(0, stage_next, coff0);
+    mfmas(1);
+    interleave(C::TM + C::TN, kLoads);
+    __builtin_amdgcn_sched_barrier(0);
+    stage = stage_next;
   }
+  // drain the loads still in flight before the caller reuses the LDS
+  wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
 }
 
 // Position of accumulator element (tm, tn, r) inside the workgroup tile.

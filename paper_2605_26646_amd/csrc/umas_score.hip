@@ -18,7 +18,10 @@
 namespace umas {
 namespace {
 
-using Cfg = TileCfg<256, 256, 2, 2>;
+using Cfg = TileCfg<256, 256, 2, 4>;   // 8 wavefronts, two per SIMD: one issues memory operations while the other feeds the matrix pipe
+constexpr int kStages = 4;
+using Ring = RingCfg<Cfg, kStages>;
+constexpr int kLogitLds = Ring::LDS_BYTES > Cfg::LDS_BYTES ? Ring::LDS_BYTES : Cfg::LDS_BYTES;   // both main loops fit
 constexpr int kGM = 4, kGN = 8;          // tile group resident on one XCD
 constexpr int kRowBlock = 256;
 constexpr float kNegInf = -INFINITY;
@@ -100,16 +103,17 @@ __device__ __forceinline__ void logit_tile(const uint16_t* __restrict__ W, const
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
   if (d % C::BK == 0) {
-    const uint32_t kofs = direct_kofs();
-    uint32_t oa[C::NA], ob[C::NB];
+    using R = RingCfg<C, kStages>;
+    const uint32_t kofs = ring_kofs();
+    uint32_t oa[R::NA], ob[R::NB];
 #pragma unroll
-    for (int i = 0; i < C::NA; ++i) oa[i] = (static_cast<uint32_t>(min(slot_row<C>(i), V - 1 - m0)) * d + kofs) * 2u;
+    for (int i = 0; i < R::NA; ++i) oa[i] = (static_cast<uint32_t>(min(ring_row<C>(i), V - 1 - m0)) * d + kofs) * 2u;
 #pragma unroll
-    for (int i = 0; i < C::NB; ++i) {
-      const int64_t n = sel0 + min(n0 + slot_row<C>(i), n_lim - 1);
+    for (int i = 0; i < R::NB; ++i) {
+      const int64_t n = sel0 + min(n0 + ring_row<C>(i), n_lim - 1);
       ob[i] = (static_cast<uint32_t>(rowsel ? rowsel[n] : n) * d + kofs) * 2u;   // host checks n_rows*d*2 < 2^32
     }
-    mfma_mainloop_direct<C>(make_rsrc(W + static_cast<int64_t>(m0) * d), oa, make_rsrc(H), ob, d, lds, acc);
+    mfma_mainloop_ring<C, kStages>(make_rsrc(W + static_cast<int64_t>(m0) * d), oa, make_rsrc(H), ob, d, lds, acc);
   } else {
     const int kofs = slot_kofs();
     const uint16_t* pa[C::NA];
@@ -133,7 +137,7 @@ k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, in
               const int32_t* __restrict__ rowsel, int64_t n_sel, const int32_t* __restrict__ ids,
               int tiles_m, int tiles_n, float4* __restrict__ partial, int64_t n_pad) {
   using C = Cfg;
-  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * C::STAGE];
+  __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
   int tile_m, tile_n;
   if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
   const int m0 = tile_m * C::BM;
@@ -363,7 +367,7 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
            const float* __restrict__ lse_c, const float* __restrict__ g_c, int tiles_m, int tiles_n,
            uint16_t* __restrict__ dZ, uint16_t* __restrict__ dZt, int64_t Vp, int64_t mcp) {
   using C = Cfg;
-  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * C::STAGE];
+  __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
   int tile_m, tile_n;
   if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
   const int m0 = tile_m * C::BM;
@@ -375,6 +379,20 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
   const int wm = wave / C::WN;
   const int vbase = m0 + wm * C::WTM + (lane >> 5) * 4;
   const bool tail = m0 + C::BM > V;
+  // each wavefront stages its 128 (rows) x 128 (vocabulary) block; 272-byte pitch keeps 16-byte alignment
+  constexpr int kStagePitch = C::WTM * 2 + 16;
+  static_assert(C::WM * C::WN * C::WTN * kStagePitch <= kLogitLds, "staging fits the tile buffers");
+  char* stage = reinterpret_cast<char*>(lds) + wave * (C::WTN * kStagePitch);
+  __syncthreads();                              // every wavefront has left the main loop's LDS reads
+  if (tail) {                                   // vocabulary ids past V: exp2(-inf) = 0 below
+#pragma unroll
+    for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < C::TN; ++tn)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (vbase + tm * 32 + (r >> 2) * 8 + (r & 3) >= V) acc[tm][tn][r] = kNegInf;
+  }
   const int t = lane & 3;                       // position in the quad of lanes holding 4 consecutive rows n
   const uint32_t sel = (t & 1) ? 0x07060302u : 0x05040100u;   // v_perm_b32: 0-3 = bytes of src1, 4-7 = bytes of src0
 #pragma unroll
@@ -393,12 +411,13 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
         float dz[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          dz[j] = g * exp2f(fmaf(acc[tm][tn][q * 4 + j], 1.44269504088896341f, -l2));
-          if (tail && v0 + j >= V) dz[j] = 0.f;
+          dz[j] = g * __builtin_amdgcn_exp2f(fmaf(acc[tm][tn][q * 4 + j], 1.44269504088896341f, -l2));
         }
         const uint32_t p01 = static_cast<uint32_t>(f2bf(dz[0])) | (static_cast<uint32_t>(f2bf(dz[1])) << 16);
         const uint32_t p23 = static_cast<uint32_t>(f2bf(dz[2])) | (static_cast<uint32_t>(f2bf(dz[3])) << 16);
-        *reinterpret_cast<uint2*>(dZ + n * Vp + v0) = make_uint2(p01, p23);
+        // orientation [row][vocabulary]: staged in this wavefront's LDS region, stored in full lines below
+        *reinterpret_cast<uint2*>(stage + (tn * 32 + (lane & 31)) * kStagePitch + (tm * 32 + q * 8 + (lane >> 5) * 4) * 2) =
+            make_uint2(p01, p23);
         // 4x4 transpose over the quad: afterwards lane t holds entry v0+t of rows n-t .. n-t+3
         const uint32_t send = t < 2 ? p23 : p01;
         const uint32_t recv = __builtin_amdgcn_update_dpp(0u, send, 0x4E, 0xF, 0xF, false);   // lane ^ 2
@@ -410,6 +429,15 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
         const uint32_t o1 = __builtin_amdgcn_perm((t & 1) ? b : bx, (t & 1) ? bx : b, sel);
         *reinterpret_cast<uint2*>(dZt + static_cast<int64_t>(v0 + t) * mcp + (n - t)) = make_uint2(o0, o1);
       }
+  }
+  // the staged block goes out 16 bytes per lane: one instruction covers 4 rows x 256 contiguous bytes
+  const int wn = wave % C::WN;
+  uint16_t* out = dZ + (n0 + wn * C::WTN) * Vp + m0 + wm * C::WTM + (lane & 15) * 8;
+#pragma unroll 8
+  for (int i = 0; i < C::WTN / 4; ++i) {
+    const int row = i * 4 + (lane >> 4);
+    const uint4 v = *reinterpret_cast<const uint4*>(stage + row * kStagePitch + (lane & 15) * 16);
+    *reinterpret_cast<uint4*>(out + static_cast<int64_t>(row) * Vp) = v;
   }
 }
 
@@ -428,14 +456,14 @@ gemm_tn_body(const uint16_t* __restrict__ A, int64_t lda, int64_t m_rows, const 
   if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
   const int64_t m0 = static_cast<int64_t>(tile_m) * C::BM;
   const int n0 = tile_n * C::BN;
-  const uint32_t kofs = direct_kofs();                              // K is a multiple of 256 here
-  uint32_t oa[C::NA], ob[C::NB];
+  const uint32_t kofs = ring_kofs();                                // K is a multiple of 256 here
+  uint32_t oa[Ring::NA], ob[Ring::NB];
 #pragma unroll
-  for (int i = 0; i < C::NA; ++i)                                   // clamped rows are not stored below
-    oa[i] = (static_cast<uint32_t>(min(static_cast<int64_t>(slot_row<C>(i)), m_rows - 1 - m0)) * static_cast<uint32_t>(lda) + kofs) * 2u;
+  for (int i = 0; i < Ring::NA; ++i)                                // clamped rows are not stored below
+    oa[i] = (static_cast<uint32_t>(min(static_cast<int64_t>(ring_row<C>(i)), m_rows - 1 - m0)) * static_cast<uint32_t>(lda) + kofs) * 2u;
 #pragma unroll
-  for (int i = 0; i < C::NB; ++i)
-    ob[i] = (static_cast<uint32_t>(min(slot_row<C>(i), n_rows - 1 - n0)) * static_cast<uint32_t>(ldb) + kofs) * 2u;
+  for (int i = 0; i < Ring::NB; ++i)
+    ob[i] = (static_cast<uint32_t>(min(ring_row<C>(i), n_rows - 1 - n0)) * static_cast<uint32_t>(ldb) + kofs) * 2u;
   floatx16 acc[C::TM][C::TN];
 #pragma unroll
   for (int tm = 0; tm < C::TM; ++tm)
@@ -443,7 +471,7 @@ gemm_tn_body(const uint16_t* __restrict__ A, int64_t lda, int64_t m_rows, const 
     for (int tn = 0; tn < C::TN; ++tn)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
-  mfma_mainloop_direct<C>(make_rsrc(A + m0 * lda), oa, make_rsrc(B + static_cast<int64_t>(n0) * ldb), ob, K, lds, acc);
+  mfma_mainloop_ring<C, kStages>(make_rsrc(A + m0 * lda), oa, make_rsrc(B + static_cast<int64_t>(n0) * ldb), ob, K, lds, acc);
 #pragma unroll
   for (int tn = 0; tn < C::TN; ++tn) {
     const int j = n0 + acc_col<C>(tn);
@@ -473,14 +501,14 @@ __global__ void __launch_bounds__(Cfg::T)
 k_gemm_dh(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uint16_t* __restrict__ Wt, int d, int tiles_m,
           int tiles_n, uint16_t* __restrict__ dH, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
           const uint16_t* __restrict__ W, const int32_t* __restrict__ ids, const float* __restrict__ g_c) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[DirectCfg<Cfg>::LDS_BYTES / 2];
+  __shared__ __attribute__((aligned(16))) uint16_t lds[Ring::LDS_BYTES / 2];
   gemm_tn_body<0>(dZ, Vp, mcp, Wt, Vp, d, static_cast<int>(Vp), tiles_m, tiles_n, dH, d, rowsel, c0, rows, 0, W, ids, g_c,
                   lds);
 }
 __global__ void __launch_bounds__(Cfg::T)
 k_gemm_dw(const uint16_t* __restrict__ dZt, int64_t mcp, int64_t Vp, const uint16_t* __restrict__ Ht, int d, int V,
           int tiles_m, int tiles_n, float* __restrict__ dW, int accumulate) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[DirectCfg<Cfg>::LDS_BYTES / 2];
+  __shared__ __attribute__((aligned(16))) uint16_t lds[Ring::LDS_BYTES / 2];
   gemm_tn_body<1>(dZt, mcp, Vp, Ht, mcp, d, static_cast<int>(mcp), tiles_m, tiles_n, dW, d, nullptr, 0, V, accumulate,
                   nullptr, nullptr, nullptr, lds);
 }
