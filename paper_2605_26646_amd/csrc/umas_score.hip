@@ -25,6 +25,7 @@ constexpr int kLogitLds = Ring::LDS_BYTES > Cfg::LDS_BYTES ? Ring::LDS_BYTES : C
 constexpr int kGM = 4, kGN = 8;          // tile group resident on one XCD
 constexpr int kRowBlock = 256;
 constexpr float kNegInf = -INFINITY;
+constexpr float kMasked = -1e30f;        // stands for a logit that does not exist (vocabulary tail)
 
 __device__ __forceinline__ uint16_t f2bf(float x) {
   return __builtin_bit_cast(uint16_t, static_cast<__bf16>(x));
@@ -154,30 +155,35 @@ k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, in
   __syncthreads();
   const int vbase = m0 + wm * C::WTM + (lane >> 5) * 4;   // vocabulary id of element (tm=0, r=0)
   const bool tail = m0 + C::BM > V;
+  if (tail) {   // vocabulary ids past V: a large negative logit whose exponential is 0 and whose products stay finite
+#pragma unroll
+    for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < C::TN; ++tn)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (vbase + tm * 32 + (r >> 2) * 8 + (r & 3) >= V) acc[tm][tn][r] = kMasked;
+  }
+  constexpr float kLog2e = 1.44269504088896341f;
 #pragma unroll
   for (int tn = 0; tn < C::TN; ++tn) {
     const int col = acc_col<C>(tn);
     const int64_t n = n0 + col;
-    float m = kNegInf;
+    float m = kMasked;
+#pragma unroll
+    for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[tm][tn][r]);
+    float s = 0.f, t = 0.f;
 #pragma unroll
     for (int tm = 0; tm < C::TM; ++tm)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        if (tail && vbase + tm * 32 + (r >> 2) * 8 + (r & 3) >= V) acc[tm][tn][r] = kNegInf;
-        m = fmaxf(m, acc[tm][tn][r]);
+        const float z = acc[tm][tn][r];
+        const float e = __builtin_amdgcn_exp2f((z - m) * kLog2e);   // z - m first: exact 0 for masked-only columns
+        s += e;
+        t = fmaf(e, z, t);
       }
-    float s = 0.f, t = 0.f;
-    if (m != kNegInf) {
-#pragma unroll
-      for (int tm = 0; tm < C::TM; ++tm)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float z = acc[tm][tn][r];
-          const float e = __expf(z - m);
-          s += e;
-          t += (z == kNegInf) ? 0.f : e * z;
-        }
-    }
     Part p{m, s, t};
     Part q{__shfl_xor(p.m, 32, kWave), __shfl_xor(p.s, 32, kWave), __shfl_xor(p.t, 32, kWave)};
     p = part_merge(p, q);
