@@ -30,6 +30,7 @@ constexpr float kMasked = -1e30f;        // stands for a logit that does not exi
 __device__ __forceinline__ uint16_t f2bf(float x) {
   return __builtin_bit_cast(uint16_t, static_cast<__bf16>(x));
 }
+__device__ __forceinline__ uint64_t pack_u64(uint32_t lo, uint32_t hi) { return static_cast<uint64_t>(lo) | (static_cast<uint64_t>(hi) << 32); }
 __device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
 
 // Online-softmax partial: m = max z, s = sum exp(z - m), t = sum exp(z - m) z.
@@ -433,7 +434,8 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
         // even lanes take the low halves (own, neighbour), odd lanes the high halves (neighbour, own)
         const uint32_t o0 = __builtin_amdgcn_perm((t & 1) ? a : ax, (t & 1) ? ax : a, sel);
         const uint32_t o1 = __builtin_amdgcn_perm((t & 1) ? b : bx, (t & 1) ? bx : b, sel);
-        *reinterpret_cast<uint2*>(dZt + static_cast<int64_t>(v0 + t) * mcp + (n - t)) = make_uint2(o0, o1);
+        // streaming stores: the chunk buffer is far larger than any cache and is read back only by later kernels
+        __builtin_nontemporal_store(pack_u64(o0, o1), reinterpret_cast<uint64_t*>(dZt + static_cast<int64_t>(v0 + t) * mcp + (n - t)));
       }
   }
   // the staged block goes out 16 bytes per lane: one instruction covers 4 rows x 256 contiguous bytes
@@ -443,7 +445,8 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
   for (int i = 0; i < C::WTN / 4; ++i) {
     const int row = i * 4 + (lane >> 4);
     const uint4 v = *reinterpret_cast<const uint4*>(stage + row * kStagePitch + (lane & 15) * 16);
-    *reinterpret_cast<uint4*>(out + static_cast<int64_t>(row) * Vp) = v;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(out + static_cast<int64_t>(row) * Vp));
   }
 }
 
