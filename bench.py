@@ -66,8 +66,8 @@ def hbm_kernels(umas, wl, torch, cfg, n_traj, iters=5):
     umas.profile_enable(False)
     N = w.n_tokens
     scored = int(w.tok_mask.sum())
-    scan_ms = sum(prof[k][0] for k in prof if k.startswith("k_scan")) / iters
-    route_names = [k for k in prof if not k.startswith("k_scan")]
+    scan_ms = sum(prof[k][0] for k in prof if k.startswith("k_gae_scan")) / iters
+    route_names = [k for k in prof if not k.startswith("k_gae_scan")]
     route_ms = sum(prof[k][0] for k in route_names) / iters
     scan_bytes = (17 if value is not None else 13) * N
     route_bytes = (1 + 8 + 4 + 4 + 1 + 4) * N + 4 * scored

@@ -117,6 +117,8 @@ typedef struct {
   int64_t* model_rowsel_off;  /* [n_models+1]  rowsel of model m = [off[m], off[m+1]) */
   float*   turn_scalar;       /* [n_turns]     composed reward of each turn, global turn order */
   int32_t* turn_step;         /* [n_turns]     1-based position of the turn inside its trajectory */
+  uint8_t* tok_flags;         /* [n_tokens]    bit 0 = mask, bit 1 = last token of its turn segment,
+                                               bit 2 = last token of its trajectory run (read by umas_advantages) */
 } umas_streams;
 
 /* Bytes of workspace umas_assign_token_rewards needs for this graph. */

@@ -37,7 +37,7 @@ class _Rewards(C.Structure):
 
 _STREAM_FIELDS = ["model_tok_off", "perm", "tok_turn", "tok_role", "tok_mask", "tok_reward", "turn_seg_off",
                   "seg_turn", "model_turn_off", "traj_seg_off", "model_trajrun_off", "rowsel",
-                  "model_rowsel_off", "turn_scalar", "turn_step"]
+                  "model_rowsel_off", "turn_scalar", "turn_step", "tok_flags"]
 
 
 class _Streams(C.Structure):
@@ -69,6 +69,7 @@ class Streams:
     model_rowsel_off: torch.Tensor
     turn_scalar: torch.Tensor
     turn_step: torch.Tensor
+    tok_flags: torch.Tensor
 
     def _c(self) -> _Streams:
         s = _Streams()
@@ -209,7 +210,8 @@ def umas_assign_token_rewards(*, n_roles, n_models, role_to_model, traj_turn_off
         model_turn_off=torch.empty(n_models + 1, **i32), traj_seg_off=torch.empty(n_turns + 1, **i64),
         model_trajrun_off=torch.empty(n_models + 1, **i32), rowsel=torch.empty(max(n_tokens, 1), **i32),
         model_rowsel_off=torch.empty(n_models + 1, **i64), turn_scalar=torch.empty(max(n_turns, 1), **f32),
-        turn_step=torch.empty(max(n_turns, 1), **i32))
+        turn_step=torch.empty(max(n_turns, 1), **i32),
+        tok_flags=torch.empty(n_tokens, dtype=torch.uint8, device=dev))
     ws = _workspace(lib.umas_assign_workspace_bytes(C.addressof(g)), dev)
     cs = out._c()
     _check(lib, lib.umas_assign_token_rewards(C.addressof(g), C.addressof(r), _ptr(tok_mask_global) or _dummy(dev).data_ptr(), C.addressof(cs),

@@ -272,7 +272,8 @@ k_tokens(int64_t n_tokens, int n_turns, int place_mode, const int64_t* __restric
          const int32_t* __restrict__ turn_role, const float* __restrict__ turn_scalar,
          const int64_t* __restrict__ last_valid, const uint8_t* __restrict__ mask_global,
          int64_t* __restrict__ perm, int32_t* __restrict__ tok_turn, int32_t* __restrict__ tok_role,
-         uint8_t* __restrict__ tok_mask, float* __restrict__ tok_reward, int64_t* __restrict__ tok_blk) {
+         uint8_t* __restrict__ tok_mask, uint8_t* __restrict__ tok_flags, float* __restrict__ tok_reward,
+         int64_t* __restrict__ tok_blk) {
   __shared__ int64_t smem[32];
   const int64_t p0 = (static_cast<int64_t>(blockIdx.x) * kTokThreads + threadIdx.x) * kTokPerThread;
   int64_t cnt = 0;
@@ -302,16 +303,32 @@ k_tokens(int64_t n_tokens, int n_turns, int place_mode, const int64_t* __restric
       *reinterpret_cast<int4*>(tok_turn + p0) = make_int4(tt[0], tt[1], tt[2], tt[3]);
       *reinterpret_cast<int4*>(tok_role + p0) = make_int4(tr[0], tr[1], tr[2], tr[3]);
       *reinterpret_cast<uchar4*>(tok_mask + p0) = make_uchar4(mk[0], mk[1], mk[2], mk[3]);
+      *reinterpret_cast<uchar4*>(tok_flags + p0) = make_uchar4(mk[0], mk[1], mk[2], mk[3]);
       *reinterpret_cast<float4*>(tok_reward + p0) = make_float4(rw[0], rw[1], rw[2], rw[3]);
     } else {
       for (int k = 0; k < kTokPerThread && p0 + k < n_tokens; ++k) {
         perm[p0 + k] = pm[k]; tok_turn[p0 + k] = tt[k]; tok_role[p0 + k] = tr[k];
-        tok_mask[p0 + k] = mk[k]; tok_reward[p0 + k] = rw[k];
+        tok_mask[p0 + k] = mk[k]; tok_flags[p0 + k] = mk[k]; tok_reward[p0 + k] = rw[k];
       }
     }
   }
   const int64_t total = block_sum<int64_t>(cnt, smem);
   if (threadIdx.x == 0) tok_blk[blockIdx.x] = total;
+}
+
+// Segment ends for the scans: the last token of every non-empty turn segment gets bit 1, and bit 2 as well
+// when a trajectory run ends there (its end offset is one of the run offsets).
+__global__ void k_flag_bounds(int n_turns, int64_t n_tokens, const int64_t* __restrict__ turn_seg_off,
+                              const int64_t* __restrict__ traj_seg_off, const uint8_t* __restrict__ tok_mask,
+                              uint8_t* __restrict__ tok_flags) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= n_turns) return;
+  const int64_t a = turn_seg_off[s], e = turn_seg_off[s + 1];
+  if (e <= a) return;
+  uint8_t f = (tok_mask[e - 1] ? 1 : 0) | 2;
+  const int j = last_le(traj_seg_off, n_turns, e);      // entries past the run count hold n_tokens
+  if (e == n_tokens || traj_seg_off[j] == e) f |= 4;
+  tok_flags[e - 1] = f;
 }
 
 // Compaction of mask=1 positions into rowsel (stream-relative), plus the per-model offsets.
@@ -395,7 +412,8 @@ umas_status validate(const umas_graph* g, const umas_rewards* r, const umas_stre
   UMAS_REQUIRE(r->norm_eps > 0.0f, UMAS_EINVAL, "norm_eps must be positive");
   UMAS_REQUIRE(o->model_tok_off && o->perm && o->tok_turn && o->tok_role && o->tok_mask && o->tok_reward &&
                    o->turn_seg_off && o->seg_turn && o->model_turn_off && o->traj_seg_off &&
-                   o->model_trajrun_off && o->rowsel && o->model_rowsel_off && o->turn_scalar && o->turn_step,
+                   o->model_trajrun_off && o->rowsel && o->model_rowsel_off && o->turn_scalar && o->turn_step &&
+                   o->tok_flags,
                UMAS_EINVAL, "every pointer of the output streams must be set");
   return UMAS_OK;
 }
@@ -515,8 +533,11 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
     const int nbk = cdiv(N, kTokBlock);
     hipLaunchKernelGGL(k_tokens, dim3(nbk), dim3(kTokThreads), 0, st, N, U, r->place_mode, o->turn_seg_off,
                        o->seg_turn, w.turn_tok_off, w.turn_role, o->turn_scalar, w.last_valid, tok_mask_global,
-                       o->perm, o->tok_turn, o->tok_role, o->tok_mask, o->tok_reward, w.tok_blk);
+                       o->perm, o->tok_turn, o->tok_role, o->tok_mask, o->tok_flags, o->tok_reward, w.tok_blk);
     UMAS_LAUNCHED("k_tokens");
+    hipLaunchKernelGGL(k_flag_bounds, dim3(cdiv(U, 256)), dim3(256), 0, st, U, N, o->turn_seg_off, o->traj_seg_off,
+                       o->tok_mask, o->tok_flags);
+    UMAS_LAUNCHED("k_flag_bounds");
     hipLaunchKernelGGL(k_excl_scan_rows, dim3(1), dim3(1024), 0, st, w.tok_blk, nbk, w.tok_total);
     UMAS_LAUNCHED("k_excl_scan_rows");
     hipLaunchKernelGGL(k_rowsel, dim3(nbk), dim3(kTokThreads), 0, st, N, K, o->tok_mask, o->model_tok_off,

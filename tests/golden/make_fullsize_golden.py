@@ -1,0 +1,56 @@
+"""Writes the stored oracle values for the full-size parity tests.
+
+For one configuration it runs the CPU oracle's scoring (float64) over every scored row of every model
+at the configuration's full size and stores logp, lse and entropy as float32, together with
+fingerprints of the seeded inputs they belong to.  It calls nothing but `oracle/` and `workloads/`.
+
+    python tests/golden/make_fullsize_golden.py 1        # about 20 minutes on 8 cores
+
+The full-size tests use these values to build old log-probs (oracle log-prob + generator noise) and to
+evaluate sampled rows of dH and dW, none of which the CPU could afford to recompute inside a test.
+"""
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+
+import workloads as wl                      # noqa: E402
+from oracle import umas_oracle as orc       # noqa: E402
+
+
+def fingerprint(t):
+    """Cheap identity of the generated tensors: a few sums that any change of the generator moves."""
+    return np.array([float(t["H"][:64].astype(np.float64).sum()), float(t["W"][:64].astype(np.float64).sum()),
+                     float(t["ids"].astype(np.int64).sum()), float(t["noise"].astype(np.float64).sum())])
+
+
+def main(cfg):
+    w = wl.make_workload(cfg)
+    st = orc.route(w.n_models, w.role_to_model, w.traj_turn_off, w.turn_role, w.turn_tok_off, w.tok_mask)
+    out = {}
+    for m in range(w.n_models):
+        t = w.model_tensors(m)
+        ra, re = int(st["model_rowsel_off"][m]), int(st["model_rowsel_off"][m + 1])
+        rows = st["rowsel"][ra:re]
+        n = len(t["ids"])
+        logp, lse, ent = np.zeros(n, np.float32), np.zeros(n, np.float32), np.zeros(n, np.float32)
+        t0 = time.time()
+        step = 2048
+        for c0 in range(0, len(rows), step):
+            rr = rows[c0:c0 + step]
+            a, b, c = orc.score(t["H"], t["W"], t["ids"], rr)
+            logp[rr], lse[rr], ent[rr] = a[rr], b[rr], c[rr]
+            print(f"cfg {cfg} model {m}: {min(c0 + step, len(rows))}/{len(rows)} rows, {time.time() - t0:.0f} s", flush=True)
+        out[f"logp_{m}"], out[f"lse_{m}"], out[f"entropy_{m}"] = logp, lse, ent
+        out[f"fingerprint_{m}"] = fingerprint(t)
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"fullsize_cfg{cfg}.npz")
+    np.savez_compressed(path, **out)
+    print("wrote", path)
+
+
+if __name__ == "__main__":
+    main(int(sys.argv[1]))
