@@ -10,8 +10,8 @@
 //   turn boundary inside a trajectory segment: state scaled by gamma_turn^(step difference)
 // Every one of these is an affine map of (G, NV) of the form
 //   G' = a G + b NV + c,  NV' = e NV + f
-// and such maps compose associatively, so inside a tile of 4096 tokens the recurrence is a parallel
-// scan over maps: threads fold their own 16 tokens, wavefronts and the block combine the folds, and
+// and such maps compose associatively, so inside a tile of a few thousand tokens the recurrence is a parallel
+// scan over maps: threads fold their own few tokens, wavefronts and the block combine the folds, and
 // each thread replays its tokens from its incoming state.
 //
 // One pass over memory (17 bytes per token): segments are independent, so the stream is cut at
@@ -23,9 +23,10 @@ namespace umas {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kIpt = 16;                         // tokens per thread
+constexpr int kIpt = 8;                          // tokens per thread (8 or 16)
 constexpr int kTile = kThreads * kIpt;           // tokens per tile
-constexpr int kLdsWords = kTile / 16 * 20;       // 16 values + 4 words of padding per thread row
+constexpr int kRow = kIpt + 4;                   // LDS words per thread row: its values + 4 words of padding
+constexpr int kLdsWords = kThreads * kRow;
 
 enum : uint8_t { kFlagMask = 1, kFlagTurnEnd = 2, kFlagRunEnd = 4 };
 
@@ -74,7 +75,7 @@ __device__ __forceinline__ int64_t boundary_at_or_after(const int64_t* __restric
 }
 
 // Position of tile element e in the padded LDS arrays.
-__device__ __forceinline__ int lds_pos(int e) { return e + 4 * (e >> 4); }
+__device__ __forceinline__ int lds_pos(int e) { return e + 4 * (e / kIpt); }
 
 // For every thread, the composition of the folds of all threads to its right inside the block
 // (exclusive, in application order right to left).
@@ -143,8 +144,14 @@ k_gae_scan(ScanParams P, float* __restrict__ adv, float* __restrict__ ret) {
     const int64_t p0 = t0 + static_cast<int64_t>(tid) * kIpt;   // this thread's first token
     uint8_t fl[kIpt];
     if (p0 + kIpt <= P.n_tokens) {
-      const uint4 f4 = *reinterpret_cast<const uint4*>(P.flags + p0);
-      const uint32_t w[4] = {f4.x, f4.y, f4.z, f4.w};
+      uint32_t w[kIpt / 4];
+      if constexpr (kIpt == 16) {
+        const uint4 f4 = *reinterpret_cast<const uint4*>(P.flags + p0);
+        w[0] = f4.x; w[1] = f4.y; w[2] = f4.z; w[3] = f4.w;
+      } else {
+        const uint2 f2 = *reinterpret_cast<const uint2*>(P.flags + p0);
+        w[0] = f2.x; w[1] = f2.y;
+      }
 #pragma unroll
       for (int k = 0; k < kIpt; ++k) fl[k] = static_cast<uint8_t>(w[k >> 2] >> (8 * (k & 3)));
     } else {
@@ -155,8 +162,8 @@ k_gae_scan(ScanParams P, float* __restrict__ adv, float* __restrict__ ret) {
     float r[kIpt], v[kIpt];
 #pragma unroll
     for (int k = 0; k < kIpt / 4; ++k) {
-      const float4 r4 = *reinterpret_cast<const float4*>(s_r + tid * 20 + 4 * k);
-      const float4 v4 = *reinterpret_cast<const float4*>(s_v + tid * 20 + 4 * k);
+      const float4 r4 = *reinterpret_cast<const float4*>(s_r + tid * kRow + 4 * k);
+      const float4 v4 = *reinterpret_cast<const float4*>(s_v + tid * kRow + 4 * k);
       r[4 * k] = r4.x; r[4 * k + 1] = r4.y; r[4 * k + 2] = r4.z; r[4 * k + 3] = r4.w;
       v[4 * k] = v4.x; v[4 * k + 1] = v4.y; v[4 * k + 2] = v4.z; v[4 * k + 3] = v4.w;
     }
@@ -206,8 +213,8 @@ k_gae_scan(ScanParams P, float* __restrict__ adv, float* __restrict__ ret) {
     }
 #pragma unroll
     for (int k = 0; k < kIpt / 4; ++k) {
-      *reinterpret_cast<float4*>(s_r + tid * 20 + 4 * k) = make_float4(r[4 * k], r[4 * k + 1], r[4 * k + 2], r[4 * k + 3]);
-      *reinterpret_cast<float4*>(s_v + tid * 20 + 4 * k) = make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
+      *reinterpret_cast<float4*>(s_r + tid * kRow + 4 * k) = make_float4(r[4 * k], r[4 * k + 1], r[4 * k + 2], r[4 * k + 3]);
+      *reinterpret_cast<float4*>(s_v + tid * kRow + 4 * k) = make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
     }
     __syncthreads();                       // everyone has read s_carry and written its results
     if (tid == 0) { s_carry[0] = G; s_carry[1] = NV; }   // state at the tile's left edge
@@ -264,9 +271,9 @@ extern "C" umas_status umas_advantages(const umas_streams* s, int64_t n_tokens, 
   prof_mark(st);
   ScanParams P;
   P.n_tokens = n_tokens;
-  // about 8 ranges per compute unit, each a whole number of tiles before it is snapped to segment boundaries
+  // about 32 ranges per compute unit (several rounds of resident blocks), each a whole number of tiles before it is snapped to segment boundaries
   const int64_t tiles = (n_tokens + kTile - 1) / kTile;
-  const int64_t tiles_per_block = (tiles + 2047) / 2048;
+  const int64_t tiles_per_block = (tiles + 8191) / 8192;
   P.chunk = tiles_per_block * kTile;
   P.n_seg_entries = n_turns;
   P.seg_off = seg_mode == UMAS_SEG_TURN ? s->turn_seg_off : s->traj_seg_off;
