@@ -144,17 +144,28 @@ __global__ void k_part_reduce(int n_turns, int n_models, int nblk, const int32_t
   }
 }
 
-// In-place exclusive prefix sum of each row of data[nrows][n]; one block per row.
+// In-place exclusive prefix sum of each row of data[nrows][n]; one block per row, 8 items per thread per round.
 __global__ void k_excl_scan_rows(int64_t* __restrict__ data, int n, int64_t* __restrict__ totals) {
+  constexpr int kItems = 8;
   __shared__ int64_t smem[32];
   int64_t* row = data + static_cast<size_t>(blockIdx.x) * n;
   int64_t carry = 0;
-  for (int i0 = 0; i0 < n; i0 += blockDim.x) {
-    const int i = i0 + threadIdx.x;
-    const int64_t v = i < n ? row[i] : 0;
+  for (int i0 = 0; i0 < n; i0 += blockDim.x * kItems) {
+    const int base = i0 + threadIdx.x * kItems;
+    int64_t v[kItems];
+    int64_t sum = 0;
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) {
+      v[k] = base + k < n ? row[base + k] : 0;
+      sum += v[k];
+    }
     int64_t total;
-    const int64_t ex = block_excl_scan<int64_t>(v, smem, &total);
-    if (i < n) row[i] = carry + ex;
+    int64_t run = carry + block_excl_scan<int64_t>(sum, smem, &total);
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) {
+      if (base + k < n) row[base + k] = run;
+      run += v[k];
+    }
     carry += total;
   }
   if (threadIdx.x == 0) totals[blockIdx.x] = carry;
@@ -264,8 +275,27 @@ __global__ void k_last_valid(int n_turns, const int32_t* __restrict__ seg_turn,
   if (lane == 0) last_valid[s] = best < 0 ? -1 : turn_seg_off[s] + best;
 }
 
+// Largest j in [0, n] with off[j] <= x (ascending off, off[0] <= x), found by one wavefront probing
+// 64 positions per round; every lane of the wavefront must call it and gets the same answer.
+__device__ __forceinline__ int wave_last_le(const int64_t* __restrict__ off, int n, int64_t x) {
+  const int lane = threadIdx.x & (kWave - 1);
+  int lo = 0, hi = n;
+  while (hi - lo >= kWave) {
+    const int step = (hi - lo) / kWave;
+    const bool ok = off[lo + (lane + 1) * step] <= x;
+    const int c = __popcll(__ballot(ok));          // probes 1..c hold
+    const int nhi = c == kWave ? hi : lo + (c + 1) * step - 1;
+    lo += c * step;
+    hi = nhi;
+  }
+  const bool ok = lo + lane <= hi && off[lo + lane] <= x;
+  return lo + __popcll(__ballot(ok)) - 1;
+}
+
 // Per token in model-local order: source index, turn, role, mask, placed reward; per block the
-// number of mask=1 tokens.
+// number of mask=1 tokens.  A block finds the segment of its first token once (one wavefront-wide
+// search) and keeps the offsets of the next kSegWin segments in LDS; its threads search there.
+constexpr int kSegWin = 256;
 __global__ void __launch_bounds__(kTokThreads)
 k_tokens(int64_t n_tokens, int n_turns, int place_mode, const int64_t* __restrict__ turn_seg_off,
          const int32_t* __restrict__ seg_turn, const int64_t* __restrict__ turn_tok_off,
@@ -275,25 +305,62 @@ k_tokens(int64_t n_tokens, int n_turns, int place_mode, const int64_t* __restric
          uint8_t* __restrict__ tok_mask, uint8_t* __restrict__ tok_flags, float* __restrict__ tok_reward,
          int64_t* __restrict__ tok_blk) {
   __shared__ int64_t smem[32];
-  const int64_t p0 = (static_cast<int64_t>(blockIdx.x) * kTokThreads + threadIdx.x) * kTokPerThread;
+  __shared__ int64_t s_off[kSegWin + 1];
+  __shared__ int s_first;
+  const int64_t blk0 = static_cast<int64_t>(blockIdx.x) * kTokBlock;
+  const int64_t blk_last = (blk0 + kTokBlock < n_tokens ? blk0 + kTokBlock : n_tokens) - 1;
+  if (threadIdx.x < kWave) {
+    const int s0 = wave_last_le(turn_seg_off, n_turns, blk0);
+    if (threadIdx.x == 0) s_first = s0;
+  }
+  __syncthreads();
+  const int s_base = s_first;
+  const int win = n_turns - s_base < kSegWin ? n_turns - s_base : kSegWin;   // s_off[0..win] are valid
+  for (int i = threadIdx.x; i <= win; i += kTokThreads) s_off[i] = turn_seg_off[s_base + i];
+  __syncthreads();
+  const bool in_window = s_off[win] > blk_last;     // every token of the block lies in a windowed segment
+  const int64_t p0 = blk0 + static_cast<int64_t>(threadIdx.x) * kTokPerThread;
   int64_t cnt = 0;
   if (p0 < n_tokens) {
-    int s = last_le(turn_seg_off, n_turns, p0);
+    int s;
+    if (in_window) {
+      int lo = 0, hi = win;                         // largest j with s_off[j] <= p0
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (s_off[mid] <= p0) lo = mid; else hi = mid - 1;
+      }
+      s = s_base + lo;
+    } else {
+      s = last_le(turn_seg_off, n_turns, p0);
+    }
     int64_t pm[kTokPerThread];
     int32_t tt[kTokPerThread], tr[kTokPerThread];
     uint8_t mk[kTokPerThread];
     float rw[kTokPerThread];
+    int cur = -1, u = 0, role = 0;
+    int64_t seg_a = 0, seg_e = 0, src = 0, lastv = -1;
+    float rho = 0.f;
 #pragma unroll
     for (int k = 0; k < kTokPerThread; ++k) {
       const int64_t p = p0 + k;
       pm[k] = 0; tt[k] = 0; tr[k] = 0; mk[k] = 0; rw[k] = 0.0f;
       if (p < n_tokens) {
-        while (turn_seg_off[s + 1] <= p) ++s;   // also steps over empty segments
-        const int u = seg_turn[s];
-        const int64_t g = turn_tok_off[u] + (p - turn_seg_off[s]);
+        if (cur < 0 || p >= seg_e) {                // first token, or the segment changed
+          if (in_window) { while (s_off[s - s_base + 1] <= p) ++s; }   // also steps over empty segments
+          else { while (turn_seg_off[s + 1] <= p) ++s; }
+          cur = s;
+          seg_a = in_window ? s_off[s - s_base] : turn_seg_off[s];
+          seg_e = in_window ? s_off[s - s_base + 1] : turn_seg_off[s + 1];
+          u = seg_turn[s];
+          src = turn_tok_off[u];
+          role = turn_role[u];
+          rho = turn_scalar[u];
+          lastv = last_valid[s];
+        }
+        const int64_t g = src + (p - seg_a);
         const uint8_t m = mask_global[g] ? 1 : 0;
-        pm[k] = g; tt[k] = u; tr[k] = turn_role[u]; mk[k] = m;
-        if (m && (place_mode == UMAS_PLACE_ALL || last_valid[s] == p)) rw[k] = turn_scalar[u];
+        pm[k] = g; tt[k] = u; tr[k] = role; mk[k] = m;
+        if (m && (place_mode == UMAS_PLACE_ALL || lastv == p)) rw[k] = rho;
         cnt += m;
       }
     }
@@ -331,38 +398,50 @@ __global__ void k_flag_bounds(int n_turns, int64_t n_tokens, const int64_t* __re
   tok_flags[e - 1] = f;
 }
 
-// Compaction of mask=1 positions into rowsel (stream-relative), plus the per-model offsets.
+// Compaction of mask=1 positions into rowsel (stream-relative), plus the per-model offsets.  A block
+// covers kSelBlock tokens = kSelBlock / kTokBlock blocks of k_tokens, whose scanned counts give its base.
+constexpr int kSelPerThread = 16;
+constexpr int kSelBlock = kTokThreads * kSelPerThread;
+static_assert(kSelBlock % kTokBlock == 0, "a compaction block spans whole token blocks");
 __global__ void __launch_bounds__(kTokThreads)
 k_rowsel(int64_t n_tokens, int n_models, const uint8_t* __restrict__ tok_mask,
          const int64_t* __restrict__ model_tok_off, const int64_t* __restrict__ tok_blk,
          const int64_t* __restrict__ tok_total, int32_t* __restrict__ rowsel,
          int64_t* __restrict__ model_rowsel_off) {
-  __shared__ int64_t smem[32];
+  __shared__ int32_t smem[32];
+  __shared__ int32_t s_out[kSelBlock];
   __shared__ int64_t moff[UMAS_MAX_MODELS + 1];
   if (threadIdx.x <= n_models) moff[threadIdx.x] = model_tok_off[threadIdx.x];
   __syncthreads();
-  const int64_t p0 = (static_cast<int64_t>(blockIdx.x) * kTokThreads + threadIdx.x) * kTokPerThread;
-  uint8_t mk[kTokPerThread];
-  int64_t cnt = 0;
-#pragma unroll
-  for (int k = 0; k < kTokPerThread; ++k) {
-    mk[k] = (p0 + k < n_tokens) ? tok_mask[p0 + k] : 0;
-    cnt += mk[k];
+  const int64_t p0 = (static_cast<int64_t>(blockIdx.x) * kTokThreads + threadIdx.x) * kSelPerThread;
+  uint32_t w[4] = {0u, 0u, 0u, 0u};
+  if (p0 + kSelPerThread <= n_tokens) {
+    const uint4 m4 = *reinterpret_cast<const uint4*>(tok_mask + p0);
+    w[0] = m4.x; w[1] = m4.y; w[2] = m4.z; w[3] = m4.w;
+  } else {
+    for (int k = 0; k < kSelPerThread; ++k)
+      if (p0 + k < n_tokens) w[k >> 2] |= static_cast<uint32_t>(tok_mask[p0 + k]) << (8 * (k & 3));
   }
-  int64_t tot;
-  int64_t pos = tok_blk[blockIdx.x] + block_excl_scan<int64_t>(cnt, smem, &tot);
+  const int32_t cnt = __popc(w[0]) + __popc(w[1]) + __popc(w[2]) + __popc(w[3]);   // mask bytes are 0 or 1
+  int32_t tot;
+  const int64_t base = tok_blk[static_cast<int64_t>(blockIdx.x) * (kSelBlock / kTokBlock)];
+  int32_t lpos = block_excl_scan<int32_t>(cnt, smem, &tot);
+  if (p0 < n_tokens) {
+    int m = 0;
+    while (m < n_models && moff[m + 1] <= p0) ++m;
 #pragma unroll
-  for (int k = 0; k < kTokPerThread; ++k) {
-    const int64_t p = p0 + k;
-    if (p < n_tokens) {
-      int m = 0;
-      for (int j = 0; j <= n_models; ++j) {
-        if (moff[j] == p) model_rowsel_off[j] = pos;
-        if (j < n_models && moff[j + 1] <= p) m = j + 1;
+    for (int k = 0; k < kSelPerThread; ++k) {
+      const int64_t p = p0 + k;
+      if (p < n_tokens) {
+        while (m < n_models && moff[m + 1] <= p) ++m;
+        for (int j = 0; j <= n_models; ++j)
+          if (moff[j] == p) model_rowsel_off[j] = base + lpos;
+        if ((w[k >> 2] >> (8 * (k & 3))) & 1u) s_out[lpos++] = static_cast<int32_t>(p - moff[m]);
       }
-      if (mk[k]) rowsel[pos++] = static_cast<int32_t>(p - moff[m]);
     }
   }
+  __syncthreads();
+  for (int i = threadIdx.x; i < tot; i += kTokThreads) rowsel[base + i] = s_out[i];   // compacted, coalesced
   if (blockIdx.x == 0 && threadIdx.x == 0)
     for (int j = 0; j <= n_models; ++j)
       if (moff[j] >= n_tokens) model_rowsel_off[j] = *tok_total;
@@ -540,7 +619,7 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
     UMAS_LAUNCHED("k_flag_bounds");
     hipLaunchKernelGGL(k_excl_scan_rows, dim3(1), dim3(1024), 0, st, w.tok_blk, nbk, w.tok_total);
     UMAS_LAUNCHED("k_excl_scan_rows");
-    hipLaunchKernelGGL(k_rowsel, dim3(nbk), dim3(kTokThreads), 0, st, N, K, o->tok_mask, o->model_tok_off,
+    hipLaunchKernelGGL(k_rowsel, dim3(cdiv(N, kSelBlock)), dim3(kTokThreads), 0, st, N, K, o->tok_mask, o->model_tok_off,
                        w.tok_blk, w.tok_total, o->rowsel, o->model_rowsel_off);
     UMAS_LAUNCHED("k_rowsel");
   }
