@@ -4,7 +4,12 @@ For one configuration it runs the CPU oracle's scoring (float64) over every scor
 at the configuration's full size and stores logp, lse and entropy as float32, together with
 fingerprints of the seeded inputs they belong to.  It calls nothing but `oracle/` and `workloads/`.
 
-    python tests/golden/make_fullsize_golden.py 1        # about 20 minutes on 8 cores
+    python tests/golden/make_fullsize_golden.py 1        # every scored row; about 12 minutes on 8 cores
+    python tests/golden/make_fullsize_golden.py 4 4096   # a seeded sample of 4096 scored rows per model
+
+With a sample size the file also holds `rows_m`, the sorted row indices (within the model's stream)
+that were evaluated: the first and last 256 scored rows plus a seeded draw from the rest; the other
+entries of logp/lse/entropy stay zero.
 
 The full-size tests use these values to build old log-probs (oracle log-prob + generator noise) and to
 evaluate sampled rows of dH and dW, none of which the CPU could afford to recompute inside a test.
@@ -28,14 +33,26 @@ def fingerprint(t):
                      float(t["ids"].astype(np.int64).sum()), float(t["noise"].astype(np.float64).sum())])
 
 
-def main(cfg):
+def sample_rows(rows, n_sample, seed):
+    """First and last 256 scored rows (tile edges, ragged tail) plus a seeded draw from the rest."""
+    if n_sample <= 0 or n_sample >= len(rows):
+        return rows
+    edge = min(256, n_sample // 4)
+    mid = rows[edge:len(rows) - edge]
+    pick = np.random.default_rng([seed, 977]).choice(len(mid), size=n_sample - 2 * edge, replace=False)
+    return np.sort(np.concatenate([rows[:edge], mid[pick], rows[len(rows) - edge:]]))
+
+
+def main(cfg, n_sample=0):
     w = wl.make_workload(cfg)
     st = orc.route(w.n_models, w.role_to_model, w.traj_turn_off, w.turn_role, w.turn_tok_off, w.tok_mask)
     out = {}
     for m in range(w.n_models):
         t = w.model_tensors(m)
         ra, re = int(st["model_rowsel_off"][m]), int(st["model_rowsel_off"][m + 1])
-        rows = st["rowsel"][ra:re]
+        rows = sample_rows(st["rowsel"][ra:re], n_sample, 1000 * cfg + m)
+        if len(rows) < re - ra:
+            out[f"rows_{m}"] = rows.astype(np.int64)
         n = len(t["ids"])
         logp, lse, ent = np.zeros(n, np.float32), np.zeros(n, np.float32), np.zeros(n, np.float32)
         t0 = time.time()
@@ -53,4 +70,4 @@ def main(cfg):
 
 
 if __name__ == "__main__":
-    main(int(sys.argv[1]))
+    main(int(sys.argv[1]), int(sys.argv[2]) if len(sys.argv) > 2 else 0)
