@@ -86,6 +86,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the CPU-oracle baseline sample (0 = skip)")
     ap.add_argument("--no-hbm", action="store_true", help="skip the batch-replicated reward/scan measurement")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy (reference for hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no collectives or sharding; run with --gpus 1")
@@ -178,6 +180,14 @@ def main():
         "policy_logprobs_ms": logprobs_ms,
         "loss": loss,
     }
+    if args.copy_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration"] = {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4, "copies": 3}
+        del src, dst
     if not args.no_hbm:
         del ws, dW, dH
         torch.cuda.empty_cache()
