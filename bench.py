@@ -45,6 +45,24 @@ def cpu_baseline(w, t, sample_rows):
             "sample": f"first {n} rows of the same workload (same W), scoring+loss+backward in float64, {dt:.1f} s"}
 
 
+def stored_traffic(kernel):
+    """HBM-side bytes per launch of `kernel` from the committed counter summary (FETCH_SIZE + WRITE_SIZE,
+    scaled by what the same counters read for a plain copy); None when the kernel sources have changed
+    since the counters were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "bench_cfg1_traffic.json")
+    if not os.path.exists(path):
+        return None
+    rec = json.load(open(path))
+    h = hashlib.sha256()
+    for fn in ("umas_score.hip", "umas_mfma.h", "umas_common.h"):
+        h.update(open(os.path.join(ROOT, "paper_2605_26646_amd", "csrc", fn), "rb").read())
+    k = rec["kernels"].get(kernel)
+    if h.hexdigest() != rec.get("kernel_sources_sha256") or k is None:
+        return None
+    return k["read_bytes"] + k["written_bytes"]
+
+
 def hbm_kernels(umas, wl, torch, cfg, n_traj, iters=5):
     """Reward/routing and scan kernels on a batch-replicated instance: achieved GB/s on algorithmic bytes."""
     w = wl.make_workload(cfg, n_traj=n_traj)
@@ -171,7 +189,7 @@ def main():
         "config": {"workload": "cfg1 Qwen2.5-3B-shaped pipeline: d=2048 V=151936, 64 traj x 3 roles x 256 tokens",
                    "tokens": w.n_tokens, "scored_tokens": n_sel, "step": "assign_token_rewards + advantages + ppo_loss_fwd_bwd"},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": stored_traffic(dom),
                      "flop_per_launch": flop_per_launch, "ms_per_launch": per_launch[dom]},
         "whole_step": {"algorithmic_tflops": algorithmic / (ms_per_step * 1e-3) / 1e12,
                        "frac_of_bf16_peak_algorithmic_6Vd": algorithmic / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
