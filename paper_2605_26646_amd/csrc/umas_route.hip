@@ -275,23 +275,6 @@ __global__ void k_last_valid(int n_turns, const int32_t* __restrict__ seg_turn,
   if (lane == 0) last_valid[s] = best < 0 ? -1 : turn_seg_off[s] + best;
 }
 
-// Largest j in [0, n] with off[j] <= x (ascending off, off[0] <= x), found by one wavefront probing
-// 64 positions per round; every lane of the wavefront must call it and gets the same answer.
-__device__ __forceinline__ int wave_last_le(const int64_t* __restrict__ off, int n, int64_t x) {
-  const int lane = threadIdx.x & (kWave - 1);
-  int lo = 0, hi = n;
-  while (hi - lo >= kWave) {
-    const int step = (hi - lo) / kWave;
-    const bool ok = off[lo + (lane + 1) * step] <= x;
-    const int c = __popcll(__ballot(ok));          // probes 1..c hold
-    const int nhi = c == kWave ? hi : lo + (c + 1) * step - 1;
-    lo += c * step;
-    hi = nhi;
-  }
-  const bool ok = lo + lane <= hi && off[lo + lane] <= x;
-  return lo + __popcll(__ballot(ok)) - 1;
-}
-
 // Per token in model-local order: source index, turn, role, mask, placed reward; per block the
 // number of mask=1 tokens.  A block finds the segment of its first token once (one wavefront-wide
 // search) and keeps the offsets of the next kSegWin segments in LDS; its threads search there.

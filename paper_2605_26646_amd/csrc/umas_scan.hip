@@ -34,19 +34,32 @@ struct Aff {
   float a, b, c, e, f;
 };
 __device__ __forceinline__ Aff aff_identity() { return Aff{1.f, 0.f, 0.f, 1.f, 0.f}; }
-// the map "first, then second"
+// the map "first, then second".  HV = false (no value estimates): NV stays 0, so only G' = a G + c is
+// carried and b, e, f are never looked at.
+template <bool HV>
 __device__ __forceinline__ Aff then(const Aff& first, const Aff& second) {
   Aff r;
   r.a = second.a * first.a;
-  r.b = second.a * first.b + second.b * first.e;
-  r.c = second.a * first.c + second.b * first.f + second.c;
-  r.e = second.e * first.e;
-  r.f = second.e * first.f + second.f;
+  if constexpr (HV) {
+    r.b = second.a * first.b + second.b * first.e;
+    r.c = second.a * first.c + second.b * first.f + second.c;
+    r.e = second.e * first.e;
+    r.f = second.e * first.f + second.f;
+  } else {
+    r.b = 0.f;
+    r.c = second.a * first.c + second.c;
+    r.e = 0.f;
+    r.f = 0.f;
+  }
   return r;
 }
+template <bool HV>
 __device__ __forceinline__ Aff aff_shfl_down(const Aff& m, int o) {
-  return Aff{__shfl_down(m.a, o, kWave), __shfl_down(m.b, o, kWave), __shfl_down(m.c, o, kWave),
-             __shfl_down(m.e, o, kWave), __shfl_down(m.f, o, kWave)};
+  if constexpr (HV)
+    return Aff{__shfl_down(m.a, o, kWave), __shfl_down(m.b, o, kWave), __shfl_down(m.c, o, kWave),
+               __shfl_down(m.e, o, kWave), __shfl_down(m.f, o, kWave)};
+  else
+    return Aff{__shfl_down(m.a, o, kWave), 0.f, __shfl_down(m.c, o, kWave), 0.f, 0.f};
 }
 
 struct ScanParams {
@@ -64,14 +77,11 @@ struct ScanParams {
   float gamma, lam, gamma_turn;
 };
 
-// Smallest boundary (value of off[0..n]) that is >= x; off[n] is the largest boundary and >= x.
+// Smallest boundary (value of off[0..n]) that is >= x; off[0] = 0 and off[n] >= x.  Wavefront-wide:
+// every lane of the calling wavefront takes part and gets the same answer.
 __device__ __forceinline__ int64_t boundary_at_or_after(const int64_t* __restrict__ off, int n, int64_t x) {
-  int lo = 0, hi = n;
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (off[mid] >= x) hi = mid; else lo = mid + 1;
-  }
-  return off[lo];
+  if (x <= 0) return 0;
+  return off[wave_last_le(off, n, x - 1) + 1];
 }
 
 // Position of tile element e in the padded LDS arrays.
@@ -79,6 +89,7 @@ __device__ __forceinline__ int lds_pos(int e) { return e + 4 * (e / kIpt); }
 
 // For every thread, the composition of the folds of all threads to its right inside the block
 // (exclusive, in application order right to left).
+template <bool HV>
 __device__ __forceinline__ Aff block_suffix_excl(Aff mine, Aff* s_w) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
@@ -86,18 +97,19 @@ __device__ __forceinline__ Aff block_suffix_excl(Aff mine, Aff* s_w) {
   Aff incl = mine;   // inclusive suffix inside the wavefront: fold(63) then ... then fold(lane)
 #pragma unroll
   for (int o = 1; o < kWave; o <<= 1) {
-    const Aff right = aff_shfl_down(incl, o);
-    if (lane + o < kWave) incl = then(right, incl);
+    const Aff right = aff_shfl_down<HV>(incl, o);
+    if (lane + o < kWave) incl = then<HV>(right, incl);
   }
-  Aff excl = aff_shfl_down(incl, 1);
+  Aff excl = aff_shfl_down<HV>(incl, 1);
   if (lane == kWave - 1) excl = aff_identity();
   if (lane == 0) s_w[wave] = incl;
   __syncthreads();
   Aff right_waves = aff_identity();
-  for (int w = nwave - 1; w > wave; --w) right_waves = then(right_waves, s_w[w]);
-  return then(right_waves, excl);
+  for (int w = nwave - 1; w > wave; --w) right_waves = then<HV>(right_waves, s_w[w]);
+  return then<HV>(right_waves, excl);
 }
 
+template <bool HV>
 __global__ void __launch_bounds__(kThreads)
 k_gae_scan(ScanParams P, float* __restrict__ adv, float* __restrict__ ret) {
   __shared__ __attribute__((aligned(16))) float s_r[kLdsWords], s_v[kLdsWords];
@@ -105,65 +117,86 @@ k_gae_scan(ScanParams P, float* __restrict__ adv, float* __restrict__ ret) {
   __shared__ float s_carry[2];
   __shared__ int64_t s_range[2];
   const int tid = threadIdx.x;
-  if (tid == 0) {
-    const int64_t p_lo = static_cast<int64_t>(blockIdx.x) * P.chunk;
-    const int64_t p_hi = p_lo + P.chunk;
-    s_range[0] = boundary_at_or_after(P.seg_off, P.n_seg_entries, p_lo);
-    s_range[1] = p_hi >= P.n_tokens ? P.n_tokens : boundary_at_or_after(P.seg_off, P.n_seg_entries, p_hi);
-    s_carry[0] = 0.f;
-    s_carry[1] = 0.f;
+  if (tid < 2 * kWave) {     // wavefront 0 finds the left end of the range, wavefront 1 the right end
+    const int which = tid / kWave;
+    const int64_t x = (static_cast<int64_t>(blockIdx.x) + which) * P.chunk;
+    const int64_t bnd = x >= P.n_tokens ? P.n_tokens : boundary_at_or_after(P.seg_off, P.n_seg_entries, x);
+    if ((tid & (kWave - 1)) == 0) {
+      s_range[which] = bnd;
+      s_carry[which] = 0.f;
+    }
   }
   __syncthreads();
   const int64_t start = s_range[0], end = s_range[1];
   if (start >= end) return;
   const float gl = P.gamma * P.lam;
 
-  for (int64_t tile = (end - 1) / kTile; tile >= start / kTile; --tile) {
-    const int64_t t0 = tile * kTile;
-    // coalesced 16-byte loads, transposed through LDS into 16 consecutive tokens per thread
+  // raw tile in registers: element e = k*(kThreads*4) + tid*4 of the tile for the values (coalesced 16-byte
+  // loads), this thread's own kIpt consecutive tokens for the flags
+  struct Raw {
+    float4 r4[kIpt / 4], v4[kIpt / 4];
+    uint32_t w[kIpt / 4];
+  };
+  auto load_tile = [&](int64_t t0, Raw& x) {
 #pragma unroll
     for (int k = 0; k < kIpt / 4; ++k) {
-      const int e = k * (kThreads * 4) + tid * 4;
-      const int64_t p = t0 + e;
-      float4 r4 = make_float4(0.f, 0.f, 0.f, 0.f), v4 = r4;
+      const int64_t p = t0 + k * (kThreads * 4) + tid * 4;
+      x.r4[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      x.v4[k] = x.r4[k];
       if (p + 3 < P.n_tokens) {
-        r4 = *reinterpret_cast<const float4*>(P.reward + p);
-        if (P.value) v4 = *reinterpret_cast<const float4*>(P.value + p);
+        x.r4[k] = *reinterpret_cast<const float4*>(P.reward + p);
+        if constexpr (HV) x.v4[k] = *reinterpret_cast<const float4*>(P.value + p);
       } else {
-        float* rp = &r4.x;
-        float* vp = &v4.x;
+        float* rp = &x.r4[k].x;
+        float* vp = &x.v4[k].x;
         for (int j = 0; j < 4; ++j)
           if (p + j < P.n_tokens) {
             rp[j] = P.reward[p + j];
-            if (P.value) vp[j] = P.value[p + j];
+            if constexpr (HV) vp[j] = P.value[p + j];
           }
       }
-      *reinterpret_cast<float4*>(s_r + lds_pos(e)) = r4;
-      *reinterpret_cast<float4*>(s_v + lds_pos(e)) = v4;
+    }
+    const int64_t p0 = t0 + static_cast<int64_t>(tid) * kIpt;
+    if (p0 + kIpt <= P.n_tokens) {
+      if constexpr (kIpt == 16) {
+        const uint4 f4 = *reinterpret_cast<const uint4*>(P.flags + p0);
+        x.w[0] = f4.x; x.w[1] = f4.y; x.w[2] = f4.z; x.w[3] = f4.w;
+      } else {
+        const uint2 f2 = *reinterpret_cast<const uint2*>(P.flags + p0);
+        x.w[0] = f2.x; x.w[1] = f2.y;
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < kIpt / 4; ++k) x.w[k] = 0;
+      for (int k = 0; k < kIpt; ++k)
+        if (p0 + k < P.n_tokens) x.w[k >> 2] |= static_cast<uint32_t>(P.flags[p0 + k]) << (8 * (k & 3));
+    }
+  };
+
+  const int64_t tile_first = start / kTile;
+  Raw nxt;
+  load_tile(((end - 1) / kTile) * kTile, nxt);
+  for (int64_t tile = (end - 1) / kTile; tile >= tile_first; --tile) {
+    const int64_t t0 = tile * kTile;
+    // transpose through LDS into kIpt consecutive tokens per thread
+#pragma unroll
+    for (int k = 0; k < kIpt / 4; ++k) {
+      const int e = k * (kThreads * 4) + tid * 4;
+      *reinterpret_cast<float4*>(s_r + lds_pos(e)) = nxt.r4[k];
+      if constexpr (HV) *reinterpret_cast<float4*>(s_v + lds_pos(e)) = nxt.v4[k];
     }
     const int64_t p0 = t0 + static_cast<int64_t>(tid) * kIpt;   // this thread's first token
     uint8_t fl[kIpt];
-    if (p0 + kIpt <= P.n_tokens) {
-      uint32_t w[kIpt / 4];
-      if constexpr (kIpt == 16) {
-        const uint4 f4 = *reinterpret_cast<const uint4*>(P.flags + p0);
-        w[0] = f4.x; w[1] = f4.y; w[2] = f4.z; w[3] = f4.w;
-      } else {
-        const uint2 f2 = *reinterpret_cast<const uint2*>(P.flags + p0);
-        w[0] = f2.x; w[1] = f2.y;
-      }
 #pragma unroll
-      for (int k = 0; k < kIpt; ++k) fl[k] = static_cast<uint8_t>(w[k >> 2] >> (8 * (k & 3)));
-    } else {
-#pragma unroll
-      for (int k = 0; k < kIpt; ++k) fl[k] = p0 + k < P.n_tokens ? P.flags[p0 + k] : 0;
-    }
+    for (int k = 0; k < kIpt; ++k) fl[k] = static_cast<uint8_t>(nxt.w[k >> 2] >> (8 * (k & 3)));
+    if (tile > tile_first) load_tile(t0 - kTile, nxt);           // in flight while this tile is computed
     __syncthreads();
     float r[kIpt], v[kIpt];
 #pragma unroll
     for (int k = 0; k < kIpt / 4; ++k) {
       const float4 r4 = *reinterpret_cast<const float4*>(s_r + tid * kRow + 4 * k);
-      const float4 v4 = *reinterpret_cast<const float4*>(s_v + tid * kRow + 4 * k);
+      float4 v4 = make_float4(0.f, 0.f, 0.f, 0.f);
+      if constexpr (HV) v4 = *reinterpret_cast<const float4*>(s_v + tid * kRow + 4 * k);
       r[4 * k] = r4.x; r[4 * k + 1] = r4.y; r[4 * k + 2] = r4.z; r[4 * k + 3] = r4.w;
       v[4 * k] = v4.x; v[4 * k + 1] = v4.y; v[4 * k + 2] = v4.z; v[4 * k + 3] = v4.w;
     }
@@ -188,12 +221,13 @@ k_gae_scan(ScanParams P, float* __restrict__ adv, float* __restrict__ ret) {
       else if (P.decay) { acc.a *= kap[k]; acc.b *= kap[k]; acc.c *= kap[k]; acc.e *= kap[k]; acc.f *= kap[k]; }
       if (fl[k] & kFlagMask) {
         const Aff t{gl, P.gamma, r[k] - v[k], 0.f, v[k]};
-        acc = then(acc, t);
+        acc = then<HV>(acc, t);
       }
     }
-    const Aff from_right = block_suffix_excl(acc, s_w);
+    const Aff from_right = block_suffix_excl<HV>(acc, s_w);
     float G = from_right.a * s_carry[0] + from_right.b * s_carry[1] + from_right.c;
-    float NV = from_right.e * s_carry[1] + from_right.f;
+    float NV = 0.f;
+    if constexpr (HV) NV = from_right.e * s_carry[1] + from_right.f;
     // replay; results overwrite this thread's own LDS rows
 #pragma unroll
     for (int k = kIpt - 1; k >= 0; --k) {
@@ -214,7 +248,8 @@ k_gae_scan(ScanParams P, float* __restrict__ adv, float* __restrict__ ret) {
 #pragma unroll
     for (int k = 0; k < kIpt / 4; ++k) {
       *reinterpret_cast<float4*>(s_r + tid * kRow + 4 * k) = make_float4(r[4 * k], r[4 * k + 1], r[4 * k + 2], r[4 * k + 3]);
-      *reinterpret_cast<float4*>(s_v + tid * kRow + 4 * k) = make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
+      if constexpr (HV)     // without values the return equals the advantage
+        *reinterpret_cast<float4*>(s_v + tid * kRow + 4 * k) = make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
     }
     __syncthreads();                       // everyone has read s_carry and written its results
     if (tid == 0) { s_carry[0] = G; s_carry[1] = NV; }   // state at the tile's left edge
@@ -223,7 +258,8 @@ k_gae_scan(ScanParams P, float* __restrict__ adv, float* __restrict__ ret) {
       const int e = k * (kThreads * 4) + tid * 4;
       const int64_t p = t0 + e;
       const float4 a4 = *reinterpret_cast<const float4*>(s_r + lds_pos(e));
-      const float4 b4 = *reinterpret_cast<const float4*>(s_v + lds_pos(e));
+      float4 b4 = a4;
+      if constexpr (HV) b4 = *reinterpret_cast<const float4*>(s_v + lds_pos(e));
       if (p >= start && p + 3 < end) {
         *reinterpret_cast<float4*>(adv + p) = a4;
         *reinterpret_cast<float4*>(ret + p) = b4;
@@ -288,7 +324,8 @@ extern "C" umas_status umas_advantages(const umas_streams* s, int64_t n_tokens, 
   P.lam = lam;
   P.gamma_turn = gamma_turn;
   const unsigned nblk = cdiv(n_tokens, P.chunk);
-  hipLaunchKernelGGL(k_gae_scan, dim3(nblk), dim3(kThreads), 0, st, P, adv, ret);
+  if (value) hipLaunchKernelGGL(k_gae_scan<true>, dim3(nblk), dim3(kThreads), 0, st, P, adv, ret);
+  else hipLaunchKernelGGL(k_gae_scan<false>, dim3(nblk), dim3(kThreads), 0, st, P, adv, ret);
   UMAS_LAUNCHED("k_gae_scan");
   return UMAS_OK;
 }
