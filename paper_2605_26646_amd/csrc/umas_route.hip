@@ -17,8 +17,21 @@ namespace {
 
 constexpr int kTurnBlock = 256;   // turns per block in the turn-level kernels
 constexpr int kTokThreads = 256;
-constexpr int kTokPerThread = 4;
-constexpr int kTokBlock = kTokThreads * kTokPerThread;
+constexpr int kTokPerThread = 4;   // consecutive tokens of one thread in one round
+constexpr int kTokRounds = 4;      // rounds of a block, kTokThreads * kTokPerThread tokens apart
+constexpr int kTokRound = kTokThreads * kTokPerThread;
+constexpr int kTokBlock = kTokRound * kTokRounds;
+
+// What the token kernel needs to know about one turn segment of a model-local stream.
+struct __attribute__((aligned(16))) SegMeta {
+  int64_t src;         // global index of the segment's first token
+  int64_t last_valid;  // model-local position of its last mask=1 token, or -1
+  int32_t turn;
+  int32_t role;
+  float rho;           // composed reward of the turn
+  int32_t end_flags;   // flag bits of the segment's last token besides the mask bit
+};
+static_assert(sizeof(SegMeta) == 32, "two 16-byte loads");
 
 struct RouteWs {
   int32_t* role_to_model;
@@ -34,7 +47,8 @@ struct RouteWs {
   float* traj_norm;     // [n_traj]
   int32_t* turn_traj;   // [n_turns]
   int32_t* turn_model;  // [n_turns]
-  int64_t* last_valid;  // [n_turns] per segment slot: model-local position or -1
+  SegMeta* seg_meta;    // [n_turns] per segment slot
+  int32_t* blk_first;   // [nblk_tok] segment that holds the first token of each token block
   int64_t* part;        // [2*K][nblk_turn] per-model (turn count, token count) per block, scanned in place
   int64_t* part_total;  // [2*K]
   int64_t* run_blk;     // [nblk_turn]
@@ -59,7 +73,8 @@ size_t carve(Carver& c, RouteWs& w, int n_roles, int n_traj, int n_turns, int64_
   w.traj_norm = c.take<float>(n_traj);
   w.turn_traj = c.take<int32_t>(n_turns);
   w.turn_model = c.take<int32_t>(n_turns);
-  w.last_valid = c.take<int64_t>(n_turns);
+  w.seg_meta = c.take<SegMeta>(n_turns);
+  w.blk_first = c.take<int32_t>(nbk);
   w.part = c.take<int64_t>(2 * UMAS_MAX_MODELS * nbt);
   w.part_total = c.take<int64_t>(2 * UMAS_MAX_MODELS);
   w.run_blk = c.take<int64_t>(nbt);
@@ -256,15 +271,22 @@ __global__ void k_fill_i64(int64_t* __restrict__ p, int64_t n, int64_t v) {
   if (i < n) p[i] = v;
 }
 
-// Highest model-local position of a mask=1 token in each turn segment; one wavefront per segment.
-__global__ void k_last_valid(int n_turns, const int32_t* __restrict__ seg_turn,
-                             const int64_t* __restrict__ turn_tok_off, const int64_t* __restrict__ turn_seg_off,
-                             const uint8_t* __restrict__ mask, int64_t* __restrict__ last_valid) {
+// Per turn segment, one wavefront each: the highest model-local position of a mask=1 token, the
+// turn's source offset, role and reward gathered into one record, the flag bits of its last token
+// (segment end; also trajectory-run end when a run starts at the segment's end offset or the stream
+// ends there), and for every token block whose first token lies in the segment, the segment's index.
+__global__ void k_seg_meta(int n_turns, int64_t n_tokens, const int32_t* __restrict__ seg_turn,
+                           const int64_t* __restrict__ turn_tok_off, const int64_t* __restrict__ turn_seg_off,
+                           const int32_t* __restrict__ turn_role, const float* __restrict__ turn_scalar,
+                           const int32_t* __restrict__ turn_traj, const int32_t* __restrict__ turn_model,
+                           const uint8_t* __restrict__ mask, SegMeta* __restrict__ seg_meta,
+                           int32_t* __restrict__ blk_first) {
   const int lane = threadIdx.x & (kWave - 1);
   const int s = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
   if (s >= n_turns) return;
   const int u = seg_turn[s];
   const int64_t g0 = turn_tok_off[u], len = turn_tok_off[u + 1] - g0;
+  const int64_t a = turn_seg_off[s], e = a + len;
   int64_t best = -1;
   // walk from the end in steps of one wavefront; stop at the first step that holds a valid token
   for (int64_t hi = len; hi > 0 && best < 0; hi -= kWave) {
@@ -272,61 +294,138 @@ __global__ void k_last_valid(int n_turns, const int32_t* __restrict__ seg_turn,
     const int64_t cand = (i >= 0 && mask[g0 + i]) ? i : -1;
     best = wave_max(cand);
   }
-  if (lane == 0) last_valid[s] = best < 0 ? -1 : turn_seg_off[s] + best;
+  if (lane == 0) {
+    bool run_end = e == n_tokens;
+    for (int t = s + 1; t < n_turns && !run_end; ++t) {     // segments that start at e: empty ones, then one more
+      run_end = run_start(t, seg_turn, turn_traj, turn_model) != 0;
+      if (turn_seg_off[t + 1] > e) break;
+    }
+    SegMeta m;
+    m.src = g0;
+    m.last_valid = best < 0 ? -1 : a + best;
+    m.turn = u;
+    m.role = turn_role[u];
+    m.rho = turn_scalar[u];
+    m.end_flags = 2 | (run_end ? 4 : 0);
+    seg_meta[s] = m;
+  }
+  for (int64_t b = (a + kTokBlock - 1) / kTokBlock + lane; b * kTokBlock < e; b += kWave) blk_first[b] = s;
 }
 
-// Per token in model-local order: source index, turn, role, mask, placed reward; per block the
-// number of mask=1 tokens.  A block finds the segment of its first token once (one wavefront-wide
-// search) and keeps the offsets of the next kSegWin segments in LDS; its threads search there.
+// Per token in model-local order: source index, turn, role, mask, flags, placed reward; per block the
+// number of mask=1 tokens.  A block keeps the offsets and records of the kSegWin segments from the
+// one that holds its first token in LDS; its threads search there (streams whose segments are so
+// short that the window does not cover the block read global memory instead).
 constexpr int kSegWin = 256;
 __global__ void __launch_bounds__(kTokThreads)
 k_tokens(int64_t n_tokens, int n_turns, int place_mode, const int64_t* __restrict__ turn_seg_off,
-         const int32_t* __restrict__ seg_turn, const int64_t* __restrict__ turn_tok_off,
-         const int32_t* __restrict__ turn_role, const float* __restrict__ turn_scalar,
-         const int64_t* __restrict__ last_valid, const uint8_t* __restrict__ mask_global,
-         int64_t* __restrict__ perm, int32_t* __restrict__ tok_turn, int32_t* __restrict__ tok_role,
-         uint8_t* __restrict__ tok_mask, uint8_t* __restrict__ tok_flags, float* __restrict__ tok_reward,
-         int64_t* __restrict__ tok_blk) {
+         const SegMeta* __restrict__ seg_meta, const int32_t* __restrict__ blk_first,
+         const uint8_t* __restrict__ mask_global, int64_t* __restrict__ perm, int32_t* __restrict__ tok_turn,
+         int32_t* __restrict__ tok_role, uint8_t* __restrict__ tok_mask, uint8_t* __restrict__ tok_flags,
+         float* __restrict__ tok_reward, int64_t* __restrict__ tok_blk) {
   __shared__ int64_t smem[32];
   __shared__ int64_t s_off[kSegWin + 1];
-  __shared__ int s_first;
+  __shared__ int32_t s_loc[kSegWin + 1];            // the same offsets relative to the block's first token, clamped
+  __shared__ SegMeta s_meta[kSegWin];
   const int64_t blk0 = static_cast<int64_t>(blockIdx.x) * kTokBlock;
-  const int64_t blk_last = (blk0 + kTokBlock < n_tokens ? blk0 + kTokBlock : n_tokens) - 1;
-  if (threadIdx.x < kWave) {
-    const int s0 = wave_last_le(turn_seg_off, n_turns, blk0);
-    if (threadIdx.x == 0) s_first = s0;
+  const int s_base = blk_first[blockIdx.x];
+  // segments s_base .. s_end hold the block's tokens (s_end = the segment of the next block's first token)
+  const int s_end = blk0 + kTokBlock < n_tokens ? blk_first[blockIdx.x + 1] : n_turns - 1;
+  const int need = s_end - s_base + 1;
+  const int win = need < kSegWin ? need : kSegWin;                           // s_off[0..win], s_meta[0..win) are valid
+  for (int i = threadIdx.x; i <= win; i += kTokThreads) {
+    const int64_t off = turn_seg_off[s_base + i];
+    const int64_t rel = off - blk0;
+    s_off[i] = off;
+    s_loc[i] = static_cast<int32_t>(rel < -(1 << 30) ? -(1 << 30) : rel > (1 << 30) ? (1 << 30) : rel);
+    if (i < win) s_meta[i] = seg_meta[s_base + i];
   }
   __syncthreads();
-  const int s_base = s_first;
-  const int win = n_turns - s_base < kSegWin ? n_turns - s_base : kSegWin;   // s_off[0..win] are valid
-  for (int i = threadIdx.x; i <= win; i += kTokThreads) s_off[i] = turn_seg_off[s_base + i];
-  __syncthreads();
-  const bool in_window = s_off[win] > blk_last;     // every token of the block lies in a windowed segment
-  const int64_t p0 = blk0 + static_cast<int64_t>(threadIdx.x) * kTokPerThread;
+  const bool in_window = need <= kSegWin;           // every token of the block lies in a windowed segment
+  const bool mask_aligned = (reinterpret_cast<uintptr_t>(mask_global) & 3) == 0;
   int64_t cnt = 0;
-  if (p0 < n_tokens) {
+  // Phase A: every round's segment search and mask load.  All loads are in flight before the first
+  // store is issued, so no round waits behind the stores of the round before it.
+  int lo_r[kTokRounds];
+  uint32_t m4_r[kTokRounds];
+  bool fast_r[kTokRounds];
+#pragma unroll
+  for (int rd = 0; rd < kTokRounds; ++rd) {
+    const int pl0 = rd * kTokRound + static_cast<int>(threadIdx.x) * kTokPerThread;   // block-relative
+    const int64_t p0 = blk0 + pl0;
+    lo_r[rd] = 0; m4_r[rd] = 0; fast_r[rd] = false;
+    if (!in_window || p0 >= n_tokens) continue;
+    int lo = 0, hi = win;                           // largest j with s_loc[j] <= pl0: the segment that holds p0
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (s_loc[mid] <= pl0) lo = mid; else hi = mid - 1;
+    }
+    lo_r[rd] = lo;
+    // fast when the four tokens lie in one segment: no per-token bookkeeping
+    fast_r[rd] = pl0 + kTokPerThread <= s_loc[lo + 1] && p0 + kTokPerThread <= n_tokens;
+    if (fast_r[rd]) {
+      const int64_t g0 = s_meta[lo].src + (p0 - s_off[lo]);
+      if (mask_aligned && (g0 & 3) == 0) {
+        m4_r[rd] = *reinterpret_cast<const uint32_t*>(mask_global + g0);
+      } else {
+        m4_r[rd] = static_cast<uint32_t>(mask_global[g0]) | (static_cast<uint32_t>(mask_global[g0 + 1]) << 8) |
+                   (static_cast<uint32_t>(mask_global[g0 + 2]) << 16) | (static_cast<uint32_t>(mask_global[g0 + 3]) << 24);
+      }
+    }
+  }
+  // Phase B: outputs
+#pragma unroll
+  for (int rd = 0; rd < kTokRounds; ++rd) {
+    const int pl0 = rd * kTokRound + static_cast<int>(threadIdx.x) * kTokPerThread;
+    const int64_t p0 = blk0 + pl0;
+    if (p0 >= n_tokens) continue;
     int s;
     if (in_window) {
-      int lo = 0, hi = win;                         // largest j with s_off[j] <= p0
-      while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (s_off[mid] <= p0) lo = mid; else hi = mid - 1;
-      }
+      const int lo = lo_r[rd];
       s = s_base + lo;
+      if (fast_r[rd]) {
+        const SegMeta M = s_meta[lo];
+        const int64_t g0 = M.src + (p0 - s_off[lo]);
+        const uint32_t m4 = m4_r[rd];
+        // every non-zero byte becomes 1: (b | 0x80) - 1 keeps bit 7 exactly when b > 0 or-ed with b's own bit 7
+        const uint32_t mk4 = ((((m4 | 0x80808080u) - 0x01010101u) | m4) >> 7) & 0x01010101u;
+        uint32_t fg4 = mk4;
+        if (pl0 + kTokPerThread == s_loc[lo + 1]) fg4 |= static_cast<uint32_t>(M.end_flags) << 24;
+        float rw4[kTokPerThread] = {0.f, 0.f, 0.f, 0.f};
+        if (place_mode == UMAS_PLACE_ALL) {
+#pragma unroll
+          for (int k = 0; k < kTokPerThread; ++k) rw4[k] = ((mk4 >> (8 * k)) & 1u) ? M.rho : 0.f;
+        } else {
+          const int64_t idx = M.last_valid - p0;
+#pragma unroll
+          for (int k = 0; k < kTokPerThread; ++k) rw4[k] = idx == k ? M.rho : 0.f;
+        }
+        cnt += __popc(mk4);
+        *reinterpret_cast<longlong2*>(perm + p0) = make_longlong2(g0, g0 + 1);
+        *reinterpret_cast<longlong2*>(perm + p0 + 2) = make_longlong2(g0 + 2, g0 + 3);
+        *reinterpret_cast<int4*>(tok_turn + p0) = make_int4(M.turn, M.turn, M.turn, M.turn);
+        *reinterpret_cast<int4*>(tok_role + p0) = make_int4(M.role, M.role, M.role, M.role);
+        *reinterpret_cast<uint32_t*>(tok_mask + p0) = mk4;
+        *reinterpret_cast<uint32_t*>(tok_flags + p0) = fg4;
+        *reinterpret_cast<float4*>(tok_reward + p0) = make_float4(rw4[0], rw4[1], rw4[2], rw4[3]);
+        continue;
+      }
     } else {
       s = last_le(turn_seg_off, n_turns, p0);
     }
     int64_t pm[kTokPerThread];
     int32_t tt[kTokPerThread], tr[kTokPerThread];
-    uint8_t mk[kTokPerThread];
+    uint8_t mk[kTokPerThread], fg[kTokPerThread];
     float rw[kTokPerThread];
-    int cur = -1, u = 0, role = 0;
-    int64_t seg_a = 0, seg_e = 0, src = 0, lastv = -1;
-    float rho = 0.f;
+    int cur = -1;
+    int64_t seg_a = 0, seg_e = 0;
+    SegMeta M{};
+    uint32_t m4 = 0;
+    bool have_m4 = false;
 #pragma unroll
     for (int k = 0; k < kTokPerThread; ++k) {
       const int64_t p = p0 + k;
-      pm[k] = 0; tt[k] = 0; tr[k] = 0; mk[k] = 0; rw[k] = 0.0f;
+      pm[k] = 0; tt[k] = 0; tr[k] = 0; mk[k] = 0; fg[k] = 0; rw[k] = 0.0f;
       if (p < n_tokens) {
         if (cur < 0 || p >= seg_e) {                // first token, or the segment changed
           if (in_window) { while (s_off[s - s_base + 1] <= p) ++s; }   // also steps over empty segments
@@ -334,16 +433,18 @@ k_tokens(int64_t n_tokens, int n_turns, int place_mode, const int64_t* __restric
           cur = s;
           seg_a = in_window ? s_off[s - s_base] : turn_seg_off[s];
           seg_e = in_window ? s_off[s - s_base + 1] : turn_seg_off[s + 1];
-          u = seg_turn[s];
-          src = turn_tok_off[u];
-          role = turn_role[u];
-          rho = turn_scalar[u];
-          lastv = last_valid[s];
+          M = in_window ? s_meta[s - s_base] : seg_meta[s];
+          if (k == 0) {                             // all four tokens in one segment and a 4-byte aligned source: one load
+            const int64_t g0 = M.src + (p0 - seg_a);
+            have_m4 = mask_aligned && (g0 & 3) == 0 && p0 + kTokPerThread <= seg_e;
+            if (have_m4) m4 = *reinterpret_cast<const uint32_t*>(mask_global + g0);
+          }
         }
-        const int64_t g = src + (p - seg_a);
-        const uint8_t m = mask_global[g] ? 1 : 0;
-        pm[k] = g; tt[k] = u; tr[k] = role; mk[k] = m;
-        if (m && (place_mode == UMAS_PLACE_ALL || lastv == p)) rw[k] = rho;
+        const int64_t g = M.src + (p - seg_a);
+        const uint8_t m = have_m4 ? (((m4 >> (8 * k)) & 0xFFu) ? 1 : 0) : (mask_global[g] ? 1 : 0);
+        pm[k] = g; tt[k] = M.turn; tr[k] = M.role; mk[k] = m;
+        fg[k] = static_cast<uint8_t>(m | (p == seg_e - 1 ? M.end_flags : 0));
+        if (m && (place_mode == UMAS_PLACE_ALL || M.last_valid == p)) rw[k] = M.rho;
         cnt += m;
       }
     }
@@ -353,32 +454,17 @@ k_tokens(int64_t n_tokens, int n_turns, int place_mode, const int64_t* __restric
       *reinterpret_cast<int4*>(tok_turn + p0) = make_int4(tt[0], tt[1], tt[2], tt[3]);
       *reinterpret_cast<int4*>(tok_role + p0) = make_int4(tr[0], tr[1], tr[2], tr[3]);
       *reinterpret_cast<uchar4*>(tok_mask + p0) = make_uchar4(mk[0], mk[1], mk[2], mk[3]);
-      *reinterpret_cast<uchar4*>(tok_flags + p0) = make_uchar4(mk[0], mk[1], mk[2], mk[3]);
+      *reinterpret_cast<uchar4*>(tok_flags + p0) = make_uchar4(fg[0], fg[1], fg[2], fg[3]);
       *reinterpret_cast<float4*>(tok_reward + p0) = make_float4(rw[0], rw[1], rw[2], rw[3]);
     } else {
       for (int k = 0; k < kTokPerThread && p0 + k < n_tokens; ++k) {
         perm[p0 + k] = pm[k]; tok_turn[p0 + k] = tt[k]; tok_role[p0 + k] = tr[k];
-        tok_mask[p0 + k] = mk[k]; tok_flags[p0 + k] = mk[k]; tok_reward[p0 + k] = rw[k];
+        tok_mask[p0 + k] = mk[k]; tok_flags[p0 + k] = fg[k]; tok_reward[p0 + k] = rw[k];
       }
     }
   }
   const int64_t total = block_sum<int64_t>(cnt, smem);
   if (threadIdx.x == 0) tok_blk[blockIdx.x] = total;
-}
-
-// Segment ends for the scans: the last token of every non-empty turn segment gets bit 1, and bit 2 as well
-// when a trajectory run ends there (its end offset is one of the run offsets).
-__global__ void k_flag_bounds(int n_turns, int64_t n_tokens, const int64_t* __restrict__ turn_seg_off,
-                              const int64_t* __restrict__ traj_seg_off, const uint8_t* __restrict__ tok_mask,
-                              uint8_t* __restrict__ tok_flags) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= n_turns) return;
-  const int64_t a = turn_seg_off[s], e = turn_seg_off[s + 1];
-  if (e <= a) return;
-  uint8_t f = (tok_mask[e - 1] ? 1 : 0) | 2;
-  const int j = last_le(traj_seg_off, n_turns, e);      // entries past the run count hold n_tokens
-  if (e == n_tokens || traj_seg_off[j] == e) f |= 4;
-  tok_flags[e - 1] = f;
 }
 
 // Compaction of mask=1 positions into rowsel (stream-relative), plus the per-model offsets.  A block
@@ -409,17 +495,30 @@ k_rowsel(int64_t n_tokens, int n_models, const uint8_t* __restrict__ tok_mask,
   int32_t tot;
   const int64_t base = tok_blk[static_cast<int64_t>(blockIdx.x) * (kSelBlock / kTokBlock)];
   int32_t lpos = block_excl_scan<int32_t>(cnt, smem, &tot);
+  // a model's stream may start inside this block: only then do tokens need the per-token boundary checks
+  const int64_t sel0 = static_cast<int64_t>(blockIdx.x) * kSelBlock;
+  bool boundary = false;
+  for (int j = 0; j <= n_models; ++j) boundary |= moff[j] > sel0 && moff[j] < sel0 + kSelBlock;
   if (p0 < n_tokens) {
     int m = 0;
     while (m < n_models && moff[m + 1] <= p0) ++m;
+    if (!boundary) {
+      for (int j = 0; j <= n_models; ++j)
+        if (moff[j] == p0) model_rowsel_off[j] = base + lpos;      // only a block's first token can start a stream here
+      const int32_t rel = static_cast<int32_t>(p0 - moff[m]);
 #pragma unroll
-    for (int k = 0; k < kSelPerThread; ++k) {
-      const int64_t p = p0 + k;
-      if (p < n_tokens) {
-        while (m < n_models && moff[m + 1] <= p) ++m;
-        for (int j = 0; j <= n_models; ++j)
-          if (moff[j] == p) model_rowsel_off[j] = base + lpos;
-        if ((w[k >> 2] >> (8 * (k & 3))) & 1u) s_out[lpos++] = static_cast<int32_t>(p - moff[m]);
+      for (int k = 0; k < kSelPerThread; ++k)
+        if ((w[k >> 2] >> (8 * (k & 3))) & 1u) s_out[lpos++] = rel + k;   // bytes past n_tokens are 0
+    } else {
+#pragma unroll
+      for (int k = 0; k < kSelPerThread; ++k) {
+        const int64_t p = p0 + k;
+        if (p < n_tokens) {
+          while (m < n_models && moff[m + 1] <= p) ++m;
+          for (int j = 0; j <= n_models; ++j)
+            if (moff[j] == p) model_rowsel_off[j] = base + lpos;
+          if ((w[k >> 2] >> (8 * (k & 3))) & 1u) s_out[lpos++] = static_cast<int32_t>(p - moff[m]);
+        }
       }
     }
   }
@@ -589,17 +688,15 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
                      o->model_trajrun_off);
   UMAS_LAUNCHED("k_run_apply");
   if (U > 0 && N > 0) {
-    hipLaunchKernelGGL(k_last_valid, dim3(cdiv(U, 4)), dim3(256), 0, st, U, o->seg_turn, w.turn_tok_off,
-                       o->turn_seg_off, tok_mask_global, w.last_valid);
-    UMAS_LAUNCHED("k_last_valid");
+    hipLaunchKernelGGL(k_seg_meta, dim3(cdiv(U, 4)), dim3(256), 0, st, U, N, o->seg_turn, w.turn_tok_off,
+                       o->turn_seg_off, w.turn_role, o->turn_scalar, w.turn_traj, w.turn_model, tok_mask_global,
+                       w.seg_meta, w.blk_first);
+    UMAS_LAUNCHED("k_seg_meta");
     const int nbk = cdiv(N, kTokBlock);
-    hipLaunchKernelGGL(k_tokens, dim3(nbk), dim3(kTokThreads), 0, st, N, U, r->place_mode, o->turn_seg_off,
-                       o->seg_turn, w.turn_tok_off, w.turn_role, o->turn_scalar, w.last_valid, tok_mask_global,
-                       o->perm, o->tok_turn, o->tok_role, o->tok_mask, o->tok_flags, o->tok_reward, w.tok_blk);
+    hipLaunchKernelGGL(k_tokens, dim3(nbk), dim3(kTokThreads), 0, st, N, U, r->place_mode, o->turn_seg_off, w.seg_meta,
+                       w.blk_first, tok_mask_global, o->perm, o->tok_turn, o->tok_role, o->tok_mask, o->tok_flags,
+                       o->tok_reward, w.tok_blk);
     UMAS_LAUNCHED("k_tokens");
-    hipLaunchKernelGGL(k_flag_bounds, dim3(cdiv(U, 256)), dim3(256), 0, st, U, N, o->turn_seg_off, o->traj_seg_off,
-                       o->tok_mask, o->tok_flags);
-    UMAS_LAUNCHED("k_flag_bounds");
     hipLaunchKernelGGL(k_excl_scan_rows, dim3(1), dim3(1024), 0, st, w.tok_blk, nbk, w.tok_total);
     UMAS_LAUNCHED("k_excl_scan_rows");
     hipLaunchKernelGGL(k_rowsel, dim3(cdiv(N, kSelBlock)), dim3(kTokThreads), 0, st, N, K, o->tok_mask, o->model_tok_off,
