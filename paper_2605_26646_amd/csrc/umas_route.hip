@@ -21,6 +21,9 @@ constexpr int kTokPerThread = 4;   // consecutive tokens of one thread in one ro
 constexpr int kTokRounds = 4;      // rounds of a block, kTokThreads * kTokPerThread tokens apart
 constexpr int kTokRound = kTokThreads * kTokPerThread;
 constexpr int kTokBlock = kTokRound * kTokRounds;
+constexpr int kCntTokens = 4096;   // mask=1 tokens are counted per this many tokens (one compaction block)
+constexpr int kCntRounds = kCntTokens / kTokRound;
+static_assert(kTokBlock % kCntTokens == 0 && kCntTokens % kTokRound == 0, "a token block is a whole number of count groups");
 
 // What the token kernel needs to know about one turn segment of a model-local stream.
 struct __attribute__((aligned(16))) SegMeta {
@@ -59,7 +62,7 @@ struct RouteWs {
 
 size_t carve(Carver& c, RouteWs& w, int n_roles, int n_traj, int n_turns, int64_t n_tokens) {
   const size_t nbt = cdiv(n_turns > 0 ? n_turns : 1, kTurnBlock);
-  const size_t nbk = cdiv(n_tokens > 0 ? n_tokens : 1, kTokBlock);
+  const size_t nbk = cdiv(n_tokens > 0 ? n_tokens : 1, kCntTokens);   // count groups (>= token blocks)
   w.role_to_model = c.take<int32_t>(n_roles);
   w.traj_turn_off = c.take<int32_t>(n_traj + 1);
   w.turn_role = c.take<int32_t>(n_turns);
@@ -282,11 +285,18 @@ __global__ void k_seg_meta(int n_turns, int64_t n_tokens, const int32_t* __restr
                            const uint8_t* __restrict__ mask, SegMeta* __restrict__ seg_meta,
                            int32_t* __restrict__ blk_first) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int s = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  // wavefront-uniform index: the per-segment reads below become scalar loads, issued together
+  const int s = __builtin_amdgcn_readfirstlane(blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave);
   if (s >= n_turns) return;
+  const bool has_next = s + 1 < n_turns;
   const int u = seg_turn[s];
+  const int un = has_next ? seg_turn[s + 1] : u;
   const int64_t g0 = turn_tok_off[u], len = turn_tok_off[u + 1] - g0;
   const int64_t a = turn_seg_off[s], e = a + len;
+  const int64_t e_next = has_next ? turn_seg_off[s + 2] : e;      // end of the next segment
+  const int role = turn_role[u];
+  const float rho = turn_scalar[u];
+  const bool next_starts_run = turn_model[u] != turn_model[un] || turn_traj[u] != turn_traj[un];
   int64_t best = -1;
   // walk from the end in steps of one wavefront; stop at the first step that holds a valid token
   for (int64_t hi = len; hi > 0 && best < 0; hi -= kWave) {
@@ -295,17 +305,20 @@ __global__ void k_seg_meta(int n_turns, int64_t n_tokens, const int32_t* __restr
     best = wave_max(cand);
   }
   if (lane == 0) {
-    bool run_end = e == n_tokens;
-    for (int t = s + 1; t < n_turns && !run_end; ++t) {     // segments that start at e: empty ones, then one more
-      run_end = run_start(t, seg_turn, turn_traj, turn_model) != 0;
-      if (turn_seg_off[t + 1] > e) break;
-    }
+    // a run ends at e when the stream ends there or a run starts at one of the segments that begin at e:
+    // the next one, and if that one is empty the ones after it up to the first non-empty one
+    bool run_end = e == n_tokens || (has_next && next_starts_run);
+    if (!run_end && has_next && e_next <= e)
+      for (int t = s + 2; t < n_turns && !run_end; ++t) {
+        run_end = run_start(t, seg_turn, turn_traj, turn_model) != 0;
+        if (turn_seg_off[t + 1] > e) break;
+      }
     SegMeta m;
     m.src = g0;
     m.last_valid = best < 0 ? -1 : a + best;
     m.turn = u;
-    m.role = turn_role[u];
-    m.rho = turn_scalar[u];
+    m.role = role;
+    m.rho = rho;
     m.end_flags = 2 | (run_end ? 4 : 0);
     seg_meta[s] = m;
   }
@@ -343,7 +356,7 @@ k_tokens(int64_t n_tokens, int n_turns, int place_mode, const int64_t* __restric
   __syncthreads();
   const bool in_window = need <= kSegWin;           // every token of the block lies in a windowed segment
   const bool mask_aligned = (reinterpret_cast<uintptr_t>(mask_global) & 3) == 0;
-  int64_t cnt = 0;
+  int64_t cnt[kTokRounds / kCntRounds] = {};
   // Phase A: every round's segment search and mask load.  All loads are in flight before the first
   // store is issued, so no round waits behind the stores of the round before it.
   int lo_r[kTokRounds];
@@ -400,7 +413,7 @@ k_tokens(int64_t n_tokens, int n_turns, int place_mode, const int64_t* __restric
 #pragma unroll
           for (int k = 0; k < kTokPerThread; ++k) rw4[k] = idx == k ? M.rho : 0.f;
         }
-        cnt += __popc(mk4);
+        cnt[rd / kCntRounds] += __popc(mk4);
         *reinterpret_cast<longlong2*>(perm + p0) = make_longlong2(g0, g0 + 1);
         *reinterpret_cast<longlong2*>(perm + p0 + 2) = make_longlong2(g0 + 2, g0 + 3);
         *reinterpret_cast<int4*>(tok_turn + p0) = make_int4(M.turn, M.turn, M.turn, M.turn);
@@ -445,7 +458,7 @@ k_tokens(int64_t n_tokens, int n_turns, int place_mode, const int64_t* __restric
         pm[k] = g; tt[k] = M.turn; tr[k] = M.role; mk[k] = m;
         fg[k] = static_cast<uint8_t>(m | (p == seg_e - 1 ? M.end_flags : 0));
         if (m && (place_mode == UMAS_PLACE_ALL || M.last_valid == p)) rw[k] = M.rho;
-        cnt += m;
+        cnt[rd / kCntRounds] += m;
       }
     }
     if (p0 + kTokPerThread <= n_tokens) {
@@ -463,15 +476,20 @@ k_tokens(int64_t n_tokens, int n_turns, int place_mode, const int64_t* __restric
       }
     }
   }
-  const int64_t total = block_sum<int64_t>(cnt, smem);
-  if (threadIdx.x == 0) tok_blk[blockIdx.x] = total;
+#pragma unroll
+  for (int gi = 0; gi < kTokRounds / kCntRounds; ++gi) {
+    const int64_t total = block_sum<int64_t>(cnt[gi], smem);
+    const int64_t slot = static_cast<int64_t>(blockIdx.x) * (kTokRounds / kCntRounds) + gi;
+    if (threadIdx.x == 0 && slot * kCntTokens < n_tokens) tok_blk[slot] = total;
+    __syncthreads();                                // smem is reused by the next group's sum
+  }
 }
 
 // Compaction of mask=1 positions into rowsel (stream-relative), plus the per-model offsets.  A block
-// covers kSelBlock tokens = kSelBlock / kTokBlock blocks of k_tokens, whose scanned counts give its base.
+// covers kSelBlock tokens = one count group of k_tokens, whose scanned counts give its base.
 constexpr int kSelPerThread = 16;
 constexpr int kSelBlock = kTokThreads * kSelPerThread;
-static_assert(kSelBlock % kTokBlock == 0, "a compaction block spans whole token blocks");
+static_assert(kSelBlock == kCntTokens, "a compaction block is one count group");
 __global__ void __launch_bounds__(kTokThreads)
 k_rowsel(int64_t n_tokens, int n_models, const uint8_t* __restrict__ tok_mask,
          const int64_t* __restrict__ model_tok_off, const int64_t* __restrict__ tok_blk,
@@ -493,7 +511,7 @@ k_rowsel(int64_t n_tokens, int n_models, const uint8_t* __restrict__ tok_mask,
   }
   const int32_t cnt = __popc(w[0]) + __popc(w[1]) + __popc(w[2]) + __popc(w[3]);   // mask bytes are 0 or 1
   int32_t tot;
-  const int64_t base = tok_blk[static_cast<int64_t>(blockIdx.x) * (kSelBlock / kTokBlock)];
+  const int64_t base = tok_blk[blockIdx.x];
   int32_t lpos = block_excl_scan<int32_t>(cnt, smem, &tot);
   // a model's stream may start inside this block: only then do tokens need the per-token boundary checks
   const int64_t sel0 = static_cast<int64_t>(blockIdx.x) * kSelBlock;
@@ -697,7 +715,7 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
                        w.blk_first, tok_mask_global, o->perm, o->tok_turn, o->tok_role, o->tok_mask, o->tok_flags,
                        o->tok_reward, w.tok_blk);
     UMAS_LAUNCHED("k_tokens");
-    hipLaunchKernelGGL(k_excl_scan_rows, dim3(1), dim3(1024), 0, st, w.tok_blk, nbk, w.tok_total);
+    hipLaunchKernelGGL(k_excl_scan_rows, dim3(1), dim3(1024), 0, st, w.tok_blk, cdiv(N, kCntTokens), w.tok_total);
     UMAS_LAUNCHED("k_excl_scan_rows");
     hipLaunchKernelGGL(k_rowsel, dim3(cdiv(N, kSelBlock)), dim3(kTokThreads), 0, st, N, K, o->tok_mask, o->model_tok_off,
                        w.tok_blk, w.tok_total, o->rowsel, o->model_rowsel_off);
