@@ -2,7 +2,10 @@
 
 A plain, slow, sequential statement in float64 of what the GPU library computes:
 reward composition and placement, routing through the agent-to-model map, GAE
-scans, LM-head scoring, the clipped surrogate and its backward.  It shares no
+scans, LM-head scoring, the clipped surrogate and its backward; then the steps around
+it: the critic's value head and clipped value loss, the reference-policy KL folded into
+the rewards, advantage whitening, and the dual-clip / entropy-bonus variants of the
+surrogate.  It shares no
 code with the HIP path and imports nothing from it; only tests, the smoke check
 and the benchmark's CPU-baseline leg may call it.  The product path never does.
 
@@ -10,7 +13,7 @@ Each function names the passage of the paper it follows.  Where the paper leaves
 the arithmetic open (it names PPO but prints no loss; it does not say which
 token carries a delayed reward) the reading taken is stated in the docstring.
 
-Parity pins (tests/test_oracle_pins.py): every function below is pinned against
+Parity pins (tests/test_oracle_pins.py, tests/test_oracle_pins_next.py): every function below is pinned against
 hand-worked workflow examples, closed forms, invariants or brute force, except
 the end-to-end composition of all steps, which is "parity unpinned" beyond the
 composition of its pinned parts (the paper prints no end-to-end numbers).
@@ -309,6 +312,185 @@ def lm_head_backward(H, W, ids, lse, g, rowsel=None, chunk=256):
         dz = -p
         dz[np.arange(len(rr)), np.asarray(ids)[rr]] += 1.0
         dz *= np.asarray(g, np.float64)[rr][:, None]
+        dH[rr] = dz @ W64
+        dW += dz.T @ Hc
+    return dH, dW
+
+
+# --------------------------------------------------------------------------------------
+# Critic  ("value estimates", "actor and critic parameters" in "PPO-Style Training Loop";
+# the paper prints no value loss: the clipped form of Schulman et al. 2017 / common PPO
+# implementations is the reading taken)
+# --------------------------------------------------------------------------------------
+def value_head(H, w, b=0.0, rowsel=None):
+    """V_i = w . h_i + b for the selected rows, 0 elsewhere.  float64 [n_rows]."""
+    n = H.shape[0]
+    rows = np.arange(n) if rowsel is None else np.asarray(rowsel, dtype=np.int64)
+    V = np.zeros(n)
+    w64 = np.asarray(w, dtype=np.float64)
+    for i in rows:
+        V[i] = float(np.dot(np.asarray(H[i], dtype=np.float64), w64)) + float(b)
+    return V
+
+
+def value_loss(V, V_old, ret, rowsel, tok_role, n_roles, clip_eps_v):
+    """Clipped value loss over the selected rows.
+
+    Vc = V_old + clip(V - V_old, -eps, +eps); L = 1/2 max((V - R)^2, (Vc - R)^2);
+    loss = sum L / S.  g = d loss / d V = (V - R) / S where the unclipped term is the
+    larger one (ties included), 0 where the clipped term is strictly larger (Vc is then
+    a constant).  Statistics per model and per role, float64 [1+n_roles, 4] =
+    (loss, clip_frac, mean V, n); g float64 [n_rows].
+    """
+    n = len(V)
+    rows = np.arange(n) if rowsel is None else np.asarray(rowsel, dtype=np.int64)
+    S = len(rows)
+    g = np.zeros(n)
+    stats = np.zeros((1 + n_roles, 4))
+    if S == 0:
+        return stats, g
+    v = np.asarray(V, np.float64)[rows]
+    vo = np.asarray(V_old, np.float64)[rows]
+    R = np.asarray(ret, np.float64)[rows]
+    vc = vo + np.minimum(np.maximum(v - vo, -clip_eps_v), clip_eps_v)
+    lu = (v - R) ** 2
+    lc = (vc - R) ** 2
+    unclipped = lu >= lc
+    L = 0.5 * np.maximum(lu, lc)
+    g[rows] = np.where(unclipped, v - R, 0.0) / S
+    role = np.asarray(tok_role)[rows]
+    for k in range(1 + n_roles):
+        sel = np.ones(S, bool) if k == 0 else (role == k - 1)
+        cnt = int(sel.sum())
+        if cnt:
+            stats[k] = (L[sel].sum() / cnt, (~unclipped[sel]).sum() / cnt, v[sel].sum() / cnt, cnt)
+    return stats, g
+
+
+def value_head_backward(H, w, g, rowsel=None):
+    """dH_i = g_i w, dw = sum_i g_i h_i, db = sum_i g_i over the selected rows (float64)."""
+    n, d = H.shape
+    rows = np.arange(n) if rowsel is None else np.asarray(rowsel, dtype=np.int64)
+    w64 = np.asarray(w, dtype=np.float64)
+    dH, dw, db = np.zeros((n, d)), np.zeros(d), 0.0
+    for i in rows:
+        dH[i] = g[i] * w64
+        dw += g[i] * np.asarray(H[i], dtype=np.float64)
+        db += g[i]
+    return dH, dw, db
+
+
+# --------------------------------------------------------------------------------------
+# Reference-policy KL folded into the token rewards  ("reference-policy log probabilities"
+# in "PPO-Style Training Loop"; the paper prints no penalty: the per-token estimate
+# log pi - log pi_ref scaled by beta and subtracted from the reward is the reading taken)
+# --------------------------------------------------------------------------------------
+def kl_penalised_rewards(tok_reward, logp, logp_ref, tok_mask, beta):
+    """r'_t = r_t - beta (logp_t - logp_ref_t) on mask=1 tokens, r_t elsewhere.
+    Also returns the mean of (logp - logp_ref) over the mask=1 tokens (0 if there are none)."""
+    r = np.asarray(tok_reward, dtype=np.float64).copy()
+    m = np.asarray(tok_mask) != 0
+    kl = np.asarray(logp, np.float64) - np.asarray(logp_ref, np.float64)
+    r[m] -= beta * kl[m]
+    return r, (float(kl[m].mean()) if m.any() else 0.0)
+
+
+# --------------------------------------------------------------------------------------
+# Advantage whitening per model or per (model, role)  (agent-wise normalisation is the
+# stabiliser the related work the paper cites centres on; role identity is kept under sharing)
+# --------------------------------------------------------------------------------------
+WHITEN_MODEL = 0
+WHITEN_MODEL_ROLE = 1
+
+
+def whiten_advantages(adv, tok_mask, tok_role, model_tok_off, n_roles, scope, eps=1e-8):
+    """A'_t = (A_t - mu) / sqrt(var + eps) over the mask=1 tokens of each group, where a group is a
+    model's stream (scope MODEL) or the tokens of one role inside it (scope MODEL_ROLE); population
+    variance; masked tokens keep 0; an empty group is left alone.  float64 [n_tokens]."""
+    A = np.asarray(adv, dtype=np.float64)
+    out = np.zeros_like(A)
+    m = np.asarray(tok_mask) != 0
+    role = np.asarray(tok_role)
+    for k in range(len(model_tok_off) - 1):
+        a, e = int(model_tok_off[k]), int(model_tok_off[k + 1])
+        groups = [np.arange(a, e)[m[a:e]]] if scope == WHITEN_MODEL else \
+            [np.arange(a, e)[m[a:e] & (role[a:e] == v)] for v in range(n_roles)]
+        for idx in groups:
+            if len(idx) == 0:
+                continue
+            mu = A[idx].mean()
+            var = ((A[idx] - mu) ** 2).mean()
+            out[idx] = (A[idx] - mu) / np.sqrt(var + eps)
+    return out
+
+
+# --------------------------------------------------------------------------------------
+# Surrogate variants: dual clip and entropy bonus
+# --------------------------------------------------------------------------------------
+def ppo_loss_variants(logp, logp_old, adv, entropy, rowsel, tok_role, n_roles, clip_eps, dual_clip=0.0,
+                      entropy_coef=0.0):
+    """The clipped surrogate with two optional terms.
+
+    dual_clip c > 1: for A < 0 the per-row term max(-A ratio, -A clip(ratio)) is capped at -A c
+    (the gradient vanishes where the cap is strictly smaller).  entropy_coef > 0: the loss
+    becomes L_clip - entropy_coef * mean entropy; its gradient reaches the logits directly
+    (lm_head_backward_entropy), g stays d L_clip / d logp.  The clip fraction counts rows whose
+    active term is not the unclipped one.  Returns (stats [1+n_roles, 5], g) like ppo_loss; stats[:, 0]
+    includes the entropy term.
+    """
+    n = len(logp)
+    rows = np.arange(n) if rowsel is None else np.asarray(rowsel, dtype=np.int64)
+    S = len(rows)
+    g = np.zeros(n)
+    stats = np.zeros((1 + n_roles, 5))
+    if S == 0:
+        return stats, g
+    lp = np.asarray(logp, np.float64)[rows]
+    lo = np.asarray(logp_old, np.float64)[rows]
+    A = np.asarray(adv, np.float64)[rows]
+    Hh = np.asarray(entropy, np.float64)[rows]
+    ratio = np.exp(lp - lo)
+    u = -A * ratio
+    c = -A * np.minimum(np.maximum(ratio, 1.0 - clip_eps), 1.0 + clip_eps)
+    L = np.maximum(u, c)
+    active_unclipped = u >= c
+    if dual_clip > 0.0:
+        cap = -A * dual_clip
+        capped = (A < 0) & (cap < L)
+        L = np.where(capped, cap, L)
+        active_unclipped &= ~capped
+    g[rows] = np.where(active_unclipped, -A * ratio, 0.0) / S
+    role = np.asarray(tok_role)[rows]
+    for k in range(1 + n_roles):
+        sel = np.ones(S, bool) if k == 0 else (role == k - 1)
+        cnt = int(sel.sum())
+        if cnt:
+            stats[k] = (L[sel].sum() / cnt - entropy_coef * Hh[sel].sum() / cnt, (~active_unclipped[sel]).sum() / cnt,
+                        Hh[sel].sum() / cnt, (lo[sel] - lp[sel]).sum() / cnt, cnt)
+    return stats, g
+
+
+def lm_head_backward_entropy(H, W, ids, lse, entropy, g, entropy_coef, n_scored, rowsel=None, chunk=256):
+    """Backward of L_clip - entropy_coef * mean entropy through the LM head.
+
+    d entropy_i / d z_iv = -p_iv (log p_iv + entropy_i), so
+    dz_iv = g_i (1[v = y_i] - p_iv) + (entropy_coef / n_scored) p_iv (log p_iv + entropy_i);
+    dH and dW follow as in lm_head_backward.  Returns (dH, dW) in float64.
+    """
+    n, d = H.shape
+    V = W.shape[0]
+    rows = np.arange(n) if rowsel is None else np.asarray(rowsel, dtype=np.int64)
+    W64 = np.asarray(W, dtype=np.float64)
+    dH, dW = np.zeros((n, d)), np.zeros((V, d))
+    for c0 in range(0, len(rows), chunk):
+        rr = rows[c0:c0 + chunk]
+        Hc = np.asarray(H[rr], dtype=np.float64)
+        z = Hc @ W64.T
+        logp_all = z - np.asarray(lse, np.float64)[rr][:, None]
+        p = np.exp(logp_all)
+        dz = -p * np.asarray(g, np.float64)[rr][:, None]
+        dz[np.arange(len(rr)), np.asarray(ids)[rr]] += np.asarray(g, np.float64)[rr]
+        dz += (entropy_coef / n_scored) * p * (logp_all + np.asarray(entropy, np.float64)[rr][:, None])
         dH[rr] = dz @ W64
         dW += dz.T @ Hc
     return dH, dW

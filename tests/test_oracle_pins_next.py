@@ -1,0 +1,194 @@
+"""Pins of the oracle's critic, KL-penalty, whitening and surrogate-variant functions: hand-worked
+examples, closed forms, invariants and finite differences (none of them retypes the oracle's formula)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import umas_oracle as orc
+
+
+# ------------------------------------------------------------------ critic
+def test_value_head_brute_force_and_selection():
+    rng = np.random.default_rng(3)
+    H = rng.normal(size=(5, 4))
+    w = rng.normal(size=4)
+    V = orc.value_head(H, w, 0.25, np.array([0, 2, 4]))
+    for i in range(5):
+        want = sum(H[i, j] * w[j] for j in range(4)) + 0.25 if i in (0, 2, 4) else 0.0
+        assert abs(V[i] - want) < 1e-14
+
+
+def test_value_loss_worked_example():
+    # row 0: V moved 0.2 from V_old, clip 0.1 -> Vc = 0.9; (1-1.5)^2 = .25 < (0.9-1.5)^2 = .36: clipped, L = .18, g = 0
+    # row 1: Vc = 2.5 - 0.1 = 2.4; (2-2)^2 = 0 < .16: clipped, L = .08, g = 0
+    # row 2: V = V_old: tie, unclipped, L = .125, g = (0.5-1)/3
+    V, Vo, R = np.array([1.0, 2.0, 0.5]), np.array([0.8, 2.5, 0.5]), np.array([1.5, 2.0, 1.0])
+    stats, g = orc.value_loss(V, Vo, R, None, np.array([0, 1, 0]), 2, 0.1)
+    assert abs(stats[0, 0] - (0.18 + 0.08 + 0.125) / 3) < 1e-15
+    assert abs(stats[0, 1] - 2 / 3) < 1e-15 and abs(stats[0, 2] - 3.5 / 3) < 1e-15 and stats[0, 3] == 3
+    assert np.allclose(g, [0.0, 0.0, -0.5 / 3], atol=1e-16)
+    # per role: role 0 holds rows 0 and 2, role 1 row 1
+    assert abs(stats[1, 0] - (0.18 + 0.125) / 2) < 1e-15 and stats[1, 3] == 2
+    assert abs(stats[2, 0] - 0.08) < 1e-15 and stats[2, 1] == 1.0
+
+
+def test_value_loss_without_movement_is_half_mse_and_rowsel():
+    rng = np.random.default_rng(5)
+    V, R = rng.normal(size=8), rng.normal(size=8)
+    rows = np.array([1, 2, 5, 7])
+    stats, g = orc.value_loss(V, V.copy(), R, rows, np.zeros(8, np.int32), 1, 0.2)
+    assert abs(stats[0, 0] - 0.5 * np.mean((V[rows] - R[rows]) ** 2)) < 1e-15
+    assert stats[0, 1] == 0.0
+    want = np.zeros(8)
+    want[rows] = (V[rows] - R[rows]) / 4
+    assert np.allclose(g, want, atol=1e-16)
+    # a huge clip range never clips either
+    stats2, g2 = orc.value_loss(V, V + rng.normal(size=8), R, rows, np.zeros(8, np.int32), 1, 1e9)
+    assert abs(stats2[0, 0] - stats[0, 0]) < 1e-15 and np.allclose(g2, g)
+
+
+def critic_scalar(H, w, b, Vo, R, rows, eps):
+    V = orc.value_head(H, w, b, rows)
+    return orc.value_loss(V, Vo, R, rows, np.zeros(len(V), np.int32), 1, eps)[0][0, 0]
+
+
+def test_critic_backward_matches_finite_differences():
+    rng = np.random.default_rng(11)
+    n, d = 7, 5
+    H, w, b = rng.normal(size=(n, d)), rng.normal(size=d), 0.1
+    rows = np.array([0, 1, 3, 4, 6])
+    V = orc.value_head(H, w, b, rows)
+    Vo = V + rng.normal(size=n) * 0.3
+    R = rng.normal(size=n)
+    stats, g = orc.value_loss(V, Vo, R, rows, np.zeros(n, np.int32), 1, 0.2)
+    assert 0 < stats[0, 1] < 1                       # both branches occur
+    dH, dw, db = orc.value_head_backward(H, w, g, rows)
+    h = 1e-6
+    for j in range(d):
+        keep = w[j]
+        w[j] = keep + h; fp = critic_scalar(H, w, b, Vo, R, rows, 0.2)
+        w[j] = keep - h; fm = critic_scalar(H, w, b, Vo, R, rows, 0.2)
+        w[j] = keep
+        assert abs((fp - fm) / (2 * h) - dw[j]) < 1e-8
+    for idx in [(0, 0), (1, 2), (2, 1), (4, 4), (6, 3)]:
+        keep = H[idx]
+        H[idx] = keep + h; fp = critic_scalar(H, w, b, Vo, R, rows, 0.2)
+        H[idx] = keep - h; fm = critic_scalar(H, w, b, Vo, R, rows, 0.2)
+        H[idx] = keep
+        assert abs((fp - fm) / (2 * h) - dH[idx]) < 1e-8
+    fp = critic_scalar(H, w, b + h, Vo, R, rows, 0.2)
+    fm = critic_scalar(H, w, b - h, Vo, R, rows, 0.2)
+    assert abs((fp - fm) / (2 * h) - db) < 1e-8
+    assert not dH[2].any() and not dH[5].any()      # unselected rows
+
+
+# ------------------------------------------------------------------ KL-penalised rewards
+def test_kl_rewards_by_hand_and_identities():
+    r = np.array([0.0, 1.0, 0.0, 0.5], np.float32)
+    lp, ref = np.array([-1.0, -2.0, -3.0, -0.5]), np.array([-1.5, -1.0, -3.0, -9.0])
+    mask = np.array([1, 1, 1, 0], np.uint8)
+    out, kl = orc.kl_penalised_rewards(r, lp, ref, mask, 0.1)
+    assert np.allclose(out, [0.0 - 0.1 * 0.5, 1.0 - 0.1 * (-1.0), 0.0, 0.5], atol=1e-15)
+    assert abs(kl - (0.5 - 1.0 + 0.0) / 3) < 1e-15
+    assert np.array_equal(orc.kl_penalised_rewards(r, lp, ref, mask, 0.0)[0], r.astype(np.float64))
+    assert np.array_equal(orc.kl_penalised_rewards(r, lp, lp, mask, 0.7)[0], r.astype(np.float64))
+    assert orc.kl_penalised_rewards(r, lp, ref, np.zeros(4, np.uint8), 0.7)[1] == 0.0
+
+
+# ------------------------------------------------------------------ whitening
+def test_whitening_moments_invariance_and_scopes():
+    rng = np.random.default_rng(17)
+    n = 400
+    mask = (rng.random(n) < 0.7).astype(np.uint8)
+    role = rng.integers(0, 3, size=n).astype(np.int32)
+    off = np.array([0, 250, 400])
+    A = rng.normal(size=n) * 3 + 1 + role            # every role has its own level
+    A[mask == 0] = 0
+    Wm = orc.whiten_advantages(A, mask, role, off, 3, orc.WHITEN_MODEL)
+    for k in range(2):
+        sel = np.arange(off[k], off[k + 1])[mask[off[k]:off[k + 1]] == 1]
+        assert abs(Wm[sel].mean()) < 1e-12 and abs(Wm[sel].std() - 1) < 1e-6
+        # second opinion: numpy's own mean/std on the group
+        assert np.allclose(Wm[sel], (A[sel] - A[sel].mean()) / np.sqrt(A[sel].var() + 1e-8), atol=1e-12)
+    assert not Wm[mask == 0].any()
+    # positive affine maps of the advantages change nothing (up to the eps in the denominator)
+    assert np.allclose(orc.whiten_advantages(np.where(mask, 5 * A - 2, 0), mask, role, off, 3, orc.WHITEN_MODEL), Wm, atol=1e-7)
+    Wr = orc.whiten_advantages(A, mask, role, off, 3, orc.WHITEN_MODEL_ROLE)
+    for k in range(2):
+        for v in range(3):
+            sel = np.arange(off[k], off[k + 1])
+            sel = sel[(mask[sel] == 1) & (role[sel] == v)]
+            assert abs(Wr[sel].mean()) < 1e-12 and abs(Wr[sel].std() - 1) < 1e-6
+    assert np.abs(Wr - Wm).max() > 0.1                # the scopes differ on this input
+    # one-role input: both scopes agree; an empty group is left alone
+    assert np.array_equal(orc.whiten_advantages(A, mask, np.zeros(n, np.int32), off, 3, orc.WHITEN_MODEL_ROLE),
+                          orc.whiten_advantages(A, mask, np.zeros(n, np.int32), off, 3, orc.WHITEN_MODEL))
+    assert not orc.whiten_advantages(A, np.zeros(n, np.uint8), role, off, 3, orc.WHITEN_MODEL).any()
+
+
+# ------------------------------------------------------------------ surrogate variants
+def test_variants_reduce_to_the_plain_surrogate():
+    rng = np.random.default_rng(19)
+    n = 50
+    lp, lo = -rng.random(n) * 3, -rng.random(n) * 3
+    A, ent = rng.normal(size=n), rng.random(n)
+    rows = np.sort(rng.choice(n, 37, replace=False))
+    role = rng.integers(0, 2, size=n)
+    s0, g0 = orc.ppo_loss(lp, lo, A, ent, rows, role, 2, 0.2)
+    s1, g1 = orc.ppo_loss_variants(lp, lo, A, ent, rows, role, 2, 0.2)
+    assert np.array_equal(s0, s1) and np.array_equal(g0, g1)
+    # a dual-clip constant so large that it never binds changes nothing either
+    s2, g2 = orc.ppo_loss_variants(lp, lo, A, ent, rows, role, 2, 0.2, dual_clip=1e9)
+    assert np.array_equal(s0, s2) and np.array_equal(g0, g2)
+
+
+def test_dual_clip_by_hand():
+    # A = -1: ratio 5 -> max(5, 1.2) = 5, capped at 3, no gradient; ratio 2 -> 2 < 3, gradient -A ratio / S
+    # A = +1: ratio 5 -> max(-5, -1.2) = -1.2 (clipped), never capped
+    lo = np.zeros(3)
+    lp = np.log(np.array([5.0, 2.0, 5.0]))
+    A = np.array([-1.0, -1.0, 1.0])
+    stats, g = orc.ppo_loss_variants(lp, lo, A, np.zeros(3), None, np.zeros(3, np.int32), 1, 0.2, dual_clip=3.0)
+    assert abs(stats[0, 0] - (3.0 + 2.0 - 1.2) / 3) < 1e-14
+    assert np.allclose(g, [0.0, 2.0 / 3, 0.0], atol=1e-15)
+    assert abs(stats[0, 1] - 2 / 3) < 1e-15
+
+
+def total_loss(H, W, ids, logp_old, A, rows, eps, c_ent):
+    logp, lse, ent = orc.score(H, W, ids, rows)
+    return orc.ppo_loss_variants(logp, logp_old, A, ent, rows, np.zeros(len(ids), np.int32), 1, eps, 0.0, c_ent)[0][0, 0]
+
+
+def test_entropy_bonus_backward_matches_finite_differences():
+    rng = np.random.default_rng(29)
+    n, d, V = 8, 5, 11
+    H, W = rng.normal(size=(n, d)), rng.normal(size=(V, d)) * 0.6
+    ids = rng.integers(0, V, size=n).astype(np.int32)
+    rows = np.array([0, 1, 2, 4, 6, 7], np.int32)
+    logp, lse, ent = orc.score(H, W, ids, rows)
+    logp_old = logp + rng.normal(size=n) * 0.3
+    A = rng.normal(size=n)
+    c_ent = 0.05
+    stats, g = orc.ppo_loss_variants(logp, logp_old, A, ent, rows, np.zeros(n, np.int32), 1, 0.2, 0.0, c_ent)
+    plain, _ = orc.ppo_loss(logp, logp_old, A, ent, rows, np.zeros(n, np.int32), 1, 0.2)
+    assert abs(stats[0, 0] - (plain[0, 0] - c_ent * plain[0, 2])) < 1e-15
+    dH, dW = orc.lm_head_backward_entropy(H, W, ids, lse, ent, g, c_ent, len(rows), rows)
+    h = 1e-6
+    for (arr, grad) in ((H, dH), (W, dW)):
+        for idx in [(0, 0), (1, 3), (2, 4), (4, 1), (7, 2), (6, 0), (5, 1)]:
+            keep = arr[idx]
+            arr[idx] = keep + h; fp = total_loss(H, W, ids, logp_old, A, rows, 0.2, c_ent)
+            arr[idx] = keep - h; fm = total_loss(H, W, ids, logp_old, A, rows, 0.2, c_ent)
+            arr[idx] = keep
+            assert abs((fp - fm) / (2 * h) - grad[idx]) < 1e-8
+    # with coefficient 0 it is the plain backward
+    dH0, dW0 = orc.lm_head_backward_entropy(H, W, ids, lse, ent, g, 0.0, len(rows), rows)
+    dH1, dW1 = orc.lm_head_backward(H, W, ids, lse, g, rows)
+    assert np.allclose(dH0, dH1, atol=1e-15) and np.allclose(dW0, dW1, atol=1e-15)
+    # W = 0: uniform softmax, entropy log V is a maximum, so the entropy term has no gradient
+    Wz = np.zeros((V, d))
+    lz, lsez, entz = orc.score(H, Wz, ids, rows)
+    assert np.allclose(entz[rows], math.log(V))
+    dHz, dWz = orc.lm_head_backward_entropy(H, Wz, ids, lsez, entz, np.zeros(n), c_ent, len(rows), rows)
+    assert np.abs(dHz).max() < 1e-15 and np.abs(dWz).max() < 1e-15
