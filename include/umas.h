@@ -201,6 +201,49 @@ umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_dtype dtype
                                   float* logp_new, void* dH, float* dW,
                                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Critic.  The worker groups compute "value estimates" next to the log-probs and update "actor and
+ * critic parameters" from the ready batch (Section "PPO-Style Training Loop", paragraphs "Advantage
+ * computation and policy evaluation" and "Model-specific updates and synchronization").  The paper
+ * prints no value loss; the clipped form that goes with PPO is taken:
+ *   V_i = w . h_i + bias
+ *   Vc = clip(V, V_old - eps, V_old + eps);  L = 1/2 max((V - R)^2, (Vc - R)^2);  loss = mean L
+ *   g = dloss/dV = (V - R) / n_sel where the unclipped term is the larger one (ties included), else 0
+ *   dH_i = g_i w;  dw = sum_i g_i h_i;  db = sum_i g_i
+ * H [n_rows, d] and w [d] are DEVICE arrays of `dtype`, 16-byte aligned; d is a multiple of 8 (bf16) or
+ * 4 (float32) and at most 8192; rowsel / n_sel select rows as in umas_policy_logprobs. */
+typedef struct umas_value_stats {
+  float loss;         /* mean over the rows of 1/2 max((V-R)^2, (Vc-R)^2) */
+  float clip_frac;    /* rows whose clipped term is strictly larger */
+  float value_mean;   /* mean V */
+  float reserved;
+  int64_t n_scored;   /* rows in the means */
+} umas_value_stats;
+
+/* value DEVICE float [n_rows]: V on the selected rows, 0 elsewhere.  Needs no workspace. */
+umas_status umas_values(const void* H, const void* w, float bias, umas_dtype dtype, int64_t n_rows, int32_t d,
+                        const int32_t* rowsel, int64_t n_sel, float* value, void* hip_stream);
+
+size_t umas_value_workspace_bytes(int64_t n_sel, int32_t d, umas_dtype dtype, int32_t n_roles);
+
+/* One pass over the selected rows of H: value head, clipped value loss, backward.
+ *   value_old, ret  DEVICE float [n_rows] (the returns are umas_advantages' `ret`)
+ *   tok_role        DEVICE int32 [n_rows] or NULL with n_roles = 0
+ *   stats           DEVICE umas_value_stats [1 + n_roles]: the model, then each role
+ *   value_new       DEVICE float [n_rows] or NULL
+ *   dH              DEVICE [n_rows, d] in the dtype of H; accumulate_dH = 0 writes g_i w on the selected rows
+ *                   and 0 elsewhere, 1 adds g_i w to the selected rows and leaves the others alone (a trunk
+ *                   shared with the policy head)
+ *   dw, db          DEVICE float [d], [1] (db may be NULL); accumulate_dw = 0 overwrites, 1 adds
+ * clip_eps_v must be positive.  The result does not depend on scheduling: partial sums are reduced in a
+ * fixed order. */
+umas_status umas_value_loss_fwd_bwd(const void* H, const void* w, float bias, umas_dtype dtype, int64_t n_rows,
+                                    int32_t d, const int32_t* rowsel, int64_t n_sel, const float* value_old,
+                                    const float* ret, const int32_t* tok_role, int32_t n_roles, float clip_eps_v,
+                                    int32_t accumulate_dH, int32_t accumulate_dw, umas_value_stats* stats,
+                                    float* value_new, void* dH, float* dw, float* db, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream);
+
 /* Kernel timing aid for benchmarks (not part of the method).  While enabled, every kernel launch
  * of the library is followed by a HIP event on its stream and the time between consecutive events
  * of one call is booked to the kernel launched in between.  umas_profile_enable(on) discards earlier

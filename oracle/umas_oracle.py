@@ -336,7 +336,7 @@ def value_head(H, w, b=0.0, rowsel=None):
 def value_loss(V, V_old, ret, rowsel, tok_role, n_roles, clip_eps_v):
     """Clipped value loss over the selected rows.
 
-    Vc = V_old + clip(V - V_old, -eps, +eps); L = 1/2 max((V - R)^2, (Vc - R)^2);
+    Vc = clip(V, V_old - eps, V_old + eps) (V itself inside the range); L = 1/2 max((V - R)^2, (Vc - R)^2);
     loss = sum L / S.  g = d loss / d V = (V - R) / S where the unclipped term is the
     larger one (ties included), 0 where the clipped term is strictly larger (Vc is then
     a constant).  Statistics per model and per role, float64 [1+n_roles, 4] =
@@ -352,7 +352,7 @@ def value_loss(V, V_old, ret, rowsel, tok_role, n_roles, clip_eps_v):
     v = np.asarray(V, np.float64)[rows]
     vo = np.asarray(V_old, np.float64)[rows]
     R = np.asarray(ret, np.float64)[rows]
-    vc = vo + np.minimum(np.maximum(v - vo, -clip_eps_v), clip_eps_v)
+    vc = np.minimum(np.maximum(v, vo - clip_eps_v), vo + clip_eps_v)
     lu = (v - R) ** 2
     lc = (vc - R) ** 2
     unclipped = lu >= lc

@@ -285,6 +285,61 @@ def umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv, tok_role, n_roles, c
     return stats, logp_new, dH, dW
 
 
+VALUE_STATS_DTYPE = np.dtype([("loss", "<f4"), ("clip_frac", "<f4"), ("value_mean", "<f4"), ("reserved", "<f4"),
+                              ("n_scored", "<i8")])
+
+
+def umas_values(H, w, bias=0.0, rowsel=None, value=None):
+    lib = load_library()
+    lib.umas_values.restype = C.c_int
+    lib.umas_values.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_int, C.c_int64, C.c_int32, C.c_void_p, C.c_int64,
+                                C.c_void_p, C.c_void_p]
+    n_rows, d = H.shape
+    n_sel = n_rows if rowsel is None else int(rowsel.numel())
+    if value is None:
+        value = torch.empty(n_rows, dtype=torch.float32, device=H.device)
+    _keep, sel = _sel_ptr(rowsel)
+    _check(lib, lib.umas_values(_ptr(H), w.data_ptr(), bias, _dtype_code(H), n_rows, d, sel, n_sel, _ptr(value), _stream()))
+    return value
+
+
+def umas_value_loss_fwd_bwd(H, w, bias, rowsel, value_old, ret, tok_role, n_roles, clip_eps_v, *, accumulate_dH=False,
+                            accumulate_dw=False, dH=None, dw=None, db=None, value_new=None, stats=None, workspace=None):
+    lib = load_library()
+    lib.umas_value_workspace_bytes.restype = C.c_size_t
+    lib.umas_value_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int, C.c_int32]
+    lib.umas_value_loss_fwd_bwd.restype = C.c_int
+    lib.umas_value_loss_fwd_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_int, C.c_int64, C.c_int32, C.c_void_p,
+                                            C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_int32,
+                                            C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_size_t, C.c_void_p]
+    n_rows, d = H.shape
+    n_sel = n_rows if rowsel is None else int(rowsel.numel())
+    dt = _dtype_code(H)
+    dev = H.device
+    if dH is None:
+        dH = torch.empty_like(H)
+    if dw is None:
+        dw = torch.empty(d, dtype=torch.float32, device=dev)
+    if db is None:
+        db = torch.empty(1, dtype=torch.float32, device=dev)
+    if value_new is None:
+        value_new = torch.empty(n_rows, dtype=torch.float32, device=dev)
+    if stats is None:
+        stats = torch.empty((1 + n_roles) * VALUE_STATS_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+    ws = workspace if workspace is not None else _workspace(lib.umas_value_workspace_bytes(n_sel, d, dt, n_roles), dev)
+    _keep, sel = _sel_ptr(rowsel)
+    _check(lib, lib.umas_value_loss_fwd_bwd(_ptr(H), w.data_ptr(), bias, dt, n_rows, d, sel, n_sel, _ptr(value_old),
+                                            _ptr(ret), _ptr(tok_role), n_roles, clip_eps_v, 1 if accumulate_dH else 0,
+                                            1 if accumulate_dw else 0, stats.data_ptr(), _ptr(value_new), _ptr(dH),
+                                            dw.data_ptr(), db.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+    return stats, value_new, dH, dw, db
+
+
+def read_value_stats(stats: torch.Tensor) -> np.ndarray:
+    return stats.cpu().numpy().view(VALUE_STATS_DTYPE)
+
+
 def read_stats(stats: torch.Tensor) -> np.ndarray:
     """Copy the device umas_loss_stats array to a numpy structured array (synchronises)."""
     return stats.cpu().numpy().view(STATS_DTYPE)

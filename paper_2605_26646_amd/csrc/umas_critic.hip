@@ -1,0 +1,350 @@
+// Critic: value head V = w . h + b on the selected rows, clipped value loss and its backward.
+//
+// The worker groups of Section "PPO-Style Training Loop" compute value estimates next to the
+// log-probs and update "actor and critic" from the ready batch.  The paper prints no value loss; the
+// clipped form used with PPO is taken:
+//   Vc = clip(V, V_old - eps, V_old + eps);  L = 1/2 max((V - R)^2, (Vc - R)^2);  loss = mean L
+//   g = dloss/dV = (V - R) / S where the unclipped term is the larger one (ties included), else 0
+//   dH_i = g_i w,  dw = sum_i g_i h_i,  db = sum_i g_i
+// The whole step is one pass over H: a workgroup stages a chunk of rows in LDS, one wavefront per row
+// forms the dot product and the row's g, then every thread walks its own columns over the chunk's
+// rows (dH written, dw accumulated in registers).  Per-workgroup partial sums are reduced by a second
+// small kernel in a fixed order, so results do not depend on scheduling.
+#include "umas_common.h"
+
+namespace umas {
+namespace {
+
+constexpr int kVT = 256;                 // threads per workgroup
+constexpr int kVWaves = kVT / kWave;
+constexpr int kMaxChunkRows = 16;
+constexpr int kChunkBytes = 64 * 1024;   // rows staged per chunk
+constexpr int kMaxD = 8192;              // 32 accumulators per thread cover d <= 8192
+constexpr int kMaxGrid = 1024;
+constexpr int kVStat = 4;                // (sum L, clipped rows, sum V, rows)
+
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+__device__ __forceinline__ uint16_t f2bf(float x) { return __builtin_bit_cast(uint16_t, static_cast<__bf16>(x)); }
+
+// 16 bytes of a row as floats: 8 bf16 or 4 float
+template <typename T> struct Vec;
+template <> struct Vec<uint16_t> {
+  static constexpr int N = 8;
+  __device__ static void load(const uint16_t* p, float (&x)[8]) {
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[2 * i] = __uint_as_float(w[i] << 16);
+      x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+    }
+  }
+  __device__ static void store(uint16_t* p, const float (&x)[8]) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = static_cast<uint32_t>(f2bf(x[2 * i])) | (static_cast<uint32_t>(f2bf(x[2 * i + 1])) << 16);
+    *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+template <> struct Vec<float> {
+  static constexpr int N = 4;
+  __device__ static void load(const float* p, float (&x)[4]) {
+    const float4 v = *reinterpret_cast<const float4*>(p);
+    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+  }
+  __device__ static void store(float* p, const float (&x)[4]) { *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]); }
+};
+
+__global__ void k_zero_u32(uint32_t* __restrict__ p, int64_t n) {
+  int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  for (; i < n; i += stride) p[i] = 0u;
+}
+
+// Forward only: one wavefront per selected row.
+template <typename T>
+__global__ void __launch_bounds__(kVT)
+k_value_fwd(const T* __restrict__ H, const T* __restrict__ w, float bias, int d, const int32_t* __restrict__ rowsel,
+            int64_t n_sel, float* __restrict__ value) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t n = static_cast<int64_t>(blockIdx.x) * kVWaves + threadIdx.x / kWave;
+  if (n >= n_sel) return;
+  const int64_t row = rowsel ? rowsel[n] : n;
+  const T* h = H + row * d;
+  float acc = 0.f;
+  for (int c = lane * Vec<T>::N; c < d; c += kWave * Vec<T>::N) {
+    float x[Vec<T>::N], y[Vec<T>::N];
+    Vec<T>::load(h + c, x);
+    Vec<T>::load(w + c, y);
+#pragma unroll
+    for (int i = 0; i < Vec<T>::N; ++i) acc = fmaf(x[i], y[i], acc);
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) value[row] = acc + bias;
+}
+
+// Loss and backward.  LDS (dynamic): rows [rc][d] in T, w as float [d], g [rc], statistics.
+template <typename T>
+__global__ void __launch_bounds__(kVT)
+k_value_rows(const T* __restrict__ H, const T* __restrict__ w, float bias, int d, const int32_t* __restrict__ rowsel,
+             int64_t n_sel, int rc, const float* __restrict__ value_old, const float* __restrict__ ret,
+             const int32_t* __restrict__ tok_role, int n_roles, float clip_eps, float* __restrict__ value_new,
+             T* __restrict__ dH, int accumulate_dH, float* __restrict__ part_dw, double* __restrict__ blk_stats) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char s_raw[];
+  constexpr int N = Vec<T>::N;
+  const int nvec = d / N;                       // 16-byte vectors per row
+  T* s_rows = reinterpret_cast<T*>(s_raw);
+  float* s_w = reinterpret_cast<float*>(s_raw + static_cast<size_t>(rc) * d * sizeof(T));
+  float* s_g = s_w + d;
+  double* s_acc = reinterpret_cast<double*>(s_g + kMaxChunkRows);
+  const int nacc = (1 + n_roles) * kVStat;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  for (int i = threadIdx.x; i < nacc; i += kVT) s_acc[i] = 0.0;
+  for (int v = threadIdx.x; v < nvec; v += kVT) {
+    float x[N];
+    Vec<T>::load(w + v * N, x);
+#pragma unroll
+    for (int i = 0; i < N; ++i) s_w[v * N + i] = x[i];
+  }
+  constexpr int kAcc = kMaxD / (kVT * N);       // column vectors per thread
+  float acc[kAcc][N];
+#pragma unroll
+  for (int k = 0; k < kAcc; ++k)
+#pragma unroll
+    for (int i = 0; i < N; ++i) acc[k][i] = 0.f;
+  float gsum = 0.f;
+  const float inv_s = 1.f / static_cast<float>(n_sel);
+
+  const int64_t n_chunks = (n_sel + rc - 1) / rc;
+  for (int64_t ch = blockIdx.x; ch < n_chunks; ch += gridDim.x) {
+    const int64_t c0 = ch * rc;
+    const int rows = n_sel - c0 < rc ? static_cast<int>(n_sel - c0) : rc;
+    __syncthreads();                            // the previous chunk's readers are done (and s_w, s_acc are set)
+    for (int v = threadIdx.x; v < rows * nvec; v += kVT) {
+      const int r = v / nvec, cv = v - r * nvec;
+      const int64_t row = rowsel ? rowsel[c0 + r] : c0 + r;
+      *reinterpret_cast<uint4*>(s_rows + static_cast<size_t>(r) * d + cv * N) =
+          *reinterpret_cast<const uint4*>(H + row * d + cv * N);
+    }
+    __syncthreads();
+    for (int r = wave; r < rows; r += kVWaves) {
+      float dot = 0.f;
+      for (int cv = lane; cv < nvec; cv += kWave) {
+        float x[N];
+        Vec<T>::load(s_rows + static_cast<size_t>(r) * d + cv * N, x);
+#pragma unroll
+        for (int i = 0; i < N; ++i) dot = fmaf(x[i], s_w[cv * N + i], dot);
+      }
+      dot = wave_sum(dot);
+      if (lane == 0) {
+        const int64_t row = rowsel ? rowsel[c0 + r] : c0 + r;
+        const float V = dot + bias, vo = value_old[row], R = ret[row];
+        const float vc = fminf(fmaxf(V, vo - clip_eps), vo + clip_eps);   // V itself inside the range: an exact tie
+        const float lu = (V - R) * (V - R), lc = (vc - R) * (vc - R);
+        const bool unclipped = lu >= lc;
+        s_g[r] = unclipped ? (V - R) * inv_s : 0.f;
+        if (value_new) value_new[row] = V;
+        const int role = (tok_role && n_roles > 0) ? tok_role[row] : -1;
+        for (int pass = 0; pass < 2; ++pass) {
+          if (pass == 1 && (role < 0 || role >= n_roles)) break;
+          double* a = s_acc + (pass == 0 ? 0 : (1 + role) * kVStat);
+          atomicAdd(a + 0, static_cast<double>(0.5f * (unclipped ? lu : lc)));
+          atomicAdd(a + 1, unclipped ? 0.0 : 1.0);
+          atomicAdd(a + 2, static_cast<double>(V));
+          atomicAdd(a + 3, 1.0);
+        }
+      }
+    }
+    __syncthreads();
+    for (int r = 0; r < rows; ++r) {
+      const float g = s_g[r];
+      const int64_t row = rowsel ? rowsel[c0 + r] : c0 + r;
+      gsum += g;
+#pragma unroll
+      for (int k = 0; k < kAcc; ++k) {
+        const int cv = threadIdx.x + k * kVT;
+        if (cv < nvec) {
+          float x[N], o[N];
+          Vec<T>::load(s_rows + static_cast<size_t>(r) * d + cv * N, x);
+          if (accumulate_dH) Vec<T>::load(dH + row * d + cv * N, o);
+#pragma unroll
+          for (int i = 0; i < N; ++i) {
+            acc[k][i] = fmaf(g, x[i], acc[k][i]);
+            o[i] = accumulate_dH ? o[i] + g * s_w[cv * N + i] : g * s_w[cv * N + i];
+          }
+          Vec<T>::store(dH + row * d + cv * N, o);
+        }
+      }
+    }
+  }
+  float* pd = part_dw + static_cast<size_t>(blockIdx.x) * (d + 1);
+#pragma unroll
+  for (int k = 0; k < kAcc; ++k) {
+    const int cv = threadIdx.x + k * kVT;
+    if (cv < nvec)
+#pragma unroll
+      for (int i = 0; i < N; ++i) pd[cv * N + i] = acc[k][i];
+  }
+  if (threadIdx.x == 0) pd[d] = gsum;
+  __syncthreads();
+  for (int i = threadIdx.x; i < nacc; i += kVT) blk_stats[static_cast<size_t>(blockIdx.x) * nacc + i] = s_acc[i];
+}
+
+// dw[j] (+)= sum_b part[b][j] for j < d, db likewise from column d; the statistics from the block sums.
+__global__ void __launch_bounds__(256)
+k_value_reduce(const float* __restrict__ part_dw, int nblk, int d, int accumulate, float* __restrict__ dw, float* __restrict__ db) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j > d) return;
+  float s = 0.f;
+  for (int b = 0; b < nblk; ++b) s += part_dw[static_cast<size_t>(b) * (d + 1) + j];
+  float* dst = j < d ? dw + j : db;
+  if (dst) *dst = accumulate ? *dst + s : s;
+}
+__global__ void __launch_bounds__(256)
+k_value_stats(int nblk, int n_roles, const double* __restrict__ blk_stats, umas_value_stats* __restrict__ stats) {
+  __shared__ double smem[32];
+  const int nacc = (1 + n_roles) * kVStat;
+  for (int k = 0; k <= n_roles; ++k) {
+    double sum[kVStat];
+    for (int j = 0; j < kVStat; ++j) {
+      double v = 0.0;
+      for (int b = threadIdx.x; b < nblk; b += blockDim.x) v += blk_stats[static_cast<size_t>(b) * nacc + k * kVStat + j];
+      sum[j] = block_sum<double>(v, smem);
+    }
+    if (threadIdx.x == 0) {
+      const double cnt = sum[3];
+      umas_value_stats s;
+      s.loss = cnt > 0 ? static_cast<float>(sum[0] / cnt) : 0.f;
+      s.clip_frac = cnt > 0 ? static_cast<float>(sum[1] / cnt) : 0.f;
+      s.value_mean = cnt > 0 ? static_cast<float>(sum[2] / cnt) : 0.f;
+      s.reserved = 0.f;
+      s.n_scored = static_cast<int64_t>(cnt);
+      stats[k] = s;
+    }
+  }
+}
+
+int chunk_rows(int d, size_t esz) {
+  const int rc = static_cast<int>(kChunkBytes / (static_cast<size_t>(d) * esz));
+  return rc < 1 ? 1 : rc > kMaxChunkRows ? kMaxChunkRows : rc;
+}
+unsigned value_grid(int64_t n_sel, int rc) {
+  const int64_t n_chunks = (n_sel + rc - 1) / rc;
+  return static_cast<unsigned>(n_chunks < 1 ? 1 : n_chunks > kMaxGrid ? kMaxGrid : n_chunks);
+}
+
+umas_status check_value_args(const void* H, const void* w, umas_dtype dt, int64_t n_rows, int d, const int32_t* rowsel,
+                             int64_t n_sel) {
+  UMAS_REQUIRE(dt == UMAS_F32 || dt == UMAS_BF16, UMAS_EDTYPE, "dtype=%d is neither F32 nor BF16", static_cast<int>(dt));
+  UMAS_REQUIRE(n_rows >= 0 && n_sel >= 0 && n_sel <= n_rows, UMAS_EINVAL, "row counts must satisfy 0 <= n_sel <= n_rows");
+  UMAS_REQUIRE(rowsel || n_sel == n_rows, UMAS_EINVAL, "rowsel is NULL but n_sel != n_rows");
+  const int n = dt == UMAS_BF16 ? 8 : 4;
+  UMAS_REQUIRE(d >= n && d % n == 0 && d <= kMaxD, UMAS_ESHAPE, "d=%d must be a multiple of %d and at most %d", d, n, kMaxD);
+  UMAS_REQUIRE((H || n_rows == 0) && w, UMAS_EINVAL, "H and w must not be NULL");
+  UMAS_REQUIRE(reinterpret_cast<uintptr_t>(H) % 16 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0, UMAS_EINVAL,
+               "H and w must be 16-byte aligned");
+  return UMAS_OK;
+}
+
+}  // namespace
+}  // namespace umas
+
+using namespace umas;
+
+extern "C" size_t umas_value_workspace_bytes(int64_t n_sel, int32_t d, umas_dtype dtype, int32_t n_roles) {
+  if (n_sel < 0 || d < 1 || n_roles < 0) return 0;
+  const unsigned grid = value_grid(n_sel, chunk_rows(d, dtype == UMAS_BF16 ? 2 : 4));
+  Carver c(nullptr);
+  c.take<float>(static_cast<size_t>(grid) * (d + 1));
+  c.take<double>(static_cast<size_t>(grid) * (1 + n_roles) * kVStat);
+  return c.off;
+}
+
+extern "C" umas_status umas_values(const void* H, const void* w, float bias, umas_dtype dtype, int64_t n_rows, int32_t d,
+                                   const int32_t* rowsel, int64_t n_sel, float* value, void* hip_stream) {
+  umas_status s = check_value_args(H, w, dtype, n_rows, d, rowsel, n_sel);
+  if (s != UMAS_OK) return s;
+  UMAS_REQUIRE(value || n_rows == 0, UMAS_EINVAL, "value must not be NULL");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  prof_mark(st);
+  if (rowsel && n_rows > 0) {
+    hipLaunchKernelGGL(k_zero_u32, dim3(cdiv(n_rows, 1024) < 4096 ? cdiv(n_rows, 1024) : 4096), dim3(256), 0, st,
+                       reinterpret_cast<uint32_t*>(value), n_rows);
+    UMAS_LAUNCHED("k_zero_u32");
+  }
+  if (n_sel == 0) return UMAS_OK;
+  if (dtype == UMAS_BF16)
+    hipLaunchKernelGGL(k_value_fwd<uint16_t>, dim3(cdiv(n_sel, kVWaves)), dim3(kVT), 0, st, static_cast<const uint16_t*>(H),
+                       static_cast<const uint16_t*>(w), bias, d, rowsel, n_sel, value);
+  else
+    hipLaunchKernelGGL(k_value_fwd<float>, dim3(cdiv(n_sel, kVWaves)), dim3(kVT), 0, st, static_cast<const float*>(H),
+                       static_cast<const float*>(w), bias, d, rowsel, n_sel, value);
+  UMAS_LAUNCHED("k_value_fwd");
+  return UMAS_OK;
+}
+
+extern "C" umas_status umas_value_loss_fwd_bwd(const void* H, const void* w, float bias, umas_dtype dtype, int64_t n_rows,
+                                               int32_t d, const int32_t* rowsel, int64_t n_sel, const float* value_old,
+                                               const float* ret, const int32_t* tok_role, int32_t n_roles,
+                                               float clip_eps_v, int32_t accumulate_dH, int32_t accumulate_dw,
+                                               umas_value_stats* stats, float* value_new, void* dH, float* dw, float* db,
+                                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  umas_status s = check_value_args(H, w, dtype, n_rows, d, rowsel, n_sel);
+  if (s != UMAS_OK) return s;
+  UMAS_REQUIRE(n_roles >= 0 && n_roles <= UMAS_MAX_ROLES, UMAS_ESHAPE, "n_roles=%d outside [0,%d]", n_roles, UMAS_MAX_ROLES);
+  UMAS_REQUIRE(clip_eps_v > 0.f, UMAS_EINVAL, "clip_eps_v must be positive");
+  UMAS_REQUIRE(stats && dw && (dH || n_rows == 0), UMAS_EINVAL, "stats, dw and dH must not be NULL");
+  UMAS_REQUIRE((value_old && ret) || n_sel == 0, UMAS_EINVAL, "value_old and ret must not be NULL");
+  UMAS_REQUIRE(reinterpret_cast<uintptr_t>(dH) % 16 == 0, UMAS_EINVAL, "dH must be 16-byte aligned");
+  const size_t need = umas_value_workspace_bytes(n_sel, d, dtype, n_roles);
+  UMAS_REQUIRE(workspace && reinterpret_cast<uintptr_t>(workspace) % kAlign == 0 && workspace_bytes >= need, UMAS_EWORKSPACE,
+               "workspace must be 256-byte aligned and hold %zu bytes (got %zu)", need, workspace_bytes);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  prof_mark(st);
+  const size_t esz = dtype == UMAS_BF16 ? 2 : 4;
+  const int rc = chunk_rows(d, esz);
+  const unsigned grid = value_grid(n_sel, rc);
+  Carver c(workspace);
+  float* part_dw = c.take<float>(static_cast<size_t>(grid) * (d + 1));
+  double* blk_stats = c.take<double>(static_cast<size_t>(grid) * (1 + n_roles) * kVStat);
+
+  auto zero = [&](void* p, size_t bytes) -> hipError_t {
+    const int64_t n = static_cast<int64_t>(bytes / 4);
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_zero_u32, dim3(cdiv(n, 1024) < 8192 ? cdiv(n, 1024) : 8192), dim3(256), 0, st,
+                       static_cast<uint32_t*>(p), n);
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess && g_prof_on) prof_kernel("k_zero_u32", st);
+    return e;
+  };
+  if (rowsel && n_rows > 0) {
+    if (value_new) UMAS_HIP(zero(value_new, n_rows * sizeof(float)));
+    if (!accumulate_dH) UMAS_HIP(zero(dH, static_cast<size_t>(n_rows) * d * esz));
+  }
+  // an empty selection still defines the outputs: zero partials give zero statistics and gradients
+  UMAS_HIP(zero(part_dw, static_cast<size_t>(grid) * (d + 1) * sizeof(float)));
+  UMAS_HIP(zero(blk_stats, static_cast<size_t>(grid) * (1 + n_roles) * kVStat * sizeof(double)));
+  if (n_sel > 0) {
+    const size_t lds = static_cast<size_t>(rc) * d * esz + static_cast<size_t>(d) * sizeof(float) +
+                       kMaxChunkRows * sizeof(float) + static_cast<size_t>(1 + n_roles) * kVStat * sizeof(double);
+    // more than 64 KB of dynamic LDS has to be asked for
+    const void* fn = dtype == UMAS_BF16 ? reinterpret_cast<const void*>(&k_value_rows<uint16_t>)
+                                        : reinterpret_cast<const void*>(&k_value_rows<float>);
+    UMAS_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+    if (dtype == UMAS_BF16)
+      hipLaunchKernelGGL(k_value_rows<uint16_t>, dim3(grid), dim3(kVT), lds, st, static_cast<const uint16_t*>(H),
+                         static_cast<const uint16_t*>(w), bias, d, rowsel, n_sel, rc, value_old, ret, tok_role, n_roles,
+                         clip_eps_v, value_new, static_cast<uint16_t*>(dH), accumulate_dH, part_dw, blk_stats);
+    else
+      hipLaunchKernelGGL(k_value_rows<float>, dim3(grid), dim3(kVT), lds, st, static_cast<const float*>(H),
+                         static_cast<const float*>(w), bias, d, rowsel, n_sel, rc, value_old, ret, tok_role, n_roles,
+                         clip_eps_v, value_new, static_cast<float*>(dH), accumulate_dH, part_dw, blk_stats);
+    UMAS_LAUNCHED("k_value_rows");
+  }
+  hipLaunchKernelGGL(k_value_reduce, dim3(cdiv(d + 1, 256)), dim3(256), 0, st, part_dw, static_cast<int>(grid), d,
+                     accumulate_dw, dw, db);
+  UMAS_LAUNCHED("k_value_reduce");
+  hipLaunchKernelGGL(k_value_stats, dim3(1), dim3(256), 0, st, static_cast<int>(grid), n_roles, blk_stats, stats);
+  UMAS_LAUNCHED("k_value_stats");
+  return UMAS_OK;
+}

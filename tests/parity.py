@@ -16,11 +16,12 @@ INT_FIELDS = ["model_tok_off", "perm", "tok_turn", "tok_role", "tok_mask", "turn
               "model_turn_off", "model_trajrun_off", "model_rowsel_off"]
 
 
-def close(x, o, tol, what):
+def close(x, o, tol, what, row_abs=0.0):
     """Relative error of x against the float64 reference o, all <= tol: element-wise
     |x-o| <= tol*max(|o|, rms(o)) (a purely element-wise relative error is meaningless where terms
     cancel to ~0), norm-wise over the array, and for matrices norm-wise over every row that carries
-    at least 1e-3 of the largest row norm."""
+    at least 1e-3 of the largest row norm.  row_abs is an absolute allowance per row norm, for rows
+    whose scale factor is itself a difference of nearly equal numbers."""
     x = np.asarray(x, dtype=np.float64)
     o = np.asarray(o, dtype=np.float64)
     assert x.shape == o.shape, f"{what}: shape {x.shape} vs {o.shape}"
@@ -36,7 +37,7 @@ def close(x, o, tol, what):
         row_norm = np.linalg.norm(o, axis=1)
         big = row_norm >= 1e-3 * row_norm.max(initial=0.0)
         if row_norm.max(initial=0.0) > 0:
-            row_rel = np.linalg.norm(x - o, axis=1)[big] / row_norm[big]
+            row_rel = np.maximum(np.linalg.norm(x - o, axis=1)[big] - row_abs, 0.0) / row_norm[big]
             assert row_rel.max() <= tol, f"{what}: worst row-wise error {row_rel.max():.3g} > {tol}"
     nrm = np.linalg.norm(o)
     rel = float(np.linalg.norm(x - o) / nrm) if nrm > 0 else float(np.linalg.norm(x - o))

@@ -129,6 +129,20 @@ class Workload:
         noise = (rng_n.standard_normal(n) * self.noise_std).astype(np.float32)
         return {"H": H, "W": W, "ids": ids, "noise": noise}
 
+    def critic_tensors(self, m: int) -> dict:
+        """Inputs of model m's critic and of the steps around the policy update, from streams of their own:
+        value-head weights w ~ N(0, std 0.02) in the model's dtype and a bias, noise for the old value
+        estimates N(0, 0.1), reference log-prob offsets N(0, 0.1) and a second LM head W_ref = W + N(0, 0.002)
+        is left to the caller (it only needs another seed offset)."""
+        spec = self.models[m]
+        n = self.model_ntok[m]
+        g = np.random.default_rng([self.seed, 7000 + m])
+        w = (g.standard_normal(spec.d) * 0.02).astype(np.float32)
+        if spec.dtype == "bf16":
+            w = round_to_bf16(w)
+        return {"w": w, "bias": np.float32(0.05), "v_noise": (g.standard_normal(n) * 0.1).astype(np.float32),
+                "ref_noise": (g.standard_normal(n) * 0.1).astype(np.float32)}
+
 
 def _fill_blocks(n_rows: int, n_cols: int, fill) -> np.ndarray:
     """Float32 [n_rows, n_cols] filled block by block; every block of rows draws from a stream of
