@@ -244,6 +244,34 @@ umas_status umas_value_loss_fwd_bwd(const void* H, const void* w, float bias, um
                                     float* value_new, void* dH, float* dw, float* db, void* workspace,
                                     size_t workspace_bytes, void* hip_stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Reference-policy KL folded into the token rewards.  The worker groups compute "reference-policy
+ * log probabilities" with the quantities of PPO-style optimisation (Section "PPO-Style Training
+ * Loop", paragraph "Advantage computation and policy evaluation"); logp_ref comes from
+ * umas_policy_logprobs with the reference head.  The paper prints no penalty; the per-token estimate
+ * is taken:  r'_t = r_t - beta (logp_t - logp_ref_t) on mask=1 tokens, r_t elsewhere.
+ *   tok_reward, logp, logp_ref  DEVICE float [n_tokens], 16-byte aligned;  tok_mask DEVICE uint8 [n_tokens]
+ *   tok_reward_out              DEVICE float [n_tokens]; may be tok_reward itself
+ *   kl_mean                     DEVICE float [1]: mean of logp - logp_ref over the mask=1 tokens (0 if none) */
+size_t umas_kl_rewards_workspace_bytes(int64_t n_tokens);
+umas_status umas_kl_rewards(const float* tok_reward, const float* logp, const float* logp_ref,
+                            const uint8_t* tok_mask, int64_t n_tokens, float beta, float* tok_reward_out,
+                            float* kl_mean, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Advantage whitening over the mask=1 tokens of each model's stream (UMAS_WHITEN_MODEL) or of each role
+ * inside it (UMAS_WHITEN_MODEL_ROLE; role identity is kept under sharing, Section "Parameter Sharing in
+ * the System"):  A'_t = (A_t - mu) / sqrt(var + eps), population variance, 0 on masked tokens; a group
+ * without tokens is left alone; a token whose role is outside [0, n_roles) joins no group and gets 0.
+ *   adv, adv_out    DEVICE float [n_tokens], 16-byte aligned; adv_out may be adv itself
+ *   tok_role        DEVICE int32 [n_tokens] (may be NULL for UMAS_WHITEN_MODEL)
+ *   model_tok_off   HOST int64 [n_models + 1]: the streams' token offsets, from 0 to n_tokens */
+typedef enum umas_whiten_scope { UMAS_WHITEN_MODEL = 0, UMAS_WHITEN_MODEL_ROLE = 1 } umas_whiten_scope;
+size_t umas_whiten_workspace_bytes(int64_t n_tokens, int32_t n_models, int32_t n_roles);
+umas_status umas_whiten_advantages(const float* adv, const uint8_t* tok_mask, const int32_t* tok_role,
+                                   const int64_t* model_tok_off, int32_t n_models, int32_t n_roles,
+                                   int64_t n_tokens, int32_t scope, float eps, float* adv_out,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Kernel timing aid for benchmarks (not part of the method).  While enabled, every kernel launch
  * of the library is followed by a HIP event on its stream and the time between consecutive events
  * of one call is booked to the kernel launched in between.  umas_profile_enable(on) discards earlier

@@ -336,6 +336,51 @@ def umas_value_loss_fwd_bwd(H, w, bias, rowsel, value_old, ret, tok_role, n_role
     return stats, value_new, dH, dw, db
 
 
+WHITEN_MODEL, WHITEN_MODEL_ROLE = 0, 1
+
+
+def umas_kl_rewards(tok_reward, logp, logp_ref, tok_mask, beta, out=None):
+    """Returns (penalised rewards, device float[1] mean of logp - logp_ref over the mask=1 tokens)."""
+    lib = load_library()
+    lib.umas_kl_rewards_workspace_bytes.restype = C.c_size_t
+    lib.umas_kl_rewards_workspace_bytes.argtypes = [C.c_int64]
+    lib.umas_kl_rewards.restype = C.c_int
+    lib.umas_kl_rewards.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    n = int(tok_reward.numel())
+    dev = tok_reward.device
+    if out is None:
+        out = torch.empty_like(tok_reward)
+    kl = torch.empty(1, dtype=torch.float32, device=dev)
+    ws = _workspace(lib.umas_kl_rewards_workspace_bytes(n), dev)
+    d = _dummy(dev).data_ptr()
+    p = (lambda t: t.data_ptr() if n else d)
+    _check(lib, lib.umas_kl_rewards(p(tok_reward), p(logp), p(logp_ref), p(tok_mask), n, beta, p(out), kl.data_ptr(),
+                                    ws.data_ptr(), ws.numel(), _stream()))
+    return out, kl
+
+
+def umas_whiten_advantages(adv, tok_mask, tok_role, model_tok_off, n_roles, scope=WHITEN_MODEL, eps=1e-8, out=None):
+    lib = load_library()
+    lib.umas_whiten_workspace_bytes.restype = C.c_size_t
+    lib.umas_whiten_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
+    lib.umas_whiten_advantages.restype = C.c_int
+    lib.umas_whiten_advantages.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int64,
+                                           C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    n = int(adv.numel())
+    dev = adv.device
+    off_keep, off_ptr = _host(model_tok_off, np.int64)
+    n_models = len(off_keep) - 1
+    if out is None:
+        out = torch.empty_like(adv)
+    ws = _workspace(lib.umas_whiten_workspace_bytes(n, n_models, n_roles), dev)
+    d = _dummy(dev).data_ptr()
+    p = (lambda t: None if t is None else (t.data_ptr() if n else d))
+    _check(lib, lib.umas_whiten_advantages(p(adv), p(tok_mask), p(tok_role), off_ptr, n_models, n_roles, n, scope, eps,
+                                           p(out), ws.data_ptr(), ws.numel(), _stream()))
+    return out
+
+
 def read_value_stats(stats: torch.Tensor) -> np.ndarray:
     return stats.cpu().numpy().view(VALUE_STATS_DTYPE)
 

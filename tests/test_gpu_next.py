@@ -114,3 +114,64 @@ def test_critic_empty_selection_and_errors():
         umas.umas_values(torch.zeros((4, 12), dtype=torch.bfloat16, device="cuda"), torch.zeros(12, dtype=torch.bfloat16, device="cuda"))
     with pytest.raises(umas.UmasError):
         umas.umas_value_loss_fwd_bwd(H, wv, 0.0, None, z, z, None, 0, -1.0)
+
+
+def shaping_case(cfg, **kw):
+    """KL-penalised rewards feed the scan with dense rewards; whitening on the resulting advantages."""
+    w = wl.make_workload(cfg, **kw)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w)
+    s, adv, ret = P.gpu_front(w)
+    n = w.n_tokens
+    rng = np.random.default_rng(1234 + cfg)
+    logp = (-3.0 * rng.random(n)).astype(np.float32)
+    logp_ref = (logp + rng.normal(size=n).astype(np.float32) * 0.1).astype(np.float32)
+    beta = 0.05
+    r_o, kl_o = orc.kl_penalised_rewards(r, logp, logp_ref, st["tok_mask"], beta)
+    r_g, kl_g = umas.umas_kl_rewards(s.tok_reward, P.to_dev(logp), P.to_dev(logp_ref), s.tok_mask, beta)
+    P.close(r_g.cpu().numpy(), r_o, 1e-5, "penalised rewards")
+    assert abs(float(kl_g.item()) - kl_o) <= 1e-5 * max(abs(kl_o), np.abs(logp - logp_ref).mean())
+    masked = st["tok_mask"] == 0
+    assert np.array_equal(r_g.cpu().numpy()[masked].view(np.uint32), r[masked].view(np.uint32)), "masked tokens keep their reward"
+    # dense rewards through the scan on both sides
+    value = None if w.value is None else w.value
+    adv2_o, ret2_o = orc.advantages(st, w.traj_turn_off, r_o.astype(np.float32), value, w.gamma, w.lam, w.gamma_turn, w.seg_mode)
+    s.tok_reward = r_g
+    adv2, ret2 = umas.umas_advantages(s, None if value is None else P.to_dev(value), w.gamma, w.lam, w.gamma_turn, w.seg_mode)
+    P.close(adv2.cpu().numpy(), adv2_o, 1e-5, "advantages on dense rewards")
+    P.close(ret2.cpu().numpy(), ret2_o, 1e-5, "returns on dense rewards")
+    # in place
+    r_in = s.tok_reward.clone()
+    umas.umas_kl_rewards(r_in, P.to_dev(logp), P.to_dev(logp_ref), s.tok_mask, beta, out=r_in)
+    r_twice, _ = orc.kl_penalised_rewards(r_o, logp, logp_ref, st["tok_mask"], beta)
+    P.close(r_in.cpu().numpy(), r_twice, 1e-5, "in-place penalty")
+    for scope, oscope in ((umas.WHITEN_MODEL, orc.WHITEN_MODEL), (umas.WHITEN_MODEL_ROLE, orc.WHITEN_MODEL_ROLE)):
+        wh_o = orc.whiten_advantages(adv2_o, st["tok_mask"], st["tok_role"], st["model_tok_off"], w.n_roles, oscope)
+        wh = umas.umas_whiten_advantages(adv2, s.tok_mask, s.tok_role, st["model_tok_off"], w.n_roles, scope)
+        P.close(wh.cpu().numpy(), wh_o, 2e-5, f"whitened advantages, scope {scope}")   # two float32 roundings: input and result
+        assert not wh.cpu().numpy()[masked].any()
+    buf = adv2.clone()
+    umas.umas_whiten_advantages(buf, s.tok_mask, s.tok_role, st["model_tok_off"], w.n_roles, umas.WHITEN_MODEL, out=buf)
+    assert np.array_equal(buf.cpu().numpy(), umas.umas_whiten_advantages(adv2, s.tok_mask, s.tok_role, st["model_tok_off"], w.n_roles).cpu().numpy())
+
+
+def test_kl_rewards_and_whitening_small_and_full_sizes():
+    shaping_case(0)
+    shaping_case(2)                                    # interior masks, values, gamma < 1
+    shaping_case(3)                                    # two models, five roles
+    shaping_case(4, n_traj=64)                         # long segments, several blocks
+
+
+def test_shaping_empty_and_errors():
+    z = torch.zeros(0, device="cuda")
+    zm = torch.zeros(0, dtype=torch.uint8, device="cuda")
+    out, kl = umas.umas_kl_rewards(z, z, z, zm, 0.1)
+    assert out.numel() == 0 and float(kl.item()) == 0.0
+    a = torch.ones(8, device="cuda")
+    m = torch.ones(8, dtype=torch.uint8, device="cuda")
+    with pytest.raises(umas.UmasError):
+        umas.umas_whiten_advantages(a, m, None, np.array([0, 5]), 1)          # offsets do not end at n_tokens
+    with pytest.raises(umas.UmasError):
+        umas.umas_whiten_advantages(a, m, None, np.array([0, 8]), 1, scope=umas.WHITEN_MODEL_ROLE)   # roles needed
+    # a group of equal values: (A - mu) is exactly 0 whatever eps does
+    out = umas.umas_whiten_advantages(a * 0.3, m, None, np.array([0, 8]), 1)
+    assert not out.cpu().numpy().any()
