@@ -192,12 +192,16 @@ size_t umas_ppo_loss_workspace_bytes(int64_t n_sel, int32_t d, int32_t V, umas_d
  *   logp_new       DEVICE float [n_rows] or NULL
  *   dH             DEVICE [n_rows, d] in the dtype of H; rows not selected are set to 0
  *   dW             DEVICE float [V, d]; accumulate_dW = 0 overwrites, 1 adds
- * clip_eps must lie in (0,1).  entropy_coef must be 0 (the entropy bonus is not built). */
+ * clip_eps must lie in (0,1).
+ * Two optional terms (stabilisers of the PPO family; both off at 0):
+ *   dual_clip c > 1: for A < 0 the row's term is capped at -A c, with no gradient where the cap binds;
+ *   entropy_coef k >= 0: the loss becomes L_clip - k mean entropy (stats.loss includes it) and
+ *     dz_iv gains (k / n_sel) p_iv (log p_iv + entropy_i), p = softmax(z_i). */
 umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_dtype dtype, int64_t n_rows,
                                   int32_t d, int32_t V, const int32_t* ids, const int32_t* rowsel,
                                   int64_t n_sel, const float* logp_old, const float* adv,
                                   const int32_t* tok_role, int32_t n_roles, float clip_eps,
-                                  float entropy_coef, int32_t accumulate_dW, umas_loss_stats* stats,
+                                  float entropy_coef, float dual_clip, int32_t accumulate_dW, umas_loss_stats* stats,
                                   float* logp_new, void* dH, float* dW,
                                   void* workspace, size_t workspace_bytes, void* hip_stream);
 

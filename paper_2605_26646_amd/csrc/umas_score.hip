@@ -291,14 +291,16 @@ k_score_f32(const float* __restrict__ W, const float* __restrict__ H, int d, int
 }
 
 // ------------------------------------------------------------------ clipped surrogate
-// Per selected row: loss term and g = dloss/dlogp; per block sums of (L, clipped, entropy,
+// Per selected row: loss term (single clip, or dual clip when dual_clip > 1) and g = dloss/dlogp of the
+// clipped part; per block sums of (L, clipped, entropy,
 // logp_old - logp, rows, invalid ids) for the model and for each role, in float64.
 constexpr int kStat = 6;
 __global__ void __launch_bounds__(kRowBlock)
 k_ppo_rows(int64_t n_sel, const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
            const float* __restrict__ logp_c, const float* __restrict__ ent_c, const float* __restrict__ logp_old,
            const float* __restrict__ adv, const int32_t* __restrict__ tok_role, int n_roles, float clip_eps,
-           float* __restrict__ g_c, double* __restrict__ blk_stats) {
+           float dual_clip, float k_ent, const float* __restrict__ lse_c, float* __restrict__ g_c,
+           float* __restrict__ a_c, float* __restrict__ kz_c, double* __restrict__ blk_stats) {
   extern __shared__ double s_acc[];   // [(1+n_roles) * kStat]
   const int nacc = (1 + n_roles) * kStat;
   for (int i = threadIdx.x; i < nacc; i += blockDim.x) s_acc[i] = 0.0;
@@ -314,14 +316,22 @@ k_ppo_rows(int64_t n_sel, const int32_t* __restrict__ rowsel, const int32_t* __r
       const float ratio = __expf(lp - lo);
       const float u = -A * ratio;
       const float c = -A * fminf(fmaxf(ratio, 1.f - clip_eps), 1.f + clip_eps);
-      const bool unclipped = u >= c;
+      bool unclipped = u >= c;
       L = unclipped ? u : c;
+      if (dual_clip > 0.f && A < 0.f && -A * dual_clip < L) {   // dual clip: the term of a negative advantage is capped
+        L = -A * dual_clip;
+        unclipped = false;
+      }
       g = unclipped ? u / static_cast<float>(n_sel) : 0.f;
       clipped = unclipped ? 0.f : 1.f;
       en = ent_c[n];
       kl = lo - lp;
     }
     g_c[n] = g;
+    // coefficients of the backward's dense part dz = p (a + kz z): -g from the surrogate, the rest from the
+    // entropy bonus k_ent p (log p + entropy); a row with an invalid id has neither
+    a_c[n] = ok ? -g + k_ent * (en - lse_c[n]) : 0.f;
+    kz_c[n] = ok ? k_ent : 0.f;
     const int role = (tok_role && n_roles > 0) ? tok_role[row] : -1;
     for (int pass = 0; pass < 2; ++pass) {
       if (pass == 1 && (role < 0 || role >= n_roles)) break;
@@ -339,7 +349,8 @@ k_ppo_rows(int64_t n_sel, const int32_t* __restrict__ rowsel, const int32_t* __r
 }
 
 __global__ void __launch_bounds__(256)
-k_ppo_stats(int nblk, int n_roles, const double* __restrict__ blk_stats, umas_loss_stats* __restrict__ stats) {
+k_ppo_stats(int nblk, int n_roles, float entropy_coef, const double* __restrict__ blk_stats,
+            umas_loss_stats* __restrict__ stats) {
   __shared__ double smem[32];
   const int nacc = (1 + n_roles) * kStat;
   for (int k = 0; k <= n_roles; ++k) {
@@ -352,7 +363,7 @@ k_ppo_stats(int nblk, int n_roles, const double* __restrict__ blk_stats, umas_lo
     if (threadIdx.x == 0) {
       const double cnt = sum[4];
       umas_loss_stats s;
-      s.loss = cnt > 0 ? static_cast<float>(sum[0] / cnt) : 0.f;
+      s.loss = cnt > 0 ? static_cast<float>((sum[0] - static_cast<double>(entropy_coef) * sum[2]) / cnt) : 0.f;
       s.clip_frac = cnt > 0 ? static_cast<float>(sum[1] / cnt) : 0.f;
       s.entropy_mean = cnt > 0 ? static_cast<float>(sum[2] / cnt) : 0.f;
       s.approx_kl = cnt > 0 ? static_cast<float>(sum[3] / cnt) : 0.f;
@@ -365,14 +376,15 @@ k_ppo_stats(int nblk, int n_roles, const double* __restrict__ blk_stats, umas_lo
 
 // ------------------------------------------------------------------ bf16: dz tiles into the chunk buffer
 // Same tile product as k_score_tiles; the epilogue forms the dense part of dz = g (onehot - softmax),
-// -g exp(z - lse), and writes it as bf16 to dZ [mcp, Vp] and dZt [Vp, mcp].  Rows past the chunk and
+// -g exp(z - lse), plus the entropy bonus's term when its coefficient is not 0, and writes it as bf16 to
+// dZ [mcp, Vp] and dZt [Vp, mcp].  Rows past the chunk and
 // vocabulary ids past V get 0.  The one-hot part g at v = y is a single term per row and is added in
 // float32 where dH and dW are written, so that it never meets the bf16 rounding of the dense part.
 __global__ void __launch_bounds__(Cfg::T)
 k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
            const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc,
-           const float* __restrict__ lse_c, const float* __restrict__ g_c, int tiles_m, int tiles_n,
-           uint16_t* __restrict__ dZ, uint16_t* __restrict__ dZt, int64_t Vp, int64_t mcp) {
+           const float* __restrict__ lse_c, const float* __restrict__ a_c, const float* __restrict__ kz_c,
+           int tiles_m, int tiles_n, uint16_t* __restrict__ dZ, uint16_t* __restrict__ dZt, int64_t Vp, int64_t mcp) {
   using C = Cfg;
   __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
   int tile_m, tile_n;
@@ -391,24 +403,27 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
   static_assert(C::WM * C::WN * C::WTN * kStagePitch <= kLogitLds, "staging fits the tile buffers");
   char* stage = reinterpret_cast<char*>(lds) + wave * (C::WTN * kStagePitch);
   __syncthreads();                              // every wavefront has left the main loop's LDS reads
-  if (tail) {                                   // vocabulary ids past V: exp2(-inf) = 0 below
+  if (tail) {                                   // vocabulary ids past V: the exponential below is 0, the factor next to it finite
 #pragma unroll
     for (int tm = 0; tm < C::TM; ++tm)
 #pragma unroll
       for (int tn = 0; tn < C::TN; ++tn)
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          if (vbase + tm * 32 + (r >> 2) * 8 + (r & 3) >= V) acc[tm][tn][r] = kNegInf;
+          if (vbase + tm * 32 + (r >> 2) * 8 + (r & 3) >= V) acc[tm][tn][r] = kMasked;
   }
   const int t = lane & 3;                       // position in the quad of lanes holding 4 consecutive rows n
   const uint32_t sel = (t & 1) ? 0x07060302u : 0x05040100u;   // v_perm_b32: 0-3 = bytes of src1, 4-7 = bytes of src0
 #pragma unroll
   for (int tn = 0; tn < C::TN; ++tn) {
     const int64_t n = n0 + acc_col<C>(tn);
-    float l2 = 0.f, g = 0.f;                    // rows past the chunk: g = 0 and a finite exponent, so dz = 0
+    // dz = p (a + kz z) with p = exp(z - lse), a = -g + k (entropy - lse), kz = k = entropy_coef / n_sel: the
+    // dense part of g (onehot - p) plus the entropy bonus's k p (log p + entropy).  Rows past the chunk: p = 0.
+    float l2 = 1e30f, a = 0.f, kz = 0.f;
     if (n < mc) {
       l2 = lse_c[c0 + n] * 1.44269504088896341f;
-      g = -g_c[c0 + n];
+      a = a_c[c0 + n];
+      kz = kz_c[c0 + n];
     }
 #pragma unroll
     for (int tm = 0; tm < C::TM; ++tm)
@@ -418,7 +433,8 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
         float dz[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          dz[j] = g * __builtin_amdgcn_exp2f(fmaf(acc[tm][tn][q * 4 + j], 1.44269504088896341f, -l2));
+          const float z = acc[tm][tn][q * 4 + j];
+          dz[j] = __builtin_amdgcn_exp2f(fmaf(z, 1.44269504088896341f, -l2)) * fmaf(kz, z, a);
         }
         const uint32_t p01 = static_cast<uint32_t>(f2bf(dz[0])) | (static_cast<uint32_t>(f2bf(dz[1])) << 16);
         const uint32_t p23 = static_cast<uint32_t>(f2bf(dz[2])) | (static_cast<uint32_t>(f2bf(dz[3])) << 16);
@@ -544,20 +560,22 @@ k_dw_onehot(const uint16_t* __restrict__ H, int d, const int32_t* __restrict__ r
 __global__ void __launch_bounds__(256)
 k_dz_f32(const float* __restrict__ W, const float* __restrict__ H, int d, int V, const int32_t* __restrict__ rowsel,
          int64_t c0, const int32_t* __restrict__ ids, const float* __restrict__ lse_c, const float* __restrict__ g_c,
-         float* __restrict__ dz) {
+         const float* __restrict__ ent_c, const float* __restrict__ kz_c, float* __restrict__ dz) {
   extern __shared__ float s_h[];
   const int64_t n = blockIdx.x;
   const int64_t row = rowsel ? rowsel[c0 + n] : c0 + n;
   for (int k = threadIdx.x; k < d; k += blockDim.x) s_h[k] = H[row * d + k];
   __syncthreads();
   const int y = ids[row];
-  const float l = lse_c[c0 + n], g = g_c[c0 + n];
+  const float l = lse_c[c0 + n], g = g_c[c0 + n], en = ent_c[c0 + n], k_ent = kz_c[c0 + n];
   for (int v = threadIdx.x; v < V; v += blockDim.x) {
     const float* w = W + static_cast<int64_t>(v) * d;
     float z = 0.f;
     for (int k = 0; k < d; ++k) z = fmaf(s_h[k], w[k], z);
     const float p = expf(z - l);
-    dz[n * V + v] = (v == y) ? g * (1.f - p) : -g * p;
+    float o = (v == y) ? g * (1.f - p) : -g * p;
+    if (k_ent != 0.f) o += k_ent * p * ((z - l) + en);     // entropy bonus: k p (log p + entropy)
+    dz[n * V + v] = o;
   }
 }
 // dH[row, j] = sum_v dz[n, v] W[v, j]
@@ -616,6 +634,8 @@ size_t carve_score(Carver& c, ScoreWs& w, int64_t n_sel, int V, umas_dtype dt, b
 struct PpoWs {
   ScoreWs score;
   float* g_c;
+  float* a_c;        // per selected row: coefficients of the backward's dense part
+  float* kz_c;
   double* blk_stats;
   uint16_t* Wt;      // bf16 [d][Vp]
   char* chunk;       // rest of the workspace
@@ -631,6 +651,8 @@ size_t carve_ppo(Carver& c, PpoWs& w, int64_t n_sel, int d, int V, umas_dtype dt
   carve_score(c, w.score, n_sel, V, dt, true);
   const int64_t n_pad = round_up(n_sel > 0 ? n_sel : 1, Cfg::BN);
   w.g_c = c.take<float>(n_pad);
+  w.a_c = c.take<float>(n_pad);
+  w.kz_c = c.take<float>(n_pad);
   w.blk_stats = c.take<double>(static_cast<size_t>(cdiv(n_pad, kRowBlock)) * (1 + n_roles) * kStat);
   w.Wt = dt == UMAS_BF16 ? c.take<uint16_t>(static_cast<size_t>(d) * round_up(V, 256)) : nullptr;
   w.chunk = c.base ? c.base + c.off : nullptr;
@@ -754,7 +776,7 @@ extern "C" size_t umas_ppo_loss_workspace_bytes(int64_t n_sel, int32_t d, int32_
 extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_dtype dtype, int64_t n_rows, int32_t d,
                                              int32_t V, const int32_t* ids, const int32_t* rowsel, int64_t n_sel,
                                              const float* logp_old, const float* adv, const int32_t* tok_role,
-                                             int32_t n_roles, float clip_eps, float entropy_coef,
+                                             int32_t n_roles, float clip_eps, float entropy_coef, float dual_clip,
                                              int32_t accumulate_dW, umas_loss_stats* stats, float* logp_new, void* dH,
                                              float* dW, void* workspace, size_t workspace_bytes, void* hip_stream) {
   umas_status s = check_model_args(H, W, dtype, n_rows, d, V, ids, rowsel, n_sel);
@@ -764,7 +786,9 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
   UMAS_REQUIRE(n_roles >= 0 && n_roles <= UMAS_MAX_ROLES, UMAS_ESHAPE, "n_roles=%d outside [0,%d]", n_roles, UMAS_MAX_ROLES);
   UMAS_REQUIRE(tok_role || n_roles == 0, UMAS_EINVAL, "tok_role is NULL but n_roles > 0");
   UMAS_REQUIRE(clip_eps > 0.f && clip_eps < 1.f, UMAS_EINVAL, "clip_eps=%g outside (0,1)", static_cast<double>(clip_eps));
-  UMAS_REQUIRE(entropy_coef == 0.f, UMAS_EINVAL, "entropy_coef must be 0: the entropy bonus is not built");
+  UMAS_REQUIRE(entropy_coef >= 0.f, UMAS_EINVAL, "entropy_coef=%g must not be negative", static_cast<double>(entropy_coef));
+  UMAS_REQUIRE(dual_clip == 0.f || dual_clip > 1.f, UMAS_EINVAL, "dual_clip=%g must be 0 (off) or larger than 1",
+               static_cast<double>(dual_clip));
   UMAS_REQUIRE(n_sel < (1LL << 31), UMAS_ESHAPE, "at most 2^31-1 selected rows");
   s = check_ws(workspace, workspace_bytes, umas_ppo_loss_workspace_bytes_min(n_sel, d, V, dtype, n_roles));
   if (s != UMAS_OK) return s;
@@ -786,10 +810,11 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
   if (s != UMAS_OK) return s;
   const int nblk = cdiv(n_sel > 0 ? n_sel : 1, kRowBlock);
   hipLaunchKernelGGL(k_ppo_rows, dim3(nblk), dim3(kRowBlock), (1 + n_roles) * kStat * sizeof(double), st, n_sel, rowsel,
-                     ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv, tok_role, n_roles, clip_eps, w.g_c,
+                     ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv, tok_role, n_roles, clip_eps, dual_clip,
+                     n_sel > 0 ? entropy_coef / static_cast<float>(n_sel) : 0.f, w.score.lse_c, w.g_c, w.a_c, w.kz_c,
                      w.blk_stats);
   UMAS_LAUNCHED("k_ppo_rows");
-  hipLaunchKernelGGL(k_ppo_stats, dim3(1), dim3(256), 0, st, nblk, n_roles, w.blk_stats, stats);
+  hipLaunchKernelGGL(k_ppo_stats, dim3(1), dim3(256), 0, st, nblk, n_roles, entropy_coef, w.blk_stats, stats);
   UMAS_LAUNCHED("k_ppo_stats");
   if (n_sel == 0) return UMAS_OK;
 
@@ -813,7 +838,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
       const int64_t rows = n_sel - c0 < mc ? n_sel - c0 : mc;
       hipLaunchKernelGGL(k_dz_f32, dim3(static_cast<unsigned>(rows)), dim3(256), d * sizeof(float), st,
                          static_cast<const float*>(W), static_cast<const float*>(H), d, V, rowsel, c0, ids,
-                         w.score.lse_c, w.g_c, dz);
+                         w.score.lse_c, w.g_c, w.score.ent_c, w.kz_c, dz);
       UMAS_LAUNCHED("k_dz_f32");
       hipLaunchKernelGGL(k_dh_f32, dim3(static_cast<unsigned>(rows)), dim3(256), 0, st, dz,
                          static_cast<const float*>(W), d, V, rowsel, c0, static_cast<float*>(dH));
@@ -842,7 +867,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     UMAS_LAUNCHED("k_transpose_bf16");
     const int tiles_v = static_cast<int>(Vp / 256), tiles_r = static_cast<int>(mcp / 256), tiles_d = (d + 255) / 256;
     hipLaunchKernelGGL(k_dz_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r)), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel,
-                       c0, rows, w.score.lse_c, w.g_c, tiles_v, tiles_r, dZ, dZt, Vp, mcp);
+                       c0, rows, w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, dZ, dZt, Vp, mcp);
     UMAS_LAUNCHED("k_dz_tiles");
     hipLaunchKernelGGL(k_gemm_dh, dim3(tile_grid<kGM, kGN>(tiles_r, tiles_d)), dim3(Cfg::T), 0, st, dZ, Vp, mcp, w.Wt, d,
                        tiles_r, tiles_d, static_cast<uint16_t*>(dH), rowsel, c0, rows, Wb, ids, w.g_c);

@@ -175,3 +175,49 @@ def test_shaping_empty_and_errors():
     # a group of equal values: (A - mu) is exactly 0 whatever eps does
     out = umas.umas_whiten_advantages(a * 0.3, m, None, np.array([0, 8]), 1)
     assert not out.cpu().numpy().any()
+
+
+def variants_case(cfg, entropy_coef, dual_clip, noise_scale, **kw):
+    """Dual clip and entropy bonus of the surrogate and its backward, per model."""
+    w = wl.make_workload(cfg, **kw)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w)
+    s, adv, ret = P.gpu_front(w)
+    for m in range(w.n_models):
+        spec = w.models[m]
+        tdt = torch.float32 if spec.dtype == "f32" else torch.bfloat16
+        tol_logp, tol = (1e-5, 1e-5) if spec.dtype == "f32" else (2e-2, 1e-2)
+        t = w.model_tensors(m)
+        a, e = int(st["model_tok_off"][m]), int(st["model_tok_off"][m + 1])
+        ra, re = int(st["model_rowsel_off"][m]), int(st["model_rowsel_off"][m + 1])
+        rows_o = st["rowsel"][ra:re]
+        role_o = st["tok_role"][a:e]
+        logp_o, lse_o, ent_o = orc.score(t["H"], t["W"], t["ids"], rows_o)
+        logp_old = (logp_o + noise_scale * t["noise"]).astype(np.float32)
+        stats_o, g_o = orc.ppo_loss_variants(logp_o, logp_old, adv_o[a:e], ent_o, rows_o, role_o, w.n_roles, w.clip_eps,
+                                             dual_clip, entropy_coef)
+        plain_o, g_plain = orc.ppo_loss(logp_o, logp_old, adv_o[a:e], ent_o, rows_o, role_o, w.n_roles, w.clip_eps)
+        if dual_clip > 0:
+            assert np.abs(g_o - g_plain).max() > 0, "the case must make the dual clip bind"
+        dH_o, dW_o = orc.lm_head_backward_entropy(t["H"], t["W"], t["ids"], lse_o, ent_o, g_o, entropy_coef, len(rows_o), rows_o)
+        H, W, ids = P.to_dev(t["H"], tdt), P.to_dev(t["W"], tdt), P.to_dev(t["ids"])
+        stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(
+            H, W, ids, s.rowsel[ra:re], P.to_dev(logp_old), adv[a:e].contiguous(), s.tok_role[a:e].contiguous(), w.n_roles,
+            w.clip_eps, entropy_coef=entropy_coef, dual_clip=dual_clip)
+        torch.cuda.synchronize()
+        sg = umas.read_stats(stats)
+        for k in range(1 + w.n_roles):
+            assert int(sg["n_scored"][k]) == int(stats_o[k, 4])
+            o = stats_o[k, 0]
+            # the loss is a mean of terms of size |A| ratio and of coef * entropy
+            assert abs(float(sg["loss"][k]) - o) <= tol * max(abs(o), abs(stats_o[0, 0]), entropy_coef * abs(stats_o[k, 2]), 1e-3)
+            assert abs(float(sg["clip_frac"][k]) - stats_o[k, 1]) <= max(tol * stats_o[k, 1], 2.0 / max(stats_o[k, 4], 1))
+        P.close(dH.float().cpu().numpy(), dH_o, tol, "dH")
+        P.close(dW.cpu().numpy(), dW_o, tol, "dW")
+
+
+def test_surrogate_variants():
+    variants_case(0, 0.01, 0.0, 1.0)                                           # entropy bonus alone, float32
+    variants_case(0, 0.0, 3.0, 14.0)                                           # dual clip alone (noise std 0.7: ratios beyond 3)
+    variants_case(0, 0.02, 2.0, 14.0)
+    variants_case(2, 0.01, 3.0, 14.0, n_traj=8, tokens_per_turn=48, models=[(200, 1000, "bf16")])
+    variants_case(3, 0.05, 0.0, 1.0, n_traj=6, tokens_per_turn=40, models=[(128, 700, "bf16"), (200, 1000, "bf16")])
