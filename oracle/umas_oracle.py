@@ -494,3 +494,45 @@ def lm_head_backward_entropy(H, W, ids, lse, entropy, g, entropy_coef, n_scored,
         dH[rr] = dz @ W64
         dW += dz.T @ Hc
     return dH, dW
+
+
+# --------------------------------------------------------------------------------------
+# Ready-batch construction  (Section "Model-Local Buffers": a buffer becomes a ready batch by
+# filtering incomplete trajectories, shuffling and matching the worker group's data-parallel
+# configuration; rewards were aligned with the tokens by place_rewards)
+# --------------------------------------------------------------------------------------
+def ready_batch(streams, traj_turn_off, traj_keep, traj_order, n_minibatch):
+    """Split every model's scored rows into minibatches of whole trajectories.
+
+    traj_keep[b] = 0 drops trajectory b (incomplete).  traj_order is the shuffle: a permutation of
+    the trajectories, supplied by the caller.  The kept trajectories, in shuffled order, are cut into
+    n_minibatch contiguous parts whose sizes differ by at most one: the q-th of n_kept goes to part
+    q * n_minibatch // n_kept.  For model m and minibatch k the rows are those of the minibatch's
+    trajectories, trajectory by trajectory in shuffled order, each trajectory's scored rows in stream
+    order (stream-relative positions, as in rowsel).
+    Returns (mb_rowsel int32 [kept scored rows], mb_off int64 [n_models, n_minibatch + 1]):
+    minibatch k of model m is mb_rowsel[mb_off[m, k] : mb_off[m, k + 1]].
+    """
+    n_traj = len(traj_turn_off) - 1
+    n_models = len(streams["model_tok_off"]) - 1
+    turn_traj = {}
+    for b in range(n_traj):
+        for u in range(int(traj_turn_off[b]), int(traj_turn_off[b + 1])):
+            turn_traj[u] = b
+    kept = [int(b) for b in traj_order if traj_keep[int(b)]]
+    part = {b: (q * n_minibatch) // len(kept) for q, b in enumerate(kept)}
+    out, off = [], np.zeros((n_models, n_minibatch + 1), dtype=np.int64)
+    for m in range(n_models):
+        a = int(streams["model_tok_off"][m])
+        ra, re = int(streams["model_rowsel_off"][m]), int(streams["model_rowsel_off"][m + 1])
+        rows_of = {}
+        for row in streams["rowsel"][ra:re]:
+            b = turn_traj[int(streams["tok_turn"][a + int(row)])]
+            rows_of.setdefault(b, []).append(int(row))
+        for k in range(n_minibatch):
+            off[m, k] = len(out)
+            for b in kept:
+                if part[b] == k:
+                    out.extend(rows_of.get(b, []))
+        off[m, n_minibatch] = len(out)
+    return np.array(out, dtype=np.int32), off

@@ -192,3 +192,68 @@ def test_entropy_bonus_backward_matches_finite_differences():
     assert np.allclose(entz[rows], math.log(V))
     dHz, dWz = orc.lm_head_backward_entropy(H, Wz, ids, lsez, entz, np.zeros(n), c_ent, len(rows), rows)
     assert np.abs(dHz).max() < 1e-15 and np.abs(dWz).max() < 1e-15
+
+
+# ------------------------------------------------------------------ ready batch
+def _routed(seed, n_traj=7, phi=(0, 1, 0)):
+    rng = np.random.default_rng(seed)
+    roles, lens = [], []
+    for b in range(n_traj):
+        k = int(rng.integers(1, 5))
+        roles.append([int(rng.integers(0, len(phi))) for _ in range(k)])
+        lens.append([int(rng.integers(0, 6)) for _ in range(k)])
+    tto = np.concatenate([[0], np.cumsum([len(r) for r in roles])])
+    role = np.array([v for r in roles for v in r], np.int32)
+    tok_off = np.concatenate([[0], np.cumsum([l for ls in lens for l in ls])])
+    mask = (rng.random(int(tok_off[-1])) < 0.7).astype(np.uint8)
+    st = orc.route(max(phi) + 1, np.array(phi), tto, role, tok_off, mask)
+    turn_traj = np.repeat(np.arange(n_traj), np.diff(tto))
+    return st, tto, turn_traj
+
+
+def test_ready_batch_hand_example():
+    # 3 trajectories of one turn each (lengths 2, 3, 2), one model, all tokens valid; shuffle (2, 0, 1), drop none,
+    # two minibatches: kept order 2,0,1 -> parts 0,0,1 -> minibatch 0 = rows of traj 2 then traj 0, minibatch 1 = traj 1
+    st = orc.route(1, np.array([0]), np.array([0, 1, 2, 3]), np.zeros(3, np.int32), np.array([0, 2, 5, 7]), np.ones(7, np.uint8))
+    rows, off = orc.ready_batch(st, np.array([0, 1, 2, 3]), np.ones(3), np.array([2, 0, 1]), 2)
+    assert rows.tolist() == [5, 6, 0, 1, 2, 3, 4] and off.tolist() == [[0, 4, 7]]
+    # dropping trajectory 0: kept order 2,1 -> one each
+    rows, off = orc.ready_batch(st, np.array([0, 1, 2, 3]), np.array([0, 1, 1]), np.array([2, 0, 1]), 2)
+    assert rows.tolist() == [5, 6, 2, 3, 4] and off.tolist() == [[0, 2, 5]]
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_ready_batch_partition_properties(seed):
+    st, tto, turn_traj = _routed(seed)
+    n_traj = len(tto) - 1
+    rng = np.random.default_rng(100 + seed)
+    keep = (rng.random(n_traj) < 0.75).astype(np.uint8)
+    keep[int(rng.integers(0, n_traj))] = 1
+    order = rng.permutation(n_traj)
+    M = 3
+    rows, off = orc.ready_batch(st, tto, keep, order, M)
+    kept = [b for b in order if keep[b]]
+    sizes = [sum(1 for q in range(len(kept)) if q * M // len(kept) == k) for k in range(M)]
+    assert max(sizes) - min(sizes) <= 1
+    for m in range(len(st["model_tok_off"]) - 1):
+        a = int(st["model_tok_off"][m])
+        ra, re = int(st["model_rowsel_off"][m]), int(st["model_rowsel_off"][m + 1])
+        want_all = [int(r) for r in st["rowsel"][ra:re] if keep[turn_traj[st["tok_turn"][a + r]]]]
+        got_all = rows[off[m, 0]:off[m, M]].tolist()
+        assert sorted(got_all) == want_all and len(set(got_all)) == len(got_all)
+        q0 = 0
+        for k in range(M):
+            trajs = kept[q0:q0 + sizes[k]]
+            q0 += sizes[k]
+            got = rows[off[m, k]:off[m, k + 1]]
+            got_traj = [int(turn_traj[st["tok_turn"][a + r]]) for r in got]
+            assert set(got_traj) <= set(trajs)
+            # trajectory by trajectory in shuffled order, rows ascending inside a trajectory
+            seen = [b for i, b in enumerate(got_traj) if i == 0 or got_traj[i - 1] != b]
+            assert seen == [b for b in trajs if b in set(got_traj)]
+            for b in set(got_traj):
+                rb = [int(r) for r, t in zip(got, got_traj) if t == b]
+                assert rb == sorted(rb)
+    # everything kept, identity order, one minibatch: the selection itself
+    rows1, off1 = orc.ready_batch(st, tto, np.ones(n_traj), np.arange(n_traj), 1)
+    assert np.array_equal(rows1, st["rowsel"]) and np.array_equal(off1[:, 0], st["model_rowsel_off"][:-1])
