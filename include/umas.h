@@ -276,6 +276,30 @@ umas_status umas_whiten_advantages(const float* adv, const uint8_t* tok_mask, co
                                    int64_t n_tokens, int32_t scope, float eps, float* adv_out,
                                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Ready-batch construction, B_i -> D_i^ready (Section "Model-Local Buffers": filtering incomplete
+ * trajectories, shuffling, matching the worker group's data-parallel configuration; the rewards were
+ * aligned with the tokens by umas_assign_token_rewards).  The kept trajectories, in the order of the
+ * shuffle, are cut into n_minibatch contiguous parts whose sizes differ by at most one: the q-th of
+ * n_kept goes to part q * n_minibatch / n_kept.  For model m and minibatch k the scored rows of the
+ * minibatch's trajectories are listed trajectory by trajectory in shuffled order, rows of one trajectory
+ * in stream order (stream-relative positions, as in rowsel), ready to be passed as the row selection of
+ * umas_policy_logprobs / umas_ppo_loss_fwd_bwd / umas_value_loss_fwd_bwd (accumulate_dW = 1 adds the
+ * gradients of successive micro-batches).
+ *   streams        the arrays written by umas_assign_token_rewards (DEVICE)
+ *   traj_turn_off  HOST int32 [n_traj+1], as in umas_graph
+ *   traj_keep      HOST uint8 [n_traj], 0 = drop the trajectory; NULL = keep all
+ *   traj_order     HOST int32 [n_traj], a permutation of the trajectories (the shuffle); NULL = identity
+ *   mb_rowsel      DEVICE int32, at least as many entries as rowsel
+ *   mb_off         DEVICE int64 [n_models * (n_minibatch + 1)]: minibatch k of model m is
+ *                  mb_rowsel[mb_off[m*(n_minibatch+1) + k] .. mb_off[m*(n_minibatch+1) + k + 1])
+ * The host arrays are copied inside the call, which waits for those copies before it returns. */
+size_t umas_ready_batch_workspace_bytes(int32_t n_traj, int32_t n_models);
+umas_status umas_ready_batch(const umas_streams* streams, int32_t n_models, int32_t n_turns,
+                             const int32_t* traj_turn_off, int32_t n_traj, const uint8_t* traj_keep,
+                             const int32_t* traj_order, int32_t n_minibatch, int32_t* mb_rowsel,
+                             int64_t* mb_off, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Kernel timing aid for benchmarks (not part of the method).  While enabled, every kernel launch
  * of the library is followed by a HIP event on its stream and the time between consecutive events
  * of one call is booked to the kernel launched in between.  umas_profile_enable(on) discards earlier

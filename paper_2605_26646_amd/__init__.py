@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     umas_assign_token_rewards, umas_advantages, umas_policy_logprobs, umas_ppo_loss_fwd_bwd,
     ppo_workspace_bytes, read_stats, profile_enable, profile_read,
     umas_values, umas_value_loss_fwd_bwd, read_value_stats, umas_kl_rewards, umas_whiten_advantages,
-    WHITEN_MODEL, WHITEN_MODEL_ROLE,
+    WHITEN_MODEL, WHITEN_MODEL_ROLE, umas_ready_batch,
     PLACE_LAST, PLACE_ALL, SEG_TURN, SEG_TRAJ,
 )

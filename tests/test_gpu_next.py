@@ -221,3 +221,66 @@ def test_surrogate_variants():
     variants_case(0, 0.02, 2.0, 14.0)
     variants_case(2, 0.01, 3.0, 14.0, n_traj=8, tokens_per_turn=48, models=[(200, 1000, "bf16")])
     variants_case(3, 0.05, 0.0, 1.0, n_traj=6, tokens_per_turn=40, models=[(128, 700, "bf16"), (200, 1000, "bf16")])
+
+
+def ready_case(cfg, n_minibatch, seed, drop=0.25, **kw):
+    w = wl.make_workload(cfg, **kw)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w)
+    s, adv, ret = P.gpu_front(w)
+    rng = np.random.default_rng(seed)
+    keep = (rng.random(w.n_traj) >= drop).astype(np.uint8)
+    keep[int(rng.integers(0, w.n_traj))] = 1
+    order = rng.permutation(w.n_traj).astype(np.int32)
+    rows_o, off_o = orc.ready_batch(st, w.traj_turn_off, keep, order, n_minibatch)
+    rows, off = umas.umas_ready_batch(s, w.traj_turn_off, n_minibatch, keep, order)
+    assert np.array_equal(off.cpu().numpy(), off_o), "minibatch offsets differ"
+    assert np.array_equal(rows.cpu().numpy()[:len(rows_o)], rows_o), "minibatch rows differ"
+    return w, st, s, adv_o, adv, rows, off, off_o, rows_o
+
+
+def test_ready_batch_index_work_is_exact():
+    ready_case(0, 2, 1)
+    ready_case(1, 4, 2)                                            # padding masks, 64 trajectories
+    ready_case(2, 3, 3)                                            # variable turns, interior masks
+    ready_case(3, 5, 4)                                            # two models
+    ready_case(4, 3, 5)                                            # long turns, 16 trajectories
+    ready_case(1, 7, 6, n_traj=1000)                               # more trajectories than one scan round
+    ready_case(2, 40, 7, drop=0.9)                                 # more minibatches than kept trajectories
+    # defaults: keep all, identity order, one minibatch = the selection itself
+    w = wl.make_workload(3)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w)
+    s, adv, ret = P.gpu_front(w)
+    rows, off = umas.umas_ready_batch(s, w.traj_turn_off, 1)
+    n = int(st["model_rowsel_off"][-1])
+    assert np.array_equal(rows.cpu().numpy()[:n], st["rowsel"])
+    assert np.array_equal(off.cpu().numpy()[:, 0], st["model_rowsel_off"][:-1])
+    with pytest.raises(umas.UmasError):
+        umas.umas_ready_batch(s, w.traj_turn_off, 2, None, np.zeros(w.n_traj, np.int32))   # not a permutation
+
+
+def test_minibatch_gradients_accumulate():
+    """The update over a ready batch: one call per minibatch, gradients of the LM head accumulated."""
+    w, st, s, adv_o, adv, rows, off, off_o, rows_o = ready_case(2, 3, 11, n_traj=8, tokens_per_turn=48, models=[(200, 1000, "bf16")])
+    t = w.model_tensors(0)
+    H, W, ids = P.to_dev(t["H"], torch.bfloat16), P.to_dev(t["W"], torch.bfloat16), P.to_dev(t["ids"])
+    n = w.model_ntok[0]
+    role_o = st["tok_role"][:n]
+    dW = torch.empty((1000, 200), dtype=torch.float32, device="cuda")
+    dW_o = np.zeros((1000, 200))
+    for k in range(3):
+        a, e = int(off_o[0, k]), int(off_o[0, k + 1])
+        rr_o = rows_o[a:e]
+        logp_o, lse_o, ent_o = orc.score(t["H"], t["W"], t["ids"], rr_o)
+        logp_old = (logp_o + t["noise"]).astype(np.float32)
+        stats_o, g_o = orc.ppo_loss(logp_o, logp_old, adv_o[:n], ent_o, rr_o, role_o, w.n_roles, w.clip_eps)
+        dH_o, dWk = orc.lm_head_backward(t["H"], t["W"], t["ids"], lse_o, g_o, rr_o)
+        dW_o += dWk
+        stats, logp_new, dH, _ = umas.umas_ppo_loss_fwd_bwd(H, W, ids, rows[a:e], P.to_dev(logp_old), adv[:n].contiguous(),
+                                                            s.tok_role[:n].contiguous(), w.n_roles, w.clip_eps,
+                                                            accumulate_dW=(k > 0), dW=dW)
+        torch.cuda.synchronize()
+        sg = umas.read_stats(stats)
+        assert int(sg["n_scored"][0]) == e - a
+        assert abs(float(sg["loss"][0]) - stats_o[0, 0]) <= 1e-2 * max(abs(stats_o[0, 0]), 1e-3)
+        P.close(dH.float().cpu().numpy(), dH_o, 1e-2, f"dH of minibatch {k}")
+    P.close(dW.cpu().numpy(), dW_o, 1e-2, "accumulated dW")
