@@ -63,7 +63,7 @@ def stored_traffic(kernel):
     return k["read_bytes"] + k["written_bytes"]
 
 
-def hbm_kernels(umas, wl, torch, cfg, n_traj, iters=5):
+def hbm_kernels(umas, wl, torch, cfg, n_traj, iters=5, shaping=False):
     """Reward/routing and scan kernels on a batch-replicated instance: achieved GB/s on algorithmic bytes."""
     w = wl.make_workload(cfg, n_traj=n_traj)
     mask = torch.from_numpy(w.tok_mask).cuda()
@@ -89,12 +89,69 @@ def hbm_kernels(umas, wl, torch, cfg, n_traj, iters=5):
     route_ms = sum(prof[k][0] for k in route_names) / iters
     scan_bytes = (17 if value is not None else 13) * N
     route_bytes = (1 + 8 + 4 + 4 + 1 + 4) * N + 4 * scored
-    return {"workload": f"{w.name} x{n_traj} trajectories", "tokens": N,
+    # the steps around the advantage step on the same instance: KL-penalised rewards, whitening, ready batch
+    extra = {}
+    if shaping:
+        logp = torch.empty(N, dtype=torch.float32, device="cuda").uniform_(-3.0, 0.0)
+        logp_ref = logp + 0.1 * torch.randn(N, device="cuda")
+        adv, _ = umas.umas_advantages(s, value, w.gamma, w.lam, w.gamma_turn, w.seg_mode)
+        order = np.random.default_rng(7).permutation(w.n_traj).astype(np.int32)
+        keep = (np.random.default_rng(8).random(w.n_traj) < 0.9).astype(np.uint8)
+
+        def run_extra():
+            umas.umas_kl_rewards(s.tok_reward, logp, logp_ref, s.tok_mask, 0.05)
+            umas.umas_whiten_advantages(adv, s.tok_mask, s.tok_role, w_off, w.n_roles, umas.WHITEN_MODEL_ROLE)
+            umas.umas_ready_batch(s, w.traj_turn_off, 8, keep, order)
+        w_off = s.model_tok_off.cpu().numpy()
+        run_extra()
+        torch.cuda.synchronize()
+        umas.profile_enable(True)
+        for _ in range(iters):
+            run_extra()
+        torch.cuda.synchronize()
+        p2 = umas.profile_read()
+        umas.profile_enable(False)
+        ms = lambda names: sum(p2[k][0] for k in p2 if k in names) / iters
+        kept_scored = scored * float(keep.mean())
+        for name, kernels, nbytes in (("kl_rewards", ("k_kl_rewards", "k_kl_mean"), 17 * N),
+                                      ("whiten_advantages", ("k_whiten_sums", "k_whiten_stats", "k_whiten_apply"), 22 * N),
+                                      ("ready_batch", ("k_zero_i64", "k_kept_flags", "k_kept_rank", "k_run_slices", "k_scan_tiles",
+                                                       "k_scan_rows", "k_scan_add", "k_mb_offsets", "k_mb_copy"), 8 * kept_scored)):
+            t = ms(kernels)
+            extra[name] = {"ms": t, "algorithmic_bytes": nbytes, "GBps": nbytes / t / 1e6,
+                           "frac_of_hbm_peak": nbytes / t / 1e6 / PEAK_HBM_GBPS}
+    return {"workload": f"{w.name} x{n_traj} trajectories", "tokens": N, **extra,
             "scan": {"ms": scan_ms, "algorithmic_bytes": scan_bytes, "GBps": scan_bytes / scan_ms / 1e6,
                      "frac_of_hbm_peak": scan_bytes / scan_ms / 1e6 / PEAK_HBM_GBPS},
             "route_place": {"ms": route_ms, "algorithmic_bytes": route_bytes, "GBps": route_bytes / route_ms / 1e6,
                             "frac_of_hbm_peak": route_bytes / route_ms / 1e6 / PEAK_HBM_GBPS},
             "kernels_ms": {k: v[0] / iters for k, v in prof.items()}}
+
+
+def critic_kernel(umas, torch, H, n_sel, d, rep=8, iters=5):
+    """The critic's fused pass (value head, clipped value loss, backward) on the benchmark's hidden states
+    repeated `rep` times, so that the rows exceed the caches: bytes = read H once + write dH once."""
+    Hr = H.repeat(rep, 1)
+    n = Hr.shape[0]
+    g = torch.Generator(device="cuda").manual_seed(3)
+    wv = (0.02 * torch.randn(d, device="cuda", generator=g)).to(H.dtype)
+    v_old = 0.1 * torch.randn(n, device="cuda", generator=g)
+    ret = 0.5 * torch.randn(n, device="cuda", generator=g)
+    dH = torch.empty_like(Hr)
+    for _ in range(2):
+        umas.umas_value_loss_fwd_bwd(Hr, wv, 0.0, None, v_old, ret, None, 0, 0.2, dH=dH)
+    torch.cuda.synchronize()
+    umas.profile_enable(True)
+    for _ in range(iters):
+        umas.umas_value_loss_fwd_bwd(Hr, wv, 0.0, None, v_old, ret, None, 0, 0.2, dH=dH)
+    torch.cuda.synchronize()
+    prof = umas.profile_read()
+    umas.profile_enable(False)
+    t = prof["k_value_rows"][0] / iters
+    nbytes = 2 * n * d * H.element_size()
+    return {"rows": n, "d": d, "kernel": "k_value_rows", "ms": t, "algorithmic_bytes": nbytes, "GBps": nbytes / t / 1e6,
+            "frac_of_hbm_peak": nbytes / t / 1e6 / PEAK_HBM_GBPS,
+            "all_kernels_ms": {k: v[0] / iters for k, v in prof.items()}}
 
 
 def main():
@@ -209,7 +266,8 @@ def main():
     if not args.no_hbm:
         del ws, dW, dH
         torch.cuda.empty_cache()
-        out["hbm_kernels"] = [hbm_kernels(umas, wl, torch, 4, 8192), hbm_kernels(umas, wl, torch, 1, 131072)]
+        out["hbm_kernels"] = [hbm_kernels(umas, wl, torch, 4, 8192), hbm_kernels(umas, wl, torch, 1, 131072, shaping=True)]
+        out["critic"] = critic_kernel(umas, torch, H, n_sel, spec.d)
     if args.cpu_rows > 0:
         out["cpu_baseline"] = cpu_baseline(w, t, args.cpu_rows)
     print(json.dumps(out))

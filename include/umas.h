@@ -215,7 +215,7 @@ umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_dtype dtype
  *   g = dloss/dV = (V - R) / n_sel where the unclipped term is the larger one (ties included), else 0
  *   dH_i = g_i w;  dw = sum_i g_i h_i;  db = sum_i g_i
  * H [n_rows, d] and w [d] are DEVICE arrays of `dtype`, 16-byte aligned; d is a multiple of 8 (bf16) or
- * 4 (float32) and at most 8192; rowsel / n_sel select rows as in umas_policy_logprobs. */
+ * 4 (float32) and at most 8192 (bf16) or 4096 (float32); rowsel / n_sel select rows as in umas_policy_logprobs. */
 typedef struct umas_value_stats {
   float loss;         /* mean over the rows of 1/2 max((V-R)^2, (Vc-R)^2) */
   float clip_frac;    /* rows whose clipped term is strictly larger */

@@ -15,23 +15,57 @@
 namespace umas {
 namespace {
 
-// rank[b] = position of trajectory b among the kept trajectories in shuffled order, or -1; one block.
-__global__ void __launch_bounds__(1024)
-k_kept_rank(int n_traj, const int32_t* __restrict__ order, const uint8_t* __restrict__ keep, int32_t* __restrict__ rank,
-            int64_t* __restrict__ n_kept) {
-  __shared__ int32_t smem[32];
-  int32_t carry = 0;
-  for (int q0 = 0; q0 < n_traj; q0 += blockDim.x) {
-    const int q = q0 + threadIdx.x;
-    const int b = q < n_traj ? (order ? order[q] : q) : 0;
-    const int32_t f = (q < n_traj && (!keep || keep[b])) ? 1 : 0;
-    int32_t total;
-    const int32_t r = carry + block_excl_scan<int32_t>(f, smem, &total);
-    if (q < n_traj) rank[b] = f ? r : -1;
-    carry += total;
-    __syncthreads();
+constexpr int kScanItems = 8;
+constexpr int kScanTile = 256 * kScanItems;       // entries one workgroup scans
+
+// flag[q] = 1 when the q-th trajectory of the shuffle is kept.
+__global__ void k_kept_flags(int n_traj, const int32_t* __restrict__ order, const uint8_t* __restrict__ keep,
+                             int64_t* __restrict__ flag) {
+  const int q = blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= n_traj) return;
+  const int b = order ? order[q] : q;
+  flag[q] = (!keep || keep[b]) ? 1 : 0;
+}
+// rank[b] = position of trajectory b among the kept trajectories in shuffled order (pos = scanned flags), or -1.
+__global__ void k_kept_rank(int n_traj, const int32_t* __restrict__ order, const uint8_t* __restrict__ keep,
+                            const int64_t* __restrict__ pos, int32_t* __restrict__ rank) {
+  const int q = blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= n_traj) return;
+  const int b = order ? order[q] : q;
+  rank[b] = (!keep || keep[b]) ? static_cast<int32_t>(pos[q]) : -1;
+}
+
+// Exclusive prefix sums of the rows of data[nrows][n] in three steps: every workgroup scans its tile of a row in
+// place and leaves the tile's total, the totals of a row are scanned by one workgroup, the tiles add their offset.
+__global__ void __launch_bounds__(256)
+k_scan_tiles(int64_t* __restrict__ data, int n, int ntile, int64_t* __restrict__ tile_sum) {
+  __shared__ int64_t smem[32];
+  int64_t* row = data + static_cast<size_t>(blockIdx.y) * n;
+  const int base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
+  int64_t v[kScanItems];
+  int64_t sum = 0;
+#pragma unroll
+  for (int k = 0; k < kScanItems; ++k) {
+    v[k] = base + k < n ? row[base + k] : 0;
+    sum += v[k];
   }
-  if (threadIdx.x == 0) *n_kept = carry;
+  int64_t total;
+  int64_t r = block_excl_scan<int64_t>(sum, smem, &total);
+#pragma unroll
+  for (int k = 0; k < kScanItems; ++k) {
+    if (base + k < n) row[base + k] = r;
+    r += v[k];
+  }
+  if (threadIdx.x == 0) tile_sum[static_cast<size_t>(blockIdx.y) * ntile + blockIdx.x] = total;
+}
+__global__ void __launch_bounds__(256)
+k_scan_add(int64_t* __restrict__ data, int n, int ntile, const int64_t* __restrict__ tile_off) {
+  int64_t* row = data + static_cast<size_t>(blockIdx.y) * n;
+  const int64_t off = tile_off[static_cast<size_t>(blockIdx.y) * ntile + blockIdx.x];
+  const int base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
+#pragma unroll
+  for (int k = 0; k < kScanItems; ++k)
+    if (base + k < n) row[base + k] += off;
 }
 
 // First index i in [0, n) with a[i] >= x (n if none).
@@ -71,18 +105,28 @@ __global__ void k_run_slices(int n_turns, int n_traj, int n_models, const int64_
   src_mq[static_cast<size_t>(m) * n_traj + q] = ra + i0;
 }
 
-// In-place exclusive prefix sum of each row of data[nrows][n]; one block per row.
+// In-place exclusive prefix sum of each row of data[nrows][n]; one block per row, 8 entries per thread per round.
 __global__ void __launch_bounds__(1024)
 k_scan_rows(int64_t* __restrict__ data, int n, int64_t* __restrict__ totals) {
   __shared__ int64_t smem[32];
   int64_t* row = data + static_cast<size_t>(blockIdx.x) * n;
   int64_t carry = 0;
-  for (int i0 = 0; i0 < n; i0 += blockDim.x) {
-    const int i = i0 + threadIdx.x;
-    const int64_t v = i < n ? row[i] : 0;
+  for (int i0 = 0; i0 < n; i0 += blockDim.x * kScanItems) {
+    const int base = i0 + threadIdx.x * kScanItems;
+    int64_t v[kScanItems];
+    int64_t sum = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) {
+      v[k] = base + k < n ? row[base + k] : 0;
+      sum += v[k];
+    }
     int64_t total;
-    const int64_t r = carry + block_excl_scan<int64_t>(v, smem, &total);
-    if (i < n) row[i] = r;
+    int64_t r = carry + block_excl_scan<int64_t>(sum, smem, &total);
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) {
+      if (base + k < n) row[base + k] = r;
+      r += v[k];
+    }
     carry += total;
     __syncthreads();
   }
@@ -122,7 +166,14 @@ k_mb_copy(int n_models, int n_traj, const int64_t* __restrict__ n_kept_p, const 
   const int64_t dst = base + scan_mq[at];
   const int64_t len = (q + 1 < n_traj ? scan_mq[at + 1] : totals[m]) - scan_mq[at];
   const int64_t src = src_mq[at];
-  for (int64_t i = lane; i < len; i += kWave) mb_rowsel[dst + i] = rowsel[src + i];
+  for (int64_t i0 = lane; i0 < len; i0 += 4 * kWave) {       // four loads in flight per lane
+    int32_t v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = i0 + k * kWave < len ? rowsel[src + i0 + k * kWave] : 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (i0 + k * kWave < len) mb_rowsel[dst + i0 + k * kWave] = v[k];
+  }
 }
 
 __global__ void k_zero_i64(int64_t* __restrict__ p, int64_t n) {
@@ -136,7 +187,9 @@ struct BatchWs {
   int32_t* order;
   uint8_t* keep;
   int32_t* rank;
+  int64_t* flag;     // [n_traj] kept flags in shuffled order, scanned in place
   int64_t* n_kept;
+  int64_t* tile_sum; // [n_models][tiles] totals of the scan tiles, scanned in place
   int64_t* cnt_mq;   // [n_models][n_traj], scanned in place
   int64_t* src_mq;   // [n_models][n_traj]
   int64_t* totals;   // [n_models]
@@ -146,7 +199,9 @@ size_t carve_batch(Carver& c, BatchWs& w, int n_traj, int n_models) {
   w.order = c.take<int32_t>(n_traj);
   w.keep = c.take<uint8_t>(n_traj);
   w.rank = c.take<int32_t>(n_traj);
+  w.flag = c.take<int64_t>(n_traj);
   w.n_kept = c.take<int64_t>(1);
+  w.tile_sum = c.take<int64_t>(static_cast<size_t>(n_models) * cdiv(n_traj > 0 ? n_traj : 1, kScanTile));
   w.cnt_mq = c.take<int64_t>(static_cast<size_t>(n_models) * n_traj);
   w.src_mq = c.take<int64_t>(static_cast<size_t>(n_models) * n_traj);
   w.totals = c.take<int64_t>(n_models);
@@ -205,17 +260,37 @@ extern "C" umas_status umas_ready_batch(const umas_streams* s, int32_t n_models,
   hipLaunchKernelGGL(k_zero_i64, dim3(cdiv(n_mq > 0 ? n_mq : 1, 256) < 4096 ? cdiv(n_mq > 0 ? n_mq : 1, 256) : 4096), dim3(256), 0,
                      st, w.cnt_mq, n_mq);
   UMAS_LAUNCHED("k_zero_i64");
-  hipLaunchKernelGGL(k_kept_rank, dim3(1), dim3(1024), 0, st, n_traj, traj_order ? w.order : nullptr,
-                     traj_keep ? w.keep : nullptr, w.rank, w.n_kept);
-  UMAS_LAUNCHED("k_kept_rank");
+  const int ntile = static_cast<int>(cdiv(n_traj > 0 ? n_traj : 1, kScanTile));
+  // exclusive scan of data[rows][n_traj]; totals[r] receives the sum of row r
+  auto scan = [&](int64_t* data, int rows, int64_t* totals) -> umas_status {
+    hipLaunchKernelGGL(k_scan_tiles, dim3(ntile, rows), dim3(256), 0, st, data, n_traj, ntile, w.tile_sum);
+    UMAS_LAUNCHED("k_scan_tiles");
+    hipLaunchKernelGGL(k_scan_rows, dim3(rows), dim3(1024), 0, st, w.tile_sum, ntile, totals);
+    UMAS_LAUNCHED("k_scan_rows");
+    hipLaunchKernelGGL(k_scan_add, dim3(ntile, rows), dim3(256), 0, st, data, n_traj, ntile, w.tile_sum);
+    UMAS_LAUNCHED("k_scan_add");
+    return UMAS_OK;
+  };
+  const int32_t* d_order = traj_order ? w.order : nullptr;
+  const uint8_t* d_keep = traj_keep ? w.keep : nullptr;
+  if (n_traj > 0) {
+    hipLaunchKernelGGL(k_kept_flags, dim3(cdiv(n_traj, 256)), dim3(256), 0, st, n_traj, d_order, d_keep, w.flag);
+    UMAS_LAUNCHED("k_kept_flags");
+  }
+  umas_status ss = scan(w.flag, 1, w.n_kept);
+  if (ss != UMAS_OK) return ss;
+  if (n_traj > 0) {
+    hipLaunchKernelGGL(k_kept_rank, dim3(cdiv(n_traj, 256)), dim3(256), 0, st, n_traj, d_order, d_keep, w.flag, w.rank);
+    UMAS_LAUNCHED("k_kept_rank");
+  }
   if (n_turns > 0 && n_traj > 0) {
     hipLaunchKernelGGL(k_run_slices, dim3(cdiv(n_turns, 256)), dim3(256), 0, st, n_turns, n_traj, n_models, s->traj_seg_off,
                        s->model_trajrun_off, s->model_tok_off, s->model_rowsel_off, s->rowsel, s->tok_turn, w.traj_turn_off,
                        w.rank, w.cnt_mq, w.src_mq);
     UMAS_LAUNCHED("k_run_slices");
   }
-  hipLaunchKernelGGL(k_scan_rows, dim3(n_models), dim3(1024), 0, st, w.cnt_mq, n_traj, w.totals);
-  UMAS_LAUNCHED("k_scan_rows");
+  ss = scan(w.cnt_mq, n_models, w.totals);
+  if (ss != UMAS_OK) return ss;
   hipLaunchKernelGGL(k_mb_offsets, dim3(cdiv(static_cast<size_t>(n_models) * (n_minibatch + 1), 256)), dim3(256), 0, st,
                      n_models, n_minibatch, n_traj, w.n_kept, w.cnt_mq, w.totals, mb_off);
   UMAS_LAUNCHED("k_mb_offsets");

@@ -6,10 +6,10 @@
 //   Vc = clip(V, V_old - eps, V_old + eps);  L = 1/2 max((V - R)^2, (Vc - R)^2);  loss = mean L
 //   g = dloss/dV = (V - R) / S where the unclipped term is the larger one (ties included), else 0
 //   dH_i = g_i w,  dw = sum_i g_i h_i,  db = sum_i g_i
-// The whole step is one pass over H: a workgroup stages a chunk of rows in LDS, one wavefront per row
-// forms the dot product and the row's g, then every thread walks its own columns over the chunk's
-// rows (dH written, dw accumulated in registers).  Per-workgroup partial sums are reduced by a second
-// small kernel in a fixed order, so results do not depend on scheduling.
+// The whole step is one pass over H: one wavefront per row keeps the row in registers, forms the dot
+// product and the row's g, writes dH and adds g h to its dw accumulators; the next row is already in
+// flight.  Per-wavefront partial sums are reduced by small kernels in a fixed order, so results do not
+// depend on scheduling.
 #include "umas_common.h"
 
 namespace umas {
@@ -17,10 +17,8 @@ namespace {
 
 constexpr int kVT = 256;                 // threads per workgroup
 constexpr int kVWaves = kVT / kWave;
-constexpr int kMaxChunkRows = 16;
-constexpr int kChunkBytes = 64 * 1024;   // rows staged per chunk
-constexpr int kMaxD = 8192;              // 32 accumulators per thread cover d <= 8192
-constexpr int kMaxGrid = 1024;
+constexpr int kMaxKV = 16;               // 16-byte column vectors per lane: d <= 64 * 16 * (8 bf16 | 4 float)
+constexpr int kMaxGrid = 1024;           // workgroups of the row kernel: one resident round at four per CU
 constexpr int kVStat = 4;                // (sum L, clipped rows, sum V, rows)
 
 __device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
@@ -30,8 +28,8 @@ __device__ __forceinline__ uint16_t f2bf(float x) { return __builtin_bit_cast(ui
 template <typename T> struct Vec;
 template <> struct Vec<uint16_t> {
   static constexpr int N = 8;
-  __device__ static void load(const uint16_t* p, float (&x)[8]) {
-    const uint4 v = *reinterpret_cast<const uint4*>(p);
+  __device__ static void load(const uint16_t* p, float (&x)[8]) { unpack(*reinterpret_cast<const uint4*>(p), x); }
+  __device__ static void unpack(const uint4& v, float (&x)[8]) {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -48,9 +46,9 @@ template <> struct Vec<uint16_t> {
 };
 template <> struct Vec<float> {
   static constexpr int N = 4;
-  __device__ static void load(const float* p, float (&x)[4]) {
-    const float4 v = *reinterpret_cast<const float4*>(p);
-    x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+  __device__ static void load(const float* p, float (&x)[4]) { unpack(*reinterpret_cast<const uint4*>(p), x); }
+  __device__ static void unpack(const uint4& v, float (&x)[4]) {
+    x[0] = __uint_as_float(v.x); x[1] = __uint_as_float(v.y); x[2] = __uint_as_float(v.z); x[3] = __uint_as_float(v.w);
   }
   __device__ static void store(float* p, const float (&x)[4]) { *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]); }
 };
@@ -83,122 +81,139 @@ k_value_fwd(const T* __restrict__ H, const T* __restrict__ w, float bias, int d,
   if (lane == 0) value[row] = acc + bias;
 }
 
-// Loss and backward.  LDS (dynamic): rows [rc][d] in T, w as float [d], g [rc], statistics.
-template <typename T>
+// Loss and backward, one wavefront per row.  Lane l owns the 16-byte column vectors l, l + 64, ... (KV of them):
+// it keeps its part of w, of the current row and of the next row (prefetched) in registers, and its part of
+// dw in float accumulators over all rows of the wavefront.  No barrier in the row loop.
+template <typename T, int KV>
 __global__ void __launch_bounds__(kVT)
 k_value_rows(const T* __restrict__ H, const T* __restrict__ w, float bias, int d, const int32_t* __restrict__ rowsel,
-             int64_t n_sel, int rc, const float* __restrict__ value_old, const float* __restrict__ ret,
+             int64_t n_sel, int64_t rows_per_block, const float* __restrict__ value_old, const float* __restrict__ ret,
              const int32_t* __restrict__ tok_role, int n_roles, float clip_eps, float* __restrict__ value_new,
              T* __restrict__ dH, int accumulate_dH, float* __restrict__ part_dw, double* __restrict__ blk_stats) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char s_raw[];
+  __shared__ double s_acc[(1 + UMAS_MAX_ROLES) * kVStat];
   constexpr int N = Vec<T>::N;
-  const int nvec = d / N;                       // 16-byte vectors per row
-  T* s_rows = reinterpret_cast<T*>(s_raw);
-  float* s_w = reinterpret_cast<float*>(s_raw + static_cast<size_t>(rc) * d * sizeof(T));
-  float* s_g = s_w + d;
-  double* s_acc = reinterpret_cast<double*>(s_g + kMaxChunkRows);
+  const int nvec = d / N;
   const int nacc = (1 + n_roles) * kVStat;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   for (int i = threadIdx.x; i < nacc; i += kVT) s_acc[i] = 0.0;
-  for (int v = threadIdx.x; v < nvec; v += kVT) {
-    float x[N];
-    Vec<T>::load(w + v * N, x);
+  __syncthreads();
+  // w and the rows stay packed as loaded (16 bytes per vector) and are unpacked where they are used
+  uint4 wp[KV];
+  float acc[KV][N];
 #pragma unroll
-    for (int i = 0; i < N; ++i) s_w[v * N + i] = x[i];
-  }
-  constexpr int kAcc = kMaxD / (kVT * N);       // column vectors per thread
-  float acc[kAcc][N];
-#pragma unroll
-  for (int k = 0; k < kAcc; ++k)
+  for (int k = 0; k < KV; ++k) {
+    const int cv = lane + k * kWave;
 #pragma unroll
     for (int i = 0; i < N; ++i) acc[k][i] = 0.f;
+    wp[k] = make_uint4(0u, 0u, 0u, 0u);
+    if (cv < nvec) wp[k] = *reinterpret_cast<const uint4*>(w + cv * N);
+  }
   float gsum = 0.f;
   const float inv_s = 1.f / static_cast<float>(n_sel);
+  const int64_t r_begin = static_cast<int64_t>(blockIdx.x) * rows_per_block;
+  const int64_t r_end = r_begin + rows_per_block < n_sel ? r_begin + rows_per_block : n_sel;
 
-  const int64_t n_chunks = (n_sel + rc - 1) / rc;
-  for (int64_t ch = blockIdx.x; ch < n_chunks; ch += gridDim.x) {
-    const int64_t c0 = ch * rc;
-    const int rows = n_sel - c0 < rc ? static_cast<int>(n_sel - c0) : rc;
-    __syncthreads();                            // the previous chunk's readers are done (and s_w, s_acc are set)
-    for (int v = threadIdx.x; v < rows * nvec; v += kVT) {
-      const int r = v / nvec, cv = v - r * nvec;
-      const int64_t row = rowsel ? rowsel[c0 + r] : c0 + r;
-      *reinterpret_cast<uint4*>(s_rows + static_cast<size_t>(r) * d + cv * N) =
-          *reinterpret_cast<const uint4*>(H + row * d + cv * N);
+  uint4 cur[KV], nxt[KV];
+  auto fetch = [&](int64_t n) {
+    const int64_t row = rowsel ? rowsel[n] : n;
+#pragma unroll
+    for (int k = 0; k < KV; ++k) {
+      const int cv = lane + k * kWave;
+      nxt[k] = make_uint4(0u, 0u, 0u, 0u);
+      if (cv < nvec) nxt[k] = *reinterpret_cast<const uint4*>(H + row * d + cv * N);
     }
-    __syncthreads();
-    for (int r = wave; r < rows; r += kVWaves) {
-      float dot = 0.f;
-      for (int cv = lane; cv < nvec; cv += kWave) {
-        float x[N];
-        Vec<T>::load(s_rows + static_cast<size_t>(r) * d + cv * N, x);
+    return row;
+  };
+  int64_t n = r_begin + wave;
+  int64_t row_next = n < r_end ? fetch(n) : 0;
+  for (; n < r_end; n += kVWaves) {
+    const int64_t row = row_next;
+    float dot = 0.f;
 #pragma unroll
-        for (int i = 0; i < N; ++i) dot = fmaf(x[i], s_w[cv * N + i], dot);
-      }
-      dot = wave_sum(dot);
-      if (lane == 0) {
-        const int64_t row = rowsel ? rowsel[c0 + r] : c0 + r;
-        const float V = dot + bias, vo = value_old[row], R = ret[row];
-        const float vc = fminf(fmaxf(V, vo - clip_eps), vo + clip_eps);   // V itself inside the range: an exact tie
-        const float lu = (V - R) * (V - R), lc = (vc - R) * (vc - R);
-        const bool unclipped = lu >= lc;
-        s_g[r] = unclipped ? (V - R) * inv_s : 0.f;
-        if (value_new) value_new[row] = V;
-        const int role = (tok_role && n_roles > 0) ? tok_role[row] : -1;
-        for (int pass = 0; pass < 2; ++pass) {
-          if (pass == 1 && (role < 0 || role >= n_roles)) break;
-          double* a = s_acc + (pass == 0 ? 0 : (1 + role) * kVStat);
-          atomicAdd(a + 0, static_cast<double>(0.5f * (unclipped ? lu : lc)));
-          atomicAdd(a + 1, unclipped ? 0.0 : 1.0);
-          atomicAdd(a + 2, static_cast<double>(V));
-          atomicAdd(a + 3, 1.0);
-        }
+    for (int k = 0; k < KV; ++k) {
+      cur[k] = nxt[k];
+      float x[N], y[N];
+      Vec<T>::unpack(cur[k], x);
+      Vec<T>::unpack(wp[k], y);
+#pragma unroll
+      for (int i = 0; i < N; ++i) dot = fmaf(x[i], y[i], dot);
+    }
+    if (n + kVWaves < r_end) row_next = fetch(n + kVWaves);     // in flight while this row is finished
+    dot = wave_sum(dot);
+    const float V = dot + bias, vo = value_old[row], R = ret[row];
+    const float vc = fminf(fmaxf(V, vo - clip_eps), vo + clip_eps);   // V itself inside the range: an exact tie
+    const float lu = (V - R) * (V - R), lc = (vc - R) * (vc - R);
+    const bool unclipped = lu >= lc;
+    const float g = unclipped ? (V - R) * inv_s : 0.f;
+    gsum += g;
+    if (lane == 0) {
+      if (value_new) value_new[row] = V;
+      const int role = (tok_role && n_roles > 0) ? tok_role[row] : -1;
+      for (int pass = 0; pass < 2; ++pass) {
+        if (pass == 1 && (role < 0 || role >= n_roles)) break;
+        double* a = s_acc + (pass == 0 ? 0 : (1 + role) * kVStat);
+        atomicAdd(a + 0, static_cast<double>(0.5f * (unclipped ? lu : lc)));
+        atomicAdd(a + 1, unclipped ? 0.0 : 1.0);
+        atomicAdd(a + 2, static_cast<double>(V));
+        atomicAdd(a + 3, 1.0);
       }
     }
-    __syncthreads();
-    for (int r = 0; r < rows; ++r) {
-      const float g = s_g[r];
-      const int64_t row = rowsel ? rowsel[c0 + r] : c0 + r;
-      gsum += g;
 #pragma unroll
-      for (int k = 0; k < kAcc; ++k) {
-        const int cv = threadIdx.x + k * kVT;
-        if (cv < nvec) {
-          float x[N], o[N];
-          Vec<T>::load(s_rows + static_cast<size_t>(r) * d + cv * N, x);
-          if (accumulate_dH) Vec<T>::load(dH + row * d + cv * N, o);
+    for (int k = 0; k < KV; ++k) {
+      const int cv = lane + k * kWave;
+      if (cv < nvec) {
+        float x[N], y[N], o[N];
+        Vec<T>::unpack(cur[k], x);
+        Vec<T>::unpack(wp[k], y);
+        if (accumulate_dH) Vec<T>::load(dH + row * d + cv * N, o);
 #pragma unroll
-          for (int i = 0; i < N; ++i) {
-            acc[k][i] = fmaf(g, x[i], acc[k][i]);
-            o[i] = accumulate_dH ? o[i] + g * s_w[cv * N + i] : g * s_w[cv * N + i];
-          }
-          Vec<T>::store(dH + row * d + cv * N, o);
+        for (int i = 0; i < N; ++i) {
+          acc[k][i] = fmaf(g, x[i], acc[k][i]);
+          o[i] = accumulate_dH ? o[i] + g * y[i] : g * y[i];
         }
+        Vec<T>::store(dH + row * d + cv * N, o);
       }
     }
   }
-  float* pd = part_dw + static_cast<size_t>(blockIdx.x) * (d + 1);
+  // every wavefront leaves its own partial row: [blocks * waves][d + 1]
+  float* pd = part_dw + (static_cast<size_t>(blockIdx.x) * kVWaves + wave) * (d + 1);
 #pragma unroll
-  for (int k = 0; k < kAcc; ++k) {
-    const int cv = threadIdx.x + k * kVT;
+  for (int k = 0; k < KV; ++k) {
+    const int cv = lane + k * kWave;
     if (cv < nvec)
 #pragma unroll
       for (int i = 0; i < N; ++i) pd[cv * N + i] = acc[k][i];
   }
-  if (threadIdx.x == 0) pd[d] = gsum;
+  if (lane == 0) pd[d] = gsum;
   __syncthreads();
   for (int i = threadIdx.x; i < nacc; i += kVT) blk_stats[static_cast<size_t>(blockIdx.x) * nacc + i] = s_acc[i];
 }
 
-// dw[j] (+)= sum_b part[b][j] for j < d, db likewise from column d; the statistics from the block sums.
+// out[o][j] = sum of the rows o*group .. o*group + group - 1 of in[n_in][ld] (fixed order); the last stage adds
+// into or overwrites dw (columns < d) and db (column d).
 __global__ void __launch_bounds__(256)
-k_value_reduce(const float* __restrict__ part_dw, int nblk, int d, int accumulate, float* __restrict__ dw, float* __restrict__ db) {
+k_value_reduce(const float* __restrict__ in, int n_in, int ld, int group, float* __restrict__ out, int d, int final_stage,
+               int accumulate, float* __restrict__ dw, float* __restrict__ db) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j > d) return;
-  float s = 0.f;
-  for (int b = 0; b < nblk; ++b) s += part_dw[static_cast<size_t>(b) * (d + 1) + j];
-  float* dst = j < d ? dw + j : db;
-  if (dst) *dst = accumulate ? *dst + s : s;
+  const int o = blockIdx.y;
+  if (j >= ld) return;
+  const int b0 = o * group, b1 = b0 + group < n_in ? b0 + group : n_in;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int b = b0;
+  for (; b + 4 <= b1; b += 4) {
+    s0 += in[static_cast<size_t>(b) * ld + j];
+    s1 += in[static_cast<size_t>(b + 1) * ld + j];
+    s2 += in[static_cast<size_t>(b + 2) * ld + j];
+    s3 += in[static_cast<size_t>(b + 3) * ld + j];
+  }
+  for (; b < b1; ++b) s0 += in[static_cast<size_t>(b) * ld + j];
+  const float s = (s0 + s1) + (s2 + s3);
+  if (!final_stage) {
+    out[static_cast<size_t>(o) * ld + j] = s;
+  } else {
+    float* dst = j < d ? dw + j : db;
+    if (dst) *dst = accumulate ? *dst + s : s;
+  }
 }
 __global__ void __launch_bounds__(256)
 k_value_stats(int nblk, int n_roles, const double* __restrict__ blk_stats, umas_value_stats* __restrict__ stats) {
@@ -224,13 +239,28 @@ k_value_stats(int nblk, int n_roles, const double* __restrict__ blk_stats, umas_
   }
 }
 
-int chunk_rows(int d, size_t esz) {
-  const int rc = static_cast<int>(kChunkBytes / (static_cast<size_t>(d) * esz));
-  return rc < 1 ? 1 : rc > kMaxChunkRows ? kMaxChunkRows : rc;
+constexpr int kReduceGroup = 64;
+unsigned value_grid(int64_t n_sel) {
+  const int64_t b = (n_sel + kVWaves - 1) / kVWaves;
+  return static_cast<unsigned>(b < 1 ? 1 : b > kMaxGrid ? kMaxGrid : b);
 }
-unsigned value_grid(int64_t n_sel, int rc) {
-  const int64_t n_chunks = (n_sel + rc - 1) / rc;
-  return static_cast<unsigned>(n_chunks < 1 ? 1 : n_chunks > kMaxGrid ? kMaxGrid : n_chunks);
+int max_d(umas_dtype dt) { return dt == UMAS_BF16 ? kWave * kMaxKV * 8 : kWave * kMaxKV * 4; }
+
+template <typename T>
+void launch_value_rows(int kv, unsigned grid, hipStream_t st, const void* H, const void* w, float bias, int d,
+                       const int32_t* rowsel, int64_t n_sel, int64_t rpb, const float* value_old, const float* ret,
+                       const int32_t* tok_role, int n_roles, float clip_eps, float* value_new, void* dH, int acc_dH,
+                       float* part_dw, double* blk_stats) {
+#define UMAS_VALUE_CASE(K)                                                                                              \
+  hipLaunchKernelGGL((k_value_rows<T, K>), dim3(grid), dim3(kVT), 0, st, static_cast<const T*>(H), static_cast<const T*>(w), \
+                     bias, d, rowsel, n_sel, rpb, value_old, ret, tok_role, n_roles, clip_eps, value_new,               \
+                     static_cast<T*>(dH), acc_dH, part_dw, blk_stats)
+  if (kv <= 1) UMAS_VALUE_CASE(1);
+  else if (kv <= 2) UMAS_VALUE_CASE(2);
+  else if (kv <= 4) UMAS_VALUE_CASE(4);
+  else if (kv <= 8) UMAS_VALUE_CASE(8);
+  else UMAS_VALUE_CASE(16);
+#undef UMAS_VALUE_CASE
 }
 
 umas_status check_value_args(const void* H, const void* w, umas_dtype dt, int64_t n_rows, int d, const int32_t* rowsel,
@@ -239,7 +269,7 @@ umas_status check_value_args(const void* H, const void* w, umas_dtype dt, int64_
   UMAS_REQUIRE(n_rows >= 0 && n_sel >= 0 && n_sel <= n_rows, UMAS_EINVAL, "row counts must satisfy 0 <= n_sel <= n_rows");
   UMAS_REQUIRE(rowsel || n_sel == n_rows, UMAS_EINVAL, "rowsel is NULL but n_sel != n_rows");
   const int n = dt == UMAS_BF16 ? 8 : 4;
-  UMAS_REQUIRE(d >= n && d % n == 0 && d <= kMaxD, UMAS_ESHAPE, "d=%d must be a multiple of %d and at most %d", d, n, kMaxD);
+  UMAS_REQUIRE(d >= n && d % n == 0 && d <= max_d(dt), UMAS_ESHAPE, "d=%d must be a multiple of %d and at most %d", d, n, max_d(dt));
   UMAS_REQUIRE((H || n_rows == 0) && w, UMAS_EINVAL, "H and w must not be NULL");
   UMAS_REQUIRE(reinterpret_cast<uintptr_t>(H) % 16 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0, UMAS_EINVAL,
                "H and w must be 16-byte aligned");
@@ -253,9 +283,11 @@ using namespace umas;
 
 extern "C" size_t umas_value_workspace_bytes(int64_t n_sel, int32_t d, umas_dtype dtype, int32_t n_roles) {
   if (n_sel < 0 || d < 1 || n_roles < 0) return 0;
-  const unsigned grid = value_grid(n_sel, chunk_rows(d, dtype == UMAS_BF16 ? 2 : 4));
+  (void)dtype;
+  const unsigned grid = value_grid(n_sel);
   Carver c(nullptr);
-  c.take<float>(static_cast<size_t>(grid) * (d + 1));
+  c.take<float>(static_cast<size_t>(grid) * kVWaves * (d + 1));                                  // one partial row per wavefront
+  c.take<float>(static_cast<size_t>(cdiv(grid * kVWaves, kReduceGroup)) * (d + 1));             // first reduction stage
   c.take<double>(static_cast<size_t>(grid) * (1 + n_roles) * kVStat);
   return c.off;
 }
@@ -302,10 +334,11 @@ extern "C" umas_status umas_value_loss_fwd_bwd(const void* H, const void* w, flo
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   prof_mark(st);
   const size_t esz = dtype == UMAS_BF16 ? 2 : 4;
-  const int rc = chunk_rows(d, esz);
-  const unsigned grid = value_grid(n_sel, rc);
+  const unsigned grid = value_grid(n_sel);
+  const int n_part = static_cast<int>(grid) * kVWaves, n_part2 = static_cast<int>(cdiv(n_part, kReduceGroup));
   Carver c(workspace);
-  float* part_dw = c.take<float>(static_cast<size_t>(grid) * (d + 1));
+  float* part_dw = c.take<float>(static_cast<size_t>(n_part) * (d + 1));
+  float* part2 = c.take<float>(static_cast<size_t>(n_part2) * (d + 1));
   double* blk_stats = c.take<double>(static_cast<size_t>(grid) * (1 + n_roles) * kVStat);
 
   auto zero = [&](void* p, size_t bytes) -> hipError_t {
@@ -321,28 +354,27 @@ extern "C" umas_status umas_value_loss_fwd_bwd(const void* H, const void* w, flo
     if (value_new) UMAS_HIP(zero(value_new, n_rows * sizeof(float)));
     if (!accumulate_dH) UMAS_HIP(zero(dH, static_cast<size_t>(n_rows) * d * esz));
   }
-  // an empty selection still defines the outputs: zero partials give zero statistics and gradients
-  UMAS_HIP(zero(part_dw, static_cast<size_t>(grid) * (d + 1) * sizeof(float)));
-  UMAS_HIP(zero(blk_stats, static_cast<size_t>(grid) * (1 + n_roles) * kVStat * sizeof(double)));
   if (n_sel > 0) {
-    const size_t lds = static_cast<size_t>(rc) * d * esz + static_cast<size_t>(d) * sizeof(float) +
-                       kMaxChunkRows * sizeof(float) + static_cast<size_t>(1 + n_roles) * kVStat * sizeof(double);
-    // more than 64 KB of dynamic LDS has to be asked for
-    const void* fn = dtype == UMAS_BF16 ? reinterpret_cast<const void*>(&k_value_rows<uint16_t>)
-                                        : reinterpret_cast<const void*>(&k_value_rows<float>);
-    UMAS_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+    const int64_t rpb = (n_sel + grid - 1) / grid;                 // rows per workgroup; every wavefront writes its partial row
+    const int nvec = d / (dtype == UMAS_BF16 ? 8 : 4);
+    const int kv = (nvec + kWave - 1) / kWave;
     if (dtype == UMAS_BF16)
-      hipLaunchKernelGGL(k_value_rows<uint16_t>, dim3(grid), dim3(kVT), lds, st, static_cast<const uint16_t*>(H),
-                         static_cast<const uint16_t*>(w), bias, d, rowsel, n_sel, rc, value_old, ret, tok_role, n_roles,
-                         clip_eps_v, value_new, static_cast<uint16_t*>(dH), accumulate_dH, part_dw, blk_stats);
+      launch_value_rows<uint16_t>(kv, grid, st, H, w, bias, d, rowsel, n_sel, rpb, value_old, ret, tok_role, n_roles,
+                                  clip_eps_v, value_new, dH, accumulate_dH, part_dw, blk_stats);
     else
-      hipLaunchKernelGGL(k_value_rows<float>, dim3(grid), dim3(kVT), lds, st, static_cast<const float*>(H),
-                         static_cast<const float*>(w), bias, d, rowsel, n_sel, rc, value_old, ret, tok_role, n_roles,
-                         clip_eps_v, value_new, static_cast<float*>(dH), accumulate_dH, part_dw, blk_stats);
+      launch_value_rows<float>(kv, grid, st, H, w, bias, d, rowsel, n_sel, rpb, value_old, ret, tok_role, n_roles,
+                               clip_eps_v, value_new, dH, accumulate_dH, part_dw, blk_stats);
     UMAS_LAUNCHED("k_value_rows");
+  } else {
+    // an empty selection still defines the outputs: zero partials give zero statistics and gradients
+    UMAS_HIP(zero(part_dw, static_cast<size_t>(n_part) * (d + 1) * sizeof(float)));
+    UMAS_HIP(zero(blk_stats, static_cast<size_t>(grid) * (1 + n_roles) * kVStat * sizeof(double)));
   }
-  hipLaunchKernelGGL(k_value_reduce, dim3(cdiv(d + 1, 256)), dim3(256), 0, st, part_dw, static_cast<int>(grid), d,
-                     accumulate_dw, dw, db);
+  hipLaunchKernelGGL(k_value_reduce, dim3(cdiv(d + 1, 256), n_part2), dim3(256), 0, st, part_dw, n_part, d + 1, kReduceGroup,
+                     part2, d, 0, 0, static_cast<float*>(nullptr), static_cast<float*>(nullptr));
+  UMAS_LAUNCHED("k_value_reduce");
+  hipLaunchKernelGGL(k_value_reduce, dim3(cdiv(d + 1, 256), 1), dim3(256), 0, st, part2, n_part2, d + 1, n_part2,
+                     static_cast<float*>(nullptr), d, 1, accumulate_dw, dw, db);
   UMAS_LAUNCHED("k_value_reduce");
   hipLaunchKernelGGL(k_value_stats, dim3(1), dim3(256), 0, st, static_cast<int>(grid), n_roles, blk_stats, stats);
   UMAS_LAUNCHED("k_value_stats");

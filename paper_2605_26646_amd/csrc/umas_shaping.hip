@@ -127,38 +127,70 @@ k_whiten_sums(int64_t n, const float* __restrict__ adv, const uint8_t* __restric
         rl[k] = (in && by_role) ? role[p0 + k] : 0;
       }
     }
-    // consecutive valid tokens of one group are summed in registers before they reach LDS
-    int cur = -1;
-    double sa = 0.0, sq = 0.0, sc = 0.0;
+    // group of each of the four tokens (-1 = not counted)
+    int gk[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
+      gk[k] = -1;
       if (!m[k] || (by_role && (rl[k] < 0 || rl[k] >= n_roles))) continue;   // a role outside [0, n_roles) joins no group
-      const int g = by_role ? model_of(mo, n_models, p0 + k) * n_roles + rl[k] : model_of(mo, n_models, p0 + k);
-      if (g != cur) {
-        if (cur >= 0) { atomicAdd(s_acc + 3 * cur, sa); atomicAdd(s_acc + 3 * cur + 1, sq); atomicAdd(s_acc + 3 * cur + 2, sc); }
-        cur = g; sa = sq = sc = 0.0;
-      }
-      const double x = static_cast<double>(a[k]);
-      sa += x; sq += x * x; sc += 1.0;
+      gk[k] = by_role ? model_of(mo, n_models, p0 + k) * n_roles + rl[k] : model_of(mo, n_models, p0 + k);
     }
-    if (cur >= 0) { atomicAdd(s_acc + 3 * cur, sa); atomicAdd(s_acc + 3 * cur + 1, sq); atomicAdd(s_acc + 3 * cur + 2, sc); }
+    // Usual case: every counted token of the wavefront's 256 belongs to one group.  Their sums are formed in
+    // float32 across the lanes (256 values: rounding far below the float32 inputs' own) and one lane adds them
+    // to the float64 accumulators; otherwise every lane adds its own tokens.
+    int g0 = -1;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) if (gk[k] >= 0 && g0 < 0) g0 = gk[k];
+    const unsigned long long have = __ballot(g0 >= 0);
+    const int gref = have ? __shfl(g0, __ffsll(static_cast<long long>(have)) - 1, kWave) : -1;
+    bool same = true;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) same = same && (gk[k] < 0 || gk[k] == gref);
+    if (__all(same)) {
+      if (have) {
+        float sa = 0.f, sq = 0.f, sc = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          if (gk[k] >= 0) { sa += a[k]; sq = fmaf(a[k], a[k], sq); sc += 1.f; }
+        sa = wave_sum(sa); sq = wave_sum(sq); sc = wave_sum(sc);
+        if ((threadIdx.x & (kWave - 1)) == 0) {
+          atomicAdd(s_acc + 3 * gref, static_cast<double>(sa));
+          atomicAdd(s_acc + 3 * gref + 1, static_cast<double>(sq));
+          atomicAdd(s_acc + 3 * gref + 2, static_cast<double>(sc));
+        }
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (gk[k] >= 0) {
+          const double x = static_cast<double>(a[k]);
+          atomicAdd(s_acc + 3 * gk[k], x); atomicAdd(s_acc + 3 * gk[k] + 1, x * x); atomicAdd(s_acc + 3 * gk[k] + 2, 1.0);
+        }
+    }
   }
   __syncthreads();
   for (int i = threadIdx.x; i < groups * 3; i += kST) blk[static_cast<size_t>(blockIdx.x) * groups * 3 + i] = s_acc[i];
 }
-// Per group: mean and 1/sqrt(var + eps) from the block sums (fixed order).
-__global__ void k_whiten_stats(const double* __restrict__ blk, int nblk, int groups, float eps, double2* __restrict__ mu_rstd) {
-  const int g = blockIdx.x * blockDim.x + threadIdx.x;
-  if (g >= groups) return;
-  double sa = 0.0, sq = 0.0, sc = 0.0;
-  for (int b = 0; b < nblk; ++b) {
+// Per group (one workgroup each): mean and 1/sqrt(var + eps) from the block sums, added in a fixed order.
+__global__ void __launch_bounds__(256)
+k_whiten_stats(const double* __restrict__ blk, int nblk, int groups, float eps, double2* __restrict__ mu_rstd) {
+  __shared__ double smem[32];
+  const int g = blockIdx.x;
+  double v[3] = {0.0, 0.0, 0.0};
+  for (int b = threadIdx.x; b < nblk; b += blockDim.x) {
     const double* p = blk + (static_cast<size_t>(b) * groups + g) * 3;
-    sa += p[0]; sq += p[1]; sc += p[2];
+    v[0] += p[0]; v[1] += p[1]; v[2] += p[2];
   }
+  double t[3];
+  for (int j = 0; j < 3; ++j) {
+    t[j] = block_sum<double>(v[j], smem);
+    __syncthreads();
+  }
+  if (threadIdx.x != 0) return;
   double2 o = make_double2(0.0, 1.0);
-  if (sc > 0) {
-    const double mu = sa / sc;
-    double var = sq / sc - mu * mu;
+  if (t[2] > 0) {
+    const double mu = t[0] / t[2];
+    double var = t[1] / t[2] - mu * mu;
     if (var < 0) var = 0;
     o = make_double2(mu, 1.0 / sqrt(var + static_cast<double>(eps)));
   }
@@ -302,7 +334,7 @@ extern "C" umas_status umas_whiten_advantages(const float* adv, const uint8_t* t
   hipLaunchKernelGGL(k_whiten_sums, dim3(grid), dim3(kST), groups * 3 * sizeof(double), st, n_tokens, adv, tok_mask, tok_role,
                      mo, n_models, n_roles, by_role, blk);
   UMAS_LAUNCHED("k_whiten_sums");
-  hipLaunchKernelGGL(k_whiten_stats, dim3(cdiv(groups, 64)), dim3(64), 0, st, blk, static_cast<int>(grid), groups, eps, ms);
+  hipLaunchKernelGGL(k_whiten_stats, dim3(groups), dim3(256), 0, st, blk, static_cast<int>(grid), groups, eps, ms);
   UMAS_LAUNCHED("k_whiten_stats");
   hipLaunchKernelGGL(k_whiten_apply, dim3(grid), dim3(kST), groups * sizeof(double2), st, n_tokens, adv, tok_mask, tok_role, mo,
                      n_models, n_roles, by_role, ms, adv_out);
