@@ -154,12 +154,33 @@ def critic_kernel(umas, torch, H, n_sel, d, rep=8, iters=5):
             "all_kernels_ms": {k: v[0] / iters for k, v in prof.items()}}
 
 
+def power_probe(umas, torch, H, W, ids, rowsel, iters=3):
+    """The scoring kernel on the benchmark's operands and on all-zero operands of the same shape: the
+    instruction stream is identical, so a faster run on zeros shows that the shader clock under random
+    data is held down by the power limit rather than by the kernel's schedule."""
+    out = {}
+    for tag, h, w_ in (("random", H, W), ("zeros", torch.zeros_like(H), torch.zeros_like(W))):
+        umas.umas_policy_logprobs(h, w_, ids, rowsel)
+        torch.cuda.synchronize()
+        umas.profile_enable(True)
+        for _ in range(iters):
+            umas.umas_policy_logprobs(h, w_, ids, rowsel)
+        torch.cuda.synchronize()
+        prof = umas.profile_read()
+        umas.profile_enable(False)
+        out[tag + "_ms"] = prof["k_score_tiles"][0] / iters
+    flop = 2.0 * W.shape[0] * W.shape[1] * (H.shape[0] if rowsel is None else rowsel.numel())
+    out["random_tflops"] = flop / out["random_ms"] / 1e9
+    out["zeros_tflops"] = flop / out["zeros_ms"] / 1e9
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the CPU-oracle baseline sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the CPU-oracle baseline sample (0 = skip)")
     ap.add_argument("--no-hbm", action="store_true", help="skip the batch-replicated reward/scan measurement")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (reference for hardware byte counters)")
@@ -255,6 +276,7 @@ def main():
         "policy_logprobs_ms": logprobs_ms,
         "loss": loss,
     }
+    out["power_probe"] = power_probe(umas, torch, H, W, ids, rowsel)
     if args.copy_calibration:
         src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
