@@ -142,3 +142,15 @@ def run_fullsize(cfg):
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4])
 def test_full_size(cfg):
     run_fullsize(cfg)
+
+
+@pytest.mark.parametrize("cfg", [1, 4])
+def test_full_size_critic(cfg):
+    """The critic's fused pass at the configurations' real row counts and hidden sizes; the oracle's per-row
+    dot products are cheap enough to run live."""
+    from tests.test_gpu_next import critic_case
+    w = wl.make_workload(cfg)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w)
+    s, adv, ret = P.gpu_front(w)
+    for m in range(w.n_models):
+        critic_case(w, m, st, ret_o, s, ret)
