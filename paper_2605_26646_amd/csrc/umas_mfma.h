@@ -1,10 +1,10 @@
 // bf16 MFMA tile engine for gfx950: C[M,N] += A[M,K] * B[N,K]^T with both operands K-contiguous.
 //
-// A workgroup owns a BM x BN tile of C and walks K in steps of 64.  Global memory is read in
-// 16-byte vectors into registers one K-step ahead, written to one of two LDS stages (row pitch
-// 72 bf16 so that the 16-byte fragment reads of 16 consecutive rows fall on distinct banks) and
-// consumed by v_mfma_f32_32x32x16_bf16.  Each wavefront owns a (BM/WM) x (BN/WN) sub-tile as a
-// grid of 32x32 MFMA blocks with float accumulators.
+// A workgroup owns a BM x BN tile of C and walks K in steps of 64; each wavefront owns a
+// (BM/WM) x (BN/WN) sub-tile as a grid of 32x32 blocks of v_mfma_f32_32x32x16_bf16 with float
+// accumulators.  Two main loops: a general one (any K that is a multiple of 8: global memory is read
+// in 16-byte vectors into registers one K-step ahead and written to one of two LDS stages of row
+// pitch 72 bf16) and a fast one for K % 64 == 0 that fills the LDS straight from global memory.
 //
 // Accumulator layout of one 32x32 block (register r of lane l):
 //   row (A side, "M")  = 8*(r/4) + 4*(l/32) + r%4
@@ -114,75 +114,55 @@ __device__ __forceinline__ void mfma_mainloop(const uint16_t* const (&pa)[C::NA]
   }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Fast main loop for K % 64 == 0.
-//
-// K is walked in sub-steps of 32.  Tiles go from global memory straight into a ring of S LDS stages
-// (buffer_load_dwordx4 ... lds: no staging registers, no ds_write), S - 2 sub-steps ahead of their
-// use, so that a load may miss in L2 without stalling the workgroup.  Fragments are read one 16-wide
-// K-slice ahead of the MFMAs that consume them.  Per sub-step j (stage j % S):
-//   slice 0: MFMAs on slice 0 | read the fragments of slice 1
-//   wait until this wavefront's loads of sub-step j+1 have landed, workgroup barrier
-//   slice 1: MFMAs on slice 1 | issue the loads of sub-step j+S-1 into the stage of sub-step j-1
-//                             | read the fragments of slice 0 of sub-step j+1
-// The barrier in the middle orders everything: a stage is last read (slice 1 fragments) before the
-// barrier of its own sub-step, and refilled only after the barrier of the next one.
-//
-// LDS layout of a stage: A rows then B rows, 64 bytes per row (32 bf16), no padding; the 16-byte chunk
-// c of row r sits in slot c ^ ((r >> 2) & 3), which spreads the fragment reads of 16 consecutive rows
-// over all banks.  One wavefront-wide load fills 16 consecutive rows (1 KB): lane l fills slot l & 3
-// of row l >> 2, i.e. fetches chunk (l & 3) ^ ((l >> 4) & 3) of that row.
-//
-// Operands are addressed as raw buffers: a wave-uniform base (the caller picks it so that every
-// byte offset of the tile fits 32 bits) plus one 32-bit byte offset per load slot.
-template <class C, int S_ = 4>
-struct RingCfg {
-  static constexpr int S = S_;                                     // stages
-  static constexpr int BK = 32;                                    // K per sub-step
-  static constexpr int ROWB = 64;                                  // bytes per LDS row
-  static constexpr int STAGEB = (C::BM + C::BN) * ROWB;            // bytes per stage
-  static constexpr int LDS_BYTES = S * STAGEB;
-  static constexpr int NA = C::BM * 4 / C::T, NB = C::BN * 4 / C::T;   // 16-byte loads per thread per sub-step
-  static constexpr int ROWS_PER_PASS = C::T / 4;
-  static_assert(C::T % 64 == 0 && (C::BM * 4) % C::T == 0 && (C::BN * 4) % C::T == 0, "load slots divide evenly");
-};
-
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0xFFFFFFFF, 0x00020000);
 }
 
-// Tile row that load slot i of this thread fetches, and the K offset (in elements) of its chunk.
+// ---------------------------------------------------------------------------------------------
+// Fast main loop for K % 64 == 0.
+//
+// K is walked in steps of 64: 128 bytes per row, the line size of the vector caches, so every line is
+// fetched once.  Tiles go from global memory straight into one of two LDS stages of (BM + BN) x 128 bytes
+// (buffer_load_dwordx4 ... lds: no staging registers, no ds_write); one wavefront-wide load fills 8
+// consecutive rows (1 KB).  Operands are addressed as raw buffers: a wave-uniform base (the caller picks it
+// so that every byte offset of the tile fits 32 bits) plus one 32-bit byte offset per load slot.  The 16-byte chunk c of row r sits in slot
+// c ^ ((r >> 1) & 7), which keeps the fragment reads of 16 consecutive rows on distinct banks.
+// Per step j (stage j & 1): loads of step j+1 go to the other stage right away (everybody left it before the
+// barrier of the previous step); slices 0..2 run; then the wavefront waits for its own loads and LDS reads,
+// the workgroup meets at the barrier, and slice 3 runs while the first fragments of the next stage are read.
 template <class C>
-__device__ __forceinline__ int ring_row(int i) { return i * (C::T / 4) + (threadIdx.x >> 2); }
-__device__ __forceinline__ int ring_kofs() {
-  const int lane = threadIdx.x & 63;
-  return 8 * ((lane & 3) ^ ((lane >> 4) & 3));
+struct Ring2Cfg {
+  static constexpr int BK = 64;
+  static constexpr int ROWB = 128;
+  static constexpr int STAGEB = (C::BM + C::BN) * ROWB;
+  static constexpr int LDS_BYTES = 2 * STAGEB;
+  static constexpr int NA = C::BM * 8 / C::T, NB = C::BN * 8 / C::T;   // 16-byte loads per thread per step
+  static constexpr int ROWS_PER_PASS = C::T / 8;
+  static_assert(C::T % 64 == 0 && (C::BM * 8) % C::T == 0 && (C::BN * 8) % C::T == 0, "load slots divide evenly");
+};
+template <class C>
+__device__ __forceinline__ int ring2_row(int i) { return i * (C::T / 8) + (threadIdx.x >> 3); }
+// K offset (elements) of the chunk this lane fetches: slot (tid & 7) of row ring2_row holds chunk slot ^ ((row >> 1) & 7);
+// rows per pass and wavefront row offsets are multiples of 8, so (row >> 1) & 7 = ((tid >> 3) >> 1) & 7 with tid >> 3 < 64
+__device__ __forceinline__ int ring2_kofs() {
+  const int t = threadIdx.x;
+  return 8 * ((t & 7) ^ (((t >> 3) >> 1) & 7));
 }
 
-// s_waitcnt that only waits for the vector-memory counter to drop to n (gfx9 encoding).
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N >= 0 && N < 64, "vmcnt has 6 bits");
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
-}
-
-// oa[i] / ob[i]: byte offset from the operand's base of (row ring_row(i), k = ring_kofs()); rows outside
-// the matrix are clamped to a valid row by the caller, which ignores what comes out of them.
-template <class C, int S>
-__device__ __forceinline__ void mfma_mainloop_ring(__amdgpu_buffer_rsrc_t ra, const uint32_t (&oa)[RingCfg<C, S>::NA],
-                                                   __amdgpu_buffer_rsrc_t rb, const uint32_t (&ob)[RingCfg<C, S>::NB],
-                                                   int K, uint16_t* lds, floatx16 (&acc)[C::TM][C::TN]) {
-  using R = RingCfg<C, S>;
+template <class C>
+__device__ __forceinline__ void mfma_mainloop_ring2(__amdgpu_buffer_rsrc_t ra, const uint32_t (&oa)[Ring2Cfg<C>::NA],
+                                                    __amdgpu_buffer_rsrc_t rb, const uint32_t (&ob)[Ring2Cfg<C>::NB],
+                                                    int K, uint16_t* lds, floatx16 (&acc)[C::TM][C::TN]) {
+  using R = Ring2Cfg<C>;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / C::WN, wn = wave % C::WN;
   char* base = reinterpret_cast<char*>(lds);
   const int nsub = K / R::BK;
-  constexpr int kLoads = R::NA + R::NB;                   // load instructions per wavefront per sub-step
 
   auto gload = [&](int sub, int stage) {
     const int kbytes = sub * R::BK * 2;
-    char* sa = base + stage * R::STAGEB + wave * 16 * R::ROWB;
+    char* sa = base + stage * R::STAGEB + wave * 8 * R::ROWB;
     char* sb = sa + C::BM * R::ROWB;
 #pragma unroll
     for (int i = 0; i < R::NA; ++i)
@@ -193,15 +173,12 @@ __device__ __forceinline__ void mfma_mainloop_ring(__amdgpu_buffer_rsrc_t ra, co
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, reinterpret_cast<uint32_t*>(sb + i * R::ROWS_PER_PASS * R::ROWB), 16,
                                                ob[i], kbytes, 0, 0);
   };
-
-  // byte offsets of this lane's fragment chunk for the two K-slices of a stage
-  const int sw = (lane >> 2) & 3;
-  const int coff0 = ((lane >> 5) ^ sw) * 16, coff1 = ((2 + (lane >> 5)) ^ sw) * 16;
+  const int sw = (lane >> 1) & 7;                    // (row >> 1) & 7 of this lane's fragment rows
   const int arow = (wm * C::WTM + (lane & 31)) * R::ROWB;
   const int brow = (C::BM + wn * C::WTN + (lane & 31)) * R::ROWB;
-
   bf16x8 af[2][C::TM], bfr[2][C::TN];
-  auto fload = [&](int buf, int stage, int coff) {
+  auto fload = [&](int buf, int stage, int kk) {
+    const int coff = ((2 * kk + (lane >> 5)) ^ sw) * 16;
     const char* sa = base + stage * R::STAGEB + arow + coff;
     const char* sb = base + stage * R::STAGEB + brow + coff;
 #pragma unroll
@@ -216,8 +193,6 @@ __device__ __forceinline__ void mfma_mainloop_ring(__amdgpu_buffer_rsrc_t ra, co
       for (int tn = 0; tn < C::TN; ++tn)
         acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][tm], bfr[buf][tn], acc[tm][tn], 0, 0, 0);
   };
-  // memory instructions are spread behind the MFMAs of a slice, so that their issue hides under the
-  // matrix pipe
   auto interleave = [&](int n_ds, int n_vm) {
 #pragma unroll
     for (int i = 0; i < C::TM * C::TN; ++i) {
@@ -227,39 +202,37 @@ __device__ __forceinline__ void mfma_mainloop_ring(__amdgpu_buffer_rsrc_t ra, co
     }
   };
 
-  // prologue: sub-steps 0 .. S-2 in flight, sub-step 0 landed
-#pragma unroll
-  for (int p = 0; p < S - 1; ++p) gload(p < nsub ? p : nsub - 1, p);
-  wait_vmcnt<(S - 2) * kLoads>();
+  gload(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();
-  fload(0, 0, coff0);
+  fload(0, 0, 0);
   __builtin_amdgcn_sched_barrier(0);
-
-  int stage = 0;                                           // j % S
   for (int j = 0; j < nsub; ++j) {
-    const int stage_next = stage + 1 == S ? 0 : stage + 1;
-    const int stage_prev = stage == 0 ? S - 1 : stage - 1;
-    // slice 0
-    fload(1, stage, coff1);
+    const int st = j & 1;
+    // past the end of K the loads repeat the last step (nobody reads them)
+    gload(j + 1 < nsub ? j + 1 : nsub - 1, st ^ 1);
+    fload(1, st, 1);
+    mfmas(0);
+    interleave(C::TM + C::TN, R::NA + R::NB);
+    __builtin_amdgcn_sched_barrier(0);
+    fload(0, st, 2);
+    mfmas(1);
+    interleave(C::TM + C::TN, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    fload(1, st, 3);
     mfmas(0);
     interleave(C::TM + C::TN, 0);
     __builtin_amdgcn_sched_barrier(0);
-    // loads of sub-step j+1 were issued S-2 sub-steps ago; everything younger may stay in flight
-    wait_vmcnt<(S - 3) * kLoads>();
+    // own loads of the next stage landed, own reads of this stage done; then everybody's
+    __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) and lgkmcnt(0), expcnt untouched (gfx9 encoding)
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    // slice 1; past the end of K the loads repeat the last sub-step (nobody reads them) so that the
-    // in-flight count stays what the waits above assume
-    const int sub_load = j + S - 1 < nsub ? j + S - 1 : nsub - 1;
-    gload(sub_load, stage_prev);
-    fload(0, stage_next, coff0);
+    fload(0, st ^ 1, 0);
     mfmas(1);
-    interleave(C::TM + C::TN, kLoads);
+    interleave(C::TM + C::TN, 0);
     __builtin_amdgcn_sched_barrier(0);
-    stage = stage_next;
   }
-  // drain the loads still in flight before the caller reuses the LDS
-  wait_vmcnt<0>();
+  __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();
 }
 

@@ -19,8 +19,7 @@ namespace umas {
 namespace {
 
 using Cfg = TileCfg<256, 256, 2, 4>;   // 8 wavefronts, two per SIMD: one issues memory operations while the other feeds the matrix pipe
-constexpr int kStages = 4;
-using Ring = RingCfg<Cfg, kStages>;
+using Ring = Ring2Cfg<Cfg>;
 constexpr int kLogitLds = Ring::LDS_BYTES > Cfg::LDS_BYTES ? Ring::LDS_BYTES : Cfg::LDS_BYTES;   // both main loops fit
 constexpr int kGM = 4, kGN = 8;          // tile group resident on one XCD
 constexpr int kRowBlock = 256;
@@ -105,17 +104,17 @@ __device__ __forceinline__ void logit_tile(const uint16_t* __restrict__ W, const
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
   if (d % C::BK == 0) {
-    using R = RingCfg<C, kStages>;
-    const uint32_t kofs = ring_kofs();
+    using R = Ring2Cfg<C>;
+    const uint32_t kofs = ring2_kofs();
     uint32_t oa[R::NA], ob[R::NB];
 #pragma unroll
-    for (int i = 0; i < R::NA; ++i) oa[i] = (static_cast<uint32_t>(min(ring_row<C>(i), V - 1 - m0)) * d + kofs) * 2u;
+    for (int i = 0; i < R::NA; ++i) oa[i] = (static_cast<uint32_t>(min(ring2_row<C>(i), V - 1 - m0)) * d + kofs) * 2u;
 #pragma unroll
     for (int i = 0; i < R::NB; ++i) {
-      const int64_t n = sel0 + min(n0 + ring_row<C>(i), n_lim - 1);
+      const int64_t n = sel0 + min(n0 + ring2_row<C>(i), n_lim - 1);
       ob[i] = (static_cast<uint32_t>(rowsel ? rowsel[n] : n) * d + kofs) * 2u;   // host checks n_rows*d*2 < 2^32
     }
-    mfma_mainloop_ring<C, kStages>(make_rsrc(W + static_cast<int64_t>(m0) * d), oa, make_rsrc(H), ob, d, lds, acc);
+    mfma_mainloop_ring2<C>(make_rsrc(W + static_cast<int64_t>(m0) * d), oa, make_rsrc(H), ob, d, lds, acc);
   } else {
     const int kofs = slot_kofs();
     const uint16_t* pa[C::NA];
@@ -481,14 +480,15 @@ gemm_tn_body(const uint16_t* __restrict__ A, int64_t lda, int64_t m_rows, const 
   if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
   const int64_t m0 = static_cast<int64_t>(tile_m) * C::BM;
   const int n0 = tile_n * C::BN;
-  const uint32_t kofs = ring_kofs();                                // K is a multiple of 256 here
-  uint32_t oa[Ring::NA], ob[Ring::NB];
+  using R2 = Ring2Cfg<C>;
+  const uint32_t kofs = ring2_kofs();                               // K is a multiple of 256 here
+  uint32_t oa[R2::NA], ob[R2::NB];
 #pragma unroll
-  for (int i = 0; i < Ring::NA; ++i)                                // clamped rows are not stored below
-    oa[i] = (static_cast<uint32_t>(min(static_cast<int64_t>(ring_row<C>(i)), m_rows - 1 - m0)) * static_cast<uint32_t>(lda) + kofs) * 2u;
+  for (int i = 0; i < R2::NA; ++i)                                  // clamped rows are not stored below
+    oa[i] = (static_cast<uint32_t>(min(static_cast<int64_t>(ring2_row<C>(i)), m_rows - 1 - m0)) * static_cast<uint32_t>(lda) + kofs) * 2u;
 #pragma unroll
-  for (int i = 0; i < Ring::NB; ++i)
-    ob[i] = (static_cast<uint32_t>(min(ring_row<C>(i), n_rows - 1 - n0)) * static_cast<uint32_t>(ldb) + kofs) * 2u;
+  for (int i = 0; i < R2::NB; ++i)
+    ob[i] = (static_cast<uint32_t>(min(ring2_row<C>(i), n_rows - 1 - n0)) * static_cast<uint32_t>(ldb) + kofs) * 2u;
   floatx16 acc[C::TM][C::TN];
 #pragma unroll
   for (int tm = 0; tm < C::TM; ++tm)
@@ -496,7 +496,7 @@ gemm_tn_body(const uint16_t* __restrict__ A, int64_t lda, int64_t m_rows, const 
     for (int tn = 0; tn < C::TN; ++tn)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
-  mfma_mainloop_ring<C, kStages>(make_rsrc(A + m0 * lda), oa, make_rsrc(B + static_cast<int64_t>(n0) * ldb), ob, K, lds, acc);
+  mfma_mainloop_ring2<C>(make_rsrc(A + m0 * lda), oa, make_rsrc(B + static_cast<int64_t>(n0) * ldb), ob, K, lds, acc);
 #pragma unroll
   for (int tn = 0; tn < C::TN; ++tn) {
     const int j = n0 + acc_col<C>(tn);
