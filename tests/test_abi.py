@@ -110,3 +110,58 @@ def test_bad_scalar_arguments(lib):
     from paper_2605_26646_amd import binding as b
     s = b._Streams(*([1] * 16))
     assert lib.umas_advantages(C.addressof(s), 10, 1, None, 1.0, 1.0, 1.0, 3, 256, 256, 256, 1 << 20, None) == -1
+
+
+def test_entry_points_around_the_update_reject_bad_arguments(lib):
+    """Host-side validation of the critic, shaping and ready-batch calls: every refusal happens before any launch."""
+    from paper_2605_26646_amd import binding as b
+    assert b.VALUE_STATS_DTYPE.itemsize == 24
+    f32, i64 = C.c_float, C.c_int64
+    # critic: d must be a multiple of 8 for bf16 and at most 8192; clip range positive
+    lib.umas_values.restype = C.c_int
+    lib.umas_values.argtypes = [C.c_void_p, C.c_void_p, f32, C.c_int, i64, C.c_int32, C.c_void_p, i64, C.c_void_p, C.c_void_p]
+    assert lib.umas_values(256, 256, 0.0, 1, 4, 12, None, 4, 256, None) == -2
+    assert lib.umas_values(256, 256, 0.0, 1, 4, 16384, None, 4, 256, None) == -2
+    assert lib.umas_values(256, 256, 0.0, 0, 4, 8192, None, 4, 256, None) == -2          # float32: at most 4096
+    assert lib.umas_values(256, 256, 0.0, 1, 4, 64, None, 3, 256, None) == -1            # NULL selection but n_sel != n_rows
+    lib.umas_value_workspace_bytes.restype = C.c_size_t
+    lib.umas_value_workspace_bytes.argtypes = [i64, C.c_int32, C.c_int, C.c_int32]
+    assert lib.umas_value_workspace_bytes(1000, 2048, 1, 3) > 0
+    lib.umas_value_loss_fwd_bwd.restype = C.c_int
+    lib.umas_value_loss_fwd_bwd.argtypes = [C.c_void_p, C.c_void_p, f32, C.c_int, i64, C.c_int32, C.c_void_p, i64, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_int32, f32, C.c_int32, C.c_int32, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    st = lib.umas_value_loss_fwd_bwd(256, 256, 0.0, 1, 4, 64, None, 4, 256, 256, None, 0, 0.0, 0, 0, 256, None, 256, 256,
+                                     None, 256, 1 << 20, None)
+    assert st == -1 and "clip_eps_v" in lib.umas_last_error().decode()
+    st = lib.umas_value_loss_fwd_bwd(256, 256, 0.0, 1, 4, 64, None, 4, 256, 256, None, 0, 0.2, 0, 0, 256, None, 256, 256,
+                                     None, 256, 16, None)
+    assert st == -4
+    # KL-penalised rewards: alignment and workspace
+    lib.umas_kl_rewards.restype = C.c_int
+    lib.umas_kl_rewards.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, i64, f32, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_size_t, C.c_void_p]
+    assert lib.umas_kl_rewards(260, 256, 256, 256, 8, 0.1, 256, 256, 256, 1 << 20, None) == -1
+    assert lib.umas_kl_rewards(256, 256, 256, 256, 8, 0.1, 256, 256, 256, 0, None) == -4
+    # whitening: offsets must run from 0 to n_tokens without decreasing; the per-role scope needs roles
+    lib.umas_whiten_advantages.restype = C.c_int
+    lib.umas_whiten_advantages.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, i64,
+                                           C.c_int32, f32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    for off, code in (([0, 5], -1), ([0, 9, 8], -1)):
+        a = np.array(off, np.int64)
+        assert lib.umas_whiten_advantages(256, 256, 256, a.ctypes.data, len(off) - 1, 2, 8, 0, 1e-8, 256, 256, 1 << 20, None) == code
+    a = np.array([0, 8], np.int64)
+    assert lib.umas_whiten_advantages(256, 256, None, a.ctypes.data, 1, 2, 8, 1, 1e-8, 256, 256, 1 << 20, None) == -1
+    assert lib.umas_whiten_advantages(256, 256, 256, a.ctypes.data, 1, 2, 8, 7, 1e-8, 256, 256, 1 << 20, None) == -1
+    assert lib.umas_whiten_advantages(256, 256, 256, a.ctypes.data, 1, 2, 8, 0, 0.0, 256, 256, 1 << 20, None) == -1
+    # ready batch: the shuffle must be a permutation, at least one minibatch
+    lib.umas_ready_batch.restype = C.c_int
+    lib.umas_ready_batch.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                     C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    s = b._Streams(*([256] * 16))
+    tto = np.array([0, 1, 2], np.int32)
+    bad = np.array([1, 1], np.int32)
+    st = lib.umas_ready_batch(C.addressof(s), 1, 2, tto.ctypes.data, 2, None, bad.ctypes.data, 2, 256, 256, 256, 1 << 20, None)
+    assert st == -1 and "permutation" in lib.umas_last_error().decode()
+    assert lib.umas_ready_batch(C.addressof(s), 1, 2, tto.ctypes.data, 2, None, None, 0, 256, 256, 256, 1 << 20, None) == -1
+    assert lib.umas_ready_batch(C.addressof(s), 1, 3, tto.ctypes.data, 2, None, None, 1, 256, 256, 256, 1 << 20, None) == -1
