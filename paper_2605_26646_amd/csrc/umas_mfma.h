@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace umas {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -230,6 +232,213 @@ __device__ __forceinline__ void mfma_mainloop_ring2(__amdgpu_buffer_rsrc_t ra, c
     fload(0, st ^ 1, 0);
     mfmas(1);
     interleave(C::TM + C::TN, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0070);
+  __builtin_amdgcn_s_barrier();
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same loop for operands that are not K-contiguous in memory.
+//
+// An operand stored K-major (row k holds the 256 tile entries of that k next to each other, 512 bytes) is
+// brought into LDS as it lies: a stage holds 64 k-rows of 512 bytes, one wavefront-wide load fills two of
+// them.  Fragments come out through ds_read_b64_tr_b16, which transposes on the way: in a group of 16
+// lanes, lane l receives element l % 4 of the 8-byte chunks addressed by lanes l / 4, l / 4 + 4, l / 4 + 8
+// and l / 4 + 12.  Lane i = q + 4 j of a group therefore points at k-row kbase + j, entries 4 q .. 4 q + 3
+// of the group's 16, and lane l ends up with entry l of the 16 for the four k of the read; two reads give
+// the eight k of an MFMA operand.  The 16-byte unit u of k-row k sits in slot u ^ (4 (k & 3)), which keeps
+// the 32 lanes served in one cycle on distinct banks.
+typedef short short4v __attribute__((ext_vector_type(4)));
+
+struct KMajor {                 // an operand tile stored K-major
+  const char* base;             // byte address of (k-row 0, first entry of the tile)
+  int64_t ld_bytes;             // bytes between consecutive k-rows
+  const int32_t* rowmap;        // if set, k-row k lives in row rowmap[k] of the matrix (ld_bytes apart, from base)
+  int k_rows;                   // k-rows that exist; later ones read the last one (the other operand is zero there)
+  int n_units;                  // 16-byte units of a k-row that exist from base on (<= 32); later ones read the last one
+};
+struct KContig {                // an operand tile stored K-contiguous: per-slot byte offsets from a base
+  __amdgpu_buffer_rsrc_t rsrc;
+  uint32_t off[4];
+};
+
+template <class C, bool ATR, bool BTR>
+__device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMajor& ka, const KContig& cb, const KMajor& kb,
+                                                    int K, uint16_t* lds, floatx16 (&acc)[C::TM][C::TN]) {
+  using R = Ring2Cfg<C>;
+  static_assert(C::BM == 256 && C::BN == 256 && C::T == 512 && R::NA == 4 && R::NB == 4, "written for 256x256 tiles, 8 wavefronts");
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / C::WN, wn = wave % C::WN;
+  char* base = reinterpret_cast<char*>(lds);
+  const int nsub = K / R::BK;
+  constexpr int kAB = C::BM * R::ROWB;               // bytes of the A region of a stage (B follows)
+
+  // K-major loads: pass p covers k-rows 16 p .. 16 p + 15, this wavefront rows 16 p + 2 wave, + 1; lane l fills slot
+  // l & 31 of row 16 p + 2 wave + (l >> 5) and fetches unit slot ^ 4 (row & 3)
+  const int tr_krow = 2 * wave + (lane >> 5);        // + 16 p
+  const int tr_slot_unit = (lane & 31) ^ (4 * (tr_krow & 3));
+  int32_t rows_a[4] = {0, 0, 0, 0}, rows_b[4] = {0, 0, 0, 0};   // rows of the step after next when a rowmap is set
+  auto map_rows = [&](const KMajor& k, int sub, int32_t (&rows)[4]) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) rows[p] = k.rowmap[min(sub * R::BK + 16 * p + tr_krow, k.k_rows - 1)];
+  };
+  auto gload_kmajor = [&](const KMajor& k, const int32_t (&rows)[4], int sub, char* region) {
+    const uint32_t ubytes = static_cast<uint32_t>(min(tr_slot_unit, k.n_units - 1)) * 16u;
+    if (k.rowmap) {
+      const __amdgpu_buffer_rsrc_t r = make_rsrc(k.base);
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, reinterpret_cast<uint32_t*>(region + (16 * p + 2 * wave) * 512), 16,
+                                                 static_cast<uint32_t>(rows[p]) * static_cast<uint32_t>(k.ld_bytes) + ubytes, 0, 0, 0);
+    } else {
+      const int k0 = min(sub * R::BK, ((k.k_rows - 1) / R::BK) * R::BK);          // first k-row of the (clamped) step
+      const __amdgpu_buffer_rsrc_t r = make_rsrc(k.base + static_cast<int64_t>(k0) * k.ld_bytes);
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, reinterpret_cast<uint32_t*>(region + (16 * p + 2 * wave) * 512), 16,
+                                                 static_cast<uint32_t>(min(16 * p + tr_krow, k.k_rows - 1 - k0)) * static_cast<uint32_t>(k.ld_bytes) + ubytes,
+                                                 0, 0, 0);
+    }
+  };
+  auto gload_kcontig = [&](const KContig& c, int sub, char* region) {
+    const int kbytes = sub * R::BK * 2;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(c.rsrc, reinterpret_cast<uint32_t*>(region + (i * R::ROWS_PER_PASS + wave * 8) * R::ROWB), 16,
+                                               c.off[i], kbytes, 0, 0);
+  };
+  auto gload = [&](int sub, int stage) {
+    char* sa = base + stage * R::STAGEB;
+    if (ATR) gload_kmajor(ka, rows_a, sub, sa); else gload_kcontig(ca, sub, sa);
+    if (BTR) gload_kmajor(kb, rows_b, sub, sa + kAB); else gload_kcontig(cb, sub, sa + kAB);
+  };
+
+  // fragment addresses
+  const int sw = (lane >> 1) & 7;
+  const int arow = (wm * C::WTM + (lane & 31)) * R::ROWB;
+  const int brow = (wn * C::WTN + (lane & 31)) * R::ROWB;
+  const int tq = lane & 3, tj = (lane >> 2) & 3;     // position q + 4 j inside the group of 16 lanes
+  // The transposing reads are issued as inline assembly: the compiler cannot tell that they do not touch the stage
+  // the LDS-filling loads are writing and would wait for those loads before every one of them.  Their results are
+  // therefore handed over by an explicit wait (tr_wait) that also names the registers, so that no use moves above it.
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+      (__attribute__((address_space(3))) char*)(base)));
+  // LDS byte address of this lane's chunk for block t of an operand whose sub-tile starts at unit u0: k-row (k half, j),
+  // 8-byte half of the unit, unit slot; stage, region, slice and the +4 k-rows of the second read are added as offsets
+  auto tr_addr = [&](int u0, int t) -> uint32_t {
+    const int unit = u0 + t * 4 + ((lane >> 4) & 1) * 2 + (tq >> 1);
+    return lds0 + ((lane >> 5) * 8 + tj) * 512 + (tq & 1) * 8 + ((unit ^ (4 * tj)) * 16);
+  };
+  uint32_t tra[C::TM], trb[C::TN];
+#pragma unroll
+  for (int tm = 0; tm < C::TM; ++tm) tra[tm] = tr_addr(wm * (C::WTM / 8), tm);
+#pragma unroll
+  for (int tn = 0; tn < C::TN; ++tn) trb[tn] = tr_addr(wn * (C::WTN / 8), tn);
+  typedef short short8v __attribute__((ext_vector_type(8)));
+  bf16x8 af[2][C::TM], bfr[2][C::TN];
+  auto fload = [&](int buf, int stage, auto kk_c) {
+    constexpr int kk = decltype(kk_c)::value;
+    const char* sa = base + stage * R::STAGEB;
+    const char* sb = sa + kAB;
+    const int coff = ((2 * kk + (lane >> 5)) ^ sw) * 16;
+    const uint32_t stoff = static_cast<uint32_t>(stage) * R::STAGEB;
+#pragma unroll
+    for (int tm = 0; tm < C::TM; ++tm) {
+      if (ATR) {
+        short4v lo, hi;
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(tra[tm] + stoff), "n"(kk * 16 * 512));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(tra[tm] + stoff), "n"(kk * 16 * 512 + 4 * 512));
+        const short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        af[buf][tm] = __builtin_bit_cast(bf16x8, v);
+      } else {
+        af[buf][tm] = *reinterpret_cast<const bf16x8*>(sa + arow + coff + tm * 32 * R::ROWB);
+      }
+    }
+#pragma unroll
+    for (int tn = 0; tn < C::TN; ++tn) {
+      if (BTR) {
+        short4v lo, hi;
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(trb[tn] + stoff), "n"(kAB + kk * 16 * 512));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(trb[tn] + stoff), "n"(kAB + kk * 16 * 512 + 4 * 512));
+        const short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        bfr[buf][tn] = __builtin_bit_cast(bf16x8, v);
+      } else {
+        bfr[buf][tn] = *reinterpret_cast<const bf16x8*>(sb + brow + coff + tn * 32 * R::ROWB);
+      }
+    }
+  };
+  // every LDS read issued so far has returned; the fragments of `buf` may be used from here on
+  auto tr_wait = [&](int buf) {
+    if (ATR) {
+#pragma unroll
+      for (int tm = 0; tm < C::TM; ++tm) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(af[buf][tm]));
+    }
+    if (BTR) {
+#pragma unroll
+      for (int tn = 0; tn < C::TN; ++tn) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bfr[buf][tn]));
+    }
+  };
+  auto mfmas = [&](int buf) {
+#pragma unroll
+    for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < C::TN; ++tn)
+        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][tm], bfr[buf][tn], acc[tm][tn], 0, 0, 0);
+  };
+
+  constexpr int kDs = (ATR ? 2 : 1) * C::TM + (BTR ? 2 : 1) * C::TN;   // LDS reads per slice
+  auto interleave = [&](int n_ds, int n_vm) {
+#pragma unroll
+    for (int i = 0; i < C::TM * C::TN; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (2 * i + 1 < n_ds) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      else if (2 * i < n_ds) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (i < n_vm) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+  };
+  using K0 = std::integral_constant<int, 0>;
+  using K1 = std::integral_constant<int, 1>;
+  using K2 = std::integral_constant<int, 2>;
+  using K3 = std::integral_constant<int, 3>;
+  if (ATR && ka.rowmap) map_rows(ka, 0, rows_a);
+  if (BTR && kb.rowmap) map_rows(kb, 0, rows_b);
+  gload(0, 0);
+  if (ATR && ka.rowmap) map_rows(ka, nsub > 1 ? 1 : 0, rows_a);
+  if (BTR && kb.rowmap) map_rows(kb, nsub > 1 ? 1 : 0, rows_b);
+  __builtin_amdgcn_s_waitcnt(0x0070);
+  __builtin_amdgcn_s_barrier();
+  fload(0, 0, K0{});
+  for (int j = 0; j < nsub; ++j) {
+    const int st = j & 1;
+    const int sub_next = j + 1 < nsub ? j + 1 : nsub - 1;      // past the end the last step is loaded again (nobody reads it)
+    tr_wait(0);
+    gload(sub_next, st ^ 1);
+    const int sub_after = j + 2 < nsub ? j + 2 : nsub - 1;
+    if (ATR && ka.rowmap) map_rows(ka, sub_after, rows_a);
+    if (BTR && kb.rowmap) map_rows(kb, sub_after, rows_b);
+    fload(1, st, K1{});
+    mfmas(0);
+    interleave(kDs, 8);
+    __builtin_amdgcn_sched_barrier(0);
+    tr_wait(1);
+    fload(0, st, K2{});
+    mfmas(1);
+    interleave(kDs, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    tr_wait(0);
+    fload(1, st, K3{});
+    mfmas(0);
+    interleave(kDs, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    tr_wait(1);
+    fload(0, st ^ 1, K0{});
+    mfmas(1);
+    interleave(kDs, 0);
     __builtin_amdgcn_sched_barrier(0);
   }
   __builtin_amdgcn_s_waitcnt(0x0070);

@@ -7,8 +7,9 @@
 // Update (paragraph "Model-specific updates and synchronization", PPO after Schulman et al.
 // 2017): ratio = exp(logp - logp_old), L = max(-A ratio, -A clip(ratio)), g = dL/dlogp, then
 // the dense part of dz = g (onehot - softmax) is recomputed tile by tile from H, W and lse, rounded
-// to bf16 into a bounded chunk buffer in both orientations, and dH = dz W, dW = dz^T H run as MFMA
-// GEMMs; the one-hot part (one term per row) is added in float32.
+// to bf16 into a bounded chunk buffer dZ [rows, vocabulary], and dH = dz W, dW = dz^T H run as MFMA
+// GEMMs that read dZ, W and H as they lie (operands that are not K-contiguous go through transposing
+// LDS reads); the one-hot part (one term per row) is added in float32.
 // The float32 path is a plain, unblocked implementation for small shapes.
 #include <math.h>
 
@@ -29,7 +30,6 @@ constexpr float kMasked = -1e30f;        // stands for a logit that does not exi
 __device__ __forceinline__ uint16_t f2bf(float x) {
   return __builtin_bit_cast(uint16_t, static_cast<__bf16>(x));
 }
-__device__ __forceinline__ uint64_t pack_u64(uint32_t lo, uint32_t hi) { return static_cast<uint64_t>(lo) | (static_cast<uint64_t>(hi) << 32); }
 __device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
 
 // Online-softmax partial: m = max z, s = sum exp(z - m), t = sum exp(z - m) z.
@@ -65,29 +65,6 @@ hipError_t fill_bytes_zero(void* p, size_t bytes, hipStream_t st) {
   const hipError_t e = hipGetLastError();
   if (e == hipSuccess && g_prof_on) prof_kernel("k_fill_u32", st);
   return e;
-}
-
-// out[c, r] = in[row(r), c] for r < n_r (row(r) = rowsel[r] or r), zero for n_r <= r < ld_out;
-// bf16 elements, in is [*, n_c] row-major, out is [n_c, ld_out].
-__global__ void k_transpose_bf16(const uint16_t* __restrict__ in, int64_t n_c, const int32_t* __restrict__ rowsel,
-                                 int64_t n_r, uint16_t* __restrict__ out, int64_t ld_out) {
-  __shared__ uint16_t tile[64][66];
-  const int64_t r0 = static_cast<int64_t>(blockIdx.x) * 64, c0 = static_cast<int64_t>(blockIdx.y) * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;   // 256 threads: 4 rows per pass
-  for (int i = ty; i < 64; i += 4) {
-    const int64_t r = r0 + i, c = c0 + tx;
-    uint16_t v = 0;
-    if (r < n_r && c < n_c) {
-      const int64_t src = rowsel ? rowsel[r] : r;
-      v = in[src * n_c + c];
-    }
-    tile[i][tx] = v;
-  }
-  __syncthreads();
-  for (int i = ty; i < 64; i += 4) {
-    const int64_t c = c0 + i, r = r0 + tx;
-    if (c < n_c && r < ld_out) out[c * ld_out + r] = tile[tx][i];
-  }
 }
 
 // Logit tile Z[v, n] = W[m0 + v, :] . H[row(n0 + n), :] for a 256x256 block of (vocabulary, selected rows),
@@ -376,14 +353,13 @@ k_ppo_stats(int nblk, int n_roles, float entropy_coef, const double* __restrict_
 // ------------------------------------------------------------------ bf16: dz tiles into the chunk buffer
 // Same tile product as k_score_tiles; the epilogue forms the dense part of dz = g (onehot - softmax),
 // -g exp(z - lse), plus the entropy bonus's term when its coefficient is not 0, and writes it as bf16 to
-// dZ [mcp, Vp] and dZt [Vp, mcp].  Rows past the chunk and
-// vocabulary ids past V get 0.  The one-hot part g at v = y is a single term per row and is added in
+// dZ [mcp, Vp].  Rows past the chunk and vocabulary ids past V get 0.  The one-hot part g at v = y is a single term per row and is added in
 // float32 where dH and dW are written, so that it never meets the bf16 rounding of the dense part.
 __global__ void __launch_bounds__(Cfg::T)
 k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
            const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc,
            const float* __restrict__ lse_c, const float* __restrict__ a_c, const float* __restrict__ kz_c,
-           int tiles_m, int tiles_n, uint16_t* __restrict__ dZ, uint16_t* __restrict__ dZt, int64_t Vp, int64_t mcp) {
+           int tiles_m, int tiles_n, uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp) {
   using C = Cfg;
   __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
   int tile_m, tile_n;
@@ -411,8 +387,6 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
         for (int r = 0; r < 16; ++r)
           if (vbase + tm * 32 + (r >> 2) * 8 + (r & 3) >= V) acc[tm][tn][r] = kMasked;
   }
-  const int t = lane & 3;                       // position in the quad of lanes holding 4 consecutive rows n
-  const uint32_t sel = (t & 1) ? 0x07060302u : 0x05040100u;   // v_perm_b32: 0-3 = bytes of src1, 4-7 = bytes of src0
 #pragma unroll
   for (int tn = 0; tn < C::TN; ++tn) {
     const int64_t n = n0 + acc_col<C>(tn);
@@ -428,7 +402,6 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
     for (int tm = 0; tm < C::TM; ++tm)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int v0 = vbase + tm * 32 + q * 8;  // this lane holds vocabulary entries v0..v0+3 of row n
         float dz[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -437,20 +410,9 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
         }
         const uint32_t p01 = static_cast<uint32_t>(f2bf(dz[0])) | (static_cast<uint32_t>(f2bf(dz[1])) << 16);
         const uint32_t p23 = static_cast<uint32_t>(f2bf(dz[2])) | (static_cast<uint32_t>(f2bf(dz[3])) << 16);
-        // orientation [row][vocabulary]: staged in this wavefront's LDS region, stored in full lines below
+        // staged in this wavefront's LDS region, stored in full lines below
         *reinterpret_cast<uint2*>(stage + (tn * 32 + (lane & 31)) * kStagePitch + (tm * 32 + q * 8 + (lane >> 5) * 4) * 2) =
             make_uint2(p01, p23);
-        // 4x4 transpose over the quad: afterwards lane t holds entry v0+t of rows n-t .. n-t+3
-        const uint32_t send = t < 2 ? p23 : p01;
-        const uint32_t recv = __builtin_amdgcn_update_dpp(0u, send, 0x4E, 0xF, 0xF, false);   // lane ^ 2
-        const uint32_t a = t < 2 ? p01 : recv, b = t < 2 ? recv : p23;
-        const uint32_t ax = __builtin_amdgcn_update_dpp(0u, a, 0xB1, 0xF, 0xF, false);        // lane ^ 1
-        const uint32_t bx = __builtin_amdgcn_update_dpp(0u, b, 0xB1, 0xF, 0xF, false);
-        // even lanes take the low halves (own, neighbour), odd lanes the high halves (neighbour, own)
-        const uint32_t o0 = __builtin_amdgcn_perm((t & 1) ? a : ax, (t & 1) ? ax : a, sel);
-        const uint32_t o1 = __builtin_amdgcn_perm((t & 1) ? b : bx, (t & 1) ? bx : b, sel);
-        // streaming stores: the chunk buffer is far larger than any cache and is read back only by later kernels
-        __builtin_nontemporal_store(pack_u64(o0, o1), reinterpret_cast<uint64_t*>(dZt + static_cast<int64_t>(v0 + t) * mcp + (n - t)));
       }
   }
   // the staged block goes out 16 bytes per lane: one instruction covers 4 rows x 256 contiguous bytes
@@ -465,77 +427,110 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
   }
 }
 
-// ------------------------------------------------------------------ bf16: C = A B^T with K-contiguous operands
-// EPI 0: dH[rowsel[c0 + m], j] = bf16(C[m, j] + g[m] W[y[m], j]) for m < mc  (A = dZ [mcp, Vp], B = Wt [d, Vp])
-// EPI 1: dW[v, j] (+)= C[v, j]                              (A = dZt [Vp, mcp], B = Ht [d, mcp])
-template <int EPI>
-__device__ __forceinline__ void
-gemm_tn_body(const uint16_t* __restrict__ A, int64_t lda, int64_t m_rows, const uint16_t* __restrict__ B, int64_t ldb,
-          int n_rows, int K, int tiles_m, int tiles_n, void* __restrict__ out, int64_t ld_out,
-          const int32_t* __restrict__ rowsel, int64_t c0, int64_t m_valid, int accumulate,
-          const uint16_t* __restrict__ W, const int32_t* __restrict__ ids, const float* __restrict__ g_c,
-          uint16_t* lds) {
-  using C = Cfg;
-  int tile_m, tile_n;
-  if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
-  const int64_t m0 = static_cast<int64_t>(tile_m) * C::BM;
-  const int n0 = tile_n * C::BN;
-  using R2 = Ring2Cfg<C>;
-  const uint32_t kofs = ring2_kofs();                               // K is a multiple of 256 here
-  uint32_t oa[R2::NA], ob[R2::NB];
-#pragma unroll
-  for (int i = 0; i < R2::NA; ++i)                                  // clamped rows are not stored below
-    oa[i] = (static_cast<uint32_t>(min(static_cast<int64_t>(ring2_row<C>(i)), m_rows - 1 - m0)) * static_cast<uint32_t>(lda) + kofs) * 2u;
-#pragma unroll
-  for (int i = 0; i < R2::NB; ++i)
-    ob[i] = (static_cast<uint32_t>(min(ring2_row<C>(i), n_rows - 1 - n0)) * static_cast<uint32_t>(ldb) + kofs) * 2u;
-  floatx16 acc[C::TM][C::TN];
+// ------------------------------------------------------------------ bf16: the two gradient products
+// dH = dZ W: A = dZ [mcp, Vp] is K-contiguous (K = vocabulary), B = W [V, d] is K-major and is read as it lies.
+//   dH[rowsel[c0 + m], j] = bf16(C[m, j] + g[m] W[y[m], j]) for m < mc
+// dW = dZ^T H: K = rows of the chunk; A = dZ [mcp, Vp] and B = the selected rows of H [*, d] are both K-major.
+//   dW[v, j] (+)= C[v, j]
+// (kernel templates whose bodies use buffer resources do not get their host stubs emitted: plain kernels)
+template <class C>
+__device__ __forceinline__ void zero_acc(floatx16 (&acc)[C::TM][C::TN]) {
 #pragma unroll
   for (int tm = 0; tm < C::TM; ++tm)
 #pragma unroll
     for (int tn = 0; tn < C::TN; ++tn)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
-  mfma_mainloop_ring2<C>(make_rsrc(A + m0 * lda), oa, make_rsrc(B + static_cast<int64_t>(n0) * ldb), ob, K, lds, acc);
+}
+// K-contiguous operand tile: rows row0 .. row0 + 255 of X [n_rows, ld] (rows past the end read the last one)
+template <class C>
+__device__ __forceinline__ KContig kcontig_tile(const uint16_t* X, int64_t ld, int64_t n_rows, int64_t row0) {
+  KContig c;
+  c.rsrc = make_rsrc(X + row0 * ld);
+  const uint32_t kofs = ring2_kofs();
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    c.off[i] = (static_cast<uint32_t>(min(static_cast<int64_t>(ring2_row<C>(i)), n_rows - 1 - row0)) * static_cast<uint32_t>(ld) + kofs) * 2u;
+  return c;
+}
+
+__global__ void __launch_bounds__(Cfg::T)
+k_gemm_dh(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uint16_t* __restrict__ W, int d, int V, int tiles_m,
+          int tiles_n, uint16_t* __restrict__ dH, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
+          const int32_t* __restrict__ ids, const float* __restrict__ g_c) {
+  using C = Cfg;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[Ring::LDS_BYTES / 2];
+  int tile_m, tile_n;
+  if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
+  const int64_t m0 = static_cast<int64_t>(tile_m) * C::BM;
+  const int n0 = tile_n * C::BN;
+  const KContig ca = kcontig_tile<C>(dZ, Vp, mcp, m0);
+  KMajor kb;
+  kb.base = reinterpret_cast<const char*>(W + n0);
+  kb.ld_bytes = static_cast<int64_t>(d) * 2;
+  kb.rowmap = nullptr;
+  kb.k_rows = V;                                                     // dz is zero for vocabulary ids past V
+  kb.n_units = min(32, (d - n0) / 8);
+  floatx16 acc[C::TM][C::TN];
+  zero_acc<C>(acc);
+  mfma_mainloop_mixed<C, false, true>(ca, KMajor{}, KContig{}, kb, static_cast<int>(Vp), lds, acc);
 #pragma unroll
   for (int tn = 0; tn < C::TN; ++tn) {
     const int j = n0 + acc_col<C>(tn);
-    if (j >= n_rows) continue;
+    if (j >= d) continue;
 #pragma unroll
     for (int tm = 0; tm < C::TM; ++tm)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int64_t m = m0 + acc_row<C>(tm, r);
-        if (m >= m_valid) continue;
-        if (EPI == 0) {
-          const int64_t row = rowsel ? rowsel[c0 + m] : c0 + m;
-          const float g = g_c[c0 + m];
-          float v = acc[tm][tn][r];
-          if (g != 0.f) v += g * bf2f(W[static_cast<int64_t>(ids[row]) * ld_out + j]);   // g = 0 for invalid ids
-          static_cast<uint16_t*>(out)[row * ld_out + j] = f2bf(v);
-        } else {
-          float* dst = static_cast<float*>(out) + m * ld_out + j;
-          *dst = accumulate ? *dst + acc[tm][tn][r] : acc[tm][tn][r];
-        }
+        if (m >= rows) continue;
+        const int64_t row = rowsel ? rowsel[c0 + m] : c0 + m;
+        const float g = g_c[c0 + m];
+        float v = acc[tm][tn][r];
+        if (g != 0.f) v += g * bf2f(W[static_cast<int64_t>(ids[row]) * d + j]);   // g = 0 for invalid ids
+        dH[row * d + j] = f2bf(v);
       }
   }
 }
-
-// (kernel templates whose bodies use buffer resources do not get their host stubs emitted: two plain kernels)
 __global__ void __launch_bounds__(Cfg::T)
-k_gemm_dh(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uint16_t* __restrict__ Wt, int d, int tiles_m,
-          int tiles_n, uint16_t* __restrict__ dH, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
-          const uint16_t* __restrict__ W, const int32_t* __restrict__ ids, const float* __restrict__ g_c) {
+k_gemm_dw(const uint16_t* __restrict__ dZ, int64_t mcp, int64_t Vp, const uint16_t* __restrict__ H, int d, int V,
+          const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows, int tiles_m, int tiles_n, float* __restrict__ dW,
+          int accumulate) {
+  using C = Cfg;
   __shared__ __attribute__((aligned(16))) uint16_t lds[Ring::LDS_BYTES / 2];
-  gemm_tn_body<0>(dZ, Vp, mcp, Wt, Vp, d, static_cast<int>(Vp), tiles_m, tiles_n, dH, d, rowsel, c0, rows, 0, W, ids, g_c,
-                  lds);
-}
-__global__ void __launch_bounds__(Cfg::T)
-k_gemm_dw(const uint16_t* __restrict__ dZt, int64_t mcp, int64_t Vp, const uint16_t* __restrict__ Ht, int d, int V,
-          int tiles_m, int tiles_n, float* __restrict__ dW, int accumulate) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[Ring::LDS_BYTES / 2];
-  gemm_tn_body<1>(dZt, mcp, Vp, Ht, mcp, d, static_cast<int>(mcp), tiles_m, tiles_n, dW, d, nullptr, 0, V, accumulate,
-                  nullptr, nullptr, nullptr, lds);
+  int tile_m, tile_n;
+  if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
+  const int64_t m0 = static_cast<int64_t>(tile_m) * C::BM;
+  const int n0 = tile_n * C::BN;
+  KMajor ka;                                                         // dZ [mcp, Vp]: k = row of the chunk, entries = vocabulary
+  ka.base = reinterpret_cast<const char*>(dZ + m0);
+  ka.ld_bytes = Vp * 2;
+  ka.rowmap = nullptr;
+  ka.k_rows = static_cast<int>(mcp);
+  ka.n_units = 32;
+  KMajor kb;                                                         // H: k = selected row, entries = hidden columns
+  kb.base = reinterpret_cast<const char*>(H + n0 + (rowsel ? 0 : c0 * d));
+  kb.ld_bytes = static_cast<int64_t>(d) * 2;
+  kb.rowmap = rowsel ? rowsel + c0 : nullptr;
+  kb.k_rows = static_cast<int>(rows);                                // dz is zero for rows past the chunk
+  kb.n_units = min(32, (d - n0) / 8);
+  floatx16 acc[C::TM][C::TN];
+  zero_acc<C>(acc);
+  mfma_mainloop_mixed<C, true, true>(KContig{}, ka, KContig{}, kb, static_cast<int>(mcp), lds, acc);
+#pragma unroll
+  for (int tn = 0; tn < C::TN; ++tn) {
+    const int j = n0 + acc_col<C>(tn);
+    if (j >= d) continue;
+#pragma unroll
+    for (int tm = 0; tm < C::TM; ++tm)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t v = m0 + acc_row<C>(tm, r);
+        if (v >= V) continue;
+        float* dst = dW + v * d + j;
+        *dst = accumulate ? *dst + acc[tm][tn][r] : acc[tm][tn][r];
+      }
+  }
 }
 
 // One-hot part of dW: dW[y_n, :] += g_n h_n for every selected row, in float32.  Rows that took the
@@ -637,7 +632,6 @@ struct PpoWs {
   float* a_c;        // per selected row: coefficients of the backward's dense part
   float* kz_c;
   double* blk_stats;
-  uint16_t* Wt;      // bf16 [d][Vp]
   char* chunk;       // rest of the workspace
   size_t fixed_bytes;
 };
@@ -645,7 +639,8 @@ struct PpoWs {
 size_t chunk_bytes(int64_t mc, int d, int V, umas_dtype dt) {
   if (dt == UMAS_F32) return align_up(static_cast<size_t>(mc) * V * sizeof(float));
   const int64_t Vp = round_up(V, 256), mcp = round_up(mc, 256);
-  return align_up(static_cast<size_t>(mcp) * Vp * 2) * 2 + align_up(static_cast<size_t>(d) * mcp * 2);
+  (void)d;
+  return align_up(static_cast<size_t>(mcp) * Vp * 2);
 }
 size_t carve_ppo(Carver& c, PpoWs& w, int64_t n_sel, int d, int V, umas_dtype dt, int n_roles) {
   carve_score(c, w.score, n_sel, V, dt, true);
@@ -654,7 +649,6 @@ size_t carve_ppo(Carver& c, PpoWs& w, int64_t n_sel, int d, int V, umas_dtype dt
   w.a_c = c.take<float>(n_pad);
   w.kz_c = c.take<float>(n_pad);
   w.blk_stats = c.take<double>(static_cast<size_t>(cdiv(n_pad, kRowBlock)) * (1 + n_roles) * kStat);
-  w.Wt = dt == UMAS_BF16 ? c.take<uint16_t>(static_cast<size_t>(d) * round_up(V, 256)) : nullptr;
   w.chunk = c.base ? c.base + c.off : nullptr;
   w.fixed_bytes = c.off;
   return c.off;
@@ -853,27 +847,19 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
   const int64_t Vp = round_up(V, 256);
   const uint16_t* Wb = static_cast<const uint16_t*>(W);
   const uint16_t* Hb = static_cast<const uint16_t*>(H);
-  hipLaunchKernelGGL(k_transpose_bf16, dim3(cdiv(Vp, 64), cdiv(d, 64)), dim3(256), 0, st, Wb, static_cast<int64_t>(d),
-                     static_cast<const int32_t*>(nullptr), static_cast<int64_t>(V), w.Wt, Vp);
-  UMAS_LAUNCHED("k_transpose_bf16");
   for (int64_t c0 = 0; c0 < n_sel; c0 += mc) {
     const int64_t rows = n_sel - c0 < mc ? n_sel - c0 : mc;
     const int64_t mcp = round_up(rows, 256);
     uint16_t* dZ = reinterpret_cast<uint16_t*>(w.chunk);
-    uint16_t* dZt = reinterpret_cast<uint16_t*>(w.chunk + align_up(static_cast<size_t>(mcp) * Vp * 2));
-    uint16_t* Ht = reinterpret_cast<uint16_t*>(w.chunk + 2 * align_up(static_cast<size_t>(mcp) * Vp * 2));
-    hipLaunchKernelGGL(k_transpose_bf16, dim3(cdiv(mcp, 64), cdiv(d, 64)), dim3(256), 0, st, Hb, static_cast<int64_t>(d),
-                       rowsel ? rowsel + c0 : nullptr, rows, Ht, mcp);
-    UMAS_LAUNCHED("k_transpose_bf16");
     const int tiles_v = static_cast<int>(Vp / 256), tiles_r = static_cast<int>(mcp / 256), tiles_d = (d + 255) / 256;
     hipLaunchKernelGGL(k_dz_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r)), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel,
-                       c0, rows, w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, dZ, dZt, Vp, mcp);
+                       c0, rows, w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, dZ, Vp, mcp);
     UMAS_LAUNCHED("k_dz_tiles");
-    hipLaunchKernelGGL(k_gemm_dh, dim3(tile_grid<kGM, kGN>(tiles_r, tiles_d)), dim3(Cfg::T), 0, st, dZ, Vp, mcp, w.Wt, d,
-                       tiles_r, tiles_d, static_cast<uint16_t*>(dH), rowsel, c0, rows, Wb, ids, w.g_c);
+    hipLaunchKernelGGL(k_gemm_dh, dim3(tile_grid<kGM, kGN>(tiles_r, tiles_d)), dim3(Cfg::T), 0, st, dZ, Vp, mcp, Wb, d, V,
+                       tiles_r, tiles_d, static_cast<uint16_t*>(dH), rowsel, c0, rows, ids, w.g_c);
     UMAS_LAUNCHED("k_gemm_dh");
-    hipLaunchKernelGGL(k_gemm_dw, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_d)), dim3(Cfg::T), 0, st, dZt, mcp, Vp, Ht, d, V,
-                       tiles_v, tiles_d, dW, (accumulate_dW || c0 > 0) ? 1 : 0);
+    hipLaunchKernelGGL(k_gemm_dw, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_d)), dim3(Cfg::T), 0, st, dZ, mcp, Vp, Hb, d, V,
+                       rowsel, c0, rows, tiles_v, tiles_d, dW, (accumulate_dW || c0 > 0) ? 1 : 0);
     UMAS_LAUNCHED("k_gemm_dw");
   }
   hipLaunchKernelGGL(k_dw_onehot, dim3(cdiv(n_sel, 4)), dim3(256), 0, st, Hb, d, rowsel, n_sel, ids, w.g_c, dW);
