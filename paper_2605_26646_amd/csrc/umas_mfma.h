@@ -254,7 +254,7 @@ typedef short short4v __attribute__((ext_vector_type(4)));
 struct KMajor {                 // an operand tile stored K-major
   const char* base;             // byte address of (k-row 0, first entry of the tile)
   int64_t ld_bytes;             // bytes between consecutive k-rows
-  const int32_t* rowmap;        // if set, k-row k lives in row rowmap[k] of the matrix (ld_bytes apart, from base)
+  const int32_t* rowmap;        // with BMAP: k-row k lives in row rowmap[k] of the matrix (ld_bytes apart, from base)
   int k_rows;                   // k-rows that exist; later ones read the last one (the other operand is zero there)
   int n_units;                  // 16-byte units of a k-row that exist from base on (<= 32); later ones read the last one
 };
@@ -263,7 +263,7 @@ struct KContig {                // an operand tile stored K-contiguous: per-slot
   uint32_t off[4];
 };
 
-template <class C, bool ATR, bool BTR>
+template <class C, bool ATR, bool BTR, bool BMAP = false>
 __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMajor& ka, const KContig& cb, const KMajor& kb,
                                                     int K, uint16_t* lds, floatx16 (&acc)[C::TM][C::TN]) {
   using R = Ring2Cfg<C>;
@@ -284,9 +284,9 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
 #pragma unroll
     for (int p = 0; p < 4; ++p) rows[p] = k.rowmap[min(sub * R::BK + 16 * p + tr_krow, k.k_rows - 1)];
   };
-  auto gload_kmajor = [&](const KMajor& k, const int32_t (&rows)[4], int sub, char* region) {
+  auto gload_kmajor = [&](const KMajor& k, const int32_t (&rows)[4], int sub, char* region, auto mapped) {
     const uint32_t ubytes = static_cast<uint32_t>(min(tr_slot_unit, k.n_units - 1)) * 16u;
-    if (k.rowmap) {
+    if constexpr (decltype(mapped)::value) {
       const __amdgpu_buffer_rsrc_t r = make_rsrc(k.base);
 #pragma unroll
       for (int p = 0; p < 4; ++p)
@@ -311,8 +311,8 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
   };
   auto gload = [&](int sub, int stage) {
     char* sa = base + stage * R::STAGEB;
-    if (ATR) gload_kmajor(ka, rows_a, sub, sa); else gload_kcontig(ca, sub, sa);
-    if (BTR) gload_kmajor(kb, rows_b, sub, sa + kAB); else gload_kcontig(cb, sub, sa + kAB);
+    if (ATR) gload_kmajor(ka, rows_a, sub, sa, std::false_type{}); else gload_kcontig(ca, sub, sa);
+    if (BTR) gload_kmajor(kb, rows_b, sub, sa + kAB, std::integral_constant<bool, BMAP>{}); else gload_kcontig(cb, sub, sa + kAB);
   };
 
   // fragment addresses
@@ -402,11 +402,9 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
   using K1 = std::integral_constant<int, 1>;
   using K2 = std::integral_constant<int, 2>;
   using K3 = std::integral_constant<int, 3>;
-  if (ATR && ka.rowmap) map_rows(ka, 0, rows_a);
-  if (BTR && kb.rowmap) map_rows(kb, 0, rows_b);
+  if (BTR && BMAP) map_rows(kb, 0, rows_b);
   gload(0, 0);
-  if (ATR && ka.rowmap) map_rows(ka, nsub > 1 ? 1 : 0, rows_a);
-  if (BTR && kb.rowmap) map_rows(kb, nsub > 1 ? 1 : 0, rows_b);
+  if (BTR && BMAP) map_rows(kb, nsub > 1 ? 1 : 0, rows_b);
   __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();
   fload(0, 0, K0{});
@@ -416,8 +414,7 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
     tr_wait(0);
     gload(sub_next, st ^ 1);
     const int sub_after = j + 2 < nsub ? j + 2 : nsub - 1;
-    if (ATR && ka.rowmap) map_rows(ka, sub_after, rows_a);
-    if (BTR && kb.rowmap) map_rows(kb, sub_after, rows_b);
+    if (BTR && BMAP) map_rows(kb, sub_after, rows_b);
     fload(1, st, K1{});
     mfmas(0);
     interleave(kDs, 8);

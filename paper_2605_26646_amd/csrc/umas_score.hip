@@ -516,7 +516,8 @@ k_gemm_dw(const uint16_t* __restrict__ dZ, int64_t mcp, int64_t Vp, const uint16
   kb.n_units = min(32, (d - n0) / 8);
   floatx16 acc[C::TM][C::TN];
   zero_acc<C>(acc);
-  mfma_mainloop_mixed<C, true, true>(KContig{}, ka, KContig{}, kb, static_cast<int>(mcp), lds, acc);
+  if (rowsel) mfma_mainloop_mixed<C, true, true, true>(KContig{}, ka, KContig{}, kb, static_cast<int>(mcp), lds, acc);
+  else mfma_mainloop_mixed<C, true, true, false>(KContig{}, ka, KContig{}, kb, static_cast<int>(mcp), lds, acc);
 #pragma unroll
   for (int tn = 0; tn < C::TN; ++tn) {
     const int j = n0 + acc_col<C>(tn);
