@@ -456,27 +456,33 @@ __device__ __forceinline__ int acc_col(int tn) {
 
 // Workgroups are handed to the 8 XCDs round-robin; give every XCD a contiguous range of the
 // logical tile order, and order tiles in groups of GM x GN so that the workgroups resident on
-// one XCD share operand rows through its L2.  Returns false for a padding workgroup.
+// one XCD share operand rows through its L2.  A workgroup handles `per_wg` tiles one after the other:
+// the tile with the same place in `per_wg` consecutive groups, so that the workgroups of an XCD keep
+// working on one group at a time.  Returns false when iteration `it` of this workgroup has no tile.
 template <int GM, int GN>
-__device__ __forceinline__ bool tile_coords(int tiles_m, int tiles_n, int* tm, int* tn) {
+__device__ __forceinline__ bool tile_coords(int tiles_m, int tiles_n, int* tm, int* tn, int it = 0, int per_wg = 1) {
   const int total_groups_n = (tiles_n + GN - 1) / GN;
   const int total_groups_m = (tiles_m + GM - 1) / GM;
-  const long long slots = static_cast<long long>(total_groups_m) * total_groups_n * (GM * GN);
-  const long long per_xcd = (slots + 7) / 8;
+  const long long groups = static_cast<long long>(total_groups_m) * total_groups_n;
+  const long long groups_per_xcd = (groups + 7) / 8;                       // contiguous range of groups per XCD
   const long long bid = blockIdx.x;
-  const long long logical = (bid & 7) * per_xcd + (bid >> 3);
-  if ((bid >> 3) >= per_xcd || logical >= slots) return false;
-  const long long grp = logical / (GM * GN);
-  const int within = static_cast<int>(logical % (GM * GN));
+  const long long w = bid >> 3;                                            // workgroup number inside its XCD
+  const long long grp_in_xcd = (w / (GM * GN)) * per_wg + it;
+  const int within = static_cast<int>(w % (GM * GN));
+  if (grp_in_xcd >= groups_per_xcd) return false;
+  const long long grp = (bid & 7) * groups_per_xcd + grp_in_xcd;
+  if (grp >= groups) return false;
   const int gm = static_cast<int>(grp / total_groups_n), gn = static_cast<int>(grp % total_groups_n);
   *tm = gm * GM + within % GM;
   *tn = gn * GN + within / GM;
   return *tm < tiles_m && *tn < tiles_n;
 }
 template <int GM, int GN>
-inline unsigned tile_grid(int tiles_m, int tiles_n) {
-  const long long slots = static_cast<long long>((tiles_m + GM - 1) / GM) * ((tiles_n + GN - 1) / GN) * (GM * GN);
-  return static_cast<unsigned>(((slots + 7) / 8) * 8);
+inline unsigned tile_grid(int tiles_m, int tiles_n, int per_wg = 1) {
+  const long long groups = static_cast<long long>((tiles_m + GM - 1) / GM) * ((tiles_n + GN - 1) / GN);
+  const long long groups_per_xcd = (groups + 7) / 8;
+  const long long wg_groups = (groups_per_xcd + per_wg - 1) / per_wg;       // groups of workgroups per XCD
+  return static_cast<unsigned>(wg_groups * (GM * GN) * 8);
 }
 
 }  // namespace umas

@@ -23,6 +23,7 @@ using Cfg = TileCfg<256, 256, 2, 4>;   // 8 wavefronts, two per SIMD: one issues
 using Ring = Ring2Cfg<Cfg>;
 constexpr int kLogitLds = Ring::LDS_BYTES > Cfg::LDS_BYTES ? Ring::LDS_BYTES : Cfg::LDS_BYTES;   // both main loops fit
 constexpr int kGM = 4, kGN = 8;          // tile group resident on one XCD
+constexpr int kTilesPerWg = 4;           // logit tiles a workgroup computes one after the other (short K: launch gaps and store drain overlap)
 constexpr int kRowBlock = 256;
 constexpr float kNegInf = -INFINITY;
 constexpr float kMasked = -1e30f;        // stands for a logit that does not exist (vocabulary tail)
@@ -116,8 +117,9 @@ k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, in
               int tiles_m, int tiles_n, float4* __restrict__ partial, int64_t n_pad) {
   using C = Cfg;
   __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
+  for (int it = 0; it < kTilesPerWg; ++it) {     // a workgroup walks the same place of kTilesPerWg consecutive tile groups
   int tile_m, tile_n;
-  if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
+  if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n, it, kTilesPerWg)) continue;
   const int m0 = tile_m * C::BM;
   const int64_t n0 = static_cast<int64_t>(tile_n) * C::BN;
   floatx16 acc[C::TM][C::TN];
@@ -192,6 +194,8 @@ k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, in
       p = part_merge(p, Part{src[0], src[1], src[2]});
     }
     if (n0 + col < n_pad) partial[static_cast<int64_t>(tile_m) * n_pad + n0 + col] = make_float4(p.m, p.s, p.t, s_zy[col]);
+  }
+  __syncthreads();                              // the LDS is the next tile's again
   }
 }
 
@@ -362,8 +366,9 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
            int tiles_m, int tiles_n, uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp) {
   using C = Cfg;
   __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
+  for (int it = 0; it < kTilesPerWg; ++it) {     // a workgroup walks the same place of kTilesPerWg consecutive tile groups
   int tile_m, tile_n;
-  if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
+  if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n, it, kTilesPerWg)) continue;
   const int m0 = tile_m * C::BM;
   const int64_t n0 = static_cast<int64_t>(tile_n) * C::BN;   // chunk-relative
   floatx16 acc[C::TM][C::TN];
@@ -424,6 +429,8 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
     const uint4 v = *reinterpret_cast<const uint4*>(stage + row * kStagePitch + (lane & 15) * 16);
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(out + static_cast<int64_t>(row) * Vp));
+  }
+  __syncthreads();                              // the LDS is the next tile's again
   }
 }
 
@@ -690,7 +697,7 @@ umas_status run_score(const void* H, const void* W, umas_dtype dt, int d, int V,
     const int tiles_m = (V + Cfg::BM - 1) / Cfg::BM;
     const int tiles_n = static_cast<int>((n_sel + Cfg::BN - 1) / Cfg::BN);
     const int64_t n_pad = round_up(n_sel, Cfg::BN);
-    hipLaunchKernelGGL(k_score_tiles, dim3(tile_grid<kGM, kGN>(tiles_m, tiles_n)), dim3(Cfg::T), 0, st,
+    hipLaunchKernelGGL(k_score_tiles, dim3(tile_grid<kGM, kGN>(tiles_m, tiles_n, kTilesPerWg)), dim3(Cfg::T), 0, st,
                        static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), d, V, rowsel, n_sel, ids,
                        tiles_m, tiles_n, w.partial, n_pad);
     UMAS_LAUNCHED("k_score_tiles");
@@ -853,7 +860,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     const int64_t mcp = round_up(rows, 256);
     uint16_t* dZ = reinterpret_cast<uint16_t*>(w.chunk);
     const int tiles_v = static_cast<int>(Vp / 256), tiles_r = static_cast<int>(mcp / 256), tiles_d = (d + 255) / 256;
-    hipLaunchKernelGGL(k_dz_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r)), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel,
+    hipLaunchKernelGGL(k_dz_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r, kTilesPerWg)), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel,
                        c0, rows, w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, dZ, Vp, mcp);
     UMAS_LAUNCHED("k_dz_tiles");
     hipLaunchKernelGGL(k_gemm_dh, dim3(tile_grid<kGM, kGN>(tiles_r, tiles_d)), dim3(Cfg::T), 0, st, dZ, Vp, mcp, Wb, d, V,
