@@ -110,28 +110,52 @@ __device__ __forceinline__ void logit_tile(const uint16_t* __restrict__ W, const
 
 // ------------------------------------------------------------------ bf16: logit tiles -> partials
 // A = W (vocabulary rows on the M side, so one lane sees many vocabulary entries of one token),
-// B = selected rows of H.  partial[tile_m][n] = (m, s, t, taken logit or 0).
-__global__ void __launch_bounds__(Cfg::T)
-k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
-              const int32_t* __restrict__ rowsel, int64_t n_sel, const int32_t* __restrict__ ids,
-              int tiles_m, int tiles_n, float4* __restrict__ partial, int64_t n_pad) {
+// B = rows c0 .. c0 + mc - 1 of the selection.  partial[tile_m][n] = (m, s, t, taken logit or 0).
+//
+// The keeping variant serves the backward pass when the dense part of dz is a row factor times the softmax
+// (no entropy bonus): it also writes E[n, v] = bf16(exp(z[n, v] - c_n)) to the chunk buffer [mcp, Vp], c_n a
+// per-row reference known before the pass (the taken token's logit), so that dz = (a_n exp(c_n - lse_n)) E
+// needs no second pass over the logits: the row factor is applied where dH is written and folded into the
+// copy of H that dW reads.  A block of 256 rows in which some logit exceeds its reference by more than kKeepMaxGap
+// (E could overflow) is flagged and gets its dz from the recomputing kernel instead.
+constexpr float kKeepMaxGap = 50.f;
+constexpr int kStagePitch = Cfg::WTM * 2 + 16;                                  // one staged row: 128 bf16, 16-byte aligned
+constexpr int kStageBytes = Cfg::WM * Cfg::WN * Cfg::WTN * kStagePitch;         // every wavefront stages its 128 x 64 block
+constexpr int kPartBytes = (Cfg::WM * Cfg::BN * 3 + Cfg::BN) * 4;
+constexpr int kKeepLds = (kLogitLds > kStageBytes ? kLogitLds : kStageBytes) + kPartBytes;
+static_assert(kStageBytes <= kLogitLds, "staging fits the tile buffers");
+static_assert(kKeepLds <= 160 * 1024, "LDS of one CU");
+
+struct KeepArgs {
+  const float* cref;   // [n_pad] reference per selected row, NaN for rows without a valid id
+  uint16_t* E;         // [mcp, Vp]
+  int64_t Vp;
+  int32_t* flags;      // per block of 256 selected rows
+};
+
+template <bool KEEP>
+__device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
+                                            const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc,
+                                            const int32_t* __restrict__ ids, int tiles_m, int tiles_n,
+                                            float4* __restrict__ partial, int64_t n_pad, const KeepArgs& keep,
+                                            uint16_t* lds) {
   using C = Cfg;
-  __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
   for (int it = 0; it < kTilesPerWg; ++it) {     // a workgroup walks the same place of kTilesPerWg consecutive tile groups
   int tile_m, tile_n;
   if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n, it, kTilesPerWg)) continue;
   const int m0 = tile_m * C::BM;
-  const int64_t n0 = static_cast<int64_t>(tile_n) * C::BN;
+  const int64_t n0 = static_cast<int64_t>(tile_n) * C::BN;   // chunk-relative
   floatx16 acc[C::TM][C::TN];
-  logit_tile<C>(W, H, d, V, rowsel, 0, n_sel, m0, n0, lds, acc);
+  logit_tile<C>(W, H, d, V, rowsel, c0, mc, m0, n0, lds, acc);
 
   // epilogue: the tile buffers are free now
-  float* s_part = reinterpret_cast<float*>(lds);          // [WM][BN][3]
+  float* s_part = reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + (KEEP ? kKeepLds - kPartBytes : 0));   // [WM][BN][3]
   float* s_zy = s_part + C::WM * C::BN * 3;               // [BN]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN;
+  char* stage = reinterpret_cast<char*>(lds) + wave * (C::WTN * kStagePitch);
   if (threadIdx.x < C::BN) s_zy[threadIdx.x] = 0.f;
-  __syncthreads();
+  __syncthreads();                                        // every wavefront has left the main loop's LDS reads
   const int vbase = m0 + wm * C::WTM + (lane >> 5) * 4;   // vocabulary id of element (tm=0, r=0)
   const bool tail = m0 + C::BM > V;
   if (tail) {   // vocabulary ids past V: a large negative logit whose exponential is 0 and whose products stay finite
@@ -144,6 +168,7 @@ k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, in
           if (vbase + tm * 32 + (r >> 2) * 8 + (r & 3) >= V) acc[tm][tn][r] = kMasked;
   }
   constexpr float kLog2e = 1.44269504088896341f;
+  bool over = false;
 #pragma unroll
   for (int tn = 0; tn < C::TN; ++tn) {
     const int col = acc_col<C>(tn);
@@ -153,15 +178,36 @@ k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, in
     for (int tm = 0; tm < C::TM; ++tm)
 #pragma unroll
       for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[tm][tn][r]);
+    // The keeping variant sums relative to the row's reference c_n instead of the lane's maximum (any reference
+    // serves the merge as long as nothing overflows), so the exponentials it sums are the numerators it keeps.
+    // A lane whose maximum lies more than kKeepMaxGap above c_n flags the block and falls back to its maximum;
+    // rows without a valid id (reference NaN) use the maximum too and flag nothing: their row factor is 0.
+    if (KEEP) {
+      const float c = n < mc ? keep.cref[c0 + n] : 1e30f;   // rows past the chunk: every exponential is 0, E = 0
+      const float gap = m - c;
+      over |= gap > kKeepMaxGap;
+      if (gap <= kKeepMaxGap) m = c;
+      else if (m == kMasked) m = 0.f;                       // nothing but vocabulary tail in this lane: exponentials 0 as well
+    }
     float s = 0.f, t = 0.f;
 #pragma unroll
     for (int tm = 0; tm < C::TM; ++tm)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float z = acc[tm][tn][r];
-        const float e = __builtin_amdgcn_exp2f((z - m) * kLog2e);   // z - m first: exact 0 for masked-only columns
-        s += e;
-        t = fmaf(e, z, t);
+      for (int q = 0; q < 4; ++q) {
+        float e[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float z = acc[tm][tn][q * 4 + j];
+          e[j] = __builtin_amdgcn_exp2f((z - m) * kLog2e);   // z - m first: exact 0 for masked-only columns
+          s += e[j];
+          t = fmaf(e[j], z, t);
+        }
+        if (KEEP) {   // staged in this wavefront's LDS region, stored in full lines below
+          const uint32_t p01 = static_cast<uint32_t>(f2bf(e[0])) | (static_cast<uint32_t>(f2bf(e[1])) << 16);
+          const uint32_t p23 = static_cast<uint32_t>(f2bf(e[2])) | (static_cast<uint32_t>(f2bf(e[3])) << 16);
+          *reinterpret_cast<uint2*>(stage + (tn * 32 + (lane & 31)) * kStagePitch + (tm * 32 + q * 8 + (lane >> 5) * 4) * 2) =
+              make_uint2(p01, p23);
+        }
       }
     Part p{m, s, t};
     Part q{__shfl_xor(p.m, 32, kWave), __shfl_xor(p.s, 32, kWave), __shfl_xor(p.t, 32, kWave)};
@@ -170,8 +216,8 @@ k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, in
       float* dst = s_part + (wm * C::BN + col) * 3;
       dst[0] = p.m; dst[1] = p.s; dst[2] = p.t;
     }
-    if (n < n_sel) {
-      const int y = ids[rowsel ? rowsel[n] : n];
+    if (n < mc) {
+      const int y = ids[rowsel ? rowsel[c0 + n] : c0 + n];
       const int rel = y - vbase;                           // offset from this lane's first element
       if (y >= 0 && y < V && rel >= 0 && rel < C::WTM && ((rel >> 2) & 1) == 0) {
         float zy = 0.f;
@@ -184,6 +230,19 @@ k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, in
       }
     }
   }
+  if (KEEP) {
+    if (over) keep.flags[(c0 >> 8) + tile_n] = 1;
+    // the staged block goes out 16 bytes per lane: one instruction covers 4 rows x 256 contiguous bytes
+    const int wn = wave % C::WN;
+    uint16_t* out = keep.E + (n0 + wn * C::WTN) * keep.Vp + m0 + wm * C::WTM + (lane & 15) * 8;
+#pragma unroll 8
+    for (int i = 0; i < C::WTN / 4; ++i) {
+      const int row = i * 4 + (lane >> 4);
+      const uint4 v = *reinterpret_cast<const uint4*>(stage + row * kStagePitch + (lane & 15) * 16);
+      typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+      __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(out + static_cast<int64_t>(row) * keep.Vp));
+    }
+  }
   __syncthreads();
   if (threadIdx.x < C::BN) {
     const int col = threadIdx.x;
@@ -193,19 +252,36 @@ k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, in
       const float* src = s_part + (w * C::BN + col) * 3;
       p = part_merge(p, Part{src[0], src[1], src[2]});
     }
-    if (n0 + col < n_pad) partial[static_cast<int64_t>(tile_m) * n_pad + n0 + col] = make_float4(p.m, p.s, p.t, s_zy[col]);
+    if (c0 + n0 + col < n_pad) partial[static_cast<int64_t>(tile_m) * n_pad + c0 + n0 + col] = make_float4(p.m, p.s, p.t, s_zy[col]);
   }
   __syncthreads();                              // the LDS is the next tile's again
   }
 }
 
+// (kernel templates whose bodies use buffer resources do not get their host stubs emitted: plain kernels)
+__global__ void __launch_bounds__(Cfg::T)
+k_score_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
+              const int32_t* __restrict__ rowsel, int64_t n_sel, const int32_t* __restrict__ ids,
+              int tiles_m, int tiles_n, float4* __restrict__ partial, int64_t n_pad) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
+  score_tiles<false>(W, H, d, V, rowsel, 0, n_sel, ids, tiles_m, tiles_n, partial, n_pad, KeepArgs{}, lds);
+}
+__global__ void __launch_bounds__(Cfg::T)
+k_score_keep_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
+                   const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc, const int32_t* __restrict__ ids,
+                   int tiles_m, int tiles_n, float4* __restrict__ partial, int64_t n_pad,
+                   const float* __restrict__ cref, uint16_t* __restrict__ E, int64_t Vp, int32_t* __restrict__ flags) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[kKeepLds / 2];
+  score_tiles<true>(W, H, d, V, rowsel, c0, mc, ids, tiles_m, tiles_n, partial, n_pad, KeepArgs{cref, E, Vp, flags}, lds);
+}
+
 // Merge the per-tile partials of each selected row; compact results and optional scatter.
-__global__ void k_score_finalize(const float4* __restrict__ partial, int tiles_m, int64_t n_pad, int64_t n_sel,
-                                 const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
+__global__ void k_score_finalize(const float4* __restrict__ partial, int tiles_m, int64_t n_pad, int64_t n_begin,
+                                 int64_t n_end, const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
                                  float* __restrict__ logp_c, float* __restrict__ lse_c, float* __restrict__ ent_c,
                                  float* __restrict__ logp, float* __restrict__ lse, float* __restrict__ entropy) {
-  const int64_t n = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (n >= n_sel) return;
+  const int64_t n = n_begin + static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (n >= n_end) return;
   Part p{kNegInf, 0.f, 0.f};
   float zy = 0.f;
   for (int tm = 0; tm < tiles_m; ++tm) {
@@ -276,7 +352,7 @@ k_score_f32(const float* __restrict__ W, const float* __restrict__ H, int d, int
 // logp_old - logp, rows, invalid ids) for the model and for each role, in float64.
 constexpr int kStat = 6;
 __global__ void __launch_bounds__(kRowBlock)
-k_ppo_rows(int64_t n_sel, const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
+k_ppo_rows(int64_t n_sel, int64_t n_begin, int64_t n_end, const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
            const float* __restrict__ logp_c, const float* __restrict__ ent_c, const float* __restrict__ logp_old,
            const float* __restrict__ adv, const int32_t* __restrict__ tok_role, int n_roles, float clip_eps,
            float dual_clip, float k_ent, const float* __restrict__ lse_c, float* __restrict__ g_c,
@@ -285,8 +361,8 @@ k_ppo_rows(int64_t n_sel, const int32_t* __restrict__ rowsel, const int32_t* __r
   const int nacc = (1 + n_roles) * kStat;
   for (int i = threadIdx.x; i < nacc; i += blockDim.x) s_acc[i] = 0.0;
   __syncthreads();
-  const int64_t n = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (n < n_sel) {
+  const int64_t n = n_begin + static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;   // n_begin is a multiple of the block size
+  if (n < n_end) {
     const int64_t row = rowsel ? rowsel[n] : n;
     const int y = ids[row];
     const bool ok = y >= 0 && y < V;
@@ -325,7 +401,8 @@ k_ppo_rows(int64_t n_sel, const int32_t* __restrict__ rowsel, const int32_t* __r
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < nacc; i += blockDim.x) blk_stats[static_cast<int64_t>(blockIdx.x) * nacc + i] = s_acc[i];
+  const int64_t blk = n_begin / kRowBlock + blockIdx.x;
+  for (int i = threadIdx.x; i < nacc; i += blockDim.x) blk_stats[blk * nacc + i] = s_acc[i];
 }
 
 __global__ void __launch_bounds__(256)
@@ -354,21 +431,81 @@ k_ppo_stats(int nblk, int n_roles, float entropy_coef, const double* __restrict_
   }
 }
 
+// ------------------------------------------------------------------ bf16: row references and row factors of the keeping pass
+__device__ __forceinline__ void bf16x8_to_f32(const uint4 v, float (&o)[8]) {
+  o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+  o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+  o[4] = __uint_as_float(v.z << 16); o[5] = __uint_as_float(v.z & 0xffff0000u);
+  o[6] = __uint_as_float(v.w << 16); o[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+// cref[n] = h_n . W[y_n], the taken token's logit (never above the row's logsumexp); NaN for an invalid id.
+// One wavefront per selected row.
+__global__ void __launch_bounds__(256)
+k_label_logit(const uint16_t* __restrict__ H, const uint16_t* __restrict__ W, int d, int V,
+              const int32_t* __restrict__ rowsel, int64_t n_sel, const int32_t* __restrict__ ids,
+              float* __restrict__ cref) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n = static_cast<int64_t>(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (n >= n_sel) return;
+  const int64_t row = rowsel ? rowsel[n] : n;
+  const int y = ids[row];
+  if (y < 0 || y >= V) {
+    if (lane == 0) cref[n] = NAN;
+    return;
+  }
+  const uint4* h = reinterpret_cast<const uint4*>(H + row * d);
+  const uint4* w = reinterpret_cast<const uint4*>(W + static_cast<int64_t>(y) * d);
+  float s = 0.f;
+  for (int k = lane; k < d / 8; k += kWave) {
+    float a[8], b[8];
+    bf16x8_to_f32(h[k], a);
+    bf16x8_to_f32(w[k], b);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s = fmaf(a[j], b[j], s);
+  }
+  s = wave_sum(s);
+  if (lane == 0) cref[n] = s;
+}
+// Row factor sc[n] = a_n exp(c_n - lse_n) of dz = sc E, and Hs[n - c0, :] = bf16(sc[n] h_n), the operand dW reads.
+// Rows of a flagged block get factor 1: their dz comes complete from the recomputing kernel.
+__global__ void __launch_bounds__(256)
+k_keep_rows(const uint16_t* __restrict__ H, int d, int V, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
+            const int32_t* __restrict__ ids, const float* __restrict__ lse_c, const float* __restrict__ a_c,
+            const float* __restrict__ cref, const int32_t* __restrict__ flags, float* __restrict__ sc,
+            uint16_t* __restrict__ Hs) {
+  const int lane = threadIdx.x & 63;
+  const int64_t m = static_cast<int64_t>(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (m >= rows) return;
+  const int64_t n = c0 + m;
+  const int64_t row = rowsel ? rowsel[n] : n;
+  const float a = a_c[n];
+  float f = 1.f;
+  if (!flags[n >> 8]) f = a != 0.f ? a * __expf(cref[n] - lse_c[n]) : 0.f;   // a = 0: invalid id (reference NaN) or no gradient
+  if (lane == 0) sc[n] = f;
+  const uint4* h = reinterpret_cast<const uint4*>(H + row * d);
+  uint4* o = reinterpret_cast<uint4*>(Hs + m * d);
+  for (int k = lane; k < d / 8; k += kWave) {
+    float x[8];
+    bf16x8_to_f32(h[k], x);
+    uint4 v;
+    v.x = static_cast<uint32_t>(f2bf(x[0] * f)) | (static_cast<uint32_t>(f2bf(x[1] * f)) << 16);
+    v.y = static_cast<uint32_t>(f2bf(x[2] * f)) | (static_cast<uint32_t>(f2bf(x[3] * f)) << 16);
+    v.z = static_cast<uint32_t>(f2bf(x[4] * f)) | (static_cast<uint32_t>(f2bf(x[5] * f)) << 16);
+    v.w = static_cast<uint32_t>(f2bf(x[6] * f)) | (static_cast<uint32_t>(f2bf(x[7] * f)) << 16);
+    o[k] = v;
+  }
+}
+
 // ------------------------------------------------------------------ bf16: dz tiles into the chunk buffer
 // Same tile product as k_score_tiles; the epilogue forms the dense part of dz = g (onehot - softmax),
 // -g exp(z - lse), plus the entropy bonus's term when its coefficient is not 0, and writes it as bf16 to
 // dZ [mcp, Vp].  Rows past the chunk and vocabulary ids past V get 0.  The one-hot part g at v = y is a single term per row and is added in
 // float32 where dH and dW are written, so that it never meets the bf16 rounding of the dense part.
-__global__ void __launch_bounds__(Cfg::T)
-k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
-           const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc,
-           const float* __restrict__ lse_c, const float* __restrict__ a_c, const float* __restrict__ kz_c,
-           int tiles_m, int tiles_n, uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp) {
+__device__ __forceinline__ void dz_tile(int tile_m, int tile_n, const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
+                                        int d, int V, const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc,
+                                        const float* __restrict__ lse_c, const float* __restrict__ a_c,
+                                        const float* __restrict__ kz_c, uint16_t* __restrict__ dZ, int64_t Vp, uint16_t* lds) {
   using C = Cfg;
-  __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
-  for (int it = 0; it < kTilesPerWg; ++it) {     // a workgroup walks the same place of kTilesPerWg consecutive tile groups
-  int tile_m, tile_n;
-  if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n, it, kTilesPerWg)) continue;
   const int m0 = tile_m * C::BM;
   const int64_t n0 = static_cast<int64_t>(tile_n) * C::BN;   // chunk-relative
   floatx16 acc[C::TM][C::TN];
@@ -378,9 +515,7 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
   const int wm = wave / C::WN;
   const int vbase = m0 + wm * C::WTM + (lane >> 5) * 4;
   const bool tail = m0 + C::BM > V;
-  // each wavefront stages its 128 (rows) x 128 (vocabulary) block; 272-byte pitch keeps 16-byte alignment
-  constexpr int kStagePitch = C::WTM * 2 + 16;
-  static_assert(C::WM * C::WN * C::WTN * kStagePitch <= kLogitLds, "staging fits the tile buffers");
+  // each wavefront stages its 64 (rows) x 128 (vocabulary) block; the 272-byte pitch keeps 16-byte alignment
   char* stage = reinterpret_cast<char*>(lds) + wave * (C::WTN * kStagePitch);
   __syncthreads();                              // every wavefront has left the main loop's LDS reads
   if (tail) {                                   // vocabulary ids past V: the exponential below is 0, the factor next to it finite
@@ -431,12 +566,38 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
     __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(out + static_cast<int64_t>(row) * Vp));
   }
   __syncthreads();                              // the LDS is the next tile's again
+}
+__global__ void __launch_bounds__(Cfg::T)
+k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
+           const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc,
+           const float* __restrict__ lse_c, const float* __restrict__ a_c, const float* __restrict__ kz_c,
+           int tiles_m, int tiles_n, uint16_t* __restrict__ dZ, int64_t Vp) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
+  for (int it = 0; it < kTilesPerWg; ++it) {     // a workgroup walks the same place of kTilesPerWg consecutive tile groups
+    int tile_m, tile_n;
+    if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n, it, kTilesPerWg)) continue;
+    dz_tile(tile_m, tile_n, W, H, d, V, rowsel, c0, mc, lse_c, a_c, kz_c, dZ, Vp, lds);
+  }
+}
+// The same tiles for the blocks of 256 rows that the keeping scoring pass has flagged, and only those: a fixed,
+// small grid walks (flagged block, vocabulary tile) pairs, so that the usual case of no flag costs next to nothing.
+constexpr int kFlaggedGrid = 256;
+__global__ void __launch_bounds__(Cfg::T)
+k_dz_flagged(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
+             const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc,
+             const float* __restrict__ lse_c, const float* __restrict__ a_c, const float* __restrict__ kz_c,
+             int tiles_m, int tiles_n, uint16_t* __restrict__ dZ, int64_t Vp, const int32_t* __restrict__ flags) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
+  for (int tile_n = 0; tile_n < tiles_n; ++tile_n) {
+    if (!flags[(c0 >> 8) + tile_n]) continue;                       // the same for every thread of the grid
+    for (int tile_m = blockIdx.x; tile_m < tiles_m; tile_m += gridDim.x)
+      dz_tile(tile_m, tile_n, W, H, d, V, rowsel, c0, mc, lse_c, a_c, kz_c, dZ, Vp, lds);
   }
 }
 
 // ------------------------------------------------------------------ bf16: the two gradient products
 // dH = dZ W: A = dZ [mcp, Vp] is K-contiguous (K = vocabulary), B = W [V, d] is K-major and is read as it lies.
-//   dH[rowsel[c0 + m], j] = bf16(C[m, j] + g[m] W[y[m], j]) for m < mc
+//   dH[rowsel[c0 + m], j] = bf16(sc[m] C[m, j] + g[m] W[y[m], j]) for m < mc (sc: the keeping pass's row factor, else 1)
 // dW = dZ^T H: K = rows of the chunk; A = dZ [mcp, Vp] and B = the selected rows of H [*, d] are both K-major.
 //   dW[v, j] (+)= C[v, j]
 // (kernel templates whose bodies use buffer resources do not get their host stubs emitted: plain kernels)
@@ -464,7 +625,7 @@ __device__ __forceinline__ KContig kcontig_tile(const uint16_t* X, int64_t ld, i
 __global__ void __launch_bounds__(Cfg::T)
 k_gemm_dh(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uint16_t* __restrict__ W, int d, int V, int tiles_m,
           int tiles_n, uint16_t* __restrict__ dH, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
-          const int32_t* __restrict__ ids, const float* __restrict__ g_c) {
+          const int32_t* __restrict__ ids, const float* __restrict__ g_c, const float* __restrict__ sc) {
   using C = Cfg;
   __shared__ __attribute__((aligned(16))) uint16_t lds[Ring::LDS_BYTES / 2];
   int tile_m, tile_n;
@@ -493,7 +654,7 @@ k_gemm_dh(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uint16
         if (m >= rows) continue;
         const int64_t row = rowsel ? rowsel[c0 + m] : c0 + m;
         const float g = g_c[c0 + m];
-        float v = acc[tm][tn][r];
+        float v = sc ? sc[c0 + m] * acc[tm][tn][r] : acc[tm][tn][r];
         if (g != 0.f) v += g * bf2f(W[static_cast<int64_t>(ids[row]) * d + j]);   // g = 0 for invalid ids
         dH[row * d + j] = f2bf(v);
       }
@@ -639,16 +800,18 @@ struct PpoWs {
   float* g_c;
   float* a_c;        // per selected row: coefficients of the backward's dense part
   float* kz_c;
+  float* cref;       // keeping pass: per selected row, the reference of E and the row factor of dz = sc E
+  float* sc;
+  int32_t* flags;    // keeping pass: blocks of 256 selected rows whose dz must be recomputed
   double* blk_stats;
-  char* chunk;       // rest of the workspace
+  char* chunk;       // rest of the workspace: dZ (or E) [mcp, Vp], then the scaled copy of the chunk's rows of H
   size_t fixed_bytes;
 };
 // bytes one chunk of mc rows needs
 size_t chunk_bytes(int64_t mc, int d, int V, umas_dtype dt) {
   if (dt == UMAS_F32) return align_up(static_cast<size_t>(mc) * V * sizeof(float));
   const int64_t Vp = round_up(V, 256), mcp = round_up(mc, 256);
-  (void)d;
-  return align_up(static_cast<size_t>(mcp) * Vp * 2);
+  return align_up(static_cast<size_t>(mcp) * Vp * 2) + align_up(static_cast<size_t>(mcp) * d * 2);
 }
 size_t carve_ppo(Carver& c, PpoWs& w, int64_t n_sel, int d, int V, umas_dtype dt, int n_roles) {
   carve_score(c, w.score, n_sel, V, dt, true);
@@ -656,6 +819,9 @@ size_t carve_ppo(Carver& c, PpoWs& w, int64_t n_sel, int d, int V, umas_dtype dt
   w.g_c = c.take<float>(n_pad);
   w.a_c = c.take<float>(n_pad);
   w.kz_c = c.take<float>(n_pad);
+  w.cref = c.take<float>(n_pad);
+  w.sc = c.take<float>(n_pad);
+  w.flags = c.take<int32_t>(static_cast<size_t>(cdiv(n_pad, kRowBlock)));
   w.blk_stats = c.take<double>(static_cast<size_t>(cdiv(n_pad, kRowBlock)) * (1 + n_roles) * kStat);
   w.chunk = c.base ? c.base + c.off : nullptr;
   w.fixed_bytes = c.off;
@@ -701,8 +867,8 @@ umas_status run_score(const void* H, const void* W, umas_dtype dt, int d, int V,
                        static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), d, V, rowsel, n_sel, ids,
                        tiles_m, tiles_n, w.partial, n_pad);
     UMAS_LAUNCHED("k_score_tiles");
-    hipLaunchKernelGGL(k_score_finalize, dim3(cdiv(n_sel, 256)), dim3(256), 0, st, w.partial, tiles_m, n_pad, n_sel,
-                       rowsel, ids, V, w.logp_c, w.lse_c, w.ent_c, logp, lse, entropy);
+    hipLaunchKernelGGL(k_score_finalize, dim3(cdiv(n_sel, 256)), dim3(256), 0, st, w.partial, tiles_m, n_pad,
+                       static_cast<int64_t>(0), n_sel, rowsel, ids, V, w.logp_c, w.lse_c, w.ent_c, logp, lse, entropy);
     UMAS_LAUNCHED("k_score_finalize");
   } else {
     hipLaunchKernelGGL(k_score_f32, dim3(static_cast<unsigned>(n_sel)), dim3(256), d * sizeof(float), st,
@@ -807,22 +973,9 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
   }
   if (!accumulate_dW && n_sel == 0) UMAS_HIP(fill_bytes_zero(dW, static_cast<size_t>(V) * d * sizeof(float), st));
 
-  // forward scoring and the surrogate
-  s = run_score(H, W, dtype, d, V, ids, rowsel, n_sel, w.score, logp_new, nullptr, nullptr, st);
-  if (s != UMAS_OK) return s;
-  const int nblk = cdiv(n_sel > 0 ? n_sel : 1, kRowBlock);
-  hipLaunchKernelGGL(k_ppo_rows, dim3(nblk), dim3(kRowBlock), (1 + n_roles) * kStat * sizeof(double), st, n_sel, rowsel,
-                     ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv, tok_role, n_roles, clip_eps, dual_clip,
-                     n_sel > 0 ? entropy_coef / static_cast<float>(n_sel) : 0.f, w.score.lse_c, w.g_c, w.a_c, w.kz_c,
-                     w.blk_stats);
-  UMAS_LAUNCHED("k_ppo_rows");
-  hipLaunchKernelGGL(k_ppo_stats, dim3(1), dim3(256), 0, st, nblk, n_roles, entropy_coef, w.blk_stats, stats);
-  UMAS_LAUNCHED("k_ppo_stats");
-  if (n_sel == 0) return UMAS_OK;
-
-  // backward in chunks of selected rows sized to the workspace
+  // chunks of selected rows sized to the workspace
   const size_t room = workspace_bytes - w.fixed_bytes;
-  int64_t mc = n_sel;
+  int64_t mc = n_sel > 0 ? n_sel : 1;
   const int64_t cap = dtype == UMAS_F32 ? kF32ChunkRows : kMaxChunkRows;
   if (mc > cap) mc = cap;
   while (mc > 256 && chunk_bytes(mc, d, V, dtype) > room) mc = round_up(mc / 2, 256);
@@ -831,8 +984,73 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     const int64_t even = round_up((n_sel + nchunk - 1) / nchunk, 256);
     if (even < mc) mc = even;
   }
-  UMAS_REQUIRE(chunk_bytes(mc < n_sel ? mc : n_sel, d, V, dtype) <= room, UMAS_EWORKSPACE,
+  UMAS_REQUIRE(chunk_bytes(mc < n_sel ? mc : (n_sel > 0 ? n_sel : 1), d, V, dtype) <= room, UMAS_EWORKSPACE,
                "workspace cannot hold one chunk of %lld rows", static_cast<long long>(mc));
+
+  const int nblk = cdiv(n_sel > 0 ? n_sel : 1, kRowBlock);
+  const float k_ent = n_sel > 0 ? entropy_coef / static_cast<float>(n_sel) : 0.f;
+  // Without an entropy bonus dz is a row factor times the softmax: the scoring pass keeps the numerators
+  // and the logits are not computed a second time.
+  const bool keep = dtype == UMAS_BF16 && entropy_coef == 0.f && n_sel > 0;
+  const int64_t Vp = round_up(V, 256);
+  const uint16_t* Wb = static_cast<const uint16_t*>(W);
+  const uint16_t* Hb = static_cast<const uint16_t*>(H);
+
+  if (!keep) {
+    // forward scoring and the surrogate
+    s = run_score(H, W, dtype, d, V, ids, rowsel, n_sel, w.score, logp_new, nullptr, nullptr, st);
+    if (s != UMAS_OK) return s;
+    hipLaunchKernelGGL(k_ppo_rows, dim3(nblk), dim3(kRowBlock), (1 + n_roles) * kStat * sizeof(double), st, n_sel,
+                       static_cast<int64_t>(0), n_sel, rowsel, ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv,
+                       tok_role, n_roles, clip_eps, dual_clip, k_ent, w.score.lse_c, w.g_c, w.a_c, w.kz_c, w.blk_stats);
+    UMAS_LAUNCHED("k_ppo_rows");
+  } else {
+    hipLaunchKernelGGL(k_label_logit, dim3(cdiv(n_sel, 4)), dim3(256), 0, st, Hb, Wb, d, V, rowsel, n_sel, ids, w.cref);
+    UMAS_LAUNCHED("k_label_logit");
+    UMAS_HIP(fill_bytes_zero(w.flags, static_cast<size_t>(nblk) * sizeof(int32_t), st));
+    const int64_t n_pad = round_up(n_sel, Cfg::BN);
+    const int tiles_v = static_cast<int>(Vp / 256), tiles_d = (d + 255) / 256;
+    for (int64_t c0 = 0; c0 < n_sel; c0 += mc) {
+      const int64_t rows = n_sel - c0 < mc ? n_sel - c0 : mc;
+      const int64_t mcp = round_up(rows, 256);
+      const int tiles_r = static_cast<int>(mcp / 256);
+      uint16_t* E = reinterpret_cast<uint16_t*>(w.chunk);
+      uint16_t* Hs = reinterpret_cast<uint16_t*>(w.chunk + align_up(static_cast<size_t>(mcp) * Vp * 2));
+      hipLaunchKernelGGL(k_score_keep_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r, kTilesPerWg)), dim3(Cfg::T), 0, st,
+                         Wb, Hb, d, V, rowsel, c0, rows, ids, tiles_v, tiles_r, w.score.partial, n_pad, w.cref, E, Vp, w.flags);
+      UMAS_LAUNCHED("k_score_keep_tiles");
+      hipLaunchKernelGGL(k_score_finalize, dim3(cdiv(rows, 256)), dim3(256), 0, st, w.score.partial, tiles_v, n_pad, c0,
+                         c0 + rows, rowsel, ids, V, w.score.logp_c, w.score.lse_c, w.score.ent_c, logp_new,
+                         static_cast<float*>(nullptr), static_cast<float*>(nullptr));
+      UMAS_LAUNCHED("k_score_finalize");
+      hipLaunchKernelGGL(k_ppo_rows, dim3(cdiv(rows, kRowBlock)), dim3(kRowBlock), (1 + n_roles) * kStat * sizeof(double),
+                         st, n_sel, c0, c0 + rows, rowsel, ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv, tok_role,
+                         n_roles, clip_eps, dual_clip, k_ent, w.score.lse_c, w.g_c, w.a_c, w.kz_c, w.blk_stats);
+      UMAS_LAUNCHED("k_ppo_rows");
+      hipLaunchKernelGGL(k_keep_rows, dim3(cdiv(rows, 4)), dim3(256), 0, st, Hb, d, V, rowsel, c0, rows, ids, w.score.lse_c,
+                         w.a_c, w.cref, w.flags, w.sc, Hs);
+      UMAS_LAUNCHED("k_keep_rows");
+      // blocks of rows the scoring pass flagged (a logit far above the row's reference) get dz the long way
+      hipLaunchKernelGGL(k_dz_flagged, dim3(kFlaggedGrid), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel, c0, rows,
+                         w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, E, Vp, w.flags);
+      UMAS_LAUNCHED("k_dz_flagged");
+      hipLaunchKernelGGL(k_gemm_dh, dim3(tile_grid<kGM, kGN>(tiles_r, tiles_d)), dim3(Cfg::T), 0, st, E, Vp, mcp, Wb, d, V,
+                         tiles_r, tiles_d, static_cast<uint16_t*>(dH), rowsel, c0, rows, ids, w.g_c, w.sc);
+      UMAS_LAUNCHED("k_gemm_dh");
+      hipLaunchKernelGGL(k_gemm_dw, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_d)), dim3(Cfg::T), 0, st, E, mcp, Vp, Hs, d, V,
+                         static_cast<const int32_t*>(nullptr), static_cast<int64_t>(0), rows, tiles_v, tiles_d, dW,
+                         (accumulate_dW || c0 > 0) ? 1 : 0);
+      UMAS_LAUNCHED("k_gemm_dw");
+    }
+  }
+  hipLaunchKernelGGL(k_ppo_stats, dim3(1), dim3(256), 0, st, nblk, n_roles, entropy_coef, w.blk_stats, stats);
+  UMAS_LAUNCHED("k_ppo_stats");
+  if (n_sel == 0) return UMAS_OK;
+  if (keep) {
+    hipLaunchKernelGGL(k_dw_onehot, dim3(cdiv(n_sel, 4)), dim3(256), 0, st, Hb, d, rowsel, n_sel, ids, w.g_c, dW);
+    UMAS_LAUNCHED("k_dw_onehot");
+    return UMAS_OK;
+  }
 
   if (dtype == UMAS_F32) {
     float* dz = reinterpret_cast<float*>(w.chunk);
@@ -852,19 +1070,16 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     return UMAS_OK;
   }
 
-  const int64_t Vp = round_up(V, 256);
-  const uint16_t* Wb = static_cast<const uint16_t*>(W);
-  const uint16_t* Hb = static_cast<const uint16_t*>(H);
   for (int64_t c0 = 0; c0 < n_sel; c0 += mc) {
     const int64_t rows = n_sel - c0 < mc ? n_sel - c0 : mc;
     const int64_t mcp = round_up(rows, 256);
     uint16_t* dZ = reinterpret_cast<uint16_t*>(w.chunk);
     const int tiles_v = static_cast<int>(Vp / 256), tiles_r = static_cast<int>(mcp / 256), tiles_d = (d + 255) / 256;
     hipLaunchKernelGGL(k_dz_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r, kTilesPerWg)), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel,
-                       c0, rows, w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, dZ, Vp, mcp);
+                       c0, rows, w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, dZ, Vp);
     UMAS_LAUNCHED("k_dz_tiles");
     hipLaunchKernelGGL(k_gemm_dh, dim3(tile_grid<kGM, kGN>(tiles_r, tiles_d)), dim3(Cfg::T), 0, st, dZ, Vp, mcp, Wb, d, V,
-                       tiles_r, tiles_d, static_cast<uint16_t*>(dH), rowsel, c0, rows, ids, w.g_c);
+                       tiles_r, tiles_d, static_cast<uint16_t*>(dH), rowsel, c0, rows, ids, w.g_c, static_cast<const float*>(nullptr));
     UMAS_LAUNCHED("k_gemm_dh");
     hipLaunchKernelGGL(k_gemm_dw, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_d)), dim3(Cfg::T), 0, st, dZ, mcp, Vp, Hb, d, V,
                        rowsel, c0, rows, tiles_v, tiles_d, dW, (accumulate_dW || c0 > 0) ? 1 : 0);

@@ -167,6 +167,36 @@ def test_invalid_token_ids_are_counted_and_ignored():
     P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW")
 
 
+def test_rows_with_wide_logits_take_the_recomputing_path():
+    """Without an entropy bonus the scoring pass keeps exp(z - z_y) in bf16 as the backward's operand; a block
+    of 256 rows in which some logit lies more than 50 above the taken token's is recomputed from H and W
+    instead.  Ten rows are scaled (by a power of two, so they stay bf16 values) until that happens in the
+    second block of rows and nowhere else; every block must still match the oracle."""
+    w = wl.make_workload(1, n_traj=6, tokens_per_turn=40, models=[(64, 700, "bf16")])
+    t = w.model_tensors(0)
+    Hn = t["H"].copy()
+    Hn[300:310] *= 256.0
+    n = len(t["ids"])
+    assert n > 600
+    z = Hn.astype(np.float64) @ t["W"].astype(np.float64).T
+    gap = z.max(axis=1) - z[np.arange(n), t["ids"]]
+    assert set(np.nonzero(gap > 55)[0] // 256) == {1} and gap[np.setdiff1d(np.arange(n), np.arange(300, 310))].max() < 40
+    rows = np.arange(n, dtype=np.int32)
+    logp_o, lse_o, ent_o = orc.score(Hn, t["W"], t["ids"], rows)
+    logp_old = (logp_o + t["noise"]).astype(np.float32)
+    adv = np.random.default_rng(5).normal(size=n).astype(np.float32)
+    st_o, g_o = orc.ppo_loss(logp_o, logp_old, adv, ent_o, rows, np.zeros(n, np.int32), 0, 0.2)
+    dH_o, dW_o = orc.lm_head_backward(Hn, t["W"], t["ids"], lse_o, g_o, rows)
+    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(P.to_dev(Hn, torch.bfloat16), P.to_dev(t["W"], torch.bfloat16),
+                                                        P.to_dev(t["ids"]), None, P.to_dev(logp_old), P.to_dev(adv),
+                                                        None, 0, 0.2)
+    sg = umas.read_stats(stats)
+    assert np.abs(logp_new.cpu().numpy() - logp_o).max() <= 2e-2
+    assert abs(float(sg["loss"][0]) - st_o[0, 0]) <= 1e-2 * max(abs(st_o[0, 0]), 1e-3)
+    P.close(dH.float().cpu().numpy(), dH_o, 1e-2, "dH")
+    P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW")
+
+
 def test_accumulate_dw_adds_to_existing_gradient():
     w = wl.make_workload(1, n_traj=2, tokens_per_turn=40, models=[(64, 300, "bf16")])
     t = w.model_tensors(0)
