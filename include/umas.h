@@ -176,7 +176,10 @@ typedef struct {
   int64_t n_invalid_ids;   /* selected rows whose token id is outside [0,V) */
 } umas_loss_stats;
 
-/* Smallest workspace the call accepts and the size at which it runs in the fewest passes. */
+/* Smallest workspace the call accepts and the size at which it runs in the fewest passes.  For bf16 the
+ * workspace holds, per chunk of selected rows, the bf16 operand of the two gradient products
+ * [rows, V] (rounded up to multiples of 256) and a scaled bf16 copy of the chunk's rows of H; the
+ * smallest size runs in chunks of 256 rows, the full size in chunks of up to 131072 rows. */
 size_t umas_ppo_loss_workspace_bytes_min(int64_t n_sel, int32_t d, int32_t V, umas_dtype dtype, int32_t n_roles);
 size_t umas_ppo_loss_workspace_bytes(int64_t n_sel, int32_t d, int32_t V, umas_dtype dtype, int32_t n_roles);
 
@@ -196,7 +199,9 @@ size_t umas_ppo_loss_workspace_bytes(int64_t n_sel, int32_t d, int32_t V, umas_d
  * Two optional terms (stabilisers of the PPO family; both off at 0):
  *   dual_clip c > 1: for A < 0 the row's term is capped at -A c, with no gradient where the cap binds;
  *   entropy_coef k >= 0: the loss becomes L_clip - k mean entropy (stats.loss includes it) and
- *     dz_iv gains (k / n_sel) p_iv (log p_iv + entropy_i), p = softmax(z_i). */
+ *     dz_iv gains (k / n_sel) p_iv (log p_iv + entropy_i), p = softmax(z_i).
+ * bf16 computes the logits once when entropy_coef = 0 (the scoring pass leaves the softmax numerators
+ * in the workspace as the operand of dH and dW) and twice otherwise; float32 logits are never stored. */
 umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_dtype dtype, int64_t n_rows,
                                   int32_t d, int32_t V, const int32_t* ids, const int32_t* rowsel,
                                   int64_t n_sel, const float* logp_old, const float* adv,

@@ -6,10 +6,14 @@
 // to per-row (max, sum exp, sum exp*z, taken logit) in registers; logits never leave the chip.
 // Update (paragraph "Model-specific updates and synchronization", PPO after Schulman et al.
 // 2017): ratio = exp(logp - logp_old), L = max(-A ratio, -A clip(ratio)), g = dL/dlogp, then
-// the dense part of dz = g (onehot - softmax) is recomputed tile by tile from H, W and lse, rounded
-// to bf16 into a bounded chunk buffer dZ [rows, vocabulary], and dH = dz W, dW = dz^T H run as MFMA
-// GEMMs that read dZ, W and H as they lie (operands that are not K-contiguous go through transposing
-// LDS reads); the one-hot part (one term per row) is added in float32.
+// dH = dz W and dW = dz^T H with dz = g (onehot - softmax) run as MFMA GEMMs over a bf16 operand
+// [rows, vocabulary] held in a bounded chunk buffer; W and H are read as they lie (operands that are not
+// K-contiguous go through transposing LDS reads), the one-hot part (one term per row) is added in float32.
+// Without an entropy bonus the dense part of dz is a row factor times the softmax, so the scoring pass of
+// the update itself leaves that operand behind: E = bf16(exp(z - z_y)), the softmax numerators relative to
+// the taken token's logit, and the row factor -g exp(z_y - lse) is applied where dH is written and folded
+// into the copy of H that dW reads; the logits are computed once.  With an entropy bonus (and for blocks
+// of rows whose logits spread too far for E) dz is recomputed tile by tile from H, W and lse instead.
 // The float32 path is a plain, unblocked implementation for small shapes.
 #include <math.h>
 
@@ -189,6 +193,7 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
       if (gap <= kKeepMaxGap) m = c;
       else if (m == kMasked) m = 0.f;                       // nothing but vocabulary tail in this lane: exponentials 0 as well
     }
+    const float m2 = m * kLog2e;
     float s = 0.f, t = 0.f;
 #pragma unroll
     for (int tm = 0; tm < C::TM; ++tm)
@@ -198,7 +203,8 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const float z = acc[tm][tn][q * 4 + j];
-          e[j] = __builtin_amdgcn_exp2f((z - m) * kLog2e);   // z - m first: exact 0 for masked-only columns
+          // without a reference from outside: z - m first, exact 0 where a lane holds nothing but vocabulary tail
+          e[j] = KEEP ? __builtin_amdgcn_exp2f(fmaf(z, kLog2e, -m2)) : __builtin_amdgcn_exp2f((z - m) * kLog2e);
           s += e[j];
           t = fmaf(e[j], z, t);
         }
@@ -216,7 +222,7 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
       float* dst = s_part + (wm * C::BN + col) * 3;
       dst[0] = p.m; dst[1] = p.s; dst[2] = p.t;
     }
-    if (n < mc) {
+    if (!KEEP && n < mc) {                                  // the keeping variant got the taken logits beforehand
       const int y = ids[rowsel ? rowsel[c0 + n] : c0 + n];
       const int rel = y - vbase;                           // offset from this lane's first element
       if (y >= 0 && y < V && rel >= 0 && rel < C::WTM && ((rel >> 2) & 1) == 0) {
@@ -277,7 +283,7 @@ k_score_keep_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ 
 
 // Merge the per-tile partials of each selected row; compact results and optional scatter.
 __global__ void k_score_finalize(const float4* __restrict__ partial, int tiles_m, int64_t n_pad, int64_t n_begin,
-                                 int64_t n_end, const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
+                                 int64_t n_end, const float* __restrict__ zy_c, const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
                                  float* __restrict__ logp_c, float* __restrict__ lse_c, float* __restrict__ ent_c,
                                  float* __restrict__ logp, float* __restrict__ lse, float* __restrict__ entropy) {
   const int64_t n = n_begin + static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -289,6 +295,7 @@ __global__ void k_score_finalize(const float4* __restrict__ partial, int tiles_m
     p = part_merge(p, Part{q.x, q.y, q.z});
     zy += q.w;
   }
+  if (zy_c) zy = zy_c[n];                                   // taken logits computed beforehand
   const int64_t row = rowsel ? rowsel[n] : n;
   const int y = ids[row];
   const bool ok = y >= 0 && y < V;
@@ -868,7 +875,8 @@ umas_status run_score(const void* H, const void* W, umas_dtype dt, int d, int V,
                        tiles_m, tiles_n, w.partial, n_pad);
     UMAS_LAUNCHED("k_score_tiles");
     hipLaunchKernelGGL(k_score_finalize, dim3(cdiv(n_sel, 256)), dim3(256), 0, st, w.partial, tiles_m, n_pad,
-                       static_cast<int64_t>(0), n_sel, rowsel, ids, V, w.logp_c, w.lse_c, w.ent_c, logp, lse, entropy);
+                       static_cast<int64_t>(0), n_sel, static_cast<const float*>(nullptr), rowsel, ids, V, w.logp_c, w.lse_c,
+                       w.ent_c, logp, lse, entropy);
     UMAS_LAUNCHED("k_score_finalize");
   } else {
     hipLaunchKernelGGL(k_score_f32, dim3(static_cast<unsigned>(n_sel)), dim3(256), d * sizeof(float), st,
@@ -1020,7 +1028,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
                          Wb, Hb, d, V, rowsel, c0, rows, ids, tiles_v, tiles_r, w.score.partial, n_pad, w.cref, E, Vp, w.flags);
       UMAS_LAUNCHED("k_score_keep_tiles");
       hipLaunchKernelGGL(k_score_finalize, dim3(cdiv(rows, 256)), dim3(256), 0, st, w.score.partial, tiles_v, n_pad, c0,
-                         c0 + rows, rowsel, ids, V, w.score.logp_c, w.score.lse_c, w.score.ent_c, logp_new,
+                         c0 + rows, w.cref, rowsel, ids, V, w.score.logp_c, w.score.lse_c, w.score.ent_c, logp_new,
                          static_cast<float*>(nullptr), static_cast<float*>(nullptr));
       UMAS_LAUNCHED("k_score_finalize");
       hipLaunchKernelGGL(k_ppo_rows, dim3(cdiv(rows, kRowBlock)), dim3(kRowBlock), (1 + n_roles) * kStat * sizeof(double),
