@@ -281,20 +281,35 @@ k_score_keep_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ 
   score_tiles<true>(W, H, d, V, rowsel, c0, mc, ids, tiles_m, tiles_n, partial, n_pad, KeepArgs{cref, E, Vp, flags}, lds);
 }
 
-// Merge the per-tile partials of each selected row; compact results and optional scatter.
-__global__ void k_score_finalize(const float4* __restrict__ partial, int tiles_m, int64_t n_pad, int64_t n_begin,
-                                 int64_t n_end, const float* __restrict__ zy_c, const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
-                                 float* __restrict__ logp_c, float* __restrict__ lse_c, float* __restrict__ ent_c,
-                                 float* __restrict__ logp, float* __restrict__ lse, float* __restrict__ entropy) {
-  const int64_t n = n_begin + static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (n >= n_end) return;
+// Merge the per-tile partials of each selected row; compact results and optional scatter.  Eight lanes
+// share a row (lane = 8 * part + row within the group of 8 rows, so a load still covers whole 128-byte lines).
+constexpr int kFinParts = 8;
+__global__ void __launch_bounds__(256)
+k_score_finalize(const float4* __restrict__ partial, int tiles_m, int64_t n_pad, int64_t n_begin,
+                 int64_t n_end, const float* __restrict__ zy_c, const int32_t* __restrict__ rowsel,
+                 const int32_t* __restrict__ ids, int V,
+                 float* __restrict__ logp_c, float* __restrict__ lse_c, float* __restrict__ ent_c,
+                 float* __restrict__ logp, float* __restrict__ lse, float* __restrict__ entropy) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int part = lane >> 3;
+  const int64_t n = n_begin + (static_cast<int64_t>(blockIdx.x) * (blockDim.x / kWave) + wave) * 8 + (lane & 7);
+  const bool live = n < n_end;                                // whole groups of lanes; the shuffles below need every lane
   Part p{kNegInf, 0.f, 0.f};
   float zy = 0.f;
-  for (int tm = 0; tm < tiles_m; ++tm) {
-    const float4 q = partial[static_cast<int64_t>(tm) * n_pad + n];
-    p = part_merge(p, Part{q.x, q.y, q.z});
-    zy += q.w;
+  if (live) {
+    for (int tm = part; tm < tiles_m; tm += kFinParts) {
+      const float4 q = partial[static_cast<int64_t>(tm) * n_pad + n];
+      p = part_merge(p, Part{q.x, q.y, q.z});
+      zy += q.w;
+    }
   }
+#pragma unroll
+  for (int o = 8; o < kWave; o <<= 1) {
+    const Part q{__shfl_xor(p.m, o, kWave), __shfl_xor(p.s, o, kWave), __shfl_xor(p.t, o, kWave)};
+    p = part_merge(p, q);
+    zy += __shfl_xor(zy, o, kWave);
+  }
+  if (!live || part != 0) return;
   if (zy_c) zy = zy_c[n];                                   // taken logits computed beforehand
   const int64_t row = rowsel ? rowsel[n] : n;
   const int y = ids[row];
@@ -874,7 +889,7 @@ umas_status run_score(const void* H, const void* W, umas_dtype dt, int d, int V,
                        static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), d, V, rowsel, n_sel, ids,
                        tiles_m, tiles_n, w.partial, n_pad);
     UMAS_LAUNCHED("k_score_tiles");
-    hipLaunchKernelGGL(k_score_finalize, dim3(cdiv(n_sel, 256)), dim3(256), 0, st, w.partial, tiles_m, n_pad,
+    hipLaunchKernelGGL(k_score_finalize, dim3(cdiv(n_sel, 32)), dim3(256), 0, st, w.partial, tiles_m, n_pad,
                        static_cast<int64_t>(0), n_sel, static_cast<const float*>(nullptr), rowsel, ids, V, w.logp_c, w.lse_c,
                        w.ent_c, logp, lse, entropy);
     UMAS_LAUNCHED("k_score_finalize");
@@ -1027,7 +1042,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
       hipLaunchKernelGGL(k_score_keep_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r, kTilesPerWg)), dim3(Cfg::T), 0, st,
                          Wb, Hb, d, V, rowsel, c0, rows, ids, tiles_v, tiles_r, w.score.partial, n_pad, w.cref, E, Vp, w.flags);
       UMAS_LAUNCHED("k_score_keep_tiles");
-      hipLaunchKernelGGL(k_score_finalize, dim3(cdiv(rows, 256)), dim3(256), 0, st, w.score.partial, tiles_v, n_pad, c0,
+      hipLaunchKernelGGL(k_score_finalize, dim3(cdiv(rows, 32)), dim3(256), 0, st, w.score.partial, tiles_v, n_pad, c0,
                          c0 + rows, w.cref, rowsel, ids, V, w.score.logp_c, w.score.lse_c, w.score.ent_c, logp_new,
                          static_cast<float*>(nullptr), static_cast<float*>(nullptr));
       UMAS_LAUNCHED("k_score_finalize");

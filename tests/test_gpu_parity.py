@@ -187,14 +187,18 @@ def test_rows_with_wide_logits_take_the_recomputing_path():
     adv = np.random.default_rng(5).normal(size=n).astype(np.float32)
     st_o, g_o = orc.ppo_loss(logp_o, logp_old, adv, ent_o, rows, np.zeros(n, np.int32), 0, 0.2)
     dH_o, dW_o = orc.lm_head_backward(Hn, t["W"], t["ids"], lse_o, g_o, rows)
-    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(P.to_dev(Hn, torch.bfloat16), P.to_dev(t["W"], torch.bfloat16),
-                                                        P.to_dev(t["ids"]), None, P.to_dev(logp_old), P.to_dev(adv),
-                                                        None, 0, 0.2)
-    sg = umas.read_stats(stats)
-    assert np.abs(logp_new.cpu().numpy() - logp_o).max() <= 2e-2
-    assert abs(float(sg["loss"][0]) - st_o[0, 0]) <= 1e-2 * max(abs(st_o[0, 0]), 1e-3)
-    P.close(dH.float().cpu().numpy(), dH_o, 1e-2, "dH")
-    P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW")
+    # once with the whole batch in one chunk, once in 256-row chunks (the flagged block is then a chunk of its own)
+    small = umas.ppo_workspace_bytes(n, 64, 700, torch.bfloat16, 0, minimum=True)
+    for ws_bytes in (None, small):
+        ws = None if ws_bytes is None else torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(P.to_dev(Hn, torch.bfloat16), P.to_dev(t["W"], torch.bfloat16),
+                                                            P.to_dev(t["ids"]), None, P.to_dev(logp_old), P.to_dev(adv),
+                                                            None, 0, 0.2, workspace=ws)
+        sg = umas.read_stats(stats)
+        assert np.abs(logp_new.cpu().numpy() - logp_o).max() <= 2e-2
+        assert abs(float(sg["loss"][0]) - st_o[0, 0]) <= 1e-2 * max(abs(st_o[0, 0]), 1e-3)
+        P.close(dH.float().cpu().numpy(), dH_o, 1e-2, "dH")
+        P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW")
 
 
 def test_accumulate_dw_adds_to_existing_gradient():
