@@ -35,6 +35,12 @@ constexpr float kMasked = -1e30f;        // stands for a logit that does not exi
 __device__ __forceinline__ uint16_t f2bf(float x) {
   return __builtin_bit_cast(uint16_t, static_cast<__bf16>(x));
 }
+// two floats rounded to bf16 in one word (first in the low half): one conversion instruction
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+}
 __device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
 
 // Online-softmax partial: m = max z, s = sum exp(z - m), t = sum exp(z - m) z.
@@ -209,8 +215,7 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
           t = fmaf(e[j], z, t);
         }
         if (KEEP) {   // staged in this wavefront's LDS region, stored in full lines below
-          const uint32_t p01 = static_cast<uint32_t>(f2bf(e[0])) | (static_cast<uint32_t>(f2bf(e[1])) << 16);
-          const uint32_t p23 = static_cast<uint32_t>(f2bf(e[2])) | (static_cast<uint32_t>(f2bf(e[3])) << 16);
+          const uint32_t p01 = pack_bf16x2(e[0], e[1]), p23 = pack_bf16x2(e[2], e[3]);
           *reinterpret_cast<uint2*>(stage + (tn * 32 + (lane & 31)) * kStagePitch + (tm * 32 + q * 8 + (lane >> 5) * 4) * 2) =
               make_uint2(p01, p23);
         }
@@ -510,10 +515,10 @@ k_keep_rows(const uint16_t* __restrict__ H, int d, int V, const int32_t* __restr
     float x[8];
     bf16x8_to_f32(h[k], x);
     uint4 v;
-    v.x = static_cast<uint32_t>(f2bf(x[0] * f)) | (static_cast<uint32_t>(f2bf(x[1] * f)) << 16);
-    v.y = static_cast<uint32_t>(f2bf(x[2] * f)) | (static_cast<uint32_t>(f2bf(x[3] * f)) << 16);
-    v.z = static_cast<uint32_t>(f2bf(x[4] * f)) | (static_cast<uint32_t>(f2bf(x[5] * f)) << 16);
-    v.w = static_cast<uint32_t>(f2bf(x[6] * f)) | (static_cast<uint32_t>(f2bf(x[7] * f)) << 16);
+    v.x = pack_bf16x2(x[0] * f, x[1] * f);
+    v.y = pack_bf16x2(x[2] * f, x[3] * f);
+    v.z = pack_bf16x2(x[4] * f, x[5] * f);
+    v.w = pack_bf16x2(x[6] * f, x[7] * f);
     o[k] = v;
   }
 }
@@ -570,8 +575,7 @@ __device__ __forceinline__ void dz_tile(int tile_m, int tile_n, const uint16_t* 
           const float z = acc[tm][tn][q * 4 + j];
           dz[j] = __builtin_amdgcn_exp2f(fmaf(z, 1.44269504088896341f, -l2)) * fmaf(kz, z, a);
         }
-        const uint32_t p01 = static_cast<uint32_t>(f2bf(dz[0])) | (static_cast<uint32_t>(f2bf(dz[1])) << 16);
-        const uint32_t p23 = static_cast<uint32_t>(f2bf(dz[2])) | (static_cast<uint32_t>(f2bf(dz[3])) << 16);
+        const uint32_t p01 = pack_bf16x2(dz[0], dz[1]), p23 = pack_bf16x2(dz[2], dz[3]);
         // staged in this wavefront's LDS region, stored in full lines below
         *reinterpret_cast<uint2*>(stage + (tn * 32 + (lane & 31)) * kStagePitch + (tm * 32 + q * 8 + (lane >> 5) * 4) * 2) =
             make_uint2(p01, p23);
