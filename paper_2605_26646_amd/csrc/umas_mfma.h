@@ -477,6 +477,25 @@ __device__ __forceinline__ bool tile_coords(int tiles_m, int tiles_n, int* tm, i
   *tn = gn * GN + within / GM;
   return *tm < tiles_m && *tn < tiles_n;
 }
+// The same order with an explicit share of the groups per XCD: XCD x owns groups first[x] .. first[x + 1] - 1.
+// `bid` is the workgroup's number among the workgroups that use this table (a multiple of 8 lies before it in
+// the grid, so bid % 8 is still its XCD).
+struct XcdGroups {
+  int first[9];
+};
+template <int GM, int GN>
+__device__ __forceinline__ bool tile_coords_shared(int tiles_m, int tiles_n, long long bid, const XcdGroups& g, int* tm, int* tn) {
+  const int total_groups_n = (tiles_n + GN - 1) / GN;
+  const int xcd = static_cast<int>(bid & 7);
+  const long long w = bid >> 3;
+  const long long grp = g.first[xcd] + w / (GM * GN);
+  const int within = static_cast<int>(w % (GM * GN));
+  if (grp >= g.first[xcd + 1]) return false;
+  const int gm = static_cast<int>(grp / total_groups_n), gn = static_cast<int>(grp % total_groups_n);
+  *tm = gm * GM + within % GM;
+  *tn = gn * GN + within / GM;
+  return *tm < tiles_m && *tn < tiles_n;
+}
 template <int GM, int GN>
 inline unsigned tile_grid(int tiles_m, int tiles_n, int per_wg = 1) {
   const long long groups = static_cast<long long>((tiles_m + GM - 1) / GM) * ((tiles_n + GN - 1) / GN);

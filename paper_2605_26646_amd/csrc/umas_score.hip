@@ -622,7 +622,7 @@ k_dz_flagged(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int
 }
 
 // ------------------------------------------------------------------ bf16: the two gradient products
-// dH = dZ W: A = dZ [mcp, Vp] is K-contiguous (K = vocabulary), B = W [V, d] is K-major and is read as it lies.
+// dH = dZ W: A = dZ [mcp, Vp] (or the kept numerators E) is K-contiguous (K = vocabulary), B = W [V, d] is K-major and is read as it lies.
 //   dH[rowsel[c0 + m], j] = bf16(sc[m] C[m, j] + g[m] W[y[m], j]) for m < mc (sc: the keeping pass's row factor, else 1)
 // dW = dZ^T H: K = rows of the chunk; A = dZ [mcp, Vp] and B = the selected rows of H [*, d] are both K-major.
 //   dW[v, j] (+)= C[v, j]
@@ -648,14 +648,12 @@ __device__ __forceinline__ KContig kcontig_tile(const uint16_t* X, int64_t ld, i
   return c;
 }
 
-__global__ void __launch_bounds__(Cfg::T)
-k_gemm_dh(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uint16_t* __restrict__ W, int d, int V, int tiles_m,
-          int tiles_n, uint16_t* __restrict__ dH, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
-          const int32_t* __restrict__ ids, const float* __restrict__ g_c, const float* __restrict__ sc) {
+__device__ __forceinline__ void dh_tile(int tile_m, int tile_n, const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp,
+                                        const uint16_t* __restrict__ W, int d, int V, uint16_t* __restrict__ dH,
+                                        const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
+                                        const int32_t* __restrict__ ids, const float* __restrict__ g_c,
+                                        const float* __restrict__ sc, uint16_t* lds) {
   using C = Cfg;
-  __shared__ __attribute__((aligned(16))) uint16_t lds[Ring::LDS_BYTES / 2];
-  int tile_m, tile_n;
-  if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
   const int64_t m0 = static_cast<int64_t>(tile_m) * C::BM;
   const int n0 = tile_n * C::BN;
   const KContig ca = kcontig_tile<C>(dZ, Vp, mcp, m0);
@@ -686,14 +684,11 @@ k_gemm_dh(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uint16
       }
   }
 }
-__global__ void __launch_bounds__(Cfg::T)
-k_gemm_dw(const uint16_t* __restrict__ dZ, int64_t mcp, int64_t Vp, const uint16_t* __restrict__ H, int d, int V,
-          const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows, int tiles_m, int tiles_n, float* __restrict__ dW,
-          int accumulate) {
+// Hx: the rows of H that go with the rows of dZ: H itself (through rowsel, or from row c0 on), or a compact copy
+__device__ __forceinline__ void dw_tile(int tile_m, int tile_n, const uint16_t* __restrict__ dZ, int64_t mcp, int64_t Vp,
+                                        const uint16_t* __restrict__ Hx, int d, int V, const int32_t* __restrict__ rowmap,
+                                        int64_t rows, float* __restrict__ dW, int accumulate, uint16_t* lds) {
   using C = Cfg;
-  __shared__ __attribute__((aligned(16))) uint16_t lds[Ring::LDS_BYTES / 2];
-  int tile_m, tile_n;
-  if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n)) return;
   const int64_t m0 = static_cast<int64_t>(tile_m) * C::BM;
   const int n0 = tile_n * C::BN;
   KMajor ka;                                                         // dZ [mcp, Vp]: k = row of the chunk, entries = vocabulary
@@ -702,15 +697,15 @@ k_gemm_dw(const uint16_t* __restrict__ dZ, int64_t mcp, int64_t Vp, const uint16
   ka.rowmap = nullptr;
   ka.k_rows = static_cast<int>(mcp);
   ka.n_units = 32;
-  KMajor kb;                                                         // H: k = selected row, entries = hidden columns
-  kb.base = reinterpret_cast<const char*>(H + n0 + (rowsel ? 0 : c0 * d));
+  KMajor kb;                                                         // rows of H: k = row of the chunk, entries = hidden columns
+  kb.base = reinterpret_cast<const char*>(Hx + n0);
   kb.ld_bytes = static_cast<int64_t>(d) * 2;
-  kb.rowmap = rowsel ? rowsel + c0 : nullptr;
+  kb.rowmap = rowmap;
   kb.k_rows = static_cast<int>(rows);                                // dz is zero for rows past the chunk
   kb.n_units = min(32, (d - n0) / 8);
   floatx16 acc[C::TM][C::TN];
   zero_acc<C>(acc);
-  if (rowsel) mfma_mainloop_mixed<C, true, true, true>(KContig{}, ka, KContig{}, kb, static_cast<int>(mcp), lds, acc);
+  if (rowmap) mfma_mainloop_mixed<C, true, true, true>(KContig{}, ka, KContig{}, kb, static_cast<int>(mcp), lds, acc);
   else mfma_mainloop_mixed<C, true, true, false>(KContig{}, ka, KContig{}, kb, static_cast<int>(mcp), lds, acc);
 #pragma unroll
   for (int tn = 0; tn < C::TN; ++tn) {
@@ -725,6 +720,25 @@ k_gemm_dw(const uint16_t* __restrict__ dZ, int64_t mcp, int64_t Vp, const uint16
         float* dst = dW + v * d + j;
         *dst = accumulate ? *dst + acc[tm][tn][r] : acc[tm][tn][r];
       }
+  }
+}
+// Both products in one launch: the first grid_dh workgroups take the dH tiles, the rest the dW tiles.  dH has few,
+// long tiles (K = vocabulary) and on its own leaves a fifth of the last round idle; here an XCD that runs out of dH
+// tiles goes on with dW tiles, and the host gives every XCD the share of dW groups that evens out the sum.
+__global__ void __launch_bounds__(Cfg::T)
+k_gemm_dh_dw(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uint16_t* __restrict__ W,
+             const uint16_t* __restrict__ Hx, const int32_t* __restrict__ h_rowmap, int d, int V, int tiles_r, int tiles_v,
+             int tiles_d, unsigned grid_dh, XcdGroups dw_groups, uint16_t* __restrict__ dH, float* __restrict__ dW,
+             int accumulate, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
+             const int32_t* __restrict__ ids, const float* __restrict__ g_c, const float* __restrict__ sc) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[Ring::LDS_BYTES / 2];
+  int tile_m, tile_n;
+  if (blockIdx.x < grid_dh) {
+    if (!tile_coords<kGM, kGN>(tiles_r, tiles_d, &tile_m, &tile_n)) return;
+    dh_tile(tile_m, tile_n, dZ, Vp, mcp, W, d, V, dH, rowsel, c0, rows, ids, g_c, sc, lds);
+  } else {
+    if (!tile_coords_shared<kGM, kGN>(tiles_v, tiles_d, blockIdx.x - grid_dh, dw_groups, &tile_m, &tile_n)) return;
+    dw_tile(tile_m, tile_n, dZ, mcp, Vp, Hx, d, V, h_rowmap, rows, dW, accumulate, lds);
   }
 }
 
@@ -878,6 +892,37 @@ umas_status check_ws(void* ws, size_t have, size_t need) {
   UMAS_REQUIRE(ws && reinterpret_cast<uintptr_t>(ws) % kAlign == 0 && have >= need, UMAS_EWORKSPACE,
                "workspace must be 256-byte aligned and hold %zu bytes (got %zu)", need, have);
   return UMAS_OK;
+}
+
+// Shares of the dW tile groups per XCD for k_gemm_dh_dw: every XCD first works through its dH groups (contiguous
+// ranges, as tile_coords hands them out; a group costs about Vp K-steps per tile), then dW groups (mcp K-steps per
+// tile) are dealt to whichever XCD would finish first.
+XcdGroups share_dw_groups(int tiles_r, int tiles_v, int tiles_d, int64_t Vp, int64_t mcp, int* max_groups) {
+  const int64_t groups_dh = static_cast<int64_t>((tiles_r + kGM - 1) / kGM) * ((tiles_d + kGN - 1) / kGN);
+  const int64_t per_xcd = (groups_dh + 7) / 8;
+  int64_t load[8];
+  int cnt[8] = {};
+  for (int x = 0; x < 8; ++x) {
+    int64_t n = groups_dh - x * per_xcd;
+    n = n < 0 ? 0 : (n > per_xcd ? per_xcd : n);
+    load[x] = n * Vp;
+  }
+  const int64_t groups_dw = static_cast<int64_t>((tiles_v + kGM - 1) / kGM) * ((tiles_d + kGN - 1) / kGN);
+  for (int64_t g = 0; g < groups_dw; ++g) {
+    int best = 0;
+    for (int x = 1; x < 8; ++x)
+      if (load[x] < load[best]) best = x;
+    ++cnt[best];
+    load[best] += mcp;
+  }
+  XcdGroups out;
+  out.first[0] = 0;
+  *max_groups = 0;
+  for (int x = 0; x < 8; ++x) {
+    out.first[x + 1] = out.first[x] + cnt[x];
+    if (cnt[x] > *max_groups) *max_groups = cnt[x];
+  }
+  return out;
 }
 
 // Forward scoring of the selected rows into compact arrays and/or scattered outputs.
@@ -1061,13 +1106,14 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
       hipLaunchKernelGGL(k_dz_flagged, dim3(kFlaggedGrid), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel, c0, rows,
                          w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, E, Vp, w.flags);
       UMAS_LAUNCHED("k_dz_flagged");
-      hipLaunchKernelGGL(k_gemm_dh, dim3(tile_grid<kGM, kGN>(tiles_r, tiles_d)), dim3(Cfg::T), 0, st, E, Vp, mcp, Wb, d, V,
-                         tiles_r, tiles_d, static_cast<uint16_t*>(dH), rowsel, c0, rows, ids, w.g_c, w.sc);
-      UMAS_LAUNCHED("k_gemm_dh");
-      hipLaunchKernelGGL(k_gemm_dw, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_d)), dim3(Cfg::T), 0, st, E, mcp, Vp, Hs, d, V,
-                         static_cast<const int32_t*>(nullptr), static_cast<int64_t>(0), rows, tiles_v, tiles_d, dW,
-                         (accumulate_dW || c0 > 0) ? 1 : 0);
-      UMAS_LAUNCHED("k_gemm_dw");
+      int max_groups = 0;
+      const XcdGroups shares = share_dw_groups(tiles_r, tiles_v, tiles_d, Vp, mcp, &max_groups);
+      const unsigned grid_dh = tile_grid<kGM, kGN>(tiles_r, tiles_d);
+      hipLaunchKernelGGL(k_gemm_dh_dw, dim3(grid_dh + static_cast<unsigned>(max_groups) * kGM * kGN * 8), dim3(Cfg::T), 0, st,
+                         E, Vp, mcp, Wb, Hs, static_cast<const int32_t*>(nullptr), d, V, tiles_r, tiles_v, tiles_d, grid_dh,
+                         shares, static_cast<uint16_t*>(dH), dW, (accumulate_dW || c0 > 0) ? 1 : 0, rowsel, c0, rows, ids,
+                         w.g_c, w.sc);
+      UMAS_LAUNCHED("k_gemm_dh_dw");
     }
   }
   hipLaunchKernelGGL(k_ppo_stats, dim3(1), dim3(256), 0, st, nblk, n_roles, entropy_coef, w.blk_stats, stats);
@@ -1105,12 +1151,14 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     hipLaunchKernelGGL(k_dz_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r, kTilesPerWg)), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel,
                        c0, rows, w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, dZ, Vp);
     UMAS_LAUNCHED("k_dz_tiles");
-    hipLaunchKernelGGL(k_gemm_dh, dim3(tile_grid<kGM, kGN>(tiles_r, tiles_d)), dim3(Cfg::T), 0, st, dZ, Vp, mcp, Wb, d, V,
-                       tiles_r, tiles_d, static_cast<uint16_t*>(dH), rowsel, c0, rows, ids, w.g_c, static_cast<const float*>(nullptr));
-    UMAS_LAUNCHED("k_gemm_dh");
-    hipLaunchKernelGGL(k_gemm_dw, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_d)), dim3(Cfg::T), 0, st, dZ, mcp, Vp, Hb, d, V,
-                       rowsel, c0, rows, tiles_v, tiles_d, dW, (accumulate_dW || c0 > 0) ? 1 : 0);
-    UMAS_LAUNCHED("k_gemm_dw");
+    int max_groups = 0;
+    const XcdGroups shares = share_dw_groups(tiles_r, tiles_v, tiles_d, Vp, mcp, &max_groups);
+    const unsigned grid_dh = tile_grid<kGM, kGN>(tiles_r, tiles_d);
+    hipLaunchKernelGGL(k_gemm_dh_dw, dim3(grid_dh + static_cast<unsigned>(max_groups) * kGM * kGN * 8), dim3(Cfg::T), 0, st,
+                       dZ, Vp, mcp, Wb, rowsel ? Hb : Hb + c0 * d, rowsel ? rowsel + c0 : static_cast<const int32_t*>(nullptr), d,
+                       V, tiles_r, tiles_v, tiles_d, grid_dh, shares, static_cast<uint16_t*>(dH), dW,
+                       (accumulate_dW || c0 > 0) ? 1 : 0, rowsel, c0, rows, ids, w.g_c, static_cast<const float*>(nullptr));
+    UMAS_LAUNCHED("k_gemm_dh_dw");
   }
   hipLaunchKernelGGL(k_dw_onehot, dim3(cdiv(n_sel, 4)), dim3(256), 0, st, Hb, d, rowsel, n_sel, ids, w.g_c, dW);
   UMAS_LAUNCHED("k_dw_onehot");
