@@ -1,14 +1,17 @@
 // bf16 MFMA tile engine for gfx950: C[M,N] += A[M,K] * B[N,K]^T with both operands K-contiguous.
 //
 // A workgroup owns a BM x BN tile of C and walks K in steps of 64; each wavefront owns a
-// (BM/WM) x (BN/WN) sub-tile as a grid of 32x32 blocks of v_mfma_f32_32x32x16_bf16 with float
-// accumulators.  Two main loops: a general one (any K that is a multiple of 8: global memory is read
-// in 16-byte vectors into registers one K-step ahead and written to one of two LDS stages of row
-// pitch 72 bf16) and a fast one for K % 64 == 0 that fills the LDS straight from global memory.
+// (BM/WM) x (BN/WN) sub-tile as a grid of 16x16 blocks of v_mfma_f32_16x16x32_bf16 with float
+// accumulators (on random operands a register-only loop of this instruction sustains 2.0 PFLOP/s on this
+// part, one of the 32x32x16 form 1.77: the chip runs into its power limit later).  Two main loops: a
+// general one (any K that is a multiple of 8: global memory is read in 16-byte vectors into registers one
+// K-step ahead and written to one of two LDS stages of row pitch 72 bf16) and a fast one for K % 64 == 0
+// that fills the LDS straight from global memory.
 //
-// Accumulator layout of one 32x32 block (register r of lane l):
-//   row (A side, "M")  = 8*(r/4) + 4*(l/32) + r%4
-//   col (B side, "N")  = l%32
+// Operand layout of one block (lane l): row (or column) l % 16, k = 8 (l / 16) .. 8 (l / 16) + 7.
+// Accumulator layout of one 16x16 block (register r of lane l):
+//   row (A side, "M")  = 4*(l/16) + r
+//   col (B side, "N")  = l%16
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -19,7 +22,7 @@
 namespace umas {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 template <int BM_, int BN_, int WM_, int WN_>
 struct TileCfg {
@@ -28,12 +31,12 @@ struct TileCfg {
   static constexpr int LDP = 72;                       // LDS row pitch in bf16 elements
   static constexpr int T = 64 * WM * WN;               // threads per workgroup
   static constexpr int WTM = BM / WM, WTN = BN / WN;   // wavefront sub-tile
-  static constexpr int TM = WTM / 32, TN = WTN / 32;   // 32x32 blocks per wavefront
+  static constexpr int MI = WTM / 16, NI = WTN / 16;   // 16x16 blocks per wavefront
   static constexpr int NA = BM * 8 / T, NB = BN * 8 / T;   // 16-byte vectors per thread per K-step
   static constexpr int ROWS_PER_PASS = T / 8;          // rows covered by one vector slot of all threads
   static constexpr int STAGE = (BM + BN) * LDP;        // bf16 elements per LDS stage
   static constexpr int LDS_BYTES = 2 * STAGE * 2;
-  static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "sub-tiles are grids of 32x32 blocks");
+  static_assert(BM % (32 * WM) == 0 && BN % (16 * WN) == 0, "sub-tiles are grids of 16x16 blocks, an even number along M");
   static_assert((BM * 8) % T == 0 && (BN * 8) % T == 0, "vector slots divide evenly");
 };
 
@@ -47,7 +50,7 @@ __device__ __forceinline__ int slot_kofs() { return (threadIdx.x & 7) * 8; }
 // (K not a multiple of 64) is zero-filled, because every output depends on it.
 template <class C>
 __device__ __forceinline__ void mfma_mainloop(const uint16_t* const (&pa)[C::NA], const uint16_t* const (&pb)[C::NB],
-                                              int K, uint16_t* lds, floatx16 (&acc)[C::TM][C::TN]) {
+                                              int K, uint16_t* lds, floatx4 (&acc)[C::MI][C::NI]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
   const int kofs = slot_kofs();
@@ -87,20 +90,21 @@ __device__ __forceinline__ void mfma_mainloop(const uint16_t* const (&pa)[C::NA]
     for (int i = 0; i < C::NB; ++i) *reinterpret_cast<uint4*>(sb + slot_row<C>(i) * C::LDP + kofs) = rb[i];
   };
   auto compute = [&](int stage) {
-    const uint16_t* sa = lds + stage * C::STAGE + (wm * C::WTM + (lane & 31)) * C::LDP + (lane >> 5) * 8;
-    const uint16_t* sb = lds + stage * C::STAGE + (C::BM + wn * C::WTN + (lane & 31)) * C::LDP + (lane >> 5) * 8;
+    // operand of a 16x16x32 block: lane l holds row l % 16, k = 8 (l / 16) .. + 7 of the 32-wide slice
+    const uint16_t* sa = lds + stage * C::STAGE + (wm * C::WTM + (lane & 15)) * C::LDP + (lane >> 4) * 8;
+    const uint16_t* sb = lds + stage * C::STAGE + (C::BM + wn * C::WTN + (lane & 15)) * C::LDP + (lane >> 4) * 8;
 #pragma unroll
-    for (int kk = 0; kk < C::BK / 16; ++kk) {
-      bf16x8 af[C::TM], bfr[C::TN];
+    for (int kk = 0; kk < C::BK / 32; ++kk) {
+      bf16x8 af[C::MI], bfr[C::NI];
 #pragma unroll
-      for (int tm = 0; tm < C::TM; ++tm) af[tm] = *reinterpret_cast<const bf16x8*>(sa + tm * 32 * C::LDP + kk * 16);
+      for (int i = 0; i < C::MI; ++i) af[i] = *reinterpret_cast<const bf16x8*>(sa + i * 16 * C::LDP + kk * 32);
 #pragma unroll
-      for (int tn = 0; tn < C::TN; ++tn) bfr[tn] = *reinterpret_cast<const bf16x8*>(sb + tn * 32 * C::LDP + kk * 16);
+      for (int j = 0; j < C::NI; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(sb + j * 16 * C::LDP + kk * 32);
 #pragma unroll
-      for (int tm = 0; tm < C::TM; ++tm)
+      for (int i = 0; i < C::MI; ++i)
 #pragma unroll
-        for (int tn = 0; tn < C::TN; ++tn)
-          acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[tm], bfr[tn], acc[tm][tn], 0, 0, 0);
+        for (int j = 0; j < C::NI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
   };
 
@@ -130,8 +134,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
 // so that every byte offset of the tile fits 32 bits) plus one 32-bit byte offset per load slot.  The 16-byte chunk c of row r sits in slot
 // c ^ ((r >> 1) & 7), which keeps the fragment reads of 16 consecutive rows on distinct banks.
 // Per step j (stage j & 1): loads of step j+1 go to the other stage right away (everybody left it before the
-// barrier of the previous step); slices 0..2 run; then the wavefront waits for its own loads and LDS reads,
-// the workgroup meets at the barrier, and slice 3 runs while the first fragments of the next stage are read.
+// barrier of the previous step); phases 0..2 run; then the wavefront waits for its own loads and LDS reads,
+// the workgroup meets at the barrier, and phase 3 runs while the first fragments of the next stage are read.
 template <class C>
 struct Ring2Cfg {
   static constexpr int BK = 64;
@@ -154,8 +158,9 @@ __device__ __forceinline__ int ring2_kofs() {
 template <class C>
 __device__ __forceinline__ void mfma_mainloop_ring2(__amdgpu_buffer_rsrc_t ra, const uint32_t (&oa)[Ring2Cfg<C>::NA],
                                                     __amdgpu_buffer_rsrc_t rb, const uint32_t (&ob)[Ring2Cfg<C>::NB],
-                                                    int K, uint16_t* lds, floatx16 (&acc)[C::TM][C::TN]) {
+                                                    int K, uint16_t* lds, floatx4 (&acc)[C::MI][C::NI]) {
   using R = Ring2Cfg<C>;
+  constexpr int HA = C::MI / 2;                      // A blocks of one half of the wavefront's sub-tile
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / C::WN, wn = wave % C::WN;
@@ -175,29 +180,35 @@ __device__ __forceinline__ void mfma_mainloop_ring2(__amdgpu_buffer_rsrc_t ra, c
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, reinterpret_cast<uint32_t*>(sb + i * R::ROWS_PER_PASS * R::ROWB), 16,
                                                ob[i], kbytes, 0, 0);
   };
+  // Operand of a 16x16x32 block: lane l holds row l % 16, k = 8 (l / 16) .. + 7 of the 32-wide slice, i.e. chunk
+  // 4 s + l / 16 of the row.  A step is four phases of 16 MFMAs: (slice 0, upper half of the A rows), (slice 0,
+  // lower half), (slice 1, upper), (slice 1, lower); the B fragments of a slice serve both of its phases.
   const int sw = (lane >> 1) & 7;                    // (row >> 1) & 7 of this lane's fragment rows
-  const int arow = (wm * C::WTM + (lane & 31)) * R::ROWB;
-  const int brow = (C::BM + wn * C::WTN + (lane & 31)) * R::ROWB;
-  bf16x8 af[2][C::TM], bfr[2][C::TN];
-  auto fload = [&](int buf, int stage, int kk) {
-    const int coff = ((2 * kk + (lane >> 5)) ^ sw) * 16;
-    const char* sa = base + stage * R::STAGEB + arow + coff;
+  const int arow = (wm * C::WTM + (lane & 15)) * R::ROWB;
+  const int brow = (C::BM + wn * C::WTN + (lane & 15)) * R::ROWB;
+  bf16x8 af[2][HA], bfr[2][C::NI];
+  auto fload_a = [&](int buf, int stage, int s, int h) {
+    const int coff = ((4 * s + (lane >> 4)) ^ sw) * 16;
+    const char* sa = base + stage * R::STAGEB + arow + coff + h * HA * 16 * R::ROWB;
+#pragma unroll
+    for (int i = 0; i < HA; ++i) af[buf][i] = *reinterpret_cast<const bf16x8*>(sa + i * 16 * R::ROWB);
+  };
+  auto fload_b = [&](int buf, int stage, int s) {
+    const int coff = ((4 * s + (lane >> 4)) ^ sw) * 16;
     const char* sb = base + stage * R::STAGEB + brow + coff;
 #pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm) af[buf][tm] = *reinterpret_cast<const bf16x8*>(sa + tm * 32 * R::ROWB);
-#pragma unroll
-    for (int tn = 0; tn < C::TN; ++tn) bfr[buf][tn] = *reinterpret_cast<const bf16x8*>(sb + tn * 32 * R::ROWB);
+    for (int j = 0; j < C::NI; ++j) bfr[buf][j] = *reinterpret_cast<const bf16x8*>(sb + j * 16 * R::ROWB);
   };
-  auto mfmas = [&](int buf) {
+  auto mfmas = [&](int abuf, int bbuf, int h) {
 #pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm)
+    for (int i = 0; i < HA; ++i)
 #pragma unroll
-      for (int tn = 0; tn < C::TN; ++tn)
-        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][tm], bfr[buf][tn], acc[tm][tn], 0, 0, 0);
+      for (int j = 0; j < C::NI; ++j)
+        acc[h * HA + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[abuf][i], bfr[bbuf][j], acc[h * HA + i][j], 0, 0, 0);
   };
   auto interleave = [&](int n_ds, int n_vm) {
 #pragma unroll
-    for (int i = 0; i < C::TM * C::TN; ++i) {
+    for (int i = 0; i < HA * C::NI; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       if (i < n_ds) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       if (i < n_vm) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
@@ -207,31 +218,34 @@ __device__ __forceinline__ void mfma_mainloop_ring2(__amdgpu_buffer_rsrc_t ra, c
   gload(0, 0);
   __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();
-  fload(0, 0, 0);
+  fload_b(0, 0, 0);
+  fload_a(0, 0, 0, 0);
   __builtin_amdgcn_sched_barrier(0);
   for (int j = 0; j < nsub; ++j) {
     const int st = j & 1;
     // past the end of K the loads repeat the last step (nobody reads them)
     gload(j + 1 < nsub ? j + 1 : nsub - 1, st ^ 1);
-    fload(1, st, 1);
-    mfmas(0);
-    interleave(C::TM + C::TN, R::NA + R::NB);
+    fload_a(1, st, 0, 1);
+    mfmas(0, 0, 0);
+    interleave(HA, R::NA + R::NB);
     __builtin_amdgcn_sched_barrier(0);
-    fload(0, st, 2);
-    mfmas(1);
-    interleave(C::TM + C::TN, 0);
+    fload_b(1, st, 1);
+    fload_a(0, st, 1, 0);
+    mfmas(1, 0, 1);
+    interleave(HA + C::NI, 0);
     __builtin_amdgcn_sched_barrier(0);
-    fload(1, st, 3);
-    mfmas(0);
-    interleave(C::TM + C::TN, 0);
+    fload_a(1, st, 1, 1);
+    mfmas(0, 1, 0);
+    interleave(HA, 0);
     __builtin_amdgcn_sched_barrier(0);
     // own loads of the next stage landed, own reads of this stage done; then everybody's
     __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) and lgkmcnt(0), expcnt untouched (gfx9 encoding)
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    fload(0, st ^ 1, 0);
-    mfmas(1);
-    interleave(C::TM + C::TN, 0);
+    fload_b(0, st ^ 1, 0);
+    fload_a(0, st ^ 1, 0, 0);
+    mfmas(1, 1, 1);
+    interleave(HA + C::NI, 0);
     __builtin_amdgcn_sched_barrier(0);
   }
   __builtin_amdgcn_s_waitcnt(0x0070);
@@ -246,9 +260,10 @@ __device__ __forceinline__ void mfma_mainloop_ring2(__amdgpu_buffer_rsrc_t ra, c
 // them.  Fragments come out through ds_read_b64_tr_b16, which transposes on the way: in a group of 16
 // lanes, lane l receives element l % 4 of the 8-byte chunks addressed by lanes l / 4, l / 4 + 4, l / 4 + 8
 // and l / 4 + 12.  Lane i = q + 4 j of a group therefore points at k-row kbase + j, entries 4 q .. 4 q + 3
-// of the group's 16, and lane l ends up with entry l of the 16 for the four k of the read; two reads give
-// the eight k of an MFMA operand.  The 16-byte unit u of k-row k sits in slot u ^ (4 (k & 3)), which keeps
-// the 32 lanes served in one cycle on distinct banks.
+// of the block's 16, and lane l ends up with entry l of the 16 for the four k of the read; two reads give
+// the eight k of a 16x16x32 operand, group g of the wavefront taking k-rows 8 g .. 8 g + 7 of the slice.
+// The 16-byte unit u of k-row k sits in slot u ^ (4 (k & 3)) ^ (2 ((k >> 3) & 1)), which keeps the 32 lanes
+// served in one cycle (two groups, four k-rows each) on distinct banks.
 typedef short short4v __attribute__((ext_vector_type(4)));
 
 struct KMajor {                 // an operand tile stored K-major
@@ -265,9 +280,10 @@ struct KContig {                // an operand tile stored K-contiguous: per-slot
 
 template <class C, bool ATR, bool BTR, bool BMAP = false>
 __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMajor& ka, const KContig& cb, const KMajor& kb,
-                                                    int K, uint16_t* lds, floatx16 (&acc)[C::TM][C::TN]) {
+                                                    int K, uint16_t* lds, floatx4 (&acc)[C::MI][C::NI]) {
   using R = Ring2Cfg<C>;
   static_assert(C::BM == 256 && C::BN == 256 && C::T == 512 && R::NA == 4 && R::NB == 4, "written for 256x256 tiles, 8 wavefronts");
+  constexpr int HA = C::MI / 2;                      // A blocks of one half of the wavefront's sub-tile
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / C::WN, wn = wave % C::WN;
@@ -276,9 +292,9 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
   constexpr int kAB = C::BM * R::ROWB;               // bytes of the A region of a stage (B follows)
 
   // K-major loads: pass p covers k-rows 16 p .. 16 p + 15, this wavefront rows 16 p + 2 wave, + 1; lane l fills slot
-  // l & 31 of row 16 p + 2 wave + (l >> 5) and fetches unit slot ^ 4 (row & 3)
+  // l & 31 of row k = 16 p + 2 wave + (l >> 5) and fetches unit slot ^ 4 (k & 3) ^ 2 ((k >> 3) & 1)
   const int tr_krow = 2 * wave + (lane >> 5);        // + 16 p
-  const int tr_slot_unit = (lane & 31) ^ (4 * (tr_krow & 3));
+  const int tr_slot_unit = (lane & 31) ^ (4 * (tr_krow & 3)) ^ (2 * ((tr_krow >> 3) & 1));
   int32_t rows_a[4] = {0, 0, 0, 0}, rows_b[4] = {0, 0, 0, 0};   // rows of the step after next when a rowmap is set
   auto map_rows = [&](const KMajor& k, int sub, int32_t (&rows)[4]) {
 #pragma unroll
@@ -315,143 +331,152 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
     if (BTR) gload_kmajor(kb, rows_b, sub, sa + kAB, std::integral_constant<bool, BMAP>{}); else gload_kcontig(cb, sub, sa + kAB);
   };
 
-  // fragment addresses
+  // fragment addresses (K-contiguous operands as in mfma_mainloop_ring2)
   const int sw = (lane >> 1) & 7;
-  const int arow = (wm * C::WTM + (lane & 31)) * R::ROWB;
-  const int brow = (wn * C::WTN + (lane & 31)) * R::ROWB;
+  const int arow = (wm * C::WTM + (lane & 15)) * R::ROWB;
+  const int brow = (wn * C::WTN + (lane & 15)) * R::ROWB;
   const int tq = lane & 3, tj = (lane >> 2) & 3;     // position q + 4 j inside the group of 16 lanes
+  const int tg = lane >> 4;                          // the group: k-rows 8 g .. 8 g + 7 of a slice
   // The transposing reads are issued as inline assembly: the compiler cannot tell that they do not touch the stage
   // the LDS-filling loads are writing and would wait for those loads before every one of them.  Their results are
-  // therefore handed over by an explicit wait (tr_wait) that also names the registers, so that no use moves above it.
+  // therefore handed over by an explicit wait (tr_wait_*) that also names the registers, so that no use moves above it.
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
       (__attribute__((address_space(3))) char*)(base)));
-  // LDS byte address of this lane's chunk for block t of an operand whose sub-tile starts at unit u0: k-row (k half, j),
-  // 8-byte half of the unit, unit slot; stage, region, slice and the +4 k-rows of the second read are added as offsets
+  // LDS byte address of this lane's chunk for block t (16 entries = two units) of an operand whose sub-tile starts at
+  // unit u0: k-row 8 g + j, 8-byte half of the unit, unit slot; stage, region, slice and the + 4 k-rows of the second
+  // read are added as offsets
   auto tr_addr = [&](int u0, int t) -> uint32_t {
-    const int unit = u0 + t * 4 + ((lane >> 4) & 1) * 2 + (tq >> 1);
-    return lds0 + ((lane >> 5) * 8 + tj) * 512 + (tq & 1) * 8 + ((unit ^ (4 * tj)) * 16);
+    const int unit = u0 + t * 2 + (tq >> 1);
+    return lds0 + (tg * 8 + tj) * 512 + (tq & 1) * 8 + ((unit ^ (4 * tj) ^ (2 * (tg & 1))) * 16);
   };
-  uint32_t tra[C::TM], trb[C::TN];
+  uint32_t tra[C::MI], trb[C::NI];
 #pragma unroll
-  for (int tm = 0; tm < C::TM; ++tm) tra[tm] = tr_addr(wm * (C::WTM / 8), tm);
+  for (int i = 0; i < C::MI; ++i) tra[i] = tr_addr(wm * (C::WTM / 8), i);
 #pragma unroll
-  for (int tn = 0; tn < C::TN; ++tn) trb[tn] = tr_addr(wn * (C::WTN / 8), tn);
+  for (int j = 0; j < C::NI; ++j) trb[j] = tr_addr(wn * (C::WTN / 8), j);
   typedef short short8v __attribute__((ext_vector_type(8)));
-  bf16x8 af[2][C::TM], bfr[2][C::TN];
-  auto fload = [&](int buf, int stage, auto kk_c) {
-    constexpr int kk = decltype(kk_c)::value;
-    const char* sa = base + stage * R::STAGEB;
-    const char* sb = sa + kAB;
-    const int coff = ((2 * kk + (lane >> 5)) ^ sw) * 16;
+  bf16x8 af[2][HA], bfr[2][C::NI];
+  auto fload_a = [&](int buf, int stage, auto s_c, auto h_c) {
+    constexpr int s = decltype(s_c)::value, h = decltype(h_c)::value;
     const uint32_t stoff = static_cast<uint32_t>(stage) * R::STAGEB;
 #pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm) {
+    for (int i = 0; i < HA; ++i) {
       if (ATR) {
         short4v lo, hi;
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(tra[tm] + stoff), "n"(kk * 16 * 512));
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(tra[tm] + stoff), "n"(kk * 16 * 512 + 4 * 512));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(tra[h * HA + i] + stoff), "n"(s * 32 * 512));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(tra[h * HA + i] + stoff), "n"(s * 32 * 512 + 4 * 512));
         const short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        af[buf][tm] = __builtin_bit_cast(bf16x8, v);
+        af[buf][i] = __builtin_bit_cast(bf16x8, v);
       } else {
-        af[buf][tm] = *reinterpret_cast<const bf16x8*>(sa + arow + coff + tm * 32 * R::ROWB);
+        const int coff = ((4 * s + (lane >> 4)) ^ sw) * 16;
+        af[buf][i] = *reinterpret_cast<const bf16x8*>(base + stage * R::STAGEB + arow + coff + (h * HA + i) * 16 * R::ROWB);
       }
     }
+  };
+  auto fload_b = [&](int buf, int stage, auto s_c) {
+    constexpr int s = decltype(s_c)::value;
+    const uint32_t stoff = static_cast<uint32_t>(stage) * R::STAGEB;
 #pragma unroll
-    for (int tn = 0; tn < C::TN; ++tn) {
+    for (int j = 0; j < C::NI; ++j) {
       if (BTR) {
         short4v lo, hi;
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(trb[tn] + stoff), "n"(kAB + kk * 16 * 512));
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(trb[tn] + stoff), "n"(kAB + kk * 16 * 512 + 4 * 512));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(trb[j] + stoff), "n"(kAB + s * 32 * 512));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(trb[j] + stoff), "n"(kAB + s * 32 * 512 + 4 * 512));
         const short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        bfr[buf][tn] = __builtin_bit_cast(bf16x8, v);
+        bfr[buf][j] = __builtin_bit_cast(bf16x8, v);
       } else {
-        bfr[buf][tn] = *reinterpret_cast<const bf16x8*>(sb + brow + coff + tn * 32 * R::ROWB);
+        const int coff = ((4 * s + (lane >> 4)) ^ sw) * 16;
+        bfr[buf][j] = *reinterpret_cast<const bf16x8*>(base + stage * R::STAGEB + kAB + brow + coff + j * 16 * R::ROWB);
       }
     }
   };
-  // every LDS read issued so far has returned; the fragments of `buf` may be used from here on
-  auto tr_wait = [&](int buf) {
+  // every LDS read issued so far has returned; the named fragments may be used from here on
+  auto tr_wait_a = [&](int buf) {
     if (ATR) {
 #pragma unroll
-      for (int tm = 0; tm < C::TM; ++tm) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(af[buf][tm]));
+      for (int i = 0; i < HA; ++i) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(af[buf][i]));
     }
+  };
+  auto tr_wait_b = [&](int buf) {
     if (BTR) {
 #pragma unroll
-      for (int tn = 0; tn < C::TN; ++tn) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bfr[buf][tn]));
+      for (int j = 0; j < C::NI; ++j) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(bfr[buf][j]));
     }
   };
-  auto mfmas = [&](int buf) {
+  auto mfmas = [&](int abuf, int bbuf, int h) {
 #pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm)
+    for (int i = 0; i < HA; ++i)
 #pragma unroll
-      for (int tn = 0; tn < C::TN; ++tn)
-        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][tm], bfr[buf][tn], acc[tm][tn], 0, 0, 0);
+      for (int j = 0; j < C::NI; ++j)
+        acc[h * HA + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[abuf][i], bfr[bbuf][j], acc[h * HA + i][j], 0, 0, 0);
   };
 
-  constexpr int kDs = (ATR ? 2 : 1) * C::TM + (BTR ? 2 : 1) * C::TN;   // LDS reads per slice
+  constexpr int kDsA = (ATR ? 2 : 1) * HA, kDsB = (BTR ? 2 : 1) * C::NI;   // LDS reads of an A half, of a slice of B
   auto interleave = [&](int n_ds, int n_vm) {
 #pragma unroll
-    for (int i = 0; i < C::TM * C::TN; ++i) {
+    for (int i = 0; i < HA * C::NI; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (2 * i + 1 < n_ds) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      else if (2 * i < n_ds) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (i < n_ds) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       if (i < n_vm) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
     }
   };
-  using K0 = std::integral_constant<int, 0>;
-  using K1 = std::integral_constant<int, 1>;
-  using K2 = std::integral_constant<int, 2>;
-  using K3 = std::integral_constant<int, 3>;
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
   if (BTR && BMAP) map_rows(kb, 0, rows_b);
   gload(0, 0);
   if (BTR && BMAP) map_rows(kb, nsub > 1 ? 1 : 0, rows_b);
   __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();
-  fload(0, 0, K0{});
+  fload_b(0, 0, I0{});
+  fload_a(0, 0, I0{}, I0{});
   for (int j = 0; j < nsub; ++j) {
     const int st = j & 1;
     const int sub_next = j + 1 < nsub ? j + 1 : nsub - 1;      // past the end the last step is loaded again (nobody reads it)
-    tr_wait(0);
+    tr_wait_a(0);
+    tr_wait_b(0);
     gload(sub_next, st ^ 1);
     const int sub_after = j + 2 < nsub ? j + 2 : nsub - 1;
     if (BTR && BMAP) map_rows(kb, sub_after, rows_b);
-    fload(1, st, K1{});
-    mfmas(0);
-    interleave(kDs, 8);
+    fload_a(1, st, I0{}, I1{});
+    mfmas(0, 0, 0);
+    interleave(kDsA, 8);
     __builtin_amdgcn_sched_barrier(0);
-    tr_wait(1);
-    fload(0, st, K2{});
-    mfmas(1);
-    interleave(kDs, 0);
+    tr_wait_a(1);
+    fload_b(1, st, I1{});
+    fload_a(0, st, I1{}, I0{});
+    mfmas(1, 0, 1);
+    interleave(kDsA + kDsB, 0);
     __builtin_amdgcn_sched_barrier(0);
-    tr_wait(0);
-    fload(1, st, K3{});
-    mfmas(0);
-    interleave(kDs, 0);
+    tr_wait_a(0);
+    tr_wait_b(1);
+    fload_a(1, st, I1{}, I1{});
+    mfmas(0, 1, 0);
+    interleave(kDsA, 0);
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_waitcnt(0x0070);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    tr_wait(1);
-    fload(0, st ^ 1, K0{});
-    mfmas(1);
-    interleave(kDs, 0);
+    tr_wait_a(1);
+    fload_b(0, st ^ 1, I0{});
+    fload_a(0, st ^ 1, I0{}, I0{});
+    mfmas(1, 1, 1);
+    interleave(kDsA + kDsB, 0);
     __builtin_amdgcn_sched_barrier(0);
   }
   __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();
 }
 
-// Position of accumulator element (tm, tn, r) inside the workgroup tile.
+// Position of accumulator element r of block (i, j) inside the workgroup tile: row 4 (l / 16) + r, column l % 16 of the block.
 template <class C>
-__device__ __forceinline__ int acc_row(int tm, int r) {
+__device__ __forceinline__ int acc_row(int i, int r) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  return (wave / C::WN) * C::WTM + tm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+  return (wave / C::WN) * C::WTM + i * 16 + (lane >> 4) * 4 + r;
 }
 template <class C>
-__device__ __forceinline__ int acc_col(int tn) {
+__device__ __forceinline__ int acc_col(int j) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  return (wave % C::WN) * C::WTN + tn * 32 + (lane & 31);
+  return (wave % C::WN) * C::WTN + j * 16 + (lane & 15);
 }
 
 // Workgroups are handed to the 8 XCDs round-robin; give every XCD a contiguous range of the

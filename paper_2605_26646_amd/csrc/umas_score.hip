@@ -84,13 +84,11 @@ hipError_t fill_bytes_zero(void* p, size_t bytes, hipStream_t st) {
 template <class C>
 __device__ __forceinline__ void logit_tile(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
                                            const int32_t* __restrict__ rowsel, int64_t sel0, int64_t n_lim, int m0,
-                                           int64_t n0, uint16_t* lds, floatx16 (&acc)[C::TM][C::TN]) {
+                                           int64_t n0, uint16_t* lds, floatx4 (&acc)[C::MI][C::NI]) {
 #pragma unroll
-  for (int tm = 0; tm < C::TM; ++tm)
+  for (int i = 0; i < C::MI; ++i)
 #pragma unroll
-    for (int tn = 0; tn < C::TN; ++tn)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
+    for (int j = 0; j < C::NI; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
   if (d % C::BK == 0) {
     using R = Ring2Cfg<C>;
     const uint32_t kofs = ring2_kofs();
@@ -155,10 +153,11 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
   if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n, it, kTilesPerWg)) continue;
   const int m0 = tile_m * C::BM;
   const int64_t n0 = static_cast<int64_t>(tile_n) * C::BN;   // chunk-relative
-  floatx16 acc[C::TM][C::TN];
+  floatx4 acc[C::MI][C::NI];
   logit_tile<C>(W, H, d, V, rowsel, c0, mc, m0, n0, lds, acc);
 
-  // epilogue: the tile buffers are free now
+  // epilogue: the tile buffers are free now.  A lane holds, for each of its NI columns (selected rows), the
+  // vocabulary entries vbase + 16 i + r (i < MI, r < 4); the four lanes l, l + 16, l + 32, l + 48 share a column.
   float* s_part = reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + (KEEP ? kKeepLds - kPartBytes : 0));   // [WM][BN][3]
   float* s_zy = s_part + C::WM * C::BN * 3;               // [BN]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -166,28 +165,28 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
   char* stage = reinterpret_cast<char*>(lds) + wave * (C::WTN * kStagePitch);
   if (threadIdx.x < C::BN) s_zy[threadIdx.x] = 0.f;
   __syncthreads();                                        // every wavefront has left the main loop's LDS reads
-  const int vbase = m0 + wm * C::WTM + (lane >> 5) * 4;   // vocabulary id of element (tm=0, r=0)
+  const int vbase = m0 + wm * C::WTM + (lane >> 4) * 4;   // vocabulary id of element (i = 0, r = 0)
   const bool tail = m0 + C::BM > V;
   if (tail) {   // vocabulary ids past V: a large negative logit whose exponential is 0 and whose products stay finite
 #pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm)
+    for (int i = 0; i < C::MI; ++i)
 #pragma unroll
-      for (int tn = 0; tn < C::TN; ++tn)
+      for (int j = 0; j < C::NI; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (vbase + tm * 32 + (r >> 2) * 8 + (r & 3) >= V) acc[tm][tn][r] = kMasked;
+        for (int r = 0; r < 4; ++r)
+          if (vbase + i * 16 + r >= V) acc[i][j][r] = kMasked;
   }
   constexpr float kLog2e = 1.44269504088896341f;
   bool over = false;
 #pragma unroll
-  for (int tn = 0; tn < C::TN; ++tn) {
-    const int col = acc_col<C>(tn);
+  for (int j = 0; j < C::NI; ++j) {
+    const int col = acc_col<C>(j);
     const int64_t n = n0 + col;
     float m = kMasked;
 #pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm)
+    for (int i = 0; i < C::MI; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[tm][tn][r]);
+      for (int r = 0; r < 4; ++r) m = fmaxf(m, acc[i][j][r]);
     // The keeping variant sums relative to the row's reference c_n instead of the lane's maximum (any reference
     // serves the merge as long as nothing overflows), so the exponentials it sums are the numerators it keeps.
     // A lane whose maximum lies more than kKeepMaxGap above c_n flags the block and falls back to its maximum;
@@ -202,41 +201,42 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
     const float m2 = m * kLog2e;
     float s = 0.f, t = 0.f;
 #pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm)
+    for (int i = 0; i < C::MI; ++i) {
+      float e[4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float e[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float z = acc[tm][tn][q * 4 + j];
-          // without a reference from outside: z - m first, exact 0 where a lane holds nothing but vocabulary tail
-          e[j] = KEEP ? __builtin_amdgcn_exp2f(fmaf(z, kLog2e, -m2)) : __builtin_amdgcn_exp2f((z - m) * kLog2e);
-          s += e[j];
-          t = fmaf(e[j], z, t);
-        }
-        if (KEEP) {   // staged in this wavefront's LDS region, stored in full lines below
-          const uint32_t p01 = pack_bf16x2(e[0], e[1]), p23 = pack_bf16x2(e[2], e[3]);
-          *reinterpret_cast<uint2*>(stage + (tn * 32 + (lane & 31)) * kStagePitch + (tm * 32 + q * 8 + (lane >> 5) * 4) * 2) =
-              make_uint2(p01, p23);
-        }
+      for (int r = 0; r < 4; ++r) {
+        const float z = acc[i][j][r];
+        // without a reference from outside: z - m first, exact 0 where a lane holds nothing but vocabulary tail
+        e[r] = KEEP ? __builtin_amdgcn_exp2f(fmaf(z, kLog2e, -m2)) : __builtin_amdgcn_exp2f((z - m) * kLog2e);
+        s += e[r];
+        t = fmaf(e[r], z, t);
       }
+      if (KEEP) {   // staged in this wavefront's LDS region, stored in full lines below
+        const uint32_t p01 = pack_bf16x2(e[0], e[1]), p23 = pack_bf16x2(e[2], e[3]);
+        *reinterpret_cast<uint2*>(stage + (j * 16 + (lane & 15)) * kStagePitch + (i * 16 + (lane >> 4) * 4) * 2) =
+            make_uint2(p01, p23);
+      }
+    }
     Part p{m, s, t};
-    Part q{__shfl_xor(p.m, 32, kWave), __shfl_xor(p.s, 32, kWave), __shfl_xor(p.t, 32, kWave)};
-    p = part_merge(p, q);
-    if (lane < 32) {
+#pragma unroll
+    for (int o = 16; o < kWave; o <<= 1) {
+      const Part q{__shfl_xor(p.m, o, kWave), __shfl_xor(p.s, o, kWave), __shfl_xor(p.t, o, kWave)};
+      p = part_merge(p, q);
+    }
+    if (lane < 16) {
       float* dst = s_part + (wm * C::BN + col) * 3;
       dst[0] = p.m; dst[1] = p.s; dst[2] = p.t;
     }
     if (!KEEP && n < mc) {                                  // the keeping variant got the taken logits beforehand
       const int y = ids[rowsel ? rowsel[c0 + n] : c0 + n];
       const int rel = y - vbase;                           // offset from this lane's first element
-      if (y >= 0 && y < V && rel >= 0 && rel < C::WTM && ((rel >> 2) & 1) == 0) {
+      if (y >= 0 && y < V && rel >= 0 && rel < C::WTM && (rel & 12) == 0) {
         float zy = 0.f;
 #pragma unroll
-        for (int tm = 0; tm < C::TM; ++tm)
+        for (int i = 0; i < C::MI; ++i)
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (tm * 32 + (r >> 2) * 8 + (r & 3) == rel) zy = acc[tm][tn][r];
+          for (int r = 0; r < 4; ++r)
+            if (i * 16 + r == rel) zy = acc[i][j][r];
         s_zy[col] = zy;
       }
     }
@@ -535,28 +535,28 @@ __device__ __forceinline__ void dz_tile(int tile_m, int tile_n, const uint16_t* 
   using C = Cfg;
   const int m0 = tile_m * C::BM;
   const int64_t n0 = static_cast<int64_t>(tile_n) * C::BN;   // chunk-relative
-  floatx16 acc[C::TM][C::TN];
+  floatx4 acc[C::MI][C::NI];
   logit_tile<C>(W, H, d, V, rowsel, c0, mc, m0, n0, lds, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN;
-  const int vbase = m0 + wm * C::WTM + (lane >> 5) * 4;
+  const int vbase = m0 + wm * C::WTM + (lane >> 4) * 4;
   const bool tail = m0 + C::BM > V;
   // each wavefront stages its 64 (rows) x 128 (vocabulary) block; the 272-byte pitch keeps 16-byte alignment
   char* stage = reinterpret_cast<char*>(lds) + wave * (C::WTN * kStagePitch);
   __syncthreads();                              // every wavefront has left the main loop's LDS reads
   if (tail) {                                   // vocabulary ids past V: the exponential below is 0, the factor next to it finite
 #pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm)
+    for (int i = 0; i < C::MI; ++i)
 #pragma unroll
-      for (int tn = 0; tn < C::TN; ++tn)
+      for (int j = 0; j < C::NI; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (vbase + tm * 32 + (r >> 2) * 8 + (r & 3) >= V) acc[tm][tn][r] = kMasked;
+        for (int r = 0; r < 4; ++r)
+          if (vbase + i * 16 + r >= V) acc[i][j][r] = kMasked;
   }
 #pragma unroll
-  for (int tn = 0; tn < C::TN; ++tn) {
-    const int64_t n = n0 + acc_col<C>(tn);
+  for (int j = 0; j < C::NI; ++j) {
+    const int64_t n = n0 + acc_col<C>(j);
     // dz = p (a + kz z) with p = exp(z - lse), a = -g + k (entropy - lse), kz = k = entropy_coef / n_sel: the
     // dense part of g (onehot - p) plus the entropy bonus's k p (log p + entropy).  Rows past the chunk: p = 0.
     float l2 = 1e30f, a = 0.f, kz = 0.f;
@@ -566,20 +566,18 @@ __device__ __forceinline__ void dz_tile(int tile_m, int tile_n, const uint16_t* 
       kz = kz_c[c0 + n];
     }
 #pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm)
+    for (int i = 0; i < C::MI; ++i) {
+      float dz[4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float dz[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float z = acc[tm][tn][q * 4 + j];
-          dz[j] = __builtin_amdgcn_exp2f(fmaf(z, 1.44269504088896341f, -l2)) * fmaf(kz, z, a);
-        }
-        const uint32_t p01 = pack_bf16x2(dz[0], dz[1]), p23 = pack_bf16x2(dz[2], dz[3]);
-        // staged in this wavefront's LDS region, stored in full lines below
-        *reinterpret_cast<uint2*>(stage + (tn * 32 + (lane & 31)) * kStagePitch + (tm * 32 + q * 8 + (lane >> 5) * 4) * 2) =
-            make_uint2(p01, p23);
+      for (int r = 0; r < 4; ++r) {
+        const float z = acc[i][j][r];
+        dz[r] = __builtin_amdgcn_exp2f(fmaf(z, 1.44269504088896341f, -l2)) * fmaf(kz, z, a);
       }
+      const uint32_t p01 = pack_bf16x2(dz[0], dz[1]), p23 = pack_bf16x2(dz[2], dz[3]);
+      // staged in this wavefront's LDS region, stored in full lines below
+      *reinterpret_cast<uint2*>(stage + (j * 16 + (lane & 15)) * kStagePitch + (i * 16 + (lane >> 4) * 4) * 2) =
+          make_uint2(p01, p23);
+    }
   }
   // the staged block goes out 16 bytes per lane: one instruction covers 4 rows x 256 contiguous bytes
   const int wn = wave % C::WN;
@@ -628,13 +626,11 @@ k_dz_flagged(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int
 //   dW[v, j] (+)= C[v, j]
 // (kernel templates whose bodies use buffer resources do not get their host stubs emitted: plain kernels)
 template <class C>
-__device__ __forceinline__ void zero_acc(floatx16 (&acc)[C::TM][C::TN]) {
+__device__ __forceinline__ void zero_acc(floatx4 (&acc)[C::MI][C::NI]) {
 #pragma unroll
-  for (int tm = 0; tm < C::TM; ++tm)
+  for (int i = 0; i < C::MI; ++i)
 #pragma unroll
-    for (int tn = 0; tn < C::TN; ++tn)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
+    for (int j = 0; j < C::NI; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 }
 // K-contiguous operand tile: rows row0 .. row0 + 255 of X [n_rows, ld] (rows past the end read the last one)
 template <class C>
@@ -663,22 +659,22 @@ __device__ __forceinline__ void dh_tile(int tile_m, int tile_n, const uint16_t* 
   kb.rowmap = nullptr;
   kb.k_rows = V;                                                     // dz is zero for vocabulary ids past V
   kb.n_units = min(32, (d - n0) / 8);
-  floatx16 acc[C::TM][C::TN];
+  floatx4 acc[C::MI][C::NI];
   zero_acc<C>(acc);
   mfma_mainloop_mixed<C, false, true>(ca, KMajor{}, KContig{}, kb, static_cast<int>(Vp), lds, acc);
 #pragma unroll
-  for (int tn = 0; tn < C::TN; ++tn) {
-    const int j = n0 + acc_col<C>(tn);
+  for (int bj = 0; bj < C::NI; ++bj) {
+    const int j = n0 + acc_col<C>(bj);
     if (j >= d) continue;
 #pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm)
+    for (int bi = 0; bi < C::MI; ++bi)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t m = m0 + acc_row<C>(tm, r);
+      for (int r = 0; r < 4; ++r) {
+        const int64_t m = m0 + acc_row<C>(bi, r);
         if (m >= rows) continue;
         const int64_t row = rowsel ? rowsel[c0 + m] : c0 + m;
         const float g = g_c[c0 + m];
-        float v = sc ? sc[c0 + m] * acc[tm][tn][r] : acc[tm][tn][r];
+        float v = sc ? sc[c0 + m] * acc[bi][bj][r] : acc[bi][bj][r];
         if (g != 0.f) v += g * bf2f(W[static_cast<int64_t>(ids[row]) * d + j]);   // g = 0 for invalid ids
         dH[row * d + j] = f2bf(v);
       }
@@ -703,22 +699,22 @@ __device__ __forceinline__ void dw_tile(int tile_m, int tile_n, const uint16_t* 
   kb.rowmap = rowmap;
   kb.k_rows = static_cast<int>(rows);                                // dz is zero for rows past the chunk
   kb.n_units = min(32, (d - n0) / 8);
-  floatx16 acc[C::TM][C::TN];
+  floatx4 acc[C::MI][C::NI];
   zero_acc<C>(acc);
   if (rowmap) mfma_mainloop_mixed<C, true, true, true>(KContig{}, ka, KContig{}, kb, static_cast<int>(mcp), lds, acc);
   else mfma_mainloop_mixed<C, true, true, false>(KContig{}, ka, KContig{}, kb, static_cast<int>(mcp), lds, acc);
 #pragma unroll
-  for (int tn = 0; tn < C::TN; ++tn) {
-    const int j = n0 + acc_col<C>(tn);
+  for (int bj = 0; bj < C::NI; ++bj) {
+    const int j = n0 + acc_col<C>(bj);
     if (j >= d) continue;
 #pragma unroll
-    for (int tm = 0; tm < C::TM; ++tm)
+    for (int bi = 0; bi < C::MI; ++bi)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t v = m0 + acc_row<C>(tm, r);
+      for (int r = 0; r < 4; ++r) {
+        const int64_t v = m0 + acc_row<C>(bi, r);
         if (v >= V) continue;
         float* dst = dW + v * d + j;
-        *dst = accumulate ? *dst + acc[tm][tn][r] : acc[tm][tn][r];
+        *dst = accumulate ? *dst + acc[bi][bj][r] : acc[bi][bj][r];
       }
   }
 }
