@@ -266,6 +266,10 @@ __device__ __forceinline__ void mfma_mainloop_ring2(__amdgpu_buffer_rsrc_t ra, c
 // served in one cycle (two groups, four k-rows each) on distinct banks.
 typedef short short4v __attribute__((ext_vector_type(4)));
 
+template <class C>
+struct MixedLdsBytes {          // LDS of mfma_mainloop_mixed: three A stages and two B stages of 32 KB
+  static constexpr int value = 5 * C::BM * 128;
+};
 struct KMajor {                 // an operand tile stored K-major
   const char* base;             // byte address of (k-row 0, first entry of the tile)
   int64_t ld_bytes;             // bytes between consecutive k-rows
@@ -289,7 +293,12 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
   const int wm = wave / C::WN, wn = wave % C::WN;
   char* base = reinterpret_cast<char*>(lds);
   const int nsub = K / R::BK;
-  constexpr int kAB = C::BM * R::ROWB;               // bytes of the A region of a stage (B follows)
+  // LDS: three stages of operand A (32 KB each), then two of operand B.  A, the operand the callers stream from HBM
+  // ([rows, vocabulary] in both gradient products), is loaded two steps ahead, B one step ahead; with a row map on B
+  // (loads of two kinds in flight, which do not return in one order) A also stays one step ahead.
+  constexpr int kAStage = C::BM * R::ROWB, kBStage = C::BN * R::ROWB, kBBase = 3 * kAStage;
+  constexpr bool kA3 = !(BTR && BMAP);
+  static_assert(kBBase + 2 * kBStage <= MixedLdsBytes<C>::value, "LDS of the mixed loop");
 
   // K-major loads: pass p covers k-rows 16 p .. 16 p + 15, this wavefront rows 16 p + 2 wave, + 1; lane l fills slot
   // l & 31 of row k = 16 p + 2 wave + (l >> 5) and fetches unit slot ^ 4 (k & 3) ^ 2 ((k >> 3) & 1)
@@ -325,10 +334,13 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
       __builtin_amdgcn_raw_ptr_buffer_load_lds(c.rsrc, reinterpret_cast<uint32_t*>(region + (i * R::ROWS_PER_PASS + wave * 8) * R::ROWB), 16,
                                                c.off[i], kbytes, 0, 0);
   };
-  auto gload = [&](int sub, int stage) {
-    char* sa = base + stage * R::STAGEB;
+  auto gload_a = [&](int sub, int ia) {
+    char* sa = base + ia * kAStage;
     if (ATR) gload_kmajor(ka, rows_a, sub, sa, std::false_type{}); else gload_kcontig(ca, sub, sa);
-    if (BTR) gload_kmajor(kb, rows_b, sub, sa + kAB, std::integral_constant<bool, BMAP>{}); else gload_kcontig(cb, sub, sa + kAB);
+  };
+  auto gload_b = [&](int sub, int ib) {
+    char* sb = base + kBBase + ib * kBStage;
+    if (BTR) gload_kmajor(kb, rows_b, sub, sb, std::integral_constant<bool, BMAP>{}); else gload_kcontig(cb, sub, sb);
   };
 
   // fragment addresses (K-contiguous operands as in mfma_mainloop_ring2)
@@ -356,9 +368,9 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
   for (int j = 0; j < C::NI; ++j) trb[j] = tr_addr(wn * (C::WTN / 8), j);
   typedef short short8v __attribute__((ext_vector_type(8)));
   bf16x8 af[2][HA], bfr[2][C::NI];
-  auto fload_a = [&](int buf, int stage, auto s_c, auto h_c) {
+  auto fload_a = [&](int buf, int ia, auto s_c, auto h_c) {
     constexpr int s = decltype(s_c)::value, h = decltype(h_c)::value;
-    const uint32_t stoff = static_cast<uint32_t>(stage) * R::STAGEB;
+    const uint32_t stoff = static_cast<uint32_t>(ia) * kAStage;
 #pragma unroll
     for (int i = 0; i < HA; ++i) {
       if (ATR) {
@@ -369,24 +381,24 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
         af[buf][i] = __builtin_bit_cast(bf16x8, v);
       } else {
         const int coff = ((4 * s + (lane >> 4)) ^ sw) * 16;
-        af[buf][i] = *reinterpret_cast<const bf16x8*>(base + stage * R::STAGEB + arow + coff + (h * HA + i) * 16 * R::ROWB);
+        af[buf][i] = *reinterpret_cast<const bf16x8*>(base + stoff + arow + coff + (h * HA + i) * 16 * R::ROWB);
       }
     }
   };
-  auto fload_b = [&](int buf, int stage, auto s_c) {
+  auto fload_b = [&](int buf, int ib, auto s_c) {
     constexpr int s = decltype(s_c)::value;
-    const uint32_t stoff = static_cast<uint32_t>(stage) * R::STAGEB;
+    const uint32_t stoff = kBBase + static_cast<uint32_t>(ib) * kBStage;
 #pragma unroll
     for (int j = 0; j < C::NI; ++j) {
       if (BTR) {
         short4v lo, hi;
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(trb[j] + stoff), "n"(kAB + s * 32 * 512));
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(trb[j] + stoff), "n"(kAB + s * 32 * 512 + 4 * 512));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(trb[j] + stoff), "n"(s * 32 * 512));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(trb[j] + stoff), "n"(s * 32 * 512 + 4 * 512));
         const short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         bfr[buf][j] = __builtin_bit_cast(bf16x8, v);
       } else {
         const int coff = ((4 * s + (lane >> 4)) ^ sw) * 16;
-        bfr[buf][j] = *reinterpret_cast<const bf16x8*>(base + stage * R::STAGEB + kAB + brow + coff + j * 16 * R::ROWB);
+        bfr[buf][j] = *reinterpret_cast<const bf16x8*>(base + stoff + brow + coff + j * 16 * R::ROWB);
       }
     }
   };
@@ -422,46 +434,55 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
+  auto clamp_sub = [&](int sub) { return sub < nsub ? sub : nsub - 1; };   // past the end the last step is loaded again (nobody reads it)
   if (BTR && BMAP) map_rows(kb, 0, rows_b);
-  gload(0, 0);
-  if (BTR && BMAP) map_rows(kb, nsub > 1 ? 1 : 0, rows_b);
+  gload_a(0, 0);
+  gload_b(0, 0);
+  if (kA3) gload_a(clamp_sub(1), 1);
+  if (BTR && BMAP) map_rows(kb, clamp_sub(1), rows_b);
   __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();
   fload_b(0, 0, I0{});
   fload_a(0, 0, I0{}, I0{});
+  int ia = 0;                                        // A stage of the current step
   for (int j = 0; j < nsub; ++j) {
-    const int st = j & 1;
-    const int sub_next = j + 1 < nsub ? j + 1 : nsub - 1;      // past the end the last step is loaded again (nobody reads it)
+    const int ib = j & 1;
+    const int ia1 = kA3 ? (ia == 2 ? 0 : ia + 1) : (ia ^ 1);       // A stage of the next step
+    const int ia2 = ia1 == 2 ? 0 : ia1 + 1;                         // and of the one after (three stages)
     tr_wait_a(0);
     tr_wait_b(0);
-    gload(sub_next, st ^ 1);
-    const int sub_after = j + 2 < nsub ? j + 2 : nsub - 1;
-    if (BTR && BMAP) map_rows(kb, sub_after, rows_b);
-    fload_a(1, st, I0{}, I1{});
+    gload_b(clamp_sub(j + 1), ib ^ 1);
+    if (kA3) gload_a(clamp_sub(j + 2), ia2); else gload_a(clamp_sub(j + 1), ia1);
+    if (BTR && BMAP) map_rows(kb, clamp_sub(j + 2), rows_b);
+    fload_a(1, ia, I0{}, I1{});
     mfmas(0, 0, 0);
     interleave(kDsA, 8);
     __builtin_amdgcn_sched_barrier(0);
     tr_wait_a(1);
-    fload_b(1, st, I1{});
-    fload_a(0, st, I1{}, I0{});
+    fload_b(1, ib, I1{});
+    fload_a(0, ia, I1{}, I0{});
     mfmas(1, 0, 1);
     interleave(kDsA + kDsB, 0);
     __builtin_amdgcn_sched_barrier(0);
     tr_wait_a(0);
     tr_wait_b(1);
-    fload_a(1, st, I1{}, I1{});
+    fload_a(1, ia, I1{}, I1{});
     mfmas(0, 1, 0);
     interleave(kDsA, 0);
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(0x0070);
+    // own LDS reads of this step done and own loads for the next step landed: with three A stages the four
+    // youngest loads (A of the step after next) may still be on their way; then everybody's
+    if (kA3) __builtin_amdgcn_s_waitcnt(0x0074);     // vmcnt(4), lgkmcnt(0)
+    else __builtin_amdgcn_s_waitcnt(0x0070);         // vmcnt(0), lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     tr_wait_a(1);
-    fload_b(0, st ^ 1, I0{});
-    fload_a(0, st ^ 1, I0{}, I0{});
+    fload_b(0, ib ^ 1, I0{});
+    fload_a(0, ia1, I0{}, I0{});
     mfmas(1, 1, 1);
     interleave(kDsA + kDsB, 0);
     __builtin_amdgcn_sched_barrier(0);
+    ia = ia1;
   }
   __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();

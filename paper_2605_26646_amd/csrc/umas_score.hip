@@ -727,7 +727,7 @@ k_gemm_dh_dw(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uin
              int tiles_d, unsigned grid_dh, XcdGroups dw_groups, uint16_t* __restrict__ dH, float* __restrict__ dW,
              int accumulate, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
              const int32_t* __restrict__ ids, const float* __restrict__ g_c, const float* __restrict__ sc) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[Ring::LDS_BYTES / 2];
+  __shared__ __attribute__((aligned(16))) uint16_t lds[MixedLdsBytes<Cfg>::value / 2];
   int tile_m, tile_n;
   if (blockIdx.x < grid_dh) {
     if (!tile_coords<kGM, kGN>(tiles_r, tiles_d, &tile_m, &tile_n)) return;
