@@ -133,15 +133,19 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
 // consecutive rows (1 KB).  Operands are addressed as raw buffers: a wave-uniform base (the caller picks it
 // so that every byte offset of the tile fits 32 bits) plus one 32-bit byte offset per load slot.  The 16-byte chunk c of row r sits in slot
 // c ^ ((r >> 1) & 7), which keeps the fragment reads of 16 consecutive rows on distinct banks.
-// Per step j (stage j & 1): loads of step j+1 go to the other stage right away (everybody left it before the
-// barrier of the previous step); phases 0..2 run; then the wavefront waits for its own loads and LDS reads,
-// the workgroup meets at the barrier, and phase 3 runs while the first fragments of the next stage are read.
+// Operand A has three stages and is loaded two steps ahead, operand B two stages, one step ahead (the callers
+// put the operand that comes from farther away in A).  Per step j: the loads of B for step j+1 and of A for step
+// j+2 go out right away (everybody left those stages before the barrier of the previous step); phases 0..2 run;
+// then the wavefront waits for its LDS reads and for all loads but the youngest ones (A of step j+2: loads into
+// LDS return in the order they were issued), the workgroup meets at the barrier, and phase 3 runs while the first
+// fragments of the next step are read.
 template <class C>
 struct Ring2Cfg {
   static constexpr int BK = 64;
   static constexpr int ROWB = 128;
-  static constexpr int STAGEB = (C::BM + C::BN) * ROWB;
-  static constexpr int LDS_BYTES = 2 * STAGEB;
+  static constexpr int ASTAGE = C::BM * ROWB, BSTAGE = C::BN * ROWB;   // bytes of one stage of an operand
+  static constexpr int BBASE = 3 * ASTAGE;                             // three stages of A, then two of B
+  static constexpr int LDS_BYTES = BBASE + 2 * BSTAGE;
   static constexpr int NA = C::BM * 8 / C::T, NB = C::BN * 8 / C::T;   // 16-byte loads per thread per step
   static constexpr int ROWS_PER_PASS = C::T / 8;
   static_assert(C::T % 64 == 0 && (C::BM * 8) % C::T == 0 && (C::BN * 8) % C::T == 0, "load slots divide evenly");
@@ -167,14 +171,18 @@ __device__ __forceinline__ void mfma_mainloop_ring2(__amdgpu_buffer_rsrc_t ra, c
   char* base = reinterpret_cast<char*>(lds);
   const int nsub = K / R::BK;
 
-  auto gload = [&](int sub, int stage) {
+  static_assert(R::NA == 4, "the wait before the barrier leaves four loads outstanding");
+  auto gload_a = [&](int sub, int ia) {
     const int kbytes = sub * R::BK * 2;
-    char* sa = base + stage * R::STAGEB + wave * 8 * R::ROWB;
-    char* sb = sa + C::BM * R::ROWB;
+    char* sa = base + ia * R::ASTAGE + wave * 8 * R::ROWB;
 #pragma unroll
     for (int i = 0; i < R::NA; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, reinterpret_cast<uint32_t*>(sa + i * R::ROWS_PER_PASS * R::ROWB), 16,
                                                oa[i], kbytes, 0, 0);
+  };
+  auto gload_b = [&](int sub, int ib) {
+    const int kbytes = sub * R::BK * 2;
+    char* sb = base + R::BBASE + ib * R::BSTAGE + wave * 8 * R::ROWB;
 #pragma unroll
     for (int i = 0; i < R::NB; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, reinterpret_cast<uint32_t*>(sb + i * R::ROWS_PER_PASS * R::ROWB), 16,
@@ -185,17 +193,17 @@ __device__ __forceinline__ void mfma_mainloop_ring2(__amdgpu_buffer_rsrc_t ra, c
   // lower half), (slice 1, upper), (slice 1, lower); the B fragments of a slice serve both of its phases.
   const int sw = (lane >> 1) & 7;                    // (row >> 1) & 7 of this lane's fragment rows
   const int arow = (wm * C::WTM + (lane & 15)) * R::ROWB;
-  const int brow = (C::BM + wn * C::WTN + (lane & 15)) * R::ROWB;
+  const int brow = R::BBASE + (wn * C::WTN + (lane & 15)) * R::ROWB;
   bf16x8 af[2][HA], bfr[2][C::NI];
-  auto fload_a = [&](int buf, int stage, int s, int h) {
+  auto fload_a = [&](int buf, int ia, int s, int h) {
     const int coff = ((4 * s + (lane >> 4)) ^ sw) * 16;
-    const char* sa = base + stage * R::STAGEB + arow + coff + h * HA * 16 * R::ROWB;
+    const char* sa = base + ia * R::ASTAGE + arow + coff + h * HA * 16 * R::ROWB;
 #pragma unroll
     for (int i = 0; i < HA; ++i) af[buf][i] = *reinterpret_cast<const bf16x8*>(sa + i * 16 * R::ROWB);
   };
-  auto fload_b = [&](int buf, int stage, int s) {
+  auto fload_b = [&](int buf, int ib, int s) {
     const int coff = ((4 * s + (lane >> 4)) ^ sw) * 16;
-    const char* sb = base + stage * R::STAGEB + brow + coff;
+    const char* sb = base + ib * R::BSTAGE + brow + coff;
 #pragma unroll
     for (int j = 0; j < C::NI; ++j) bfr[buf][j] = *reinterpret_cast<const bf16x8*>(sb + j * 16 * R::ROWB);
   };
@@ -215,38 +223,45 @@ __device__ __forceinline__ void mfma_mainloop_ring2(__amdgpu_buffer_rsrc_t ra, c
     }
   };
 
-  gload(0, 0);
+  auto clamp_sub = [&](int sub) { return sub < nsub ? sub : nsub - 1; };   // past the end of K the loads repeat the last step (nobody reads them)
+  gload_a(0, 0);
+  gload_b(0, 0);
+  gload_a(clamp_sub(1), 1);
   __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();
   fload_b(0, 0, 0);
   fload_a(0, 0, 0, 0);
   __builtin_amdgcn_sched_barrier(0);
+  int ia = 0;                                        // A stage of the current step
   for (int j = 0; j < nsub; ++j) {
-    const int st = j & 1;
-    // past the end of K the loads repeat the last step (nobody reads them)
-    gload(j + 1 < nsub ? j + 1 : nsub - 1, st ^ 1);
-    fload_a(1, st, 0, 1);
+    const int ib = j & 1;
+    const int ia1 = ia == 2 ? 0 : ia + 1, ia2 = ia1 == 2 ? 0 : ia1 + 1;
+    gload_b(clamp_sub(j + 1), ib ^ 1);
+    gload_a(clamp_sub(j + 2), ia2);
+    fload_a(1, ia, 0, 1);
     mfmas(0, 0, 0);
     interleave(HA, R::NA + R::NB);
     __builtin_amdgcn_sched_barrier(0);
-    fload_b(1, st, 1);
-    fload_a(0, st, 1, 0);
+    fload_b(1, ib, 1);
+    fload_a(0, ia, 1, 0);
     mfmas(1, 0, 1);
     interleave(HA + C::NI, 0);
     __builtin_amdgcn_sched_barrier(0);
-    fload_a(1, st, 1, 1);
+    fload_a(1, ia, 1, 1);
     mfmas(0, 1, 0);
     interleave(HA, 0);
     __builtin_amdgcn_sched_barrier(0);
-    // own loads of the next stage landed, own reads of this stage done; then everybody's
-    __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) and lgkmcnt(0), expcnt untouched (gfx9 encoding)
+    // own reads of this step done, own loads for the next step landed (the four youngest, A of the step after
+    // next, may still be on their way); then everybody's
+    __builtin_amdgcn_s_waitcnt(0x0074);              // vmcnt(4) and lgkmcnt(0), expcnt untouched (gfx9 encoding)
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    fload_b(0, st ^ 1, 0);
-    fload_a(0, st ^ 1, 0, 0);
+    fload_b(0, ib ^ 1, 0);
+    fload_a(0, ia1, 0, 0);
     mfmas(1, 1, 1);
     interleave(HA + C::NI, 0);
     __builtin_amdgcn_sched_barrier(0);
+    ia = ia1;
   }
   __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();
@@ -267,8 +282,8 @@ __device__ __forceinline__ void mfma_mainloop_ring2(__amdgpu_buffer_rsrc_t ra, c
 typedef short short4v __attribute__((ext_vector_type(4)));
 
 template <class C>
-struct MixedLdsBytes {          // LDS of mfma_mainloop_mixed: three A stages and two B stages of 32 KB
-  static constexpr int value = 5 * C::BM * 128;
+struct MixedLdsBytes {          // LDS of mfma_mainloop_mixed: three A stages and two B stages of 32 KB, like the ring's
+  static constexpr int value = Ring2Cfg<C>::LDS_BYTES;
 };
 struct KMajor {                 // an operand tile stored K-major
   const char* base;             // byte address of (k-row 0, first entry of the tile)

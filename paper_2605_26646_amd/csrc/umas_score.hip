@@ -130,9 +130,8 @@ constexpr float kKeepMaxGap = 50.f;
 constexpr int kStagePitch = Cfg::WTM * 2 + 16;                                  // one staged row: 128 bf16, 16-byte aligned
 constexpr int kStageBytes = Cfg::WM * Cfg::WN * Cfg::WTN * kStagePitch;         // every wavefront stages its 128 x 64 block
 constexpr int kPartBytes = (Cfg::WM * Cfg::BN * 3 + Cfg::BN) * 4;
-constexpr int kKeepLds = (kLogitLds > kStageBytes ? kLogitLds : kStageBytes) + kPartBytes;
-static_assert(kStageBytes <= kLogitLds, "staging fits the tile buffers");
-static_assert(kKeepLds <= 160 * 1024, "LDS of one CU");
+static_assert(kStageBytes + kPartBytes <= kLogitLds, "staging and the partials fit the tile buffers");
+static_assert(kLogitLds <= 160 * 1024, "LDS of one CU");
 
 struct KeepArgs {
   const float* cref;   // [n_pad] reference per selected row, NaN for rows without a valid id
@@ -158,7 +157,7 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
 
   // epilogue: the tile buffers are free now.  A lane holds, for each of its NI columns (selected rows), the
   // vocabulary entries vbase + 16 i + r (i < MI, r < 4); the four lanes l, l + 16, l + 32, l + 48 share a column.
-  float* s_part = reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + (KEEP ? kKeepLds - kPartBytes : 0));   // [WM][BN][3]
+  float* s_part = reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + (KEEP ? kStageBytes : 0));   // [WM][BN][3], behind the staging area
   float* s_zy = s_part + C::WM * C::BN * 3;               // [BN]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN;
@@ -282,7 +281,7 @@ k_score_keep_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ 
                    const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc, const int32_t* __restrict__ ids,
                    int tiles_m, int tiles_n, float4* __restrict__ partial, int64_t n_pad,
                    const float* __restrict__ cref, uint16_t* __restrict__ E, int64_t Vp, int32_t* __restrict__ flags) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[kKeepLds / 2];
+  __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
   score_tiles<true>(W, H, d, V, rowsel, c0, mc, ids, tiles_m, tiles_n, partial, n_pad, KeepArgs{cref, E, Vp, flags}, lds);
 }
 
