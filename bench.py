@@ -45,20 +45,28 @@ def cpu_baseline(w, t, sample_rows):
             "sample": f"first {n} rows of the same workload (same W), scoring+loss+backward in float64, {dt:.1f} s"}
 
 
+def kernel_source_hash():
+    """sha256 over the MFMA kernels' sources with comments and white space removed: a change of the code
+    invalidates the stored counters, a change of a comment does not."""
+    import hashlib, re
+    h = hashlib.sha256()
+    for fn in ("umas_score.hip", "umas_mfma.h", "umas_common.h"):
+        text = open(os.path.join(ROOT, "paper_2605_26646_amd", "csrc", fn)).read()
+        text = re.sub(r"//[^\n]*", "", text)
+        h.update(re.sub(r"\s+", "", text).encode())
+    return h.hexdigest()
+
+
 def stored_traffic(kernel):
     """HBM-side bytes per launch of `kernel` from the committed counter summary (FETCH_SIZE + WRITE_SIZE,
     scaled by what the same counters read for a plain copy); None when the kernel sources have changed
     since the counters were taken."""
-    import hashlib
     path = os.path.join(ROOT, "profiles", "bench_cfg1_traffic.json")
     if not os.path.exists(path):
         return None
     rec = json.load(open(path))
-    h = hashlib.sha256()
-    for fn in ("umas_score.hip", "umas_mfma.h", "umas_common.h"):
-        h.update(open(os.path.join(ROOT, "paper_2605_26646_amd", "csrc", fn), "rb").read())
     k = rec["kernels"].get(kernel)
-    if h.hexdigest() != rec.get("kernel_sources_sha256") or k is None:
+    if kernel_source_hash() != rec.get("kernel_sources_sha256") or k is None:
         return None
     return k["read_bytes"] + k["written_bytes"]
 

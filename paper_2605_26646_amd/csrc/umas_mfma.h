@@ -128,7 +128,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
 // Fast main loop for K % 64 == 0.
 //
 // K is walked in steps of 64: 128 bytes per row, the line size of the vector caches, so every line is
-// fetched once.  Tiles go from global memory straight into one of two LDS stages of (BM + BN) x 128 bytes
+// fetched once.  Tiles go from global memory straight into LDS stages of 256 rows x 128 bytes per operand
 // (buffer_load_dwordx4 ... lds: no staging registers, no ds_write); one wavefront-wide load fills 8
 // consecutive rows (1 KB).  Operands are addressed as raw buffers: a wave-uniform base (the caller picks it
 // so that every byte offset of the tile fits 32 bits) plus one 32-bit byte offset per load slot.  The 16-byte chunk c of row r sits in slot

@@ -128,7 +128,7 @@ __device__ __forceinline__ void logit_tile(const uint16_t* __restrict__ W, const
 // (E could overflow) is flagged and gets its dz from the recomputing kernel instead.
 constexpr float kKeepMaxGap = 50.f;
 constexpr int kStagePitch = Cfg::WTM * 2 + 16;                                  // one staged row: 128 bf16, 16-byte aligned
-constexpr int kStageBytes = Cfg::WM * Cfg::WN * Cfg::WTN * kStagePitch;         // every wavefront stages its 128 x 64 block
+constexpr int kStageBytes = Cfg::WM * Cfg::WN * Cfg::WTN * kStagePitch;         // every wavefront stages its block: 64 rows x 128 vocabulary entries
 constexpr int kPartBytes = (Cfg::WM * Cfg::BN * 3 + Cfg::BN) * 4;
 static_assert(kStageBytes + kPartBytes <= kLogitLds, "staging and the partials fit the tile buffers");
 static_assert(kLogitLds <= 160 * 1024, "LDS of one CU");
