@@ -144,6 +144,34 @@ def test_full_size(cfg):
     run_fullsize(cfg)
 
 
+def test_full_size_single_pass_backward_agrees_with_recomputing_backward():
+    """Without an entropy bonus the update keeps the softmax numerators of its scoring pass and never computes a
+    logit twice; with one it recomputes them tile by tile.  An entropy coefficient too small to change any
+    float32 result selects the second path: both must give the same loss and the same gradients, everywhere,
+    at the benchmark's size (the oracle covers sampled entries only there)."""
+    w = wl.make_workload(1)
+    s, adv, ret = P.gpu_front(w)
+    spec = w.models[0]
+    t = w.model_tensors(0)
+    n_sel = int(s.rowsel.numel())
+    H, W, ids = P.to_dev(t["H"], torch.bfloat16), P.to_dev(t["W"], torch.bfloat16), P.to_dev(t["ids"])
+    logp, _, _ = umas.umas_policy_logprobs(H, W, ids, s.rowsel)
+    logp_old = logp + P.to_dev(t["noise"].astype(np.float32))
+    ws = torch.empty(umas.ppo_workspace_bytes(n_sel, spec.d, spec.V, torch.bfloat16, w.n_roles), dtype=torch.uint8, device="cuda")
+    out = []
+    for coef in (0.0, 1e-30):
+        stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(H, W, ids, s.rowsel, logp_old, adv, s.tok_role, w.n_roles,
+                                                            w.clip_eps, entropy_coef=coef, workspace=ws)
+        torch.cuda.synchronize()
+        out.append((umas.read_stats(stats), logp_new.cpu().numpy(), dH.float().cpu().numpy(), dW.cpu().numpy()))
+        del dH, dW
+    (sa, la, dHa, dWa), (sb, lb, dHb, dWb) = out
+    assert np.abs(la - lb).max() <= 1e-4
+    assert abs(float(sa["loss"][0]) - float(sb["loss"][0])) <= 1e-5 * max(abs(float(sb["loss"][0])), 1e-3)
+    P.close(dHa, dHb, TOL, "dH, kept numerators against recomputed logits")
+    P.close(dWa, dWb, TOL, "dW, kept numerators against recomputed logits")
+
+
 @pytest.mark.parametrize("cfg", [1, 4])
 def test_full_size_critic(cfg):
     """The critic's fused pass at the configurations' real row counts and hidden sizes; the oracle's per-row
