@@ -297,7 +297,7 @@ struct KContig {                // an operand tile stored K-contiguous: per-slot
   uint32_t off[4];
 };
 
-template <class C, bool ATR, bool BTR, bool BMAP = false>
+template <class C, bool ATR, bool BTR, bool BMAP = false, int AHEAD = (BMAP ? 0 : 1)>
 __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMajor& ka, const KContig& cb, const KMajor& kb,
                                                     int K, uint16_t* lds, floatx4 (&acc)[C::MI][C::NI]) {
   using R = Ring2Cfg<C>;
@@ -308,12 +308,14 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
   const int wm = wave / C::WN, wn = wave % C::WN;
   char* base = reinterpret_cast<char*>(lds);
   const int nsub = K / R::BK;
-  // LDS: three stages of operand A (32 KB each), then two of operand B.  A, the operand the callers stream from HBM
-  // ([rows, vocabulary] in both gradient products), is loaded two steps ahead, B one step ahead; with a row map on B
-  // (loads of two kinds in flight, which do not return in one order) A also stays one step ahead.
-  constexpr int kAStage = C::BM * R::ROWB, kBStage = C::BN * R::ROWB, kBBase = 3 * kAStage;
-  constexpr bool kA3 = !(BTR && BMAP);
-  static_assert(kBBase + 2 * kBStage <= MixedLdsBytes<C>::value, "LDS of the mixed loop");
+  // LDS: five stages of 32 KB.  One operand (AHEAD = 1: A, AHEAD = 2: B) has three of them and is loaded two steps
+  // ahead, the other two, one step ahead; the callers give the third stage to the operand that comes from farther
+  // away.  With a row map on B (loads of two kinds in flight, which do not return in one order) AHEAD is 0 and both
+  // stay one step ahead.
+  static_assert(AHEAD >= 0 && AHEAD <= 2 && !(BMAP && AHEAD != 0), "which operand is loaded two steps ahead");
+  constexpr int kAStage = C::BM * R::ROWB, kBStage = C::BN * R::ROWB;
+  constexpr int kABase = AHEAD == 2 ? 3 * kBStage : 0, kBBase = AHEAD == 2 ? 0 : 3 * kAStage;
+  static_assert(3 * kAStage + 2 * kBStage <= MixedLdsBytes<C>::value && kAStage == kBStage, "LDS of the mixed loop");
 
   // K-major loads: pass p covers k-rows 16 p .. 16 p + 15, this wavefront rows 16 p + 2 wave, + 1; lane l fills slot
   // l & 31 of row k = 16 p + 2 wave + (l >> 5) and fetches unit slot ^ 4 (k & 3) ^ 2 ((k >> 3) & 1)
@@ -350,7 +352,7 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
                                                c.off[i], kbytes, 0, 0);
   };
   auto gload_a = [&](int sub, int ia) {
-    char* sa = base + ia * kAStage;
+    char* sa = base + kABase + ia * kAStage;
     if (ATR) gload_kmajor(ka, rows_a, sub, sa, std::false_type{}); else gload_kcontig(ca, sub, sa);
   };
   auto gload_b = [&](int sub, int ib) {
@@ -385,7 +387,7 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
   bf16x8 af[2][HA], bfr[2][C::NI];
   auto fload_a = [&](int buf, int ia, auto s_c, auto h_c) {
     constexpr int s = decltype(s_c)::value, h = decltype(h_c)::value;
-    const uint32_t stoff = static_cast<uint32_t>(ia) * kAStage;
+    const uint32_t stoff = kABase + static_cast<uint32_t>(ia) * kAStage;
 #pragma unroll
     for (int i = 0; i < HA; ++i) {
       if (ATR) {
@@ -453,21 +455,30 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
   if (BTR && BMAP) map_rows(kb, 0, rows_b);
   gload_a(0, 0);
   gload_b(0, 0);
-  if (kA3) gload_a(clamp_sub(1), 1);
+  if (AHEAD == 1) gload_a(clamp_sub(1), 1);
+  if (AHEAD == 2) gload_b(clamp_sub(1), 1);
   if (BTR && BMAP) map_rows(kb, clamp_sub(1), rows_b);
   __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();
   fload_b(0, 0, I0{});
   fload_a(0, 0, I0{}, I0{});
-  int ia = 0;                                        // A stage of the current step
+  auto next3 = [](int i) { return i == 2 ? 0 : i + 1; };
+  int ia = 0, ib = 0;                                // stages of the current step
   for (int j = 0; j < nsub; ++j) {
-    const int ib = j & 1;
-    const int ia1 = kA3 ? (ia == 2 ? 0 : ia + 1) : (ia ^ 1);       // A stage of the next step
-    const int ia2 = ia1 == 2 ? 0 : ia1 + 1;                         // and of the one after (three stages)
+    const int ia1 = AHEAD == 1 ? next3(ia) : (ia ^ 1);              // stages of the next step
+    const int ib1 = AHEAD == 2 ? next3(ib) : (ib ^ 1);
     tr_wait_a(0);
     tr_wait_b(0);
-    gload_b(clamp_sub(j + 1), ib ^ 1);
-    if (kA3) gload_a(clamp_sub(j + 2), ia2); else gload_a(clamp_sub(j + 1), ia1);
+    if (AHEAD == 1) {                                // the loads that may stay outstanding go out last
+      gload_b(clamp_sub(j + 1), ib1);
+      gload_a(clamp_sub(j + 2), next3(ia1));
+    } else if (AHEAD == 2) {
+      gload_a(clamp_sub(j + 1), ia1);
+      gload_b(clamp_sub(j + 2), next3(ib1));
+    } else {
+      gload_a(clamp_sub(j + 1), ia1);
+      gload_b(clamp_sub(j + 1), ib1);
+    }
     if (BTR && BMAP) map_rows(kb, clamp_sub(j + 2), rows_b);
     fload_a(1, ia, I0{}, I1{});
     mfmas(0, 0, 0);
@@ -487,17 +498,18 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
     __builtin_amdgcn_sched_barrier(0);
     // own LDS reads of this step done and own loads for the next step landed: with three A stages the four
     // youngest loads (A of the step after next) may still be on their way; then everybody's
-    if (kA3) __builtin_amdgcn_s_waitcnt(0x0074);     // vmcnt(4), lgkmcnt(0)
+    if (AHEAD != 0) __builtin_amdgcn_s_waitcnt(0x0074);   // vmcnt(4), lgkmcnt(0)
     else __builtin_amdgcn_s_waitcnt(0x0070);         // vmcnt(0), lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     tr_wait_a(1);
-    fload_b(0, ib ^ 1, I0{});
+    fload_b(0, ib1, I0{});
     fload_a(0, ia1, I0{}, I0{});
     mfmas(1, 1, 1);
     interleave(kDsA + kDsB, 0);
     __builtin_amdgcn_sched_barrier(0);
     ia = ia1;
+    ib = ib1;
   }
   __builtin_amdgcn_s_waitcnt(0x0070);
   __builtin_amdgcn_s_barrier();

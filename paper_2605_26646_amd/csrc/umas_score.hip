@@ -660,7 +660,8 @@ __device__ __forceinline__ void dh_tile(int tile_m, int tile_n, const uint16_t* 
   kb.n_units = min(32, (d - n0) / 8);
   floatx4 acc[C::MI][C::NI];
   zero_acc<C>(acc);
-  mfma_mainloop_mixed<C, false, true>(ca, KMajor{}, KContig{}, kb, static_cast<int>(Vp), lds, acc);
+  // the third LDS stage goes to W: every group of row tiles streams all of it (twice the bytes of the [rows, V] operand)
+  mfma_mainloop_mixed<C, false, true, false, 2>(ca, KMajor{}, KContig{}, kb, static_cast<int>(Vp), lds, acc);
 #pragma unroll
   for (int bj = 0; bj < C::NI; ++bj) {
     const int j = n0 + acc_col<C>(bj);
