@@ -288,6 +288,7 @@ struct MixedLdsBytes {          // LDS of mfma_mainloop_mixed: three A stages an
 struct KMajor {                 // an operand tile stored K-major
   const char* base;             // byte address of (k-row 0, first entry of the tile)
   int64_t ld_bytes;             // bytes between consecutive k-rows
+  int64_t hi_bytes;             // added once more per 256 k-rows (an operand stored in blocks of 256 rows), else 0
   const int32_t* rowmap;        // with BMAP: k-row k lives in row rowmap[k] of the matrix (ld_bytes apart, from base)
   int k_rows;                   // k-rows that exist; later ones read the last one (the other operand is zero there)
   int n_units;                  // 16-byte units of a k-row that exist from base on (<= 32); later ones read the last one
@@ -295,6 +296,7 @@ struct KMajor {                 // an operand tile stored K-major
 struct KContig {                // an operand tile stored K-contiguous: per-slot byte offsets from a base
   __amdgpu_buffer_rsrc_t rsrc;
   uint32_t off[4];
+  uint32_t hi_bytes;            // added once more per 256 k (an operand stored in blocks of 256 columns), else 0
 };
 
 template <class C, bool ATR, bool BTR, bool BMAP = false, int AHEAD = (BMAP ? 0 : 1)>
@@ -336,7 +338,7 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
                                                  static_cast<uint32_t>(rows[p]) * static_cast<uint32_t>(k.ld_bytes) + ubytes, 0, 0, 0);
     } else {
       const int k0 = min(sub * R::BK, ((k.k_rows - 1) / R::BK) * R::BK);          // first k-row of the (clamped) step
-      const __amdgpu_buffer_rsrc_t r = make_rsrc(k.base + static_cast<int64_t>(k0) * k.ld_bytes);
+      const __amdgpu_buffer_rsrc_t r = make_rsrc(k.base + static_cast<int64_t>(k0) * k.ld_bytes + (k0 >> 8) * k.hi_bytes);
 #pragma unroll
       for (int p = 0; p < 4; ++p)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(r, reinterpret_cast<uint32_t*>(region + (16 * p + 2 * wave) * 512), 16,
@@ -345,7 +347,7 @@ __device__ __forceinline__ void mfma_mainloop_mixed(const KContig& ca, const KMa
     }
   };
   auto gload_kcontig = [&](const KContig& c, int sub, char* region) {
-    const int kbytes = sub * R::BK * 2;
+    const int kbytes = sub * R::BK * 2 + (sub >> 2) * static_cast<int>(c.hi_bytes);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(c.rsrc, reinterpret_cast<uint32_t*>(region + (i * R::ROWS_PER_PASS + wave * 8) * R::ROWB), 16,

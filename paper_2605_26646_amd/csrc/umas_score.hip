@@ -127,6 +127,14 @@ __device__ __forceinline__ void logit_tile(const uint16_t* __restrict__ W, const
 // copy of H that dW reads.  A block of 256 rows in which some logit exceeds its reference by more than kKeepMaxGap
 // (E could overflow) is flagged and gets its dz from the recomputing kernel instead.
 constexpr float kKeepMaxGap = 50.f;
+// The [rows, vocabulary] operand of the backward (E, or dz on the recomputing path) lies in blocks of 256 rows x 256
+// vocabulary entries, 128 KB each, row-major inside, vocabulary blocks of one block row next to each other: what a
+// gradient tile reads per K step is then one run of memory (32 KB of consecutive rows for dW, four steps per block
+// for dH) instead of 256 or 64 pieces a row pitch of 300 KB apart.
+constexpr int64_t kBlkElems = 256 * 256;
+__host__ __device__ __forceinline__ int64_t blk_offset(int64_t row_blk, int64_t voc_blk, int64_t tiles_v) {
+  return (row_blk * tiles_v + voc_blk) * kBlkElems;
+}
 constexpr int kStagePitch = Cfg::WTM * 2 + 16;                                  // one staged row: 128 bf16, 16-byte aligned
 constexpr int kStageBytes = Cfg::WM * Cfg::WN * Cfg::WTN * kStagePitch;         // every wavefront stages its block: 64 rows x 128 vocabulary entries
 constexpr int kPartBytes = (Cfg::WM * Cfg::BN * 3 + Cfg::BN) * 4;
@@ -244,13 +252,13 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
     if (over) keep.flags[(c0 >> 8) + tile_n] = 1;
     // the staged block goes out 16 bytes per lane: one instruction covers 4 rows x 256 contiguous bytes
     const int wn = wave % C::WN;
-    uint16_t* out = keep.E + (n0 + wn * C::WTN) * keep.Vp + m0 + wm * C::WTM + (lane & 15) * 8;
+    uint16_t* out = keep.E + blk_offset(tile_n, tile_m, keep.Vp >> 8) + (wn * C::WTN) * 256 + wm * C::WTM + (lane & 15) * 8;
 #pragma unroll 8
     for (int i = 0; i < C::WTN / 4; ++i) {
       const int row = i * 4 + (lane >> 4);
       const uint4 v = *reinterpret_cast<const uint4*>(stage + row * kStagePitch + (lane & 15) * 16);
       typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-      __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(out + static_cast<int64_t>(row) * keep.Vp));
+      __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(out + row * 256));
     }
   }
   __syncthreads();
@@ -492,13 +500,14 @@ k_label_logit(const uint16_t* __restrict__ H, const uint16_t* __restrict__ W, in
   s = wave_sum(s);
   if (lane == 0) cref[n] = s;
 }
-// Row factor sc[n] = a_n exp(c_n - lse_n) of dz = sc E, and Hs[n - c0, :] = bf16(sc[n] h_n), the operand dW reads.
+// Row factor sc[n] = a_n exp(c_n - lse_n) of dz = sc E, and Hs[n - c0, :] = bf16(sc[n] h_n), the operand dW reads, in
+// column blocks [d / 256][mcp][256].
 // Rows of a flagged block get factor 1: their dz comes complete from the recomputing kernel.
 __global__ void __launch_bounds__(256)
 k_keep_rows(const uint16_t* __restrict__ H, int d, int V, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
             const int32_t* __restrict__ ids, const float* __restrict__ lse_c, const float* __restrict__ a_c,
             const float* __restrict__ cref, const int32_t* __restrict__ flags, float* __restrict__ sc,
-            uint16_t* __restrict__ Hs) {
+            uint16_t* __restrict__ Hs, int64_t mcp) {
   const int lane = threadIdx.x & 63;
   const int64_t m = static_cast<int64_t>(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave;
   if (m >= rows) return;
@@ -509,8 +518,8 @@ k_keep_rows(const uint16_t* __restrict__ H, int d, int V, const int32_t* __restr
   if (!flags[n >> 8]) f = a != 0.f ? a * __expf(cref[n] - lse_c[n]) : 0.f;   // a = 0: invalid id (reference NaN) or no gradient
   if (lane == 0) sc[n] = f;
   const uint4* h = reinterpret_cast<const uint4*>(H + row * d);
-  uint4* o = reinterpret_cast<uint4*>(Hs + m * d);
   for (int k = lane; k < d / 8; k += kWave) {
+    uint4* o = reinterpret_cast<uint4*>(Hs + (static_cast<int64_t>(k >> 5) * mcp + m) * 256);   // column block k / 32 of the row
     float x[8];
     bf16x8_to_f32(h[k], x);
     uint4 v;
@@ -518,7 +527,7 @@ k_keep_rows(const uint16_t* __restrict__ H, int d, int V, const int32_t* __restr
     v.y = pack_bf16x2(x[2] * f, x[3] * f);
     v.z = pack_bf16x2(x[4] * f, x[5] * f);
     v.w = pack_bf16x2(x[6] * f, x[7] * f);
-    o[k] = v;
+    o[k & 31] = v;
   }
 }
 
@@ -580,13 +589,13 @@ __device__ __forceinline__ void dz_tile(int tile_m, int tile_n, const uint16_t* 
   }
   // the staged block goes out 16 bytes per lane: one instruction covers 4 rows x 256 contiguous bytes
   const int wn = wave % C::WN;
-  uint16_t* out = dZ + (n0 + wn * C::WTN) * Vp + m0 + wm * C::WTM + (lane & 15) * 8;
+  uint16_t* out = dZ + blk_offset(tile_n, tile_m, Vp >> 8) + (wn * C::WTN) * 256 + wm * C::WTM + (lane & 15) * 8;
 #pragma unroll 8
   for (int i = 0; i < C::WTN / 4; ++i) {
     const int row = i * 4 + (lane >> 4);
     const uint4 v = *reinterpret_cast<const uint4*>(stage + row * kStagePitch + (lane & 15) * 16);
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(out + static_cast<int64_t>(row) * Vp));
+    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(out + row * 256));
   }
   __syncthreads();                              // the LDS is the next tile's again
 }
@@ -631,15 +640,16 @@ __device__ __forceinline__ void zero_acc(floatx4 (&acc)[C::MI][C::NI]) {
 #pragma unroll
     for (int j = 0; j < C::NI; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 }
-// K-contiguous operand tile: rows row0 .. row0 + 255 of X [n_rows, ld] (rows past the end read the last one)
+// K-contiguous operand tile: block row `row_blk` of the blocked [rows, vocabulary] operand; K runs over the vocabulary,
+// four steps of 64 per block
 template <class C>
-__device__ __forceinline__ KContig kcontig_tile(const uint16_t* X, int64_t ld, int64_t n_rows, int64_t row0) {
+__device__ __forceinline__ KContig blocked_rows_tile(const uint16_t* X, int64_t tiles_v, int64_t row_blk) {
   KContig c;
-  c.rsrc = make_rsrc(X + row0 * ld);
+  c.rsrc = make_rsrc(X + blk_offset(row_blk, 0, tiles_v));
+  c.hi_bytes = static_cast<uint32_t>(kBlkElems * 2 - 4 * 128);        // from the fourth step of a block to the next block
   const uint32_t kofs = ring2_kofs();
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-    c.off[i] = (static_cast<uint32_t>(min(static_cast<int64_t>(ring2_row<C>(i)), n_rows - 1 - row0)) * static_cast<uint32_t>(ld) + kofs) * 2u;
+  for (int i = 0; i < 4; ++i) c.off[i] = (static_cast<uint32_t>(ring2_row<C>(i)) * 256u + kofs) * 2u;
   return c;
 }
 
@@ -651,10 +661,11 @@ __device__ __forceinline__ void dh_tile(int tile_m, int tile_n, const uint16_t* 
   using C = Cfg;
   const int64_t m0 = static_cast<int64_t>(tile_m) * C::BM;
   const int n0 = tile_n * C::BN;
-  const KContig ca = kcontig_tile<C>(dZ, Vp, mcp, m0);
+  const KContig ca = blocked_rows_tile<C>(dZ, Vp >> 8, tile_m);
   KMajor kb;
   kb.base = reinterpret_cast<const char*>(W + n0);
   kb.ld_bytes = static_cast<int64_t>(d) * 2;
+  kb.hi_bytes = 0;
   kb.rowmap = nullptr;
   kb.k_rows = V;                                                     // dz is zero for vocabulary ids past V
   kb.n_units = min(32, (d - n0) / 8);
@@ -680,22 +691,26 @@ __device__ __forceinline__ void dh_tile(int tile_m, int tile_n, const uint16_t* 
       }
   }
 }
-// Hx: the rows of H that go with the rows of dZ: H itself (through rowsel, or from row c0 on), or a compact copy
+// Hx: the rows of H that go with the rows of dZ: H itself (through rowsel, or from row c0 on), or, with hx_blocked, the
+// scaled compact copy, which lies in column blocks [d / 256][mcp][256] so that a tile's k-rows are one run of memory
 __device__ __forceinline__ void dw_tile(int tile_m, int tile_n, const uint16_t* __restrict__ dZ, int64_t mcp, int64_t Vp,
-                                        const uint16_t* __restrict__ Hx, int d, int V, const int32_t* __restrict__ rowmap,
-                                        int64_t rows, float* __restrict__ dW, int accumulate, uint16_t* lds) {
+                                        const uint16_t* __restrict__ Hx, int hx_blocked, int d, int V,
+                                        const int32_t* __restrict__ rowmap, int64_t rows, float* __restrict__ dW,
+                                        int accumulate, uint16_t* lds) {
   using C = Cfg;
   const int64_t m0 = static_cast<int64_t>(tile_m) * C::BM;
   const int n0 = tile_n * C::BN;
-  KMajor ka;                                                         // dZ [mcp, Vp]: k = row of the chunk, entries = vocabulary
-  ka.base = reinterpret_cast<const char*>(dZ + m0);
-  ka.ld_bytes = Vp * 2;
+  KMajor ka;                                                         // blocked dZ: k = row of the chunk, entries = vocabulary
+  ka.base = reinterpret_cast<const char*>(dZ + blk_offset(0, tile_m, Vp >> 8));
+  ka.ld_bytes = 512;
+  ka.hi_bytes = (Vp >> 8) * kBlkElems * 2 - 256 * 512;               // from the last row of a block to the block below
   ka.rowmap = nullptr;
   ka.k_rows = static_cast<int>(mcp);
   ka.n_units = 32;
   KMajor kb;                                                         // rows of H: k = row of the chunk, entries = hidden columns
-  kb.base = reinterpret_cast<const char*>(Hx + n0);
-  kb.ld_bytes = static_cast<int64_t>(d) * 2;
+  kb.base = reinterpret_cast<const char*>(hx_blocked ? Hx + static_cast<int64_t>(tile_n) * mcp * 256 : Hx + n0);
+  kb.ld_bytes = hx_blocked ? 512 : static_cast<int64_t>(d) * 2;
+  kb.hi_bytes = 0;
   kb.rowmap = rowmap;
   kb.k_rows = static_cast<int>(rows);                                // dz is zero for rows past the chunk
   kb.n_units = min(32, (d - n0) / 8);
@@ -723,7 +738,7 @@ __device__ __forceinline__ void dw_tile(int tile_m, int tile_n, const uint16_t* 
 // tiles goes on with dW tiles, and the host gives every XCD the share of dW groups that evens out the sum.
 __global__ void __launch_bounds__(Cfg::T)
 k_gemm_dh_dw(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uint16_t* __restrict__ W,
-             const uint16_t* __restrict__ Hx, const int32_t* __restrict__ h_rowmap, int d, int V, int tiles_r, int tiles_v,
+             const uint16_t* __restrict__ Hx, int hx_blocked, const int32_t* __restrict__ h_rowmap, int d, int V, int tiles_r, int tiles_v,
              int tiles_d, unsigned grid_dh, XcdGroups dw_groups, uint16_t* __restrict__ dH, float* __restrict__ dW,
              int accumulate, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
              const int32_t* __restrict__ ids, const float* __restrict__ g_c, const float* __restrict__ sc) {
@@ -734,7 +749,7 @@ k_gemm_dh_dw(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uin
     dh_tile(tile_m, tile_n, dZ, Vp, mcp, W, d, V, dH, rowsel, c0, rows, ids, g_c, sc, lds);
   } else {
     if (!tile_coords_shared<kGM, kGN>(tiles_v, tiles_d, blockIdx.x - grid_dh, dw_groups, &tile_m, &tile_n)) return;
-    dw_tile(tile_m, tile_n, dZ, mcp, Vp, Hx, d, V, h_rowmap, rows, dW, accumulate, lds);
+    dw_tile(tile_m, tile_n, dZ, mcp, Vp, Hx, hx_blocked, d, V, h_rowmap, rows, dW, accumulate, lds);
   }
 }
 
@@ -847,7 +862,7 @@ struct PpoWs {
 size_t chunk_bytes(int64_t mc, int d, int V, umas_dtype dt) {
   if (dt == UMAS_F32) return align_up(static_cast<size_t>(mc) * V * sizeof(float));
   const int64_t Vp = round_up(V, 256), mcp = round_up(mc, 256);
-  return align_up(static_cast<size_t>(mcp) * Vp * 2) + align_up(static_cast<size_t>(mcp) * d * 2);
+  return align_up(static_cast<size_t>(mcp) * Vp * 2) + align_up(static_cast<size_t>(mcp) * round_up(d, 256) * 2);
 }
 size_t carve_ppo(Carver& c, PpoWs& w, int64_t n_sel, int d, int V, umas_dtype dt, int n_roles) {
   carve_score(c, w.score, n_sel, V, dt, true);
@@ -1096,7 +1111,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
                          n_roles, clip_eps, dual_clip, k_ent, w.score.lse_c, w.g_c, w.a_c, w.kz_c, w.blk_stats);
       UMAS_LAUNCHED("k_ppo_rows");
       hipLaunchKernelGGL(k_keep_rows, dim3(cdiv(rows, 4)), dim3(256), 0, st, Hb, d, V, rowsel, c0, rows, ids, w.score.lse_c,
-                         w.a_c, w.cref, w.flags, w.sc, Hs);
+                         w.a_c, w.cref, w.flags, w.sc, Hs, mcp);
       UMAS_LAUNCHED("k_keep_rows");
       // blocks of rows the scoring pass flagged (a logit far above the row's reference) get dz the long way
       hipLaunchKernelGGL(k_dz_flagged, dim3(kFlaggedGrid), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel, c0, rows,
@@ -1106,7 +1121,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
       const XcdGroups shares = share_dw_groups(tiles_r, tiles_v, tiles_d, Vp, mcp, &max_groups);
       const unsigned grid_dh = tile_grid<kGM, kGN>(tiles_r, tiles_d);
       hipLaunchKernelGGL(k_gemm_dh_dw, dim3(grid_dh + static_cast<unsigned>(max_groups) * kGM * kGN * 8), dim3(Cfg::T), 0, st,
-                         E, Vp, mcp, Wb, Hs, static_cast<const int32_t*>(nullptr), d, V, tiles_r, tiles_v, tiles_d, grid_dh,
+                         E, Vp, mcp, Wb, Hs, 1, static_cast<const int32_t*>(nullptr), d, V, tiles_r, tiles_v, tiles_d, grid_dh,
                          shares, static_cast<uint16_t*>(dH), dW, (accumulate_dW || c0 > 0) ? 1 : 0, rowsel, c0, rows, ids,
                          w.g_c, w.sc);
       UMAS_LAUNCHED("k_gemm_dh_dw");
@@ -1151,7 +1166,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     const XcdGroups shares = share_dw_groups(tiles_r, tiles_v, tiles_d, Vp, mcp, &max_groups);
     const unsigned grid_dh = tile_grid<kGM, kGN>(tiles_r, tiles_d);
     hipLaunchKernelGGL(k_gemm_dh_dw, dim3(grid_dh + static_cast<unsigned>(max_groups) * kGM * kGN * 8), dim3(Cfg::T), 0, st,
-                       dZ, Vp, mcp, Wb, rowsel ? Hb : Hb + c0 * d, rowsel ? rowsel + c0 : static_cast<const int32_t*>(nullptr), d,
+                       dZ, Vp, mcp, Wb, rowsel ? Hb : Hb + c0 * d, 0, rowsel ? rowsel + c0 : static_cast<const int32_t*>(nullptr), d,
                        V, tiles_r, tiles_v, tiles_d, grid_dh, shares, static_cast<uint16_t*>(dH), dW,
                        (accumulate_dW || c0 > 0) ? 1 : 0, rowsel, c0, rows, ids, w.g_c, static_cast<const float*>(nullptr));
     UMAS_LAUNCHED("k_gemm_dh_dw");
