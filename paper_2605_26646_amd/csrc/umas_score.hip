@@ -146,6 +146,7 @@ struct KeepArgs {
   uint16_t* E;         // [mcp, Vp]
   int64_t Vp;
   int32_t* flags;      // per block of 256 selected rows
+  const int32_t* cidx; // per block of 256 selected rows: its place among the chunk's live blocks, -1 for a dead one
 };
 
 template <bool KEEP>
@@ -185,6 +186,9 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
   }
   constexpr float kLog2e = 1.44269504088896341f;
   bool over = false;
+  // a block of rows none of which has a gradient (all advantages 0) keeps nothing: the backward never looks at it
+  const int out_blk = KEEP ? keep.cidx[(c0 >> 8) + tile_n] : -1;
+  const bool keeping = KEEP && out_blk >= 0;
 #pragma unroll
   for (int j = 0; j < C::NI; ++j) {
     const int col = acc_col<C>(j);
@@ -198,7 +202,7 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
     // serves the merge as long as nothing overflows), so the exponentials it sums are the numerators it keeps.
     // A lane whose maximum lies more than kKeepMaxGap above c_n flags the block and falls back to its maximum;
     // rows without a valid id (reference NaN) use the maximum too and flag nothing: their row factor is 0.
-    if (KEEP) {
+    if (keeping) {
       const float c = n < mc ? keep.cref[c0 + n] : 1e30f;   // rows past the chunk: every exponential is 0, E = 0
       const float gap = m - c;
       over |= gap > kKeepMaxGap;
@@ -214,11 +218,11 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
       for (int r = 0; r < 4; ++r) {
         const float z = acc[i][j][r];
         // without a reference from outside: z - m first, exact 0 where a lane holds nothing but vocabulary tail
-        e[r] = KEEP ? __builtin_amdgcn_exp2f(fmaf(z, kLog2e, -m2)) : __builtin_amdgcn_exp2f((z - m) * kLog2e);
+        e[r] = keeping ? __builtin_amdgcn_exp2f(fmaf(z, kLog2e, -m2)) : __builtin_amdgcn_exp2f((z - m) * kLog2e);
         s += e[r];
         t = fmaf(e[r], z, t);
       }
-      if (KEEP) {   // staged in this wavefront's LDS region, stored in full lines below
+      if (keeping) {   // staged in this wavefront's LDS region, stored in full lines below
         const uint32_t p01 = pack_bf16x2(e[0], e[1]), p23 = pack_bf16x2(e[2], e[3]);
         *reinterpret_cast<uint2*>(stage + (j * 16 + (lane & 15)) * kStagePitch + (i * 16 + (lane >> 4) * 4) * 2) =
             make_uint2(p01, p23);
@@ -248,11 +252,11 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
       }
     }
   }
-  if (KEEP) {
+  if (keeping) {
     if (over) keep.flags[(c0 >> 8) + tile_n] = 1;
     // the staged block goes out 16 bytes per lane: one instruction covers 4 rows x 256 contiguous bytes
     const int wn = wave % C::WN;
-    uint16_t* out = keep.E + blk_offset(tile_n, tile_m, keep.Vp >> 8) + (wn * C::WTN) * 256 + wm * C::WTM + (lane & 15) * 8;
+    uint16_t* out = keep.E + blk_offset(out_blk, tile_m, keep.Vp >> 8) + (wn * C::WTN) * 256 + wm * C::WTM + (lane & 15) * 8;
 #pragma unroll 8
     for (int i = 0; i < C::WTN / 4; ++i) {
       const int row = i * 4 + (lane >> 4);
@@ -288,9 +292,10 @@ __global__ void __launch_bounds__(Cfg::T)
 k_score_keep_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
                    const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc, const int32_t* __restrict__ ids,
                    int tiles_m, int tiles_n, float4* __restrict__ partial, int64_t n_pad,
-                   const float* __restrict__ cref, uint16_t* __restrict__ E, int64_t Vp, int32_t* __restrict__ flags) {
+                   const float* __restrict__ cref, uint16_t* __restrict__ E, int64_t Vp, int32_t* __restrict__ flags,
+                   const int32_t* __restrict__ cidx) {
   __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
-  score_tiles<true>(W, H, d, V, rowsel, c0, mc, ids, tiles_m, tiles_n, partial, n_pad, KeepArgs{cref, E, Vp, flags}, lds);
+  score_tiles<true>(W, H, d, V, rowsel, c0, mc, ids, tiles_m, tiles_n, partial, n_pad, KeepArgs{cref, E, Vp, flags, cidx}, lds);
 }
 
 // Merge the per-tile partials of each selected row; compact results and optional scatter.  Eight lanes
@@ -465,6 +470,76 @@ k_ppo_stats(int nblk, int n_roles, float entropy_coef, const double* __restrict_
   }
 }
 
+// ------------------------------------------------------------------ bf16: blocks of rows that have a gradient
+// A selected row whose advantage is 0 has g = 0 and (without an entropy bonus) no gradient at all; group-normalised
+// outcome rewards make whole trajectory groups such rows.  The keeping pass therefore works on the chunk's live blocks
+// of 256 selected rows only: E and the scaled copy of H hold them packed, dH has as many row tiles and dW as many K
+// steps as there are, and everything that depends on their number is worked out on the device.
+struct LiveInfo {
+  int32_t n_live;        // live blocks of the chunk
+  int32_t k_rows;        // rows of the packed operands that exist (the chunk's last block may be partly filled)
+  XcdGroups dw_groups;   // dW tile groups per XCD (see share_dw_groups)
+};
+__global__ void __launch_bounds__(256)
+k_live_flags(int64_t n_sel, const int32_t* __restrict__ rowsel, const float* __restrict__ adv, int32_t* __restrict__ blk_live) {
+  const int64_t n = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  const int live = n < n_sel && adv[rowsel ? rowsel[n] : n] != 0.f;
+  const int any = __syncthreads_or(live);
+  if (threadIdx.x == 0) blk_live[blockIdx.x] = any;
+}
+// Shares of the dW tile groups per XCD for k_gemm_dh_dw: every XCD first works through its dH groups (contiguous
+// ranges, as tile_coords hands them out; a group costs about Vp K-steps per tile), then dW groups (k_len K-steps per
+// tile) are dealt to whichever XCD would finish first, at most max_groups to one XCD (the grid has no more).
+__device__ void share_dw_groups(int tiles_r, int tiles_v, int tiles_d, int64_t Vp, int64_t k_len, int max_groups, XcdGroups* out) {
+  const int64_t groups_dh = static_cast<int64_t>((tiles_r + kGM - 1) / kGM) * ((tiles_d + kGN - 1) / kGN);
+  const int64_t per_xcd = (groups_dh + 7) / 8;
+  int64_t load[8];
+  int cnt[8] = {};
+  for (int x = 0; x < 8; ++x) {
+    int64_t n = groups_dh - x * per_xcd;
+    n = n < 0 ? 0 : (n > per_xcd ? per_xcd : n);
+    load[x] = n * Vp;
+  }
+  const int64_t groups_dw = static_cast<int64_t>((tiles_v + kGM - 1) / kGM) * ((tiles_d + kGN - 1) / kGN);
+  for (int64_t g = 0; g < groups_dw; ++g) {
+    int best = -1;
+    for (int x = 0; x < 8; ++x)
+      if (cnt[x] < max_groups && (best < 0 || load[x] < load[best])) best = x;
+    ++cnt[best];
+    load[best] += k_len;
+  }
+  out->first[0] = 0;
+  for (int x = 0; x < 8; ++x) out->first[x + 1] = out->first[x] + cnt[x];
+}
+inline int max_dw_groups_per_xcd(int tiles_v, int tiles_d) {   // 8 x this many cover every group with room to even out
+  const int64_t groups_dw = static_cast<int64_t>((tiles_v + kGM - 1) / kGM) * ((tiles_d + kGN - 1) / kGN);
+  return static_cast<int>((groups_dw + 7) / 8 + 20);
+}
+// One workgroup per chunk: packs the live blocks (all of them with all_live), blk0 = first block of the chunk.
+__global__ void __launch_bounds__(512)
+k_live_scan(int blk0, int nblk, int64_t rows, int all_live, int tiles_v, int tiles_d, int64_t Vp, int max_groups,
+            const int32_t* __restrict__ blk_live, int32_t* __restrict__ blk_cidx, int32_t* __restrict__ blk_orig,
+            LiveInfo* __restrict__ info) {
+  __shared__ int smem[32];
+  const int t = threadIdx.x;
+  const int live = t < nblk && (all_live || blk_live[blk0 + t]);
+  int total;
+  const int pos = block_excl_scan<int>(live, smem, &total);
+  if (t < nblk) {
+    blk_cidx[blk0 + t] = live ? pos : -1;
+    if (live) blk_orig[blk0 + pos] = t;
+  }
+  __shared__ int s_last_live;
+  if (t == nblk - 1) s_last_live = live;
+  __syncthreads();
+  if (t == 0) {
+    info->n_live = total;
+    const int64_t last_rows = rows - static_cast<int64_t>(nblk - 1) * 256;     // rows of the chunk's last block
+    info->k_rows = static_cast<int32_t>(s_last_live ? static_cast<int64_t>(total - 1) * 256 + last_rows : static_cast<int64_t>(total) * 256);
+    share_dw_groups(total, tiles_v, tiles_d, Vp, static_cast<int64_t>(total) * 256, max_groups, &info->dw_groups);
+  }
+}
+
 // ------------------------------------------------------------------ bf16: row references and row factors of the keeping pass
 __device__ __forceinline__ void bf16x8_to_f32(const uint4 v, float (&o)[8]) {
   o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
@@ -506,20 +581,26 @@ k_label_logit(const uint16_t* __restrict__ H, const uint16_t* __restrict__ W, in
 __global__ void __launch_bounds__(256)
 k_keep_rows(const uint16_t* __restrict__ H, int d, int V, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
             const int32_t* __restrict__ ids, const float* __restrict__ lse_c, const float* __restrict__ a_c,
-            const float* __restrict__ cref, const int32_t* __restrict__ flags, float* __restrict__ sc,
-            uint16_t* __restrict__ Hs, int64_t mcp) {
+            const float* __restrict__ cref, const int32_t* __restrict__ flags, const int32_t* __restrict__ cidx,
+            float* __restrict__ sc, uint16_t* __restrict__ Hs, int64_t mcp) {
   const int lane = threadIdx.x & 63;
   const int64_t m = static_cast<int64_t>(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave;
   if (m >= rows) return;
   const int64_t n = c0 + m;
   const int64_t row = rowsel ? rowsel[n] : n;
   const float a = a_c[n];
+  const int blk = cidx[n >> 8];                              // place of the row's block among the live ones
+  if (blk < 0) {                                             // a dead block: no row of it has a gradient
+    if (lane == 0) sc[n] = 0.f;
+    return;
+  }
+  const int64_t mp = static_cast<int64_t>(blk) * 256 + (m & 255);   // row in the packed operands
   float f = 1.f;
   if (!flags[n >> 8]) f = a != 0.f ? a * __expf(cref[n] - lse_c[n]) : 0.f;   // a = 0: invalid id (reference NaN) or no gradient
   if (lane == 0) sc[n] = f;
   const uint4* h = reinterpret_cast<const uint4*>(H + row * d);
   for (int k = lane; k < d / 8; k += kWave) {
-    uint4* o = reinterpret_cast<uint4*>(Hs + (static_cast<int64_t>(k >> 5) * mcp + m) * 256);   // column block k / 32 of the row
+    uint4* o = reinterpret_cast<uint4*>(Hs + (static_cast<int64_t>(k >> 5) * mcp + mp) * 256);   // column block k / 32 of the row
     float x[8];
     bf16x8_to_f32(h[k], x);
     uint4 v;
@@ -539,7 +620,8 @@ k_keep_rows(const uint16_t* __restrict__ H, int d, int V, const int32_t* __restr
 __device__ __forceinline__ void dz_tile(int tile_m, int tile_n, const uint16_t* __restrict__ W, const uint16_t* __restrict__ H,
                                         int d, int V, const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc,
                                         const float* __restrict__ lse_c, const float* __restrict__ a_c,
-                                        const float* __restrict__ kz_c, uint16_t* __restrict__ dZ, int64_t Vp, uint16_t* lds) {
+                                        const float* __restrict__ kz_c, uint16_t* __restrict__ dZ, int64_t Vp, int out_blk,
+                                        uint16_t* lds) {
   using C = Cfg;
   const int m0 = tile_m * C::BM;
   const int64_t n0 = static_cast<int64_t>(tile_n) * C::BN;   // chunk-relative
@@ -589,7 +671,7 @@ __device__ __forceinline__ void dz_tile(int tile_m, int tile_n, const uint16_t* 
   }
   // the staged block goes out 16 bytes per lane: one instruction covers 4 rows x 256 contiguous bytes
   const int wn = wave % C::WN;
-  uint16_t* out = dZ + blk_offset(tile_n, tile_m, Vp >> 8) + (wn * C::WTN) * 256 + wm * C::WTM + (lane & 15) * 8;
+  uint16_t* out = dZ + blk_offset(out_blk, tile_m, Vp >> 8) + (wn * C::WTN) * 256 + wm * C::WTM + (lane & 15) * 8;
 #pragma unroll 8
   for (int i = 0; i < C::WTN / 4; ++i) {
     const int row = i * 4 + (lane >> 4);
@@ -608,7 +690,7 @@ k_dz_tiles(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d
   for (int it = 0; it < kTilesPerWg; ++it) {     // a workgroup walks the same place of kTilesPerWg consecutive tile groups
     int tile_m, tile_n;
     if (!tile_coords<kGM, kGN>(tiles_m, tiles_n, &tile_m, &tile_n, it, kTilesPerWg)) continue;
-    dz_tile(tile_m, tile_n, W, H, d, V, rowsel, c0, mc, lse_c, a_c, kz_c, dZ, Vp, lds);
+    dz_tile(tile_m, tile_n, W, H, d, V, rowsel, c0, mc, lse_c, a_c, kz_c, dZ, Vp, tile_n, lds);
   }
 }
 // The same tiles for the blocks of 256 rows that the keeping scoring pass has flagged, and only those: a fixed,
@@ -618,12 +700,14 @@ __global__ void __launch_bounds__(Cfg::T)
 k_dz_flagged(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int d, int V,
              const int32_t* __restrict__ rowsel, int64_t c0, int64_t mc,
              const float* __restrict__ lse_c, const float* __restrict__ a_c, const float* __restrict__ kz_c,
-             int tiles_m, int tiles_n, uint16_t* __restrict__ dZ, int64_t Vp, const int32_t* __restrict__ flags) {
+             int tiles_m, int tiles_n, uint16_t* __restrict__ dZ, int64_t Vp, const int32_t* __restrict__ flags,
+             const int32_t* __restrict__ cidx) {
   __shared__ __attribute__((aligned(16))) uint16_t lds[kLogitLds / 2];
   for (int tile_n = 0; tile_n < tiles_n; ++tile_n) {
-    if (!flags[(c0 >> 8) + tile_n]) continue;                       // the same for every thread of the grid
+    const int out_blk = cidx[(c0 >> 8) + tile_n];
+    if (!flags[(c0 >> 8) + tile_n] || out_blk < 0) continue;        // the same for every thread of the grid
     for (int tile_m = blockIdx.x; tile_m < tiles_m; tile_m += gridDim.x)
-      dz_tile(tile_m, tile_n, W, H, d, V, rowsel, c0, mc, lse_c, a_c, kz_c, dZ, Vp, lds);
+      dz_tile(tile_m, tile_n, W, H, d, V, rowsel, c0, mc, lse_c, a_c, kz_c, dZ, Vp, out_blk, lds);
   }
 }
 
@@ -653,13 +737,14 @@ __device__ __forceinline__ KContig blocked_rows_tile(const uint16_t* X, int64_t 
   return c;
 }
 
-__device__ __forceinline__ void dh_tile(int tile_m, int tile_n, const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp,
+// tile_m counts the chunk's live blocks of rows; orig_blk is the block's place in the chunk
+__device__ __forceinline__ void dh_tile(int tile_m, int orig_blk, int tile_n, const uint16_t* __restrict__ dZ, int64_t Vp,
                                         const uint16_t* __restrict__ W, int d, int V, uint16_t* __restrict__ dH,
                                         const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
                                         const int32_t* __restrict__ ids, const float* __restrict__ g_c,
                                         const float* __restrict__ sc, uint16_t* lds) {
   using C = Cfg;
-  const int64_t m0 = static_cast<int64_t>(tile_m) * C::BM;
+  const int64_t m0 = static_cast<int64_t>(orig_blk) * C::BM;
   const int n0 = tile_n * C::BN;
   const KContig ca = blocked_rows_tile<C>(dZ, Vp >> 8, tile_m);
   KMajor kb;
@@ -693,9 +778,10 @@ __device__ __forceinline__ void dh_tile(int tile_m, int tile_n, const uint16_t* 
 }
 // Hx: the rows of H that go with the rows of dZ: H itself (through rowsel, or from row c0 on), or, with hx_blocked, the
 // scaled compact copy, which lies in column blocks [d / 256][mcp][256] so that a tile's k-rows are one run of memory
+// k_len: rows of the packed [rows, V] operand (a multiple of 256, 0 when no block is live); rows: those that exist
 __device__ __forceinline__ void dw_tile(int tile_m, int tile_n, const uint16_t* __restrict__ dZ, int64_t mcp, int64_t Vp,
                                         const uint16_t* __restrict__ Hx, int hx_blocked, int d, int V,
-                                        const int32_t* __restrict__ rowmap, int64_t rows, float* __restrict__ dW,
+                                        const int32_t* __restrict__ rowmap, int k_len, int rows, float* __restrict__ dW,
                                         int accumulate, uint16_t* lds) {
   using C = Cfg;
   const int64_t m0 = static_cast<int64_t>(tile_m) * C::BM;
@@ -705,19 +791,21 @@ __device__ __forceinline__ void dw_tile(int tile_m, int tile_n, const uint16_t* 
   ka.ld_bytes = 512;
   ka.hi_bytes = (Vp >> 8) * kBlkElems * 2 - 256 * 512;               // from the last row of a block to the block below
   ka.rowmap = nullptr;
-  ka.k_rows = static_cast<int>(mcp);
+  ka.k_rows = k_len;
   ka.n_units = 32;
   KMajor kb;                                                         // rows of H: k = row of the chunk, entries = hidden columns
   kb.base = reinterpret_cast<const char*>(hx_blocked ? Hx + static_cast<int64_t>(tile_n) * mcp * 256 : Hx + n0);
   kb.ld_bytes = hx_blocked ? 512 : static_cast<int64_t>(d) * 2;
   kb.hi_bytes = 0;
   kb.rowmap = rowmap;
-  kb.k_rows = static_cast<int>(rows);                                // dz is zero for rows past the chunk
+  kb.k_rows = rows;                                                  // dz is zero for rows past the chunk
   kb.n_units = min(32, (d - n0) / 8);
   floatx4 acc[C::MI][C::NI];
   zero_acc<C>(acc);
-  if (rowmap) mfma_mainloop_mixed<C, true, true, true>(KContig{}, ka, KContig{}, kb, static_cast<int>(mcp), lds, acc);
-  else mfma_mainloop_mixed<C, true, true, false>(KContig{}, ka, KContig{}, kb, static_cast<int>(mcp), lds, acc);
+  if (k_len > 0) {
+    if (rowmap) mfma_mainloop_mixed<C, true, true, true>(KContig{}, ka, KContig{}, kb, k_len, lds, acc);
+    else mfma_mainloop_mixed<C, true, true, false>(KContig{}, ka, KContig{}, kb, k_len, lds, acc);
+  }
 #pragma unroll
   for (int bj = 0; bj < C::NI; ++bj) {
     const int j = n0 + acc_col<C>(bj);
@@ -738,18 +826,20 @@ __device__ __forceinline__ void dw_tile(int tile_m, int tile_n, const uint16_t* 
 // tiles goes on with dW tiles, and the host gives every XCD the share of dW groups that evens out the sum.
 __global__ void __launch_bounds__(Cfg::T)
 k_gemm_dh_dw(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uint16_t* __restrict__ W,
-             const uint16_t* __restrict__ Hx, int hx_blocked, const int32_t* __restrict__ h_rowmap, int d, int V, int tiles_r, int tiles_v,
-             int tiles_d, unsigned grid_dh, XcdGroups dw_groups, uint16_t* __restrict__ dH, float* __restrict__ dW,
-             int accumulate, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
-             const int32_t* __restrict__ ids, const float* __restrict__ g_c, const float* __restrict__ sc) {
+             const uint16_t* __restrict__ Hx, int hx_blocked, const int32_t* __restrict__ h_rowmap, int d, int V, int tiles_v,
+             int tiles_d, unsigned grid_dh, const LiveInfo* __restrict__ info, const int32_t* __restrict__ blk_orig,
+             uint16_t* __restrict__ dH, float* __restrict__ dW, int accumulate, const int32_t* __restrict__ rowsel,
+             int64_t c0, int64_t rows, const int32_t* __restrict__ ids, const float* __restrict__ g_c,
+             const float* __restrict__ sc) {
   __shared__ __attribute__((aligned(16))) uint16_t lds[MixedLdsBytes<Cfg>::value / 2];
+  const int n_live = info->n_live;                     // live blocks of rows: dH row tiles, dW K blocks
   int tile_m, tile_n;
   if (blockIdx.x < grid_dh) {
-    if (!tile_coords<kGM, kGN>(tiles_r, tiles_d, &tile_m, &tile_n)) return;
-    dh_tile(tile_m, tile_n, dZ, Vp, mcp, W, d, V, dH, rowsel, c0, rows, ids, g_c, sc, lds);
+    if (!tile_coords<kGM, kGN>(n_live, tiles_d, &tile_m, &tile_n)) return;
+    dh_tile(tile_m, blk_orig[(c0 >> 8) + tile_m], tile_n, dZ, Vp, W, d, V, dH, rowsel, c0, rows, ids, g_c, sc, lds);
   } else {
-    if (!tile_coords_shared<kGM, kGN>(tiles_v, tiles_d, blockIdx.x - grid_dh, dw_groups, &tile_m, &tile_n)) return;
-    dw_tile(tile_m, tile_n, dZ, mcp, Vp, Hx, hx_blocked, d, V, h_rowmap, rows, dW, accumulate, lds);
+    if (!tile_coords_shared<kGM, kGN>(tiles_v, tiles_d, blockIdx.x - grid_dh, info->dw_groups, &tile_m, &tile_n)) return;
+    dw_tile(tile_m, tile_n, dZ, mcp, Vp, Hx, hx_blocked, d, V, h_rowmap, n_live * 256, info->k_rows, dW, accumulate, lds);
   }
 }
 
@@ -854,6 +944,10 @@ struct PpoWs {
   float* cref;       // keeping pass: per selected row, the reference of E and the row factor of dz = sc E
   float* sc;
   int32_t* flags;    // keeping pass: blocks of 256 selected rows whose dz must be recomputed
+  int32_t* blk_live; // per block of 256 selected rows: some row has a gradient
+  int32_t* blk_cidx; // its place among the live blocks of its chunk, -1 for a dead one
+  int32_t* blk_orig; // per chunk: live block -> block of the chunk
+  LiveInfo* live;    // of the chunk in work
   double* blk_stats;
   char* chunk;       // rest of the workspace: dZ (or E) [mcp, Vp], then the scaled copy of the chunk's rows of H
   size_t fixed_bytes;
@@ -873,6 +967,10 @@ size_t carve_ppo(Carver& c, PpoWs& w, int64_t n_sel, int d, int V, umas_dtype dt
   w.cref = c.take<float>(n_pad);
   w.sc = c.take<float>(n_pad);
   w.flags = c.take<int32_t>(static_cast<size_t>(cdiv(n_pad, kRowBlock)));
+  w.blk_live = c.take<int32_t>(static_cast<size_t>(cdiv(n_pad, kRowBlock)));
+  w.blk_cidx = c.take<int32_t>(static_cast<size_t>(cdiv(n_pad, kRowBlock)));
+  w.blk_orig = c.take<int32_t>(static_cast<size_t>(cdiv(n_pad, kRowBlock)));
+  w.live = c.take<LiveInfo>(1);
   w.blk_stats = c.take<double>(static_cast<size_t>(cdiv(n_pad, kRowBlock)) * (1 + n_roles) * kStat);
   w.chunk = c.base ? c.base + c.off : nullptr;
   w.fixed_bytes = c.off;
@@ -903,37 +1001,6 @@ umas_status check_ws(void* ws, size_t have, size_t need) {
   UMAS_REQUIRE(ws && reinterpret_cast<uintptr_t>(ws) % kAlign == 0 && have >= need, UMAS_EWORKSPACE,
                "workspace must be 256-byte aligned and hold %zu bytes (got %zu)", need, have);
   return UMAS_OK;
-}
-
-// Shares of the dW tile groups per XCD for k_gemm_dh_dw: every XCD first works through its dH groups (contiguous
-// ranges, as tile_coords hands them out; a group costs about Vp K-steps per tile), then dW groups (mcp K-steps per
-// tile) are dealt to whichever XCD would finish first.
-XcdGroups share_dw_groups(int tiles_r, int tiles_v, int tiles_d, int64_t Vp, int64_t mcp, int* max_groups) {
-  const int64_t groups_dh = static_cast<int64_t>((tiles_r + kGM - 1) / kGM) * ((tiles_d + kGN - 1) / kGN);
-  const int64_t per_xcd = (groups_dh + 7) / 8;
-  int64_t load[8];
-  int cnt[8] = {};
-  for (int x = 0; x < 8; ++x) {
-    int64_t n = groups_dh - x * per_xcd;
-    n = n < 0 ? 0 : (n > per_xcd ? per_xcd : n);
-    load[x] = n * Vp;
-  }
-  const int64_t groups_dw = static_cast<int64_t>((tiles_v + kGM - 1) / kGM) * ((tiles_d + kGN - 1) / kGN);
-  for (int64_t g = 0; g < groups_dw; ++g) {
-    int best = 0;
-    for (int x = 1; x < 8; ++x)
-      if (load[x] < load[best]) best = x;
-    ++cnt[best];
-    load[best] += mcp;
-  }
-  XcdGroups out;
-  out.first[0] = 0;
-  *max_groups = 0;
-  for (int x = 0; x < 8; ++x) {
-    out.first[x + 1] = out.first[x] + cnt[x];
-    if (cnt[x] > *max_groups) *max_groups = cnt[x];
-  }
-  return out;
 }
 
 // Forward scoring of the selected rows into compact arrays and/or scattered outputs.
@@ -1050,10 +1117,11 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
   PpoWs w;
   carve_ppo(c, w, n_sel, d, V, dtype, n_roles);
 
-  if (rowsel && n_rows > 0) {
-    if (logp_new) UMAS_HIP(fill_bytes_zero(logp_new, n_rows * sizeof(float), st));
-    UMAS_HIP(fill_bytes_zero(dH, static_cast<size_t>(n_rows) * d * esz, st));
-  }
+  // rows that are not selected, and (bf16 without an entropy bonus) selected rows in blocks without any gradient,
+  // are not visited by the backward
+  const bool skips_dead_blocks = dtype == UMAS_BF16 && entropy_coef == 0.f;
+  if (rowsel && n_rows > 0 && logp_new) UMAS_HIP(fill_bytes_zero(logp_new, n_rows * sizeof(float), st));
+  if ((rowsel || skips_dead_blocks) && n_rows > 0) UMAS_HIP(fill_bytes_zero(dH, static_cast<size_t>(n_rows) * d * esz, st));
   if (!accumulate_dW && n_sel == 0) UMAS_HIP(fill_bytes_zero(dW, static_cast<size_t>(V) * d * sizeof(float), st));
 
   // chunks of selected rows sized to the workspace
@@ -1091,16 +1159,23 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     hipLaunchKernelGGL(k_label_logit, dim3(cdiv(n_sel, 4)), dim3(256), 0, st, Hb, Wb, d, V, rowsel, n_sel, ids, w.cref);
     UMAS_LAUNCHED("k_label_logit");
     UMAS_HIP(fill_bytes_zero(w.flags, static_cast<size_t>(nblk) * sizeof(int32_t), st));
+    hipLaunchKernelGGL(k_live_flags, dim3(nblk), dim3(256), 0, st, n_sel, rowsel, adv, w.blk_live);
+    UMAS_LAUNCHED("k_live_flags");
     const int64_t n_pad = round_up(n_sel, Cfg::BN);
     const int tiles_v = static_cast<int>(Vp / 256), tiles_d = (d + 255) / 256;
+    const int max_groups = max_dw_groups_per_xcd(tiles_v, tiles_d);
     for (int64_t c0 = 0; c0 < n_sel; c0 += mc) {
       const int64_t rows = n_sel - c0 < mc ? n_sel - c0 : mc;
       const int64_t mcp = round_up(rows, 256);
       const int tiles_r = static_cast<int>(mcp / 256);
       uint16_t* E = reinterpret_cast<uint16_t*>(w.chunk);
       uint16_t* Hs = reinterpret_cast<uint16_t*>(w.chunk + align_up(static_cast<size_t>(mcp) * Vp * 2));
+      hipLaunchKernelGGL(k_live_scan, dim3(1), dim3(512), 0, st, static_cast<int>(c0 >> 8), tiles_r, rows, 0, tiles_v, tiles_d, Vp,
+                         max_groups, w.blk_live, w.blk_cidx, w.blk_orig, w.live);
+      UMAS_LAUNCHED("k_live_scan");
       hipLaunchKernelGGL(k_score_keep_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r, kTilesPerWg)), dim3(Cfg::T), 0, st,
-                         Wb, Hb, d, V, rowsel, c0, rows, ids, tiles_v, tiles_r, w.score.partial, n_pad, w.cref, E, Vp, w.flags);
+                         Wb, Hb, d, V, rowsel, c0, rows, ids, tiles_v, tiles_r, w.score.partial, n_pad, w.cref, E, Vp, w.flags,
+                         w.blk_cidx);
       UMAS_LAUNCHED("k_score_keep_tiles");
       hipLaunchKernelGGL(k_score_finalize, dim3(cdiv(rows, 32)), dim3(256), 0, st, w.score.partial, tiles_v, n_pad, c0,
                          c0 + rows, w.cref, rowsel, ids, V, w.score.logp_c, w.score.lse_c, w.score.ent_c, logp_new,
@@ -1111,19 +1186,17 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
                          n_roles, clip_eps, dual_clip, k_ent, w.score.lse_c, w.g_c, w.a_c, w.kz_c, w.blk_stats);
       UMAS_LAUNCHED("k_ppo_rows");
       hipLaunchKernelGGL(k_keep_rows, dim3(cdiv(rows, 4)), dim3(256), 0, st, Hb, d, V, rowsel, c0, rows, ids, w.score.lse_c,
-                         w.a_c, w.cref, w.flags, w.sc, Hs, mcp);
+                         w.a_c, w.cref, w.flags, w.blk_cidx, w.sc, Hs, mcp);
       UMAS_LAUNCHED("k_keep_rows");
       // blocks of rows the scoring pass flagged (a logit far above the row's reference) get dz the long way
       hipLaunchKernelGGL(k_dz_flagged, dim3(kFlaggedGrid), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel, c0, rows,
-                         w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, E, Vp, w.flags);
+                         w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, E, Vp, w.flags, w.blk_cidx);
       UMAS_LAUNCHED("k_dz_flagged");
-      int max_groups = 0;
-      const XcdGroups shares = share_dw_groups(tiles_r, tiles_v, tiles_d, Vp, mcp, &max_groups);
       const unsigned grid_dh = tile_grid<kGM, kGN>(tiles_r, tiles_d);
       hipLaunchKernelGGL(k_gemm_dh_dw, dim3(grid_dh + static_cast<unsigned>(max_groups) * kGM * kGN * 8), dim3(Cfg::T), 0, st,
-                         E, Vp, mcp, Wb, Hs, 1, static_cast<const int32_t*>(nullptr), d, V, tiles_r, tiles_v, tiles_d, grid_dh,
-                         shares, static_cast<uint16_t*>(dH), dW, (accumulate_dW || c0 > 0) ? 1 : 0, rowsel, c0, rows, ids,
-                         w.g_c, w.sc);
+                         E, Vp, mcp, Wb, Hs, 1, static_cast<const int32_t*>(nullptr), d, V, tiles_v, tiles_d, grid_dh,
+                         w.live, w.blk_orig, static_cast<uint16_t*>(dH), dW, (accumulate_dW || c0 > 0) ? 1 : 0, rowsel, c0,
+                         rows, ids, w.g_c, w.sc);
       UMAS_LAUNCHED("k_gemm_dh_dw");
     }
   }
@@ -1162,12 +1235,15 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     hipLaunchKernelGGL(k_dz_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r, kTilesPerWg)), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel,
                        c0, rows, w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, dZ, Vp);
     UMAS_LAUNCHED("k_dz_tiles");
-    int max_groups = 0;
-    const XcdGroups shares = share_dw_groups(tiles_r, tiles_v, tiles_d, Vp, mcp, &max_groups);
+    // with an entropy bonus every row has a gradient: all blocks are live
+    const int max_groups = max_dw_groups_per_xcd(tiles_v, tiles_d);
+    hipLaunchKernelGGL(k_live_scan, dim3(1), dim3(512), 0, st, static_cast<int>(c0 >> 8), tiles_r, rows, 1, tiles_v, tiles_d, Vp,
+                       max_groups, w.blk_live, w.blk_cidx, w.blk_orig, w.live);
+    UMAS_LAUNCHED("k_live_scan");
     const unsigned grid_dh = tile_grid<kGM, kGN>(tiles_r, tiles_d);
     hipLaunchKernelGGL(k_gemm_dh_dw, dim3(grid_dh + static_cast<unsigned>(max_groups) * kGM * kGN * 8), dim3(Cfg::T), 0, st,
                        dZ, Vp, mcp, Wb, rowsel ? Hb : Hb + c0 * d, 0, rowsel ? rowsel + c0 : static_cast<const int32_t*>(nullptr), d,
-                       V, tiles_r, tiles_v, tiles_d, grid_dh, shares, static_cast<uint16_t*>(dH), dW,
+                       V, tiles_v, tiles_d, grid_dh, w.live, w.blk_orig, static_cast<uint16_t*>(dH), dW,
                        (accumulate_dW || c0 > 0) ? 1 : 0, rowsel, c0, rows, ids, w.g_c, static_cast<const float*>(nullptr));
     UMAS_LAUNCHED("k_gemm_dh_dw");
   }

@@ -201,6 +201,44 @@ def test_rows_with_wide_logits_take_the_recomputing_path():
         P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW")
 
 
+def test_blocks_of_rows_without_gradient_are_left_out():
+    """Rows with advantage 0 have no gradient.  Without an entropy bonus the backward packs the blocks of 256
+    selected rows that have one and works on those alone: a dead first block, a live block with dead rows in it, a
+    dead block in the middle of a chunked run, and a batch without any gradient at all must all match the oracle."""
+    w = wl.make_workload(1, n_traj=8, tokens_per_turn=40, models=[(64, 700, "bf16")])
+    t = w.model_tensors(0)
+    n = len(t["ids"])
+    assert n == 960
+    rows = np.arange(n, dtype=np.int32)
+    logp_o, lse_o, ent_o = orc.score(t["H"], t["W"], t["ids"], rows)
+    logp_old = (logp_o + t["noise"]).astype(np.float32)
+    H, W, ids = P.to_dev(t["H"], torch.bfloat16), P.to_dev(t["W"], torch.bfloat16), P.to_dev(t["ids"])
+    small = umas.ppo_workspace_bytes(n, 64, 700, torch.bfloat16, 0, minimum=True)
+    base = np.random.default_rng(6).normal(size=n).astype(np.float32)
+    cases = {"first block dead, last block half dead": [(0, 256), (800, 960)],
+             "middle blocks dead": [(256, 768)],
+             "no gradient anywhere": [(0, n)]}
+    for name, dead in cases.items():
+        adv = base.copy()
+        for a, e in dead:
+            adv[a:e] = 0.0
+        st_o, g_o = orc.ppo_loss(logp_o, logp_old, adv, ent_o, rows, np.zeros(n, np.int32), 0, 0.2)
+        dH_o, dW_o = orc.lm_head_backward(t["H"], t["W"], t["ids"], lse_o, g_o, rows)
+        for ws_bytes in (None, small):
+            ws = None if ws_bytes is None else torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+            stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(H, W, ids, None, P.to_dev(logp_old), P.to_dev(adv), None, 0,
+                                                                0.2, workspace=ws)
+            sg = umas.read_stats(stats)
+            assert np.abs(logp_new.cpu().numpy() - logp_o).max() <= 2e-2, name
+            assert abs(float(sg["loss"][0]) - st_o[0, 0]) <= 1e-2 * max(abs(st_o[0, 0]), 1e-3), name
+            assert abs(float(sg["entropy_mean"][0]) - st_o[0, 2]) <= 2e-2, name
+            dH_g = dH.float().cpu().numpy()
+            for a, e in dead:
+                assert not dH_g[a:e].any(), name
+            P.close(dH_g, dH_o, 1e-2, "dH, " + name)
+            P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW, " + name)
+
+
 def test_accumulate_dw_adds_to_existing_gradient():
     w = wl.make_workload(1, n_traj=2, tokens_per_turn=40, models=[(64, 300, "bf16")])
     t = w.model_tensors(0)
