@@ -258,34 +258,63 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     loss = float(umas.read_stats(stats)["loss"][0])
 
+    # Rows whose advantage is 0 have no gradient; the backward packs the blocks of 256 selected rows that have one
+    # and does no work for the others (group-normalised outcome rewards zero out whole trajectory groups).  The
+    # flop counts below follow that: scoring covers every selected row, dH and dW the rows they work on.
+    st0 = umas.umas_assign_token_rewards(**kw)
+    adv0, _ = umas.umas_advantages(st0, None, w.gamma, w.lam, w.gamma_turn, w.seg_mode)
+    nz = (adv0[st0.rowsel[:n_sel].long()] != 0).cpu().numpy()
+    rows_with_gradient = int(nz.sum())
+    rows_in_live_blocks = int(sum(min(256, n_sel - i) for i in range(0, n_sel, 256) if nz[i:i + 256].any()))
+
+    # the same update with every row given a gradient (advantage 0 replaced by a small number), for comparison
+    adv_all = torch.where(adv0 == 0, torch.full_like(adv0, 1e-3), adv0)
+
+    def update_ms(a):
+        for timed in (False, True):
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(3 if timed else 2):
+                umas.umas_ppo_loss_fwd_bwd(H, W, ids, st0.rowsel[:n_sel], logp_old, a, st0.tok_role, w.n_roles,
+                                           w.clip_eps, dW=dW, dH=dH, logp_new=logp_new, stats=stats, workspace=ws)
+            torch.cuda.synchronize()
+        return (time.perf_counter() - t1) * 1e3 / 3
+    update_workload_ms, update_all_live_ms = update_ms(adv0), update_ms(adv_all)
+
     # dominant kernel: the one with the largest summed time; a vocabulary-sized GEMM does 2*V*d flop per row
     per_launch = {k: v[0] / v[1] for k, v in prof.items()}
     per_step = {k: v[0] / args.steps for k, v in prof.items()}
     dom = max(per_step, key=per_step.get)
     launches_per_step = prof[dom][1] / args.steps
-    rows_per_launch = n_sel / launches_per_step
     passes = {"k_gemm_dh_dw": 2}          # GEMMs of 2*V*d flop per row inside one launch
+    rows_of = {"k_gemm_dh_dw": rows_in_live_blocks}          # rows a kernel works on per step (default: all selected rows)
+    rows_per_launch = rows_of.get(dom, n_sel) / launches_per_step
     flop_per_launch = 2.0 * spec.V * spec.d * rows_per_launch * passes.get(dom, 1)
     achieved = flop_per_launch / (per_launch[dom] * 1e-3) / 1e12
-    algorithmic = 6.0 * spec.V * spec.d * n_sel
-    # every vocabulary-sized GEMM kernel that ran covers all scored rows once per step (2*V*d flop per row)
-    n_gemms = sum(passes.get(k, 1) for k in ("k_score_tiles", "k_score_keep_tiles", "k_dz_tiles", "k_gemm_dh_dw")
-                  if k in per_step)
-    executed = 2.0 * spec.V * spec.d * n_sel * n_gemms
+    algorithmic = 2.0 * spec.V * spec.d * (n_sel + 2 * rows_with_gradient)
+    gemms = [k for k in ("k_score_tiles", "k_score_keep_tiles", "k_dz_tiles", "k_gemm_dh_dw") if k in per_step]
+    n_gemms = sum(passes.get(k, 1) for k in gemms)
+    executed = 2.0 * spec.V * spec.d * sum(passes.get(k, 1) * rows_of.get(k, n_sel) for k in gemms)
     out = {
         "metric": "scored tokens/sec, PPO loss fwd+bwd (3B-shape, V=151936) + % bf16 MFMA peak",
         "value": n_sel / (ms_per_step * 1e-3), "unit": "scored tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "cfg1 Qwen2.5-3B-shaped pipeline: d=2048 V=151936, 64 traj x 3 roles x 256 tokens",
-                   "tokens": w.n_tokens, "scored_tokens": n_sel, "step": "assign_token_rewards + advantages + ppo_loss_fwd_bwd"},
+                   "tokens": w.n_tokens, "scored_tokens": n_sel, "scored_tokens_with_gradient": rows_with_gradient,
+                   "rows_in_blocks_with_gradient": rows_in_live_blocks,
+                   "step": "assign_token_rewards + advantages + ppo_loss_fwd_bwd"},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": stored_traffic(dom),
                      "flop_per_launch": flop_per_launch, "ms_per_launch": per_launch[dom]},
+        # algorithmic: 2*V*d per scored row for the logits + 4*V*d per row that has a gradient; executed: what the
+        # kernels did (whole blocks of 256 rows); nominal: 6*V*d for every scored row, gradient or not
         "whole_step": {"algorithmic_tflops": algorithmic / (ms_per_step * 1e-3) / 1e12,
-                       "frac_of_bf16_peak_algorithmic_6Vd": algorithmic / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                       "frac_of_bf16_peak_algorithmic": algorithmic / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                        "executed_gemm_passes": n_gemms,
-                       "frac_of_bf16_peak_executed": executed / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+                       "frac_of_bf16_peak_executed": executed / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                       "frac_of_bf16_peak_nominal_6Vd_all_rows": 6.0 * spec.V * spec.d * n_sel / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+        "update_call_ms": {"workload": update_workload_ms, "every_row_given_a_gradient": update_all_live_ms},
         "kernels_ms_per_step": per_step,
         "policy_logprobs_ms": logprobs_ms,
         "loss": loss,

@@ -489,7 +489,8 @@ k_live_flags(int64_t n_sel, const int32_t* __restrict__ rowsel, const float* __r
 }
 // Shares of the dW tile groups per XCD for k_gemm_dh_dw: every XCD first works through its dH groups (contiguous
 // ranges, as tile_coords hands them out; a group costs about Vp K-steps per tile), then dW groups (k_len K-steps per
-// tile) are dealt to whichever XCD would finish first, at most max_groups to one XCD (the grid has no more).
+// tile) go to the XCDs so that all finish as evenly as whole groups allow, at most max_groups to one XCD (the grid has
+// no more; 8 max_groups cover all groups).
 __device__ void share_dw_groups(int tiles_r, int tiles_v, int tiles_d, int64_t Vp, int64_t k_len, int max_groups, XcdGroups* out) {
   const int64_t groups_dh = static_cast<int64_t>((tiles_r + kGM - 1) / kGM) * ((tiles_d + kGN - 1) / kGN);
   const int64_t per_xcd = (groups_dh + 7) / 8;
@@ -501,12 +502,33 @@ __device__ void share_dw_groups(int tiles_r, int tiles_v, int tiles_d, int64_t V
     load[x] = n * Vp;
   }
   const int64_t groups_dw = static_cast<int64_t>((tiles_v + kGM - 1) / kGM) * ((tiles_d + kGN - 1) / kGN);
-  for (int64_t g = 0; g < groups_dw; ++g) {
-    int best = -1;
-    for (int x = 0; x < 8; ++x)
-      if (cnt[x] < max_groups && (best < 0 || load[x] < load[best])) best = x;
-    ++cnt[best];
-    load[best] += k_len;
+  if (k_len <= 0) {                                    // nothing to even out
+    for (int x = 0; x < 8; ++x) cnt[x] = static_cast<int>(groups_dw / 8 + (x < groups_dw % 8 ? 1 : 0));
+  } else {
+    // the lowest level T up to which the XCDs can be filled with whole groups so that all groups are placed ...
+    auto take = [&](int x, int64_t T) {
+      // (a double quotient: the operands stay far below 2^53 and 64-bit integer division is slow here)
+      const int64_t n = T > load[x] ? static_cast<int64_t>(static_cast<double>(T - load[x]) / static_cast<double>(k_len)) : 0;
+      return static_cast<int>(n < max_groups ? n : max_groups);
+    };
+    int64_t lo = load[0], hi = load[0];
+    for (int x = 1; x < 8; ++x) { lo = load[x] < lo ? load[x] : lo; hi = load[x] > hi ? load[x] : hi; }
+    hi += groups_dw * k_len;
+    while (lo < hi) {
+      const int64_t mid = lo + (hi - lo) / 2;
+      int64_t sum = 0;
+      for (int x = 0; x < 8; ++x) sum += take(x, mid);
+      if (sum >= groups_dw) hi = mid; else lo = mid + 1;
+    }
+    int64_t total = 0;
+    for (int x = 0; x < 8; ++x) { cnt[x] = take(x, lo); total += cnt[x]; }
+    // ... and the few groups too many at that level come off the XCDs that would finish last
+    for (; total > groups_dw; --total) {
+      int worst = -1;
+      for (int x = 0; x < 8; ++x)
+        if (cnt[x] > 0 && (worst < 0 || load[x] + cnt[x] * k_len > load[worst] + cnt[worst] * k_len)) worst = x;
+      --cnt[worst];
+    }
   }
   out->first[0] = 0;
   for (int x = 0; x < 8; ++x) out->first[x + 1] = out->first[x] + cnt[x];
