@@ -190,6 +190,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the CPU-oracle baseline sample (0 = skip)")
     ap.add_argument("--no-hbm", action="store_true", help="skip the batch-replicated reward/scan measurement")
+    ap.add_argument("--all-live", action="store_true",
+                    help="also time the update call with every zero advantage replaced by a small number")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -279,7 +281,9 @@ def main():
                                            w.clip_eps, dW=dW, dH=dH, logp_new=logp_new, stats=stats, workspace=ws)
             torch.cuda.synchronize()
         return (time.perf_counter() - t1) * 1e3 / 3
-    update_workload_ms, update_all_live_ms = update_ms(adv0), update_ms(adv_all)
+    update_call_ms = None
+    if args.all_live:      # off by default: these launches would mix into the per-kernel averages of a profile of this command
+        update_call_ms = {"workload": update_ms(adv0), "every_row_given_a_gradient": update_ms(adv_all)}
 
     # dominant kernel: the one with the largest summed time; a vocabulary-sized GEMM does 2*V*d flop per row
     per_launch = {k: v[0] / v[1] for k, v in prof.items()}
@@ -314,7 +318,7 @@ def main():
                        "executed_gemm_passes": n_gemms,
                        "frac_of_bf16_peak_executed": executed / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                        "frac_of_bf16_peak_nominal_6Vd_all_rows": 6.0 * spec.V * spec.d * n_sel / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
-        "update_call_ms": {"workload": update_workload_ms, "every_row_given_a_gradient": update_all_live_ms},
+        "update_call_ms": update_call_ms,
         "kernels_ms_per_step": per_step,
         "policy_logprobs_ms": logprobs_ms,
         "loss": loss,
