@@ -274,37 +274,51 @@ __global__ void k_fill_i64(int64_t* __restrict__ p, int64_t n, int64_t v) {
   if (i < n) p[i] = v;
 }
 
-// Per turn segment, one wavefront each: the highest model-local position of a mask=1 token, the
-// turn's source offset, role and reward gathered into one record, the flag bits of its last token
-// (segment end; also trajectory-run end when a run starts at the segment's end offset or the stream
-// ends there), and for every token block whose first token lies in the segment, the segment's index.
+// Per turn segment, sixteen lanes each (four segments per wavefront, so that four chains of dependent loads are in
+// flight per wavefront): the highest model-local position of a mask=1 token, the turn's source offset, role and
+// reward gathered into one record, the flag bits of its last token (segment end; also trajectory-run end when a run
+// starts at the segment's end offset or the stream ends there), and for every token block whose first token lies in
+// the segment, the segment's index.
+constexpr int kSegLanes = 16;
 __global__ void k_seg_meta(int n_turns, int64_t n_tokens, const int32_t* __restrict__ seg_turn,
                            const int64_t* __restrict__ turn_tok_off, const int64_t* __restrict__ turn_seg_off,
                            const int32_t* __restrict__ turn_role, const float* __restrict__ turn_scalar,
                            const int32_t* __restrict__ turn_traj, const int32_t* __restrict__ turn_model,
                            const uint8_t* __restrict__ mask, SegMeta* __restrict__ seg_meta,
                            int32_t* __restrict__ blk_first) {
-  const int lane = threadIdx.x & (kWave - 1);
-  // wavefront-uniform index: the per-segment reads below become scalar loads, issued together
-  const int s = __builtin_amdgcn_readfirstlane(blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave);
-  if (s >= n_turns) return;
-  const bool has_next = s + 1 < n_turns;
-  const int u = seg_turn[s];
-  const int un = has_next ? seg_turn[s + 1] : u;
-  const int64_t g0 = turn_tok_off[u], len = turn_tok_off[u + 1] - g0;
-  const int64_t a = turn_seg_off[s], e = a + len;
-  const int64_t e_next = has_next ? turn_seg_off[s + 2] : e;      // end of the next segment
+  const int sub = threadIdx.x & (kSegLanes - 1);
+  const int s = (blockIdx.x * blockDim.x + threadIdx.x) / kSegLanes;
+  const bool live = s < n_turns;                          // whole groups of sixteen lanes; everybody stays for the shuffles
+  const int sc = live ? s : n_turns - 1;
+  const bool has_next = sc + 1 < n_turns;
+  const int u = seg_turn[sc];
+  const int un = has_next ? seg_turn[sc + 1] : u;
+  const int64_t g0 = turn_tok_off[u], len = live ? turn_tok_off[u + 1] - g0 : 0;
+  const int64_t a = turn_seg_off[sc], e = a + len;
+  const int64_t e_next = has_next ? turn_seg_off[sc + 2] : e;     // end of the next segment
   const int role = turn_role[u];
   const float rho = turn_scalar[u];
   const bool next_starts_run = turn_model[u] != turn_model[un] || turn_traj[u] != turn_traj[un];
   int64_t best = -1;
-  // walk from the end in steps of one wavefront; stop at the first step that holds a valid token
-  for (int64_t hi = len; hi > 0 && best < 0; hi -= kWave) {
-    const int64_t i = hi - 1 - lane;
-    const int64_t cand = (i >= 0 && mask[g0 + i]) ? i : -1;
-    best = wave_max(cand);
+  // walk from the end, 64 tokens (four per lane) at a time; stop at the first step that holds a valid token
+  for (int64_t hi = len; __any(hi > 0 && best < 0); hi -= 4 * kSegLanes) {
+    int64_t cand = -1;
+    if (hi > 0 && best < 0) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {                       // the highest index first
+        const int64_t i = hi - 1 - (4 * sub + k);
+        if (cand < 0 && i >= 0 && mask[g0 + i]) cand = i;
+      }
+    }
+    // tokens 4 sub .. 4 sub + 3 counted from the end: a lower lane holds higher positions, the maximum is wanted
+#pragma unroll
+    for (int o = kSegLanes / 2; o > 0; o >>= 1) {
+      const int64_t other = __shfl_xor(cand, o, kSegLanes);
+      cand = other > cand ? other : cand;
+    }
+    if (hi > 0 && best < 0) best = cand;
   }
-  if (lane == 0) {
+  if (live && sub == 0) {
     // a run ends at e when the stream ends there or a run starts at one of the segments that begin at e:
     // the next one, and if that one is empty the ones after it up to the first non-empty one
     bool run_end = e == n_tokens || (has_next && next_starts_run);
@@ -322,7 +336,8 @@ __global__ void k_seg_meta(int n_turns, int64_t n_tokens, const int32_t* __restr
     m.end_flags = 2 | (run_end ? 4 : 0);
     seg_meta[s] = m;
   }
-  for (int64_t b = (a + kTokBlock - 1) / kTokBlock + lane; b * kTokBlock < e; b += kWave) blk_first[b] = s;
+  if (live)
+    for (int64_t b = (a + kTokBlock - 1) / kTokBlock + sub; b * kTokBlock < e; b += kSegLanes) blk_first[b] = s;
 }
 
 // Per token in model-local order: source index, turn, role, mask, flags, placed reward; per block the
@@ -706,7 +721,7 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
                      o->model_trajrun_off);
   UMAS_LAUNCHED("k_run_apply");
   if (U > 0 && N > 0) {
-    hipLaunchKernelGGL(k_seg_meta, dim3(cdiv(U, 4)), dim3(256), 0, st, U, N, o->seg_turn, w.turn_tok_off,
+    hipLaunchKernelGGL(k_seg_meta, dim3(cdiv(U, 256 / kSegLanes)), dim3(256), 0, st, U, N, o->seg_turn, w.turn_tok_off,
                        o->turn_seg_off, w.turn_role, o->turn_scalar, w.turn_traj, w.turn_model, tok_mask_global,
                        w.seg_meta, w.blk_first);
     UMAS_LAUNCHED("k_seg_meta");
