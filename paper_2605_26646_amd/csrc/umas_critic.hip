@@ -21,7 +21,6 @@ constexpr int kMaxKV = 16;               // 16-byte column vectors per lane: d <
 constexpr int kMaxGrid = 1024;           // workgroups of the row kernel: one resident round at four per CU
 constexpr int kVStat = 4;                // (sum L, clipped rows, sum V, rows)
 
-__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
 __device__ __forceinline__ uint16_t f2bf(float x) { return __builtin_bit_cast(uint16_t, static_cast<__bf16>(x)); }
 
 // 16 bytes of a row as floats: 8 bf16 or 4 float

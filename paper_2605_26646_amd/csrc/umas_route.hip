@@ -513,7 +513,7 @@ k_rowsel(int64_t n_tokens, int n_models, const uint8_t* __restrict__ tok_mask,
   __shared__ int32_t smem[32];
   __shared__ int32_t s_out[kSelBlock];
   __shared__ int64_t moff[UMAS_MAX_MODELS + 1];
-  if (threadIdx.x <= n_models) moff[threadIdx.x] = model_tok_off[threadIdx.x];
+  if (static_cast<int>(threadIdx.x) <= n_models) moff[threadIdx.x] = model_tok_off[threadIdx.x];
   __syncthreads();
   const int64_t p0 = (static_cast<int64_t>(blockIdx.x) * kTokThreads + threadIdx.x) * kSelPerThread;
   uint32_t w[4] = {0u, 0u, 0u, 0u};

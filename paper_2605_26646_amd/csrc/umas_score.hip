@@ -56,11 +56,6 @@ __device__ __forceinline__ Part part_merge(Part x, Part y) {
 }
 
 // ------------------------------------------------------------------ small helpers
-__global__ void k_fill_f32(float* __restrict__ p, int64_t n, float v) {
-  int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
-  for (; i < n; i += stride) p[i] = v;
-}
 __global__ void k_fill_u32(uint32_t* __restrict__ p, int64_t n, uint32_t v) {
   int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
   const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
@@ -601,8 +596,8 @@ k_label_logit(const uint16_t* __restrict__ H, const uint16_t* __restrict__ W, in
 // column blocks [d / 256][mcp][256].
 // Rows of a flagged block get factor 1: their dz comes complete from the recomputing kernel.
 __global__ void __launch_bounds__(256)
-k_keep_rows(const uint16_t* __restrict__ H, int d, int V, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
-            const int32_t* __restrict__ ids, const float* __restrict__ lse_c, const float* __restrict__ a_c,
+k_keep_rows(const uint16_t* __restrict__ H, int d, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
+            const float* __restrict__ lse_c, const float* __restrict__ a_c,
             const float* __restrict__ cref, const int32_t* __restrict__ flags, const int32_t* __restrict__ cidx,
             float* __restrict__ sc, uint16_t* __restrict__ Hs, int64_t mcp) {
   const int lane = threadIdx.x & 63;
@@ -981,6 +976,7 @@ size_t chunk_bytes(int64_t mc, int d, int V, umas_dtype dt) {
   return align_up(static_cast<size_t>(mcp) * Vp * 2) + align_up(static_cast<size_t>(mcp) * round_up(d, 256) * 2);
 }
 size_t carve_ppo(Carver& c, PpoWs& w, int64_t n_sel, int d, int V, umas_dtype dt, int n_roles) {
+  (void)d;                                      // the per-chunk buffers depend on d, the fixed part does not
   carve_score(c, w.score, n_sel, V, dt, true);
   const int64_t n_pad = round_up(n_sel > 0 ? n_sel : 1, Cfg::BN);
   w.g_c = c.take<float>(n_pad);
@@ -1207,7 +1203,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
                          st, n_sel, c0, c0 + rows, rowsel, ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv, tok_role,
                          n_roles, clip_eps, dual_clip, k_ent, w.score.lse_c, w.g_c, w.a_c, w.kz_c, w.blk_stats);
       UMAS_LAUNCHED("k_ppo_rows");
-      hipLaunchKernelGGL(k_keep_rows, dim3(cdiv(rows, 4)), dim3(256), 0, st, Hb, d, V, rowsel, c0, rows, ids, w.score.lse_c,
+      hipLaunchKernelGGL(k_keep_rows, dim3(cdiv(rows, 4)), dim3(256), 0, st, Hb, d, rowsel, c0, rows, w.score.lse_c,
                          w.a_c, w.cref, w.flags, w.blk_cidx, w.sc, Hs, mcp);
       UMAS_LAUNCHED("k_keep_rows");
       // blocks of rows the scoring pass flagged (a logit far above the row's reference) get dz the long way
