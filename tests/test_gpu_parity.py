@@ -239,6 +239,47 @@ def test_blocks_of_rows_without_gradient_are_left_out():
             P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW, " + name)
 
 
+def test_dead_blocks_wide_logits_and_invalid_ids_together():
+    """One batch with everything the single-pass backward treats specially: a block of rows without gradient, rows
+    whose logits spread too far for the kept numerators (their block is recomputed), token ids outside the
+    vocabulary, a ragged vocabulary (1000) and a hidden size that is not a multiple of the K step (200)."""
+    w = wl.make_workload(1, n_traj=8, tokens_per_turn=40, models=[(200, 1000, "bf16")])
+    t = w.model_tensors(0)
+    n = len(t["ids"])
+    assert n == 960
+    Hn = t["H"].copy()
+    Hn[600:606] *= 256.0                                  # block 2: wide logits
+    ids_bad = t["ids"].copy()
+    bad = np.array([5, 130, 770, 959])
+    ids_bad[bad] = [1000, -7, 1 << 20, 4096]
+    adv = np.random.default_rng(8).normal(size=n).astype(np.float32)
+    adv[256:512] = 0.0                                    # block 1: no gradient
+    good = np.setdiff1d(np.arange(n), bad).astype(np.int32)
+    logp_o, lse_o, ent_o = orc.score(Hn, t["W"], t["ids"], good)
+    z = Hn.astype(np.float64) @ t["W"].astype(np.float64).T
+    gap = z.max(axis=1) - z[np.arange(n), t["ids"]]
+    assert (gap[600:606] > 55).any() and gap[good[(good < 600) | (good >= 606)]].max() < 40
+    logp_old = np.zeros(n, np.float32)
+    logp_old[good] = (logp_o[good] + t["noise"][good]).astype(np.float32)
+    st_o, g_o = orc.ppo_loss(logp_o, logp_old, adv, ent_o, good, np.zeros(n, np.int32), 0, 0.2)
+    g_o *= len(good) / n                                   # the mean runs over all n selected rows
+    dH_o, dW_o = orc.lm_head_backward(Hn, t["W"], t["ids"], lse_o, g_o, good)
+    small = umas.ppo_workspace_bytes(n, 200, 1000, torch.bfloat16, 0, minimum=True)
+    for ws_bytes in (None, small):
+        ws = None if ws_bytes is None else torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(P.to_dev(Hn, torch.bfloat16), P.to_dev(t["W"], torch.bfloat16),
+                                                            P.to_dev(ids_bad), None, P.to_dev(logp_old), P.to_dev(adv),
+                                                            None, 0, 0.2, workspace=ws)
+        sg = umas.read_stats(stats)
+        assert int(sg["n_invalid_ids"][0]) == len(bad) and int(sg["n_scored"][0]) == n
+        lp = logp_new.cpu().numpy()
+        assert np.abs(lp[good] - logp_o[good]).max() <= 2e-2 and not lp[bad].any()
+        dH_g = dH.float().cpu().numpy()
+        assert not dH_g[bad].any() and not dH_g[256:512].any()
+        P.close(dH_g, dH_o, 1e-2, "dH")
+        P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW")
+
+
 def test_accumulate_dw_adds_to_existing_gradient():
     w = wl.make_workload(1, n_traj=2, tokens_per_turn=40, models=[(64, 300, "bf16")])
     t = w.model_tensors(0)
