@@ -165,6 +165,18 @@ def test_full_size_single_pass_backward_agrees_with_recomputing_backward():
         torch.cuda.synchronize()
         out.append((umas.read_stats(stats), logp_new.cpu().numpy(), dH.float().cpu().numpy(), dW.cpu().numpy()))
         del dH, dW
+    # the same update in three chunks of selected rows (a workspace a third of the size): dW is accumulated
+    # over the chunks, everything else is per row
+    part = umas.ppo_workspace_bytes((n_sel + 2) // 3, spec.d, spec.V, torch.bfloat16, w.n_roles)
+    assert umas.ppo_workspace_bytes(n_sel, spec.d, spec.V, torch.bfloat16, w.n_roles, minimum=True) < part < ws.numel() // 2
+    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(H, W, ids, s.rowsel, logp_old, adv, s.tok_role, w.n_roles,
+                                                        w.clip_eps, workspace=ws[:part])
+    torch.cuda.synchronize()
+    sc_, lc, dHc, dWc = umas.read_stats(stats), logp_new.cpu().numpy(), dH.float().cpu().numpy(), dW.cpu().numpy()
+    del dH, dW
+    assert np.array_equal(lc, out[0][1]) and np.array_equal(dHc, out[0][2])
+    assert float(sc_["loss"][0]) == float(out[0][0]["loss"][0])
+    P.close(dWc, out[0][3], 1e-4, "dW, three chunks against one")
     (sa, la, dHa, dWa), (sb, lb, dHb, dWb) = out
     assert np.abs(la - lb).max() <= 1e-4
     assert abs(float(sa["loss"][0]) - float(sb["loss"][0])) <= 1e-5 * max(abs(float(sb["loss"][0])), 1e-3)
