@@ -292,7 +292,8 @@ def main():
     launches_per_step = prof[dom][1] / args.steps
     passes = {"k_gemm_dh_dw": 2}          # GEMMs of 2*V*d flop per row inside one launch
     rows_of = {"k_gemm_dh_dw": rows_in_live_blocks}          # rows a kernel works on per step (default: all selected rows)
-    rows_per_launch = rows_of.get(dom, n_sel) / launches_per_step
+    rows_needed = {"k_gemm_dh_dw": rows_with_gradient}       # rows it has to work on: the algorithmic count
+    rows_per_launch = rows_needed.get(dom, n_sel) / launches_per_step
     flop_per_launch = 2.0 * spec.V * spec.d * rows_per_launch * passes.get(dom, 1)
     achieved = flop_per_launch / (per_launch[dom] * 1e-3) / 1e12
     algorithmic = 2.0 * spec.V * spec.d * (n_sel + 2 * rows_with_gradient)
