@@ -389,7 +389,7 @@ __global__ void __launch_bounds__(kRowBlock)
 k_ppo_rows(int64_t n_sel, int64_t n_begin, int64_t n_end, const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
            const float* __restrict__ logp_c, const float* __restrict__ ent_c, const float* __restrict__ logp_old,
            const float* __restrict__ adv, const int32_t* __restrict__ tok_role, int n_roles, float clip_eps,
-           float dual_clip, float k_ent, const float* __restrict__ lse_c, float* __restrict__ g_c,
+           float dual_clip, float k_ent, int label_apart, const float* __restrict__ lse_c, float* __restrict__ g_c,
            float* __restrict__ a_c, float* __restrict__ kz_c, double* __restrict__ blk_stats) {
   extern __shared__ double s_acc[];   // [(1+n_roles) * kStat]
   const int nacc = (1 + n_roles) * kStat;
@@ -400,9 +400,10 @@ k_ppo_rows(int64_t n_sel, int64_t n_begin, int64_t n_end, const int32_t* __restr
     const int64_t row = rowsel ? rowsel[n] : n;
     const int y = ids[row];
     const bool ok = y >= 0 && y < V;
-    float L = 0.f, g = 0.f, clipped = 0.f, en = 0.f, kl = 0.f;
+    float L = 0.f, g = 0.f, clipped = 0.f, en = 0.f, kl = 0.f, lp = 0.f;
     if (ok) {
-      const float lp = logp_c[n], lo = logp_old[row], A = adv[row];
+      lp = logp_c[n];
+      const float lo = logp_old[row], A = adv[row];
       const float ratio = __expf(lp - lo);
       const float u = -A * ratio;
       const float c = -A * fminf(fmaxf(ratio, 1.f - clip_eps), 1.f + clip_eps);
@@ -417,7 +418,10 @@ k_ppo_rows(int64_t n_sel, int64_t n_begin, int64_t n_end, const int32_t* __restr
       en = ent_c[n];
       kl = lo - lp;
     }
-    g_c[n] = g;
+    // With label_apart the taken token's column is left out of the dense (bf16) part of dz and g_c carries all of
+    // dz[n, y] = g (1 - p_y) + k_ent p_y (log p_y + entropy) in float32: for a confident token g and g p_y nearly
+    // cancel, and the rounding of a bf16 g p_y would be as large as what is left.
+    g_c[n] = label_apart && ok ? fmaf(g, -expm1f(lp), k_ent * __expf(lp) * (lp + en)) : g;
     // coefficients of the backward's dense part dz = p (a + kz z): -g from the surrogate, the rest from the
     // entropy bonus k_ent p (log p + entropy); a row with an invalid id has neither
     a_c[n] = ok ? -g + k_ent * (en - lse_c[n]) : 0.f;
@@ -594,10 +598,12 @@ k_label_logit(const uint16_t* __restrict__ H, const uint16_t* __restrict__ W, in
 }
 // Row factor sc[n] = a_n exp(c_n - lse_n) of dz = sc E, and Hs[n - c0, :] = bf16(sc[n] h_n), the operand dW reads, in
 // column blocks [d / 256][mcp][256].
-// Rows of a flagged block get factor 1: their dz comes complete from the recomputing kernel.
+// Rows of a flagged block get factor 1: their dz comes complete from the recomputing kernel.  The entry of the
+// taken token is cleared in the [rows, V] operand (see k_ppo_rows).
 __global__ void __launch_bounds__(256)
-k_keep_rows(const uint16_t* __restrict__ H, int d, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
-            const float* __restrict__ lse_c, const float* __restrict__ a_c,
+k_keep_rows(const uint16_t* __restrict__ H, int d, int V, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
+            const int32_t* __restrict__ ids, uint16_t* __restrict__ E, int64_t tiles_v, const float* __restrict__ lse_c,
+            const float* __restrict__ a_c,
             const float* __restrict__ cref, const int32_t* __restrict__ flags, const int32_t* __restrict__ cidx,
             float* __restrict__ sc, uint16_t* __restrict__ Hs, int64_t mcp) {
   const int lane = threadIdx.x & 63;
@@ -612,6 +618,9 @@ k_keep_rows(const uint16_t* __restrict__ H, int d, const int32_t* __restrict__ r
     return;
   }
   const int64_t mp = static_cast<int64_t>(blk) * 256 + (m & 255);   // row in the packed operands
+  const int y = ids[row];
+  if (lane == 0 && y >= 0 && y < V)                          // the taken token's column goes through g_c in float32
+    E[blk_offset(blk, y >> 8, tiles_v) + (m & 255) * 256 + (y & 255)] = 0;
   float f = 1.f;
   if (!flags[n >> 8]) f = a != 0.f ? a * __expf(cref[n] - lse_c[n]) : 0.f;   // a = 0: invalid id (reference NaN) or no gradient
   if (lane == 0) sc[n] = f;
@@ -726,6 +735,17 @@ k_dz_flagged(const uint16_t* __restrict__ W, const uint16_t* __restrict__ H, int
     for (int tile_m = blockIdx.x; tile_m < tiles_m; tile_m += gridDim.x)
       dz_tile(tile_m, tile_n, W, H, d, V, rowsel, c0, mc, lse_c, a_c, kz_c, dZ, Vp, out_blk, lds);
   }
+}
+
+// The taken token's entry of every row of the chunk's blocked dZ is cleared: that column goes through g_c in float32
+// (see k_ppo_rows).  One thread per row.
+__global__ void __launch_bounds__(256)
+k_zero_label(uint16_t* __restrict__ dZ, int64_t tiles_v, int V, const int32_t* __restrict__ rowsel, int64_t c0, int64_t rows,
+             const int32_t* __restrict__ ids) {
+  const int64_t m = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (m >= rows) return;
+  const int y = ids[rowsel ? rowsel[c0 + m] : c0 + m];
+  if (y >= 0 && y < V) dZ[blk_offset(m >> 8, y >> 8, tiles_v) + (m & 255) * 256 + (y & 255)] = 0;
 }
 
 // ------------------------------------------------------------------ bf16: the two gradient products
@@ -1171,7 +1191,8 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     if (s != UMAS_OK) return s;
     hipLaunchKernelGGL(k_ppo_rows, dim3(nblk), dim3(kRowBlock), (1 + n_roles) * kStat * sizeof(double), st, n_sel,
                        static_cast<int64_t>(0), n_sel, rowsel, ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv,
-                       tok_role, n_roles, clip_eps, dual_clip, k_ent, w.score.lse_c, w.g_c, w.a_c, w.kz_c, w.blk_stats);
+                       tok_role, n_roles, clip_eps, dual_clip, k_ent, dtype == UMAS_BF16 ? 1 : 0, w.score.lse_c, w.g_c, w.a_c, w.kz_c,
+                       w.blk_stats);
     UMAS_LAUNCHED("k_ppo_rows");
   } else {
     hipLaunchKernelGGL(k_label_logit, dim3(cdiv(n_sel, 4)), dim3(256), 0, st, Hb, Wb, d, V, rowsel, n_sel, ids, w.cref);
@@ -1201,15 +1222,15 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
       UMAS_LAUNCHED("k_score_finalize");
       hipLaunchKernelGGL(k_ppo_rows, dim3(cdiv(rows, kRowBlock)), dim3(kRowBlock), (1 + n_roles) * kStat * sizeof(double),
                          st, n_sel, c0, c0 + rows, rowsel, ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv, tok_role,
-                         n_roles, clip_eps, dual_clip, k_ent, w.score.lse_c, w.g_c, w.a_c, w.kz_c, w.blk_stats);
+                         n_roles, clip_eps, dual_clip, k_ent, 1, w.score.lse_c, w.g_c, w.a_c, w.kz_c, w.blk_stats);
       UMAS_LAUNCHED("k_ppo_rows");
-      hipLaunchKernelGGL(k_keep_rows, dim3(cdiv(rows, 4)), dim3(256), 0, st, Hb, d, rowsel, c0, rows, w.score.lse_c,
-                         w.a_c, w.cref, w.flags, w.blk_cidx, w.sc, Hs, mcp);
-      UMAS_LAUNCHED("k_keep_rows");
       // blocks of rows the scoring pass flagged (a logit far above the row's reference) get dz the long way
       hipLaunchKernelGGL(k_dz_flagged, dim3(kFlaggedGrid), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel, c0, rows,
                          w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, E, Vp, w.flags, w.blk_cidx);
       UMAS_LAUNCHED("k_dz_flagged");
+      hipLaunchKernelGGL(k_keep_rows, dim3(cdiv(rows, 4)), dim3(256), 0, st, Hb, d, V, rowsel, c0, rows, ids, E,
+                         static_cast<int64_t>(tiles_v), w.score.lse_c, w.a_c, w.cref, w.flags, w.blk_cidx, w.sc, Hs, mcp);
+      UMAS_LAUNCHED("k_keep_rows");
       const unsigned grid_dh = tile_grid<kGM, kGN>(tiles_r, tiles_d);
       hipLaunchKernelGGL(k_gemm_dh_dw, dim3(grid_dh + static_cast<unsigned>(max_groups) * kGM * kGN * 8), dim3(Cfg::T), 0, st,
                          E, Vp, mcp, Wb, Hs, 1, static_cast<const int32_t*>(nullptr), d, V, tiles_v, tiles_d, grid_dh,
@@ -1253,6 +1274,9 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     hipLaunchKernelGGL(k_dz_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r, kTilesPerWg)), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel,
                        c0, rows, w.score.lse_c, w.a_c, w.kz_c, tiles_v, tiles_r, dZ, Vp);
     UMAS_LAUNCHED("k_dz_tiles");
+    hipLaunchKernelGGL(k_zero_label, dim3(cdiv(rows, 256)), dim3(256), 0, st, dZ, static_cast<int64_t>(tiles_v), V, rowsel, c0, rows,
+                       ids);
+    UMAS_LAUNCHED("k_zero_label");
     // with an entropy bonus every row has a gradient: all blocks are live
     const int max_groups = max_dw_groups_per_xcd(tiles_v, tiles_d);
     hipLaunchKernelGGL(k_live_scan, dim3(1), dim3(512), 0, st, static_cast<int>(c0 >> 8), tiles_r, rows, 1, tiles_v, tiles_d, Vp,

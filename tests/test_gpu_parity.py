@@ -280,6 +280,68 @@ def test_dead_blocks_wide_logits_and_invalid_ids_together():
         P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW")
 
 
+@pytest.mark.parametrize("seed", range(32))
+def test_random_small_shapes(seed):
+    """Seeded random shapes around the tile edges: hidden sizes that are and are not multiples of the K step and of
+    the 256-wide column tile, vocabularies below and above one tile, row counts around one block, a random row
+    selection, some dead rows and blocks, one invalid id, chunked or not, accumulating or not."""
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([8, 64, 72, 128, 200, 264, 320]))
+    V = int(rng.choice([5, 255, 256, 257, 700, 1030]))
+    n = int(rng.choice([1, 17, 255, 256, 257, 600, 1100]))
+    H = workloads_round(rng.normal(size=(n, d)) / np.sqrt(d) * 4)
+    W = workloads_round(rng.normal(size=(V, d)))
+    ids = rng.integers(0, V, size=n).astype(np.int32)
+    n_sel = int(rng.integers(1, n + 1))
+    rowsel = np.sort(rng.choice(n, size=n_sel, replace=False)).astype(np.int32) if rng.random() < 0.7 else None
+    sel = rowsel if rowsel is not None else np.arange(n, dtype=np.int32)
+    ids_bad = ids.copy()
+    bad_row = int(sel[rng.integers(len(sel))])
+    if len(sel) > 1 and rng.random() < 0.5:
+        ids_bad[bad_row] = V + 3
+    good = sel[ids_bad[sel] < V]
+    adv = rng.normal(size=n).astype(np.float32)
+    adv[rng.random(n) < 0.2] = 0.0
+    if len(sel) > 300 and rng.random() < 0.7:
+        adv[sel[256:512]] = 0.0                           # a dead block of selected rows
+    logp_o, lse_o, ent_o = orc.score(H, W, ids, good)
+    logp_old = np.zeros(n, np.float32)
+    logp_old[good] = (logp_o[good] + 0.05 * rng.normal(size=len(good))).astype(np.float32)
+    st_o, g_o = orc.ppo_loss(logp_o, logp_old, adv, ent_o, good, np.zeros(n, np.int32), 0, 0.2)
+    g_o *= len(good) / len(sel)
+    dH_o, dW_o = orc.lm_head_backward(H, W, ids, lse_o, g_o, good)
+    dW0 = (0.01 * rng.normal(size=(V, d))).astype(np.float32) if rng.random() < 0.5 else None
+    ws = None
+    if rng.random() < 0.5:
+        ws = torch.empty(umas.ppo_workspace_bytes(len(sel), d, V, torch.bfloat16, 0, minimum=True), dtype=torch.uint8, device="cuda")
+    dW = P.to_dev(dW0) if dW0 is not None else None
+    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(P.to_dev(H, torch.bfloat16), P.to_dev(W, torch.bfloat16), P.to_dev(ids_bad),
+                                                        None if rowsel is None else P.to_dev(rowsel), P.to_dev(logp_old),
+                                                        P.to_dev(adv), None, 0, 0.2, accumulate_dW=dW0 is not None, dW=dW,
+                                                        workspace=ws)
+    sg = umas.read_stats(stats)
+    what = f"seed {seed}: d={d} V={V} n={n} sel={len(sel)} rowsel={rowsel is not None} chunked={ws is not None} acc={dW0 is not None}"
+    assert int(sg["n_scored"][0]) == len(sel) and int(sg["n_invalid_ids"][0]) == len(sel) - len(good), what
+    lp = logp_new.cpu().numpy()
+    assert np.abs(lp[good] - logp_o[good]).max(initial=0) <= 2e-2, what
+    unsel = np.setdiff1d(np.arange(n), good)
+    dH_g = dH.float().cpu().numpy()
+    assert not dH_g[unsel].any() and not lp[unsel].any(), what
+    # These logits are far more peaked than the workloads' (W ~ N(0,1), a handful of tokens carry a row's softmax), so
+    # a gradient entry is a sum of a few products that may cancel; every product carries the bf16 rounding of both of
+    # its factors (kept numerator and scaled hidden state: up to 0.8 % together).  Single entries and rows get 4 % of
+    # max(|entry|, rms), the arrays as a whole the 1 % of the other tests.
+    assert P.close(dH_g, dH_o, 4e-2, "dH, " + what) <= 1e-2, what
+    ref = dW_o if dW0 is None else dW_o + dW0
+    # an accumulated gradient is compared on what was added to it
+    assert P.close(dW.cpu().numpy() - (0 if dW0 is None else dW0), dW_o, 4e-2, "dW, " + what,
+                   row_abs=0 if dW0 is None else 1e-5 * np.abs(ref).max() * np.sqrt(d)) <= 1e-2, what
+
+
+def workloads_round(x):
+    return wl.round_to_bf16(x.astype(np.float32))
+
+
 def test_accumulate_dw_adds_to_existing_gradient():
     w = wl.make_workload(1, n_traj=2, tokens_per_turn=40, models=[(64, 300, "bf16")])
     t = w.model_tensors(0)
