@@ -200,13 +200,19 @@ size_t umas_ppo_loss_workspace_bytes(int64_t n_sel, int32_t d, int32_t V, umas_d
  *   dual_clip c > 1: for A < 0 the row's term is capped at -A c, with no gradient where the cap binds;
  *   entropy_coef k >= 0: the loss becomes L_clip - k mean entropy (stats.loss includes it) and
  *     dz_iv gains (k / n_sel) p_iv (log p_iv + entropy_i), p = softmax(z_i).
+ * norm_rows: 0, or the number of rows the token mean is taken over when the call is one micro-batch of a
+ *   minibatch of norm_rows >= n_sel scored rows (gradient accumulation over the parts of a ready batch, paragraph
+ *   "Model-specific updates and synchronization"): g, the entropy term and stats[0].loss are divided by it in
+ *   place of n_sel, so that the micro-batches' dW (accumulate_dW = 1), dH rows and losses add up to those of one
+ *   call on the whole minibatch.  The roles' rows of stats and the other fields stay means over the call's rows.
  * bf16 computes the logits once when entropy_coef = 0 (the scoring pass leaves the softmax numerators
  * in the workspace as the operand of dH and dW) and twice otherwise; float32 logits are never stored. */
 umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_dtype dtype, int64_t n_rows,
                                   int32_t d, int32_t V, const int32_t* ids, const int32_t* rowsel,
                                   int64_t n_sel, const float* logp_old, const float* adv,
                                   const int32_t* tok_role, int32_t n_roles, float clip_eps,
-                                  float entropy_coef, float dual_clip, int32_t accumulate_dW, umas_loss_stats* stats,
+                                  float entropy_coef, float dual_clip, int32_t accumulate_dW, int64_t norm_rows,
+                                  umas_loss_stats* stats,
                                   float* logp_new, void* dH, float* dW,
                                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
@@ -244,12 +250,13 @@ size_t umas_value_workspace_bytes(int64_t n_sel, int32_t d, umas_dtype dtype, in
  *                   and 0 elsewhere, 1 adds g_i w to the selected rows and leaves the others alone (a trunk
  *                   shared with the policy head)
  *   dw, db          DEVICE float [d], [1] (db may be NULL); accumulate_dw = 0 overwrites, 1 adds
+ *   norm_rows       0, or the row count the mean is taken over (>= n_sel), as in umas_ppo_loss_fwd_bwd
  * clip_eps_v must be positive.  The result does not depend on scheduling: partial sums are reduced in a
  * fixed order. */
 umas_status umas_value_loss_fwd_bwd(const void* H, const void* w, float bias, umas_dtype dtype, int64_t n_rows,
                                     int32_t d, const int32_t* rowsel, int64_t n_sel, const float* value_old,
                                     const float* ret, const int32_t* tok_role, int32_t n_roles, float clip_eps_v,
-                                    int32_t accumulate_dH, int32_t accumulate_dw, umas_value_stats* stats,
+                                    int32_t accumulate_dH, int32_t accumulate_dw, int64_t norm_rows, umas_value_stats* stats,
                                     float* value_new, void* dH, float* dw, float* db, void* workspace,
                                     size_t workspace_bytes, void* hip_stream);
 

@@ -127,8 +127,8 @@ def load_library():
     lib.umas_ppo_loss_fwd_bwd.restype = C.c_int
     lib.umas_ppo_loss_fwd_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int32, C.c_int32,
                                           C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
-                                          C.c_int32, C.c_float, C.c_float, C.c_float, C.c_int32, C.c_void_p, C.c_void_p,
-                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+                                          C.c_int32, C.c_float, C.c_float, C.c_float, C.c_int32, C.c_int64, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     _LIB = lib
     return lib
 
@@ -259,7 +259,8 @@ def ppo_workspace_bytes(n_sel, d, V, dtype: torch.dtype, n_roles, minimum=False)
 
 
 def umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv, tok_role, n_roles, clip_eps, *, entropy_coef=0.0,
-                          dual_clip=0.0, accumulate_dW=False, dW=None, dH=None, logp_new=None, stats=None, workspace=None):
+                          dual_clip=0.0, accumulate_dW=False, norm_rows=0, dW=None, dH=None, logp_new=None, stats=None,
+                          workspace=None):
     lib = load_library()
     n_rows, d = H.shape
     V = W.shape[0]
@@ -279,7 +280,8 @@ def umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv, tok_role, n_roles, c
     _keep, sel = _sel_ptr(rowsel)
     _check(lib, lib.umas_ppo_loss_fwd_bwd(H.data_ptr(), W.data_ptr(), dt, n_rows, d, V, ids.data_ptr(), sel,
                                           n_sel, logp_old.data_ptr(), adv.data_ptr(), _ptr(tok_role), n_roles,
-                                          clip_eps, entropy_coef, dual_clip, 1 if accumulate_dW else 0, stats.data_ptr(),
+                                          clip_eps, entropy_coef, dual_clip, 1 if accumulate_dW else 0, int(norm_rows),
+                                          stats.data_ptr(),
                                           logp_new.data_ptr(), dH.data_ptr(), dW.data_ptr(), ws.data_ptr(), ws.numel(),
                                           _stream()))
     return stats, logp_new, dH, dW
@@ -304,14 +306,15 @@ def umas_values(H, w, bias=0.0, rowsel=None, value=None):
 
 
 def umas_value_loss_fwd_bwd(H, w, bias, rowsel, value_old, ret, tok_role, n_roles, clip_eps_v, *, accumulate_dH=False,
-                            accumulate_dw=False, dH=None, dw=None, db=None, value_new=None, stats=None, workspace=None):
+                            accumulate_dw=False, norm_rows=0, dH=None, dw=None, db=None, value_new=None, stats=None,
+                            workspace=None):
     lib = load_library()
     lib.umas_value_workspace_bytes.restype = C.c_size_t
     lib.umas_value_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int, C.c_int32]
     lib.umas_value_loss_fwd_bwd.restype = C.c_int
     lib.umas_value_loss_fwd_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_int, C.c_int64, C.c_int32, C.c_void_p,
                                             C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_int32,
-                                            C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_size_t, C.c_void_p]
     n_rows, d = H.shape
     n_sel = n_rows if rowsel is None else int(rowsel.numel())
@@ -331,7 +334,7 @@ def umas_value_loss_fwd_bwd(H, w, bias, rowsel, value_old, ret, tok_role, n_role
     _keep, sel = _sel_ptr(rowsel)
     _check(lib, lib.umas_value_loss_fwd_bwd(_ptr(H), w.data_ptr(), bias, dt, n_rows, d, sel, n_sel, _ptr(value_old),
                                             _ptr(ret), _ptr(tok_role), n_roles, clip_eps_v, 1 if accumulate_dH else 0,
-                                            1 if accumulate_dw else 0, stats.data_ptr(), _ptr(value_new), _ptr(dH),
+                                            1 if accumulate_dw else 0, int(norm_rows), stats.data_ptr(), _ptr(value_new), _ptr(dH),
                                             dw.data_ptr(), db.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
     return stats, value_new, dH, dw, db
 

@@ -86,7 +86,7 @@ k_value_fwd(const T* __restrict__ H, const T* __restrict__ w, float bias, int d,
 template <typename T, int KV>
 __global__ void __launch_bounds__(kVT)
 k_value_rows(const T* __restrict__ H, const T* __restrict__ w, float bias, int d, const int32_t* __restrict__ rowsel,
-             int64_t n_sel, int64_t rows_per_block, const float* __restrict__ value_old, const float* __restrict__ ret,
+             int64_t n_sel, int64_t norm, int64_t rows_per_block, const float* __restrict__ value_old, const float* __restrict__ ret,
              const int32_t* __restrict__ tok_role, int n_roles, float clip_eps, float* __restrict__ value_new,
              T* __restrict__ dH, int accumulate_dH, float* __restrict__ part_dw, double* __restrict__ blk_stats) {
   __shared__ double s_acc[(1 + UMAS_MAX_ROLES) * kVStat];
@@ -108,7 +108,7 @@ k_value_rows(const T* __restrict__ H, const T* __restrict__ w, float bias, int d
     if (cv < nvec) wp[k] = *reinterpret_cast<const uint4*>(w + cv * N);
   }
   float gsum = 0.f;
-  const float inv_s = 1.f / static_cast<float>(n_sel);
+  const float inv_s = 1.f / static_cast<float>(norm);
   const int64_t r_begin = static_cast<int64_t>(blockIdx.x) * rows_per_block;
   const int64_t r_end = r_begin + rows_per_block < n_sel ? r_begin + rows_per_block : n_sel;
 
@@ -215,7 +215,7 @@ k_value_reduce(const float* __restrict__ in, int n_in, int ld, int group, float*
   }
 }
 __global__ void __launch_bounds__(256)
-k_value_stats(int nblk, int n_roles, const double* __restrict__ blk_stats, umas_value_stats* __restrict__ stats) {
+k_value_stats(int nblk, int n_roles, int64_t norm_rows, const double* __restrict__ blk_stats, umas_value_stats* __restrict__ stats) {
   __shared__ double smem[32];
   const int nacc = (1 + n_roles) * kVStat;
   for (int k = 0; k <= n_roles; ++k) {
@@ -228,7 +228,8 @@ k_value_stats(int nblk, int n_roles, const double* __restrict__ blk_stats, umas_
     if (threadIdx.x == 0) {
       const double cnt = sum[3];
       umas_value_stats s;
-      s.loss = cnt > 0 ? static_cast<float>(sum[0] / cnt) : 0.f;
+      const double den = (k == 0 && norm_rows > 0) ? static_cast<double>(norm_rows) : cnt;   // the caller's normaliser
+      s.loss = cnt > 0 ? static_cast<float>(sum[0] / den) : 0.f;
       s.clip_frac = cnt > 0 ? static_cast<float>(sum[1] / cnt) : 0.f;
       s.value_mean = cnt > 0 ? static_cast<float>(sum[2] / cnt) : 0.f;
       s.reserved = 0.f;
@@ -247,12 +248,12 @@ int max_d(umas_dtype dt) { return dt == UMAS_BF16 ? kWave * kMaxKV * 8 : kWave *
 
 template <typename T>
 void launch_value_rows(int kv, unsigned grid, hipStream_t st, const void* H, const void* w, float bias, int d,
-                       const int32_t* rowsel, int64_t n_sel, int64_t rpb, const float* value_old, const float* ret,
+                       const int32_t* rowsel, int64_t n_sel, int64_t norm, int64_t rpb, const float* value_old, const float* ret,
                        const int32_t* tok_role, int n_roles, float clip_eps, float* value_new, void* dH, int acc_dH,
                        float* part_dw, double* blk_stats) {
 #define UMAS_VALUE_CASE(K)                                                                                              \
   hipLaunchKernelGGL((k_value_rows<T, K>), dim3(grid), dim3(kVT), 0, st, static_cast<const T*>(H), static_cast<const T*>(w), \
-                     bias, d, rowsel, n_sel, rpb, value_old, ret, tok_role, n_roles, clip_eps, value_new,               \
+                     bias, d, rowsel, n_sel, norm, rpb, value_old, ret, tok_role, n_roles, clip_eps, value_new,         \
                      static_cast<T*>(dH), acc_dH, part_dw, blk_stats)
   if (kv <= 1) UMAS_VALUE_CASE(1);
   else if (kv <= 2) UMAS_VALUE_CASE(2);
@@ -318,7 +319,7 @@ extern "C" umas_status umas_value_loss_fwd_bwd(const void* H, const void* w, flo
                                                int32_t d, const int32_t* rowsel, int64_t n_sel, const float* value_old,
                                                const float* ret, const int32_t* tok_role, int32_t n_roles,
                                                float clip_eps_v, int32_t accumulate_dH, int32_t accumulate_dw,
-                                               umas_value_stats* stats, float* value_new, void* dH, float* dw, float* db,
+                                               int64_t norm_rows, umas_value_stats* stats, float* value_new, void* dH, float* dw, float* db,
                                                void* workspace, size_t workspace_bytes, void* hip_stream) {
   umas_status s = check_value_args(H, w, dtype, n_rows, d, rowsel, n_sel);
   if (s != UMAS_OK) return s;
@@ -327,6 +328,9 @@ extern "C" umas_status umas_value_loss_fwd_bwd(const void* H, const void* w, flo
   UMAS_REQUIRE(stats && dw && (dH || n_rows == 0), UMAS_EINVAL, "stats, dw and dH must not be NULL");
   UMAS_REQUIRE((value_old && ret) || n_sel == 0, UMAS_EINVAL, "value_old and ret must not be NULL");
   UMAS_REQUIRE(reinterpret_cast<uintptr_t>(dH) % 16 == 0, UMAS_EINVAL, "dH must be 16-byte aligned");
+  UMAS_REQUIRE(norm_rows == 0 || norm_rows >= n_sel, UMAS_EINVAL, "norm_rows=%lld must be 0 or at least n_sel=%lld",
+               static_cast<long long>(norm_rows), static_cast<long long>(n_sel));
+  const int64_t norm = norm_rows > 0 ? norm_rows : n_sel;   // rows the mean is taken over
   const size_t need = umas_value_workspace_bytes(n_sel, d, dtype, n_roles);
   UMAS_REQUIRE(workspace && reinterpret_cast<uintptr_t>(workspace) % kAlign == 0 && workspace_bytes >= need, UMAS_EWORKSPACE,
                "workspace must be 256-byte aligned and hold %zu bytes (got %zu)", need, workspace_bytes);
@@ -358,10 +362,10 @@ extern "C" umas_status umas_value_loss_fwd_bwd(const void* H, const void* w, flo
     const int nvec = d / (dtype == UMAS_BF16 ? 8 : 4);
     const int kv = (nvec + kWave - 1) / kWave;
     if (dtype == UMAS_BF16)
-      launch_value_rows<uint16_t>(kv, grid, st, H, w, bias, d, rowsel, n_sel, rpb, value_old, ret, tok_role, n_roles,
+      launch_value_rows<uint16_t>(kv, grid, st, H, w, bias, d, rowsel, n_sel, norm, rpb, value_old, ret, tok_role, n_roles,
                                   clip_eps_v, value_new, dH, accumulate_dH, part_dw, blk_stats);
     else
-      launch_value_rows<float>(kv, grid, st, H, w, bias, d, rowsel, n_sel, rpb, value_old, ret, tok_role, n_roles,
+      launch_value_rows<float>(kv, grid, st, H, w, bias, d, rowsel, n_sel, norm, rpb, value_old, ret, tok_role, n_roles,
                                clip_eps_v, value_new, dH, accumulate_dH, part_dw, blk_stats);
     UMAS_LAUNCHED("k_value_rows");
   } else {
@@ -375,7 +379,7 @@ extern "C" umas_status umas_value_loss_fwd_bwd(const void* H, const void* w, flo
   hipLaunchKernelGGL(k_value_reduce, dim3(cdiv(d + 1, 256), 1), dim3(256), 0, st, part2, n_part2, d + 1, n_part2,
                      static_cast<float*>(nullptr), d, 1, accumulate_dw, dw, db);
   UMAS_LAUNCHED("k_value_reduce");
-  hipLaunchKernelGGL(k_value_stats, dim3(1), dim3(256), 0, st, static_cast<int>(grid), n_roles, blk_stats, stats);
+  hipLaunchKernelGGL(k_value_stats, dim3(1), dim3(256), 0, st, static_cast<int>(grid), n_roles, norm_rows, blk_stats, stats);
   UMAS_LAUNCHED("k_value_stats");
   return UMAS_OK;
 }

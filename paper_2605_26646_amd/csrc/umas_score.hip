@@ -386,7 +386,7 @@ k_score_f32(const float* __restrict__ W, const float* __restrict__ H, int d, int
 // logp_old - logp, rows, invalid ids) for the model and for each role, in float64.
 constexpr int kStat = 6;
 __global__ void __launch_bounds__(kRowBlock)
-k_ppo_rows(int64_t n_sel, int64_t n_begin, int64_t n_end, const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
+k_ppo_rows(int64_t norm, int64_t n_begin, int64_t n_end, const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
            const float* __restrict__ logp_c, const float* __restrict__ ent_c, const float* __restrict__ logp_old,
            const float* __restrict__ adv, const int32_t* __restrict__ tok_role, int n_roles, float clip_eps,
            float dual_clip, float k_ent, int label_apart, const float* __restrict__ lse_c, float* __restrict__ g_c,
@@ -413,7 +413,7 @@ k_ppo_rows(int64_t n_sel, int64_t n_begin, int64_t n_end, const int32_t* __restr
         L = -A * dual_clip;
         unclipped = false;
       }
-      g = unclipped ? u / static_cast<float>(n_sel) : 0.f;
+      g = unclipped ? u / static_cast<float>(norm) : 0.f;
       clipped = unclipped ? 0.f : 1.f;
       en = ent_c[n];
       kl = lo - lp;
@@ -444,7 +444,7 @@ k_ppo_rows(int64_t n_sel, int64_t n_begin, int64_t n_end, const int32_t* __restr
 }
 
 __global__ void __launch_bounds__(256)
-k_ppo_stats(int nblk, int n_roles, float entropy_coef, const double* __restrict__ blk_stats,
+k_ppo_stats(int nblk, int n_roles, float entropy_coef, int64_t norm_rows, const double* __restrict__ blk_stats,
             umas_loss_stats* __restrict__ stats) {
   __shared__ double smem[32];
   const int nacc = (1 + n_roles) * kStat;
@@ -458,7 +458,9 @@ k_ppo_stats(int nblk, int n_roles, float entropy_coef, const double* __restrict_
     if (threadIdx.x == 0) {
       const double cnt = sum[4];
       umas_loss_stats s;
-      s.loss = cnt > 0 ? static_cast<float>((sum[0] - static_cast<double>(entropy_coef) * sum[2]) / cnt) : 0.f;
+      // the model's loss over the caller's normaliser when one is given: micro-batch losses then add up
+      const double den = (k == 0 && norm_rows > 0) ? static_cast<double>(norm_rows) : cnt;
+      s.loss = cnt > 0 ? static_cast<float>((sum[0] - static_cast<double>(entropy_coef) * sum[2]) / den) : 0.f;
       s.clip_frac = cnt > 0 ? static_cast<float>(sum[1] / cnt) : 0.f;
       s.entropy_mean = cnt > 0 ? static_cast<float>(sum[2] / cnt) : 0.f;
       s.approx_kl = cnt > 0 ? static_cast<float>(sum[3] / cnt) : 0.f;
@@ -908,17 +910,28 @@ k_dz_f32(const float* __restrict__ W, const float* __restrict__ H, int d, int V,
   const int64_t row = rowsel ? rowsel[c0 + n] : c0 + n;
   for (int k = threadIdx.x; k < d; k += blockDim.x) s_h[k] = H[row * d + k];
   __syncthreads();
+  __shared__ float s_red[32];
   const int y = ids[row];
   const float l = lse_c[c0 + n], g = g_c[c0 + n], en = ent_c[c0 + n], k_ent = kz_c[c0 + n];
+  // The taken token's entry g (1 - p_y): for a confident token (p_y > 1/2) 1 - p_y cancels down to the error of p_y,
+  // and the sum of the other probabilities, which carries only their relative error, is taken in its place.
+  float rest = 0.f, label_ent = 0.f, p_label = 0.f;
   for (int v = threadIdx.x; v < V; v += blockDim.x) {
     const float* w = W + static_cast<int64_t>(v) * d;
     float z = 0.f;
     for (int k = 0; k < d; ++k) z = fmaf(s_h[k], w[k], z);
     const float p = expf(z - l);
-    float o = (v == y) ? g * (1.f - p) : -g * p;
-    if (k_ent != 0.f) o += k_ent * p * ((z - l) + en);     // entropy bonus: k p (log p + entropy)
-    dz[n * V + v] = o;
+    const float e = k_ent != 0.f ? k_ent * p * ((z - l) + en) : 0.f;     // entropy bonus: k p (log p + entropy)
+    if (v == y) {
+      label_ent = e;
+      p_label = p;
+    } else {
+      rest += p;
+      dz[n * V + v] = -g * p + e;
+    }
   }
+  rest = block_sum<float>(rest, s_red);
+  if (y >= 0 && y < V && threadIdx.x == y % static_cast<int>(blockDim.x)) dz[n * V + y] = g * (p_label > 0.5f ? rest : 1.f - p_label) + label_ent;
 }
 // dH[row, j] = sum_v dz[n, v] W[v, j]
 __global__ void __launch_bounds__(256)
@@ -1133,7 +1146,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
                                              int32_t V, const int32_t* ids, const int32_t* rowsel, int64_t n_sel,
                                              const float* logp_old, const float* adv, const int32_t* tok_role,
                                              int32_t n_roles, float clip_eps, float entropy_coef, float dual_clip,
-                                             int32_t accumulate_dW, umas_loss_stats* stats, float* logp_new, void* dH,
+                                             int32_t accumulate_dW, int64_t norm_rows, umas_loss_stats* stats, float* logp_new, void* dH,
                                              float* dW, void* workspace, size_t workspace_bytes, void* hip_stream) {
   umas_status s = check_model_args(H, W, dtype, n_rows, d, V, ids, rowsel, n_sel);
   if (s != UMAS_OK) return s;
@@ -1146,6 +1159,8 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
   UMAS_REQUIRE(dual_clip == 0.f || dual_clip > 1.f, UMAS_EINVAL, "dual_clip=%g must be 0 (off) or larger than 1",
                static_cast<double>(dual_clip));
   UMAS_REQUIRE(n_sel < (1LL << 31), UMAS_ESHAPE, "at most 2^31-1 selected rows");
+  UMAS_REQUIRE(norm_rows == 0 || norm_rows >= n_sel, UMAS_EINVAL, "norm_rows=%lld must be 0 or at least n_sel=%lld",
+               static_cast<long long>(norm_rows), static_cast<long long>(n_sel));
   s = check_ws(workspace, workspace_bytes, umas_ppo_loss_workspace_bytes_min(n_sel, d, V, dtype, n_roles));
   if (s != UMAS_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -1177,7 +1192,8 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
                "workspace cannot hold one chunk of %lld rows", static_cast<long long>(mc));
 
   const int nblk = cdiv(n_sel > 0 ? n_sel : 1, kRowBlock);
-  const float k_ent = n_sel > 0 ? entropy_coef / static_cast<float>(n_sel) : 0.f;
+  const int64_t norm = norm_rows > 0 ? norm_rows : n_sel;   // rows the token mean is taken over
+  const float k_ent = norm > 0 ? entropy_coef / static_cast<float>(norm) : 0.f;
   // Without an entropy bonus dz is a row factor times the softmax: the scoring pass keeps the numerators
   // and the logits are not computed a second time.
   const bool keep = dtype == UMAS_BF16 && entropy_coef == 0.f && n_sel > 0;
@@ -1189,7 +1205,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     // forward scoring and the surrogate
     s = run_score(H, W, dtype, d, V, ids, rowsel, n_sel, w.score, logp_new, nullptr, nullptr, st);
     if (s != UMAS_OK) return s;
-    hipLaunchKernelGGL(k_ppo_rows, dim3(nblk), dim3(kRowBlock), (1 + n_roles) * kStat * sizeof(double), st, n_sel,
+    hipLaunchKernelGGL(k_ppo_rows, dim3(nblk), dim3(kRowBlock), (1 + n_roles) * kStat * sizeof(double), st, norm,
                        static_cast<int64_t>(0), n_sel, rowsel, ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv,
                        tok_role, n_roles, clip_eps, dual_clip, k_ent, dtype == UMAS_BF16 ? 1 : 0, w.score.lse_c, w.g_c, w.a_c, w.kz_c,
                        w.blk_stats);
@@ -1221,7 +1237,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
                          static_cast<float*>(nullptr), static_cast<float*>(nullptr));
       UMAS_LAUNCHED("k_score_finalize");
       hipLaunchKernelGGL(k_ppo_rows, dim3(cdiv(rows, kRowBlock)), dim3(kRowBlock), (1 + n_roles) * kStat * sizeof(double),
-                         st, n_sel, c0, c0 + rows, rowsel, ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv, tok_role,
+                         st, norm, c0, c0 + rows, rowsel, ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv, tok_role,
                          n_roles, clip_eps, dual_clip, k_ent, 1, w.score.lse_c, w.g_c, w.a_c, w.kz_c, w.blk_stats);
       UMAS_LAUNCHED("k_ppo_rows");
       // blocks of rows the scoring pass flagged (a logit far above the row's reference) get dz the long way
@@ -1239,7 +1255,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
       UMAS_LAUNCHED("k_gemm_dh_dw");
     }
   }
-  hipLaunchKernelGGL(k_ppo_stats, dim3(1), dim3(256), 0, st, nblk, n_roles, entropy_coef, w.blk_stats, stats);
+  hipLaunchKernelGGL(k_ppo_stats, dim3(1), dim3(256), 0, st, nblk, n_roles, entropy_coef, norm_rows, w.blk_stats, stats);
   UMAS_LAUNCHED("k_ppo_stats");
   if (n_sel == 0) return UMAS_OK;
   if (keep) {

@@ -93,20 +93,24 @@ def test_bad_scalar_arguments(lib):
     assert lib.umas_policy_logprobs(256, 256, 1, 4, 12, 8, 256, None, 4, 256, 256, None, 256, 1 << 20, None) == -2
     assert "d % 8" in lib.umas_last_error().decode()
     # clip_eps outside (0,1)
-    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 1.5, 0.0, 0.0, 0, 256, None,
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 1.5, 0.0, 0.0, 0, 0, 256, None,
                                    256, 256, 256, 1 << 30, None)
     assert st == -1 and "clip_eps" in lib.umas_last_error().decode()
     # workspace too small
-    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0.0, 0, 256, None,
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0.0, 0, 0, 256, None,
                                    256, 256, 256, 16, None)
     assert st == -4
     # dual clip constants in (0, 1] and a negative entropy coefficient are refused
-    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0.5, 0, 256, None,
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0.5, 0, 0, 256, None,
                                    256, 256, 256, 1 << 30, None)
     assert st == -1 and "dual_clip" in lib.umas_last_error().decode()
-    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, -0.1, 0.0, 0, 256, None,
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, -0.1, 0.0, 0, 0, 256, None,
                                    256, 256, 256, 1 << 30, None)
     assert st == -1 and "entropy_coef" in lib.umas_last_error().decode()
+    # a normaliser smaller than the call's own row count is refused
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0.0, 0, 3, 256, None,
+                                   256, 256, 256, 1 << 30, None)
+    assert st == -1 and "norm_rows" in lib.umas_last_error().decode()
     from paper_2605_26646_amd import binding as b
     s = b._Streams(*([1] * 16))
     assert lib.umas_advantages(C.addressof(s), 10, 1, None, 1.0, 1.0, 1.0, 3, 256, 256, 256, 1 << 20, None) == -1
@@ -129,12 +133,12 @@ def test_entry_points_around_the_update_reject_bad_arguments(lib):
     assert lib.umas_value_workspace_bytes(1000, 2048, 1, 3) > 0
     lib.umas_value_loss_fwd_bwd.restype = C.c_int
     lib.umas_value_loss_fwd_bwd.argtypes = [C.c_void_p, C.c_void_p, f32, C.c_int, i64, C.c_int32, C.c_void_p, i64, C.c_void_p,
-                                            C.c_void_p, C.c_void_p, C.c_int32, f32, C.c_int32, C.c_int32, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_int32, f32, C.c_int32, C.c_int32, i64, C.c_void_p,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
-    st = lib.umas_value_loss_fwd_bwd(256, 256, 0.0, 1, 4, 64, None, 4, 256, 256, None, 0, 0.0, 0, 0, 256, None, 256, 256,
+    st = lib.umas_value_loss_fwd_bwd(256, 256, 0.0, 1, 4, 64, None, 4, 256, 256, None, 0, 0.0, 0, 0, 0, 256, None, 256, 256,
                                      None, 256, 1 << 20, None)
     assert st == -1 and "clip_eps_v" in lib.umas_last_error().decode()
-    st = lib.umas_value_loss_fwd_bwd(256, 256, 0.0, 1, 4, 64, None, 4, 256, 256, None, 0, 0.2, 0, 0, 256, None, 256, 256,
+    st = lib.umas_value_loss_fwd_bwd(256, 256, 0.0, 1, 4, 64, None, 4, 256, 256, None, 0, 0.2, 0, 0, 0, 256, None, 256, 256,
                                      None, 256, 16, None)
     assert st == -4
     # KL-penalised rewards: alignment and workspace

@@ -284,3 +284,83 @@ def test_minibatch_gradients_accumulate():
         assert abs(float(sg["loss"][0]) - stats_o[0, 0]) <= 1e-2 * max(abs(stats_o[0, 0]), 1e-3)
         P.close(dH.float().cpu().numpy(), dH_o, 1e-2, f"dH of minibatch {k}")
     P.close(dW.cpu().numpy(), dW_o, 1e-2, "accumulated dW")
+
+
+@pytest.mark.parametrize("dtype,entropy_coef", [("bf16", 0.0), ("bf16", 0.02), ("f32", 0.0)])
+def test_micro_batches_add_up_to_the_minibatch(dtype, entropy_coef):
+    """One minibatch cut into three micro-batches of unequal size, each call normalised by the minibatch's
+    row count: loss, dH and the accumulated dW equal the oracle's on the whole minibatch."""
+    if dtype == "f32":      # the float32 configuration (its logits are small enough for the 1e-5 bar): 4 trajectories in 3 parts
+        w, st, s, adv_o, adv, rows, off, off_o, rows_o = ready_case(0, 3, 17, drop=0.0)
+    else:
+        w, st, s, adv_o, adv, rows, off, off_o, rows_o = ready_case(2, 3, 17, n_traj=7, tokens_per_turn=48, models=[(200, 1000, dtype)])
+    d, V = w.models[0].d, w.models[0].V
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    tol = 1e-5 if dtype == "f32" else 1e-2
+    t = w.model_tensors(0)
+    H, W, ids = P.to_dev(t["H"], tdt), P.to_dev(t["W"], tdt), P.to_dev(t["ids"])
+    n = w.model_ntok[0]
+    role_o = st["tok_role"][:n]
+    rr_all = rows_o[int(off_o[0, 0]):int(off_o[0, 3])]
+    S = len(rr_all)
+    sizes = [int(off_o[0, k + 1] - off_o[0, k]) for k in range(3)]
+    assert len(set(sizes)) > 1, "the micro-batches must differ in size"
+    logp_o, lse_o, ent_o = orc.score(t["H"], t["W"], t["ids"], rr_all)
+    logp_old = (logp_o + t["noise"]).astype(np.float32)
+    stats_o, g_o = orc.ppo_loss_variants(logp_o, logp_old, adv_o[:n], ent_o, rr_all, role_o, w.n_roles, w.clip_eps,
+                                         entropy_coef=entropy_coef)
+    dH_o, dW_o = orc.lm_head_backward_entropy(t["H"], t["W"], t["ids"], lse_o, ent_o, g_o, entropy_coef, S, rr_all)
+    dW = torch.empty((V, d), dtype=torch.float32, device="cuda")
+    dH_sum = np.zeros(t["H"].shape)
+    loss_sum, n_sum = 0.0, 0
+    for k in range(3):
+        a, e = int(off_o[0, k]), int(off_o[0, k + 1])
+        stats, logp_new, dH, _ = umas.umas_ppo_loss_fwd_bwd(H, W, ids, rows[a:e], P.to_dev(logp_old), adv[:n].contiguous(),
+                                                            s.tok_role[:n].contiguous(), w.n_roles, w.clip_eps,
+                                                            entropy_coef=entropy_coef, accumulate_dW=(k > 0), norm_rows=S, dW=dW)
+        torch.cuda.synchronize()
+        sg = umas.read_stats(stats)
+        loss_sum += float(sg["loss"][0])
+        n_sum += int(sg["n_scored"][0])
+        dH_k = dH.float().cpu().numpy().astype(np.float64)
+        assert not dH_k[np.setdiff1d(np.arange(n), rows_o[a:e])].any()
+        dH_sum += dH_k
+    assert n_sum == S
+    assert abs(loss_sum - stats_o[0, 0]) <= tol * max(abs(stats_o[0, 0]), 1e-3)
+    P.close(dH_sum, dH_o, tol, "dH over the micro-batches")
+    P.close(dW.cpu().numpy(), dW_o, tol, "dW accumulated over the micro-batches")
+    with pytest.raises(umas.UmasError):
+        umas.umas_ppo_loss_fwd_bwd(H, W, ids, rows[:sizes[0]], P.to_dev(logp_old), adv[:n].contiguous(),
+                                   s.tok_role[:n].contiguous(), w.n_roles, w.clip_eps, norm_rows=sizes[0] - 1)
+
+
+def test_critic_micro_batches_add_up_to_the_minibatch():
+    w, st, s, adv_o, adv, rows, off, off_o, rows_o = ready_case(2, 3, 19, n_traj=7, tokens_per_turn=48, models=[(200, 1000, "bf16")])
+    rho, st2, r, adv2, ret_o = P.oracle_front(w)
+    _, _, ret = P.gpu_front(w)
+    t, c = w.model_tensors(0), w.critic_tensors(0)
+    n = w.model_ntok[0]
+    rr_all = rows_o[int(off_o[0, 0]):int(off_o[0, 3])]
+    S = len(rr_all)
+    bias = float(c["bias"])
+    V_o = orc.value_head(t["H"], c["w"], bias, rr_all)
+    V_old = (V_o + c["v_noise"]).astype(np.float32)
+    stats_o, g_o = orc.value_loss(V_o, V_old, ret_o[:n], rr_all, st["tok_role"][:n], w.n_roles, 0.1)
+    dH_o, dw_o, db_o = orc.value_head_backward(t["H"], c["w"], g_o, rr_all)
+    H, wv = P.to_dev(t["H"], torch.bfloat16), P.to_dev(c["w"], torch.bfloat16)
+    dw = torch.empty(200, dtype=torch.float32, device="cuda")
+    db = torch.empty(1, dtype=torch.float32, device="cuda")
+    dH = torch.zeros_like(H)
+    loss_sum = 0.0
+    for k in range(3):
+        a, e = int(off_o[0, k]), int(off_o[0, k + 1])
+        stats, _, _, _, _ = umas.umas_value_loss_fwd_bwd(H, wv, bias, rows[a:e], P.to_dev(V_old), ret[:n].contiguous(),
+                                                         s.tok_role[:n].contiguous(), w.n_roles, 0.1, accumulate_dH=True,
+                                                         accumulate_dw=(k > 0), norm_rows=S, dH=dH, dw=dw, db=db)
+        torch.cuda.synchronize()
+        loss_sum += float(umas.read_value_stats(stats)["loss"][0])
+    assert abs(loss_sum - stats_o[0, 0]) <= 1e-2 * max(abs(stats_o[0, 0]), 1e-3)
+    row_abs = 2e-2 / S * float(np.linalg.norm(c["w"].astype(np.float64)))
+    P.close(dH.float().cpu().numpy(), dH_o, 1e-2, "dH over the micro-batches", row_abs=row_abs)
+    P.close(dw.cpu().numpy(), dw_o, 1e-2, "dw accumulated over the micro-batches")
+    assert abs(float(db.item()) - db_o) <= 1e-2 * max(abs(db_o), np.abs(g_o).sum() * 1e-2 + 1e-12)
