@@ -16,10 +16,12 @@
  *     metadata).  FAT tensors (masks, rewards per token, hidden states, weights, outputs,
  *     workspace) are DEVICE pointers, caller-allocated; the library owns no memory.
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default
- *     stream).  No call synchronises with the device, except umas_assign_token_rewards, which
- *     copies the thin host arrays to the device and waits for those copies (not for its
- *     kernels) so that the caller may free them on return.  Results, including loss
- *     statistics, stay on the device.
+ *     stream).  No call synchronises with the device, except umas_assign_token_rewards and
+ *     umas_ready_batch, which copy the thin host arrays to the device and wait for those copies
+ *     (not for their kernels) so that the caller may free them on return.  Results, including
+ *     loss statistics, stay on the device.  Every other call only launches kernels (memory is
+ *     cleared by fill kernels, never by memset nodes), so it may be recorded into a HIP graph
+ *     as long as profiling (umas_profile_enable) is off.
  *   - Every call returns a umas_status.  Argument errors are found on the host before any
  *     launch, leave outputs untouched and set a thread-local message (umas_last_error).
  *   - Workspace sizes come from the umas_*_workspace_bytes queries; workspace must be
