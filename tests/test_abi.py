@@ -92,6 +92,10 @@ def test_bad_scalar_arguments(lib):
     assert lib.umas_policy_logprobs(256, 256, 7, 4, 8, 8, 256, None, 4, 256, 256, None, 256, 1 << 20, None) == -3
     assert lib.umas_policy_logprobs(256, 256, 1, 4, 12, 8, 256, None, 4, 256, 256, None, 256, 1 << 20, None) == -2
     assert "d % 8" in lib.umas_last_error().decode()
+    # bf16 H of 4 GiB or more is refused (32-bit buffer offsets); one row less gets as far as the workspace check
+    assert lib.umas_policy_logprobs(256, 256, 1, 1 << 28, 8, 8, 256, None, 1 << 28, 256, 256, None, 256, 1 << 20, None) == -2
+    assert "4 GiB" in lib.umas_last_error().decode()
+    assert lib.umas_policy_logprobs(256, 256, 1, (1 << 28) - 1, 8, 8, 256, None, (1 << 28) - 1, 256, 256, None, 256, 1 << 20, None) == -4
     # clip_eps outside (0,1)
     st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 1.5, 0.0, 0.0, 0, 0, 256, None,
                                    256, 256, 256, 1 << 30, None)

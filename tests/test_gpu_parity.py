@@ -355,3 +355,51 @@ def test_accumulate_dw_adds_to_existing_gradient():
     torch.cuda.synchronize()
     # float atomics add the one-hot rows in any order: equal up to float32 rounding of the sums
     assert torch.allclose(dW2, 2 * dW1, rtol=1e-5, atol=1e-6 * dW1.abs().max().item())
+
+
+def test_hidden_states_just_under_the_4_gib_limit():
+    """bf16 H is addressed with 32-bit byte offsets: the largest H the library accepts (one row short of 4 GiB),
+    with the selected rows at its start, in the middle and at its very end."""
+    d, V = 2048, 1000
+    n_rows = (1 << 32) // (2 * d) - 1
+    w = wl.make_workload(1, n_traj=3, tokens_per_turn=80, models=[(d, V, "bf16")])
+    t = w.model_tensors(0)
+    n = len(t["ids"])
+    assert n == 720
+    pos = np.concatenate([np.arange(200), n_rows // 2 + 3 * np.arange(220), n_rows - 300 + np.arange(300)]).astype(np.int32)
+    rowsel = P.to_dev(pos)
+    idx = rowsel.long()
+    H = torch.zeros((n_rows, d), dtype=torch.bfloat16, device="cuda")
+    H[idx] = P.to_dev(t["H"], torch.bfloat16)
+    W = P.to_dev(t["W"], torch.bfloat16)
+    ids = torch.zeros(n_rows, dtype=torch.int32, device="cuda")
+    ids[idx] = P.to_dev(t["ids"]).int()
+    with pytest.raises(umas.UmasError):              # one more row reaches 4 GiB: refused before any launch
+        umas.umas_policy_logprobs(torch.empty((n_rows + 1, d), dtype=torch.bfloat16, device="cuda"), W,
+                                  torch.zeros(n_rows + 1, dtype=torch.int32, device="cuda"))
+    logp, lse, ent = umas.umas_policy_logprobs(H, W, ids, rowsel)
+    logp_o, lse_o, ent_o = orc.score(t["H"], t["W"], t["ids"])
+    assert np.abs(logp[idx].cpu().numpy() - logp_o).max() <= 2e-2
+    assert np.abs(ent[idx].cpu().numpy() - ent_o).max() <= 2e-2
+    assert int((logp != 0).sum().item()) <= n and not logp[300:n_rows // 2].any().item()
+    rng = np.random.default_rng(5)
+    adv_o = rng.normal(size=n).astype(np.float32)
+    logp_old_o = (logp_o + t["noise"]).astype(np.float32)
+    adv = torch.zeros(n_rows, device="cuda")
+    adv[idx] = P.to_dev(adv_o)
+    logp_old = torch.zeros(n_rows, device="cuda")
+    logp_old[idx] = P.to_dev(logp_old_o)
+    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv, None, 0, 0.2)
+    torch.cuda.synchronize()
+    st_o, g_o = orc.ppo_loss(logp_o, logp_old_o, adv_o, ent_o, None, np.zeros(n, np.int32), 0, 0.2)
+    dH_o, dW_o = orc.lm_head_backward(t["H"], t["W"], t["ids"], lse_o, g_o)
+    sg = umas.read_stats(stats)
+    assert int(sg["n_scored"][0]) == n
+    assert abs(float(sg["loss"][0]) - st_o[0, 0]) <= 1e-2 * max(abs(st_o[0, 0]), 1e-3)
+    P.close(dH[idx].float().cpu().numpy(), dH_o, 1e-2, "dH of the selected rows")
+    P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW")
+    touched = torch.zeros(n_rows, dtype=torch.bool, device="cuda")
+    for a in range(0, n_rows, 1 << 17):              # rows of dH that hold anything: only selected ones
+        touched[a:a + (1 << 17)] = (dH[a:a + (1 << 17)] != 0).any(dim=1)
+    touched[idx] = False
+    assert not touched.any().item(), "dH was written outside the selected rows"
