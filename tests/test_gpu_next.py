@@ -100,6 +100,14 @@ def test_critic_full_width_rows():
     run_critic(3, n_traj=3, tokens_per_turn=37, models=[(2048, 512, "bf16"), (3584, 512, "bf16")])
 
 
+def test_critic_widest_rows():
+    # the widest rows the value head takes: 8192 (bf16, 16 column vectors per lane) and 4096 (float32)
+    run_critic(3, n_traj=2, tokens_per_turn=23, models=[(8192, 256, "bf16"), (4096, 256, "f32")])
+    H = torch.zeros((4, 8200), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(umas.UmasError):
+        umas.umas_values(H, torch.zeros(8200, dtype=torch.bfloat16, device="cuda"))
+
+
 def test_critic_empty_selection_and_errors():
     H = torch.zeros((8, 64), dtype=torch.bfloat16, device="cuda")
     wv = torch.ones(64, dtype=torch.bfloat16, device="cuda")

@@ -403,3 +403,37 @@ def test_hidden_states_just_under_the_4_gib_limit():
         touched[a:a + (1 << 17)] = (dH[a:a + (1 << 17)] != 0).any(dim=1)
     touched[idx] = False
     assert not touched.any().item(), "dH was written outside the selected rows"
+
+
+@pytest.mark.parametrize("d,V,n", [(1, 2, 1), (3, 300, 5), (64, 513, 260), (130, 7, 300), (8192, 300, 40)])
+def test_float32_shapes(d, V, n):
+    """The float32 path has no alignment rule for d: odd sizes, a two-token vocabulary, one row, and the widest row it
+    takes.  Logits stay small (rows of H have unit RMS, W ~ N(0, 0.02)), as in the float32 configuration, so that the
+    float32 bar applies; a sequential float32 dot product of 8192 terms is allowed 4e-5."""
+    tol = 1e-5 if d <= 1024 else 4e-5
+    rng = np.random.default_rng(7000 + d)
+    H = rng.normal(size=(n, d)).astype(np.float32)
+    H /= np.sqrt((H * H).mean(axis=1, keepdims=True))
+    W = (0.02 * rng.normal(size=(V, d))).astype(np.float32)
+    ids = rng.integers(0, V, size=n).astype(np.int32)
+    rowsel = np.sort(rng.choice(n, size=max(1, (2 * n) // 3), replace=False)).astype(np.int32) if n > 1 else None
+    sel = rowsel if rowsel is not None else np.arange(n, dtype=np.int32)
+    adv = rng.normal(size=n).astype(np.float32)
+    logp_o, lse_o, ent_o = orc.score(H, W, ids, sel)
+    logp_old = (logp_o + 0.1 * rng.normal(size=n)).astype(np.float32)
+    st_o, g_o = orc.ppo_loss(logp_o, logp_old, adv, ent_o, sel, np.zeros(n, np.int32), 0, 0.2)
+    dH_o, dW_o = orc.lm_head_backward(H, W, ids, lse_o, g_o, sel)
+    Hd, Wd, idd = P.to_dev(H), P.to_dev(W), P.to_dev(ids)
+    rs = None if rowsel is None else P.to_dev(rowsel)
+    logp, lse, ent = umas.umas_policy_logprobs(Hd, Wd, idd, rs)
+    P.close(logp.cpu().numpy(), logp_o, tol, "logp")
+    P.close(ent.cpu().numpy(), ent_o, tol, "entropy")
+    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(Hd, Wd, idd, rs, P.to_dev(logp_old), P.to_dev(adv), None, 0, 0.2)
+    sg = umas.read_stats(stats)
+    assert int(sg["n_scored"][0]) == len(sel)
+    assert abs(float(sg["loss"][0]) - st_o[0, 0]) <= tol * max(abs(st_o[0, 0]), 1e-3)
+    P.close(dH.cpu().numpy(), dH_o, tol, "dH")
+    P.close(dW.cpu().numpy(), dW_o, tol, "dW")
+    with pytest.raises(umas.UmasError):
+        umas.umas_policy_logprobs(torch.zeros((2, 8200), device="cuda"), torch.zeros((4, 8200), device="cuda"),
+                                  torch.zeros(2, dtype=torch.int32, device="cuda"))
