@@ -438,3 +438,9 @@ def test_float32_shapes(d, V, n):
     with pytest.raises(umas.UmasError):
         umas.umas_policy_logprobs(torch.zeros((2, 8200), device="cuda"), torch.zeros((4, 8200), device="cuda"),
                                   torch.zeros(2, dtype=torch.int32, device="cuda"))
+
+
+def test_bf16_wide_hidden_sizes():
+    # 8192 (128 K steps per tile, 32 column tiles of dH and dW) and 4104 (a ragged K tail and a ragged column tile)
+    P.run_config_parity(1, verbose=True, n_traj=16, tokens_per_turn=40, models=[(8192, 700, "bf16")])
+    P.run_config_parity(2, verbose=True, n_traj=4, tokens_per_turn=48, models=[(4104, 300, "bf16")])
