@@ -198,10 +198,14 @@ size_t umas_ppo_loss_workspace_bytes(int64_t n_sel, int32_t d, int32_t V, umas_d
  *   dH             DEVICE [n_rows, d] in the dtype of H; rows not selected are set to 0
  *   dW             DEVICE float [V, d]; accumulate_dW = 0 overwrites, 1 adds
  * clip_eps must lie in (0,1).
- * Two optional terms (stabilisers of the PPO family; both off at 0):
+ * Optional terms (stabilisers of the PPO family; all off at 0):
  *   dual_clip c > 1: for A < 0 the row's term is capped at -A c, with no gradient where the cap binds;
  *   entropy_coef k >= 0: the loss becomes L_clip - k mean entropy (stats.loss includes it) and
  *     dz_iv gains (k / n_sel) p_iv (log p_iv + entropy_i), p = softmax(z_i).
+ *   kl_coef b >= 0 with logp_ref DEVICE float [n_rows] (NULL when b = 0): the loss gains b times the mean over the
+ *     scored rows of e^x - x - 1, x = logp_ref - logp (the non-negative estimate of KL(pi || pi_ref) whose mean over
+ *     tokens drawn from pi is that divergence), and g gains b (1 - e^x) / n_sel.  The penalty may instead be folded into
+ *     the rewards (umas_kl_rewards).  With b > 0 every scored row has a gradient.
  * norm_rows: 0, or the number of rows the token mean is taken over when the call is one micro-batch of a
  *   minibatch of norm_rows >= n_sel scored rows (gradient accumulation over the parts of a ready batch, paragraph
  *   "Model-specific updates and synchronization"): g, the entropy term and stats[0].loss are divided by it in
@@ -214,7 +218,7 @@ umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_dtype dtype
                                   int64_t n_sel, const float* logp_old, const float* adv,
                                   const int32_t* tok_role, int32_t n_roles, float clip_eps,
                                   float entropy_coef, float dual_clip, int32_t accumulate_dW, int64_t norm_rows,
-                                  umas_loss_stats* stats,
+                                  const float* logp_ref, float kl_coef, umas_loss_stats* stats,
                                   float* logp_new, void* dH, float* dW,
                                   void* workspace, size_t workspace_bytes, void* hip_stream);
 

@@ -428,15 +428,19 @@ def whiten_advantages(adv, tok_mask, tok_role, model_tok_off, n_roles, scope, ep
 # Surrogate variants: dual clip and entropy bonus
 # --------------------------------------------------------------------------------------
 def ppo_loss_variants(logp, logp_old, adv, entropy, rowsel, tok_role, n_roles, clip_eps, dual_clip=0.0,
-                      entropy_coef=0.0):
-    """The clipped surrogate with two optional terms.
+                      entropy_coef=0.0, kl_coef=0.0, logp_ref=None):
+    """The clipped surrogate with its optional terms.
 
     dual_clip c > 1: for A < 0 the per-row term max(-A ratio, -A clip(ratio)) is capped at -A c
     (the gradient vanishes where the cap is strictly smaller).  entropy_coef > 0: the loss
     becomes L_clip - entropy_coef * mean entropy; its gradient reaches the logits directly
     (lm_head_backward_entropy), g stays d L_clip / d logp.  The clip fraction counts rows whose
-    active term is not the unclipped one.  Returns (stats [1+n_roles, 5], g) like ppo_loss; stats[:, 0]
-    includes the entropy term.
+    active term is not the unclipped one.  kl_coef > 0: the reference-policy log-probs (listed with
+    the quantities of the update in "Advantage computation and policy evaluation"; the paper prints
+    no penalty) enter the loss as kl_coef * mean(e^x - x - 1), x = logp_ref - logp: each term is
+    non-negative and its expectation over tokens drawn from the policy is KL(policy || reference);
+    d/dlogp of a term is 1 - e^x, which is added to g (divided by S).
+    Returns (stats [1+n_roles, 5], g) like ppo_loss; stats[:, 0] includes the entropy and KL terms.
     """
     n = len(logp)
     rows = np.arange(n) if rowsel is None else np.asarray(rowsel, dtype=np.int64)
@@ -460,6 +464,10 @@ def ppo_loss_variants(logp, logp_old, adv, entropy, rowsel, tok_role, n_roles, c
         L = np.where(capped, cap, L)
         active_unclipped &= ~capped
     g[rows] = np.where(active_unclipped, -A * ratio, 0.0) / S
+    if kl_coef > 0.0:
+        x = np.asarray(logp_ref, np.float64)[rows] - lp
+        L = L + kl_coef * (np.exp(x) - x - 1.0)
+        g[rows] += kl_coef * (1.0 - np.exp(x)) / S
     role = np.asarray(tok_role)[rows]
     for k in range(1 + n_roles):
         sel = np.ones(S, bool) if k == 0 else (role == k - 1)

@@ -128,7 +128,8 @@ def load_library():
     lib.umas_ppo_loss_fwd_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int32, C.c_int32,
                                           C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_int32, C.c_float, C.c_float, C.c_float, C.c_int32, C.c_int64, C.c_void_p,
-                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+                                          C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                          C.c_void_p]
     _LIB = lib
     return lib
 
@@ -259,8 +260,8 @@ def ppo_workspace_bytes(n_sel, d, V, dtype: torch.dtype, n_roles, minimum=False)
 
 
 def umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv, tok_role, n_roles, clip_eps, *, entropy_coef=0.0,
-                          dual_clip=0.0, accumulate_dW=False, norm_rows=0, dW=None, dH=None, logp_new=None, stats=None,
-                          workspace=None):
+                          dual_clip=0.0, accumulate_dW=False, norm_rows=0, logp_ref=None, kl_coef=0.0, dW=None, dH=None,
+                          logp_new=None, stats=None, workspace=None):
     lib = load_library()
     n_rows, d = H.shape
     V = W.shape[0]
@@ -281,7 +282,7 @@ def umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv, tok_role, n_roles, c
     _check(lib, lib.umas_ppo_loss_fwd_bwd(H.data_ptr(), W.data_ptr(), dt, n_rows, d, V, ids.data_ptr(), sel,
                                           n_sel, logp_old.data_ptr(), adv.data_ptr(), _ptr(tok_role), n_roles,
                                           clip_eps, entropy_coef, dual_clip, 1 if accumulate_dW else 0, int(norm_rows),
-                                          stats.data_ptr(),
+                                          _ptr(logp_ref), kl_coef, stats.data_ptr(),
                                           logp_new.data_ptr(), dH.data_ptr(), dW.data_ptr(), ws.data_ptr(), ws.numel(),
                                           _stream()))
     return stats, logp_new, dH, dW

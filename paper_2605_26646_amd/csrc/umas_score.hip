@@ -389,7 +389,8 @@ __global__ void __launch_bounds__(kRowBlock)
 k_ppo_rows(int64_t norm, int64_t n_begin, int64_t n_end, const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids, int V,
            const float* __restrict__ logp_c, const float* __restrict__ ent_c, const float* __restrict__ logp_old,
            const float* __restrict__ adv, const int32_t* __restrict__ tok_role, int n_roles, float clip_eps,
-           float dual_clip, float k_ent, int label_apart, const float* __restrict__ lse_c, float* __restrict__ g_c,
+           float dual_clip, float k_ent, const float* __restrict__ logp_ref, float kl_coef, int label_apart,
+           const float* __restrict__ lse_c, float* __restrict__ g_c,
            float* __restrict__ a_c, float* __restrict__ kz_c, double* __restrict__ blk_stats) {
   extern __shared__ double s_acc[];   // [(1+n_roles) * kStat]
   const int nacc = (1 + n_roles) * kStat;
@@ -415,6 +416,11 @@ k_ppo_rows(int64_t norm, int64_t n_begin, int64_t n_end, const int32_t* __restri
       }
       g = unclipped ? u / static_cast<float>(norm) : 0.f;
       clipped = unclipped ? 0.f : 1.f;
+      if (kl_coef != 0.f) {   // penalty towards the reference policy: kl_coef (e^x - x - 1), x = logp_ref - logp
+        const float x = logp_ref[row] - lp, ex = __expf(x);
+        L += kl_coef * (ex - x - 1.f);
+        g += kl_coef * (1.f - ex) / static_cast<float>(norm);
+      }
       en = ent_c[n];
       kl = lo - lp;
     }
@@ -472,7 +478,7 @@ k_ppo_stats(int nblk, int n_roles, float entropy_coef, int64_t norm_rows, const 
 }
 
 // ------------------------------------------------------------------ bf16: blocks of rows that have a gradient
-// A selected row whose advantage is 0 has g = 0 and (without an entropy bonus) no gradient at all; group-normalised
+// A selected row whose advantage is 0 has g = 0 and (without an entropy bonus or a KL term) no gradient at all; group-normalised
 // outcome rewards make whole trajectory groups such rows.  The keeping pass therefore works on the chunk's live blocks
 // of 256 selected rows only: E and the scaled copy of H hold them packed, dH has as many row tiles and dW as many K
 // steps as there are, and everything that depends on their number is worked out on the device.
@@ -1146,7 +1152,8 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
                                              int32_t V, const int32_t* ids, const int32_t* rowsel, int64_t n_sel,
                                              const float* logp_old, const float* adv, const int32_t* tok_role,
                                              int32_t n_roles, float clip_eps, float entropy_coef, float dual_clip,
-                                             int32_t accumulate_dW, int64_t norm_rows, umas_loss_stats* stats, float* logp_new, void* dH,
+                                             int32_t accumulate_dW, int64_t norm_rows, const float* logp_ref,
+                                             float kl_coef, umas_loss_stats* stats, float* logp_new, void* dH,
                                              float* dW, void* workspace, size_t workspace_bytes, void* hip_stream) {
   umas_status s = check_model_args(H, W, dtype, n_rows, d, V, ids, rowsel, n_sel);
   if (s != UMAS_OK) return s;
@@ -1161,6 +1168,8 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
   UMAS_REQUIRE(n_sel < (1LL << 31), UMAS_ESHAPE, "at most 2^31-1 selected rows");
   UMAS_REQUIRE(norm_rows == 0 || norm_rows >= n_sel, UMAS_EINVAL, "norm_rows=%lld must be 0 or at least n_sel=%lld",
                static_cast<long long>(norm_rows), static_cast<long long>(n_sel));
+  UMAS_REQUIRE(kl_coef >= 0.f, UMAS_EINVAL, "kl_coef=%g must not be negative", static_cast<double>(kl_coef));
+  UMAS_REQUIRE(kl_coef == 0.f || logp_ref || n_rows == 0, UMAS_EINVAL, "kl_coef > 0 needs logp_ref");
   s = check_ws(workspace, workspace_bytes, umas_ppo_loss_workspace_bytes_min(n_sel, d, V, dtype, n_roles));
   if (s != UMAS_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -1207,7 +1216,8 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
     if (s != UMAS_OK) return s;
     hipLaunchKernelGGL(k_ppo_rows, dim3(nblk), dim3(kRowBlock), (1 + n_roles) * kStat * sizeof(double), st, norm,
                        static_cast<int64_t>(0), n_sel, rowsel, ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv,
-                       tok_role, n_roles, clip_eps, dual_clip, k_ent, dtype == UMAS_BF16 ? 1 : 0, w.score.lse_c, w.g_c, w.a_c, w.kz_c,
+                       tok_role, n_roles, clip_eps, dual_clip, k_ent, logp_ref, kl_coef, dtype == UMAS_BF16 ? 1 : 0, w.score.lse_c,
+                       w.g_c, w.a_c, w.kz_c,
                        w.blk_stats);
     UMAS_LAUNCHED("k_ppo_rows");
   } else {
@@ -1225,8 +1235,8 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
       const int tiles_r = static_cast<int>(mcp / 256);
       uint16_t* E = reinterpret_cast<uint16_t*>(w.chunk);
       uint16_t* Hs = reinterpret_cast<uint16_t*>(w.chunk + align_up(static_cast<size_t>(mcp) * Vp * 2));
-      hipLaunchKernelGGL(k_live_scan, dim3(1), dim3(512), 0, st, static_cast<int>(c0 >> 8), tiles_r, rows, 0, tiles_v, tiles_d, Vp,
-                         max_groups, w.blk_live, w.blk_cidx, w.blk_orig, w.live);
+      hipLaunchKernelGGL(k_live_scan, dim3(1), dim3(512), 0, st, static_cast<int>(c0 >> 8), tiles_r, rows, kl_coef != 0.f ? 1 : 0, tiles_v,
+                         tiles_d, Vp, max_groups, w.blk_live, w.blk_cidx, w.blk_orig, w.live);   // a KL term gives every row a gradient
       UMAS_LAUNCHED("k_live_scan");
       hipLaunchKernelGGL(k_score_keep_tiles, dim3(tile_grid<kGM, kGN>(tiles_v, tiles_r, kTilesPerWg)), dim3(Cfg::T), 0, st,
                          Wb, Hb, d, V, rowsel, c0, rows, ids, tiles_v, tiles_r, w.score.partial, n_pad, w.cref, E, Vp, w.flags,
@@ -1238,7 +1248,8 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
       UMAS_LAUNCHED("k_score_finalize");
       hipLaunchKernelGGL(k_ppo_rows, dim3(cdiv(rows, kRowBlock)), dim3(kRowBlock), (1 + n_roles) * kStat * sizeof(double),
                          st, norm, c0, c0 + rows, rowsel, ids, V, w.score.logp_c, w.score.ent_c, logp_old, adv, tok_role,
-                         n_roles, clip_eps, dual_clip, k_ent, 1, w.score.lse_c, w.g_c, w.a_c, w.kz_c, w.blk_stats);
+                         n_roles, clip_eps, dual_clip, k_ent, logp_ref, kl_coef, 1, w.score.lse_c, w.g_c, w.a_c, w.kz_c,
+                         w.blk_stats);
       UMAS_LAUNCHED("k_ppo_rows");
       // blocks of rows the scoring pass flagged (a logit far above the row's reference) get dz the long way
       hipLaunchKernelGGL(k_dz_flagged, dim3(kFlaggedGrid), dim3(Cfg::T), 0, st, Wb, Hb, d, V, rowsel, c0, rows,

@@ -97,24 +97,31 @@ def test_bad_scalar_arguments(lib):
     assert "4 GiB" in lib.umas_last_error().decode()
     assert lib.umas_policy_logprobs(256, 256, 1, (1 << 28) - 1, 8, 8, 256, None, (1 << 28) - 1, 256, 256, None, 256, 1 << 20, None) == -4
     # clip_eps outside (0,1)
-    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 1.5, 0.0, 0.0, 0, 0, 256, None,
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 1.5, 0.0, 0.0, 0, 0, None, 0.0, 256, None,
                                    256, 256, 256, 1 << 30, None)
     assert st == -1 and "clip_eps" in lib.umas_last_error().decode()
     # workspace too small
-    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0.0, 0, 0, 256, None,
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0.0, 0, 0, None, 0.0, 256, None,
                                    256, 256, 256, 16, None)
     assert st == -4
     # dual clip constants in (0, 1] and a negative entropy coefficient are refused
-    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0.5, 0, 0, 256, None,
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0.5, 0, 0, None, 0.0, 256, None,
                                    256, 256, 256, 1 << 30, None)
     assert st == -1 and "dual_clip" in lib.umas_last_error().decode()
-    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, -0.1, 0.0, 0, 0, 256, None,
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, -0.1, 0.0, 0, 0, None, 0.0, 256, None,
                                    256, 256, 256, 1 << 30, None)
     assert st == -1 and "entropy_coef" in lib.umas_last_error().decode()
     # a normaliser smaller than the call's own row count is refused
-    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0.0, 0, 3, 256, None,
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0.0, 0, 3, None, 0.0, 256, None,
                                    256, 256, 256, 1 << 30, None)
     assert st == -1 and "norm_rows" in lib.umas_last_error().decode()
+    # a KL coefficient without reference log-probs, and a negative one
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0.0, 0, 0, None, 0.1, 256, None,
+                                   256, 256, 256, 1 << 30, None)
+    assert st == -1 and "logp_ref" in lib.umas_last_error().decode()
+    st = lib.umas_ppo_loss_fwd_bwd(256, 256, 0, 4, 8, 8, 256, None, 4, 256, 256, None, 0, 0.2, 0.0, 0.0, 0, 0, 256, -0.1, 256, None,
+                                   256, 256, 256, 1 << 30, None)
+    assert st == -1 and "kl_coef" in lib.umas_last_error().decode()
     from paper_2605_26646_amd import binding as b
     s = b._Streams(*([1] * 16))
     assert lib.umas_advantages(C.addressof(s), 10, 1, None, 1.0, 1.0, 1.0, 3, 256, 256, 256, 1 << 20, None) == -1

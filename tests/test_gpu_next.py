@@ -185,11 +185,14 @@ def test_shaping_empty_and_errors():
     assert not out.cpu().numpy().any()
 
 
-def variants_case(cfg, entropy_coef, dual_clip, noise_scale, **kw):
-    """Dual clip and entropy bonus of the surrogate and its backward, per model."""
+def variants_case(cfg, entropy_coef, dual_clip, noise_scale, kl_coef=0.0, zero_adv=False, **kw):
+    """Dual clip, entropy bonus and KL term of the surrogate and its backward, per model."""
     w = wl.make_workload(cfg, **kw)
     rho, st, r, adv_o, ret_o = P.oracle_front(w)
     s, adv, ret = P.gpu_front(w)
+    if zero_adv:                                     # only the KL term is left: every row still has a gradient
+        adv_o = np.zeros_like(adv_o)
+        adv = torch.zeros_like(adv)
     for m in range(w.n_models):
         spec = w.models[m]
         tdt = torch.float32 if spec.dtype == "f32" else torch.bfloat16
@@ -201,8 +204,9 @@ def variants_case(cfg, entropy_coef, dual_clip, noise_scale, **kw):
         role_o = st["tok_role"][a:e]
         logp_o, lse_o, ent_o = orc.score(t["H"], t["W"], t["ids"], rows_o)
         logp_old = (logp_o + noise_scale * t["noise"]).astype(np.float32)
+        logp_ref = (logp_o + w.critic_tensors(m)["ref_noise"]).astype(np.float32) if kl_coef > 0 else None
         stats_o, g_o = orc.ppo_loss_variants(logp_o, logp_old, adv_o[a:e], ent_o, rows_o, role_o, w.n_roles, w.clip_eps,
-                                             dual_clip, entropy_coef)
+                                             dual_clip, entropy_coef, kl_coef, logp_ref)
         plain_o, g_plain = orc.ppo_loss(logp_o, logp_old, adv_o[a:e], ent_o, rows_o, role_o, w.n_roles, w.clip_eps)
         if dual_clip > 0:
             assert np.abs(g_o - g_plain).max() > 0, "the case must make the dual clip bind"
@@ -210,16 +214,25 @@ def variants_case(cfg, entropy_coef, dual_clip, noise_scale, **kw):
         H, W, ids = P.to_dev(t["H"], tdt), P.to_dev(t["W"], tdt), P.to_dev(t["ids"])
         stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(
             H, W, ids, s.rowsel[ra:re], P.to_dev(logp_old), adv[a:e].contiguous(), s.tok_role[a:e].contiguous(), w.n_roles,
-            w.clip_eps, entropy_coef=entropy_coef, dual_clip=dual_clip)
+            w.clip_eps, entropy_coef=entropy_coef, dual_clip=dual_clip, kl_coef=kl_coef,
+            logp_ref=None if logp_ref is None else P.to_dev(logp_ref))
         torch.cuda.synchronize()
         sg = umas.read_stats(stats)
+        if zero_adv:
+            assert np.abs(dH_o[rows_o]).max(axis=1).min() > 0, "every scored row must have a gradient"
         for k in range(1 + w.n_roles):
             assert int(sg["n_scored"][k]) == int(stats_o[k, 4])
             o = stats_o[k, 0]
             # the loss is a mean of terms of size |A| ratio and of coef * entropy
+            # (a KL term is a mean of non-negative terms: its own size)
             assert abs(float(sg["loss"][k]) - o) <= tol * max(abs(o), abs(stats_o[0, 0]), entropy_coef * abs(stats_o[k, 2]), 1e-3)
             assert abs(float(sg["clip_frac"][k]) - stats_o[k, 1]) <= max(tol * stats_o[k, 1], 2.0 / max(stats_o[k, 4], 1))
-        P.close(dH.float().cpu().numpy(), dH_o, tol, "dH")
+        # The KL part of g, b (1 - e^x) / S with x = logp_ref - logp, carries the absolute error of logp itself (a few
+        # units in the last place of a float32 |logp| of about 6), whatever is left of 1 - e^x for a small x: an absolute
+        # allowance per row of that error times the largest possible norm of d logp / d h.
+        lp_err = 4e-6 if spec.dtype == "f32" else 1e-4
+        row_abs = kl_coef * lp_err / max(len(rows_o), 1) * 2.0 * float(np.linalg.norm(t["W"].astype(np.float64), axis=1).max())
+        P.close(dH.float().cpu().numpy(), dH_o, tol, "dH", row_abs=row_abs)
         P.close(dW.cpu().numpy(), dW_o, tol, "dW")
 
 
@@ -229,6 +242,13 @@ def test_surrogate_variants():
     variants_case(0, 0.02, 2.0, 14.0)
     variants_case(2, 0.01, 3.0, 14.0, n_traj=8, tokens_per_turn=48, models=[(200, 1000, "bf16")])
     variants_case(3, 0.05, 0.0, 1.0, n_traj=6, tokens_per_turn=40, models=[(128, 700, "bf16"), (200, 1000, "bf16")])
+
+
+def test_kl_loss_term():
+    variants_case(0, 0.0, 0.0, 1.0, kl_coef=0.1)                                # float32
+    variants_case(2, 0.0, 0.0, 1.0, kl_coef=0.1, n_traj=8, tokens_per_turn=48, models=[(200, 1000, "bf16")])   # single pass
+    variants_case(1, 0.0, 0.0, 1.0, kl_coef=0.2, zero_adv=True, n_traj=16, tokens_per_turn=40, models=[(200, 1000, "bf16")])
+    variants_case(3, 0.02, 3.0, 14.0, kl_coef=0.05, n_traj=6, tokens_per_turn=40, models=[(128, 700, "bf16"), (200, 1000, "bf16")])
 
 
 def ready_case(cfg, n_minibatch, seed, drop=0.25, **kw):

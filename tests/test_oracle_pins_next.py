@@ -194,6 +194,46 @@ def test_entropy_bonus_backward_matches_finite_differences():
     assert np.abs(dHz).max() < 1e-15 and np.abs(dWz).max() < 1e-15
 
 
+def test_kl_loss_term_by_hand_expectation_and_finite_differences():
+    n = 3
+    z3 = np.zeros(n, np.int32)
+    # by hand: A = 0 leaves only the penalty; x = ln 2 -> e^x - x - 1 = 1 - ln 2, x = 0 -> 0, x = -ln 2 -> ln 2 - 1/2
+    lp = np.zeros(n)
+    ref = np.array([math.log(2.0), 0.0, -math.log(2.0)])
+    stats, g = orc.ppo_loss_variants(lp, lp, np.zeros(n), np.zeros(n), None, z3, 1, 0.2, kl_coef=0.5, logp_ref=ref)
+    assert abs(stats[0, 0] - 0.5 * ((1 - math.log(2.0)) + 0.0 + (math.log(2.0) - 0.5)) / 3) < 1e-15
+    assert np.allclose(g, 0.5 * np.array([1 - 2.0, 0.0, 1 - 0.5]) / 3, atol=1e-16)
+    # every term is non-negative and vanishes only where the two policies agree on the token
+    rng = np.random.default_rng(41)
+    x = rng.normal(size=1000)
+    assert (np.exp(x) - x - 1 >= 0).all()
+    # its mean over tokens drawn from the policy is KL(policy || reference): exact enumeration of a small distribution
+    p = rng.random(7); p /= p.sum()
+    q = rng.random(7); q /= q.sum()
+    st7, _ = orc.ppo_loss_variants(np.log(p), np.log(p), np.zeros(7), np.zeros(7), None, np.zeros(7, np.int32), 1, 0.2,
+                                   kl_coef=1.0, logp_ref=np.log(q))
+    per_token = np.exp(np.log(q) - np.log(p)) - (np.log(q) - np.log(p)) - 1
+    assert abs(float((p * per_token).sum()) - float((p * np.log(p / q)).sum())) < 1e-14       # the identity itself
+    assert abs(st7[0, 0] - per_token.mean()) < 1e-15                                          # and what the oracle averages
+    # gradient with respect to logp by central differences, with the surrogate active and a row selection
+    n = 9
+    lp, lo, ref = -rng.random(n) * 2, -rng.random(n) * 2, -rng.random(n) * 2
+    A, ent = rng.normal(size=n), rng.random(n)
+    rows = np.array([0, 2, 3, 5, 8], np.int32)
+    role = np.zeros(n, np.int32)
+    f = lambda v: orc.ppo_loss_variants(v, lo, A, ent, rows, role, 1, 0.2, kl_coef=0.3, logp_ref=ref)[0][0, 0]
+    _, g = orc.ppo_loss_variants(lp, lo, A, ent, rows, role, 1, 0.2, kl_coef=0.3, logp_ref=ref)
+    h = 1e-6
+    for i in range(n):
+        e = np.zeros(n); e[i] = h
+        assert abs((f(lp + e) - f(lp - e)) / (2 * h) - g[i]) < 1e-8
+    assert not g[[1, 4, 6, 7]].any()
+    # coefficient 0 is the plain surrogate
+    s0, g0 = orc.ppo_loss(lp, lo, A, ent, rows, role, 1, 0.2)
+    s1, g1 = orc.ppo_loss_variants(lp, lo, A, ent, rows, role, 1, 0.2, kl_coef=0.0, logp_ref=ref)
+    assert np.array_equal(s0, s1) and np.array_equal(g0, g1)
+
+
 # ------------------------------------------------------------------ ready batch
 def _routed(seed, n_traj=7, phi=(0, 1, 0)):
     rng = np.random.default_rng(seed)
