@@ -180,3 +180,11 @@ def test_entry_points_around_the_update_reject_bad_arguments(lib):
     assert st == -1 and "permutation" in lib.umas_last_error().decode()
     assert lib.umas_ready_batch(C.addressof(s), 1, 2, tto.ctypes.data, 2, None, None, 0, 256, 256, 256, 1 << 20, None) == -1
     assert lib.umas_ready_batch(C.addressof(s), 1, 3, tto.ctypes.data, 2, None, None, 1, 256, 256, 256, 1 << 20, None) == -1
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
