@@ -392,3 +392,57 @@ def test_critic_micro_batches_add_up_to_the_minibatch():
     P.close(dH.float().cpu().numpy(), dH_o, 1e-2, "dH over the micro-batches", row_abs=row_abs)
     P.close(dw.cpu().numpy(), dw_o, 1e-2, "dw accumulated over the micro-batches")
     assert abs(float(db.item()) - db_o) <= 1e-2 * max(abs(db_o), np.abs(g_o).sum() * 1e-2 + 1e-12)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_with_optional_terms(seed):
+    """Seeded random shapes around the tile edges with random combinations of the optional terms (entropy bonus, dual
+    clip, KL term, the caller's normaliser, roles, the smallest workspace).  Peaked logits as in
+    test_random_small_shapes: single entries and rows 4 %, arrays 1 %."""
+    rng = np.random.default_rng(5000 + seed)
+    d = int(rng.choice([8, 64, 72, 200, 264, 320]))
+    V = int(rng.choice([5, 255, 257, 700, 1030]))
+    n = int(rng.choice([1, 17, 256, 257, 600, 1100]))
+    H = wl.round_to_bf16((rng.normal(size=(n, d)) / np.sqrt(d) * 2).astype(np.float32))
+    W = wl.round_to_bf16(rng.normal(size=(V, d)).astype(np.float32))
+    ids = rng.integers(0, V, size=n).astype(np.int32)
+    n_sel = int(rng.integers(1, n + 1))
+    rowsel = np.sort(rng.choice(n, size=n_sel, replace=False)).astype(np.int32) if rng.random() < 0.7 else None
+    sel = rowsel if rowsel is not None else np.arange(n, dtype=np.int32)
+    adv = rng.normal(size=n).astype(np.float32)
+    adv[rng.random(n) < 0.2] = 0.0
+    if len(sel) > 300 and rng.random() < 0.7:
+        adv[sel[256:512]] = 0.0                           # a block of selected rows without an advantage
+    ent_c = float(rng.choice([0.0, 0.0, 0.02]))
+    dual = float(rng.choice([0.0, 0.0, 2.5]))
+    kl_c = float(rng.choice([0.0, 0.1, 0.3]))
+    S = len(sel)
+    norm = int(S + rng.integers(0, 50)) if rng.random() < 0.5 else 0
+    Sn = norm if norm else S
+    n_roles = int(rng.choice([0, 3]))
+    role = rng.integers(0, max(n_roles, 1), size=n).astype(np.int32)
+    logp_o, lse_o, ent_o = orc.score(H, W, ids, sel)
+    logp_old = (logp_o + 0.3 * rng.normal(size=n)).astype(np.float32)
+    logp_ref = (logp_o + 0.2 * rng.normal(size=n)).astype(np.float32)
+    st_o, g_o = orc.ppo_loss_variants(logp_o, logp_old, adv, ent_o, sel, role, n_roles, 0.2, dual, ent_c, kl_c, logp_ref)
+    g_o = g_o * S / Sn                                    # the oracle divides by S; the call by the caller's normaliser
+    dH_o, dW_o = orc.lm_head_backward_entropy(H, W, ids, lse_o, ent_o, g_o, ent_c, Sn, sel)
+    loss_o = st_o[0, 0] * S / Sn
+    ws = None
+    if rng.random() < 0.5:
+        ws = torch.empty(umas.ppo_workspace_bytes(S, d, V, torch.bfloat16, n_roles, minimum=True), dtype=torch.uint8, device="cuda")
+    what = (f"seed {seed}: d={d} V={V} n={n} sel={S} entropy={ent_c} dual={dual} kl={kl_c} norm={norm} roles={n_roles} "
+            f"chunked={ws is not None}")
+    stats, lp, dH, dW = umas.umas_ppo_loss_fwd_bwd(
+        P.to_dev(H, torch.bfloat16), P.to_dev(W, torch.bfloat16), P.to_dev(ids), None if rowsel is None else P.to_dev(rowsel),
+        P.to_dev(logp_old), P.to_dev(adv), P.to_dev(role) if n_roles else None, n_roles, 0.2, entropy_coef=ent_c, dual_clip=dual,
+        kl_coef=kl_c, logp_ref=P.to_dev(logp_ref) if kl_c else None, norm_rows=norm, workspace=ws)
+    torch.cuda.synchronize()
+    sg = umas.read_stats(stats)
+    term = float(np.abs(adv[sel]).mean())                 # the size of the terms the losses are means of
+    assert abs(float(sg["loss"][0]) - loss_o) <= 1e-2 * max(abs(loss_o), term * S / Sn, 1e-3), what
+    for k in range(1, 1 + n_roles):
+        assert int(sg["n_scored"][k]) == int(st_o[k, 4]), what
+        assert abs(float(sg["loss"][k]) - st_o[k, 0]) <= 1e-2 * max(abs(st_o[k, 0]), term, 1e-3), what
+    assert P.close(dH.float().cpu().numpy(), dH_o, 4e-2, "dH, " + what) <= 1e-2, what
+    assert P.close(dW.cpu().numpy(), dW_o, 4e-2, "dW, " + what) <= 1e-2, what
