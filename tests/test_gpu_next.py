@@ -446,3 +446,32 @@ def test_random_shapes_with_optional_terms(seed):
         assert abs(float(sg["loss"][k]) - st_o[k, 0]) <= 1e-2 * max(abs(st_o[k, 0]), term, 1e-3), what
     assert P.close(dH.float().cpu().numpy(), dH_o, 4e-2, "dH, " + what) <= 1e-2, what
     assert P.close(dW.cpu().numpy(), dW_o, 4e-2, "dW, " + what) <= 1e-2, what
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_random_graphs_around_the_update(seed):
+    """Ready batch (bit-exact), KL-penalised rewards and both whitening scopes on seeded random workflow graphs."""
+    w, kw = wl.random_graph(seed)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w, **kw)
+    s, adv, ret = P.gpu_front(w, **kw)
+    rng = np.random.default_rng(777 + seed)
+    n = w.n_tokens
+    keep = (rng.random(w.n_traj) >= 0.3).astype(np.uint8)
+    order = rng.permutation(w.n_traj).astype(np.int32)
+    n_parts = int(rng.integers(1, 9))
+    rows_o, off_o = orc.ready_batch(st, w.traj_turn_off, keep, order, n_parts)
+    rows, off = umas.umas_ready_batch(s, w.traj_turn_off, n_parts, keep, order)
+    assert np.array_equal(off.cpu().numpy(), off_o), "minibatch offsets differ"
+    assert np.array_equal(rows.cpu().numpy()[:len(rows_o)], rows_o), "minibatch rows differ"
+    logp = (-3.0 * rng.random(n)).astype(np.float32)
+    logp_ref = (logp + 0.1 * rng.normal(size=n)).astype(np.float32)
+    r_o, kl_o = orc.kl_penalised_rewards(r, logp, logp_ref, st["tok_mask"], 0.05)
+    r_g, kl_g = umas.umas_kl_rewards(s.tok_reward, P.to_dev(logp), P.to_dev(logp_ref), s.tok_mask, 0.05)
+    P.close(r_g.cpu().numpy(), r_o, 1e-5, "penalised rewards")
+    assert abs(float(kl_g.item()) - kl_o) <= 1e-5 * max(abs(kl_o), float(np.abs(logp - logp_ref).mean()) if n else 0.0) + 1e-30
+    a_in = (rng.normal(size=n) * 3 + 1).astype(np.float32)
+    for scope, oscope in ((umas.WHITEN_MODEL, orc.WHITEN_MODEL), (umas.WHITEN_MODEL_ROLE, orc.WHITEN_MODEL_ROLE)):
+        wh_o = orc.whiten_advantages(a_in, st["tok_mask"], st["tok_role"], st["model_tok_off"], w.n_roles, oscope)
+        wh = umas.umas_whiten_advantages(P.to_dev(a_in), s.tok_mask, s.tok_role, st["model_tok_off"], w.n_roles, scope)
+        # groups of a few tokens: the whitened values are differences from a mean, on the scale of 1
+        P.close(wh.cpu().numpy(), wh_o, 5e-5, f"whitened advantages, scope {scope}", floor=1e-3)

@@ -448,37 +448,8 @@ def test_bf16_wide_hidden_sizes():
 
 @pytest.mark.parametrize("seed", range(40))
 def test_random_graphs(seed):
-    """Seeded random workflow graphs through routing, placement and the scans: 1-39 trajectories of 0-6 turns, 1-5
-    roles on 1-3 models, turn lengths from 0 to 9000 tokens around the tile edges, mask densities from none to all,
-    any subset of the three reward levels and their weights, groups of 1-4, both placements and segment modes."""
-    rng = np.random.default_rng(9000 + seed)
-    w = wl.make_workload(0)
-    B, R, K = int(rng.integers(1, 40)), int(rng.integers(1, 6)), int(rng.integers(1, 4))
-    turns = [int(rng.integers(0, 7)) for _ in range(B)]
-    U = sum(turns)
-    big = rng.random() < 0.3
-    lens = np.array([int(rng.choice([0, 1, 2, 5, 63, 64, 65, 300, 2049 if big else 17, 9000 if big else 30])) for _ in range(U)],
-                    np.int64)
-    w.n_traj, w.n_turns, w.n_roles, w.n_models = B, U, R, K
-    w.traj_turn_off = np.concatenate([[0], np.cumsum(turns)]).astype(np.int32)
-    w.turn_role = rng.integers(0, R, size=U).astype(np.int32)
-    w.role_to_model = rng.integers(0, K, size=R).astype(np.int32)
-    w.turn_tok_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
-    w.n_tokens = int(w.turn_tok_off[-1])
-    w.turn_pred_off, w.turn_pred = None, None
-    w.tok_mask = (rng.random(w.n_tokens) < float(rng.choice([0.0, 0.3, 0.9, 1.0]))).astype(np.uint8)
-    w.traj_reward = rng.normal(size=B).astype(np.float32) if rng.random() < 0.8 else None
-    grouped = w.traj_reward is not None and rng.random() < 0.5
-    w.traj_group = (np.arange(B) // int(rng.integers(1, 5))).astype(np.int32) if grouped else None
-    w.role_reward = rng.normal(size=B * R).astype(np.float32) if rng.random() < 0.6 else None
-    w.turn_reward = rng.normal(size=U).astype(np.float32) if rng.random() < 0.6 else None
-    w.w_role = rng.random(R).astype(np.float32) if rng.random() < 0.5 else None
-    w.w_turn = rng.random(R).astype(np.float32) if rng.random() < 0.5 else None
-    w.w_traj = rng.random(R).astype(np.float32) if rng.random() < 0.5 else None
-    w.value = rng.normal(size=w.n_tokens).astype(np.float32) if rng.random() < 0.6 else None
-    kw = dict(seg_mode=int(rng.choice([orc.SEG_TURN, orc.SEG_TRAJ])), gamma_turn=float(rng.choice([1.0, 0.8])),
-              place_mode=int(rng.choice([orc.PLACE_LAST, orc.PLACE_ALL])), gamma=float(rng.choice([1.0, 0.97])),
-              lam=float(rng.choice([1.0, 0.9])))
+    """Seeded random workflow graphs (workloads.random_graph) through routing, placement and the scans."""
+    w, kw = wl.random_graph(seed)
     rho, st, r, adv_o, ret_o = P.oracle_front(w, **kw)
     s, adv, ret = P.gpu_front(w, **kw)
     P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)

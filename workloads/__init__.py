@@ -313,3 +313,39 @@ def make_workload(cfg: int, *, n_traj: Optional[int] = None, tokens_per_turn: Op
         tok_mask=tok_mask, value=value, gamma=gamma, lam=lam, gamma_turn=gamma_turn, seg_mode=seg_mode,
         clip_eps=clip_eps, noise_std=noise_std,
         models=[ModelSpec(int(d), int(V), str(t)) for d, V, t in mdl], model_ntok=model_ntok)
+
+
+def random_graph(seed: int):
+    """A seeded random workflow graph for robustness tests: 1-39 trajectories of 0-6 turns, 1-5 roles on 1-3 models,
+    turn lengths from 0 to 9000 tokens around the tile edges, mask densities from none to all, any subset of the three
+    reward levels and their weights, normalisation groups of 1-4.  Returns (workload, dict of scan and placement
+    parameters).  The model tensors of the returned workload are not meant to be used."""
+    rng = np.random.default_rng(9000 + seed)
+    w = make_workload(0)
+    B, R, K = int(rng.integers(1, 40)), int(rng.integers(1, 6)), int(rng.integers(1, 4))
+    turns = [int(rng.integers(0, 7)) for _ in range(B)]
+    U = sum(turns)
+    big = rng.random() < 0.3
+    lens = np.array([int(rng.choice([0, 1, 2, 5, 63, 64, 65, 300, 2049 if big else 17, 9000 if big else 30])) for _ in range(U)],
+                    np.int64)
+    w.n_traj, w.n_turns, w.n_roles, w.n_models = B, U, R, K
+    w.traj_turn_off = np.concatenate([[0], np.cumsum(turns)]).astype(np.int32)
+    w.turn_role = rng.integers(0, R, size=U).astype(np.int32)
+    w.role_to_model = rng.integers(0, K, size=R).astype(np.int32)
+    w.turn_tok_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    w.n_tokens = int(w.turn_tok_off[-1])
+    w.turn_pred_off, w.turn_pred = None, None
+    w.tok_mask = (rng.random(w.n_tokens) < float(rng.choice([0.0, 0.3, 0.9, 1.0]))).astype(np.uint8)
+    w.traj_reward = rng.normal(size=B).astype(np.float32) if rng.random() < 0.8 else None
+    grouped = w.traj_reward is not None and rng.random() < 0.5
+    w.traj_group = (np.arange(B) // int(rng.integers(1, 5))).astype(np.int32) if grouped else None
+    w.role_reward = rng.normal(size=B * R).astype(np.float32) if rng.random() < 0.6 else None
+    w.turn_reward = rng.normal(size=U).astype(np.float32) if rng.random() < 0.6 else None
+    w.w_role = rng.random(R).astype(np.float32) if rng.random() < 0.5 else None
+    w.w_turn = rng.random(R).astype(np.float32) if rng.random() < 0.5 else None
+    w.w_traj = rng.random(R).astype(np.float32) if rng.random() < 0.5 else None
+    w.value = rng.normal(size=w.n_tokens).astype(np.float32) if rng.random() < 0.6 else None
+    kw = dict(seg_mode=int(rng.choice([SEG_TURN, SEG_TRAJ])), gamma_turn=float(rng.choice([1.0, 0.8])),
+              place_mode=int(rng.choice([PLACE_LAST, PLACE_ALL])), gamma=float(rng.choice([1.0, 0.97])),
+              lam=float(rng.choice([1.0, 0.9])))
+    return w, kw
