@@ -191,7 +191,9 @@ size_t umas_ppo_loss_workspace_bytes(int64_t n_sel, int32_t d, int32_t V, umas_d
  * selected rows as loss, then the backward through the LM head:
  *   ratio = exp(logp - logp_old); L = max(-A ratio, -A clip(ratio, 1-eps, 1+eps))
  *   g = dloss/dlogp;  dz_iv = g_i (1[v = ids[i]] - softmax(z_i)_v);  dH = dz W;  dW = dz^T H
- *   logp_old, adv  DEVICE float [n_rows]
+ *   logp_old, adv  DEVICE float [n_rows]; logp_old = NULL: the update is on-policy, logp_old is taken to be the
+ *                  log-probs this call computes (ratio 1 on every row: L = -A, g = -A / n_sel, approx_kl = 0), which
+ *                  saves the separate umas_policy_logprobs pass of the first update after a rollout
  *   tok_role       DEVICE int32 [n_rows] or NULL with n_roles = 0
  *   stats          DEVICE umas_loss_stats [1 + n_roles]
  *   logp_new       DEVICE float [n_rows] or NULL

@@ -280,7 +280,7 @@ def umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv, tok_role, n_roles, c
         lib.umas_ppo_loss_workspace_bytes(n_sel, d, V, dt, n_roles), dev)
     _keep, sel = _sel_ptr(rowsel)
     _check(lib, lib.umas_ppo_loss_fwd_bwd(H.data_ptr(), W.data_ptr(), dt, n_rows, d, V, ids.data_ptr(), sel,
-                                          n_sel, logp_old.data_ptr(), adv.data_ptr(), _ptr(tok_role), n_roles,
+                                          n_sel, _ptr(logp_old), adv.data_ptr(), _ptr(tok_role), n_roles,
                                           clip_eps, entropy_coef, dual_clip, 1 if accumulate_dW else 0, int(norm_rows),
                                           _ptr(logp_ref), kl_coef, stats.data_ptr(),
                                           logp_new.data_ptr(), dH.data_ptr(), dW.data_ptr(), ws.data_ptr(), ws.numel(),

@@ -404,7 +404,7 @@ k_ppo_rows(int64_t norm, int64_t n_begin, int64_t n_end, const int32_t* __restri
     float L = 0.f, g = 0.f, clipped = 0.f, en = 0.f, kl = 0.f, lp = 0.f;
     if (ok) {
       lp = logp_c[n];
-      const float lo = logp_old[row], A = adv[row];
+      const float lo = logp_old ? logp_old[row] : lp, A = adv[row];   // no old log-probs: the update is on-policy, ratio 1
       const float ratio = __expf(lp - lo);
       const float u = -A * ratio;
       const float c = -A * fminf(fmaxf(ratio, 1.f - clip_eps), 1.f + clip_eps);
@@ -1157,7 +1157,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
                                              float* dW, void* workspace, size_t workspace_bytes, void* hip_stream) {
   umas_status s = check_model_args(H, W, dtype, n_rows, d, V, ids, rowsel, n_sel);
   if (s != UMAS_OK) return s;
-  UMAS_REQUIRE((logp_old && adv && dH) || n_rows == 0, UMAS_EINVAL, "logp_old, adv and dH must not be NULL");
+  UMAS_REQUIRE((adv && dH) || n_rows == 0, UMAS_EINVAL, "adv and dH must not be NULL");
   UMAS_REQUIRE(stats && dW, UMAS_EINVAL, "stats and dW must not be NULL");
   UMAS_REQUIRE(n_roles >= 0 && n_roles <= UMAS_MAX_ROLES, UMAS_ESHAPE, "n_roles=%d outside [0,%d]", n_roles, UMAS_MAX_ROLES);
   UMAS_REQUIRE(tok_role || n_roles == 0, UMAS_EINVAL, "tok_role is NULL but n_roles > 0");

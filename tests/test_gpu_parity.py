@@ -453,3 +453,34 @@ def test_random_graphs(seed):
     rho, st, r, adv_o, ret_o = P.oracle_front(w, **kw)
     s, adv, ret = P.gpu_front(w, **kw)
     P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_on_policy_update_without_old_logprobs(dtype):
+    """logp_old = NULL: the call's own log-probs stand for the old ones (ratio 1 on every row, nothing clipped)."""
+    if dtype == "f32":
+        w = wl.make_workload(0)
+    else:
+        w = wl.make_workload(2, n_traj=8, tokens_per_turn=48, models=SMALL_BF16)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w)
+    s, adv, ret = P.gpu_front(w)
+    t = w.model_tensors(0)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    tol = 1e-5 if dtype == "f32" else 1e-2
+    n = w.model_ntok[0]
+    S = int(st["model_rowsel_off"][1])
+    rows_o, role_o = st["rowsel"][:S], st["tok_role"][:n]
+    logp_o, lse_o, ent_o = orc.score(t["H"], t["W"], t["ids"], rows_o)
+    st_o, g_o = orc.ppo_loss(logp_o, logp_o, adv_o[:n], ent_o, rows_o, role_o, w.n_roles, w.clip_eps)
+    assert np.allclose(g_o[rows_o], -adv_o[:n][rows_o] / S, rtol=1e-15, atol=0)
+    dH_o, dW_o = orc.lm_head_backward(t["H"], t["W"], t["ids"], lse_o, g_o, rows_o)
+    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(P.to_dev(t["H"], tdt), P.to_dev(t["W"], tdt), P.to_dev(t["ids"]),
+                                                        s.rowsel[:S].contiguous(), None, adv[:n].contiguous(),
+                                                        s.tok_role[:n].contiguous(), w.n_roles, w.clip_eps)
+    torch.cuda.synchronize()
+    sg = umas.read_stats(stats)
+    assert float(sg["clip_frac"][0]) == 0.0 and float(sg["approx_kl"][0]) == 0.0
+    term = float(np.abs(adv_o[:n][rows_o]).mean())
+    assert abs(float(sg["loss"][0]) - st_o[0, 0]) <= tol * max(abs(st_o[0, 0]), term)
+    P.close(dH.float().cpu().numpy(), dH_o, tol, "dH")
+    P.close(dW.cpu().numpy(), dW_o, tol, "dW")
