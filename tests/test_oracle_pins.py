@@ -311,6 +311,91 @@ def test_traj_mode_workflow_d_coder_stream_telescopes():
     assert adv[a] == 0.75
 
 
+def gae_double_sum_varying_discount(r, V, disc, lam):
+    """A_t = sum_l (prod_{j<l} disc_{t+j} lam) delta_{t+l}, delta_t = r_t + disc_t V_{t+1} - V_t: the printed closed
+    form with the discount of the transition t -> t+1 given per transition, V beyond the end = 0."""
+    T = len(r)
+    Vn = list(V) + [0.0]
+    delta = [r[t] + disc[t] * Vn[t + 1] - Vn[t] for t in range(T)]
+    out = []
+    for t in range(T):
+        acc, w = 0.0, 1.0
+        for l in range(T - t):
+            acc += w * delta[t + l]
+            w *= disc[t + l] * lam
+        out.append(acc)
+    return out
+
+
+def test_traj_mode_with_values_worked_example():
+    # two turns of one trajectory at steps 1 and 3 inside one model stream, value estimates given
+    _, kv = read_golden("gae_traj_value_worked_example.txt")
+    tto, role, tok_off = chain_graph([[0, 1, 0]], [[2, 5, 1]])
+    st = orc.route(2, np.array([0, 1], np.int32), tto, role, tok_off, np.ones(8, np.uint8))
+    a, e = int(st["model_tok_off"][0]), int(st["model_tok_off"][1])
+    assert e - a == 3 and st["traj_seg_off"][:2].tolist() == [0, 3]
+    r, V = np.zeros(8), np.zeros(8)
+    r[a:e], V[a:e] = kv["r"], kv["V"]
+    adv, ret = orc.advantages(st, tto, r, V, kv["gamma"][0], kv["lam"][0], gamma_turn=kv["gamma_turn"][0],
+                              seg_mode=orc.SEG_TRAJ)
+    assert adv[a:e].tolist() == kv["adv"] and ret[a:e].tolist() == kv["ret"]
+
+
+@pytest.mark.parametrize("gamma,lam", [(1.0, 0.95), (0.99, 0.95), (0.9, 0.0), (0.7, 0.3)])
+def test_traj_mode_with_values_equals_printed_double_sum_on_the_concatenated_run(gamma, lam):
+    # gamma_turn = 1: a trajectory run is one episode, so the printed closed form holds on the concatenation of
+    # its turns, value estimates included (the next token's value crosses turn boundaries unchanged)
+    rng = np.random.default_rng(17)
+    trajs, lens = [[0, 0, 0, 0], [0, 0, 0]], [[4, 1, 6, 3], [2, 5, 2]]
+    tto, role, tok_off = chain_graph(trajs, lens)
+    N = int(tok_off[-1])
+    st = orc.route(1, np.array([0], np.int32), tto, role, tok_off, np.ones(N, np.uint8))
+    r, V = rng.normal(size=N), rng.normal(size=N)
+    adv, ret = orc.advantages(st, tto, r, V, gamma, lam, gamma_turn=1.0, seg_mode=orc.SEG_TRAJ)
+    a = 0
+    for L in (sum(lens[0]), sum(lens[1])):
+        want = gae_double_sum(r[a:a + L], V[a:a + L], gamma, lam)
+        assert np.allclose(adv[a:a + L], want, rtol=0, atol=1e-12)
+        a += L
+    assert np.allclose(ret - adv, V, atol=1e-12)
+    # and it differs from treating every turn as an episode: the boundary terms matter
+    adv_turn, _ = orc.advantages(st, tto, r, V, gamma, lam, seg_mode=orc.SEG_TURN)
+    assert np.abs(adv_turn - adv).max() > 1e-3
+
+
+@pytest.mark.parametrize("gamma,lam,gamma_turn", [(1.0, 0.95, 0.5), (0.99, 0.9, 0.8), (0.9, 0.0, 0.7), (1.0, 1.0, 0.9)])
+def test_traj_mode_with_values_and_step_discount_against_closed_form(gamma, lam, gamma_turn):
+    # partial sharing: roles 0 and 2 share model 0, role 1 has model 1, so model 0's run of a trajectory skips
+    # steps.  Crossing from the turn at step s to the turn at step s' > s discounts the transition by
+    # gamma * gamma_turn^(s' - s) in place of gamma: GAE with a per-transition discount, whose closed form is
+    # written out above.  Masked tokens are no actions and drop out of the episode.
+    rng = np.random.default_rng(19)
+    trajs = [[0, 1, 1, 2, 0, 1, 2], [2, 1, 0]]
+    lens = [[3, 2, 4, 2, 1, 3, 4], [2, 2, 3]]
+    tto, role, tok_off = chain_graph(trajs, lens)
+    N = int(tok_off[-1])
+    mask = np.ones(N, np.uint8)
+    mask[[1, 12, 20]] = 0                      # a token inside a turn, a whole one-token turn (step 5), a last token
+    st = orc.route(2, np.array([0, 1, 0], np.int32), tto, role, tok_off, mask)
+    r, V = rng.normal(size=N), rng.normal(size=N)
+    adv, ret = orc.advantages(st, tto, r, V, gamma, lam, gamma_turn=gamma_turn, seg_mode=orc.SEG_TRAJ)
+    step = np.concatenate([np.arange(1, len(t) + 1) for t in trajs])
+    seg = st["traj_seg_off"]
+    checked = 0
+    for s in range(len(seg) - 1):
+        pos = [p for p in range(int(seg[s]), int(seg[s + 1])) if st["tok_mask"][p]]
+        if not pos:
+            continue
+        steps = [int(step[st["tok_turn"][p]]) for p in pos]
+        disc = [gamma * gamma_turn ** (steps[i + 1] - steps[i]) for i in range(len(pos) - 1)] + [gamma]
+        want = gae_double_sum_varying_discount(r[pos], V[pos], disc, lam)
+        assert np.allclose(adv[pos], want, rtol=0, atol=1e-12)
+        assert np.allclose(ret[pos] - adv[pos], V[pos], atol=1e-12)
+        checked += len(pos)
+    assert checked == int(mask.sum())
+    assert np.all(adv[st["tok_mask"] == 0] == 0) and np.all(ret[st["tok_mask"] == 0] == 0)
+
+
 def test_traj_mode_reproduces_discounted_objective():
     # the objective discounts role invocations by gamma^(t-1); with token gamma = lam = 1,
     # V = 0 and gamma_turn = gamma the advantage on a token of step k is
