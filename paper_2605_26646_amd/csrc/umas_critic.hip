@@ -10,6 +10,8 @@
 // product and the row's g, writes dH and adds g h to its dw accumulators; the next row is already in
 // flight.  Per-wavefront partial sums are reduced by small kernels in a fixed order, so results do not
 // depend on scheduling.
+#include <type_traits>
+
 #include "umas_common.h"
 
 namespace umas {
@@ -22,6 +24,11 @@ constexpr int kMaxGrid = 1024;           // workgroups of the row kernel: one re
 constexpr int kVStat = 4;                // (sum L, clipped rows, sum V, rows)
 
 __device__ __forceinline__ uint16_t f2bf(float x) { return __builtin_bit_cast(uint16_t, static_cast<__bf16>(x)); }
+
+// Sums over a row and over rows: float for bf16 inputs (every product is exact in float), float64 for float32
+// inputs, whose bar is 1e-5 and whose speed does not matter (a float sum of d float32 products loses up to
+// d 2^-24 of the sum of their magnitudes, which the difference V - R then magnifies).
+template <typename T> using AccT = std::conditional_t<std::is_same<T, float>::value, double, float>;
 
 // 16 bytes of a row as floats: 8 bf16 or 4 float
 template <typename T> struct Vec;
@@ -68,16 +75,16 @@ k_value_fwd(const T* __restrict__ H, const T* __restrict__ w, float bias, int d,
   if (n >= n_sel) return;
   const int64_t row = rowsel ? rowsel[n] : n;
   const T* h = H + row * d;
-  float acc = 0.f;
+  AccT<T> acc = 0;
   for (int c = lane * Vec<T>::N; c < d; c += kWave * Vec<T>::N) {
     float x[Vec<T>::N], y[Vec<T>::N];
     Vec<T>::load(h + c, x);
     Vec<T>::load(w + c, y);
 #pragma unroll
-    for (int i = 0; i < Vec<T>::N; ++i) acc = fmaf(x[i], y[i], acc);
+    for (int i = 0; i < Vec<T>::N; ++i) acc = fma(static_cast<AccT<T>>(x[i]), static_cast<AccT<T>>(y[i]), acc);
   }
   acc = wave_sum(acc);
-  if (lane == 0) value[row] = acc + bias;
+  if (lane == 0) value[row] = static_cast<float>(acc + static_cast<AccT<T>>(bias));
 }
 
 // Loss and backward, one wavefront per row.  Lane l owns the 16-byte column vectors l, l + 64, ... (KV of them):
@@ -97,13 +104,14 @@ k_value_rows(const T* __restrict__ H, const T* __restrict__ w, float bias, int d
   for (int i = threadIdx.x; i < nacc; i += kVT) s_acc[i] = 0.0;
   __syncthreads();
   // w and the rows stay packed as loaded (16 bytes per vector) and are unpacked where they are used
+  using A = AccT<T>;
   uint4 wp[KV];
-  float acc[KV][N];
+  A acc[KV][N];
 #pragma unroll
   for (int k = 0; k < KV; ++k) {
     const int cv = lane + k * kWave;
 #pragma unroll
-    for (int i = 0; i < N; ++i) acc[k][i] = 0.f;
+    for (int i = 0; i < N; ++i) acc[k][i] = 0;
     wp[k] = make_uint4(0u, 0u, 0u, 0u);
     if (cv < nvec) wp[k] = *reinterpret_cast<const uint4*>(w + cv * N);
   }
@@ -127,7 +135,7 @@ k_value_rows(const T* __restrict__ H, const T* __restrict__ w, float bias, int d
   int64_t row_next = n < r_end ? fetch(n) : 0;
   for (; n < r_end; n += kVWaves) {
     const int64_t row = row_next;
-    float dot = 0.f;
+    A dot = 0;
 #pragma unroll
     for (int k = 0; k < KV; ++k) {
       cur[k] = nxt[k];
@@ -135,11 +143,12 @@ k_value_rows(const T* __restrict__ H, const T* __restrict__ w, float bias, int d
       Vec<T>::unpack(cur[k], x);
       Vec<T>::unpack(wp[k], y);
 #pragma unroll
-      for (int i = 0; i < N; ++i) dot = fmaf(x[i], y[i], dot);
+      for (int i = 0; i < N; ++i) dot = fma(static_cast<A>(x[i]), static_cast<A>(y[i]), dot);
     }
     if (n + kVWaves < r_end) row_next = fetch(n + kVWaves);     // in flight while this row is finished
     dot = wave_sum(dot);
-    const float V = dot + bias, vo = value_old[row], R = ret[row];
+    // the value is a float32 result; loss and gradient are formed from that rounded value
+    const float V = static_cast<float>(dot + static_cast<A>(bias)), vo = value_old[row], R = ret[row];
     const float vc = fminf(fmaxf(V, vo - clip_eps), vo + clip_eps);   // V itself inside the range: an exact tie
     const float lu = (V - R) * (V - R), lc = (vc - R) * (vc - R);
     const bool unclipped = lu >= lc;
@@ -167,7 +176,7 @@ k_value_rows(const T* __restrict__ H, const T* __restrict__ w, float bias, int d
         if (accumulate_dH) Vec<T>::load(dH + row * d + cv * N, o);
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-          acc[k][i] = fmaf(g, x[i], acc[k][i]);
+          acc[k][i] = fma(static_cast<A>(g), static_cast<A>(x[i]), acc[k][i]);
           o[i] = accumulate_dH ? o[i] + g * y[i] : g * y[i];
         }
         Vec<T>::store(dH + row * d + cv * N, o);
@@ -181,7 +190,7 @@ k_value_rows(const T* __restrict__ H, const T* __restrict__ w, float bias, int d
     const int cv = lane + k * kWave;
     if (cv < nvec)
 #pragma unroll
-      for (int i = 0; i < N; ++i) pd[cv * N + i] = acc[k][i];
+      for (int i = 0; i < N; ++i) pd[cv * N + i] = static_cast<float>(acc[k][i]);
   }
   if (lane == 0) pd[d] = gsum;
   __syncthreads();

@@ -336,46 +336,63 @@ k_score_finalize(const float4* __restrict__ partial, int tiles_m, int64_t n_pad,
 }
 
 // ------------------------------------------------------------------ float32: plain scoring
-// One block per selected row; every thread walks vocabulary entries v = tid, tid + T, ...
+// One block per selected row; every thread walks vocabulary entries v = tid, tid + T, ...  The float32 path is the
+// plain one for small shapes: its speed does not matter, so dot products and softmax statistics are carried in
+// float64 and only the results are rounded to float32 (a float32 dot product of d terms would cost up to
+// d 2^-24 of the sum of its terms' magnitudes).
+struct PartD {
+  double m, s, t;
+};
+__device__ __forceinline__ PartD partd_merge(PartD x, PartD y) {
+  if (x.s == 0.0) return y;
+  if (y.s == 0.0) return x;
+  const double M = fmax(x.m, y.m);
+  const double ex = exp(x.m - M), ey = exp(y.m - M);
+  return PartD{M, x.s * ex + y.s * ey, x.t * ex + y.t * ey};
+}
+__device__ __forceinline__ double dot_f64(const float* __restrict__ a, const float* __restrict__ b, int d) {
+  double z = 0.0;
+  for (int k = 0; k < d; ++k) z = fma(static_cast<double>(a[k]), static_cast<double>(b[k]), z);
+  return z;
+}
 __global__ void __launch_bounds__(256)
 k_score_f32(const float* __restrict__ W, const float* __restrict__ H, int d, int V,
             const int32_t* __restrict__ rowsel, const int32_t* __restrict__ ids,
             float* __restrict__ logp_c, float* __restrict__ lse_c, float* __restrict__ ent_c,
             float* __restrict__ logp, float* __restrict__ lse, float* __restrict__ entropy) {
-  extern __shared__ float s_h[];   // [d] + 3*4 scratch
-  __shared__ float s_m[4], s_s[4], s_t[4], s_zy;
+  extern __shared__ float s_h[];   // [d]
+  __shared__ double s_m[4], s_s[4], s_t[4], s_zy;
   const int64_t n = blockIdx.x;
   const int64_t row = rowsel ? rowsel[n] : n;
   for (int k = threadIdx.x; k < d; k += blockDim.x) s_h[k] = H[row * d + k];
-  if (threadIdx.x == 0) s_zy = 0.f;
+  if (threadIdx.x == 0) s_zy = 0.0;
   __syncthreads();
   const int y = ids[row];
-  Part p{kNegInf, 0.f, 0.f};
+  PartD p{0.0, 0.0, 0.0};
   for (int v = threadIdx.x; v < V; v += blockDim.x) {
-    const float* w = W + static_cast<int64_t>(v) * d;
-    float z = 0.f;
-    for (int k = 0; k < d; ++k) z = fmaf(s_h[k], w[k], z);
+    const double z = dot_f64(s_h, W + static_cast<int64_t>(v) * d, d);
     if (v == y) s_zy = z;
-    p = part_merge(p, Part{z, 1.f, z});
+    p = partd_merge(p, PartD{z, 1.0, z});
   }
   // merge over the block: lanes, then wavefronts
   for (int o = 32; o > 0; o >>= 1) {
-    Part q{__shfl_xor(p.m, o, kWave), __shfl_xor(p.s, o, kWave), __shfl_xor(p.t, o, kWave)};
-    p = part_merge(p, q);
+    PartD q{__shfl_xor(p.m, o, kWave), __shfl_xor(p.s, o, kWave), __shfl_xor(p.t, o, kWave)};
+    p = partd_merge(p, q);
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (lane == 0) { s_m[wave] = p.m; s_s[wave] = p.s; s_t[wave] = p.t; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    Part a{kNegInf, 0.f, 0.f};
-    for (int w = 0; w < 4; ++w) a = part_merge(a, Part{s_m[w], s_s[w], s_t[w]});
+    PartD a{0.0, 0.0, 0.0};
+    for (int w = 0; w < 4; ++w) a = partd_merge(a, PartD{s_m[w], s_s[w], s_t[w]});
     const bool ok = y >= 0 && y < V;
-    const float l = a.m + logf(a.s);
-    const float lp = ok ? s_zy - l : 0.f;
-    const float en = ok ? l - a.t / a.s : 0.f;
-    if (logp_c) { logp_c[n] = lp; lse_c[n] = l; ent_c[n] = en; }
+    const double l = a.m + log(a.s);
+    const float lf = static_cast<float>(l);
+    const float lp = ok ? static_cast<float>(s_zy - l) : 0.f;
+    const float en = ok ? static_cast<float>(l - a.t / a.s) : 0.f;
+    if (logp_c) { logp_c[n] = lp; lse_c[n] = lf; ent_c[n] = en; }
     if (logp) logp[row] = lp;
-    if (lse) lse[row] = l;
+    if (lse) lse[row] = lf;
     if (entropy) entropy[row] = en;
   }
 }
@@ -905,8 +922,8 @@ k_dw_onehot(const uint16_t* __restrict__ H, int d, const int32_t* __restrict__ r
 }
 
 // ------------------------------------------------------------------ float32: plain backward
-// dz[n, v] = g (onehot - exp(z - lse)) for a chunk of selected rows, z recomputed with the same
-// sequential dot product as the forward pass.
+// dz[n, v] = g (onehot - exp(z - lse)) for a chunk of selected rows, z recomputed with the same float64 dot
+// product as the forward pass; sums are carried in float64 here too.
 __global__ void __launch_bounds__(256)
 k_dz_f32(const float* __restrict__ W, const float* __restrict__ H, int d, int V, const int32_t* __restrict__ rowsel,
          int64_t c0, const int32_t* __restrict__ ids, const float* __restrict__ lse_c, const float* __restrict__ g_c,
@@ -916,28 +933,27 @@ k_dz_f32(const float* __restrict__ W, const float* __restrict__ H, int d, int V,
   const int64_t row = rowsel ? rowsel[c0 + n] : c0 + n;
   for (int k = threadIdx.x; k < d; k += blockDim.x) s_h[k] = H[row * d + k];
   __syncthreads();
-  __shared__ float s_red[32];
+  __shared__ double s_red[32];
   const int y = ids[row];
-  const float l = lse_c[c0 + n], g = g_c[c0 + n], en = ent_c[c0 + n], k_ent = kz_c[c0 + n];
+  const double l = lse_c[c0 + n], g = g_c[c0 + n], en = ent_c[c0 + n], k_ent = kz_c[c0 + n];
   // The taken token's entry g (1 - p_y): for a confident token (p_y > 1/2) 1 - p_y cancels down to the error of p_y,
   // and the sum of the other probabilities, which carries only their relative error, is taken in its place.
-  float rest = 0.f, label_ent = 0.f, p_label = 0.f;
+  double rest = 0.0, label_ent = 0.0, p_label = 0.0;
   for (int v = threadIdx.x; v < V; v += blockDim.x) {
-    const float* w = W + static_cast<int64_t>(v) * d;
-    float z = 0.f;
-    for (int k = 0; k < d; ++k) z = fmaf(s_h[k], w[k], z);
-    const float p = expf(z - l);
-    const float e = k_ent != 0.f ? k_ent * p * ((z - l) + en) : 0.f;     // entropy bonus: k p (log p + entropy)
+    const double z = dot_f64(s_h, W + static_cast<int64_t>(v) * d, d);
+    const double p = exp(z - l);
+    const double e = k_ent != 0.0 ? k_ent * p * ((z - l) + en) : 0.0;     // entropy bonus: k p (log p + entropy)
     if (v == y) {
       label_ent = e;
       p_label = p;
     } else {
       rest += p;
-      dz[n * V + v] = -g * p + e;
+      dz[n * V + v] = static_cast<float>(-g * p + e);
     }
   }
-  rest = block_sum<float>(rest, s_red);
-  if (y >= 0 && y < V && threadIdx.x == y % static_cast<int>(blockDim.x)) dz[n * V + y] = g * (p_label > 0.5f ? rest : 1.f - p_label) + label_ent;
+  rest = block_sum<double>(rest, s_red);
+  if (y >= 0 && y < V && threadIdx.x == y % static_cast<int>(blockDim.x))
+    dz[n * V + y] = static_cast<float>(g * (p_label > 0.5 ? rest : 1.0 - p_label) + label_ent);
 }
 // dH[row, j] = sum_v dz[n, v] W[v, j]
 __global__ void __launch_bounds__(256)
@@ -946,9 +962,9 @@ k_dh_f32(const float* __restrict__ dz, const float* __restrict__ W, int d, int V
   const int64_t n = blockIdx.x;
   const int64_t row = rowsel ? rowsel[c0 + n] : c0 + n;
   for (int j = threadIdx.x; j < d; j += blockDim.x) {
-    float s = 0.f;
-    for (int v = 0; v < V; ++v) s = fmaf(dz[n * V + v], W[static_cast<int64_t>(v) * d + j], s);
-    dH[row * d + j] = s;
+    double s = 0.0;
+    for (int v = 0; v < V; ++v) s = fma(static_cast<double>(dz[n * V + v]), static_cast<double>(W[static_cast<int64_t>(v) * d + j]), s);
+    dH[row * d + j] = static_cast<float>(s);
   }
 }
 // dW[v, j] (+)= sum_n dz[n, v] H[row(n), j]
@@ -957,18 +973,19 @@ k_dw_f32(const float* __restrict__ dz, const float* __restrict__ H, int d, int V
          int64_t c0, int64_t mc, int accumulate, float* __restrict__ dW) {
   const int v = blockIdx.x;
   for (int j = threadIdx.x; j < d; j += blockDim.x) {
-    float s = 0.f;
+    double s = 0.0;
     for (int64_t n = 0; n < mc; ++n) {
       const int64_t row = rowsel ? rowsel[c0 + n] : c0 + n;
-      s = fmaf(dz[n * V + v], H[row * d + j], s);
+      s = fma(static_cast<double>(dz[n * V + v]), static_cast<double>(H[row * d + j]), s);
     }
     float* dst = dW + static_cast<int64_t>(v) * d + j;
-    *dst = accumulate ? *dst + s : s;
+    *dst = accumulate ? static_cast<float>(static_cast<double>(*dst) + s) : static_cast<float>(s);
   }
 }
 
 // ------------------------------------------------------------------ host side
 constexpr int64_t kF32ChunkRows = 4096;
+constexpr double kF32MaxWork = 137438953472.0;   // 2^37 multiply-adds per product
 constexpr int64_t kMaxChunkRows = 1 << 17;
 
 int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -1041,6 +1058,10 @@ umas_status check_model_args(const void* H, const void* W, umas_dtype dt, int64_
   UMAS_REQUIRE(d >= 1 && V >= 1, UMAS_ESHAPE, "d=%d and V=%d must be positive", d, V);
   UMAS_REQUIRE(dt != UMAS_BF16 || d % 8 == 0, UMAS_ESHAPE, "bf16 needs d %% 8 == 0 (d=%d)", d);
   UMAS_REQUIRE(dt != UMAS_F32 || d <= 8192, UMAS_ESHAPE, "the float32 path supports d <= 8192 (d=%d)", d);
+  // the float32 path is the plain, untiled one (every thread walks whole rows of W): small shapes only
+  UMAS_REQUIRE(dt != UMAS_F32 || static_cast<double>(n_sel) * V * d <= kF32MaxWork, UMAS_ESHAPE,
+               "the float32 path is for small shapes: n_sel * V * d = %.3g exceeds %.3g; use bf16",
+               static_cast<double>(n_sel) * V * d, kF32MaxWork);
   UMAS_REQUIRE(dt != UMAS_BF16 || static_cast<uint64_t>(n_rows) * d * 2 < (1ull << 32), UMAS_ESHAPE,
                "bf16 H must be smaller than 4 GiB (32-bit buffer offsets): n_rows=%lld d=%d",
                static_cast<long long>(n_rows), d);

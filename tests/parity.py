@@ -46,6 +46,81 @@ def close(x, o, tol, what, row_abs=0.0, floor=0.0):
     return rel
 
 
+BF16_U = 2.0 ** -8      # largest relative error of rounding to bf16 (8 significant bits, round to nearest)
+
+
+def close_bounded(x, o, bound, tol, what):
+    """For gradients of shapes whose sums cancel: element-wise |x-o| <= bound, an array of error bounds derived from
+    the arithmetic (see bf16_gradient_bounds), and norm-wise over the array <= tol.  Returns the norm-wise error."""
+    x = np.asarray(x, dtype=np.float64)
+    o = np.asarray(o, dtype=np.float64)
+    assert x.shape == o.shape == bound.shape, f"{what}: shapes {x.shape}, {o.shape}, {bound.shape}"
+    if o.size == 0:
+        return 0.0
+    assert np.isfinite(x).all(), f"{what}: non-finite values"
+    err = np.abs(x - o)
+    worst = float((err / np.maximum(bound, 1e-300)).max())
+    assert (err <= bound).all(), f"{what}: element-wise error {worst:.3g} x its bound"
+    nrm = float(np.linalg.norm(o))
+    rel = float(np.linalg.norm(x - o) / nrm) if nrm > 0 else float(np.linalg.norm(x - o))
+    assert rel <= tol, f"{what}: norm-wise error {rel:.3g} > {tol}"
+    return rel
+
+
+def oracle_dz(H, W, ids, lse, g, rows, entropy=None, k_ent=0.0):
+    """The oracle's gradient with respect to the logits of `rows`, written out for the error bounds:
+    g (onehot - p) + k_ent p (log p + entropy)."""
+    z = np.asarray(H, np.float64)[rows] @ np.asarray(W, np.float64).T
+    logp_all = z - np.asarray(lse, np.float64)[rows][:, None]
+    p = np.exp(logp_all)
+    gr = np.asarray(g, np.float64)[rows]
+    dz = -p * gr[:, None]
+    dz[np.arange(len(rows)), np.asarray(ids)[rows]] += gr
+    if k_ent != 0.0:
+        dz += k_ent * p * (logp_all + np.asarray(entropy, np.float64)[rows][:, None])
+    return dz
+
+
+def bf16_gradient_bounds(H, W, dz, dH_o, dW_o, rows):
+    """Element-wise error bounds of the bf16 backward, from its arithmetic.  dz [len(rows), V] is the oracle's
+    gradient with respect to the logits of the rows `rows`.  The kernels round the dense part of dz to bf16 once (as
+    the kept softmax numerator, or as dz itself), for dW also the scaled hidden state; products are exact in float32
+    and sums are accumulated in float32 over K terms; dH is stored as bf16.  With u = 2^-8:
+      |dH - dH_o| <= (u + K 2^-23) |dz| |W|  + u |dH_o|
+      |dW - dW_o| <= (2u + u^2 + K 2^-23) |dz|^T |H|
+    plus 5 % for the float32 evaluation of the row factors and logits; an absolute floor of 1e-30 keeps exact zeros."""
+    u = BF16_U
+    A = np.abs(np.asarray(dz, np.float64))
+    Wa = np.abs(np.asarray(W, np.float64))
+    Ha = np.abs(np.asarray(H, np.float64)[rows])
+    V, n = Wa.shape[0], len(rows)
+    bound_h = np.zeros_like(np.asarray(dH_o, np.float64))
+    bound_h[rows] = 1.05 * ((u + V * 2.0 ** -23) * (A @ Wa) + u * np.abs(np.asarray(dH_o, np.float64)[rows]))
+    bound_w = 1.05 * (2 * u + u * u + n * 2.0 ** -23) * (A.T @ Ha)
+    return bound_h + 1e-30, bound_w + 1e-30
+
+
+def whiten_bounds(adv, tok_mask, tok_role, model_tok_off, n_roles, by_role, eps=1e-8):
+    """Element-wise error bounds of float32 whitening (A - mu) / sqrt(var + eps) from its conditioning: the difference
+    A - mu inherits 2^-24 (|A| + |mu|) from the float32 input and mean, divided by the group's deviation; on top of
+    that the 1e-5 relative of the float32 bar on the result, whose scale is 1."""
+    A = np.asarray(adv, np.float64)
+    m = np.asarray(tok_mask) != 0
+    role = np.asarray(tok_role)
+    bound = np.zeros_like(A)
+    for k in range(len(model_tok_off) - 1):
+        a, e = int(model_tok_off[k]), int(model_tok_off[k + 1])
+        idx_all = np.arange(a, e)
+        groups = [idx_all[m[a:e] & (role[a:e] == v)] for v in range(n_roles)] if by_role else [idx_all[m[a:e]]]
+        for idx in groups:
+            if len(idx) == 0:
+                continue
+            mu = A[idx].mean()
+            sd = np.sqrt(((A[idx] - mu) ** 2).mean() + eps)
+            bound[idx] = 1e-5 * np.maximum(np.abs((A[idx] - mu) / sd), 1.0) + 8 * 2.0 ** -24 * (np.abs(A[idx]) + abs(mu)) / sd
+    return bound
+
+
 def to_dev(a, dtype=None):
     t = torch.from_numpy(np.ascontiguousarray(a))
     if dtype is not None:

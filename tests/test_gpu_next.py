@@ -153,9 +153,12 @@ def shaping_case(cfg, **kw):
     r_twice, _ = orc.kl_penalised_rewards(r_o, logp, logp_ref, st["tok_mask"], beta)
     P.close(r_in.cpu().numpy(), r_twice, 1e-5, "in-place penalty")
     for scope, oscope in ((umas.WHITEN_MODEL, orc.WHITEN_MODEL), (umas.WHITEN_MODEL_ROLE, orc.WHITEN_MODEL_ROLE)):
-        wh_o = orc.whiten_advantages(adv2_o, st["tok_mask"], st["tok_role"], st["model_tok_off"], w.n_roles, oscope)
-        wh = umas.umas_whiten_advantages(adv2, s.tok_mask, s.tok_role, st["model_tok_off"], w.n_roles, scope)
-        P.close(wh.cpu().numpy(), wh_o, 2e-5, f"whitened advantages, scope {scope}")   # two float32 roundings: input and result
+        # both sides whiten the same float32 input: the oracle's advantages, rounded once
+        a_in = adv2_o.astype(np.float32)
+        wh_o = orc.whiten_advantages(a_in, st["tok_mask"], st["tok_role"], st["model_tok_off"], w.n_roles, oscope)
+        wh = umas.umas_whiten_advantages(P.to_dev(a_in), s.tok_mask, s.tok_role, st["model_tok_off"], w.n_roles, scope)
+        bound = P.whiten_bounds(a_in, st["tok_mask"], st["tok_role"], st["model_tok_off"], w.n_roles, oscope == orc.WHITEN_MODEL_ROLE)
+        P.close_bounded(wh.cpu().numpy(), wh_o, bound + 1e-30, 1e-5, f"whitened advantages, scope {scope}")
         assert not wh.cpu().numpy()[masked].any()
     buf = adv2.clone()
     umas.umas_whiten_advantages(buf, s.tok_mask, s.tok_role, st["model_tok_off"], w.n_roles, umas.WHITEN_MODEL, out=buf)
@@ -394,11 +397,13 @@ def test_critic_micro_batches_add_up_to_the_minibatch():
     assert abs(float(db.item()) - db_o) <= 1e-2 * max(abs(db_o), np.abs(g_o).sum() * 1e-2 + 1e-12)
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", list(range(24)) + [443])
 def test_random_shapes_with_optional_terms(seed):
     """Seeded random shapes around the tile edges with random combinations of the optional terms (entropy bonus, dual
     clip, KL term, the caller's normaliser, roles, the smallest workspace).  Peaked logits as in
-    test_random_small_shapes: single entries and rows 4 %, arrays 1 %."""
+    test_random_small_shapes: every entry within the error bound that follows from the kernels' arithmetic, arrays
+    1 %.  Seed 443 (five vocabulary entries, 169 of 1100 rows selected, chunked) once sat exactly on an ad hoc 4 %
+    per-entry limit."""
     rng = np.random.default_rng(5000 + seed)
     d = int(rng.choice([8, 64, 72, 200, 264, 320]))
     V = int(rng.choice([5, 255, 257, 700, 1030]))
@@ -444,8 +449,58 @@ def test_random_shapes_with_optional_terms(seed):
     for k in range(1, 1 + n_roles):
         assert int(sg["n_scored"][k]) == int(st_o[k, 4]), what
         assert abs(float(sg["loss"][k]) - st_o[k, 0]) <= 1e-2 * max(abs(st_o[k, 0]), term, 1e-3), what
-    assert P.close(dH.float().cpu().numpy(), dH_o, 4e-2, "dH, " + what) <= 1e-2, what
-    assert P.close(dW.cpu().numpy(), dW_o, 4e-2, "dW, " + what) <= 1e-2, what
+    dz = P.oracle_dz(H, W, ids, lse_o, g_o, sel, ent_o, ent_c / Sn)
+    bound_h, bound_w = P.bf16_gradient_bounds(H, W, dz, dH_o, dW_o, sel)
+    P.close_bounded(dH.float().cpu().numpy(), dH_o, bound_h, 1e-2, "dH, " + what)
+    P.close_bounded(dW.cpu().numpy(), dW_o, bound_w, 1e-2, "dW, " + what)
+
+
+@pytest.mark.parametrize("seed", list(range(12)) + [33, 101, 333, 356])
+def test_random_critic_shapes(seed):
+    """Seeded random shapes of the critic's fused pass in both dtypes: hidden sizes around the vector width, row counts
+    around a workgroup's share, random selections, roles, a caller's normaliser.  Seeds 33, 101, 333 and 356 are
+    float32 cases with d = 4096 whose dH once missed 1e-5 by a factor of up to two, when the value head summed its
+    float32 products in float32; the float32 path now carries its sums in float64."""
+    rng = np.random.default_rng(31000 + seed)
+    bf = rng.random() < 0.7
+    d = int(rng.choice([8, 16, 64, 72, 200, 512, 520, 2048, 3584, 8192])) if bf else int(rng.choice([4, 12, 64, 100, 1024, 4096]))
+    n = int(rng.choice([1, 3, 8, 9, 64, 257, 1000, 5000]))
+    H = rng.normal(size=(n, d)).astype(np.float32)
+    w_ = (rng.normal(size=d) * 0.05).astype(np.float32)
+    if bf:
+        H, w_ = wl.round_to_bf16(H), wl.round_to_bf16(w_)
+    tdt = torch.bfloat16 if bf else torch.float32
+    n_sel = int(rng.integers(0, n + 1))
+    rowsel = np.sort(rng.choice(n, size=n_sel, replace=False)).astype(np.int32) if rng.random() < 0.7 else None
+    sel = rowsel if rowsel is not None else np.arange(n, dtype=np.int32)
+    S = len(sel)
+    n_roles = int(rng.choice([0, 4]))
+    role = rng.integers(0, max(n_roles, 1), size=n).astype(np.int32)
+    bias = float(rng.normal() * 0.1)
+    V_o = orc.value_head(H, w_, bias, sel)
+    V_old = (V_o + 0.1 * rng.normal(size=n)).astype(np.float32)
+    ret = (V_o + 0.3 * rng.normal(size=n)).astype(np.float32)
+    norm = int(S + rng.integers(0, 9)) if (rng.random() < 0.5 and S > 0) else 0
+    Sn = norm if norm else max(S, 1)
+    st_o, g_o = orc.value_loss(V_o, V_old, ret, sel, role, n_roles, 0.1)
+    g_o = g_o * max(S, 1) / Sn
+    dH_o, dw_o, db_o = orc.value_head_backward(H, w_, g_o, sel)
+    what = f"seed {seed}: bf16={bf} d={d} n={n} sel={S} rowsel={rowsel is not None} roles={n_roles} norm={norm}"
+    tol = 1e-2 if bf else 1e-5
+    lim = 2e-2 if bf else 1e-5 * max(1.0, np.abs(V_o).max(initial=0))            # the value itself: absolute / relative to its scale
+    stats, V_new, dH, dw, db = umas.umas_value_loss_fwd_bwd(
+        P.to_dev(H, tdt), P.to_dev(w_, tdt), bias, None if rowsel is None else P.to_dev(rowsel), P.to_dev(V_old), P.to_dev(ret),
+        P.to_dev(role) if n_roles else None, n_roles, 0.1, norm_rows=norm)
+    torch.cuda.synchronize()
+    sg = umas.read_value_stats(stats)
+    assert int(sg["n_scored"][0]) == S, what
+    assert np.abs(V_new.cpu().numpy() - V_o).max(initial=0) <= lim, what
+    if S:
+        assert abs(float(sg["loss"][0]) - st_o[0, 0] * S / Sn) <= tol * max(abs(st_o[0, 0]) * S / Sn, 1e-3) + lim * 0.5, what
+    # g_i = (V_i - R_i) / S inherits the absolute error of V_i, whatever is left of V_i - R_i after cancellation
+    row_abs = lim / Sn * float(np.linalg.norm(w_.astype(np.float64)))
+    P.close(dH.float().cpu().numpy(), dH_o, tol, "dH, " + what, row_abs=row_abs)
+    P.close(dw.cpu().numpy(), dw_o, tol, "dw, " + what, floor=lim / Sn * float(np.abs(H).max()) * np.sqrt(max(S, 1)))
 
 
 @pytest.mark.parametrize("seed", range(30))
@@ -473,5 +528,7 @@ def test_random_graphs_around_the_update(seed):
     for scope, oscope in ((umas.WHITEN_MODEL, orc.WHITEN_MODEL), (umas.WHITEN_MODEL_ROLE, orc.WHITEN_MODEL_ROLE)):
         wh_o = orc.whiten_advantages(a_in, st["tok_mask"], st["tok_role"], st["model_tok_off"], w.n_roles, oscope)
         wh = umas.umas_whiten_advantages(P.to_dev(a_in), s.tok_mask, s.tok_role, st["model_tok_off"], w.n_roles, scope)
-        # groups of a few tokens: the whitened values are differences from a mean, on the scale of 1
-        P.close(wh.cpu().numpy(), wh_o, 5e-5, f"whitened advantages, scope {scope}", floor=1e-3)
+        # groups of a few tokens: the whitened values are differences from a mean, on the scale of 1, and inherit the
+        # float32 rounding of the values and of the mean divided by the group's deviation
+        bound = P.whiten_bounds(a_in, st["tok_mask"], st["tok_role"], st["model_tok_off"], w.n_roles, oscope == orc.WHITEN_MODEL_ROLE)
+        P.close_bounded(wh.cpu().numpy(), wh_o, bound + 1e-30, 1e-5, f"whitened advantages, scope {scope}")
