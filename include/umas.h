@@ -14,14 +14,17 @@
  *   - THIN metadata (graph, reward scalars) are HOST pointers, caller-owned, read during the
  *     call only (the paper's controller keeps exactly this: role ids, routing ids, reward
  *     metadata).  FAT tensors (masks, rewards per token, hidden states, weights, outputs,
- *     workspace) are DEVICE pointers, caller-allocated; the library owns no memory.
+ *     workspace) are DEVICE pointers, caller-allocated; the library owns no device memory.
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default
- *     stream).  No call synchronises with the device, except umas_assign_token_rewards and
- *     umas_ready_batch, which copy the thin host arrays to the device and wait for those copies
- *     (not for their kernels) so that the caller may free them on return.  Results, including
- *     loss statistics, stay on the device.  Every other call only launches kernels (memory is
- *     cleared by fill kernels, never by memset nodes), so it may be recorded into a HIP graph
- *     as long as profiling (umas_profile_enable) is off.
+ *     stream).  No call waits for the stream.  umas_assign_token_rewards and umas_ready_batch
+ *     gather their thin host arrays in a block of pinned host memory that the library keeps (a
+ *     ring of four blocks, each as large as the largest graph it has seen) and enqueue one
+ *     asynchronous copy of it: the caller may free or overwrite its arrays on return, and the
+ *     host can queue the next step while this one runs.  The one wait there is: a block is
+ *     reused four such calls later, after the copy that was issued from it has run.  Results,
+ *     including loss statistics, stay on the device.  Every other call only launches kernels
+ *     (memory is cleared by fill kernels, never by memset nodes), so it may be recorded into a
+ *     HIP graph as long as profiling (umas_profile_enable) is off.
  *   - Every call returns a umas_status.  Argument errors are found on the host before any
  *     launch, leave outputs untouched and set a thread-local message (umas_last_error).
  *   - Workspace sizes come from the umas_*_workspace_bytes queries; workspace must be
@@ -213,8 +216,14 @@ size_t umas_ppo_loss_workspace_bytes(int64_t n_sel, int32_t d, int32_t V, umas_d
  *   "Model-specific updates and synchronization"): g, the entropy term and stats[0].loss are divided by it in
  *   place of n_sel, so that the micro-batches' dW (accumulate_dW = 1), dH rows and losses add up to those of one
  *   call on the whole minibatch.  The roles' rows of stats and the other fields stay means over the call's rows.
- * bf16 computes the logits once when entropy_coef = 0 (the scoring pass leaves the softmax numerators
- * in the workspace as the operand of dH and dW) and twice otherwise; float32 logits are never stored. */
+ * What the bf16 update keeps in memory, stated plainly: for every chunk of selected rows it WRITES one bf16 number
+ * per (row, vocabulary entry) pair to the workspace and the two gradient products read that [rows, V] matrix back
+ * (2 * rows * V bytes: 11.9 GB for 39 224 rows against V = 151 936 in one chunk).  With entropy_coef = 0 the
+ * matrix holds the softmax numerators exp(z - z_y), written by the scoring pass itself, so the logits are computed
+ * once; with an entropy bonus it holds dz, written by a second pass over the logits.  The float32 logits are
+ * never stored, but a [rows, V] operand does pass through HBM; only umas_policy_logprobs keeps everything of that
+ * shape on chip.  The workspace bounds it: the call works in chunks of as many rows as the workspace holds (256
+ * at the least), at the price of one more pass over W per chunk.  The float32 path stores float32 dz per chunk. */
 umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_dtype dtype, int64_t n_rows,
                                   int32_t d, int32_t V, const int32_t* ids, const int32_t* rowsel,
                                   int64_t n_sel, const float* logp_old, const float* adv,
@@ -313,7 +322,8 @@ umas_status umas_whiten_advantages(const float* adv, const uint8_t* tok_mask, co
  *   mb_rowsel      DEVICE int32, at least as many entries as rowsel
  *   mb_off         DEVICE int64 [n_models * (n_minibatch + 1)]: minibatch k of model m is
  *                  mb_rowsel[mb_off[m*(n_minibatch+1) + k] .. mb_off[m*(n_minibatch+1) + k + 1])
- * The host arrays are copied inside the call, which waits for those copies before it returns. */
+ * The host arrays are read inside the call (through the library's pinned staging memory); the call does not wait
+ * for the stream. */
 size_t umas_ready_batch_workspace_bytes(int32_t n_traj, int32_t n_models);
 umas_status umas_ready_batch(const umas_streams* streams, int32_t n_models, int32_t n_turns,
                              const int32_t* traj_turn_off, int32_t n_traj, const uint8_t* traj_keep,

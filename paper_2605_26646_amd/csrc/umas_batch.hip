@@ -249,11 +249,18 @@ extern "C" umas_status umas_ready_batch(const umas_streams* s, int32_t n_models,
   Carver c(workspace);
   BatchWs w;
   carve_batch(c, w, n_traj, n_models);
-  UMAS_HIP(hipMemcpyAsync(w.traj_turn_off, traj_turn_off, (static_cast<size_t>(n_traj) + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st));
-  if (traj_order && n_traj > 0) UMAS_HIP(hipMemcpyAsync(w.order, traj_order, static_cast<size_t>(n_traj) * sizeof(int32_t), hipMemcpyHostToDevice, st));
-  if (traj_keep && n_traj > 0) UMAS_HIP(hipMemcpyAsync(w.keep, traj_keep, static_cast<size_t>(n_traj), hipMemcpyHostToDevice, st));
-  // the host arrays are only promised for the duration of the call: wait until the copies have read them
-  UMAS_HIP(hipStreamSynchronize(st));
+  // the thin arrays (the first arrays of the workspace, up to rank) go through pinned staging memory in one
+  // asynchronous copy: they have been read when the call returns, and the host does not wait for the stream
+  char* const ws_base = static_cast<char*>(workspace);
+  const size_t staged_bytes = static_cast<size_t>(reinterpret_cast<char*>(w.rank) - ws_base);
+  ThinStage stage;
+  umas_status vs = stage.begin(staged_bytes);
+  if (vs != UMAS_OK) return vs;
+  stage.put(static_cast<size_t>(reinterpret_cast<char*>(w.traj_turn_off) - ws_base), traj_turn_off, (static_cast<size_t>(n_traj) + 1) * sizeof(int32_t));
+  stage.put(static_cast<size_t>(reinterpret_cast<char*>(w.order) - ws_base), traj_order, static_cast<size_t>(n_traj) * sizeof(int32_t));
+  stage.put(static_cast<size_t>(reinterpret_cast<char*>(w.keep) - ws_base), traj_keep, static_cast<size_t>(n_traj));
+  vs = stage.flush(workspace, staged_bytes, st);
+  if (vs != UMAS_OK) return vs;
   prof_mark(st);
 
   const int64_t n_mq = static_cast<int64_t>(n_models) * n_traj;

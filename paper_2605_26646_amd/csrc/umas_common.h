@@ -18,6 +18,28 @@ extern bool g_prof_on;
 void prof_mark(hipStream_t st);                     // opens an interval at the start of an API call
 void prof_kernel(const char* name, hipStream_t st); // closes the interval of the kernel just launched
 
+// Staging of thin host arrays.  The calls that take host arrays copy them into a block of pinned host memory that
+// the library keeps (a ring of kSlots blocks, each grown to the largest request it has seen) and enqueue ONE
+// asynchronous copy of the block to the device: the caller's arrays have been read when the call returns, and the
+// host never waits for the stream.  A block is reused kSlots calls later; only then does the host wait, and only
+// until the copy that was issued from that block has run.
+class ThinStage {
+ public:
+  static constexpr int kSlots = 4;
+  // Takes the next block of the ring with room for `bytes`; 256-byte aligned.  Holds the ring's lock until flush().
+  umas_status begin(size_t bytes);
+  // Copies n bytes to offset `off` of the block (nothing for src == nullptr or n == 0).
+  void put(size_t off, const void* src, size_t n);
+  // Enqueues the copy of the first `bytes` bytes of the block to `dst` on `st` and releases the ring.
+  umas_status flush(void* dst, size_t bytes, hipStream_t st);
+  // Releases the ring without copying (an error between begin and flush).
+  void abandon();
+
+ private:
+  char* cur_ = nullptr;
+  int slot_ = -1;
+};
+
 #define UMAS_HIP(expr)                                                                 \
   do {                                                                                 \
     hipError_t e__ = (expr);                                                           \

@@ -1,5 +1,8 @@
-// Thread-local error message and the optional kernel timing aid of libumas.
+// Thread-local error message, the pinned staging ring for thin host arrays and the optional kernel timing aid of libumas.
+#include <string.h>
+
 #include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -34,6 +37,81 @@ void reset() {
 }  // namespace
 
 bool g_prof_on = false;
+
+// ------------------------------------------------------------------ pinned staging ring
+namespace {
+struct StageSlot {
+  char* host = nullptr;
+  size_t cap = 0;
+  hipEvent_t copied = nullptr;   // recorded behind the last copy issued from this block
+  bool in_flight = false;
+};
+StageSlot g_slots[ThinStage::kSlots];
+int g_next_slot = 0;
+std::mutex g_stage_mutex;
+}  // namespace
+
+umas_status ThinStage::begin(size_t bytes) {
+  g_stage_mutex.lock();
+  slot_ = g_next_slot;
+  g_next_slot = (g_next_slot + 1) % kSlots;
+  StageSlot& s = g_slots[slot_];
+  auto bail = [&](hipError_t e, const char* what) {
+    slot_ = -1;
+    cur_ = nullptr;
+    g_stage_mutex.unlock();
+    return fail(UMAS_EHIP, "%s failed: %s", what, hipGetErrorString(e));
+  };
+  if (s.in_flight) {             // the copy issued from this block kSlots calls ago must have read it
+    const hipError_t e = hipEventSynchronize(s.copied);
+    if (e != hipSuccess) return bail(e, "hipEventSynchronize");
+    s.in_flight = false;
+  }
+  if (!s.copied) {
+    const hipError_t e = hipEventCreateWithFlags(&s.copied, hipEventDisableTiming);
+    if (e != hipSuccess) return bail(e, "hipEventCreateWithFlags");
+  }
+  if (s.cap < bytes) {
+    if (s.host) (void)hipHostFree(s.host);
+    s.host = nullptr;
+    s.cap = 0;
+    size_t cap = 1 << 16;
+    while (cap < bytes) cap <<= 1;
+    void* p = nullptr;
+    const hipError_t e = hipHostMalloc(&p, cap, hipHostMallocDefault);
+    if (e != hipSuccess) return bail(e, "hipHostMalloc");
+    s.host = static_cast<char*>(p);
+    s.cap = cap;
+  }
+  cur_ = s.host;
+  return UMAS_OK;
+}
+
+void ThinStage::put(size_t off, const void* src, size_t n) {
+  if (src && n) memcpy(cur_ + off, src, n);
+}
+
+umas_status ThinStage::flush(void* dst, size_t bytes, hipStream_t st) {
+  StageSlot& s = g_slots[slot_];
+  hipError_t e = hipSuccess;
+  if (bytes) {
+    e = hipMemcpyAsync(dst, cur_, bytes, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipEventRecord(s.copied, st);
+    if (e == hipSuccess) s.in_flight = true;
+  }
+  slot_ = -1;
+  cur_ = nullptr;
+  g_stage_mutex.unlock();
+  if (e != hipSuccess) return fail(UMAS_EHIP, "staging copy failed: %s", hipGetErrorString(e));
+  return UMAS_OK;
+}
+
+void ThinStage::abandon() {
+  if (slot_ < 0) return;
+  slot_ = -1;
+  cur_ = nullptr;
+  g_stage_mutex.unlock();
+}
 
 umas_status fail(umas_status code, const char* fmt, ...) {
   va_list ap;

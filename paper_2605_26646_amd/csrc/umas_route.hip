@@ -612,12 +612,6 @@ umas_status validate(const umas_graph* g, const umas_rewards* r, const umas_stre
   return UMAS_OK;
 }
 
-template <typename T>
-hipError_t stage(T* dst, const T* src, size_t n, hipStream_t st) {
-  if (!src || n == 0) return hipSuccess;
-  return hipMemcpyAsync(dst, src, n * sizeof(T), hipMemcpyHostToDevice, st);
-}
-
 }  // namespace
 }  // namespace umas
 
@@ -663,22 +657,33 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
     n_groups = static_cast<int>(goff.size()) - 1;
   }
 
-  UMAS_HIP(stage(w.role_to_model, g->role_to_model, R, st));
-  UMAS_HIP(stage(w.traj_turn_off, g->traj_turn_off, B + 1, st));
-  UMAS_HIP(stage(w.turn_role, g->turn_role, U, st));
-  UMAS_HIP(stage(w.turn_tok_off, g->turn_tok_off, U + 1, st));
-  UMAS_HIP(stage(w.role_reward, r->role_reward, static_cast<size_t>(B) * R, st));
-  UMAS_HIP(stage(w.turn_reward, r->turn_reward, U, st));
-  UMAS_HIP(stage(w.traj_reward, r->traj_reward, B, st));
-  UMAS_HIP(stage(w.weights, r->w_role, R, st));
-  UMAS_HIP(stage(w.weights + R, r->w_turn, R, st));
-  UMAS_HIP(stage(w.weights + 2 * R, r->w_traj, R, st));
+  // The thin arrays are the first arrays of the workspace, up to traj_norm: they are gathered at the same offsets in a
+  // block of pinned host memory and go to the device in one asynchronous copy.  The host arrays have been read when
+  // the call returns; the host does not wait for the stream.
+  char* const ws_base = static_cast<char*>(workspace);
+  const size_t staged_bytes = static_cast<size_t>(reinterpret_cast<char*>(w.traj_norm) - ws_base);
+  ThinStage stage;
+  vs = stage.begin(staged_bytes);
+  if (vs != UMAS_OK) return vs;
+  auto put = [&](const void* dst, const void* src, size_t bytes) {
+    stage.put(static_cast<size_t>(static_cast<const char*>(dst) - ws_base), src, bytes);
+  };
+  put(w.role_to_model, g->role_to_model, sizeof(int32_t) * R);
+  put(w.traj_turn_off, g->traj_turn_off, sizeof(int32_t) * (static_cast<size_t>(B) + 1));
+  put(w.turn_role, g->turn_role, sizeof(int32_t) * U);
+  put(w.turn_tok_off, g->turn_tok_off, sizeof(int64_t) * (static_cast<size_t>(U) + 1));
+  put(w.role_reward, r->role_reward, sizeof(float) * static_cast<size_t>(B) * R);
+  put(w.turn_reward, r->turn_reward, sizeof(float) * U);
+  put(w.traj_reward, r->traj_reward, sizeof(float) * B);
+  put(w.weights, r->w_role, sizeof(float) * R);
+  put(w.weights + R, r->w_turn, sizeof(float) * R);
+  put(w.weights + 2 * R, r->w_traj, sizeof(float) * R);
   if (n_groups > 0) {
-    UMAS_HIP(stage(w.group_off, goff.data(), goff.size(), st));
-    UMAS_HIP(stage(w.group_members, gmem.data(), gmem.size(), st));
+    put(w.group_off, goff.data(), sizeof(int32_t) * goff.size());
+    put(w.group_members, gmem.data(), sizeof(int32_t) * gmem.size());
   }
-  // the host arrays are only promised for the duration of the call: wait until the copies have read them
-  UMAS_HIP(hipStreamSynchronize(st));
+  vs = stage.flush(workspace, staged_bytes, st);
+  if (vs != UMAS_OK) return vs;
   prof_mark(st);
 
   const float* traj_r = r->traj_reward ? w.traj_reward : nullptr;

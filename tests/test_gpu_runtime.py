@@ -1,0 +1,132 @@
+"""Run-time behaviour of the boundary on the GPU: the calls that take host arrays do not wait for the stream, the
+pinned staging ring survives back-to-back calls, and results do not depend on scheduling."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import umas_oracle as orc
+import paper_2605_26646_amd as umas
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+SMALL_BF16 = [(128, 1000, "bf16")]
+
+
+def assign_kwargs(w, mask):
+    return dict(n_roles=w.n_roles, n_models=w.n_models, role_to_model=w.role_to_model, traj_turn_off=w.traj_turn_off,
+                turn_role=w.turn_role, turn_tok_off=w.turn_tok_off, tok_mask_global=mask, turn_pred_off=w.turn_pred_off,
+                turn_pred=w.turn_pred, traj_group=w.traj_group, role_reward=w.role_reward, turn_reward=w.turn_reward,
+                traj_reward=w.traj_reward, place_mode=w.place_mode, norm_eps=w.norm_eps)
+
+
+def queue_long_work(n_matmuls=60):
+    """About 0.4 s of matrix products on the current stream; returns an event recorded behind them."""
+    x = torch.randn(16384, 16384, device="cuda", dtype=torch.bfloat16)
+    y = x
+    for _ in range(n_matmuls):
+        y = x @ x
+    ev = torch.cuda.Event()
+    ev.record()
+    return ev, y
+
+
+def test_calls_with_host_arrays_return_while_earlier_work_is_still_running():
+    w = wl.make_workload(2, n_traj=8, tokens_per_turn=48, models=SMALL_BF16)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w)
+    mask = P.to_dev(w.tok_mask)
+    kw = assign_kwargs(w, mask)
+    s = umas.umas_assign_token_rewards(**kw)              # first use: the staging memory is allocated here
+    umas.umas_ready_batch(s, w.traj_turn_off, 2)
+    queue_long_work(2)
+    torch.cuda.synchronize()
+    ev, _ = queue_long_work()
+    t0 = time.perf_counter()
+    s = umas.umas_assign_token_rewards(**kw)
+    t1 = time.perf_counter()
+    still_running_after_assign = not ev.query()
+    rows, off = umas.umas_ready_batch(s, w.traj_turn_off, 2)
+    t2 = time.perf_counter()
+    still_running_after_batch = not ev.query()
+    torch.cuda.synchronize()
+    assert still_running_after_assign, f"umas_assign_token_rewards returned after {1e3 * (t1 - t0):.1f} ms, when the earlier work had ended"
+    assert still_running_after_batch, f"umas_ready_batch returned after {1e3 * (t2 - t1):.1f} ms, when the earlier work had ended"
+    assert t2 - t0 < 0.1, f"the two calls took {1e3 * (t2 - t0):.1f} ms of host time"
+    adv, ret = umas.umas_advantages(s, P.to_dev(w.value), w.gamma, w.lam, w.gamma_turn, w.seg_mode)
+    P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+    rows_o, off_o = orc.ready_batch(st, w.traj_turn_off, np.ones(w.n_traj, np.uint8), np.arange(w.n_traj), 2)
+    assert np.array_equal(off.cpu().numpy(), off_o) and np.array_equal(rows.cpu().numpy()[:len(rows_o)], rows_o)
+
+
+def test_staging_ring_keeps_every_queued_call_apart():
+    """Ten routing calls on ten different graphs queued behind long-running work, none of them waited for: more calls
+    than the ring has blocks, sizes going up and down, so blocks are reused and regrown while copies are pending.  The
+    caller's host arrays are scribbled over right after each call returns."""
+    cases = []
+    for k, (cfg, n_traj, L) in enumerate([(2, 6, 40), (0, 3, 16), (4, 4, 64), (1, 16, 24), (3, 5, 32), (2, 30, 56), (0, 1, 8),
+                                          (4, 8, 128), (1, 8, 8), (3, 12, 20)]):
+        w = wl.make_workload(cfg, n_traj=n_traj, tokens_per_turn=L, seed_offset=k,
+                             models=SMALL_BF16 * (2 if cfg == 3 else 1))
+        cases.append((w, P.oracle_front(w)))
+    s0 = umas.umas_assign_token_rewards(**assign_kwargs(cases[0][0], P.to_dev(cases[0][0].tok_mask)))   # allocate the first block
+    torch.cuda.synchronize()
+    ev, _ = queue_long_work(30)
+    outs = []
+    for w, _o in cases:
+        kw = assign_kwargs(w, P.to_dev(w.tok_mask))
+        host = {k: (None if v is None else np.array(v, copy=True)) for k, v in kw.items() if isinstance(v, np.ndarray) or v is None}
+        kw.update(host)
+        s = umas.umas_assign_token_rewards(**kw)
+        for v in host.values():                            # the call has read them: the caller may reuse its arrays
+            if v is not None:
+                v[...] = 0
+        value = None if w.value is None else P.to_dev(w.value)
+        outs.append((s, *umas.umas_advantages(s, value, w.gamma, w.lam, w.gamma_turn, w.seg_mode)))
+    torch.cuda.synchronize()
+    for (w, (rho, st, r, adv_o, ret_o)), (s, adv, ret) in zip(cases, outs):
+        P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+
+
+def test_results_do_not_depend_on_scheduling():
+    """Two runs of the whole path on the same inputs: routing, placement, advantages, log-probs, statistics and dH are
+    bit-equal (no atomics on their way); dW adds its one-hot rows with float atomics in whatever order the wavefronts
+    arrive (its dense part has one writer per entry and a fixed order), so it is equal up to float32 rounding of those
+    sums: 1e-4 relative here against the 1e-2 of the gradient bar."""
+    w = wl.make_workload(3, n_traj=12, tokens_per_turn=96, models=[(256, 3000, "bf16"), (320, 2100, "bf16")])
+    mask = P.to_dev(w.tok_mask)
+    runs = []
+    for _ in range(2):
+        s = umas.umas_assign_token_rewards(**assign_kwargs(w, mask))
+        adv, ret = umas.umas_advantages(s, P.to_dev(w.value), w.gamma, w.lam, w.gamma_turn, w.seg_mode)
+        per_model = []
+        off = s.model_tok_off.cpu().numpy()
+        roff = s.model_rowsel_off.cpu().numpy()
+        for m in range(w.n_models):
+            t = w.model_tensors(m)
+            a, e = int(off[m]), int(off[m + 1])
+            H, W, ids = P.to_dev(t["H"], torch.bfloat16), P.to_dev(t["W"], torch.bfloat16), P.to_dev(t["ids"])
+            rowsel = s.rowsel[int(roff[m]):int(roff[m + 1])]
+            logp, lse, ent = umas.umas_policy_logprobs(H, W, ids, rowsel)
+            logp_old = logp + P.to_dev(t["noise"].astype(np.float32))
+            stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv[a:e].contiguous(),
+                                                                s.tok_role[a:e].contiguous(), w.n_roles, w.clip_eps)
+            torch.cuda.synchronize()
+            per_model.append((logp, lse, ent, stats, logp_new, dH, dW))
+        runs.append((s, adv, ret, per_model))
+    (s1, adv1, ret1, pm1), (s2, adv2, ret2, pm2) = runs
+    for f in ("model_tok_off", "perm", "tok_turn", "tok_role", "tok_mask", "tok_flags", "tok_reward", "turn_seg_off", "seg_turn",
+              "model_turn_off", "traj_seg_off", "model_trajrun_off", "model_rowsel_off", "turn_scalar", "turn_step"):
+        assert torch.equal(getattr(s1, f), getattr(s2, f)), f
+    n_scored = int(s1.model_rowsel_off[-1].item())
+    assert torch.equal(s1.rowsel[:n_scored], s2.rowsel[:n_scored])
+    assert torch.equal(adv1, adv2) and torch.equal(ret1, ret2)
+    for a, b in zip(pm1, pm2):
+        for k, name in enumerate(("logp", "lse", "entropy", "stats", "logp_new", "dH")):
+            assert torch.equal(a[k], b[k]), name
+        dW1, dW2 = a[6], b[6]
+        # a frequent token's row of dW is a float32 sum of hundreds of one-hot terms in arrival order: up to about
+        # sqrt(terms) 2^-24 of their magnitudes apart between runs, two orders of magnitude inside the gradient bar
+        P.close(dW2.cpu().numpy(), dW1.cpu().numpy().astype(np.float64), 1e-4, "dW of the second run against the first")
