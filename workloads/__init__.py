@@ -186,13 +186,15 @@ def _alternating_mask(rng, n_turns: int, length: int, mean_valid: float, mean_ma
 
 def make_workload(cfg: int, *, n_traj: Optional[int] = None, tokens_per_turn: Optional[int] = None,
                   models: Optional[Sequence[Tuple[int, int, str]]] = None,
-                  noise_std: float = 0.05, seed_offset: int = 0) -> Workload:
+                  noise_std: float = 0.05, seed_offset: int = 0, fixed_rounds: Optional[int] = None) -> Workload:
     """Build workload ``cfg`` (0..4).  Overrides shrink or replicate it while keeping its structure.
 
     n_traj           number of trajectories (default: the configuration's own)
     tokens_per_turn  scales every turn length so the base turn has this many tokens
     models           list of (d, V, dtype) replacing the configuration's model shapes
     noise_std        std of the old-log-prob noise (0.05 nominal, 0.25 for the clip-stress variant)
+    fixed_rounds     configuration 4 only: every trajectory runs this many coder -> critic rounds (no early
+                     termination; 3 gives the 16 x 3 x 5120 = 245 760 tokens of the configuration read literally)
     """
     seed = BASE_SEED + cfg + 1000 * seed_offset
     rng = np.random.default_rng(seed)
@@ -249,14 +251,14 @@ def make_workload(cfg: int, *, n_traj: Optional[int] = None, tokens_per_turn: Op
         B = n_traj or 16
         Lc = tokens_per_turn or 4096
         Lr = max(1, Lc // 4)
-        rounds = np.array([[1, 2, 3, 2][b % 4] for b in range(B)])
+        rounds = np.array([[1, 2, 3, 2][b % 4] if fixed_rounds is None else fixed_rounds for b in range(B)])
         turn_role = np.concatenate([np.tile(np.array([0, 1], np.int32), r) for r in rounds])
         traj_turn_off = np.concatenate([[0], np.cumsum(2 * rounds)]).astype(np.int32)
         turn_len = np.where(turn_role == 0, Lc, Lr).astype(np.int64)
         n_roles, phi = 2, [0, 0]
         mdl = [(3584, 152064, "bf16")]
         gamma, lam = 1.0, 0.95
-        name = "cfg4_reflective_code"
+        name = "cfg4_reflective_code" if fixed_rounds is None else f"cfg4_reflective_code_{fixed_rounds}_rounds"
     else:
         raise ValueError("cfg must be 0..4")
 
