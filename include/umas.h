@@ -14,7 +14,8 @@
  *   - THIN metadata (graph, reward scalars) are HOST pointers, caller-owned, read during the
  *     call only (the paper's controller keeps exactly this: role ids, routing ids, reward
  *     metadata).  FAT tensors (masks, rewards per token, hidden states, weights, outputs,
- *     workspace) are DEVICE pointers, caller-allocated; the library owns no device memory.
+ *     workspace) are DEVICE pointers, caller-allocated; the library owns no device memory
+ *     besides the static scratch of umas_policy_logprobs_static.
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default
  *     stream).  No call waits for the stream.  umas_assign_token_rewards and umas_ready_batch
  *     gather their thin host arrays in a block of pinned host memory that the library keeps (a
@@ -170,6 +171,25 @@ umas_status umas_policy_logprobs(const void* H, const void* W, umas_dtype dtype,
                                  int32_t d, int32_t V, const int32_t* ids, const int32_t* rowsel,
                                  int64_t n_sel, float* logp, float* lse, float* entropy,
                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The same scoring for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  No workspace argument and no allocation of any kind inside the call
+ * (no hipMalloc, no hipFree, no host allocation): the per-tile partials that umas_policy_logprobs keeps in
+ * its workspace go to a device array of UMAS_STATIC_SCRATCH_BYTES that is part of the library's code object;
+ * each GPU the library runs on holds its own copy until the process ends.  Same arguments, outputs, kernels
+ * and results as umas_policy_logprobs.
+ *   limit   umas_policy_logprobs_workspace_bytes(n_sel, d, V, dtype) <= UMAS_STATIC_SCRATCH_BYTES, i.e. for bf16
+ *           ceil(V / 256) * roundup(n_sel, 256) * 16 bytes: 3328 selected rows per call at V = 151936;
+ *           float32 needs no scratch.  More returns UMAS_EWORKSPACE, nothing launched.
+ *   sharing every call on one GPU uses that GPU's one array: calls that overlap on a GPU (two streams, two
+ *           threads) race; calls on one stream are ordered and safe.  Nothing in the array carries over
+ *           between calls (each call overwrites what it reads).
+ *   set-up  the first call on a device (with that device current) looks the array's address up once; make that
+ *           call outside graph capture. */
+#define UMAS_STATIC_SCRATCH_BYTES (32u << 20)
+umas_status umas_policy_logprobs_static(const void* H, const void* W, umas_dtype dtype, int64_t n_rows,
+                                        int32_t d, int32_t V, const int32_t* ids, const int32_t* rowsel,
+                                        int64_t n_sel, float* logp, float* lse, float* entropy, void* hip_stream);
 
 /* Row 0: the model's totals; rows 1..n_roles: the same numbers over the rows of one role. */
 typedef struct {

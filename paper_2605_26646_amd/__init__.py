@@ -8,6 +8,7 @@ PyTorch supplies device memory and the current stream, nothing else.
 from .binding import (  # noqa: F401
     UmasError, Streams, lib_path, load_library,
     umas_assign_token_rewards, umas_advantages, umas_policy_logprobs, umas_ppo_loss_fwd_bwd,
+    umas_policy_logprobs_static, STATIC_SCRATCH_BYTES,
     ppo_workspace_bytes, read_stats, profile_enable, profile_read,
     umas_values, umas_value_loss_fwd_bwd, read_value_stats, umas_kl_rewards, umas_whiten_advantages,
     WHITEN_MODEL, WHITEN_MODEL_ROLE, umas_ready_batch,

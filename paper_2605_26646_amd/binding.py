@@ -252,6 +252,34 @@ def umas_policy_logprobs(H: torch.Tensor, W: torch.Tensor, ids: torch.Tensor, ro
     return logp, lse, ent
 
 
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def umas_policy_logprobs_static(H: torch.Tensor, W: torch.Tensor, ids: torch.Tensor, rowsel: Optional[torch.Tensor] = None,
+                                logp=None, lse=None, entropy=None):
+    """umas_policy_logprobs without a workspace (the library's static scratch); the outputs may be passed in, so that
+    the call itself allocates nothing."""
+    lib = load_library()
+    lib.umas_policy_logprobs_static.restype = C.c_int
+    lib.umas_policy_logprobs_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int32, C.c_int32,
+                                                C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                C.c_void_p]
+    n_rows, d = H.shape
+    V = W.shape[0]
+    n_sel = n_rows if rowsel is None else int(rowsel.numel())
+    dev = H.device
+    if logp is None:
+        logp = torch.empty(n_rows, dtype=torch.float32, device=dev)
+    if lse is None:
+        lse = torch.empty(n_rows, dtype=torch.float32, device=dev)
+    if entropy is None:
+        entropy = torch.empty(n_rows, dtype=torch.float32, device=dev)
+    _keep, sel = _sel_ptr(rowsel)
+    _check(lib, lib.umas_policy_logprobs_static(H.data_ptr(), W.data_ptr(), _dtype_code(H), n_rows, d, V, ids.data_ptr(),
+                                                sel, n_sel, logp.data_ptr(), lse.data_ptr(), entropy.data_ptr(), _stream()))
+    return logp, lse, entropy
+
+
 def ppo_workspace_bytes(n_sel, d, V, dtype: torch.dtype, n_roles, minimum=False) -> int:
     lib = load_library()
     code = UMAS_BF16 if dtype == torch.bfloat16 else UMAS_F32

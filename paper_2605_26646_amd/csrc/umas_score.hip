@@ -17,6 +17,8 @@
 // The float32 path is a plain, unblocked implementation for small shapes.
 #include <math.h>
 
+#include <mutex>
+
 #include "umas_common.h"
 #include "umas_mfma.h"
 
@@ -1139,6 +1141,63 @@ extern "C" umas_status umas_policy_logprobs(const void* H, const void* W, umas_d
     if (entropy) UMAS_HIP(fill_bytes_zero(entropy, n_rows * sizeof(float), st));
   }
   Carver c(workspace);
+  ScoreWs w;
+  carve_score(c, w, n_sel, V, dtype, false);
+  return run_score(H, W, dtype, d, V, ids, rowsel, n_sel, w, logp, lse, entropy, st);
+}
+
+// ------------------------------------------------------------------ scoring without any allocation
+// The per-tile partials of the scoring pass live in a file-scope device array in place of a caller's workspace.
+// Every GPU holds its own copy of the array at its own address, resolved once per device; host code only ever
+// uses that resolved address.  Nothing in it has to start at zero: the tile kernel writes every partial that the
+// merge kernel reads.
+static __device__ __align__(256) unsigned char scratch[UMAS_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];   // per device: address of `scratch` there, NULL until first used
+
+umas_status static_scratch(void** out) {
+  int dev = -1;
+  UMAS_HIP(hipGetDevice(&dev));
+  UMAS_REQUIRE(dev >= 0 && dev < kMaxDevices, UMAS_ESHAPE, "device %d outside [0,%d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    UMAS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    UMAS_REQUIRE(p, UMAS_EHIP, "hipGetSymbolAddress returned no address for the static scratch");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return UMAS_OK;
+}
+}  // namespace
+
+extern "C" umas_status umas_policy_logprobs_static(const void* H, const void* W, umas_dtype dtype, int64_t n_rows,
+                                                   int32_t d, int32_t V, const int32_t* ids, const int32_t* rowsel,
+                                                   int64_t n_sel, float* logp, float* lse, float* entropy,
+                                                   void* hip_stream) {
+  umas_status s = check_model_args(H, W, dtype, n_rows, d, V, ids, rowsel, n_sel);
+  if (s != UMAS_OK) return s;
+  UMAS_REQUIRE((logp && lse) || n_rows == 0, UMAS_EINVAL, "logp and lse must not be NULL");
+  UMAS_REQUIRE(n_sel < (1LL << 31), UMAS_ESHAPE, "at most 2^31-1 selected rows");
+  const size_t need = umas_policy_logprobs_workspace_bytes(n_sel, d, V, dtype);
+  UMAS_REQUIRE(need <= static_cast<size_t>(UMAS_STATIC_SCRATCH_BYTES), UMAS_EWORKSPACE,
+               "%lld selected rows against a vocabulary of %d need %zu bytes of scratch, the static scratch holds %zu: "
+               "score fewer rows per call or use umas_policy_logprobs with a workspace",
+               static_cast<long long>(n_sel), V, need, static_cast<size_t>(UMAS_STATIC_SCRATCH_BYTES));
+  void* ws = nullptr;
+  s = static_scratch(&ws);
+  if (s != UMAS_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  prof_mark(st);
+  if (rowsel && n_rows > 0) {
+    UMAS_HIP(fill_bytes_zero(logp, n_rows * sizeof(float), st));
+    UMAS_HIP(fill_bytes_zero(lse, n_rows * sizeof(float), st));
+    if (entropy) UMAS_HIP(fill_bytes_zero(entropy, n_rows * sizeof(float), st));
+  }
+  Carver c(ws);
   ScoreWs w;
   carve_score(c, w, n_sel, V, dtype, false);
   return run_score(H, W, dtype, d, V, ids, rowsel, n_sel, w, logp, lse, entropy, st);
