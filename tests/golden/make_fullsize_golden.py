@@ -6,6 +6,10 @@ fingerprints of the seeded inputs they belong to.  It calls nothing but `oracle/
 
     python tests/golden/make_fullsize_golden.py 1        # every scored row; about 12 minutes on 8 cores
     python tests/golden/make_fullsize_golden.py 4 4096   # a seeded sample of 4096 scored rows per model
+    python tests/golden/make_fullsize_golden.py 4 0 4    # every scored row, four worker processes
+
+The optional third argument runs the oracle in that many worker processes, each on its own blocks of
+rows (the oracle's element-wise passes are single-threaded; its matrix product is a library call).
 
 With a sample size the file also holds `rows_m`, the sorted row indices (within the model's stream)
 that were evaluated: the first and last 256 scored rows plus a seeded draw from the rest; the other
@@ -43,7 +47,16 @@ def sample_rows(rows, n_sample, seed):
     return np.sort(np.concatenate([rows[:edge], mid[pick], rows[len(rows) - edge:]]))
 
 
-def main(cfg, n_sample=0):
+_T = None
+
+
+def _score_block(rr):
+    a, b, c = orc.score(_T["H"], _T["W"], _T["ids"], rr)
+    return rr, a[rr].astype(np.float32), b[rr].astype(np.float32), c[rr].astype(np.float32)
+
+
+def main(cfg, n_sample=0, procs=1):
+    global _T
     w = wl.make_workload(cfg)
     st = orc.route(w.n_models, w.role_to_model, w.traj_turn_off, w.turn_role, w.turn_tok_off, w.tok_mask)
     out = {}
@@ -57,11 +70,24 @@ def main(cfg, n_sample=0):
         logp, lse, ent = np.zeros(n, np.float32), np.zeros(n, np.float32), np.zeros(n, np.float32)
         t0 = time.time()
         step = 2048
-        for c0 in range(0, len(rows), step):
-            rr = rows[c0:c0 + step]
-            a, b, c = orc.score(t["H"], t["W"], t["ids"], rr)
-            logp[rr], lse[rr], ent[rr] = a[rr], b[rr], c[rr]
-            print(f"cfg {cfg} model {m}: {min(c0 + step, len(rows))}/{len(rows)} rows, {time.time() - t0:.0f} s", flush=True)
+        blocks = [rows[c0:c0 + step] for c0 in range(0, len(rows), step)]
+        _T = t
+        if procs > 1:
+            import multiprocessing as mp
+            from threadpoolctl import threadpool_limits
+            with threadpool_limits(limits=max(1, (os.cpu_count() or 1) // procs)):
+                with mp.get_context("fork").Pool(procs) as pool:      # the workers inherit the tensors
+                    results = pool.imap(_score_block, blocks)
+                    done = 0
+                    for rr, a, b, c in results:
+                        logp[rr], lse[rr], ent[rr] = a, b, c
+                        done += len(rr)
+                        print(f"cfg {cfg} model {m}: {done}/{len(rows)} rows, {time.time() - t0:.0f} s", flush=True)
+        else:
+            for rr in blocks:
+                _, a, b, c = _score_block(rr)
+                logp[rr], lse[rr], ent[rr] = a, b, c
+                print(f"cfg {cfg} model {m}: {rr[-1]}/{len(rows)} rows, {time.time() - t0:.0f} s", flush=True)
         out[f"logp_{m}"], out[f"lse_{m}"], out[f"entropy_{m}"] = logp, lse, ent
         out[f"fingerprint_{m}"] = fingerprint(t)
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"fullsize_cfg{cfg}.npz")
@@ -70,4 +96,4 @@ def main(cfg, n_sample=0):
 
 
 if __name__ == "__main__":
-    main(int(sys.argv[1]), int(sys.argv[2]) if len(sys.argv) > 2 else 0)
+    main(int(sys.argv[1]), int(sys.argv[2]) if len(sys.argv) > 2 else 0, int(sys.argv[3]) if len(sys.argv) > 3 else 1)
