@@ -162,20 +162,32 @@ __device__ __forceinline__ int last_le(const T* __restrict__ off, int n, T x) {
 }
 
 // Largest j in [0, n] with off[j] <= x (ascending off, off[0] <= x), found by one wavefront probing
-// 64 positions per round; every lane of the wavefront must call it and gets the same answer.
+// 256 positions per round (four per lane, all four loads in flight together: a round costs one trip to
+// memory); every lane of the wavefront must call it and gets the same answer.
 __device__ __forceinline__ int wave_last_le(const int64_t* __restrict__ off, int n, int64_t x) {
   const int lane = threadIdx.x & (kWave - 1);
+  constexpr int kProbes = 4 * kWave;
   int lo = 0, hi = n;
-  while (hi - lo >= kWave) {
-    const int step = (hi - lo) / kWave;
-    const bool ok = off[lo + (lane + 1) * step] <= x;
-    const int c = __popcll(__ballot(ok));          // probes 1..c hold
-    const int nhi = c == kWave ? hi : lo + (c + 1) * step - 1;
+  while (hi - lo >= kProbes) {
+    const int step = (hi - lo) / kProbes;
+    // probe i = 1 .. 256 sits at lo + i * step; lane l takes probes l + 1, l + 65, l + 129, l + 193
+    bool ok[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) ok[k] = off[lo + (lane + 1 + k * kWave) * step] <= x;
+    int c = 0;                                     // probes 1..c hold (the predicate is monotone)
+#pragma unroll
+    for (int k = 0; k < 4; ++k) c += __popcll(__ballot(ok[k]));
+    const int nhi = c == kProbes ? hi : lo + (c + 1) * step - 1;
     lo += c * step;
     hi = nhi;
   }
-  const bool ok = lo + lane <= hi && off[lo + lane] <= x;
-  return lo + __popcll(__ballot(ok)) - 1;
+  int c = 0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int j = lo + lane + k * kWave;
+    c += __popcll(__ballot(j <= hi && off[j] <= x));
+  }
+  return lo + c - 1;
 }
 
 }  // namespace umas

@@ -10,23 +10,35 @@
 //   turn boundary inside a trajectory segment: state scaled by gamma_turn^(step difference)
 // Every one of these is an affine map of (G, NV) of the form
 //   G' = a G + b NV + c,  NV' = e NV + f
-// and such maps compose associatively, so inside a tile of a few thousand tokens the recurrence is a parallel
-// scan over maps: threads fold their own few tokens, wavefronts and the block combine the folds, and
-// each thread replays its tokens from its incoming state.
+// and such maps compose associatively, so inside a tile of 1024 tokens the recurrence is a parallel scan over maps:
+// threads fold their own four tokens, wavefronts and the block combine the folds, and each thread replays its tokens
+// from its incoming state.
 //
-// One pass over memory (17 bytes per token): segments are independent, so the stream is cut at
-// segment boundaries into ranges of about `chunk` tokens; a block walks the tiles of its range from
-// right to left and carries the state from tile to tile itself.  No block waits for another.
+// One pass over memory (17 bytes per token).  Segments are independent, so the stream is cut into ranges of about
+// `chunk` tokens at segment boundaries; a workgroup walks the tiles of one range from right to left and carries the
+// state from tile to tile itself, the loads of the next tile in flight.  Ranges of ordinary segments need nothing
+// from each other: one workgroup per range, in any order (k_gae_scan).
+// Only a segment longer than kLongSegment tokens is cut inside.  A range whose right end lies inside such a segment
+// is left to a second kernel (k_gae_scan_cut): it first folds all of its tiles into one map and publishes it (a
+// second read of that range), composes the published maps of the ranges to its right up to the segment's end into its
+// incoming state, and then replays, so a stream that is one giant segment is still spread over the whole device.
+// That kernel's workgroups are persistent (range number j G + b from the right in round j of workgroup b) and few
+// (one per compute unit at most, a fraction of what the device holds at once, so all of them run together): a range
+// only ever waits for maps of ranges to its right, written by the first kernel or by a workgroup that is running,
+// and publishing a map waits for nothing, so every wait ends.  When no segment is that long the second kernel finds
+// nothing to do and leaves at once.
 #include "umas_common.h"
 
 namespace umas {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kIpt = 8;                          // tokens per thread (8 or 16)
+constexpr int kIpt = 4;                          // tokens per thread: one 16-byte load per array, no transposition
 constexpr int kTile = kThreads * kIpt;           // tokens per tile
-constexpr int kRow = kIpt + 4;                   // LDS words per thread row: its values + 4 words of padding
-constexpr int kLdsWords = kThreads * kRow;
+constexpr int kChunkTiles = 8;                   // nominal tiles per range
+constexpr int64_t kChunk = static_cast<int64_t>(kChunkTiles) * kTile;
+constexpr int64_t kLongSegment = 16 * kTile;     // a segment end farther away than this does not move a range's edge
+constexpr int kAhead = 1;                        // tiles whose loads are in flight beyond the one in work
 
 enum : uint8_t { kFlagMask = 1, kFlagTurnEnd = 2, kFlagRunEnd = 4 };
 
@@ -62,35 +74,79 @@ __device__ __forceinline__ Aff aff_shfl_down(const Aff& m, int o) {
     return Aff{__shfl_down(m.a, o, kWave), 0.f, __shfl_down(m.c, o, kWave), 0.f, 0.f};
 }
 
+// One range of the stream.  Ranges are numbered from the right end of the stream.
+struct __attribute__((aligned(16))) Range {
+  int64_t start, end;          // tokens [start, end); empty when start == end
+  int32_t cut_right;           // `end` lies inside a long segment: the state entering the range comes from the right
+  int32_t cut_left;            // `start` lies inside a long segment: the range to the left will ask for this one's map
+  int64_t pad;
+};
+static_assert(sizeof(Range) == 32, "two 16-byte loads");
+
+constexpr int kStateWords = 5;                     // a, b, c, e, f (without value estimates only a and c are used)
+constexpr unsigned long long kReady = 1ull << 32;  // mark in the upper half of a published word
+
 struct ScanParams {
   int64_t n_tokens;
-  int64_t chunk;               // tokens per block before snapping to segment boundaries (multiple of kTile)
-  int n_seg_entries;           // seg_off has n_seg_entries + 1 entries, ascending, from 0 to n_tokens
-  const int64_t* seg_off;
+  uint32_t n_ranges;
+  Range* ranges;                    // [n_ranges], written by k_gae_scan
+  const int64_t* seg_off;           // [n_seg_entries + 1] ascending segment offsets, from 0 to n_tokens
+  int n_seg_entries;
+  unsigned long long* range_state;  // [n_ranges][kStateWords]: a published map, one float and its ready mark per 64-bit word
   const uint8_t* flags;        // per token: mask, last-of-turn, last-of-run
   const float* reward;
   const float* value;          // may be NULL
-  const int32_t* tok_turn;     // only read when decay is on
-  const int32_t* turn_step;    // only read when decay is on
+  const int32_t* tok_turn;     // only read when the step discount is on
+  const int32_t* turn_step;    // only read when the step discount is on
   uint8_t seg_bit;             // kFlagTurnEnd or kFlagRunEnd: which flag ends a segment
-  int decay;                   // 1: scale the state by gamma_turn^dstep at turn boundaries inside a segment
   float gamma, lam, gamma_turn;
 };
 
-// Smallest boundary (value of off[0..n]) that is >= x; off[0] = 0 and off[n] >= x.  Wavefront-wide:
-// every lane of the calling wavefront takes part and gets the same answer.
+// A record is published word by word; every word carries its own ready mark, so no ordering between the words
+// is needed: a reader takes a record when all of its words are marked.  (Device-scope atomics, relaxed.)
+__device__ __forceinline__ void publish_word(unsigned long long* p, float x) {
+  __hip_atomic_store(p, kReady | static_cast<unsigned long long>(__float_as_uint(x)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool read_word(unsigned long long* p, float* x) {
+  const unsigned long long w = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  *x = __uint_as_float(static_cast<uint32_t>(w));
+  return (w >> 32) != 0;
+}
+template <bool HV>
+__device__ __forceinline__ void publish(unsigned long long* rec, const Aff& m) {
+  publish_word(rec + 0, m.a);
+  publish_word(rec + 2, m.c);
+  if constexpr (HV) {
+    publish_word(rec + 1, m.b);
+    publish_word(rec + 3, m.e);
+    publish_word(rec + 4, m.f);
+  }
+}
+
+// ------------------------------------------------------------------ ranges
+// Smallest boundary (value of off[0..n]) that is >= x, for ascending off with off[0] = 0 and off[n] >= x.
+// Wavefront-wide: every lane of the calling wavefront takes part and gets the same answer.
 __device__ __forceinline__ int64_t boundary_at_or_after(const int64_t* __restrict__ off, int n, int64_t x) {
   if (x <= 0) return 0;
   return off[wave_last_le(off, n, x - 1) + 1];
 }
-
-// Position of tile element e in the padded LDS arrays.
-__device__ __forceinline__ int lds_pos(int e) { return e + 4 * (e / kIpt); }
-
-// For every thread, the composition of the folds of all threads to its right inside the block
-// (exclusive, in application order right to left).
+// Where the range edge nominally at x really lies: at the next segment boundary unless that is farther than
+// kLongSegment away, in which case the edge stays at x, inside the segment (*cut = 1).
+__device__ __forceinline__ int64_t range_edge(const int64_t* __restrict__ off, int n, int64_t n_tokens, int64_t x, int* cut) {
+  *cut = 0;
+  if (x <= 0) return 0;
+  if (x >= n_tokens) return n_tokens;
+  const int64_t b = boundary_at_or_after(off, n, x);
+  if (b - x < kLongSegment) return b;
+  *cut = 1;
+  return x;
+}
+// ------------------------------------------------------------------ the scan
+// For every thread, the composition of the folds of all threads to its right inside the block (exclusive, in
+// application order right to left); *block_total gets the composition of all folds.  s_w holds one map per
+// wavefront; the caller alternates between two such arrays so that one barrier per tile is enough.
 template <bool HV>
-__device__ __forceinline__ Aff block_suffix_excl(Aff mine, Aff* s_w) {
+__device__ __forceinline__ Aff block_suffix_excl(Aff mine, Aff* s_w, Aff* block_total) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   constexpr int nwave = kThreads / kWave;
@@ -106,173 +162,252 @@ __device__ __forceinline__ Aff block_suffix_excl(Aff mine, Aff* s_w) {
   __syncthreads();
   Aff right_waves = aff_identity();
   for (int w = nwave - 1; w > wave; --w) right_waves = then<HV>(right_waves, s_w[w]);
+  Aff total = right_waves;
+  for (int w = wave; w >= 0; --w) total = then<HV>(total, s_w[w]);
+  *block_total = total;
   return then<HV>(right_waves, excl);
 }
 
+// The state that enters range q from the right, found by one wavefront: lane l looks at range q - 1 - l (ranges are
+// numbered from the right), and the maps are composed up to the nearest range whose map is a constant, i.e. which
+// holds the segment's end.  Only the records up to that range are waited for.
 template <bool HV>
-__global__ void __launch_bounds__(kThreads)
-k_gae_scan(ScanParams P, float* __restrict__ adv, float* __restrict__ ret) {
-  __shared__ __attribute__((aligned(16))) float s_r[kLdsWords], s_v[kLdsWords];
-  __shared__ Aff s_w[kThreads / kWave];
-  __shared__ float s_carry[2];
-  __shared__ int64_t s_range[2];
-  const int tid = threadIdx.x;
-  if (tid < 2 * kWave) {     // wavefront 0 finds the left end of the range, wavefront 1 the right end
-    const int which = tid / kWave;
-    const int64_t x = (static_cast<int64_t>(blockIdx.x) + which) * P.chunk;
-    const int64_t bnd = x >= P.n_tokens ? P.n_tokens : boundary_at_or_after(P.seg_off, P.n_seg_entries, x);
-    if ((tid & (kWave - 1)) == 0) {
-      s_range[which] = bnd;
-      s_carry[which] = 0.f;
+__device__ __forceinline__ void look_back(const ScanParams& P, uint32_t q, float* G_in, float* NV_in) {
+  const int lane = threadIdx.x & (kWave - 1);
+  Aff M = aff_identity();
+  for (int64_t base = static_cast<int64_t>(q) - 1;; base -= kWave) {
+    const int64_t k = base - lane;
+    Aff A{0.f, 0.f, 0.f, 0.f, 0.f};                 // past the right end of the stream: the constant map to (0, 0)
+    bool ready = true;
+    int first = kWave;
+    while (true) {
+      if (k >= 0) {
+        unsigned long long* rec = P.range_state + static_cast<size_t>(k) * kStateWords;
+        ready = read_word(rec + 0, &A.a);
+        ready = read_word(rec + 2, &A.c) && ready;
+        if constexpr (HV) {
+          ready = read_word(rec + 1, &A.b) && ready;
+          ready = read_word(rec + 3, &A.e) && ready;
+          ready = read_word(rec + 4, &A.f) && ready;
+        }
+      }
+      const bool closed = ready && A.a == 0.f && (!HV || (A.b == 0.f && A.e == 0.f));   // a constant map: nothing further right matters
+      const unsigned long long rdy = __ballot(ready), cls = __ballot(closed);
+      const int n_ready = rdy == ~0ull ? kWave : __ffsll(static_cast<long long>(~rdy)) - 1;   // ready records in a row from lane 0
+      first = cls ? __ffsll(static_cast<long long>(cls)) - 1 : kWave;
+      if (first < n_ready || n_ready == kWave) break;
+      __builtin_amdgcn_s_sleep(8);
     }
+    const int upto = first < kWave ? first : kWave - 1;
+    for (int j = 0; j <= upto; ++j) {
+      Aff Aj;
+      Aj.a = __shfl(A.a, j, kWave);
+      Aj.c = __shfl(A.c, j, kWave);
+      Aj.b = HV ? __shfl(A.b, j, kWave) : 0.f;
+      Aj.e = HV ? __shfl(A.e, j, kWave) : 0.f;
+      Aj.f = HV ? __shfl(A.f, j, kWave) : 0.f;
+      M = then<HV>(Aj, M);                          // the farther range acts first
+    }
+    if (first < kWave) break;
   }
-  __syncthreads();
-  const int64_t start = s_range[0], end = s_range[1];
-  if (start >= end) return;
+  *G_in = M.c;                                      // a constant map: its value
+  *NV_in = HV ? M.f : 0.f;
+}
+
+// this thread's four consecutive tokens of a tile: 16 bytes per array, 4 bytes of flags; tokens past the end of the
+// stream read as masked, without flags
+struct Raw {
+  float4 r4, v4;
+  uint32_t w;
+};
+template <bool HV>
+__device__ __forceinline__ void load_tile(const ScanParams& P, const Range& R, int64_t tile, Raw& x) {
+  const int64_t p = tile * kTile + static_cast<int64_t>(threadIdx.x) * kIpt;
+  x.r4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  x.v4 = x.r4;
+  x.w = 0;
+  if (p + kIpt <= R.start || p >= R.end) return;    // none of these tokens belongs to the range: a neighbour reads them
+  if (p + kIpt <= P.n_tokens) {
+    x.r4 = *reinterpret_cast<const float4*>(P.reward + p);
+    if constexpr (HV) x.v4 = *reinterpret_cast<const float4*>(P.value + p);
+    x.w = *reinterpret_cast<const uint32_t*>(P.flags + p);
+  } else {
+    float* rp = &x.r4.x;
+    float* vp = &x.v4.x;
+    for (int j = 0; j < kIpt; ++j)
+      if (p + j < P.n_tokens) {
+        rp[j] = P.reward[p + j];
+        if constexpr (HV) vp[j] = P.value[p + j];
+        x.w |= static_cast<uint32_t>(P.flags[p + j]) << (8 * j);
+      }
+  }
+}
+
+// One walk over the tiles of a range, right to left.  REPLAY = false: fold only, returns the range's map in *total.
+// REPLAY = true: starts from the state (*G_io, *NV_io), writes advantages and returns, leaves the state at the
+// range's left edge in (*G_io, *NV_io) (valid in thread 0).
+template <bool HV, bool DECAY, bool REPLAY>
+__device__ __forceinline__ void walk_range(const ScanParams& P, const Range& R, float* __restrict__ adv, float* __restrict__ ret,
+                                           Aff (*s_w)[kThreads / kWave], float (*s_carry)[2], float* G_io, float* NV_io, Aff* total) {
+  const int tid = threadIdx.x;
   const float gl = P.gamma * P.lam;
-
-  // raw tile in registers: element e = k*(kThreads*4) + tid*4 of the tile for the values (coalesced 16-byte
-  // loads), this thread's own kIpt consecutive tokens for the flags
-  struct Raw {
-    float4 r4[kIpt / 4], v4[kIpt / 4];
-    uint32_t w[kIpt / 4];
-  };
-  auto load_tile = [&](int64_t t0, Raw& x) {
+  const int64_t t_hi = (R.end - 1) / kTile, t_lo = R.start / kTile;
+  Raw buf[kAhead + 1];
 #pragma unroll
-    for (int k = 0; k < kIpt / 4; ++k) {
-      const int64_t p = t0 + k * (kThreads * 4) + tid * 4;
-      x.r4[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-      x.v4[k] = x.r4[k];
-      if (p + 3 < P.n_tokens) {
-        x.r4[k] = *reinterpret_cast<const float4*>(P.reward + p);
-        if constexpr (HV) x.v4[k] = *reinterpret_cast<const float4*>(P.value + p);
-      } else {
-        float* rp = &x.r4[k].x;
-        float* vp = &x.v4[k].x;
-        for (int j = 0; j < 4; ++j)
-          if (p + j < P.n_tokens) {
-            rp[j] = P.reward[p + j];
-            if constexpr (HV) vp[j] = P.value[p + j];
-          }
-      }
-    }
-    const int64_t p0 = t0 + static_cast<int64_t>(tid) * kIpt;
-    if (p0 + kIpt <= P.n_tokens) {
-      if constexpr (kIpt == 16) {
-        const uint4 f4 = *reinterpret_cast<const uint4*>(P.flags + p0);
-        x.w[0] = f4.x; x.w[1] = f4.y; x.w[2] = f4.z; x.w[3] = f4.w;
-      } else {
-        const uint2 f2 = *reinterpret_cast<const uint2*>(P.flags + p0);
-        x.w[0] = f2.x; x.w[1] = f2.y;
-      }
-    } else {
+  for (int a = 0; a <= kAhead; ++a)
+    if (t_hi - a >= t_lo) load_tile<HV>(P, R, t_hi - a, buf[a]);
+  Aff range_map = aff_identity();
+  if (REPLAY && tid == 0) { s_carry[0][0] = *G_io; s_carry[0][1] = *NV_io; }
+  int par = 0;
+  float G = 0.f, NV = 0.f;
+  for (int64_t tile = t_hi; tile >= t_lo; --tile) {
+    const Raw x = buf[0];
 #pragma unroll
-      for (int k = 0; k < kIpt / 4; ++k) x.w[k] = 0;
-      for (int k = 0; k < kIpt; ++k)
-        if (p0 + k < P.n_tokens) x.w[k >> 2] |= static_cast<uint32_t>(P.flags[p0 + k]) << (8 * (k & 3));
-    }
-  };
-
-  const int64_t tile_first = start / kTile;
-  Raw nxt;
-  load_tile(((end - 1) / kTile) * kTile, nxt);
-  for (int64_t tile = (end - 1) / kTile; tile >= tile_first; --tile) {
-    const int64_t t0 = tile * kTile;
-    // transpose through LDS into kIpt consecutive tokens per thread
-#pragma unroll
-    for (int k = 0; k < kIpt / 4; ++k) {
-      const int e = k * (kThreads * 4) + tid * 4;
-      *reinterpret_cast<float4*>(s_r + lds_pos(e)) = nxt.r4[k];
-      if constexpr (HV) *reinterpret_cast<float4*>(s_v + lds_pos(e)) = nxt.v4[k];
-    }
-    const int64_t p0 = t0 + static_cast<int64_t>(tid) * kIpt;   // this thread's first token
-    uint8_t fl[kIpt];
-#pragma unroll
-    for (int k = 0; k < kIpt; ++k) fl[k] = static_cast<uint8_t>(nxt.w[k >> 2] >> (8 * (k & 3)));
-    if (tile > tile_first) load_tile(t0 - kTile, nxt);           // in flight while this tile is computed
-    __syncthreads();
-    float r[kIpt], v[kIpt];
-#pragma unroll
-    for (int k = 0; k < kIpt / 4; ++k) {
-      const float4 r4 = *reinterpret_cast<const float4*>(s_r + tid * kRow + 4 * k);
-      float4 v4 = make_float4(0.f, 0.f, 0.f, 0.f);
-      if constexpr (HV) v4 = *reinterpret_cast<const float4*>(s_v + tid * kRow + 4 * k);
-      r[4 * k] = r4.x; r[4 * k + 1] = r4.y; r[4 * k + 2] = r4.z; r[4 * k + 3] = r4.w;
-      v[4 * k] = v4.x; v[4 * k + 1] = v4.y; v[4 * k + 2] = v4.z; v[4 * k + 3] = v4.w;
-    }
-    // tokens outside this block's range belong to a neighbour: identity here, not stored
-    float kap[kIpt];   // decay applied before the token (1 = none)
+    for (int a = 0; a < kAhead; ++a) buf[a] = buf[a + 1];
+    if (tile - kAhead - 1 >= t_lo) load_tile<HV>(P, R, tile - kAhead - 1, buf[kAhead]);
+    const int64_t p0 = tile * kTile + static_cast<int64_t>(tid) * kIpt;
+    const float r[kIpt] = {x.r4.x, x.r4.y, x.r4.z, x.r4.w};
+    const float v[kIpt] = {x.v4.x, x.v4.y, x.v4.z, x.v4.w};
+    uint32_t fl[kIpt];
+    float kap[kIpt];                                // step discount applied before the token (1 = none)
+    bool mine[kIpt];                                // tokens outside the range belong to a neighbour
 #pragma unroll
     for (int k = 0; k < kIpt; ++k) {
-      const int64_t p = p0 + k;
-      if (p < start || p >= end) fl[k] = 0xFF;                   // marks "not mine"
+      fl[k] = (x.w >> (8 * k)) & 0xFFu;
+      mine[k] = p0 + k >= R.start && p0 + k < R.end;
       kap[k] = 1.f;
-      if (P.decay && fl[k] != 0xFF && (fl[k] & kFlagTurnEnd) && !(fl[k] & P.seg_bit)) {
-        const int ds = P.turn_step[P.tok_turn[p + 1]] - P.turn_step[P.tok_turn[p]];
-        kap[k] = powf(P.gamma_turn, static_cast<float>(ds));
+      if constexpr (DECAY) {
+        if (mine[k] && (fl[k] & kFlagTurnEnd) && !(fl[k] & P.seg_bit)) {   // a later turn of the same run follows: p + 1 exists
+          const int64_t p = p0 + k;
+          const int ds = P.turn_step[P.tok_turn[p + 1]] - P.turn_step[P.tok_turn[p]];
+          kap[k] = powf(P.gamma_turn, static_cast<float>(ds));
+        }
       }
     }
     // fold of this thread's tokens, right to left
     Aff acc = aff_identity();
 #pragma unroll
     for (int k = kIpt - 1; k >= 0; --k) {
-      if (fl[k] == 0xFF) continue;
+      if (!mine[k]) continue;
       if (fl[k] & P.seg_bit) acc = Aff{0.f, 0.f, 0.f, 0.f, 0.f};
-      else if (P.decay) { acc.a *= kap[k]; acc.b *= kap[k]; acc.c *= kap[k]; acc.e *= kap[k]; acc.f *= kap[k]; }
+      else if constexpr (DECAY) { acc.a *= kap[k]; acc.b *= kap[k]; acc.c *= kap[k]; acc.e *= kap[k]; acc.f *= kap[k]; }
       if (fl[k] & kFlagMask) {
         const Aff t{gl, P.gamma, r[k] - v[k], 0.f, v[k]};
         acc = then<HV>(acc, t);
       }
     }
-    const Aff from_right = block_suffix_excl<HV>(acc, s_w);
-    float G = from_right.a * s_carry[0] + from_right.b * s_carry[1] + from_right.c;
-    float NV = 0.f;
-    if constexpr (HV) NV = from_right.e * s_carry[1] + from_right.f;
-    // replay; results overwrite this thread's own LDS rows
+    Aff tile_map;
+    const Aff from_right = block_suffix_excl<HV>(acc, s_w[par], &tile_map);   // the one barrier of a tile
+    if constexpr (!REPLAY) {
+      range_map = then<HV>(range_map, tile_map);    // tiles further right act first
+    } else {
+      G = from_right.a * s_carry[par][0] + from_right.b * s_carry[par][1] + from_right.c;
+      NV = 0.f;
+      if constexpr (HV) NV = from_right.e * s_carry[par][1] + from_right.f;
+      float a[kIpt], b[kIpt];
 #pragma unroll
-    for (int k = kIpt - 1; k >= 0; --k) {
-      float a = 0.f, b = 0.f;
-      if (fl[k] != 0xFF) {
+      for (int k = kIpt - 1; k >= 0; --k) {
+        a[k] = 0.f;
+        b[k] = 0.f;
+        if (!mine[k]) continue;
         if (fl[k] & P.seg_bit) { G = 0.f; NV = 0.f; }
-        else if (P.decay) { G *= kap[k]; NV *= kap[k]; }
+        else if constexpr (DECAY) { G *= kap[k]; NV *= kap[k]; }
         if (fl[k] & kFlagMask) {
           G = (r[k] - v[k]) + P.gamma * NV + gl * G;
           NV = v[k];
-          a = G;
-          b = G + v[k];
+          a[k] = G;
+          b[k] = G + v[k];
         }
       }
-      r[k] = a;
-      v[k] = b;
-    }
-#pragma unroll
-    for (int k = 0; k < kIpt / 4; ++k) {
-      *reinterpret_cast<float4*>(s_r + tid * kRow + 4 * k) = make_float4(r[4 * k], r[4 * k + 1], r[4 * k + 2], r[4 * k + 3]);
-      if constexpr (HV)     // without values the return equals the advantage
-        *reinterpret_cast<float4*>(s_v + tid * kRow + 4 * k) = make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
-    }
-    __syncthreads();                       // everyone has read s_carry and written its results
-    if (tid == 0) { s_carry[0] = G; s_carry[1] = NV; }   // state at the tile's left edge
-#pragma unroll
-    for (int k = 0; k < kIpt / 4; ++k) {
-      const int e = k * (kThreads * 4) + tid * 4;
-      const int64_t p = t0 + e;
-      const float4 a4 = *reinterpret_cast<const float4*>(s_r + lds_pos(e));
-      float4 b4 = a4;
-      if constexpr (HV) b4 = *reinterpret_cast<const float4*>(s_v + lds_pos(e));
-      if (p >= start && p + 3 < end) {
-        *reinterpret_cast<float4*>(adv + p) = a4;
-        *reinterpret_cast<float4*>(ret + p) = b4;
+      if (tid == 0) { s_carry[par ^ 1][0] = G; s_carry[par ^ 1][1] = NV; }   // state at the tile's left edge
+      if (mine[0] && mine[kIpt - 1]) {
+        *reinterpret_cast<float4*>(adv + p0) = make_float4(a[0], a[1], a[2], a[3]);
+        *reinterpret_cast<float4*>(ret + p0) = make_float4(b[0], b[1], b[2], b[3]);
       } else {
-        const float* ap = &a4.x;
-        const float* bp = &b4.x;
-        for (int j = 0; j < 4; ++j)
-          if (p + j >= start && p + j < end) { adv[p + j] = ap[j]; ret[p + j] = bp[j]; }
+#pragma unroll
+        for (int k = 0; k < kIpt; ++k)
+          if (mine[k]) { adv[p0 + k] = a[k]; ret[p0 + k] = b[k]; }
       }
     }
-    __syncthreads();                       // LDS and s_carry are reused by the next tile
+    par ^= 1;
+  }
+  if constexpr (REPLAY) { *G_io = G; *NV_io = NV; } else { *total = range_map; }
+}
+
+// One workgroup per range.  It finds the range's edges (two wavefront-wide searches, one wavefront each), leaves them
+// for the second kernel and clears the range's record; then, unless the range is empty or its right end lies inside a
+// long segment, it scans the range: nothing comes in from the right.
+template <bool HV, bool DECAY>
+__global__ void __launch_bounds__(kThreads)
+k_gae_scan(ScanParams P, float* __restrict__ adv, float* __restrict__ ret) {
+  __shared__ Aff s_w[2][kThreads / kWave];
+  __shared__ float s_carry[2][2];
+  __shared__ int64_t s_edge[2];
+  __shared__ int s_cut[2];
+  const int tid = threadIdx.x;
+  const uint32_t q = blockIdx.x;                                                   // from the right
+  const int64_t i = static_cast<int64_t>(P.n_ranges) - 1 - q;                      // from the left
+  if (tid < 2 * kWave) {
+    const int which = tid / kWave;                   // wavefront 0: left edge, wavefront 1: right edge
+    int cut;
+    const int64_t edge = range_edge(P.seg_off, P.n_seg_entries, P.n_tokens, (i + which) * kChunk, &cut);
+    if ((tid & (kWave - 1)) == 0) { s_edge[which] = edge; s_cut[which] = cut; }
+  }
+  __syncthreads();
+  Range R;
+  R.start = s_edge[0];
+  R.end = s_edge[1];
+  R.cut_left = s_cut[0];
+  R.cut_right = s_cut[1];
+  R.pad = 0;
+  if (tid == 0) P.ranges[q] = R;
+  if (tid < kStateWords) P.range_state[static_cast<size_t>(q) * kStateWords + tid] = 0ull;
+  if (R.start >= R.end || R.cut_right) return;      // the same for every thread
+  float G = 0.f, NV = 0.f;
+  Aff unused;
+  walk_range<HV, DECAY, true>(P, R, adv, ret, s_w, s_carry, &G, &NV, &unused);
+  // a range that starts inside a long segment: what it hands to the left is a constant
+  if (R.cut_left && tid == 0)
+    publish<HV>(P.range_state + static_cast<size_t>(q) * kStateWords, Aff{0.f, 0.f, G, 0.f, HV ? NV : 0.f});
+}
+
+// The ranges whose right end lies inside a long segment; persistent workgroups.
+template <bool HV, bool DECAY>
+__global__ void __launch_bounds__(kThreads)
+k_gae_scan_cut(ScanParams P, float* __restrict__ adv, float* __restrict__ ret) {
+  __shared__ Aff s_w[2][kThreads / kWave];
+  __shared__ float s_carry[2][2];
+  __shared__ float s_in[2];
+  const int tid = threadIdx.x;
+  // does any of this workgroup's ranges need it?  every thread looks at some of them, all loads at once
+  int mine = 0;
+  for (uint64_t q = blockIdx.x + static_cast<uint64_t>(tid) * gridDim.x; q < P.n_ranges; q += static_cast<uint64_t>(kThreads) * gridDim.x)
+    mine |= P.ranges[q].cut_right;
+  if (!__syncthreads_or(mine)) return;
+  for (uint32_t q = blockIdx.x; q < P.n_ranges; q += gridDim.x) {
+    const Range R = P.ranges[q];
+    if (R.start >= R.end || !R.cut_right) continue; // the same for every thread
+    // the range's own map first (published if the left end is cut too), then the state that the ranges to its right
+    // hand over, then the replay
+    float G = 0.f, NV = 0.f;
+    Aff range_map;
+    walk_range<HV, DECAY, false>(P, R, adv, ret, s_w, s_carry, &G, &NV, &range_map);
+    if (R.cut_left && tid == 0) publish<HV>(P.range_state + static_cast<size_t>(q) * kStateWords, range_map);
+    if (tid < kWave) {
+      float g_in, nv_in;
+      look_back<HV>(P, q, &g_in, &nv_in);
+      if (tid == 0) { s_in[0] = g_in; s_in[1] = nv_in; }
+    }
+    __syncthreads();                                // also: the LDS of the first walk is free
+    G = s_in[0];
+    NV = s_in[1];
+    Aff unused;
+    walk_range<HV, DECAY, true>(P, R, adv, ret, s_w, s_carry, &G, &NV, &unused);
+    __syncthreads();
   }
 }
+
+inline int64_t scan_ranges(int64_t n_tokens) { return (n_tokens + kChunk - 1) / kChunk; }
 
 }  // namespace
 }  // namespace umas
@@ -280,16 +415,15 @@ k_gae_scan(ScanParams P, float* __restrict__ adv, float* __restrict__ ret) {
 using namespace umas;
 
 extern "C" size_t umas_advantages_workspace_bytes(int64_t n_tokens) {
-  (void)n_tokens;
-  return kAlign;   // the scan keeps its state on chip; the argument is kept for interface stability
+  if (n_tokens < 0) return 0;
+  const size_t n = static_cast<size_t>(scan_ranges(n_tokens) > 0 ? scan_ranges(n_tokens) : 1);
+  return align_up(n * sizeof(Range)) + align_up(n * kStateWords * sizeof(unsigned long long));   // ranges, records
 }
 
 extern "C" umas_status umas_advantages(const umas_streams* s, int64_t n_tokens, int32_t n_turns,
                                        const float* value, float gamma, float lam, float gamma_turn,
                                        int32_t seg_mode, float* adv, float* ret, void* workspace,
                                        size_t workspace_bytes, void* hip_stream) {
-  (void)workspace;
-  (void)workspace_bytes;
   UMAS_REQUIRE(s, UMAS_EINVAL, "streams is NULL");
   UMAS_REQUIRE(n_tokens >= 0 && n_turns >= 0, UMAS_EINVAL, "negative size");
   UMAS_REQUIRE(seg_mode == UMAS_SEG_TURN || seg_mode == UMAS_SEG_TRAJ, UMAS_EINVAL, "seg_mode=%d is neither TURN nor TRAJ",
@@ -302,30 +436,47 @@ extern "C" umas_status umas_advantages(const umas_streams* s, int64_t n_tokens, 
                    reinterpret_cast<uintptr_t>(s->tok_flags) % 16 == 0 && reinterpret_cast<uintptr_t>(adv) % 16 == 0 &&
                    reinterpret_cast<uintptr_t>(ret) % 16 == 0,
                UMAS_EINVAL, "tok_reward, tok_flags, value, adv and ret must be 16-byte aligned");
+  UMAS_REQUIRE(scan_ranges(n_tokens) < (1LL << 31), UMAS_ESHAPE, "at most 2^43 tokens");
+  const size_t need = umas_advantages_workspace_bytes(n_tokens);
+  UMAS_REQUIRE(workspace && reinterpret_cast<uintptr_t>(workspace) % kAlign == 0 && workspace_bytes >= need, UMAS_EWORKSPACE,
+               "workspace must be 256-byte aligned and hold %zu bytes (got %zu)", need, workspace_bytes);
   if (n_tokens == 0) return UMAS_OK;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   prof_mark(st);
+  const int64_t n_ranges = scan_ranges(n_tokens);
   ScanParams P;
   P.n_tokens = n_tokens;
-  // about 32 ranges per compute unit (several rounds of resident blocks), each a whole number of tiles before it is snapped to segment boundaries
-  const int64_t tiles = (n_tokens + kTile - 1) / kTile;
-  const int64_t tiles_per_block = (tiles + 8191) / 8192;
-  P.chunk = tiles_per_block * kTile;
-  P.n_seg_entries = n_turns;
+  P.n_ranges = static_cast<uint32_t>(n_ranges);
+  Range* ranges = static_cast<Range*>(workspace);
+  P.ranges = ranges;
+  P.range_state = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + align_up(static_cast<size_t>(n_ranges) * sizeof(Range)));
   P.seg_off = seg_mode == UMAS_SEG_TURN ? s->turn_seg_off : s->traj_seg_off;
+  P.n_seg_entries = n_turns;
   P.flags = s->tok_flags;
   P.reward = s->tok_reward;
   P.value = value;
   P.tok_turn = s->tok_turn;
   P.turn_step = s->turn_step;
   P.seg_bit = seg_mode == UMAS_SEG_TURN ? kFlagTurnEnd : kFlagRunEnd;
-  P.decay = (seg_mode == UMAS_SEG_TRAJ && gamma_turn != 1.0f) ? 1 : 0;
   P.gamma = gamma;
   P.lam = lam;
   P.gamma_turn = gamma_turn;
-  const unsigned nblk = cdiv(n_tokens, P.chunk);
-  if (value) hipLaunchKernelGGL(k_gae_scan<true>, dim3(nblk), dim3(kThreads), 0, st, P, adv, ret);
-  else hipLaunchKernelGGL(k_gae_scan<false>, dim3(nblk), dim3(kThreads), 0, st, P, adv, ret);
+  const bool decay = seg_mode == UMAS_SEG_TRAJ && gamma_turn != 1.0f;
+  void (*kernel)(ScanParams, float*, float*) =
+      value ? (decay ? k_gae_scan<true, true> : k_gae_scan<true, false>) : (decay ? k_gae_scan<false, true> : k_gae_scan<false, false>);
+  hipLaunchKernelGGL(kernel, dim3(P.n_ranges), dim3(kThreads), 0, st, P, adv, ret);
   UMAS_LAUNCHED("k_gae_scan");
+  // The ranges cut inside long segments: persistent workgroups that wait for each other's maps.  At most one workgroup
+  // per compute unit, far fewer than the device holds at once: whatever else is running, all of them get to run
+  // together, so no workgroup waits for one that cannot start.
+  void (*kernel_cut)(ScanParams, float*, float*) =
+      value ? (decay ? k_gae_scan_cut<true, true> : k_gae_scan_cut<true, false>)
+            : (decay ? k_gae_scan_cut<false, true> : k_gae_scan_cut<false, false>);
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+    n_cu = 64;
+  const unsigned nblk = static_cast<unsigned>(n_ranges < n_cu ? n_ranges : n_cu);
+  hipLaunchKernelGGL(kernel_cut, dim3(nblk), dim3(kThreads), 0, st, P, adv, ret);
+  UMAS_LAUNCHED("k_gae_scan_cut");
   return UMAS_OK;
 }

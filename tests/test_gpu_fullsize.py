@@ -2,8 +2,8 @@
 
 The CPU oracle cannot score 10^5 rows against a 152k-entry vocabulary inside a test, so its
 log-probs, logsumexps and entropies come from files under tests/golden/ that
-tests/golden/make_fullsize_golden.py wrote by calling the oracle alone (all scored rows for the
-3B-shaped configurations, a seeded row sample for the larger ones).  Everything else the oracle
+tests/golden/make_fullsize_golden.py wrote by calling the oracle alone (every scored row of every model of
+configurations 1 to 4; the code also takes files that hold a seeded row sample).  Everything else the oracle
 computes here, live: routing, rewards and advantages on the whole batch, the surrogate statistics and
 per-row gradients, and dH / dW on sampled rows and vocabulary entries, which depend on one row or one
 vocabulary entry at a time once the stored logsumexp is given.
@@ -23,7 +23,7 @@ pytestmark = pytest.mark.gpu
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 TOL_LOGP, TOL = 2e-2, 1e-2          # bf16: absolute on log-probs, relative on loss and gradients
-N_DH_ROWS, N_DW_ROWS = 96, 192
+N_DH_ROWS, N_DW_ROWS = 128, 320        # sampled rows of dH; sampled vocabulary entries of dW (at least 256 after merging)
 
 
 def fingerprint(t):
@@ -128,6 +128,7 @@ def run_fullsize(cfg):
             pos[vs] = np.arange(len(vs))
             W_sub = np.concatenate([t["W"][vs], np.zeros((1, spec.d), t["W"].dtype)])
             _, dW_sub = orc.lm_head_backward(t["H"], W_sub, pos[t["ids"]], lse_o, g_o, rowsel_o, chunk=4096)
+            assert len(vs) >= 256
             rel_w = P.close(dW_host[vs], dW_sub[:len(vs)], TOL, "dW sample")
         # every row of dz sums to zero over the vocabulary, so dW summed over the vocabulary vanishes
         col = dW_host.sum(axis=0, dtype=np.float64)
@@ -176,7 +177,10 @@ def test_full_size_single_pass_backward_agrees_with_recomputing_backward():
     del dH, dW
     assert np.array_equal(lc, out[0][1]) and np.array_equal(dHc, out[0][2])
     assert float(sc_["loss"][0]) == float(out[0][0]["loss"][0])
-    P.close(dWc, out[0][3], 1e-4, "dW, three chunks against one")
+    # the same products summed in float32 in another grouping (three partial sums) and one-hot rows added by atomics in
+    # another order: a few 2^-24 of the sum of the terms' magnitudes, which is up to a hundred times an entry that
+    # cancels; a tenth of the gradient bar
+    P.close(dWc, out[0][3], 1e-3, "dW, three chunks against one")
     (sa, la, dHa, dWa), (sb, lb, dHb, dWb) = out
     assert np.abs(la - lb).max() <= 1e-4
     assert abs(float(sa["loss"][0]) - float(sb["loss"][0])) <= 1e-5 * max(abs(float(sb["loss"][0])), 1e-3)

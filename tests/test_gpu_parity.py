@@ -457,6 +457,44 @@ def test_random_graphs(seed):
     P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
 
 
+@pytest.mark.parametrize("seg_mode,gamma_turn,with_value,dense,gamma,lam", [
+    (0, 1.0, True, False, 1.0, 1.0), (1, 0.9, True, True, 1.0, 1.0), (1, 1.0, False, True, 1.0, 1.0),
+    (0, 1.0, True, False, 0.99, 0.95), (1, 0.9, True, False, 0.9999, 0.9995), (1, 1.0, True, True, 1.0, 0.99)])
+def test_scan_segments_far_longer_than_a_range(seg_mode, gamma_turn, with_value, dense, gamma, lam):
+    """Turns of up to 150 000 tokens and a trajectory run of 400 000: far more than one workgroup's range, so the
+    segments are cut inside and the ranges hand their state over through published maps (dozens of ranges deep, with
+    a masked stretch longer than a range, short segments in between and a long one at either end of the stream).
+    With gamma = lam = 1 a token feels everything to its right in the segment; with the slowly decaying pairs thousands
+    of tokens, and there the sums of terms that cancel get the float32 allowance of parity.scan_conditioning."""
+    w = wl.make_workload(0)
+    rng = np.random.default_rng(4242 + 10 * seg_mode + int(10 * gamma_turn))
+    lens_per_traj = [[150000, 3, 0, 100000, 150000], [17], [40000, 2049], [5, 70000, 1, 90000]]
+    roles_per_traj = [[0, 1, 0, 0, 1], [1], [0, 0], [1, 0, 1, 1]]
+    lens = np.array([l for t in lens_per_traj for l in t], np.int64)
+    w.n_traj, w.n_turns, w.n_roles, w.n_models = len(lens_per_traj), len(lens), 2, 1
+    w.traj_turn_off = np.concatenate([[0], np.cumsum([len(t) for t in lens_per_traj])]).astype(np.int32)
+    w.turn_role = np.array([r for t in roles_per_traj for r in t], np.int32)
+    w.role_to_model = np.zeros(2, np.int32)
+    w.turn_tok_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    w.n_tokens = int(w.turn_tok_off[-1])
+    w.turn_pred_off, w.turn_pred, w.traj_group = None, None, None
+    mask = (rng.random(w.n_tokens) < 0.8).astype(np.uint8)
+    mask[200000:230000] = 0                                  # a masked stretch longer than a range
+    w.tok_mask = mask
+    w.traj_reward = rng.normal(size=w.n_traj).astype(np.float32)
+    w.turn_reward = rng.normal(size=w.n_turns).astype(np.float32)
+    w.role_reward = None
+    w.value = (0.1 * rng.normal(size=w.n_tokens)).astype(np.float32) if with_value else None
+    kw = dict(seg_mode=seg_mode, gamma_turn=gamma_turn, place_mode=wl.PLACE_ALL if dense else wl.PLACE_LAST, gamma=gamma, lam=lam)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w, **kw)
+    s, adv, ret = P.gpu_front(w, **kw)
+    adv_abs = None
+    if gamma * lam < 1.0 and gamma * lam > 0.96:
+        adv_abs = 4 * 2.0 ** -24 * P.scan_conditioning(st, w.traj_turn_off, r, w.value, gamma, lam, gamma_turn, seg_mode)
+    P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o, adv_abs=adv_abs)
+    assert np.abs(adv_o[:1000]).max() > 0
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_on_policy_update_without_old_logprobs(dtype):
     """logp_old = NULL: the call's own log-probs stand for the old ones (ratio 1 on every row, nothing clipped)."""
