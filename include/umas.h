@@ -124,7 +124,10 @@ typedef struct {
   float*   turn_scalar;       /* [n_turns]     composed reward of each turn, global turn order */
   int32_t* turn_step;         /* [n_turns]     1-based position of the turn inside its trajectory */
   uint8_t* tok_flags;         /* [n_tokens]    bit 0 = mask, bit 1 = last token of its turn segment,
-                                               bit 2 = last token of its trajectory run (read by umas_advantages) */
+                                               bit 2 = last token of its trajectory run; on a turn's last token that
+                                               does not end the run, bits 3-7 = steps from this turn to the run's next
+                                               turn with tokens (31 = more than 30: take the difference of turn_step);
+                                               read by umas_advantages */
 } umas_streams;
 
 /* Bytes of workspace umas_assign_token_rewards needs for this graph. */

@@ -30,6 +30,7 @@ class ThinStage {
   umas_status begin(size_t bytes);
   // Copies n bytes to offset `off` of the block (nothing for src == nullptr or n == 0).
   void put(size_t off, const void* src, size_t n);
+  void zero(size_t off, size_t n);
   // Enqueues the copy of the first `bytes` bytes of the block to `dst` on `st` and releases the ring.
   umas_status flush(void* dst, size_t bytes, hipStream_t st);
   // Releases the ring without copying (an error between begin and flush).

@@ -91,6 +91,10 @@ void ThinStage::put(size_t off, const void* src, size_t n) {
   if (src && n) memcpy(cur_ + off, src, n);
 }
 
+void ThinStage::zero(size_t off, size_t n) {
+  if (n) memset(cur_ + off, 0, n);
+}
+
 umas_status ThinStage::flush(void* dst, size_t bytes, hipStream_t st) {
   StageSlot& s = g_slots[slot_];
   hipError_t e = hipSuccess;

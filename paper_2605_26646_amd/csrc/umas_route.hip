@@ -7,36 +7,47 @@
 // phi(role) into model-local streams (Sections "Agent--LLM Mapping", "Model-Local Buffers")
 // and the alignment of each turn's reward with its token sequence (paragraph "Batch
 // construction").
+//
+// Three kernels (four with normalisation groups).  k_turn_plan does everything that is per turn: one thread walks
+// one trajectory's turns (a trajectory's turns are consecutive, and everything a turn needs from its neighbours -
+// whether it opens or closes the trajectory's run inside its model's stream, how many steps lie between it and the
+// run's next turn - lies inside its trajectory), blocks of 256 trajectories publish their per-model totals and read
+// everybody else's to place themselves.  k_tokens writes everything that is per token in one pass over the streams
+// (22 bytes per token, the mask read once); k_rowsel compacts the positions of the scored tokens (the gathered mask
+// read again, 4 bytes per scored token written).
 #include <algorithm>
 #include <vector>
 
 #include "umas_common.h"
 
 namespace umas {
+
 namespace {
 
-constexpr int kTurnBlock = 256;   // turns per block in the turn-level kernels
+constexpr int kPlanThreads = 256;  // trajectories per chunk of the plan kernel
+constexpr int kPlanMaxGrid = 512;  // its workgroups at most: light ones, all of them resident at once
+constexpr int kCnt = 3;            // per model and chunk: turns, tokens, trajectory runs
+constexpr int kPlanWords = UMAS_MAX_MODELS * kCnt;
 constexpr int kTokThreads = 256;
 constexpr int kTokPerThread = 4;   // consecutive tokens of one thread in one round
 constexpr int kTokRounds = 4;      // rounds of a block, kTokThreads * kTokPerThread tokens apart
 constexpr int kTokRound = kTokThreads * kTokPerThread;
 constexpr int kTokBlock = kTokRound * kTokRounds;
-constexpr int kCntTokens = 4096;   // mask=1 tokens are counted per this many tokens (one compaction block)
-constexpr int kCntRounds = kCntTokens / kTokRound;
-static_assert(kTokBlock % kCntTokens == 0 && kCntTokens % kTokRound == 0, "a token block is a whole number of count groups");
+constexpr unsigned long long kMark = 1ull << 63;          // ready mark of a published count
 
 // What the token kernel needs to know about one turn segment of a model-local stream.
 struct __attribute__((aligned(16))) SegMeta {
   int64_t src;         // global index of the segment's first token
-  int64_t last_valid;  // model-local position of its last mask=1 token, or -1
   int32_t turn;
   int32_t role;
   float rho;           // composed reward of the turn
   int32_t end_flags;   // flag bits of the segment's last token besides the mask bit
+  int64_t pad;
 };
 static_assert(sizeof(SegMeta) == 32, "two 16-byte loads");
 
 struct RouteWs {
+  // the thin arrays, staged from the host in one copy (everything up to traj_norm)
   int32_t* role_to_model;
   int32_t* traj_turn_off;
   int32_t* turn_role;
@@ -47,22 +58,24 @@ struct RouteWs {
   float* turn_reward;
   float* traj_reward;
   float* weights;       // [3 * n_roles]: role, turn, traj
+  unsigned long long* plan_part;   // [n_chunks][kPlanWords] per-chunk totals of the plan kernel; zeros come with the staged copy
+  // written on the device
   float* traj_norm;     // [n_traj]
-  int32_t* turn_traj;   // [n_turns]
-  int32_t* turn_model;  // [n_turns]
   SegMeta* seg_meta;    // [n_turns] per segment slot
   int32_t* blk_first;   // [nblk_tok] segment that holds the first token of each token block
-  int64_t* part;        // [2*K][nblk_turn] per-model (turn count, token count) per block, scanned in place
-  int64_t* part_total;  // [2*K]
-  int64_t* run_blk;     // [nblk_turn]
-  int64_t* run_total;   // [1]
-  int64_t* tok_blk;     // [nblk_tok]
-  int64_t* tok_total;   // [1]
+  unsigned long long* tok_count;   // [nblk_tok + groups] scored tokens of the token kernel's blocks, then of its groups of blocks
 };
 
+// Blocks of the token kernel are grouped 2^shift to a group, about the square root of their number and at least 64.
+inline int group_shift(size_t nbk) {
+  int sh = 6;
+  while ((size_t{1} << (2 * sh)) < nbk) ++sh;
+  return sh;
+}
+inline int plan_chunks(int n_traj) { return static_cast<int>(cdiv(n_traj > 0 ? n_traj : 1, kPlanThreads)); }
+
 size_t carve(Carver& c, RouteWs& w, int n_roles, int n_traj, int n_turns, int64_t n_tokens) {
-  const size_t nbt = cdiv(n_turns > 0 ? n_turns : 1, kTurnBlock);
-  const size_t nbk = cdiv(n_tokens > 0 ? n_tokens : 1, kCntTokens);   // count groups (>= token blocks)
+  const size_t nbk = cdiv(n_tokens > 0 ? n_tokens : 1, kTokBlock);
   w.role_to_model = c.take<int32_t>(n_roles);
   w.traj_turn_off = c.take<int32_t>(n_traj + 1);
   w.turn_role = c.take<int32_t>(n_turns);
@@ -73,17 +86,11 @@ size_t carve(Carver& c, RouteWs& w, int n_roles, int n_traj, int n_turns, int64_
   w.turn_reward = c.take<float>(n_turns);
   w.traj_reward = c.take<float>(n_traj);
   w.weights = c.take<float>(3 * n_roles);
+  w.plan_part = c.take<unsigned long long>(static_cast<size_t>(plan_chunks(n_traj)) * kPlanWords);
   w.traj_norm = c.take<float>(n_traj);
-  w.turn_traj = c.take<int32_t>(n_turns);
-  w.turn_model = c.take<int32_t>(n_turns);
   w.seg_meta = c.take<SegMeta>(n_turns);
   w.blk_first = c.take<int32_t>(nbk);
-  w.part = c.take<int64_t>(2 * UMAS_MAX_MODELS * nbt);
-  w.part_total = c.take<int64_t>(2 * UMAS_MAX_MODELS);
-  w.run_blk = c.take<int64_t>(nbt);
-  w.run_total = c.take<int64_t>(1);
-  w.tok_blk = c.take<int64_t>(nbk);
-  w.tok_total = c.take<int64_t>(1);
+  w.tok_count = c.take<unsigned long long>(nbk + (nbk >> group_shift(nbk)) + 1);
   return c.off;
 }
 
@@ -113,453 +120,586 @@ __global__ void k_group_norm(const float* __restrict__ R, const int32_t* __restr
   }
 }
 
-// Per turn: owning trajectory, step inside it, model phi(role), composed reward.
-__global__ void k_turn_meta(int n_traj, int n_turns, int n_roles, const int32_t* __restrict__ traj_turn_off,
-                            const int32_t* __restrict__ turn_role, const int32_t* __restrict__ role_to_model,
-                            const float* __restrict__ role_reward, const float* __restrict__ turn_reward,
-                            const float* __restrict__ traj_reward, const float* __restrict__ w_role,
-                            const float* __restrict__ w_turn, const float* __restrict__ w_traj,
-                            int32_t* __restrict__ turn_traj, int32_t* __restrict__ turn_model,
-                            int32_t* __restrict__ turn_step, float* __restrict__ turn_scalar) {
-  const int u = blockIdx.x * blockDim.x + threadIdx.x;
-  if (u >= n_turns) return;
-  // last b with traj_turn_off[b] <= u, skipping empty trajectories that start at the same turn
-  int b = last_le(traj_turn_off, n_traj, u);
-  const int v = turn_role[u];
-  turn_traj[u] = b;
-  turn_step[u] = u - traj_turn_off[b] + 1;
-  turn_model[u] = role_to_model[v];
-  const float rr = role_reward ? role_reward[static_cast<size_t>(b) * n_roles + v] : 0.0f;
-  const float rt = turn_reward ? turn_reward[u] : 0.0f;
-  const float rj = traj_reward ? traj_reward[b] : 0.0f;
-  const float wr = w_role ? w_role[v] : 1.0f;
-  const float wt = w_turn ? w_turn[v] : 1.0f;
-  const float wj = w_traj ? w_traj[v] : 1.0f;
-  // (node + turn) + traj with every product and sum rounded on its own: contraction into fused
-  // multiply-adds is switched off for this expression so that the result is reproducible bit for bit
-  {
-#pragma clang fp contract(off)
-    const float pr = wr * rr, pt = wt * rt, pj = wj * rj;
-    const float s1 = pr + pt;
-    turn_scalar[u] = s1 + pj;
-  }
-}
+// ------------------------------------------------------------------ the plan: everything per turn
+struct PlanArgs {
+  int n_traj, n_turns, n_roles, n_models, n_chunks;
+  int64_t n_tokens, n_count;          // n_count: words of tok_count to clear
+  const int32_t* __restrict__ traj_turn_off;
+  const int32_t* __restrict__ turn_role;
+  const int32_t* __restrict__ role_to_model;
+  const int64_t* __restrict__ turn_tok_off;
+  const float* __restrict__ role_reward;   // NULL level = 0
+  const float* __restrict__ turn_reward;
+  const float* __restrict__ traj_reward;   // already normalised when groups are given
+  const float* __restrict__ w_role;        // NULL weight = 1
+  const float* __restrict__ w_turn;
+  const float* __restrict__ w_traj;
+  unsigned long long* __restrict__ plan_part;
+  SegMeta* __restrict__ seg_meta;
+  int32_t* __restrict__ blk_first;
+  unsigned long long* __restrict__ tok_count;
+  // outputs
+  int64_t* __restrict__ model_tok_off;
+  int32_t* __restrict__ model_turn_off;
+  int32_t* __restrict__ model_trajrun_off;
+  int64_t* __restrict__ model_rowsel_off;
+  int64_t* __restrict__ turn_seg_off;
+  int32_t* __restrict__ seg_turn;
+  int64_t* __restrict__ traj_seg_off;
+  float* __restrict__ turn_scalar;
+  int32_t* __restrict__ turn_step;
+};
 
-// Per block of turns and per model: number of turns and of tokens routed to that model.
-__global__ void k_part_reduce(int n_turns, int n_models, int nblk, const int32_t* __restrict__ turn_model,
-                              const int64_t* __restrict__ turn_tok_off, int64_t* __restrict__ part) {
-  __shared__ int64_t smem[32];
-  const int u = blockIdx.x * blockDim.x + threadIdx.x;
-  const int m = u < n_turns ? turn_model[u] : -1;
-  const int64_t len = u < n_turns ? turn_tok_off[u + 1] - turn_tok_off[u] : 0;
-  for (int k = 0; k < n_models; ++k) {
-    const int64_t c = block_sum<int64_t>(m == k ? 1 : 0, smem);
-    const int64_t t = block_sum<int64_t>(m == k ? len : 0, smem);
-    if (threadIdx.x == 0) {
-      part[static_cast<size_t>(2 * k) * nblk + blockIdx.x] = c;
-      part[static_cast<size_t>(2 * k + 1) * nblk + blockIdx.x] = t;
-    }
-  }
-}
-
-// In-place exclusive prefix sum of each row of data[nrows][n]; one block per row, 8 items per thread per round.
-__global__ void k_excl_scan_rows(int64_t* __restrict__ data, int n, int64_t* __restrict__ totals) {
-  constexpr int kItems = 8;
-  __shared__ int64_t smem[32];
-  int64_t* row = data + static_cast<size_t>(blockIdx.x) * n;
-  int64_t carry = 0;
-  for (int i0 = 0; i0 < n; i0 += blockDim.x * kItems) {
-    const int base = i0 + threadIdx.x * kItems;
-    int64_t v[kItems];
-    int64_t sum = 0;
+// v[k] of a small per-model array with a run-time k, without indexing registers dynamically
+template <typename T, int KM>
+__device__ __forceinline__ T pick(const T (&v)[KM], int k) {
+  T r = v[0];
 #pragma unroll
-    for (int k = 0; k < kItems; ++k) {
-      v[k] = base + k < n ? row[base + k] : 0;
-      sum += v[k];
-    }
-    int64_t total;
-    int64_t run = carry + block_excl_scan<int64_t>(sum, smem, &total);
+  for (int i = 1; i < KM; ++i) r = k == i ? v[i] : r;
+  return r;
+}
+template <typename T, int KM>
+__device__ __forceinline__ void bump(T (&v)[KM], int k, T by) {
 #pragma unroll
-    for (int k = 0; k < kItems; ++k) {
-      if (base + k < n) row[base + k] = run;
-      run += v[k];
-    }
-    carry += total;
-  }
-  if (threadIdx.x == 0) totals[blockIdx.x] = carry;
+  for (int i = 0; i < KM; ++i) v[i] += k == i ? by : T(0);
 }
 
-// Stream offsets from the per-model totals, then each turn's segment slot and token offset.
-__global__ void k_part_apply(int n_turns, int n_models, int nblk, int64_t n_tokens,
-                             const int32_t* __restrict__ turn_model, const int64_t* __restrict__ turn_tok_off,
-                             const int64_t* __restrict__ part, const int64_t* __restrict__ part_total,
-                             int64_t* __restrict__ model_tok_off, int32_t* __restrict__ model_turn_off,
-                             int64_t* __restrict__ turn_seg_off, int32_t* __restrict__ seg_turn) {
-  __shared__ int64_t smem[32];
-  __shared__ int64_t base_turn[UMAS_MAX_MODELS + 1], base_tok[UMAS_MAX_MODELS + 1];
-  if (threadIdx.x == 0) {
-    int64_t ct = 0, tk = 0;
-    for (int k = 0; k < n_models; ++k) {
-      base_turn[k] = ct;
-      base_tok[k] = tk;
-      ct += part_total[2 * k];
-      tk += part_total[2 * k + 1];
-    }
-    base_turn[n_models] = ct;
-    base_tok[n_models] = tk;
-    if (blockIdx.x == 0) {
-      for (int k = 0; k <= n_models; ++k) {
-        model_turn_off[k] = static_cast<int32_t>(base_turn[k]);
-        model_tok_off[k] = base_tok[k];
-      }
-      turn_seg_off[n_turns] = n_tokens;
-    }
+// Per-model counts of one trajectory: turns, tokens, and whether the model has a run in it.
+template <int KM>
+struct TrajCounts {
+  int64_t cnt[KM], tok[KM];
+  uint32_t seen;
+};
+template <int KM>
+__device__ __forceinline__ void traj_counts(const PlanArgs& A, const uint8_t* s_phi, int b, TrajCounts<KM>& c) {
+#pragma unroll
+  for (int k = 0; k < KM; ++k) { c.cnt[k] = 0; c.tok[k] = 0; }
+  c.seen = 0;
+  if (b >= A.n_traj) return;
+  const int t0 = A.traj_turn_off[b], t1 = A.traj_turn_off[b + 1];
+  int64_t g0 = A.turn_tok_off[t0];
+  for (int u = t0; u < t1; ++u) {
+    const int m = s_phi[A.turn_role[u]];
+    const int64_t g1 = A.turn_tok_off[u + 1];
+    bump(c.cnt, m, int64_t{1});
+    bump(c.tok, m, g1 - g0);
+    c.seen |= 1u << m;
+    g0 = g1;
   }
+}
+
+// KM: the smallest of 1, 2, 4, 8 that is at least the number of models (per-model state lives in registers).
+template <int KM>
+__global__ void __launch_bounds__(kPlanThreads, 2)
+k_turn_plan(PlanArgs A) {
+  __shared__ int64_t smem[32];
+  __shared__ long long s_sum[2][kPlanWords][kPlanThreads / kPlanWords];   // [total | before this chunk][counter][group of threads]
+  __shared__ long long s_res[2][kPlanWords];
+  __shared__ uint8_t s_phi[UMAS_MAX_ROLES];          // role -> model
+  const int tid = threadIdx.x;
+  const int K = A.n_models;
+  if (tid < A.n_roles) s_phi[tid] = static_cast<uint8_t>(A.role_to_model[tid]);
   __syncthreads();
-  const int u = blockIdx.x * blockDim.x + threadIdx.x;
-  const int m = u < n_turns ? turn_model[u] : -1;
-  const int64_t len = u < n_turns ? turn_tok_off[u + 1] - turn_tok_off[u] : 0;
-  for (int k = 0; k < n_models; ++k) {
-    int64_t tot;
-    const int64_t c = block_excl_scan<int64_t>(m == k ? 1 : 0, smem, &tot);
-    const int64_t t = block_excl_scan<int64_t>(m == k ? len : 0, smem, &tot);
-    if (m == k) {
-      const int64_t slot = base_turn[k] + part[static_cast<size_t>(2 * k) * nblk + blockIdx.x] + c;
-      seg_turn[slot] = u;
-      turn_seg_off[slot] = base_tok[k] + part[static_cast<size_t>(2 * k + 1) * nblk + blockIdx.x] + t;
-    }
-  }
-}
 
-// A trajectory run starts at a segment slot whose stream or trajectory differs from the slot before.
-__device__ __forceinline__ int run_start(int s, const int32_t* seg_turn, const int32_t* turn_traj,
-                                         const int32_t* turn_model) {
-  if (s == 0) return 1;
-  const int u = seg_turn[s], up = seg_turn[s - 1];
-  return (turn_model[u] != turn_model[up] || turn_traj[u] != turn_traj[up]) ? 1 : 0;
-}
-
-__global__ void k_run_reduce(int n_turns, const int32_t* __restrict__ seg_turn,
-                             const int32_t* __restrict__ turn_traj, const int32_t* __restrict__ turn_model,
-                             int64_t* __restrict__ run_blk) {
-  __shared__ int64_t smem[32];
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t f = s < n_turns ? run_start(s, seg_turn, turn_traj, turn_model) : 0;
-  const int64_t c = block_sum<int64_t>(f, smem);
-  if (threadIdx.x == 0) run_blk[blockIdx.x] = c;
-}
-
-__global__ void k_run_apply(int n_turns, int n_models, const int32_t* __restrict__ seg_turn,
-                            const int32_t* __restrict__ turn_traj, const int32_t* __restrict__ turn_model,
-                            const int64_t* __restrict__ run_blk, const int64_t* __restrict__ run_total,
-                            const int64_t* __restrict__ turn_seg_off, const int32_t* __restrict__ model_turn_off,
-                            int64_t* __restrict__ traj_seg_off, int32_t* __restrict__ model_trajrun_off) {
-  __shared__ int64_t smem[32];
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t f = s < n_turns ? run_start(s, seg_turn, turn_traj, turn_model) : 0;
-  int64_t tot;
-  const int64_t r = run_blk[blockIdx.x] + block_excl_scan<int64_t>(f, smem, &tot);
-  if (s < n_turns) {
-    if (f) traj_seg_off[r] = turn_seg_off[s];
-    for (int k = 0; k <= n_models; ++k)
-      if (model_turn_off[k] == s) model_trajrun_off[k] = static_cast<int32_t>(r);
-  }
-  if (s == 0)
-    for (int k = 0; k <= n_models; ++k)
-      if (model_turn_off[k] == n_turns) model_trajrun_off[k] = static_cast<int32_t>(*run_total);
-}
-
-__global__ void k_fill_i64(int64_t* __restrict__ p, int64_t n, int64_t v) {
-  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = v;
-}
-
-// Per turn segment, sixteen lanes each (four segments per wavefront, so that four chains of dependent loads are in
-// flight per wavefront): the highest model-local position of a mask=1 token, the turn's source offset, role and
-// reward gathered into one record, the flag bits of its last token (segment end; also trajectory-run end when a run
-// starts at the segment's end offset or the stream ends there), and for every token block whose first token lies in
-// the segment, the segment's index.
-constexpr int kSegLanes = 16;
-__global__ void k_seg_meta(int n_turns, int64_t n_tokens, const int32_t* __restrict__ seg_turn,
-                           const int64_t* __restrict__ turn_tok_off, const int64_t* __restrict__ turn_seg_off,
-                           const int32_t* __restrict__ turn_role, const float* __restrict__ turn_scalar,
-                           const int32_t* __restrict__ turn_traj, const int32_t* __restrict__ turn_model,
-                           const uint8_t* __restrict__ mask, SegMeta* __restrict__ seg_meta,
-                           int32_t* __restrict__ blk_first) {
-  const int sub = threadIdx.x & (kSegLanes - 1);
-  const int s = (blockIdx.x * blockDim.x + threadIdx.x) / kSegLanes;
-  const bool live = s < n_turns;                          // whole groups of sixteen lanes; everybody stays for the shuffles
-  const int sc = live ? s : n_turns - 1;
-  const bool has_next = sc + 1 < n_turns;
-  const int u = seg_turn[sc];
-  const int un = has_next ? seg_turn[sc + 1] : u;
-  const int64_t g0 = turn_tok_off[u], len = live ? turn_tok_off[u + 1] - g0 : 0;
-  const int64_t a = turn_seg_off[sc], e = a + len;
-  const int64_t e_next = has_next ? turn_seg_off[sc + 2] : e;     // end of the next segment
-  const int role = turn_role[u];
-  const float rho = turn_scalar[u];
-  const bool next_starts_run = turn_model[u] != turn_model[un] || turn_traj[u] != turn_traj[un];
-  int64_t best = -1;
-  // walk from the end, 64 tokens (four per lane) at a time; stop at the first step that holds a valid token
-  for (int64_t hi = len; __any(hi > 0 && best < 0); hi -= 4 * kSegLanes) {
-    int64_t cand = -1;
-    if (hi > 0 && best < 0) {
+  // 1. every chunk of this workgroup: per-model totals of its 256 trajectories, published at once.  The counts of the
+  // workgroup's first chunk (its only one unless there are more chunks than workgroups) stay in registers for step 2.
+  TrajCounts<KM> first;
+  for (int c = blockIdx.x; c < A.n_chunks; c += gridDim.x) {
+    TrajCounts<KM> tc;
+    traj_counts(A, s_phi, c * kPlanThreads + tid, tc);
+    if (c == static_cast<int>(blockIdx.x)) first = tc;
+    for (int k = 0; k < K; ++k) {
+      const int64_t v[kCnt] = {pick(tc.cnt, k), pick(tc.tok, k), static_cast<int64_t>((tc.seen >> k) & 1u)};
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {                       // the highest index first
-        const int64_t i = hi - 1 - (4 * sub + k);
-        if (cand < 0 && i >= 0 && mask[g0 + i]) cand = i;
+      for (int j = 0; j < kCnt; ++j) {
+        const int64_t total = block_sum<int64_t>(v[j], smem);
+        if (tid == 0)
+          __hip_atomic_store(A.plan_part + static_cast<size_t>(c) * kPlanWords + k * kCnt + j,
+                             kMark | static_cast<unsigned long long>(total), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
-    // tokens 4 sub .. 4 sub + 3 counted from the end: a lower lane holds higher positions, the maximum is wanted
-#pragma unroll
-    for (int o = kSegLanes / 2; o > 0; o >>= 1) {
-      const int64_t other = __shfl_xor(cand, o, kSegLanes);
-      cand = other > cand ? other : cand;
-    }
-    if (hi > 0 && best < 0) best = cand;
   }
-  if (live && sub == 0) {
-    // a run ends at e when the stream ends there or a run starts at one of the segments that begin at e:
-    // the next one, and if that one is empty the ones after it up to the first non-empty one
-    bool run_end = e == n_tokens || (has_next && next_starts_run);
-    if (!run_end && has_next && e_next <= e)
-      for (int t = s + 2; t < n_turns && !run_end; ++t) {
-        run_end = run_start(t, seg_turn, turn_traj, turn_model) != 0;
-        if (turn_seg_off[t + 1] > e) break;
+
+  // housekeeping that waits for nobody: the token kernel's counts start at zero; with no tokens or no turns it does not run
+  {
+    const int64_t gtid = static_cast<int64_t>(blockIdx.x) * kPlanThreads + tid, gsize = static_cast<int64_t>(gridDim.x) * kPlanThreads;
+    for (int64_t i = gtid; i < A.n_count; i += gsize) A.tok_count[i] = 0ull;
+    if (gtid <= K) A.model_rowsel_off[gtid] = 0;
+  }
+
+  // 2. every chunk again: where its trajectories' turns go
+  for (int c = blockIdx.x; c < A.n_chunks; c += gridDim.x) {
+    // totals over all chunks and over the chunks before this one, for every (model, counter): thread t adds up
+    // counter t % 24 over the chunks t / 24, t / 24 + 10, ...; a word is taken when its ready mark is set
+    constexpr int kGroups = kPlanThreads / kPlanWords;
+    const int j = tid % kPlanWords, grp = tid / kPlanWords;
+    if (grp < kGroups) {
+      long long all = 0, before = 0;
+      if (j < K * kCnt) {
+        for (int cc = grp; cc < A.n_chunks; cc += kGroups) {
+          unsigned long long w;
+          while (!((w = __hip_atomic_load(A.plan_part + static_cast<size_t>(cc) * kPlanWords + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) & kMark))
+            __builtin_amdgcn_s_sleep(2);
+          const long long v = static_cast<long long>(w & ~kMark);
+          all += v;
+          before += cc < c ? v : 0;
+        }
       }
-    SegMeta m;
-    m.src = g0;
-    m.last_valid = best < 0 ? -1 : a + best;
-    m.turn = u;
-    m.role = role;
-    m.rho = rho;
-    m.end_flags = 2 | (run_end ? 4 : 0);
-    seg_meta[s] = m;
+      s_sum[0][j][grp] = all;
+      s_sum[1][j][grp] = before;
+    }
+    __syncthreads();
+    if (tid < 2 * kPlanWords) {
+      long long t = 0;
+      for (int g = 0; g < kGroups; ++g) t += s_sum[tid / kPlanWords][tid % kPlanWords][g];
+      s_res[tid / kPlanWords][tid % kPlanWords] = t;
+    }
+    __syncthreads();
+    // first slot, token offset and run of every stream: streams lie one after the other
+    int64_t slot_at[KM], tok_at[KM], run_at[KM];
+    {
+      int64_t bs = 0, bt = 0, br = 0;
+#pragma unroll
+      for (int k = 0; k < KM; ++k) {
+        slot_at[k] = bs; tok_at[k] = bt; run_at[k] = br;
+        if (k < K) { bs += s_res[0][k * kCnt + 0]; bt += s_res[0][k * kCnt + 1]; br += s_res[0][k * kCnt + 2]; }
+      }
+      if (c == 0 && tid == 0) {
+        for (int k = 0; k <= K; ++k) {
+          A.model_turn_off[k] = static_cast<int32_t>(k < K ? pick(slot_at, k) : bs);
+          A.model_tok_off[k] = k < K ? pick(tok_at, k) : bt;
+          A.model_trajrun_off[k] = static_cast<int32_t>(k < K ? pick(run_at, k) : br);
+        }
+        A.turn_seg_off[A.n_turns] = A.n_tokens;
+      }
+      // entries of traj_seg_off past the runs read n_tokens
+      const int64_t gtid = static_cast<int64_t>(c) * kPlanThreads + tid, gsize = static_cast<int64_t>(A.n_chunks) * kPlanThreads;
+      for (int64_t i = br + gtid; i <= A.n_turns; i += gsize) A.traj_seg_off[i] = A.n_tokens;
+#pragma unroll
+      for (int k = 0; k < KM; ++k)
+        if (k < K) { slot_at[k] += s_res[1][k * kCnt + 0]; tok_at[k] += s_res[1][k * kCnt + 1]; run_at[k] += s_res[1][k * kCnt + 2]; }
+    }
+    // ... plus what the trajectories before this thread's one inside the chunk hold
+    const int b = c * kPlanThreads + tid;
+    {
+      TrajCounts<KM> tc;
+      if (c == static_cast<int>(blockIdx.x)) tc = first;
+      else traj_counts(A, s_phi, b, tc);
+      for (int k = 0; k < K; ++k) {
+        int64_t total;
+        const int64_t e0 = block_excl_scan<int64_t>(pick(tc.cnt, k), smem, &total);
+        const int64_t e1 = block_excl_scan<int64_t>(pick(tc.tok, k), smem, &total);
+        const int64_t e2 = block_excl_scan<int64_t>(static_cast<int64_t>((tc.seen >> k) & 1u), smem, &total);
+        bump(slot_at, k, e0);
+        bump(tok_at, k, e1);
+        bump(run_at, k, e2);
+      }
+    }
+    if (b < A.n_traj) {
+      const int t0 = A.traj_turn_off[b], t1 = A.traj_turn_off[b + 1];
+      const float rj = A.traj_reward ? A.traj_reward[b] : 0.0f;
+      // One walk over the trajectory's turns: slots, offsets, runs, composed rewards, the first segment of every token
+      // block, the record of every segment.  What a segment's last token says about its end - bit 1: last token of its
+      // turn; bit 2: also the last token of the trajectory's run (no later turn of the trajectory with tokens in this
+      // stream); bits 3-7: else the number of steps to the run's next turn with tokens (31 = more than 30: look it
+      // up) - is known only when that next turn comes by: the record is written as a run's end and its flags are
+      // written again then.
+      uint32_t seen = 0;
+      int last_slot[KM], last_step[KM];   // the model's latest turn with tokens in this trajectory
+#pragma unroll
+      for (int k = 0; k < KM; ++k) { last_slot[k] = -1; last_step[k] = 0; }
+      int64_t g0 = A.turn_tok_off[t0];
+      for (int u = t0; u < t1; ++u) {
+        const int v = A.turn_role[u];
+        const int m = s_phi[v];
+        const int64_t g1 = A.turn_tok_off[u + 1], len = g1 - g0;
+        const int64_t slot = pick(slot_at, m), off = pick(tok_at, m);
+        const int step = u - t0 + 1;
+        bump(slot_at, m, int64_t{1});
+        bump(tok_at, m, len);
+        A.seg_turn[slot] = u;
+        A.turn_seg_off[slot] = off;
+        if (!((seen >> m) & 1u)) {                   // the trajectory's one run in stream m starts here
+          A.traj_seg_off[pick(run_at, m)] = off;
+          seen |= 1u << m;
+        }
+        const float rr = A.role_reward ? A.role_reward[static_cast<size_t>(b) * A.n_roles + v] : 0.0f;
+        const float rt = A.turn_reward ? A.turn_reward[u] : 0.0f;
+        const float wr = A.w_role ? A.w_role[v] : 1.0f;
+        const float wt = A.w_turn ? A.w_turn[v] : 1.0f;
+        const float wj = A.w_traj ? A.w_traj[v] : 1.0f;
+        // (node + turn) + traj with every product and sum rounded on its own: contraction into fused
+        // multiply-adds is switched off for this expression so that the result is reproducible bit for bit
+        float rho;
+        {
+#pragma clang fp contract(off)
+          const float pr = wr * rr, pt = wt * rt, pj = wj * rj;
+          const float s1 = pr + pt;
+          rho = s1 + pj;
+        }
+        A.turn_scalar[u] = rho;
+        A.turn_step[u] = step;
+        for (int64_t blk = (off + kTokBlock - 1) / kTokBlock; blk * kTokBlock < off + len; ++blk) A.blk_first[blk] = static_cast<int32_t>(slot);
+        SegMeta M;
+        M.src = g0;
+        M.turn = u;
+        M.role = v;
+        M.rho = rho;
+        M.end_flags = 2 | 4;
+        M.pad = 0;
+        A.seg_meta[slot] = M;
+        if (len > 0) {
+          const int prev = pick(last_slot, m);
+          if (prev >= 0) {
+            const int ds = step - pick(last_step, m);
+            A.seg_meta[prev].end_flags = 2 | ((ds < 31 ? ds : 31) << 3);
+          }
+#pragma unroll
+          for (int k = 0; k < KM; ++k) {
+            last_slot[k] = m == k ? static_cast<int>(slot) : last_slot[k];
+            last_step[k] = m == k ? step : last_step[k];
+          }
+        }
+        g0 = g1;
+      }
+    }
+    __syncthreads();                                 // s_sum and s_res are the next chunk's
   }
-  if (live)
-    for (int64_t b = (a + kTokBlock - 1) / kTokBlock + sub; b * kTokBlock < e; b += kSegLanes) blk_first[b] = s;
 }
 
-// Per token in model-local order: source index, turn, role, mask, flags, placed reward; per block the
-// number of mask=1 tokens.  A block keeps the offsets and records of the kSegWin segments from the
-// one that holds its first token in LDS; its threads search there (streams whose segments are so
-// short that the window does not cover the block read global memory instead).
+// ------------------------------------------------------------------ the tokens: everything per token
+// Per token in model-local order: source index, turn, role, mask, flags, placed reward.  A block of 4096 tokens keeps
+// the offsets and records of the segments that hold its tokens in LDS (up to kSegWin of them; a block of more and
+// therefore very short segments takes a plain per-token path).  What a block cannot know from its own tokens is
+// whether its last segment, if it goes on past the block, has another scored token further on, which decides if the
+// segment's last scored token so far carries the reward: one wavefront reads ahead in the mask until it finds one or
+// the segment ends.  The block also leaves its number of scored tokens for the compaction kernel, and adds it to the
+// total of its group of blocks (about the square root of the number of blocks to a group).
 constexpr int kSegWin = 256;
+constexpr int kCompact = kTokBlock / kTokThreads;   // consecutive tokens of one thread when the scored positions are compacted
+static_assert(kCompact == 16, "one 16-byte LDS read per thread");
+
+struct TokArgs {
+  int64_t n_tokens;
+  int n_turns, n_models, place_mode, grp_shift;
+  const int64_t* turn_seg_off;
+  const SegMeta* seg_meta;
+  const int32_t* blk_first;
+  const uint8_t* mask_global;
+  unsigned long long* blk_count;   // [blocks] scored tokens of the block
+  unsigned long long* grp_count;   // [groups of 2^grp_shift blocks] scored tokens of the group, zero at the start
+  int64_t* perm;
+  int32_t* tok_turn;
+  int32_t* tok_role;
+  uint8_t* tok_mask;
+  uint8_t* tok_flags;
+  float* tok_reward;
+};
+
+// every non-zero byte becomes 1: (b | 0x80) - 1 keeps bit 7 exactly when b > 0, or-ed with b's own bit 7
+__device__ __forceinline__ uint32_t bytes_to_01(uint32_t m4) {
+  return ((((m4 | 0x80808080u) - 0x01010101u) | m4) >> 7) & 0x01010101u;
+}
+// mask bytes of four consecutive global tokens as one word (one load when the address allows it)
+__device__ __forceinline__ uint32_t load_mask4(const uint8_t* __restrict__ mask, int64_t g0, bool base_aligned) {
+  if (base_aligned && (g0 & 3) == 0) return *reinterpret_cast<const uint32_t*>(mask + g0);
+  return static_cast<uint32_t>(mask[g0]) | (static_cast<uint32_t>(mask[g0 + 1]) << 8) |
+         (static_cast<uint32_t>(mask[g0 + 2]) << 16) | (static_cast<uint32_t>(mask[g0 + 3]) << 24);
+}
+// One wavefront: does segment s, which goes on past position `from`, hold a scored token at or after it?
+__device__ __forceinline__ bool scored_token_ahead(const TokArgs& A, int s, int64_t from) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t seg_e = A.turn_seg_off[s + 1];
+  const int64_t g = A.seg_meta[s].src + (from - A.turn_seg_off[s]), n = seg_e - from;
+  bool found = false;
+  for (int64_t i0 = 0; i0 < n && !found; i0 += 8 * kWave) {   // eight bytes per lane, all in flight together
+    uint32_t any = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int64_t i = i0 + lane * 8 + k;
+      any |= i < n ? A.mask_global[g + i] : 0u;
+    }
+    found = __any(any != 0);
+  }
+  return found;
+}
+
+// The plain path of a block with more than kSegWin segments: one token at a time, the segment found by a search in
+// global memory.  First the masks (into s_mk) ...
+__device__ __forceinline__ void many_segments_masks(const TokArgs& A, int64_t blk0, int ntok, int s_first, int s_last, uint8_t* s_mk) {
+  for (int pl = threadIdx.x; pl < ntok; pl += kTokThreads) {
+    const int64_t p = blk0 + pl;
+    const int s = s_first + last_le(A.turn_seg_off + s_first, s_last - s_first, p);
+    s_mk[pl] = A.mask_global[A.seg_meta[s].src + (p - A.turn_seg_off[s])] ? 1 : 0;
+  }
+}
+// ... then the outputs.  A scored token carries the reward of its segment if no scored token follows it there: the
+// gaps between scored tokens are disjoint, so all these searches together read the block's masks once.
+__device__ __forceinline__ void many_segments_outputs(const TokArgs& A, int64_t blk0, int ntok, int s_first, int s_last, const uint8_t* s_mk,
+                                                   bool ahead) {
+  for (int pl = threadIdx.x; pl < ntok; pl += kTokThreads) {
+    const int64_t p = blk0 + pl;
+    const int s = s_first + last_le(A.turn_seg_off + s_first, s_last - s_first, p);
+    const SegMeta M = A.seg_meta[s];
+    const int64_t seg_a = A.turn_seg_off[s], seg_e = A.turn_seg_off[s + 1];
+    const uint8_t m = s_mk[pl];
+    float rw = 0.f;
+    if (m) {
+      bool carries = A.place_mode == UMAS_PLACE_ALL;
+      if (!carries) {
+        const int stop = seg_e - blk0 < ntok ? static_cast<int>(seg_e - blk0) : ntok;
+        int q = pl + 1;
+        while (q < stop && !s_mk[q]) ++q;
+        carries = q == stop && (seg_e - blk0 <= ntok || !ahead);
+      }
+      rw = carries ? M.rho : 0.f;
+    }
+    A.perm[p] = M.src + (p - seg_a);
+    A.tok_turn[p] = M.turn;
+    A.tok_role[p] = M.role;
+    A.tok_mask[p] = m;
+    A.tok_flags[p] = static_cast<uint8_t>(m | (p == seg_e - 1 ? M.end_flags : 0));
+    A.tok_reward[p] = rw;
+  }
+}
+
 __global__ void __launch_bounds__(kTokThreads)
-k_tokens(int64_t n_tokens, int n_turns, int place_mode, const int64_t* __restrict__ turn_seg_off,
-         const SegMeta* __restrict__ seg_meta, const int32_t* __restrict__ blk_first,
-         const uint8_t* __restrict__ mask_global, int64_t* __restrict__ perm, int32_t* __restrict__ tok_turn,
-         int32_t* __restrict__ tok_role, uint8_t* __restrict__ tok_mask, uint8_t* __restrict__ tok_flags,
-         float* __restrict__ tok_reward, int64_t* __restrict__ tok_blk) {
+k_tokens(TokArgs A) {
   __shared__ int64_t smem[32];
   __shared__ int64_t s_off[kSegWin + 1];
   __shared__ int32_t s_loc[kSegWin + 1];            // the same offsets relative to the block's first token, clamped
   __shared__ SegMeta s_meta[kSegWin];
+  __shared__ int32_t s_lastv[kSegWin];              // block-relative position of the segment's last scored token in this block, -1
+  __shared__ __attribute__((aligned(16))) uint8_t s_mk[kTokBlock];   // the block's masks, 0 or 1 (plain path)
+  __shared__ int s_ahead;
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
   const int64_t blk0 = static_cast<int64_t>(blockIdx.x) * kTokBlock;
-  const int s_base = blk_first[blockIdx.x];
-  // segments s_base .. s_end hold the block's tokens (s_end = the segment of the next block's first token)
-  const int s_end = blk0 + kTokBlock < n_tokens ? blk_first[blockIdx.x + 1] : n_turns - 1;
-  const int need = s_end - s_base + 1;
-  const int win = need < kSegWin ? need : kSegWin;                           // s_off[0..win], s_meta[0..win) are valid
-  for (int i = threadIdx.x; i <= win; i += kTokThreads) {
-    const int64_t off = turn_seg_off[s_base + i];
-    const int64_t rel = off - blk0;
-    s_off[i] = off;
-    s_loc[i] = static_cast<int32_t>(rel < -(1 << 30) ? -(1 << 30) : rel > (1 << 30) ? (1 << 30) : rel);
-    if (i < win) s_meta[i] = seg_meta[s_base + i];
+  const int64_t blk_end = blk0 + kTokBlock < A.n_tokens ? blk0 + kTokBlock : A.n_tokens;
+  const int ntok = static_cast<int>(blk_end - blk0);
+  const int s_first = A.blk_first[blockIdx.x];
+  // segments s_first .. s_last hold the block's tokens (s_last = the segment of the next block's first token)
+  const int s_last = blk_end < A.n_tokens ? A.blk_first[blockIdx.x + 1] : A.n_turns - 1;
+  const int n_seg = s_last - s_first + 1;
+  const bool windowed = n_seg <= kSegWin;
+  const bool mask_aligned = (reinterpret_cast<uintptr_t>(A.mask_global) & 3) == 0;
+  if (tid == 0) s_ahead = 0;
+  *reinterpret_cast<uint4*>(s_mk + tid * kCompact) = make_uint4(0u, 0u, 0u, 0u);
+  if (windowed) {
+    for (int i = tid; i <= n_seg; i += kTokThreads) {
+      const int64_t off = A.turn_seg_off[s_first + i];
+      const int64_t rel = off - blk0;
+      s_off[i] = off;
+      s_loc[i] = static_cast<int32_t>(rel < -(1 << 30) ? -(1 << 30) : rel > (1 << 30) ? (1 << 30) : rel);
+      if (i < n_seg) { s_meta[i] = A.seg_meta[s_first + i]; s_lastv[i] = -1; }
+    }
   }
   __syncthreads();
-  const bool in_window = need <= kSegWin;           // every token of the block lies in a windowed segment
-  const bool mask_aligned = (reinterpret_cast<uintptr_t>(mask_global) & 3) == 0;
-  int64_t cnt[kTokRounds / kCntRounds] = {};
-  // Phase A: every round's segment search and mask load.  All loads are in flight before the first
-  // store is issued, so no round waits behind the stores of the round before it.
-  int lo_r[kTokRounds];
-  uint32_t m4_r[kTokRounds];
-  bool fast_r[kTokRounds];
+
+  // ---- masks: into registers (windowed path) and LDS, the last scored token of every segment
+  uint32_t mk_r[kTokRounds];                        // 0/1 bytes of this thread's four tokens in each round
+  int lo_r[kTokRounds];                             // their first token's segment in the window; bit 30: all four lie in it
 #pragma unroll
-  for (int rd = 0; rd < kTokRounds; ++rd) {
-    const int pl0 = rd * kTokRound + static_cast<int>(threadIdx.x) * kTokPerThread;   // block-relative
-    const int64_t p0 = blk0 + pl0;
-    lo_r[rd] = 0; m4_r[rd] = 0; fast_r[rd] = false;
-    if (!in_window || p0 >= n_tokens) continue;
-    int lo = 0, hi = win;                           // largest j with s_loc[j] <= pl0: the segment that holds p0
-    while (lo < hi) {
-      const int mid = (lo + hi + 1) >> 1;
-      if (s_loc[mid] <= pl0) lo = mid; else hi = mid - 1;
-    }
-    lo_r[rd] = lo;
-    // fast when the four tokens lie in one segment: no per-token bookkeeping
-    fast_r[rd] = pl0 + kTokPerThread <= s_loc[lo + 1] && p0 + kTokPerThread <= n_tokens;
-    if (fast_r[rd]) {
-      const int64_t g0 = s_meta[lo].src + (p0 - s_off[lo]);
-      if (mask_aligned && (g0 & 3) == 0) {
-        m4_r[rd] = *reinterpret_cast<const uint32_t*>(mask_global + g0);
-      } else {
-        m4_r[rd] = static_cast<uint32_t>(mask_global[g0]) | (static_cast<uint32_t>(mask_global[g0 + 1]) << 8) |
-                   (static_cast<uint32_t>(mask_global[g0 + 2]) << 16) | (static_cast<uint32_t>(mask_global[g0 + 3]) << 24);
+  for (int rd = 0; rd < kTokRounds; ++rd) { mk_r[rd] = 0; lo_r[rd] = 0; }
+  if (windowed) {
+    uint32_t m4_r[kTokRounds];
+#pragma unroll
+    for (int rd = 0; rd < kTokRounds; ++rd) {       // every load of the block goes out before anything waits for one
+      const int pl0 = rd * kTokRound + tid * kTokPerThread;
+      m4_r[rd] = 0;
+      if (pl0 >= ntok) continue;
+      int lo = 0, hi = n_seg;                       // largest j with s_loc[j] <= pl0: the segment that holds the token
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (s_loc[mid] <= pl0) lo = mid; else hi = mid - 1;
       }
+      const bool fast = pl0 + kTokPerThread <= s_loc[lo + 1];
+      lo_r[rd] = lo | (fast ? 1 << 30 : 0);
+      if (fast) m4_r[rd] = load_mask4(A.mask_global, s_meta[lo].src + (blk0 + pl0 - s_off[lo]), mask_aligned);
+    }
+#pragma unroll
+    for (int rd = 0; rd < kTokRounds; ++rd) {
+      const int pl0 = rd * kTokRound + tid * kTokPerThread;
+      const bool in = pl0 < ntok, fast = (lo_r[rd] >> 30) != 0;
+      const int lo = lo_r[rd] & ((1 << 30) - 1);
+      uint32_t mk4 = 0;
+      int cand = -1;                                // this thread's last scored token of segment lo
+      if (fast) {
+        mk4 = bytes_to_01(m4_r[rd]);
+        cand = mk4 ? pl0 + (31 - __clz(mk4)) / 8 : -1;
+      }
+      // when the whole wavefront sits in one segment, one update of the segment's last scored token does
+      const int lo0 = __shfl(lo, 0, kWave);
+      if (__all(fast && lo == lo0)) {
+        const int best = wave_max(cand);
+        if (lane == 0 && best >= 0) atomicMax(&s_lastv[lo], best);
+      } else if (cand >= 0) {
+        atomicMax(&s_lastv[lo], cand);
+      }
+      if (in && !fast) {                            // a segment boundary or the stream's end inside the four tokens
+        int s = lo;
+        for (int k = 0; k < kTokPerThread; ++k) {
+          const int pl = pl0 + k;
+          if (pl >= ntok) break;
+          while (s_loc[s + 1] <= pl) ++s;           // also steps over empty segments
+          const uint32_t m = A.mask_global[s_meta[s].src + (blk0 + pl - s_off[s])] ? 1u : 0u;
+          mk4 |= m << (8 * k);
+          if (m) atomicMax(&s_lastv[s], pl);
+        }
+      }
+      mk_r[rd] = mk4;
+    }
+  } else {
+    many_segments_masks(A, blk0, ntok, s_first, s_last, s_mk);
+  }
+  // the block's last segment, if it goes on past the block: is there a scored token further on?
+  if (wave == 1 && A.place_mode == UMAS_PLACE_LAST && A.turn_seg_off[s_last + 1] > blk_end) {
+    const bool found = scored_token_ahead(A, s_last, blk_end);
+    if (lane == 0) s_ahead = found ? 1 : 0;
+  }
+  __syncthreads();
+  const bool ahead = s_ahead != 0;
+
+  // ---- the block's count of scored tokens, for the compaction kernel: its own word and its group's total
+  {
+    int32_t c = 0;
+    if (windowed) {
+#pragma unroll
+      for (int rd = 0; rd < kTokRounds; ++rd) c += __popc(mk_r[rd]);
+    } else {
+      const uint4 w = *reinterpret_cast<const uint4*>(s_mk + tid * kCompact);
+      c = __popc(w.x) + __popc(w.y) + __popc(w.z) + __popc(w.w);
+    }
+    const int32_t total = block_sum<int32_t>(c, reinterpret_cast<int32_t*>(smem));
+    if (tid == 0) {
+      A.blk_count[blockIdx.x] = static_cast<unsigned long long>(total);
+      (void)__hip_atomic_fetch_add(A.grp_count + (blockIdx.x >> A.grp_shift), static_cast<unsigned long long>(total), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
     }
   }
-  // Phase B: outputs
+
+  // ---- outputs per token
+  if (windowed) {
 #pragma unroll
-  for (int rd = 0; rd < kTokRounds; ++rd) {
-    const int pl0 = rd * kTokRound + static_cast<int>(threadIdx.x) * kTokPerThread;
-    const int64_t p0 = blk0 + pl0;
-    if (p0 >= n_tokens) continue;
-    int s;
-    if (in_window) {
-      const int lo = lo_r[rd];
-      s = s_base + lo;
-      if (fast_r[rd]) {
-        const SegMeta M = s_meta[lo];
-        const int64_t g0 = M.src + (p0 - s_off[lo]);
-        const uint32_t m4 = m4_r[rd];
-        // every non-zero byte becomes 1: (b | 0x80) - 1 keeps bit 7 exactly when b > 0 or-ed with b's own bit 7
-        const uint32_t mk4 = ((((m4 | 0x80808080u) - 0x01010101u) | m4) >> 7) & 0x01010101u;
+    for (int rd = 0; rd < kTokRounds; ++rd) {
+      const int pl0 = rd * kTokRound + tid * kTokPerThread;
+      const int64_t p0 = blk0 + pl0;
+      if (pl0 >= ntok) continue;
+      int s = lo_r[rd] & ((1 << 30) - 1);
+      const uint32_t mk4 = mk_r[rd];
+      if ((lo_r[rd] >> 30) != 0) {                  // four tokens of one segment: no per-token bookkeeping
+        const SegMeta M = s_meta[s];
+        const int64_t g0 = M.src + (p0 - s_off[s]);
         uint32_t fg4 = mk4;
-        if (pl0 + kTokPerThread == s_loc[lo + 1]) fg4 |= static_cast<uint32_t>(M.end_flags) << 24;
-        float rw4[kTokPerThread] = {0.f, 0.f, 0.f, 0.f};
-        if (place_mode == UMAS_PLACE_ALL) {
+        if (pl0 + kTokPerThread == s_loc[s + 1]) fg4 |= static_cast<uint32_t>(M.end_flags) << 24;
+        // the segment's last scored token carries the reward, unless the segment goes on past the block and has another
+        const int lastv = s_loc[s + 1] <= kTokBlock || !ahead ? s_lastv[s] : -1;
+        float rw[kTokPerThread];
 #pragma unroll
-          for (int k = 0; k < kTokPerThread; ++k) rw4[k] = ((mk4 >> (8 * k)) & 1u) ? M.rho : 0.f;
-        } else {
-          const int64_t idx = M.last_valid - p0;
-#pragma unroll
-          for (int k = 0; k < kTokPerThread; ++k) rw4[k] = idx == k ? M.rho : 0.f;
-        }
-        cnt[rd / kCntRounds] += __popc(mk4);
-        *reinterpret_cast<longlong2*>(perm + p0) = make_longlong2(g0, g0 + 1);
-        *reinterpret_cast<longlong2*>(perm + p0 + 2) = make_longlong2(g0 + 2, g0 + 3);
-        *reinterpret_cast<int4*>(tok_turn + p0) = make_int4(M.turn, M.turn, M.turn, M.turn);
-        *reinterpret_cast<int4*>(tok_role + p0) = make_int4(M.role, M.role, M.role, M.role);
-        *reinterpret_cast<uint32_t*>(tok_mask + p0) = mk4;
-        *reinterpret_cast<uint32_t*>(tok_flags + p0) = fg4;
-        *reinterpret_cast<float4*>(tok_reward + p0) = make_float4(rw4[0], rw4[1], rw4[2], rw4[3]);
+        for (int k = 0; k < kTokPerThread; ++k)
+          rw[k] = ((mk4 >> (8 * k)) & 1u) && (A.place_mode == UMAS_PLACE_ALL || pl0 + k == lastv) ? M.rho : 0.f;
+        *reinterpret_cast<longlong2*>(A.perm + p0) = make_longlong2(g0, g0 + 1);
+        *reinterpret_cast<longlong2*>(A.perm + p0 + 2) = make_longlong2(g0 + 2, g0 + 3);
+        *reinterpret_cast<int4*>(A.tok_turn + p0) = make_int4(M.turn, M.turn, M.turn, M.turn);
+        *reinterpret_cast<int4*>(A.tok_role + p0) = make_int4(M.role, M.role, M.role, M.role);
+        *reinterpret_cast<uint32_t*>(A.tok_mask + p0) = mk4;
+        *reinterpret_cast<uint32_t*>(A.tok_flags + p0) = fg4;
+        *reinterpret_cast<float4*>(A.tok_reward + p0) = make_float4(rw[0], rw[1], rw[2], rw[3]);
         continue;
       }
-    } else {
-      s = last_le(turn_seg_off, n_turns, p0);
-    }
-    int64_t pm[kTokPerThread];
-    int32_t tt[kTokPerThread], tr[kTokPerThread];
-    uint8_t mk[kTokPerThread], fg[kTokPerThread];
-    float rw[kTokPerThread];
-    int cur = -1;
-    int64_t seg_a = 0, seg_e = 0;
-    SegMeta M{};
-    uint32_t m4 = 0;
-    bool have_m4 = false;
-#pragma unroll
-    for (int k = 0; k < kTokPerThread; ++k) {
-      const int64_t p = p0 + k;
-      pm[k] = 0; tt[k] = 0; tr[k] = 0; mk[k] = 0; fg[k] = 0; rw[k] = 0.0f;
-      if (p < n_tokens) {
-        if (cur < 0 || p >= seg_e) {                // first token, or the segment changed
-          if (in_window) { while (s_off[s - s_base + 1] <= p) ++s; }   // also steps over empty segments
-          else { while (turn_seg_off[s + 1] <= p) ++s; }
-          cur = s;
-          seg_a = in_window ? s_off[s - s_base] : turn_seg_off[s];
-          seg_e = in_window ? s_off[s - s_base + 1] : turn_seg_off[s + 1];
-          M = in_window ? s_meta[s - s_base] : seg_meta[s];
-          if (k == 0) {                             // all four tokens in one segment and a 4-byte aligned source: one load
-            const int64_t g0 = M.src + (p0 - seg_a);
-            have_m4 = mask_aligned && (g0 & 3) == 0 && p0 + kTokPerThread <= seg_e;
-            if (have_m4) m4 = *reinterpret_cast<const uint32_t*>(mask_global + g0);
-          }
-        }
-        const int64_t g = M.src + (p - seg_a);
-        const uint8_t m = have_m4 ? (((m4 >> (8 * k)) & 0xFFu) ? 1 : 0) : (mask_global[g] ? 1 : 0);
-        pm[k] = g; tt[k] = M.turn; tr[k] = M.role; mk[k] = m;
-        fg[k] = static_cast<uint8_t>(m | (p == seg_e - 1 ? M.end_flags : 0));
-        if (m && (place_mode == UMAS_PLACE_ALL || M.last_valid == p)) rw[k] = M.rho;
-        cnt[rd / kCntRounds] += m;
+      for (int k = 0; k < kTokPerThread; ++k) {
+        const int pl = pl0 + k;
+        if (pl >= ntok) break;
+        while (s_loc[s + 1] <= pl) ++s;
+        const SegMeta M = s_meta[s];
+        const uint32_t m = (mk4 >> (8 * k)) & 1u;
+        const bool seg_done = s_loc[s + 1] <= kTokBlock || !ahead;
+        A.perm[p0 + k] = M.src + (p0 + k - s_off[s]);
+        A.tok_turn[p0 + k] = M.turn;
+        A.tok_role[p0 + k] = M.role;
+        A.tok_mask[p0 + k] = static_cast<uint8_t>(m);
+        A.tok_flags[p0 + k] = static_cast<uint8_t>(m | (pl + 1 == s_loc[s + 1] ? M.end_flags : 0));
+        A.tok_reward[p0 + k] = m && (A.place_mode == UMAS_PLACE_ALL || (seg_done && pl == s_lastv[s])) ? M.rho : 0.f;
       }
     }
-    if (p0 + kTokPerThread <= n_tokens) {
-      *reinterpret_cast<longlong2*>(perm + p0) = make_longlong2(pm[0], pm[1]);
-      *reinterpret_cast<longlong2*>(perm + p0 + 2) = make_longlong2(pm[2], pm[3]);
-      *reinterpret_cast<int4*>(tok_turn + p0) = make_int4(tt[0], tt[1], tt[2], tt[3]);
-      *reinterpret_cast<int4*>(tok_role + p0) = make_int4(tr[0], tr[1], tr[2], tr[3]);
-      *reinterpret_cast<uchar4*>(tok_mask + p0) = make_uchar4(mk[0], mk[1], mk[2], mk[3]);
-      *reinterpret_cast<uchar4*>(tok_flags + p0) = make_uchar4(fg[0], fg[1], fg[2], fg[3]);
-      *reinterpret_cast<float4*>(tok_reward + p0) = make_float4(rw[0], rw[1], rw[2], rw[3]);
-    } else {
-      for (int k = 0; k < kTokPerThread && p0 + k < n_tokens; ++k) {
-        perm[p0 + k] = pm[k]; tok_turn[p0 + k] = tt[k]; tok_role[p0 + k] = tr[k];
-        tok_mask[p0 + k] = mk[k]; tok_flags[p0 + k] = fg[k]; tok_reward[p0 + k] = rw[k];
-      }
-    }
+  } else {
+    many_segments_outputs(A, blk0, ntok, s_first, s_last, s_mk, ahead);
   }
-#pragma unroll
-  for (int gi = 0; gi < kTokRounds / kCntRounds; ++gi) {
-    const int64_t total = block_sum<int64_t>(cnt[gi], smem);
-    const int64_t slot = static_cast<int64_t>(blockIdx.x) * (kTokRounds / kCntRounds) + gi;
-    if (threadIdx.x == 0 && slot * kCntTokens < n_tokens) tok_blk[slot] = total;
-    __syncthreads();                                // smem is reused by the next group's sum
-  }
+
 }
 
-// Compaction of mask=1 positions into rowsel (stream-relative), plus the per-model offsets.  A block
-// covers kSelBlock tokens = one count group of k_tokens, whose scanned counts give its base.
-constexpr int kSelPerThread = 16;
-constexpr int kSelBlock = kTokThreads * kSelPerThread;
-static_assert(kSelBlock == kCntTokens, "a compaction block is one count group");
+// The compacted list of scored positions, per stream and stream-relative, from the masks in model-local order.  A
+// block of 4096 tokens finds the number of scored tokens in front of it as the totals of the groups of blocks before
+// its group plus the counts of the blocks before it in its group, all written by the token kernel.
+struct SelArgs {
+  int64_t n_tokens;
+  int n_models, grp_shift;
+  const uint8_t* tok_mask;
+  const int64_t* model_tok_off;
+  const unsigned long long* blk_count;
+  const unsigned long long* grp_count;
+  int32_t* rowsel;
+  int64_t* model_rowsel_off;
+};
+
 __global__ void __launch_bounds__(kTokThreads)
-k_rowsel(int64_t n_tokens, int n_models, const uint8_t* __restrict__ tok_mask,
-         const int64_t* __restrict__ model_tok_off, const int64_t* __restrict__ tok_blk,
-         const int64_t* __restrict__ tok_total, int32_t* __restrict__ rowsel,
-         int64_t* __restrict__ model_rowsel_off) {
-  __shared__ int32_t smem[32];
-  __shared__ int32_t s_out[kSelBlock];
+k_rowsel(SelArgs A) {
+  __shared__ int64_t smem[32];
+  __shared__ uint16_t s_out[kTokBlock];             // the block's scored positions, block-relative, compacted
   __shared__ int64_t moff[UMAS_MAX_MODELS + 1];
-  if (static_cast<int>(threadIdx.x) <= n_models) moff[threadIdx.x] = model_tok_off[threadIdx.x];
-  __syncthreads();
-  const int64_t p0 = (static_cast<int64_t>(blockIdx.x) * kTokThreads + threadIdx.x) * kSelPerThread;
-  uint32_t w[4] = {0u, 0u, 0u, 0u};
-  if (p0 + kSelPerThread <= n_tokens) {
-    const uint4 m4 = *reinterpret_cast<const uint4*>(tok_mask + p0);
-    w[0] = m4.x; w[1] = m4.y; w[2] = m4.z; w[3] = m4.w;
-  } else {
-    for (int k = 0; k < kSelPerThread; ++k)
-      if (p0 + k < n_tokens) w[k >> 2] |= static_cast<uint32_t>(tok_mask[p0 + k]) << (8 * (k & 3));
+  __shared__ int32_t s_mro[UMAS_MAX_MODELS + 1];    // scored tokens of the block in front of a stream that starts in it, -1
+  const int tid = threadIdx.x;
+  const int64_t blk0 = static_cast<int64_t>(blockIdx.x) * kTokBlock;
+  const int64_t blk_end = blk0 + kTokBlock < A.n_tokens ? blk0 + kTokBlock : A.n_tokens;
+  if (tid <= A.n_models) { moff[tid] = A.model_tok_off[tid]; s_mro[tid] = -1; }
+  // what lies in front of the block
+  int64_t part = 0;
+  {
+    const int64_t grp = static_cast<int64_t>(blockIdx.x) >> A.grp_shift;
+    for (int64_t g = tid; g < grp; g += kTokThreads) part += static_cast<int64_t>(A.grp_count[g]);
+    for (int64_t k = (grp << A.grp_shift) + tid; k < blockIdx.x; k += kTokThreads) part += static_cast<int64_t>(A.blk_count[k]);
   }
-  const int32_t cnt = __popc(w[0]) + __popc(w[1]) + __popc(w[2]) + __popc(w[3]);   // mask bytes are 0 or 1
-  int32_t tot;
-  const int64_t base = tok_blk[blockIdx.x];
-  int32_t lpos = block_excl_scan<int32_t>(cnt, smem, &tot);
-  // a model's stream may start inside this block: only then do tokens need the per-token boundary checks
-  const int64_t sel0 = static_cast<int64_t>(blockIdx.x) * kSelBlock;
-  bool boundary = false;
-  for (int j = 0; j <= n_models; ++j) boundary |= moff[j] > sel0 && moff[j] < sel0 + kSelBlock;
-  if (p0 < n_tokens) {
-    int m = 0;
-    while (m < n_models && moff[m + 1] <= p0) ++m;
-    if (!boundary) {
-      for (int j = 0; j <= n_models; ++j)
-        if (moff[j] == p0) model_rowsel_off[j] = base + lpos;      // only a block's first token can start a stream here
-      const int32_t rel = static_cast<int32_t>(p0 - moff[m]);
+  const int64_t p0 = blk0 + tid * kCompact;
+  uint32_t w4[4] = {0u, 0u, 0u, 0u};
+  if (p0 + kCompact <= A.n_tokens) {
+    const uint4 w = *reinterpret_cast<const uint4*>(A.tok_mask + p0);
+    w4[0] = w.x; w4[1] = w.y; w4[2] = w.z; w4[3] = w.w;
+  } else {
+    for (int k = 0; k < kCompact; ++k)
+      if (p0 + k < A.n_tokens) w4[k >> 2] |= static_cast<uint32_t>(A.tok_mask[p0 + k]) << (8 * (k & 3));
+  }
+  const int64_t prefix = block_sum<int64_t>(part, smem);
+  const int32_t c = __popc(w4[0]) + __popc(w4[1]) + __popc(w4[2]) + __popc(w4[3]);   // mask bytes are 0 or 1
+  int32_t block_count;
+  int o = block_excl_scan<int32_t>(c, reinterpret_cast<int32_t*>(smem), &block_count);
+  // a stream may start inside the block: the scored tokens in front of its first token give its place in rowsel
+  const int e = o;
 #pragma unroll
-      for (int k = 0; k < kSelPerThread; ++k)
-        if ((w[k >> 2] >> (8 * (k & 3))) & 1u) s_out[lpos++] = rel + k;   // bytes past n_tokens are 0
-    } else {
+  for (int k = 0; k < kCompact; ++k)
+    if ((w4[k >> 2] >> (8 * (k & 3))) & 1u) s_out[o++] = static_cast<uint16_t>(tid * kCompact + k);
+  for (int j = 0; j <= A.n_models; ++j) {
+    const int64_t q = moff[j] - p0;
+    if (q >= 0 && q < kCompact && moff[j] < A.n_tokens) {
+      int before = 0;
 #pragma unroll
-      for (int k = 0; k < kSelPerThread; ++k) {
-        const int64_t p = p0 + k;
-        if (p < n_tokens) {
-          while (m < n_models && moff[m + 1] <= p) ++m;
-          for (int j = 0; j <= n_models; ++j)
-            if (moff[j] == p) model_rowsel_off[j] = base + lpos;
-          if ((w[k >> 2] >> (8 * (k & 3))) & 1u) s_out[lpos++] = static_cast<int32_t>(p - moff[m]);
-        }
-      }
+      for (int k = 0; k < kCompact; ++k) before += k < q ? static_cast<int>((w4[k >> 2] >> (8 * (k & 3))) & 1u) : 0;
+      s_mro[j] = e + before;
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < tot; i += kTokThreads) rowsel[base + i] = s_out[i];   // compacted, coalesced
-  if (blockIdx.x == 0 && threadIdx.x == 0)
-    for (int j = 0; j <= n_models; ++j)
-      if (moff[j] >= n_tokens) model_rowsel_off[j] = *tok_total;
+  for (int j = tid; j <= A.n_models; j += kTokThreads)
+    if (s_mro[j] >= 0) A.model_rowsel_off[j] = prefix + s_mro[j];
+  int m0 = 0;                                        // the stream of the block's first token
+  while (m0 < A.n_models && moff[m0 + 1] <= blk0) ++m0;
+  for (int i = tid; i < block_count; i += kTokThreads) {   // compacted, coalesced, stream-relative
+    const int64_t p = blk0 + s_out[i];
+    int m = m0;
+    while (m < A.n_models && moff[m + 1] <= p) ++m;
+    A.rowsel[prefix + i] = static_cast<int32_t>(p - moff[m]);
+  }
+  if (blk_end == A.n_tokens && tid == 0)             // streams that start at the very end hold nothing
+    for (int j = 0; j <= A.n_models; ++j)
+      if (moff[j] >= A.n_tokens) A.model_rowsel_off[j] = prefix + block_count;
 }
 
 // ------------------------------------------------------------------ host side
@@ -612,6 +752,7 @@ umas_status validate(const umas_graph* g, const umas_rewards* r, const umas_stre
   return UMAS_OK;
 }
 
+
 }  // namespace
 }  // namespace umas
 
@@ -658,10 +799,12 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
   }
 
   // The thin arrays are the first arrays of the workspace, up to traj_norm: they are gathered at the same offsets in a
-  // block of pinned host memory and go to the device in one asynchronous copy.  The host arrays have been read when
-  // the call returns; the host does not wait for the stream.
+  // block of pinned host memory and go to the device in one asynchronous copy, together with the zeros that the plan
+  // kernel's per-chunk totals start from.  The host arrays have been read when the call returns; the host does not
+  // wait for the stream.
   char* const ws_base = static_cast<char*>(workspace);
   const size_t staged_bytes = static_cast<size_t>(reinterpret_cast<char*>(w.traj_norm) - ws_base);
+  const int n_chunks = plan_chunks(B);
   ThinStage stage;
   vs = stage.begin(staged_bytes);
   if (vs != UMAS_OK) return vs;
@@ -682,6 +825,8 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
     put(w.group_off, goff.data(), sizeof(int32_t) * goff.size());
     put(w.group_members, gmem.data(), sizeof(int32_t) * gmem.size());
   }
+  stage.zero(static_cast<size_t>(reinterpret_cast<char*>(w.plan_part) - ws_base),
+             sizeof(unsigned long long) * static_cast<size_t>(n_chunks) * kPlanWords);
   vs = stage.flush(workspace, staged_bytes, st);
   if (vs != UMAS_OK) return vs;
   prof_mark(st);
@@ -693,52 +838,44 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
     UMAS_LAUNCHED("k_group_norm");
     traj_r = w.traj_norm;
   }
-  const int nbt = cdiv(U > 0 ? U : 1, kTurnBlock);
-  hipLaunchKernelGGL(k_fill_i64, dim3(cdiv(U + 1, 256)), dim3(256), 0, st, o->traj_seg_off,
-                     static_cast<int64_t>(U) + 1, N);
-  UMAS_LAUNCHED("k_fill_i64");
-  hipLaunchKernelGGL(k_fill_i64, dim3(1), dim3(256), 0, st, o->model_rowsel_off, static_cast<int64_t>(K) + 1,
-                     static_cast<int64_t>(0));
-  UMAS_LAUNCHED("k_fill_i64");
-  if (U > 0) {
-    hipLaunchKernelGGL(k_turn_meta, dim3(nbt), dim3(kTurnBlock), 0, st, B, U, R, w.traj_turn_off, w.turn_role,
-                       w.role_to_model, r->role_reward ? w.role_reward : nullptr,
-                       r->turn_reward ? w.turn_reward : nullptr, traj_r, r->w_role ? w.weights : nullptr,
-                       r->w_turn ? w.weights + R : nullptr, r->w_traj ? w.weights + 2 * R : nullptr,
-                       w.turn_traj, w.turn_model, o->turn_step, o->turn_scalar);
-    UMAS_LAUNCHED("k_turn_meta");
-  }
-  hipLaunchKernelGGL(k_part_reduce, dim3(nbt), dim3(kTurnBlock), 0, st, U, K, nbt, w.turn_model, w.turn_tok_off,
-                     w.part);
-  UMAS_LAUNCHED("k_part_reduce");
-  hipLaunchKernelGGL(k_excl_scan_rows, dim3(2 * K), dim3(1024), 0, st, w.part, nbt, w.part_total);
-  UMAS_LAUNCHED("k_excl_scan_rows");
-  hipLaunchKernelGGL(k_part_apply, dim3(nbt), dim3(kTurnBlock), 0, st, U, K, nbt, N, w.turn_model, w.turn_tok_off,
-                     w.part, w.part_total, o->model_tok_off, o->model_turn_off, o->turn_seg_off, o->seg_turn);
-  UMAS_LAUNCHED("k_part_apply");
-  hipLaunchKernelGGL(k_run_reduce, dim3(nbt), dim3(kTurnBlock), 0, st, U, o->seg_turn, w.turn_traj, w.turn_model,
-                     w.run_blk);
-  UMAS_LAUNCHED("k_run_reduce");
-  hipLaunchKernelGGL(k_excl_scan_rows, dim3(1), dim3(1024), 0, st, w.run_blk, nbt, w.run_total);
-  UMAS_LAUNCHED("k_excl_scan_rows");
-  hipLaunchKernelGGL(k_run_apply, dim3(nbt), dim3(kTurnBlock), 0, st, U, K, o->seg_turn, w.turn_traj, w.turn_model,
-                     w.run_blk, w.run_total, o->turn_seg_off, o->model_turn_off, o->traj_seg_off,
-                     o->model_trajrun_off);
-  UMAS_LAUNCHED("k_run_apply");
+  const int64_t nbk = cdiv(N > 0 ? N : 1, kTokBlock);
+  PlanArgs P;
+  P.n_traj = B; P.n_turns = U; P.n_roles = R; P.n_models = K; P.n_chunks = n_chunks;
+  const int gsh = group_shift(nbk);
+  P.n_tokens = N; P.n_count = nbk + (nbk >> gsh) + 1;
+  P.traj_turn_off = w.traj_turn_off; P.turn_role = w.turn_role; P.role_to_model = w.role_to_model;
+  P.turn_tok_off = w.turn_tok_off;
+  P.role_reward = r->role_reward ? w.role_reward : nullptr;
+  P.turn_reward = r->turn_reward ? w.turn_reward : nullptr;
+  P.traj_reward = traj_r;
+  P.w_role = r->w_role ? w.weights : nullptr;
+  P.w_turn = r->w_turn ? w.weights + R : nullptr;
+  P.w_traj = r->w_traj ? w.weights + 2 * R : nullptr;
+  P.plan_part = w.plan_part; P.seg_meta = w.seg_meta; P.blk_first = w.blk_first;
+  P.tok_count = w.tok_count;
+  P.model_tok_off = o->model_tok_off; P.model_turn_off = o->model_turn_off; P.model_trajrun_off = o->model_trajrun_off;
+  P.model_rowsel_off = o->model_rowsel_off; P.turn_seg_off = o->turn_seg_off; P.seg_turn = o->seg_turn;
+  P.traj_seg_off = o->traj_seg_off; P.turn_scalar = o->turn_scalar; P.turn_step = o->turn_step;
+  const dim3 plan_grid(std::min(n_chunks, kPlanMaxGrid));
+  if (K <= 1) hipLaunchKernelGGL(k_turn_plan<1>, plan_grid, dim3(kPlanThreads), 0, st, P);
+  else if (K <= 2) hipLaunchKernelGGL(k_turn_plan<2>, plan_grid, dim3(kPlanThreads), 0, st, P);
+  else if (K <= 4) hipLaunchKernelGGL(k_turn_plan<4>, plan_grid, dim3(kPlanThreads), 0, st, P);
+  else hipLaunchKernelGGL(k_turn_plan<UMAS_MAX_MODELS>, plan_grid, dim3(kPlanThreads), 0, st, P);
+  UMAS_LAUNCHED("k_turn_plan");
   if (U > 0 && N > 0) {
-    hipLaunchKernelGGL(k_seg_meta, dim3(cdiv(U, 256 / kSegLanes)), dim3(256), 0, st, U, N, o->seg_turn, w.turn_tok_off,
-                       o->turn_seg_off, w.turn_role, o->turn_scalar, w.turn_traj, w.turn_model, tok_mask_global,
-                       w.seg_meta, w.blk_first);
-    UMAS_LAUNCHED("k_seg_meta");
-    const int nbk = cdiv(N, kTokBlock);
-    hipLaunchKernelGGL(k_tokens, dim3(nbk), dim3(kTokThreads), 0, st, N, U, r->place_mode, o->turn_seg_off, w.seg_meta,
-                       w.blk_first, tok_mask_global, o->perm, o->tok_turn, o->tok_role, o->tok_mask, o->tok_flags,
-                       o->tok_reward, w.tok_blk);
+    TokArgs T;
+    T.n_tokens = N; T.n_turns = U; T.n_models = K; T.place_mode = r->place_mode; T.grp_shift = gsh;
+    T.turn_seg_off = o->turn_seg_off; T.seg_meta = w.seg_meta; T.blk_first = w.blk_first; T.mask_global = tok_mask_global;
+    T.blk_count = w.tok_count; T.grp_count = w.tok_count + nbk;
+    T.perm = o->perm; T.tok_turn = o->tok_turn; T.tok_role = o->tok_role; T.tok_mask = o->tok_mask;
+    T.tok_flags = o->tok_flags; T.tok_reward = o->tok_reward;
+    hipLaunchKernelGGL(k_tokens, dim3(static_cast<unsigned>(nbk)), dim3(kTokThreads), 0, st, T);
     UMAS_LAUNCHED("k_tokens");
-    hipLaunchKernelGGL(k_excl_scan_rows, dim3(1), dim3(1024), 0, st, w.tok_blk, cdiv(N, kCntTokens), w.tok_total);
-    UMAS_LAUNCHED("k_excl_scan_rows");
-    hipLaunchKernelGGL(k_rowsel, dim3(cdiv(N, kSelBlock)), dim3(kTokThreads), 0, st, N, K, o->tok_mask, o->model_tok_off,
-                       w.tok_blk, w.tok_total, o->rowsel, o->model_rowsel_off);
+    SelArgs S;
+    S.n_tokens = N; S.n_models = K; S.grp_shift = gsh;
+    S.tok_mask = o->tok_mask; S.model_tok_off = o->model_tok_off; S.blk_count = w.tok_count; S.grp_count = w.tok_count + nbk;
+    S.rowsel = o->rowsel; S.model_rowsel_off = o->model_rowsel_off;
+    hipLaunchKernelGGL(k_rowsel, dim3(static_cast<unsigned>(nbk)), dim3(kTokThreads), 0, st, S);
     UMAS_LAUNCHED("k_rowsel");
   }
   return UMAS_OK;

@@ -41,6 +41,7 @@ constexpr int64_t kLongSegment = 16 * kTile;     // a segment end farther away t
 constexpr int kAhead = 1;                        // tiles whose loads are in flight beyond the one in work
 
 enum : uint8_t { kFlagMask = 1, kFlagTurnEnd = 2, kFlagRunEnd = 4 };
+constexpr int kFlagStepShift = 3, kFlagStepMany = 31;   // bits 3-7 of a turn end inside a run: steps to the next turn
 
 struct Aff {
   float a, b, c, e, f;
@@ -278,8 +279,11 @@ __device__ __forceinline__ void walk_range(const ScanParams& P, const Range& R, 
       kap[k] = 1.f;
       if constexpr (DECAY) {
         if (mine[k] && (fl[k] & kFlagTurnEnd) && !(fl[k] & P.seg_bit)) {   // a later turn of the same run follows: p + 1 exists
-          const int64_t p = p0 + k;
-          const int ds = P.turn_step[P.tok_turn[p + 1]] - P.turn_step[P.tok_turn[p]];
+          int ds = static_cast<int>(fl[k] >> kFlagStepShift);   // steps to the run's next turn; kFlagStepMany: more than fit
+          if (ds == kFlagStepMany) {
+            const int64_t p = p0 + k;
+            ds = P.turn_step[P.tok_turn[p + 1]] - P.turn_step[P.tok_turn[p]];
+          }
           kap[k] = powf(P.gamma_turn, static_cast<float>(ds));
         }
       }

@@ -176,6 +176,27 @@ def scan_conditioning(st, traj_turn_off, r, value, gamma, lam, gamma_turn, seg_m
     return cond
 
 
+def expected_flags(w: wl.Workload, st, step):
+    """The flag byte of every token from the oracle's streams: bit 0 the mask, bit 1 on a turn segment's last token,
+    bit 2 on a trajectory run's last token, bits 3-7 on a turn's last token inside a run the number of steps to the
+    run's next turn with tokens (31 for more than 30)."""
+    flags = st["tok_mask"].astype(np.uint8).copy()
+    off = st["turn_seg_off"]
+    n_runs = int(st["model_trajrun_off"][-1])
+    run_end = set((st["traj_seg_off"][1:n_runs + 1] - 1).tolist()) | set((st["model_tok_off"][1:] - 1).tolist())
+    filled = [sl for sl in range(w.n_turns) if off[sl + 1] > off[sl]]
+    for i, sl in enumerate(filled):
+        last = int(off[sl + 1]) - 1
+        flags[last] |= 2
+        if last in run_end:
+            flags[last] |= 4
+        else:
+            ds = int(step[st["seg_turn"][filled[i + 1]]] - step[st["seg_turn"][sl]])
+            assert ds > 0
+            flags[last] |= min(ds, 31) << 3
+    return flags
+
+
 def check_front(w: wl.Workload, s, adv, ret, rho, st, r, adv_o, ret_o, tol=1e-5, adv_abs=None):
     """Routing, masks and placement bit-exact; composed rewards and advantages within tol.  adv_abs, when given, is an
     absolute allowance per token on top of tol (scan_conditioning: slowly decaying sums of terms that cancel)."""
@@ -193,6 +214,7 @@ def check_front(w: wl.Workload, s, adv, ret, rho, st, r, adv_o, ret_o, tol=1e-5,
     if w.n_turns:
         step = np.concatenate([np.arange(1, n + 1) for n in np.diff(w.traj_turn_off)]) if w.n_traj else np.zeros(0)
         assert np.array_equal(s.turn_step.cpu().numpy()[:w.n_turns], step)
+        assert np.array_equal(s.tok_flags.cpu().numpy(), expected_flags(w, st, step)), "tok_flags differ"
     ts = s.turn_scalar.cpu().numpy()[:w.n_turns]
     if w.traj_group is None:
         assert np.array_equal(ts.view(np.uint32), rho.view(np.uint32)), "composed turn rewards are not bit-exact"

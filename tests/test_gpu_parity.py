@@ -457,6 +457,71 @@ def test_random_graphs(seed):
     P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
 
 
+def _short_segment_graph(seed, n_traj, max_len, long_every):
+    """Trajectories of many turns of 0 .. max_len tokens (hundreds of turn segments to a block of 4096 tokens), a turn
+    of a few thousand tokens now and then, three roles on two models."""
+    w = wl.make_workload(0)
+    rng = np.random.default_rng(seed)
+    turns = rng.integers(1, 40, size=n_traj)
+    lens = rng.integers(0, max_len + 1, size=int(turns.sum())).astype(np.int64)
+    lens[::long_every] = rng.integers(1500, 6000, size=len(lens[::long_every]))
+    w.n_traj, w.n_turns, w.n_roles, w.n_models = n_traj, len(lens), 3, 2
+    w.traj_turn_off = np.concatenate([[0], np.cumsum(turns)]).astype(np.int32)
+    w.turn_role = rng.integers(0, 3, size=w.n_turns).astype(np.int32)
+    w.role_to_model = np.array([0, 1, 0], np.int32)
+    w.turn_tok_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    w.n_tokens = int(w.turn_tok_off[-1])
+    w.turn_pred_off, w.turn_pred, w.traj_group = None, None, None
+    w.tok_mask = (rng.random(w.n_tokens) < 0.5).astype(np.uint8)
+    w.traj_reward = rng.normal(size=w.n_traj).astype(np.float32)
+    w.turn_reward = rng.normal(size=w.n_turns).astype(np.float32)
+    w.role_reward = rng.normal(size=w.n_traj * 3).astype(np.float32)
+    w.value = (0.1 * rng.normal(size=w.n_tokens)).astype(np.float32)
+    return w
+
+
+@pytest.mark.parametrize("seed,max_len,long_every,dense,seg_mode", [
+    (1, 8, 97, False, 0), (2, 3, 1000000, False, 1), (3, 8, 211, True, 1), (4, 24, 53, False, 1), (5, 1, 400, False, 0)])
+def test_blocks_of_many_short_segments(seed, max_len, long_every, dense, seg_mode):
+    """Blocks of tokens that hold more turn segments than the token kernel keeps in LDS (its plain per-token path),
+    mixed with blocks that do not, empty turns in between, and long turns that begin or end inside such blocks."""
+    w = _short_segment_graph(seed, 300, max_len, long_every)
+    kw = dict(seg_mode=seg_mode, gamma_turn=0.95, place_mode=wl.PLACE_ALL if dense else wl.PLACE_LAST)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w, **kw)
+    s, adv, ret = P.gpu_front(w, **kw)
+    assert np.diff(st["turn_seg_off"]).size / max(1, w.n_tokens / 4096) > 256 or long_every < 1000
+    P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+
+
+@pytest.mark.parametrize("gap", [30, 31, 32, 75])
+def test_steps_between_turns_of_a_run_at_the_limit_of_the_flag_bits(gap):
+    """A model's turns `gap` steps apart inside one trajectory: up to 30 the step difference travels in the flag byte,
+    beyond that the scan looks it up."""
+    w = wl.make_workload(0)
+    rng = np.random.default_rng(gap)
+    n_turns = gap + 3
+    lens = rng.integers(1, 9, size=2 * n_turns).astype(np.int64)
+    w.n_traj, w.n_turns, w.n_roles, w.n_models = 2, 2 * n_turns, 2, 2
+    w.traj_turn_off = np.array([0, n_turns, 2 * n_turns], np.int32)
+    role = np.zeros(n_turns, np.int32)
+    role[[1, 1 + gap]] = 1                                   # model 1: steps 2 and 2 + gap
+    w.turn_role = np.concatenate([role, role]).astype(np.int32)
+    w.role_to_model = np.array([0, 1], np.int32)
+    w.turn_tok_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    w.n_tokens = int(w.turn_tok_off[-1])
+    w.turn_pred_off, w.turn_pred, w.traj_group = None, None, None
+    w.tok_mask = (rng.random(w.n_tokens) < 0.7).astype(np.uint8)
+    w.traj_reward = rng.normal(size=2).astype(np.float32)
+    w.turn_reward = rng.normal(size=w.n_turns).astype(np.float32)
+    w.role_reward = None
+    w.value = (0.1 * rng.normal(size=w.n_tokens)).astype(np.float32)
+    kw = dict(seg_mode=1, gamma_turn=0.99, place_mode=wl.PLACE_LAST)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w, **kw)
+    s, adv, ret = P.gpu_front(w, **kw)
+    assert (s.tok_flags.cpu().numpy() >> 3).max() == min(gap, 31)
+    P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+
+
 @pytest.mark.parametrize("seg_mode,gamma_turn,with_value,dense,gamma,lam", [
     (0, 1.0, True, False, 1.0, 1.0), (1, 0.9, True, True, 1.0, 1.0), (1, 1.0, False, True, 1.0, 1.0),
     (0, 1.0, True, False, 0.99, 0.95), (1, 0.9, True, False, 0.9999, 0.9995), (1, 1.0, True, True, 1.0, 0.99)])
