@@ -180,7 +180,8 @@ def hbm_kernels(umas, wl, torch, cfg, n_traj, iters=5, shaping=False, traj_scan=
     route_names = [k for k in prof if not k.startswith("k_gae_scan")]
     route_ms = sum(prof[k][0] for k in route_names) / iters
     scan_bytes = (17 if value is not None else 13) * N
-    route_bytes = (1 + 8 + 4 + 4 + 1 + 4) * N + 4 * scored
+    # global mask read; perm, turn, role, mask, flags, reward written per token; rowsel per scored token
+    route_bytes = (1 + 8 + 4 + 4 + 1 + 1 + 4) * N + 4 * scored
 
     def entry(t, nbytes):
         return {"ms": t, "algorithmic_bytes": nbytes, "GBps": nbytes / t / 1e6, "frac_of_hbm_peak": nbytes / t / 1e6 / PEAK_HBM_GBPS}

@@ -25,7 +25,7 @@ namespace umas {
 namespace {
 
 constexpr int kPlanThreads = 256;  // trajectories per chunk of the plan kernel
-constexpr int kPlanMaxGrid = 512;  // its workgroups at most: light ones, all of them resident at once
+constexpr int kPlanPerCu = 2;      // its workgroups per compute unit at most: every instance fits twice, so all of them are resident at once
 constexpr int kCnt = 3;            // per model and chunk: turns, tokens, trajectory runs
 constexpr int kPlanWords = UMAS_MAX_MODELS * kCnt;
 constexpr int kTokThreads = 256;
@@ -193,8 +193,7 @@ template <int KM>
 __global__ void __launch_bounds__(kPlanThreads, 2)
 k_turn_plan(PlanArgs A) {
   __shared__ int64_t smem[32];
-  __shared__ long long s_sum[2][kPlanWords][kPlanThreads / kPlanWords];   // [total | before this chunk][counter][group of threads]
-  __shared__ long long s_res[2][kPlanWords];
+  __shared__ long long s_res[2][kPlanWords];         // [total | before this chunk][model, counter]
   __shared__ uint8_t s_phi[UMAS_MAX_ROLES];          // role -> model
   const int tid = threadIdx.x;
   const int K = A.n_models;
@@ -229,30 +228,39 @@ k_turn_plan(PlanArgs A) {
 
   // 2. every chunk again: where its trajectories' turns go
   for (int c = blockIdx.x; c < A.n_chunks; c += gridDim.x) {
-    // totals over all chunks and over the chunks before this one, for every (model, counter): thread t adds up
-    // counter t % 24 over the chunks t / 24, t / 24 + 10, ...; a word is taken when its ready mark is set
-    constexpr int kGroups = kPlanThreads / kPlanWords;
-    const int j = tid % kPlanWords, grp = tid / kPlanWords;
-    if (grp < kGroups) {
-      long long all = 0, before = 0;
-      if (j < K * kCnt) {
-        for (int cc = grp; cc < A.n_chunks; cc += kGroups) {
-          unsigned long long w;
-          while (!((w = __hip_atomic_load(A.plan_part + static_cast<size_t>(cc) * kPlanWords + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) & kMark))
+    // totals over all chunks and over the chunks before this one, for every (model, counter): thread t takes the
+    // chunks t, t + 256, ..., all words of a chunk in flight together; a word is taken when its ready mark is set
+    if (tid < 2 * kPlanWords) (&s_res[0][0])[tid] = 0;
+    __syncthreads();
+    {
+      constexpr int kW = KM * kCnt;
+      long long all[kW], before[kW];
+#pragma unroll
+      for (int j = 0; j < kW; ++j) { all[j] = 0; before[j] = 0; }
+      for (int cc = tid; cc < A.n_chunks; cc += kPlanThreads) {
+        unsigned long long* const src = A.plan_part + static_cast<size_t>(cc) * kPlanWords;
+        unsigned long long w[kW];
+#pragma unroll
+        for (int j = 0; j < kW; ++j) w[j] = j < K * kCnt ? __hip_atomic_load(src + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : kMark;
+#pragma unroll
+        for (int j = 0; j < kW; ++j) {
+          while (!(w[j] & kMark)) {
             __builtin_amdgcn_s_sleep(2);
-          const long long v = static_cast<long long>(w & ~kMark);
-          all += v;
-          before += cc < c ? v : 0;
+            w[j] = __hip_atomic_load(src + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+          const long long v = static_cast<long long>(w[j] & ~kMark);
+          all[j] += v;
+          before[j] += cc < c ? v : 0;
         }
       }
-      s_sum[0][j][grp] = all;
-      s_sum[1][j][grp] = before;
-    }
-    __syncthreads();
-    if (tid < 2 * kPlanWords) {
-      long long t = 0;
-      for (int g = 0; g < kGroups; ++g) t += s_sum[tid / kPlanWords][tid % kPlanWords][g];
-      s_res[tid / kPlanWords][tid % kPlanWords] = t;
+#pragma unroll
+      for (int j = 0; j < kW; ++j) {
+        const long long ta = wave_sum(all[j]), tb = wave_sum(before[j]);
+        if ((tid & (kWave - 1)) == 0) {
+          atomicAdd(reinterpret_cast<unsigned long long*>(&s_res[0][j]), static_cast<unsigned long long>(ta));
+          atomicAdd(reinterpret_cast<unsigned long long*>(&s_res[1][j]), static_cast<unsigned long long>(tb));
+        }
+      }
     }
     __syncthreads();
     // first slot, token offset and run of every stream: streams lie one after the other
@@ -363,7 +371,7 @@ k_turn_plan(PlanArgs A) {
         g0 = g1;
       }
     }
-    __syncthreads();                                 // s_sum and s_res are the next chunk's
+    __syncthreads();                                 // s_res is the next chunk's
   }
 }
 
@@ -642,47 +650,60 @@ struct SelArgs {
   int64_t* model_rowsel_off;
 };
 
+constexpr int kSelMul = 2;                          // blocks of the token kernel to one block of the compaction kernel
+constexpr int kSelBlock = kTokBlock * kSelMul;
+constexpr int kSelPerThread = kSelBlock / kTokThreads;
+constexpr int kSelWords = kSelPerThread / 4;
+
 __global__ void __launch_bounds__(kTokThreads)
 k_rowsel(SelArgs A) {
   __shared__ int64_t smem[32];
-  __shared__ uint16_t s_out[kTokBlock];             // the block's scored positions, block-relative, compacted
+  __shared__ uint16_t s_out[kSelBlock];             // the block's scored positions, block-relative, compacted
   __shared__ int64_t moff[UMAS_MAX_MODELS + 1];
   __shared__ int32_t s_mro[UMAS_MAX_MODELS + 1];    // scored tokens of the block in front of a stream that starts in it, -1
   const int tid = threadIdx.x;
-  const int64_t blk0 = static_cast<int64_t>(blockIdx.x) * kTokBlock;
-  const int64_t blk_end = blk0 + kTokBlock < A.n_tokens ? blk0 + kTokBlock : A.n_tokens;
+  const int64_t blk0 = static_cast<int64_t>(blockIdx.x) * kSelBlock;
+  const int64_t blk_end = blk0 + kSelBlock < A.n_tokens ? blk0 + kSelBlock : A.n_tokens;
   if (tid <= A.n_models) { moff[tid] = A.model_tok_off[tid]; s_mro[tid] = -1; }
   // what lies in front of the block
   int64_t part = 0;
   {
-    const int64_t grp = static_cast<int64_t>(blockIdx.x) >> A.grp_shift;
+    const int64_t first = static_cast<int64_t>(blockIdx.x) * kSelMul;   // in blocks of the token kernel
+    const int64_t grp = first >> A.grp_shift;
     for (int64_t g = tid; g < grp; g += kTokThreads) part += static_cast<int64_t>(A.grp_count[g]);
-    for (int64_t k = (grp << A.grp_shift) + tid; k < blockIdx.x; k += kTokThreads) part += static_cast<int64_t>(A.blk_count[k]);
+    for (int64_t k = (grp << A.grp_shift) + tid; k < first; k += kTokThreads) part += static_cast<int64_t>(A.blk_count[k]);
   }
-  const int64_t p0 = blk0 + tid * kCompact;
-  uint32_t w4[4] = {0u, 0u, 0u, 0u};
-  if (p0 + kCompact <= A.n_tokens) {
-    const uint4 w = *reinterpret_cast<const uint4*>(A.tok_mask + p0);
-    w4[0] = w.x; w4[1] = w.y; w4[2] = w.z; w4[3] = w.w;
+  const int64_t p0 = blk0 + tid * kSelPerThread;
+  uint32_t w4[kSelWords];
+#pragma unroll
+  for (int k = 0; k < kSelWords; ++k) w4[k] = 0u;
+  if (p0 + kSelPerThread <= A.n_tokens) {
+#pragma unroll
+    for (int q = 0; q < kSelWords / 4; ++q) {
+      const uint4 w = *reinterpret_cast<const uint4*>(A.tok_mask + p0 + 16 * q);
+      w4[4 * q] = w.x; w4[4 * q + 1] = w.y; w4[4 * q + 2] = w.z; w4[4 * q + 3] = w.w;
+    }
   } else {
-    for (int k = 0; k < kCompact; ++k)
+    for (int k = 0; k < kSelPerThread; ++k)
       if (p0 + k < A.n_tokens) w4[k >> 2] |= static_cast<uint32_t>(A.tok_mask[p0 + k]) << (8 * (k & 3));
   }
   const int64_t prefix = block_sum<int64_t>(part, smem);
-  const int32_t c = __popc(w4[0]) + __popc(w4[1]) + __popc(w4[2]) + __popc(w4[3]);   // mask bytes are 0 or 1
+  int32_t c = 0;                                    // mask bytes are 0 or 1
+#pragma unroll
+  for (int k = 0; k < kSelWords; ++k) c += __popc(w4[k]);
   int32_t block_count;
   int o = block_excl_scan<int32_t>(c, reinterpret_cast<int32_t*>(smem), &block_count);
   // a stream may start inside the block: the scored tokens in front of its first token give its place in rowsel
   const int e = o;
 #pragma unroll
-  for (int k = 0; k < kCompact; ++k)
-    if ((w4[k >> 2] >> (8 * (k & 3))) & 1u) s_out[o++] = static_cast<uint16_t>(tid * kCompact + k);
+  for (int k = 0; k < kSelPerThread; ++k)
+    if ((w4[k >> 2] >> (8 * (k & 3))) & 1u) s_out[o++] = static_cast<uint16_t>(tid * kSelPerThread + k);
   for (int j = 0; j <= A.n_models; ++j) {
     const int64_t q = moff[j] - p0;
-    if (q >= 0 && q < kCompact && moff[j] < A.n_tokens) {
+    if (q >= 0 && q < kSelPerThread && moff[j] < A.n_tokens) {
       int before = 0;
 #pragma unroll
-      for (int k = 0; k < kCompact; ++k) before += k < q ? static_cast<int>((w4[k >> 2] >> (8 * (k & 3))) & 1u) : 0;
+      for (int k = 0; k < kSelPerThread; ++k) before += k < q ? static_cast<int>((w4[k >> 2] >> (8 * (k & 3))) & 1u) : 0;
       s_mro[j] = e + before;
     }
   }
@@ -691,11 +712,25 @@ k_rowsel(SelArgs A) {
     if (s_mro[j] >= 0) A.model_rowsel_off[j] = prefix + s_mro[j];
   int m0 = 0;                                        // the stream of the block's first token
   while (m0 < A.n_models && moff[m0 + 1] <= blk0) ++m0;
-  for (int i = tid; i < block_count; i += kTokThreads) {   // compacted, coalesced, stream-relative
+  auto entry = [&](int i) -> int32_t {               // compacted entry i of the block, stream-relative
     const int64_t p = blk0 + s_out[i];
     int m = m0;
     while (m < A.n_models && moff[m + 1] <= p) ++m;
-    A.rowsel[prefix + i] = static_cast<int32_t>(p - moff[m]);
+    return static_cast<int32_t>(p - moff[m]);
+  };
+  // coalesced: single entries up to the first 16-byte boundary of rowsel, four at a time from there, single ones at the end
+  int32_t* const dst = A.rowsel + prefix;
+  const int to_boundary = static_cast<int>((4 - ((reinterpret_cast<uintptr_t>(dst) >> 2) & 3)) & 3);
+  const int head = to_boundary < block_count ? to_boundary : block_count;
+  const int n_vec = (block_count - head) / 4;
+  if (tid < head) dst[tid] = entry(tid);
+  for (int v = tid; v < n_vec; v += kTokThreads) {
+    const int i = head + 4 * v;
+    *reinterpret_cast<int4*>(dst + i) = make_int4(entry(i), entry(i + 1), entry(i + 2), entry(i + 3));
+  }
+  {
+    const int i = head + 4 * n_vec + tid;
+    if (i < block_count) dst[i] = entry(i);
   }
   if (blk_end == A.n_tokens && tid == 0)             // streams that start at the very end hold nothing
     for (int j = 0; j <= A.n_models; ++j)
@@ -856,7 +891,11 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
   P.model_tok_off = o->model_tok_off; P.model_turn_off = o->model_turn_off; P.model_trajrun_off = o->model_trajrun_off;
   P.model_rowsel_off = o->model_rowsel_off; P.turn_seg_off = o->turn_seg_off; P.seg_turn = o->seg_turn;
   P.traj_seg_off = o->traj_seg_off; P.turn_scalar = o->turn_scalar; P.turn_step = o->turn_step;
-  const dim3 plan_grid(std::min(n_chunks, kPlanMaxGrid));
+  // workgroups of the plan kernel wait for one another's totals: no more of them than the device holds at once
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+    n_cu = 64;
+  const dim3 plan_grid(std::min(n_chunks, kPlanPerCu * n_cu));
   if (K <= 1) hipLaunchKernelGGL(k_turn_plan<1>, plan_grid, dim3(kPlanThreads), 0, st, P);
   else if (K <= 2) hipLaunchKernelGGL(k_turn_plan<2>, plan_grid, dim3(kPlanThreads), 0, st, P);
   else if (K <= 4) hipLaunchKernelGGL(k_turn_plan<4>, plan_grid, dim3(kPlanThreads), 0, st, P);
@@ -875,7 +914,7 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
     S.n_tokens = N; S.n_models = K; S.grp_shift = gsh;
     S.tok_mask = o->tok_mask; S.model_tok_off = o->model_tok_off; S.blk_count = w.tok_count; S.grp_count = w.tok_count + nbk;
     S.rowsel = o->rowsel; S.model_rowsel_off = o->model_rowsel_off;
-    hipLaunchKernelGGL(k_rowsel, dim3(static_cast<unsigned>(nbk)), dim3(kTokThreads), 0, st, S);
+    hipLaunchKernelGGL(k_rowsel, dim3(cdiv(N, kSelBlock)), dim3(kTokThreads), 0, st, S);
     UMAS_LAUNCHED("k_rowsel");
   }
   return UMAS_OK;
