@@ -8,6 +8,7 @@
 // order, rows of one trajectory in stream order.  All of it is index work on the streams that
 // umas_assign_token_rewards wrote: a trajectory's turns are contiguous inside a stream (one "trajectory
 // run"), so a run's rows are one slice of rowsel, and minibatches are built by moving slices.
+#include <algorithm>
 #include <vector>
 
 #include "umas_common.h"
@@ -16,70 +17,81 @@ namespace umas {
 namespace {
 
 constexpr int kScanItems = 8;
-constexpr int kScanTile = 256 * kScanItems;       // entries one workgroup scans
+constexpr int kScanTile = 256 * kScanItems;       // entries one workgroup scans at a time
+constexpr int kPerCu = 2;                         // workgroups per compute unit of the kernels that wait for one another
+constexpr unsigned long long kMark = 1ull << 63;  // ready mark of a published sum
 
-// flag[q] = 1 when the q-th trajectory of the shuffle is kept.
-__global__ void k_kept_flags(int n_traj, const int32_t* __restrict__ order, const uint8_t* __restrict__ keep,
-                             int64_t* __restrict__ flag) {
-  const int q = blockIdx.x * blockDim.x + threadIdx.x;
-  if (q >= n_traj) return;
-  const int b = order ? order[q] : q;
-  flag[q] = (!keep || keep[b]) ? 1 : 0;
-}
-// rank[b] = position of trajectory b among the kept trajectories in shuffled order (pos = scanned flags), or -1.
-__global__ void k_kept_rank(int n_traj, const int32_t* __restrict__ order, const uint8_t* __restrict__ keep,
-                            const int64_t* __restrict__ pos, int32_t* __restrict__ rank) {
-  const int q = blockIdx.x * blockDim.x + threadIdx.x;
-  if (q >= n_traj) return;
-  const int b = order ? order[q] : q;
-  rank[b] = (!keep || keep[b]) ? static_cast<int32_t>(pos[q]) : -1;
+// Sum of the published words part[0 .. n): every thread takes some, a word is taken when its ready mark is set;
+// also returns, in *before, the sum of the words part[0 .. upto).  Result in every thread.  Waiting is safe because
+// every workgroup publishes all of its words before it reads any, and all workgroups of the grid are resident.
+__device__ __forceinline__ int64_t sum_published(unsigned long long* part, int n, int upto, int64_t* smem, int64_t* before) {
+  int64_t all = 0, bef = 0;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    unsigned long long w;
+    while (!((w = __hip_atomic_load(part + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) & kMark)) __builtin_amdgcn_s_sleep(2);
+    const int64_t v = static_cast<int64_t>(w & ~kMark);
+    all += v;
+    bef += i < upto ? v : 0;
+  }
+  *before = block_sum<int64_t>(bef, smem);
+  return block_sum<int64_t>(all, smem);
 }
 
-// Exclusive prefix sums of the rows of data[nrows][n] in three steps: every workgroup scans its tile of a row in
-// place and leaves the tile's total, the totals of a row are scanned by one workgroup, the tiles add their offset.
+// rank[b] = position of trajectory b among the kept trajectories in shuffled order, or -1; *n_kept = their number.
+// Tiles of kScanTile positions of the shuffle; a workgroup publishes the kept count of each of its tiles, then places
+// each of them behind the tiles before it.  Also clears what the later kernels add to or wait for: zero_a, zero_b.
 __global__ void __launch_bounds__(256)
-k_scan_tiles(int64_t* __restrict__ data, int n, int ntile, int64_t* __restrict__ tile_sum) {
+k_kept_ranks(int n_traj, int ntile, const int32_t* __restrict__ order, const uint8_t* __restrict__ keep,
+             unsigned long long* part, int32_t* __restrict__ rank, int64_t* __restrict__ n_kept,
+             int64_t* __restrict__ zero_a, int64_t n_zero_a, unsigned long long* __restrict__ zero_b, int64_t n_zero_b) {
   __shared__ int64_t smem[32];
-  int64_t* row = data + static_cast<size_t>(blockIdx.y) * n;
-  const int base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
-  int64_t v[kScanItems];
-  int64_t sum = 0;
+  const int tid = threadIdx.x;
+  auto flags_of = [&](int t, int32_t (&b)[kScanItems], int (&f)[kScanItems]) {
+    int sum = 0;
 #pragma unroll
-  for (int k = 0; k < kScanItems; ++k) {
-    v[k] = base + k < n ? row[base + k] : 0;
-    sum += v[k];
-  }
-  int64_t total;
-  int64_t r = block_excl_scan<int64_t>(sum, smem, &total);
+    for (int k = 0; k < kScanItems; ++k) {
+      const int q = t * kScanTile + tid * kScanItems + k;
+      b[k] = q < n_traj ? (order ? order[q] : q) : -1;
+    }
 #pragma unroll
-  for (int k = 0; k < kScanItems; ++k) {
-    if (base + k < n) row[base + k] = r;
-    r += v[k];
+    for (int k = 0; k < kScanItems; ++k) {
+      f[k] = b[k] >= 0 && (!keep || keep[b[k]]) ? 1 : 0;
+      sum += f[k];
+    }
+    return sum;
+  };
+  for (int t = blockIdx.x; t < ntile; t += gridDim.x) {
+    int32_t b[kScanItems];
+    int f[kScanItems];
+    const int64_t total = block_sum<int64_t>(flags_of(t, b, f), smem);
+    if (tid == 0) __hip_atomic_store(part + t, kMark | static_cast<unsigned long long>(total), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  if (threadIdx.x == 0) tile_sum[static_cast<size_t>(blockIdx.y) * ntile + blockIdx.x] = total;
-}
-__global__ void __launch_bounds__(256)
-k_scan_add(int64_t* __restrict__ data, int n, int ntile, const int64_t* __restrict__ tile_off) {
-  int64_t* row = data + static_cast<size_t>(blockIdx.y) * n;
-  const int64_t off = tile_off[static_cast<size_t>(blockIdx.y) * ntile + blockIdx.x];
-  const int base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
+  {
+    const int64_t gtid = static_cast<int64_t>(blockIdx.x) * blockDim.x + tid, gsize = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    for (int64_t i = gtid; i < n_zero_a; i += gsize) zero_a[i] = 0;
+    for (int64_t i = gtid; i < n_zero_b; i += gsize) zero_b[i] = 0ull;
+  }
+  for (int t = blockIdx.x; t < ntile; t += gridDim.x) {
+    int64_t before;
+    const int64_t all = sum_published(part, ntile, t, smem, &before);
+    if (t == 0 && tid == 0) *n_kept = all;
+    int32_t b[kScanItems];
+    int f[kScanItems];
+    const int mine = flags_of(t, b, f);
+    int32_t total;
+    int32_t pos = static_cast<int32_t>(before) + block_excl_scan<int32_t>(mine, reinterpret_cast<int32_t*>(smem), &total);
 #pragma unroll
-  for (int k = 0; k < kScanItems; ++k)
-    if (base + k < n) row[base + k] += off;
-}
-
-// First index i in [0, n) with a[i] >= x (n if none).
-__device__ __forceinline__ int64_t lower_bound_i32(const int32_t* __restrict__ a, int64_t n, int64_t x) {
-  int64_t lo = 0, hi = n;
-  while (lo < hi) {
-    const int64_t mid = (lo + hi) >> 1;
-    if (a[mid] < x) lo = mid + 1; else hi = mid;
+    for (int k = 0; k < kScanItems; ++k) {
+      if (b[k] >= 0) rank[b[k]] = f[k] ? pos : -1;
+      pos += f[k];
+    }
   }
-  return lo;
 }
 
 // Per trajectory run: its model, trajectory and the slice of rowsel that holds its scored rows; written
-// at (model, rank of the trajectory) when the trajectory is kept.
+// at (model, rank of the trajectory) when the trajectory is kept.  Three binary searches per run (the first row at
+// or behind its start, the same for its end, its trajectory) advance in one loop, their loads in flight together.
+// (Wider searches were slower here: the kernel is bound by the number of scattered loads, not by their latency.)
 __global__ void k_run_slices(int n_turns, int n_traj, int n_models, const int64_t* __restrict__ traj_seg_off,
                              const int32_t* __restrict__ model_trajrun_off, const int64_t* __restrict__ model_tok_off,
                              const int64_t* __restrict__ model_rowsel_off, const int32_t* __restrict__ rowsel,
@@ -92,60 +104,85 @@ __global__ void k_run_slices(int n_turns, int n_traj, int n_models, const int64_
   int m = 0;
   while (m + 1 < n_models && model_trajrun_off[m + 1] <= j) ++m;
   const int u = tok_turn[start];
+  const int64_t ra = model_rowsel_off[m], n_m = model_rowsel_off[m + 1] - ra, t0 = model_tok_off[m];
+  const int32_t* __restrict__ rs = rowsel + ra;
   int lo = 0, hi = n_traj;                         // trajectory of turn u: last b with traj_turn_off[b] <= u
-  while (lo < hi) {
+  int64_t lo0 = 0, hi0 = n_m, lo1 = 0, hi1 = n_m;  // first rows at or behind the run's start and its end
+  const int64_t x0 = start - t0, x1 = end - t0;
+  while (lo < hi || lo0 < hi0 || lo1 < hi1) {
     const int mid = (lo + hi + 1) >> 1;
-    if (traj_turn_off[mid] <= u) lo = mid; else hi = mid - 1;
+    const int64_t mid0 = (lo0 + hi0) >> 1, mid1 = (lo1 + hi1) >> 1;
+    const int32_t a = lo < hi ? traj_turn_off[mid] : 0;
+    const int32_t r0 = lo0 < hi0 ? rs[mid0] : 0;
+    const int32_t r1 = lo1 < hi1 ? rs[mid1] : 0;
+    if (lo < hi) { if (a <= u) lo = mid; else hi = mid - 1; }
+    if (lo0 < hi0) { if (r0 < x0) lo0 = mid0 + 1; else hi0 = mid0; }
+    if (lo1 < hi1) { if (r1 < x1) lo1 = mid1 + 1; else hi1 = mid1; }
   }
   const int q = rank[lo];
   if (q < 0) return;
-  const int64_t ra = model_rowsel_off[m], n_m = model_rowsel_off[m + 1] - ra, t0 = model_tok_off[m];
-  const int64_t i0 = lower_bound_i32(rowsel + ra, n_m, start - t0), i1 = lower_bound_i32(rowsel + ra, n_m, end - t0);
-  cnt_mq[static_cast<size_t>(m) * n_traj + q] = i1 - i0;
-  src_mq[static_cast<size_t>(m) * n_traj + q] = ra + i0;
+  cnt_mq[static_cast<size_t>(m) * n_traj + q] = lo1 - lo0;
+  src_mq[static_cast<size_t>(m) * n_traj + q] = ra + lo0;
 }
 
-// In-place exclusive prefix sum of each row of data[nrows][n]; one block per row, 8 entries per thread per round.
-__global__ void __launch_bounds__(1024)
-k_scan_rows(int64_t* __restrict__ data, int n, int64_t* __restrict__ totals) {
+// In-place exclusive prefix sums of the rows of data[n_models][n_traj] (the rows of every model by kept rank), the
+// rows' totals, and mb_off[m][k] = rows before minibatch k of model m: minibatch k starts at the first kept
+// trajectory q with q * n_minibatch / n_kept >= k, i.e. q = ceil(k n_kept / n_minibatch).  Tiles of kScanTile
+// entries of a row; a workgroup publishes the sum of each of its tiles, then places each of them behind the tiles
+// before it in its row and the rows before that.
+__global__ void __launch_bounds__(256)
+k_mb_scan(int n_models, int n_traj, int ntile, int n_minibatch, const int64_t* __restrict__ n_kept_p, int64_t* __restrict__ data,
+          unsigned long long* part, int64_t* __restrict__ totals, int64_t* __restrict__ mb_off) {
   __shared__ int64_t smem[32];
-  int64_t* row = data + static_cast<size_t>(blockIdx.x) * n;
-  int64_t carry = 0;
-  for (int i0 = 0; i0 < n; i0 += blockDim.x * kScanItems) {
-    const int base = i0 + threadIdx.x * kScanItems;
+  __shared__ int64_t s_scan[kScanTile];
+  const int tid = threadIdx.x;
+  const int n_all = n_models * ntile;
+  for (int t = blockIdx.x; t < n_all; t += gridDim.x) {
+    const int64_t* row = data + static_cast<size_t>(t / ntile) * n_traj;
+    const int base = (t % ntile) * kScanTile + tid * kScanItems;
+    int64_t sum = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; ++k) sum += base + k < n_traj ? row[base + k] : 0;
+    const int64_t total = block_sum<int64_t>(sum, smem);
+    if (tid == 0) __hip_atomic_store(part + t, kMark | static_cast<unsigned long long>(total), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  const int64_t n_kept = *n_kept_p;
+  for (int t = blockIdx.x; t < n_all; t += gridDim.x) {
+    const int m = t / ntile, tile0 = (t % ntile) * kScanTile;
+    int64_t before_row, in_row_before, unused;
+    const int64_t row_total = sum_published(part + static_cast<size_t>(m) * ntile, ntile, t % ntile, smem, &in_row_before);
+    (void)sum_published(part, m * ntile, m * ntile, smem, &before_row);   // the rows of the models before m
+    (void)unused;
+    int64_t* row = data + static_cast<size_t>(m) * n_traj;
+    const int base = tile0 + tid * kScanItems;
     int64_t v[kScanItems];
     int64_t sum = 0;
 #pragma unroll
     for (int k = 0; k < kScanItems; ++k) {
-      v[k] = base + k < n ? row[base + k] : 0;
+      v[k] = base + k < n_traj ? row[base + k] : 0;
       sum += v[k];
     }
     int64_t total;
-    int64_t r = carry + block_excl_scan<int64_t>(sum, smem, &total);
+    int64_t r = in_row_before + block_excl_scan<int64_t>(sum, smem, &total);
 #pragma unroll
     for (int k = 0; k < kScanItems; ++k) {
-      if (base + k < n) row[base + k] = r;
+      if (base + k < n_traj) row[base + k] = r;
+      s_scan[tid * kScanItems + k] = r;
       r += v[k];
     }
-    carry += total;
     __syncthreads();
+    if (t % ntile == 0 && tid == 0) totals[m] = row_total;
+    for (int k = tid; k <= n_minibatch; k += blockDim.x) {
+      const int64_t q = (static_cast<int64_t>(k) * n_kept + n_minibatch - 1) / n_minibatch;
+      int64_t* out = mb_off + static_cast<size_t>(m) * (n_minibatch + 1) + k;
+      if (k == n_minibatch || q >= n_kept) {
+        if (t % ntile == 0) *out = before_row + row_total;
+      } else if (q >= tile0 && q < tile0 + kScanTile) {
+        *out = before_row + s_scan[q - tile0];
+      }
+    }
+    __syncthreads();                                // s_scan and smem are the next tile's
   }
-  if (threadIdx.x == 0) totals[blockIdx.x] = carry;
-}
-
-// mb_off[m][k] = rows before minibatch k of model m; minibatch k starts at the first kept trajectory q
-// with q * n_minibatch / n_kept >= k, i.e. q = ceil(k n_kept / n_minibatch).
-__global__ void k_mb_offsets(int n_models, int n_minibatch, int n_traj, const int64_t* __restrict__ n_kept_p,
-                             const int64_t* __restrict__ scan_mq, const int64_t* __restrict__ totals,
-                             int64_t* __restrict__ mb_off) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n_models * (n_minibatch + 1)) return;
-  const int m = i / (n_minibatch + 1), k = i % (n_minibatch + 1);
-  int64_t base = 0;
-  for (int mm = 0; mm < m; ++mm) base += totals[mm];
-  const int64_t n_kept = *n_kept_p;
-  const int64_t q = (static_cast<int64_t>(k) * n_kept + n_minibatch - 1) / n_minibatch;
-  mb_off[i] = base + ((k == n_minibatch || q >= n_kept) ? totals[m] : scan_mq[static_cast<size_t>(m) * n_traj + q]);
 }
 
 // One wavefront per (model, kept trajectory): its rowsel slice goes to its place in mb_rowsel.
@@ -176,32 +213,27 @@ k_mb_copy(int n_models, int n_traj, const int64_t* __restrict__ n_kept_p, const 
   }
 }
 
-__global__ void k_zero_i64(int64_t* __restrict__ p, int64_t n) {
-  int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
-  for (; i < n; i += stride) p[i] = 0;
-}
-
 struct BatchWs {
   int32_t* traj_turn_off;
   int32_t* order;
   uint8_t* keep;
+  unsigned long long* part_q;   // [tiles] kept counts of the tiles of the shuffle; zeros come with the staged copy
   int32_t* rank;
-  int64_t* flag;     // [n_traj] kept flags in shuffled order, scanned in place
   int64_t* n_kept;
-  int64_t* tile_sum; // [n_models][tiles] totals of the scan tiles, scanned in place
+  unsigned long long* part_mq;  // [n_models][tiles] sums of the tiles of cnt_mq
   int64_t* cnt_mq;   // [n_models][n_traj], scanned in place
   int64_t* src_mq;   // [n_models][n_traj]
   int64_t* totals;   // [n_models]
 };
+inline int scan_tiles(int n_traj) { return static_cast<int>(cdiv(n_traj > 0 ? n_traj : 1, kScanTile)); }
 size_t carve_batch(Carver& c, BatchWs& w, int n_traj, int n_models) {
   w.traj_turn_off = c.take<int32_t>(static_cast<size_t>(n_traj) + 1);
   w.order = c.take<int32_t>(n_traj);
   w.keep = c.take<uint8_t>(n_traj);
+  w.part_q = c.take<unsigned long long>(scan_tiles(n_traj));
   w.rank = c.take<int32_t>(n_traj);
-  w.flag = c.take<int64_t>(n_traj);
   w.n_kept = c.take<int64_t>(1);
-  w.tile_sum = c.take<int64_t>(static_cast<size_t>(n_models) * cdiv(n_traj > 0 ? n_traj : 1, kScanTile));
+  w.part_mq = c.take<unsigned long long>(static_cast<size_t>(n_models) * scan_tiles(n_traj));
   w.cnt_mq = c.take<int64_t>(static_cast<size_t>(n_models) * n_traj);
   w.src_mq = c.take<int64_t>(static_cast<size_t>(n_models) * n_traj);
   w.totals = c.take<int64_t>(n_models);
@@ -250,57 +282,41 @@ extern "C" umas_status umas_ready_batch(const umas_streams* s, int32_t n_models,
   BatchWs w;
   carve_batch(c, w, n_traj, n_models);
   // the thin arrays (the first arrays of the workspace, up to rank) go through pinned staging memory in one
-  // asynchronous copy: they have been read when the call returns, and the host does not wait for the stream
+  // asynchronous copy, together with the zeros that the first kernel's tile counts start from: they have been read
+  // when the call returns, and the host does not wait for the stream
   char* const ws_base = static_cast<char*>(workspace);
   const size_t staged_bytes = static_cast<size_t>(reinterpret_cast<char*>(w.rank) - ws_base);
+  const int ntile = scan_tiles(n_traj);
   ThinStage stage;
   umas_status vs = stage.begin(staged_bytes);
   if (vs != UMAS_OK) return vs;
   stage.put(static_cast<size_t>(reinterpret_cast<char*>(w.traj_turn_off) - ws_base), traj_turn_off, (static_cast<size_t>(n_traj) + 1) * sizeof(int32_t));
   stage.put(static_cast<size_t>(reinterpret_cast<char*>(w.order) - ws_base), traj_order, static_cast<size_t>(n_traj) * sizeof(int32_t));
   stage.put(static_cast<size_t>(reinterpret_cast<char*>(w.keep) - ws_base), traj_keep, static_cast<size_t>(n_traj));
+  stage.zero(static_cast<size_t>(reinterpret_cast<char*>(w.part_q) - ws_base), static_cast<size_t>(ntile) * sizeof(unsigned long long));
   vs = stage.flush(workspace, staged_bytes, st);
   if (vs != UMAS_OK) return vs;
   prof_mark(st);
 
+  // workgroups of the two scanning kernels wait for one another's sums: no more of them than the device holds at once
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+    n_cu = 64;
   const int64_t n_mq = static_cast<int64_t>(n_models) * n_traj;
-  hipLaunchKernelGGL(k_zero_i64, dim3(cdiv(n_mq > 0 ? n_mq : 1, 256) < 4096 ? cdiv(n_mq > 0 ? n_mq : 1, 256) : 4096), dim3(256), 0,
-                     st, w.cnt_mq, n_mq);
-  UMAS_LAUNCHED("k_zero_i64");
-  const int ntile = static_cast<int>(cdiv(n_traj > 0 ? n_traj : 1, kScanTile));
-  // exclusive scan of data[rows][n_traj]; totals[r] receives the sum of row r
-  auto scan = [&](int64_t* data, int rows, int64_t* totals) -> umas_status {
-    hipLaunchKernelGGL(k_scan_tiles, dim3(ntile, rows), dim3(256), 0, st, data, n_traj, ntile, w.tile_sum);
-    UMAS_LAUNCHED("k_scan_tiles");
-    hipLaunchKernelGGL(k_scan_rows, dim3(rows), dim3(1024), 0, st, w.tile_sum, ntile, totals);
-    UMAS_LAUNCHED("k_scan_rows");
-    hipLaunchKernelGGL(k_scan_add, dim3(ntile, rows), dim3(256), 0, st, data, n_traj, ntile, w.tile_sum);
-    UMAS_LAUNCHED("k_scan_add");
-    return UMAS_OK;
-  };
   const int32_t* d_order = traj_order ? w.order : nullptr;
   const uint8_t* d_keep = traj_keep ? w.keep : nullptr;
-  if (n_traj > 0) {
-    hipLaunchKernelGGL(k_kept_flags, dim3(cdiv(n_traj, 256)), dim3(256), 0, st, n_traj, d_order, d_keep, w.flag);
-    UMAS_LAUNCHED("k_kept_flags");
-  }
-  umas_status ss = scan(w.flag, 1, w.n_kept);
-  if (ss != UMAS_OK) return ss;
-  if (n_traj > 0) {
-    hipLaunchKernelGGL(k_kept_rank, dim3(cdiv(n_traj, 256)), dim3(256), 0, st, n_traj, d_order, d_keep, w.flag, w.rank);
-    UMAS_LAUNCHED("k_kept_rank");
-  }
+  hipLaunchKernelGGL(k_kept_ranks, dim3(std::min(ntile, kPerCu * n_cu)), dim3(256), 0, st, n_traj, ntile, d_order, d_keep, w.part_q,
+                     w.rank, w.n_kept, w.cnt_mq, n_mq, w.part_mq, static_cast<int64_t>(n_models) * ntile);
+  UMAS_LAUNCHED("k_kept_ranks");
   if (n_turns > 0 && n_traj > 0) {
     hipLaunchKernelGGL(k_run_slices, dim3(cdiv(n_turns, 256)), dim3(256), 0, st, n_turns, n_traj, n_models, s->traj_seg_off,
                        s->model_trajrun_off, s->model_tok_off, s->model_rowsel_off, s->rowsel, s->tok_turn, w.traj_turn_off,
                        w.rank, w.cnt_mq, w.src_mq);
     UMAS_LAUNCHED("k_run_slices");
   }
-  ss = scan(w.cnt_mq, n_models, w.totals);
-  if (ss != UMAS_OK) return ss;
-  hipLaunchKernelGGL(k_mb_offsets, dim3(cdiv(static_cast<size_t>(n_models) * (n_minibatch + 1), 256)), dim3(256), 0, st,
-                     n_models, n_minibatch, n_traj, w.n_kept, w.cnt_mq, w.totals, mb_off);
-  UMAS_LAUNCHED("k_mb_offsets");
+  hipLaunchKernelGGL(k_mb_scan, dim3(std::min(n_models * ntile, kPerCu * n_cu)), dim3(256), 0, st, n_models, n_traj, ntile, n_minibatch,
+                     w.n_kept, w.cnt_mq, w.part_mq, w.totals, mb_off);
+  UMAS_LAUNCHED("k_mb_scan");
   if (n_mq > 0) {
     hipLaunchKernelGGL(k_mb_copy, dim3(cdiv(n_mq, 4)), dim3(256), 0, st, n_models, n_traj, w.n_kept, w.cnt_mq, w.src_mq,
                        w.totals, s->rowsel, mb_rowsel);

@@ -275,7 +275,9 @@ def test_ready_batch_index_work_is_exact():
     ready_case(2, 3, 3)                                            # variable turns, interior masks
     ready_case(3, 5, 4)                                            # two models
     ready_case(4, 3, 5)                                            # long turns, 16 trajectories
-    ready_case(1, 7, 6, n_traj=1000)                               # more trajectories than one scan round
+    ready_case(1, 7, 6, n_traj=1000)
+    ready_case(1, 13, 8, n_traj=9000, tokens_per_turn=6)          # five scan tiles of trajectories, their sums handed over
+    ready_case(3, 6, 9, n_traj=5000, tokens_per_turn=4, models=[(128, 700, "bf16"), (200, 1000, "bf16")])   # the same with two models
     ready_case(2, 40, 7, drop=0.9)                                 # more minibatches than kept trajectories
     # defaults: keep all, identity order, one minibatch = the selection itself
     w = wl.make_workload(3)
