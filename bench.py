@@ -433,7 +433,15 @@ def main():
             ms = event_times_ms(torch, lambda: umas.umas_ppo_loss_fwd_bwd(
                 H, W, ids, st0.rowsel[:n_sel], logp_old, adv_all, st0.tok_role, w.n_roles, w.clip_eps, dW=dW, dH=dH,
                 logp_new=logp_new, stats=stats, workspace=view), 5 if nbytes == ws_min else 10, 1)
-            sizes.append({"workspace": label, "bytes": int(nbytes), "median_ms": statistics.median(ms)})
+            # the same call on the path that recomputes the logits in the backward instead of keeping the numerators
+            # (an entropy coefficient too small to change a bit of the result selects it): the trade in numbers
+            if nbytes == ws_min:
+                rec = None                       # minutes at 256-row chunks: left out
+            else:
+                rec = statistics.median(event_times_ms(torch, lambda: umas.umas_ppo_loss_fwd_bwd(
+                    H, W, ids, st0.rowsel[:n_sel], logp_old, adv_all, st0.tok_role, w.n_roles, w.clip_eps, dW=dW, dH=dH,
+                    logp_new=logp_new, stats=stats, workspace=view, entropy_coef=1e-30), 5, 1))
+            sizes.append({"workspace": label, "bytes": int(nbytes), "median_ms": statistics.median(ms), "recomputing_path_median_ms": rec})
         out["update_call_ms_by_workspace"] = sizes
     out["power_probe"] = power_probe(umas, torch, H, W, ids, rowsel)
     if args.copy_calibration:

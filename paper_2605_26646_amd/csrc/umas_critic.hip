@@ -12,6 +12,8 @@
 // depend on scheduling.
 #include <type_traits>
 
+#include <algorithm>
+
 #include "umas_common.h"
 
 namespace umas {
@@ -20,7 +22,7 @@ namespace {
 constexpr int kVT = 256;                 // threads per workgroup
 constexpr int kVWaves = kVT / kWave;
 constexpr int kMaxKV = 16;               // 16-byte column vectors per lane: d <= 64 * 16 * (8 bf16 | 4 float)
-constexpr int kMaxGrid = 1024;           // workgroups of the row kernel: one resident round at four per CU
+constexpr int kMaxGrid = 1024;           // workgroups of the row kernel at most (the launch takes no more than are resident at once)
 constexpr int kVStat = 4;                // (sum L, clipped rows, sum V, rows)
 
 __device__ __forceinline__ uint16_t f2bf(float x) { return __builtin_bit_cast(uint16_t, static_cast<__bf16>(x)); }
@@ -121,6 +123,7 @@ k_value_rows(const T* __restrict__ H, const T* __restrict__ w, float bias, int d
   const int64_t r_end = r_begin + rows_per_block < n_sel ? r_begin + rows_per_block : n_sel;
 
   uint4 cur[KV], nxt[KV];
+  float vo_next = 0.f, ret_next = 0.f;               // the next row's old value and return come with the row
   auto fetch = [&](int64_t n) {
     const int64_t row = rowsel ? rowsel[n] : n;
 #pragma unroll
@@ -129,12 +132,15 @@ k_value_rows(const T* __restrict__ H, const T* __restrict__ w, float bias, int d
       nxt[k] = make_uint4(0u, 0u, 0u, 0u);
       if (cv < nvec) nxt[k] = *reinterpret_cast<const uint4*>(H + row * d + cv * N);
     }
+    vo_next = value_old[row];
+    ret_next = ret[row];
     return row;
   };
   int64_t n = r_begin + wave;
   int64_t row_next = n < r_end ? fetch(n) : 0;
   for (; n < r_end; n += kVWaves) {
     const int64_t row = row_next;
+    const float vo = vo_next, R = ret_next;
     A dot = 0;
 #pragma unroll
     for (int k = 0; k < KV; ++k) {
@@ -148,7 +154,7 @@ k_value_rows(const T* __restrict__ H, const T* __restrict__ w, float bias, int d
     if (n + kVWaves < r_end) row_next = fetch(n + kVWaves);     // in flight while this row is finished
     dot = wave_sum(dot);
     // the value is a float32 result; loss and gradient are formed from that rounded value
-    const float V = static_cast<float>(dot + static_cast<A>(bias)), vo = value_old[row], R = ret[row];
+    const float V = static_cast<float>(dot + static_cast<A>(bias));
     const float vc = fminf(fmaxf(V, vo - clip_eps), vo + clip_eps);   // V itself inside the range: an exact tie
     const float lu = (V - R) * (V - R), lc = (vc - R) * (vc - R);
     const bool unclipped = lu >= lc;
@@ -255,6 +261,29 @@ unsigned value_grid(int64_t n_sel) {
 }
 int max_d(umas_dtype dt) { return dt == UMAS_BF16 ? kWave * kMaxKV * 8 : kWave * kMaxKV * 4; }
 
+// Workgroups of the row kernel that the device holds at once (the kernel's register use differs with KV): its grid is
+// one resident round, so that no second, partly filled round follows.  Looked up once per instance.
+template <typename T, int K>
+unsigned resident_value_blocks() {
+  static unsigned cached = 0;
+  if (cached) return cached;
+  int dev = 0, n_cu = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+    n_cu = 64;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_value_rows<T, K>, kVT, 0) != hipSuccess || per_cu < 1) per_cu = 1;
+  cached = static_cast<unsigned>(per_cu) * static_cast<unsigned>(n_cu);
+  return cached;
+}
+
+template <typename T>
+unsigned resident_value_blocks_kv(int kv) {
+  if (kv <= 1) return resident_value_blocks<T, 1>();
+  if (kv <= 2) return resident_value_blocks<T, 2>();
+  if (kv <= 4) return resident_value_blocks<T, 4>();
+  if (kv <= 8) return resident_value_blocks<T, 8>();
+  return resident_value_blocks<T, 16>();
+}
+
 template <typename T>
 void launch_value_rows(int kv, unsigned grid, hipStream_t st, const void* H, const void* w, float bias, int d,
                        const int32_t* rowsel, int64_t n_sel, int64_t norm, int64_t rpb, const float* value_old, const float* ret,
@@ -346,7 +375,11 @@ extern "C" umas_status umas_value_loss_fwd_bwd(const void* H, const void* w, flo
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   prof_mark(st);
   const size_t esz = dtype == UMAS_BF16 ? 2 : 4;
-  const unsigned grid = value_grid(n_sel);
+  const int nvec = d / (dtype == UMAS_BF16 ? 8 : 4);
+  const int kv = (nvec + kWave - 1) / kWave;
+  // at most value_grid(n_sel) workgroups (what the workspace is sized for), and no more than are resident at once
+  const unsigned resident = dtype == UMAS_BF16 ? resident_value_blocks_kv<uint16_t>(kv) : resident_value_blocks_kv<float>(kv);
+  const unsigned grid = std::min(value_grid(n_sel), resident);
   const int n_part = static_cast<int>(grid) * kVWaves, n_part2 = static_cast<int>(cdiv(n_part, kReduceGroup));
   Carver c(workspace);
   float* part_dw = c.take<float>(static_cast<size_t>(n_part) * (d + 1));
@@ -368,8 +401,6 @@ extern "C" umas_status umas_value_loss_fwd_bwd(const void* H, const void* w, flo
   }
   if (n_sel > 0) {
     const int64_t rpb = (n_sel + grid - 1) / grid;                 // rows per workgroup; every wavefront writes its partial row
-    const int nvec = d / (dtype == UMAS_BF16 ? 8 : 4);
-    const int kv = (nvec + kWave - 1) / kWave;
     if (dtype == UMAS_BF16)
       launch_value_rows<uint16_t>(kv, grid, st, H, w, bias, d, rowsel, n_sel, norm, rpb, value_old, ret, tok_role, n_roles,
                                   clip_eps_v, value_new, dH, accumulate_dH, part_dw, blk_stats);
