@@ -493,6 +493,40 @@ def test_blocks_of_many_short_segments(seed, max_len, long_every, dense, seg_mod
     P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
 
 
+@pytest.mark.parametrize("n_models,n_traj,seed", [(8, 700, 1), (5, 300, 2), (7, 1100, 3)])
+def test_many_models_and_trajectories(n_models, n_traj, seed):
+    """Up to the largest number of models, twelve roles, and more trajectories than one workgroup of the plan kernel
+    takes (several workgroups place their turns behind one another's totals); then the ready batch on the same streams."""
+    w = wl.make_workload(0)
+    rng = np.random.default_rng(9000 + seed)
+    turns = rng.integers(0, 6, size=n_traj)
+    lens = rng.integers(0, 40, size=int(turns.sum())).astype(np.int64)
+    w.n_traj, w.n_turns, w.n_roles, w.n_models = n_traj, len(lens), 12, n_models
+    w.traj_turn_off = np.concatenate([[0], np.cumsum(turns)]).astype(np.int32)
+    w.turn_role = rng.integers(0, 12, size=w.n_turns).astype(np.int32)
+    w.role_to_model = rng.integers(0, n_models, size=12).astype(np.int32)
+    w.role_to_model[:n_models] = rng.permutation(n_models)       # every model serves some role
+    w.turn_tok_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    w.n_tokens = int(w.turn_tok_off[-1])
+    w.turn_pred_off, w.turn_pred = None, None
+    w.traj_group = (np.arange(n_traj) // 5).astype(np.int32)
+    w.tok_mask = (rng.random(w.n_tokens) < 0.6).astype(np.uint8)
+    w.traj_reward = rng.normal(size=n_traj).astype(np.float32)
+    w.turn_reward = rng.normal(size=w.n_turns).astype(np.float32)
+    w.role_reward = rng.normal(size=n_traj * 12).astype(np.float32)
+    w.value = (0.1 * rng.normal(size=w.n_tokens)).astype(np.float32)
+    kw = dict(seg_mode=1, gamma_turn=0.9, place_mode=wl.PLACE_LAST)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w, **kw)
+    s, adv, ret = P.gpu_front(w, **kw)
+    P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+    keep = (rng.random(n_traj) >= 0.2).astype(np.uint8)
+    order = rng.permutation(n_traj).astype(np.int32)
+    rows_o, off_o = orc.ready_batch(st, w.traj_turn_off, keep, order, 5)
+    rows, off = umas.umas_ready_batch(s, w.traj_turn_off, 5, keep, order)
+    assert np.array_equal(off.cpu().numpy(), off_o), "minibatch offsets differ"
+    assert np.array_equal(rows.cpu().numpy()[:len(rows_o)], rows_o), "minibatch rows differ"
+
+
 @pytest.mark.parametrize("gap", [30, 31, 32, 75])
 def test_steps_between_turns_of_a_run_at_the_limit_of_the_flag_bits(gap):
     """A model's turns `gap` steps apart inside one trajectory: up to 30 the step difference travels in the flag byte,
