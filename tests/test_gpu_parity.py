@@ -527,6 +527,31 @@ def test_many_models_and_trajectories(n_models, n_traj, seed):
     assert np.array_equal(rows.cpu().numpy()[:len(rows_o)], rows_o), "minibatch rows differ"
 
 
+def test_more_trajectories_than_the_plan_kernel_has_threads():
+    """140 000 short trajectories: the plan kernel's workgroups (two per compute unit, 256 trajectories each) take
+    several chunks of trajectories apiece."""
+    w = wl.make_workload(0)
+    rng = np.random.default_rng(31337)
+    n_traj = 140000
+    turns = rng.integers(0, 3, size=n_traj)
+    lens = rng.integers(0, 4, size=int(turns.sum())).astype(np.int64)
+    w.n_traj, w.n_turns, w.n_roles, w.n_models = n_traj, len(lens), 3, 2
+    w.traj_turn_off = np.concatenate([[0], np.cumsum(turns)]).astype(np.int32)
+    w.turn_role = rng.integers(0, 3, size=w.n_turns).astype(np.int32)
+    w.role_to_model = np.array([1, 0, 1], np.int32)
+    w.turn_tok_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    w.n_tokens = int(w.turn_tok_off[-1])
+    w.turn_pred_off, w.turn_pred, w.traj_group = None, None, None
+    w.tok_mask = (rng.random(w.n_tokens) < 0.7).astype(np.uint8)
+    w.traj_reward = rng.normal(size=n_traj).astype(np.float32)
+    w.turn_reward, w.role_reward = None, None
+    w.value = (0.1 * rng.normal(size=w.n_tokens)).astype(np.float32)
+    kw = dict(seg_mode=1, gamma_turn=0.9, place_mode=wl.PLACE_LAST)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w, **kw)
+    s, adv, ret = P.gpu_front(w, **kw)
+    P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+
+
 @pytest.mark.parametrize("gap", [30, 31, 32, 75])
 def test_steps_between_turns_of_a_run_at_the_limit_of_the_flag_bits(gap):
     """A model's turns `gap` steps apart inside one trajectory: up to 30 the step difference travels in the flag byte,
