@@ -509,7 +509,7 @@ def lm_head_backward_entropy(H, W, ids, lse, entropy, g, entropy_coef, n_scored,
 # filtering incomplete trajectories, shuffling and matching the worker group's data-parallel
 # configuration; rewards were aligned with the tokens by place_rewards)
 # --------------------------------------------------------------------------------------
-def ready_batch(streams, traj_turn_off, traj_keep, traj_order, n_minibatch):
+def ready_batch(streams, traj_turn_off, traj_keep, traj_order, n_minibatch, balance_rows=False):
     """Split every model's scored rows into minibatches of whole trajectories.
 
     traj_keep[b] = 0 drops trajectory b (incomplete).  traj_order is the shuffle: a permutation of
@@ -518,6 +518,11 @@ def ready_batch(streams, traj_turn_off, traj_keep, traj_order, n_minibatch):
     q * n_minibatch // n_kept.  For model m and minibatch k the rows are those of the minibatch's
     trajectories, trajectory by trajectory in shuffled order, each trajectory's scored rows in stream
     order (stream-relative positions, as in rowsel).
+    With balance_rows the parts are cut by scored rows instead of by trajectories, per model (worker groups
+    "can receive different amounts of data"; what is matched to the data-parallel configuration is the work):
+    listing a model's rows trajectory by trajectory in shuffled order, T rows in all, the trajectory whose
+    first row is the r-th (from 0) goes to part r * n_minibatch // T, so that every part holds T / n_minibatch
+    rows give or take one trajectory.
     Returns (mb_rowsel int32 [kept scored rows], mb_off int64 [n_models, n_minibatch + 1]):
     minibatch k of model m is mb_rowsel[mb_off[m, k] : mb_off[m, k + 1]].
     """
@@ -537,10 +542,17 @@ def ready_batch(streams, traj_turn_off, traj_keep, traj_order, n_minibatch):
         for row in streams["rowsel"][ra:re]:
             b = turn_traj[int(streams["tok_turn"][a + int(row)])]
             rows_of.setdefault(b, []).append(int(row))
+        part_m = part
+        if balance_rows:
+            total = sum(len(rows_of.get(b, [])) for b in kept)
+            part_m, first_row = {}, 0
+            for b in kept:
+                part_m[b] = (first_row * n_minibatch) // total if total else 0
+                first_row += len(rows_of.get(b, []))
         for k in range(n_minibatch):
             off[m, k] = len(out)
             for b in kept:
-                if part[b] == k:
+                if part_m[b] == k:
                     out.extend(rows_of.get(b, []))
         off[m, n_minibatch] = len(out)
     return np.array(out, dtype=np.int32), off

@@ -297,3 +297,52 @@ def test_ready_batch_partition_properties(seed):
     # everything kept, identity order, one minibatch: the selection itself
     rows1, off1 = orc.ready_batch(st, tto, np.ones(n_traj), np.arange(n_traj), 1)
     assert np.array_equal(rows1, st["rowsel"]) and np.array_equal(off1[:, 0], st["model_rowsel_off"][:-1])
+
+
+def test_ready_batch_balanced_by_rows_hand_example():
+    # 4 trajectories of one turn each with 6, 1, 1, 4 valid tokens, one model, identity order, two parts.
+    # By trajectories: {0, 1} | {2, 3} = 7 + 5 rows.  By rows (T = 12, first rows 0, 6, 7, 8 -> parts 0, 1, 1, 1): {0} | {1, 2, 3}.
+    st = orc.route(1, np.array([0]), np.arange(5), np.zeros(4, np.int32), np.array([0, 6, 7, 8, 12]), np.ones(12, np.uint8))
+    rows, off = orc.ready_batch(st, np.arange(5), np.ones(4), np.arange(4), 2)
+    assert off.tolist() == [[0, 7, 12]]
+    rows_b, off_b = orc.ready_batch(st, np.arange(5), np.ones(4), np.arange(4), 2, balance_rows=True)
+    assert off_b.tolist() == [[0, 6, 12]] and rows_b.tolist() == rows.tolist()
+    # three parts: thresholds ceil(12 k / 3) = 4, 8: first rows 0 | 6, 7 | 8 -> {0} | {1, 2} | {3}
+    _, off_3 = orc.ready_batch(st, np.arange(5), np.ones(4), np.arange(4), 3, balance_rows=True)
+    assert off_3.tolist() == [[0, 6, 8, 12]]
+    # shuffled and filtered: order 3, 1, 0, 2 without trajectory 1 -> rows 4, 6, 1 -> T = 11, first rows 0, 4, 10 -> parts 0, 0, 1
+    rows_s, off_s = orc.ready_batch(st, np.arange(5), np.array([1, 0, 1, 1]), np.array([3, 1, 0, 2]), 2, balance_rows=True)
+    assert off_s.tolist() == [[0, 10, 11]] and rows_s.tolist() == [8, 9, 10, 11, 0, 1, 2, 3, 4, 5, 7]
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
+def test_ready_batch_balanced_by_rows_properties(seed):
+    """The same rows in the same order as the split by trajectories; cuts only between trajectories; part k starts
+    at the first trajectory whose first row is at or behind ceil(k T / M) (the rule stated from the cut's side);
+    every part holds T / M rows give or take the rows of one trajectory."""
+    st, tto, turn_traj = _routed(seed)
+    n_traj = len(tto) - 1
+    rng = np.random.default_rng(200 + seed)
+    keep = (rng.random(n_traj) < 0.8).astype(np.uint8)
+    keep[int(rng.integers(0, n_traj))] = 1
+    order = rng.permutation(n_traj)
+    M = int(rng.integers(2, 6))
+    rows, off = orc.ready_batch(st, tto, keep, order, M)
+    rows_b, off_b = orc.ready_batch(st, tto, keep, order, M, balance_rows=True)
+    assert np.array_equal(rows, rows_b) and np.array_equal(off[:, [0, M]], off_b[:, [0, M]])
+    kept = [b for b in order if keep[b]]
+    for m in range(len(st["model_tok_off"]) - 1):
+        a = int(st["model_tok_off"][m])
+        got = rows_b[off_b[m, 0]:off_b[m, M]]
+        got_traj = [int(turn_traj[st["tok_turn"][a + r]]) for r in got]
+        n_rows = {b: got_traj.count(b) for b in kept}
+        first = np.concatenate([[0], np.cumsum([n_rows[b] for b in kept])])       # first row of every kept trajectory, then T
+        T = int(first[-1])
+        for k in range(M + 1):
+            thr = -(-k * T // M)
+            start = int(np.argmax(first >= thr))                                   # first trajectory at or behind the threshold
+            assert off_b[m, k] - off_b[m, 0] == first[start]
+        if T:
+            sizes = np.diff(off_b[m])
+            biggest = max(n_rows.values())
+            assert sizes.max() <= -(-T // M) + biggest and sizes.min() >= T // M - biggest
