@@ -353,6 +353,18 @@ umas_status umas_ready_batch(const umas_streams* streams, int32_t n_models, int3
                              const int32_t* traj_order, int32_t n_minibatch, int32_t* mb_rowsel,
                              int64_t* mb_off, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same with the parts cut by scored rows instead of by trajectories, per model, for worker groups whose
+ * micro-batches should carry equal work (Section "Model-Local Buffers": batches are built per model, and
+ * "different worker groups can receive different amounts of data"): listing model m's kept rows trajectory by
+ * trajectory in shuffled order, T_m rows in all, the trajectory whose first row is the r-th (from 0) goes to part
+ * r * n_minibatch / T_m; every part then holds T_m / n_minibatch rows give or take one trajectory.  mb_rowsel is
+ * the same list as umas_ready_batch writes; only mb_off differs, and the cuts of different models fall between
+ * different trajectories.  Same arguments, workspace and errors. */
+umas_status umas_ready_batch_balanced(const umas_streams* streams, int32_t n_models, int32_t n_turns,
+                                      const int32_t* traj_turn_off, int32_t n_traj, const uint8_t* traj_keep,
+                                      const int32_t* traj_order, int32_t n_minibatch, int32_t* mb_rowsel,
+                                      int64_t* mb_off, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Kernel timing aid for benchmarks (not part of the method).  While enabled, every kernel launch
  * of the library is followed by a HIP event on its stream and the time between consecutive events
  * of one call is booked to the kernel launched in between.  umas_profile_enable(on) discards earlier

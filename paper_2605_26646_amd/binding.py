@@ -413,14 +413,16 @@ def umas_whiten_advantages(adv, tok_mask, tok_role, model_tok_off, n_roles, scop
     return out
 
 
-def umas_ready_batch(streams: Streams, traj_turn_off, n_minibatch, traj_keep=None, traj_order=None):
-    """Returns (mb_rowsel device int32, mb_off device int64 [n_models, n_minibatch + 1])."""
+def umas_ready_batch(streams: Streams, traj_turn_off, n_minibatch, traj_keep=None, traj_order=None, balance_rows=False):
+    """Returns (mb_rowsel device int32, mb_off device int64 [n_models, n_minibatch + 1]); balance_rows selects
+    umas_ready_batch_balanced (parts cut by scored rows per model instead of by trajectories)."""
     lib = load_library()
     lib.umas_ready_batch_workspace_bytes.restype = C.c_size_t
     lib.umas_ready_batch_workspace_bytes.argtypes = [C.c_int32, C.c_int32]
-    lib.umas_ready_batch.restype = C.c_int
-    lib.umas_ready_batch.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
-                                     C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    fn = lib.umas_ready_batch_balanced if balance_rows else lib.umas_ready_batch
+    fn.restype = C.c_int
+    fn.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                   C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     dev = streams.rowsel.device
     tto_keep, tto = _host(traj_turn_off, np.int32)
     n_traj = len(tto_keep) - 1
@@ -430,9 +432,8 @@ def umas_ready_batch(streams: Streams, traj_turn_off, n_minibatch, traj_keep=Non
     mb_off = torch.empty((streams.n_models, n_minibatch + 1), dtype=torch.int64, device=dev)
     ws = _workspace(lib.umas_ready_batch_workspace_bytes(n_traj, streams.n_models), dev)
     cs = streams._c()
-    _check(lib, lib.umas_ready_batch(C.addressof(cs), streams.n_models, streams.n_turns, tto, n_traj, keep, order,
-                                     n_minibatch, mb_rowsel.data_ptr(), mb_off.data_ptr(), ws.data_ptr(), ws.numel(),
-                                     _stream()))
+    _check(lib, fn(C.addressof(cs), streams.n_models, streams.n_turns, tto, n_traj, keep, order,
+                   n_minibatch, mb_rowsel.data_ptr(), mb_off.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
     return mb_rowsel, mb_off
 
 

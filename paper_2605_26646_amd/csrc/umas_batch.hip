@@ -131,8 +131,8 @@ __global__ void k_run_slices(int n_turns, int n_traj, int n_models, const int64_
 // entries of a row; a workgroup publishes the sum of each of its tiles, then places each of them behind the tiles
 // before it in its row and the rows before that.
 __global__ void __launch_bounds__(256)
-k_mb_scan(int n_models, int n_traj, int ntile, int n_minibatch, const int64_t* __restrict__ n_kept_p, int64_t* __restrict__ data,
-          unsigned long long* part, int64_t* __restrict__ totals, int64_t* __restrict__ mb_off) {
+k_mb_scan(int n_models, int n_traj, int ntile, int n_minibatch, int balance_rows, const int64_t* __restrict__ n_kept_p,
+          int64_t* __restrict__ data, unsigned long long* part, int64_t* __restrict__ totals, int64_t* __restrict__ mb_off) {
   __shared__ int64_t smem[32];
   __shared__ int64_t s_scan[kScanTile];
   const int tid = threadIdx.x;
@@ -173,8 +173,23 @@ k_mb_scan(int n_models, int n_traj, int ntile, int n_minibatch, const int64_t* _
     __syncthreads();
     if (t % ntile == 0 && tid == 0) totals[m] = row_total;
     for (int k = tid; k <= n_minibatch; k += blockDim.x) {
-      const int64_t q = (static_cast<int64_t>(k) * n_kept + n_minibatch - 1) / n_minibatch;
       int64_t* out = mb_off + static_cast<size_t>(m) * (n_minibatch + 1) + k;
+      if (balance_rows) {
+        // cut by rows: part k starts at the first trajectory whose first row is at or behind ceil(k T / M); the tile
+        // whose prefix sums first reach the threshold writes it (the first tile when the threshold is 0)
+        const int64_t thr = (static_cast<int64_t>(k) * row_total + n_minibatch - 1) / n_minibatch;
+        const int len = n_traj - tile0 < kScanTile ? n_traj - tile0 : kScanTile;   // entries of the tile that exist
+        if (thr <= in_row_before ? tile0 == 0 : thr <= in_row_before + total) {
+          int lo = 0, hi = len;                          // first entry of the tile at or above the threshold, len if none
+          while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_scan[mid] < thr) lo = mid + 1; else hi = mid;
+          }
+          *out = before_row + (lo < len ? s_scan[lo] : in_row_before + total);
+        }
+        continue;
+      }
+      const int64_t q = (static_cast<int64_t>(k) * n_kept + n_minibatch - 1) / n_minibatch;
       if (k == n_minibatch || q >= n_kept) {
         if (t % ntile == 0) *out = before_row + row_total;
       } else if (q >= tile0 && q < tile0 + kScanTile) {
@@ -252,10 +267,10 @@ extern "C" size_t umas_ready_batch_workspace_bytes(int32_t n_traj, int32_t n_mod
   return carve_batch(c, w, n_traj, n_models);
 }
 
-extern "C" umas_status umas_ready_batch(const umas_streams* s, int32_t n_models, int32_t n_turns,
-                                        const int32_t* traj_turn_off, int32_t n_traj, const uint8_t* traj_keep,
-                                        const int32_t* traj_order, int32_t n_minibatch, int32_t* mb_rowsel,
-                                        int64_t* mb_off, void* workspace, size_t workspace_bytes, void* hip_stream) {
+namespace {
+umas_status ready_batch(const umas_streams* s, int32_t n_models, int32_t n_turns, const int32_t* traj_turn_off, int32_t n_traj,
+                        const uint8_t* traj_keep, const int32_t* traj_order, int32_t n_minibatch, int balance_rows,
+                        int32_t* mb_rowsel, int64_t* mb_off, void* workspace, size_t workspace_bytes, void* hip_stream) {
   UMAS_REQUIRE(s && s->traj_seg_off && s->model_trajrun_off && s->model_tok_off && s->model_rowsel_off && s->rowsel && s->tok_turn,
                UMAS_EINVAL, "streams lacks traj_seg_off, model_trajrun_off, model_tok_off, model_rowsel_off, rowsel or tok_turn");
   UMAS_REQUIRE(n_models >= 1 && n_models <= UMAS_MAX_MODELS, UMAS_ESHAPE, "n_models=%d outside [1,%d]", n_models, UMAS_MAX_MODELS);
@@ -315,7 +330,7 @@ extern "C" umas_status umas_ready_batch(const umas_streams* s, int32_t n_models,
     UMAS_LAUNCHED("k_run_slices");
   }
   hipLaunchKernelGGL(k_mb_scan, dim3(std::min(n_models * ntile, kPerCu * n_cu)), dim3(256), 0, st, n_models, n_traj, ntile, n_minibatch,
-                     w.n_kept, w.cnt_mq, w.part_mq, w.totals, mb_off);
+                     balance_rows, w.n_kept, w.cnt_mq, w.part_mq, w.totals, mb_off);
   UMAS_LAUNCHED("k_mb_scan");
   if (n_mq > 0) {
     hipLaunchKernelGGL(k_mb_copy, dim3(cdiv(n_mq, 4)), dim3(256), 0, st, n_models, n_traj, w.n_kept, w.cnt_mq, w.src_mq,
@@ -323,4 +338,21 @@ extern "C" umas_status umas_ready_batch(const umas_streams* s, int32_t n_models,
     UMAS_LAUNCHED("k_mb_copy");
   }
   return UMAS_OK;
+}
+}  // namespace
+
+extern "C" umas_status umas_ready_batch(const umas_streams* s, int32_t n_models, int32_t n_turns,
+                                        const int32_t* traj_turn_off, int32_t n_traj, const uint8_t* traj_keep,
+                                        const int32_t* traj_order, int32_t n_minibatch, int32_t* mb_rowsel,
+                                        int64_t* mb_off, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return ready_batch(s, n_models, n_turns, traj_turn_off, n_traj, traj_keep, traj_order, n_minibatch, 0, mb_rowsel, mb_off, workspace,
+                     workspace_bytes, hip_stream);
+}
+
+extern "C" umas_status umas_ready_batch_balanced(const umas_streams* s, int32_t n_models, int32_t n_turns,
+                                                 const int32_t* traj_turn_off, int32_t n_traj, const uint8_t* traj_keep,
+                                                 const int32_t* traj_order, int32_t n_minibatch, int32_t* mb_rowsel,
+                                                 int64_t* mb_off, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return ready_batch(s, n_models, n_turns, traj_turn_off, n_traj, traj_keep, traj_order, n_minibatch, 1, mb_rowsel, mb_off, workspace,
+                     workspace_bytes, hip_stream);
 }

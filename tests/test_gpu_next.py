@@ -255,6 +255,7 @@ def test_kl_loss_term():
 
 
 def ready_case(cfg, n_minibatch, seed, drop=0.25, **kw):
+    """Both cuts of the ready batch (by trajectories, by scored rows) against the oracle, bit for bit."""
     w = wl.make_workload(cfg, **kw)
     rho, st, r, adv_o, ret_o = P.oracle_front(w)
     s, adv, ret = P.gpu_front(w)
@@ -266,6 +267,10 @@ def ready_case(cfg, n_minibatch, seed, drop=0.25, **kw):
     rows, off = umas.umas_ready_batch(s, w.traj_turn_off, n_minibatch, keep, order)
     assert np.array_equal(off.cpu().numpy(), off_o), "minibatch offsets differ"
     assert np.array_equal(rows.cpu().numpy()[:len(rows_o)], rows_o), "minibatch rows differ"
+    rows_bo, off_bo = orc.ready_batch(st, w.traj_turn_off, keep, order, n_minibatch, balance_rows=True)
+    rows_b, off_b = umas.umas_ready_batch(s, w.traj_turn_off, n_minibatch, keep, order, balance_rows=True)
+    assert np.array_equal(off_b.cpu().numpy(), off_bo), "minibatch offsets differ (cut by rows)"
+    assert np.array_equal(rows_b.cpu().numpy()[:len(rows_bo)], rows_bo), "minibatch rows differ (cut by rows)"
     return w, st, s, adv_o, adv, rows, off, off_o, rows_o
 
 
@@ -520,6 +525,9 @@ def test_random_graphs_around_the_update(seed):
     rows, off = umas.umas_ready_batch(s, w.traj_turn_off, n_parts, keep, order)
     assert np.array_equal(off.cpu().numpy(), off_o), "minibatch offsets differ"
     assert np.array_equal(rows.cpu().numpy()[:len(rows_o)], rows_o), "minibatch rows differ"
+    _, off_bo = orc.ready_batch(st, w.traj_turn_off, keep, order, n_parts, balance_rows=True)
+    _, off_b = umas.umas_ready_batch(s, w.traj_turn_off, n_parts, keep, order, balance_rows=True)
+    assert np.array_equal(off_b.cpu().numpy(), off_bo), "minibatch offsets differ (cut by rows)"
     logp = (-3.0 * rng.random(n)).astype(np.float32)
     logp_ref = (logp + 0.1 * rng.normal(size=n)).astype(np.float32)
     r_o, kl_o = orc.kl_penalised_rewards(r, logp, logp_ref, st["tok_mask"], 0.05)
