@@ -147,13 +147,19 @@ def oracle_front(w: wl.Workload, place_mode=None, seg_mode=None, gamma_turn=None
 
 
 def gpu_front(w: wl.Workload, place_mode=None, seg_mode=None, gamma_turn=None, gamma=None, lam=None,
-              zero_value=False):
+              zero_value=False, mask_offset=0):
+    """mask_offset: the global mask is handed over as a view that many bytes into a larger buffer (an address that
+    is not a multiple of four)."""
     place_mode = w.place_mode if place_mode is None else place_mode
     seg_mode = w.seg_mode if seg_mode is None else seg_mode
     gamma_turn = w.gamma_turn if gamma_turn is None else gamma_turn
     gamma = w.gamma if gamma is None else gamma
     lam = w.lam if lam is None else lam
     mask = to_dev(w.tok_mask)
+    if mask_offset:
+        buf = torch.zeros(mask.numel() + mask_offset, dtype=torch.uint8, device=mask.device)
+        buf[mask_offset:] = mask
+        mask = buf[mask_offset:]
     s = umas.umas_assign_token_rewards(
         n_roles=w.n_roles, n_models=w.n_models, role_to_model=w.role_to_model, traj_turn_off=w.traj_turn_off,
         turn_role=w.turn_role, turn_tok_off=w.turn_tok_off, tok_mask_global=mask, turn_pred_off=w.turn_pred_off,

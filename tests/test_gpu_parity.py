@@ -552,6 +552,21 @@ def test_more_trajectories_than_the_plan_kernel_has_threads():
     P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
 
 
+@pytest.mark.parametrize("offset", [1, 2, 3])
+def test_mask_at_an_address_that_is_not_a_multiple_of_four(offset):
+    """The token kernel reads four mask bytes in one load where the address allows it and byte by byte where not."""
+    for seed in (3, 11):
+        w, kw = wl.random_graph(seed)
+        rho, st, r, adv_o, ret_o = P.oracle_front(w, **kw)
+        s, adv, ret = P.gpu_front(w, mask_offset=offset, **kw)
+        P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+    w = _short_segment_graph(21, 100, 24, 13)
+    kw = dict(seg_mode=0, gamma_turn=1.0, place_mode=wl.PLACE_LAST)
+    rho, st, r, adv_o, ret_o = P.oracle_front(w, **kw)
+    s, adv, ret = P.gpu_front(w, mask_offset=offset, **kw)
+    P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
+
+
 @pytest.mark.parametrize("gap", [30, 31, 32, 75])
 def test_steps_between_turns_of_a_run_at_the_limit_of_the_flag_bits(gap):
     """A model's turns `gap` steps apart inside one trajectory: up to 30 the step difference travels in the flag byte,
