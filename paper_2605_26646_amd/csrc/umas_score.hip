@@ -190,40 +190,62 @@ __device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ W, cons
   for (int j = 0; j < C::NI; ++j) {
     const int col = acc_col<C>(j);
     const int64_t n = n0 + col;
-    float m = kMasked;
+    // exponentials of this lane's entries of column j relative to m (log2 domain), their sum s and sum of e z; the
+    // keeping variant stages them as bf16 in this wavefront's LDS region, stored in full lines below
+    float m = kMasked, s = 0.f, t = 0.f;
+    auto column = [&](float ref, auto premultiplied) {
+      const float r2 = ref * kLog2e;
+      s = 0.f;
+      t = 0.f;
 #pragma unroll
-    for (int i = 0; i < C::MI; ++i)
+      for (int i = 0; i < C::MI; ++i) {
+        float e[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) m = fmaxf(m, acc[i][j][r]);
-    // The keeping variant sums relative to the row's reference c_n instead of the lane's maximum (any reference
-    // serves the merge as long as nothing overflows), so the exponentials it sums are the numerators it keeps.
-    // A lane whose maximum lies more than kKeepMaxGap above c_n flags the block and falls back to its maximum;
-    // rows without a valid id (reference NaN) use the maximum too and flag nothing: their row factor is 0.
+        for (int r = 0; r < 4; ++r) {
+          const float z = acc[i][j][r];
+          // without a reference from outside: z - m first, exact 0 where a lane holds nothing but vocabulary tail
+          e[r] = decltype(premultiplied)::value ? __builtin_amdgcn_exp2f(fmaf(z, kLog2e, -r2)) : __builtin_amdgcn_exp2f((z - ref) * kLog2e);
+          s += e[r];
+          t = fmaf(e[r], z, t);
+        }
+        if (keeping) {
+          const uint32_t p01 = pack_bf16x2(e[0], e[1]), p23 = pack_bf16x2(e[2], e[3]);
+          *reinterpret_cast<uint2*>(stage + (j * 16 + (lane & 15)) * kStagePitch + (i * 16 + (lane >> 4) * 4) * 2) =
+              make_uint2(p01, p23);
+        }
+      }
+    };
+    auto lane_max = [&]() {
+      float mx = kMasked;
+#pragma unroll
+      for (int i = 0; i < C::MI; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mx = fmaxf(mx, acc[i][j][r]);
+      return mx;
+    };
     if (keeping) {
+      // The keeping variant sums relative to the row's reference c_n instead of the lane's maximum (any reference
+      // serves the merge as long as nothing overflows), so the exponentials it sums are the numerators it keeps,
+      // and it does not look for the maximum first: a sum beyond 32 e^kKeepMaxGap (or not a number: rows without
+      // a valid id have the reference NaN) shows afterwards that some logit may lie more than kKeepMaxGap above
+      // c_n.  Only then is the column done again the long way, relative to the lane's maximum: a lane whose maximum
+      // does lie that far above c_n flags the block (its dz is recomputed later); rows without a valid id flag
+      // nothing, their row factor is 0.
       const float c = n < mc ? keep.cref[c0 + n] : 1e30f;   // rows past the chunk: every exponential is 0, E = 0
-      const float gap = m - c;
-      over |= gap > kKeepMaxGap;
-      if (gap <= kKeepMaxGap) m = c;
-      else if (m == kMasked) m = 0.f;                       // nothing but vocabulary tail in this lane: exponentials 0 as well
-    }
-    const float m2 = m * kLog2e;
-    float s = 0.f, t = 0.f;
-#pragma unroll
-    for (int i = 0; i < C::MI; ++i) {
-      float e[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float z = acc[i][j][r];
-        // without a reference from outside: z - m first, exact 0 where a lane holds nothing but vocabulary tail
-        e[r] = keeping ? __builtin_amdgcn_exp2f(fmaf(z, kLog2e, -m2)) : __builtin_amdgcn_exp2f((z - m) * kLog2e);
-        s += e[r];
-        t = fmaf(e[r], z, t);
+      m = c;
+      column(c, std::true_type{});
+      constexpr float kSumLimit = 1.6e23f;                   // 32 e^50 = 1.66e23
+      if (!(s < kSumLimit)) {
+        m = lane_max();
+        const float gap = m - c;
+        over |= gap > kKeepMaxGap;
+        if (gap <= kKeepMaxGap) m = c;                       // many large terms, none too large: c serves after all
+        else if (m == kMasked) m = 0.f;                     // nothing but vocabulary tail in this lane: exponentials 0 as well
+        column(m, std::true_type{});
       }
-      if (keeping) {   // staged in this wavefront's LDS region, stored in full lines below
-        const uint32_t p01 = pack_bf16x2(e[0], e[1]), p23 = pack_bf16x2(e[2], e[3]);
-        *reinterpret_cast<uint2*>(stage + (j * 16 + (lane & 15)) * kStagePitch + (i * 16 + (lane >> 4) * 4) * 2) =
-            make_uint2(p01, p23);
-      }
+    } else {
+      m = lane_max();
+      column(m, std::false_type{});
     }
     Part p{m, s, t};
 #pragma unroll
@@ -920,7 +942,16 @@ k_dw_onehot(const uint16_t* __restrict__ H, int d, const int32_t* __restrict__ r
   const int64_t row = rowsel ? rowsel[n] : n;
   const uint16_t* h = H + row * d;
   float* dst = dW + static_cast<int64_t>(ids[row]) * d;
-  for (int j = lane; j < d; j += kWave) unsafeAtomicAdd(dst + j, g * bf2f(h[j]));
+  // 32 columns per lane at a time: all their loads are in flight before the first add goes out
+  constexpr int kBatch = 32;
+  for (int j0 = lane; j0 < d; j0 += kBatch * kWave) {
+    uint16_t v[kBatch];
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k) v[k] = j0 + k * kWave < d ? h[j0 + k * kWave] : 0;
+#pragma unroll
+    for (int k = 0; k < kBatch; ++k)
+      if (j0 + k * kWave < d) unsafeAtomicAdd(dst + j0 + k * kWave, g * bf2f(v[k]));
+  }
 }
 
 // ------------------------------------------------------------------ float32: plain backward
