@@ -31,7 +31,11 @@
  *   - Workspace sizes come from the umas_*_workspace_bytes queries; workspace must be
  *     256-byte aligned.  Passing less than the required size returns UMAS_EWORKSPACE.
  *   - One GPU, one process; calls on different streams may run concurrently only with
- *     disjoint outputs and workspaces.
+ *     disjoint outputs and workspaces.  Some kernels of umas_assign_token_rewards,
+ *     umas_ready_batch and umas_advantages have workgroups that wait for words published by
+ *     their other workgroups; their grids are a fraction of what the device holds at once, so
+ *     two or three such calls fit side by side.  Do not run more of them concurrently when
+ *     each carries more than 65536 trajectories (or segments of more than 16384 tokens).
  */
 #ifndef UMAS_H
 #define UMAS_H

@@ -25,7 +25,8 @@ namespace umas {
 namespace {
 
 constexpr int kPlanThreads = 256;  // trajectories per chunk of the plan kernel
-constexpr int kPlanPerCu = 2;      // its workgroups per compute unit at most: every instance fits twice, so all of them are resident at once
+constexpr int kPlanPerCu = 2;      // its workgroups per compute unit at most (one with more than two models): a fraction of what
+                                   // the device holds at once, so all of them are resident, also next to a second call's
 constexpr int kCnt = 3;            // per model and chunk: turns, tokens, trajectory runs
 constexpr int kPlanWords = UMAS_MAX_MODELS * kCnt;
 constexpr int kTokThreads = 256;
@@ -895,7 +896,7 @@ extern "C" umas_status umas_assign_token_rewards(const umas_graph* g, const umas
   int dev = 0, n_cu = 0;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
     n_cu = 64;
-  const dim3 plan_grid(std::min(n_chunks, kPlanPerCu * n_cu));
+  const dim3 plan_grid(std::min(n_chunks, (K <= 2 ? kPlanPerCu : 1) * n_cu));
   if (K <= 1) hipLaunchKernelGGL(k_turn_plan<1>, plan_grid, dim3(kPlanThreads), 0, st, P);
   else if (K <= 2) hipLaunchKernelGGL(k_turn_plan<2>, plan_grid, dim3(kPlanThreads), 0, st, P);
   else if (K <= 4) hipLaunchKernelGGL(k_turn_plan<4>, plan_grid, dim3(kPlanThreads), 0, st, P);
