@@ -929,28 +929,99 @@ k_gemm_dh_dw(const uint16_t* __restrict__ dZ, int64_t Vp, int64_t mcp, const uin
   }
 }
 
-// One-hot part of dW: dW[y_n, :] += g_n h_n for every selected row, in float32.  Rows that took the
-// same token add into the same dW row, hence atomics; one wavefront per row.
+// One-hot part of dW: dW[y_n, :] += g_n h_n for every selected row, in float32.  Rows that took the same token add
+// into the same dW row, hence atomics - and token frequencies are skewed (a seventh of the rows of a Zipf(1.1) batch
+// took the most frequent token), so adding row by row queues thousands of atomics on the same cache lines.  A
+// workgroup therefore takes kOneHotRows consecutive selected rows and adds them up by token first: the first row of
+// every token in the group is its leader; a wavefront sums the leader and its followers in registers, 2048 columns at
+// a time (16-byte loads, a lane owning eight consecutive columns of each of four pieces), turns every piece through
+// its corner of LDS so that consecutive lanes hold consecutive columns, and issues one atomic per element of the sum.
+constexpr int kOneHotRows = 128;
+constexpr int kOneHotPieces = 4;                    // pieces of 512 columns a wavefront holds at a time
 __global__ void __launch_bounds__(256)
 k_dw_onehot(const uint16_t* __restrict__ H, int d, const int32_t* __restrict__ rowsel, int64_t n_sel,
             const int32_t* __restrict__ ids, const float* __restrict__ g_c, float* __restrict__ dW) {
-  const int lane = threadIdx.x & 63;
-  const int64_t n = static_cast<int64_t>(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave;
-  if (n >= n_sel) return;
-  const float g = g_c[n];
-  if (g == 0.f) return;                      // clipped rows, zero advantage, invalid ids
-  const int64_t row = rowsel ? rowsel[n] : n;
-  const uint16_t* h = H + row * d;
-  float* dst = dW + static_cast<int64_t>(ids[row]) * d;
-  // 32 columns per lane at a time: all their loads are in flight before the first add goes out
-  constexpr int kBatch = 32;
-  for (int j0 = lane; j0 < d; j0 += kBatch * kWave) {
-    uint16_t v[kBatch];
+  __shared__ int32_t s_id[kOneHotRows];             // token of the row, -1 when the row adds nothing
+  __shared__ float s_g[kOneHotRows];
+  __shared__ int64_t s_row[kOneHotRows];
+  __shared__ int32_t s_leader[kOneHotRows];         // the group's leaders, compacted
+  __shared__ int32_t s_n_leader;
+  __shared__ float s_turn[256 / kWave][8 * kWave];  // one piece per wavefront, in column order
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid / kWave;
+  if (tid < kOneHotRows) {
+    const int64_t n = static_cast<int64_t>(blockIdx.x) * kOneHotRows + tid;
+    float g = 0.f;
+    int64_t row = 0;
+    int32_t id = -1;
+    if (n < n_sel) {
+      g = g_c[n];                                  // 0: clipped rows, zero advantage, invalid ids
+      row = rowsel ? rowsel[n] : n;
+      if (g != 0.f) id = ids[row];
+    }
+    s_id[tid] = id; s_g[tid] = g; s_row[tid] = row;
+  }
+  if (tid == 0) s_n_leader = 0;
+  __syncthreads();
+  if (tid < kOneHotRows) {
+    const int32_t id = s_id[tid];
+    bool leader = id >= 0;
+    for (int u = 0; u < tid && leader; ++u) leader = s_id[u] != id;
+    if (leader) s_leader[atomicAdd(&s_n_leader, 1)] = tid;
+  }
+  __syncthreads();
+  const int n_leader = s_n_leader;
+  float* turn = s_turn[wave];
+  for (int li = wave; li < n_leader; li += 256 / kWave) {
+    const int32_t id = s_id[s_leader[li]];
+    float* dst = dW + static_cast<int64_t>(id) * d;
+    unsigned long long same[kOneHotRows / kWave];   // the rows of the group that took this token
 #pragma unroll
-    for (int k = 0; k < kBatch; ++k) v[k] = j0 + k * kWave < d ? h[j0 + k * kWave] : 0;
+    for (int k = 0; k < kOneHotRows / kWave; ++k) same[k] = __ballot(s_id[lane + kWave * k] == id);
+    for (int c0 = 0; c0 < d; c0 += kOneHotPieces * 8 * kWave) {   // d is a multiple of 8: a lane's eight columns are all inside or all outside
+      float acc[kOneHotPieces][8];
 #pragma unroll
-    for (int k = 0; k < kBatch; ++k)
-      if (j0 + k * kWave < d) unsafeAtomicAdd(dst + j0 + k * kWave, g * bf2f(v[k]));
+      for (int q = 0; q < kOneHotPieces; ++q)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[q][k] = 0.f;
+#pragma unroll
+      for (int k = 0; k < kOneHotRows / kWave; ++k) {
+        for (unsigned long long m = same[k]; m; m &= m - 1) {
+          const int u = kWave * k + __ffsll(static_cast<long long>(m)) - 1;
+          const uint16_t* h = H + s_row[u] * d;
+          const float g = s_g[u];
+          uint4 hv[kOneHotPieces];
+#pragma unroll
+          for (int q = 0; q < kOneHotPieces; ++q) {   // the row's pieces are in flight together
+            const int c = c0 + (q * kWave + lane) * 8;
+            hv[q] = c < d ? *reinterpret_cast<const uint4*>(h + c) : make_uint4(0u, 0u, 0u, 0u);
+          }
+#pragma unroll
+          for (int q = 0; q < kOneHotPieces; ++q) {
+            const uint32_t w4[4] = {hv[q].x, hv[q].y, hv[q].z, hv[q].w};
+#pragma unroll
+            for (int k2 = 0; k2 < 4; ++k2) {
+              acc[q][2 * k2] += g * bf2f(static_cast<uint16_t>(w4[k2] & 0xFFFFu));
+              acc[q][2 * k2 + 1] += g * bf2f(static_cast<uint16_t>(w4[k2] >> 16));
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kOneHotPieces; ++q) {
+        const int cq = c0 + q * 8 * kWave;           // first column of the piece
+        if (cq >= d) break;
+        // column cq + 8 lane + k sits in this lane's acc[q][k]; after the turn, lane l adds columns cq + 64 k + l
+        *reinterpret_cast<float4*>(turn + 8 * lane) = make_float4(acc[q][0], acc[q][1], acc[q][2], acc[q][3]);
+        *reinterpret_cast<float4*>(turn + 8 * lane + 4) = make_float4(acc[q][4], acc[q][5], acc[q][6], acc[q][7]);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int c = cq + kWave * k + lane;
+          if (c < d) unsafeAtomicAdd(dst + c, turn[kWave * k + lane]);
+        }
+        __builtin_amdgcn_wave_barrier();
+      }
+    }
   }
 }
 
@@ -1381,7 +1452,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
   UMAS_LAUNCHED("k_ppo_stats");
   if (n_sel == 0) return UMAS_OK;
   if (keep) {
-    hipLaunchKernelGGL(k_dw_onehot, dim3(cdiv(n_sel, 4)), dim3(256), 0, st, Hb, d, rowsel, n_sel, ids, w.g_c, dW);
+    hipLaunchKernelGGL(k_dw_onehot, dim3(cdiv(n_sel, kOneHotRows)), dim3(256), 0, st, Hb, d, rowsel, n_sel, ids, w.g_c, dW);
     UMAS_LAUNCHED("k_dw_onehot");
     return UMAS_OK;
   }
@@ -1427,7 +1498,7 @@ extern "C" umas_status umas_ppo_loss_fwd_bwd(const void* H, const void* W, umas_
                        (accumulate_dW || c0 > 0) ? 1 : 0, rowsel, c0, rows, ids, w.g_c, static_cast<const float*>(nullptr));
     UMAS_LAUNCHED("k_gemm_dh_dw");
   }
-  hipLaunchKernelGGL(k_dw_onehot, dim3(cdiv(n_sel, 4)), dim3(256), 0, st, Hb, d, rowsel, n_sel, ids, w.g_c, dW);
+  hipLaunchKernelGGL(k_dw_onehot, dim3(cdiv(n_sel, kOneHotRows)), dim3(256), 0, st, Hb, d, rowsel, n_sel, ids, w.g_c, dW);
   UMAS_LAUNCHED("k_dw_onehot");
   return UMAS_OK;
 }
