@@ -97,3 +97,65 @@ def test_update_calls_replay_from_a_hip_graph(entropy_coef):
         P.close(got[5].cpu().numpy(), dwv_o, 1e-2, f"replay {k}: dw of the value head")
         vg = umas.read_value_stats(got[8])
         assert abs(float(vg["loss"][0]) - vstats_o[0, 0]) <= 1e-2 * max(abs(vstats_o[0, 0]), 1e-3)
+
+
+def test_scan_and_shaping_calls_replay_from_a_hip_graph():
+    """umas_advantages (with a segment long enough to be cut inside, so that the kernel whose workgroups hand their
+    state over through published maps is part of the graph), umas_kl_rewards and umas_whiten_advantages recorded once
+    and replayed with the values and log-probs changed in place."""
+    w = wl.make_workload(0)
+    rng = np.random.default_rng(77)
+    lens = np.array([40000, 7, 300, 2500, 0, 64], np.int64)
+    w.n_traj, w.n_turns, w.n_roles, w.n_models = 2, len(lens), 2, 1
+    w.traj_turn_off = np.array([0, 3, 6], np.int32)
+    w.turn_role = np.array([0, 1, 0, 1, 1, 0], np.int32)
+    w.role_to_model = np.zeros(2, np.int32)
+    w.turn_tok_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    w.n_tokens = int(w.turn_tok_off[-1])
+    w.turn_pred_off, w.turn_pred, w.traj_group = None, None, None
+    w.tok_mask = (rng.random(w.n_tokens) < 0.8).astype(np.uint8)
+    w.traj_reward = rng.normal(size=2).astype(np.float32)
+    w.turn_reward = rng.normal(size=w.n_turns).astype(np.float32)
+    w.role_reward = None
+    n = w.n_tokens
+    kw = dict(seg_mode=1, gamma_turn=0.9, place_mode=wl.PLACE_ALL, gamma=1.0, lam=0.97)
+    w.value = np.zeros(n, np.float32)
+    rho, st, r, _, _ = P.oracle_front(w, **kw)
+    s, _, _ = P.gpu_front(w, **kw)
+    value_s = torch.zeros(n, dtype=torch.float32, device="cuda")
+    logp_s = torch.zeros(n, dtype=torch.float32, device="cuda")
+    logp_ref_s = torch.zeros(n, dtype=torch.float32, device="cuda")
+    off = s.model_tok_off.cpu().numpy()
+
+    def calls():
+        adv, ret = umas.umas_advantages(s, value_s, 1.0, 0.97, 0.9, 1)
+        r2, kl = umas.umas_kl_rewards(s.tok_reward, logp_s, logp_ref_s, s.tok_mask, 0.05)
+        a2 = umas.umas_whiten_advantages(adv, s.tok_mask, s.tok_role, off, w.n_roles, umas.WHITEN_MODEL_ROLE)
+        return adv, ret, r2, kl, a2
+
+    calls()                                          # once eagerly
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        outs = calls()
+    torch.cuda.synchronize()
+    for k in range(3):
+        value = (0.1 * rng.normal(size=n)).astype(np.float32)
+        logp = (-3.0 * rng.random(n)).astype(np.float32)
+        logp_ref = (logp + 0.1 * rng.normal(size=n)).astype(np.float32)
+        value_s.copy_(P.to_dev(value)); logp_s.copy_(P.to_dev(logp)); logp_ref_s.copy_(P.to_dev(logp_ref))
+        for o in outs:
+            o.fill_(float("nan"))
+        P.gpu_front(w, **kw)                         # eager work of the library between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [o.clone() for o in outs]
+        eager = calls()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("adv", "ret", "penalised rewards", "mean kl", "whitened"), got, eager):
+            assert torch.equal(a, b), f"replay {k}: {name} differs from the eager call"
+        adv_o, ret_o = orc.advantages(st, w.traj_turn_off, r, value, 1.0, 0.97, 0.9, 1)
+        P.close(got[0].cpu().numpy(), adv_o, 1e-5, f"replay {k}: advantages")
+        r_o, kl_o = orc.kl_penalised_rewards(r, logp, logp_ref, st["tok_mask"], 0.05)
+        P.close(got[2].cpu().numpy(), r_o, 1e-5, f"replay {k}: penalised rewards")
