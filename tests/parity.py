@@ -81,14 +81,22 @@ def oracle_dz(H, W, ids, lse, g, rows, entropy=None, k_ent=0.0):
     return dz
 
 
-def bf16_gradient_bounds(H, W, dz, dH_o, dW_o, rows):
+def bf16_gradient_bounds(H, W, dz, dH_o, dW_o, rows, ids=None, lse=None, coef=None, g_slope=None):
     """Element-wise error bounds of the bf16 backward, from its arithmetic.  dz [len(rows), V] is the oracle's
     gradient with respect to the logits of the rows `rows`.  The kernels round the dense part of dz to bf16 once (as
     the kept softmax numerator, or as dz itself), for dW also the scaled hidden state; products are exact in float32
     and sums are accumulated in float32 over K terms; dH is stored as bf16.  With u = 2^-8:
       |dH - dH_o| <= (u + K 2^-23) |dz| |W|  + u |dH_o|
       |dW - dW_o| <= (2u + u^2 + K 2^-23) |dz|^T |H|
-    plus 5 % for the float32 evaluation of the row factors and logits; an absolute floor of 1e-30 keeps exact zeros."""
+    plus 5 % for the float32 evaluation of the row factors and logits; an absolute floor of 1e-30 keeps exact zeros.
+    The taken token's entry dz[n, y] = g (1 - p_y) is formed in float32 from log p_y = z_y - lse, a difference of
+    two float32 numbers: its absolute error 2^-24 (|z_y| + |lse|) times the coefficient (|g|, given as coef per
+    row of the matrix, with ids and lse) does not shrink with 1 - p_y, so for a confident token (p_y within 1e-4 of
+    1) it exceeds the relative bounds above.  It enters row n of dH through W[y] and row y of dW through H[n]; four
+    such errors are allowed (z_y and lse each carry the rounding of their own float32 sums).
+    g_slope (per row of the matrix): |dg/dlogp| of a part of g that can be far larger than g itself - the KL term
+    kl (1 - e^x) / S with x = logp_ref - logp near 0 has slope kl / S - so that the same float32 error of log p_y
+    moves g, and with it the row's whole dz = g (onehot - p), by more than the relative bounds allow."""
     u = BF16_U
     A = np.abs(np.asarray(dz, np.float64))
     Wa = np.abs(np.asarray(W, np.float64))
@@ -97,6 +105,17 @@ def bf16_gradient_bounds(H, W, dz, dH_o, dW_o, rows):
     bound_h = np.zeros_like(np.asarray(dH_o, np.float64))
     bound_h[rows] = 1.05 * ((u + V * 2.0 ** -23) * (A @ Wa) + u * np.abs(np.asarray(dH_o, np.float64)[rows]))
     bound_w = 1.05 * (2 * u + u * u + n * 2.0 ** -23) * (A.T @ Ha)
+    if coef is not None:
+        y = np.asarray(ids)[rows]
+        zy = np.einsum("ij,ij->i", np.asarray(H, np.float64)[rows], np.asarray(W, np.float64)[y])
+        label_abs = 4 * 2.0 ** -24 * (np.abs(zy) + np.abs(np.asarray(lse, np.float64)[rows])) * np.abs(np.asarray(coef, np.float64)[rows])
+        bound_h[rows] += label_abs[:, None] * Wa[y]
+        np.add.at(bound_w, y, label_abs[:, None] * Ha)
+        if g_slope is not None:
+            dlogp = 4 * 2.0 ** -24 * (np.abs(zy) + np.abs(np.asarray(lse, np.float64)[rows]))
+            D = np.abs(oracle_dz(H, W, ids, lse, np.ones(len(np.asarray(lse))), rows)) * (np.abs(np.asarray(g_slope, np.float64)[rows]) * dlogp)[:, None]
+            bound_h[rows] += D @ Wa
+            bound_w += D.T @ Ha
     return bound_h + 1e-30, bound_w + 1e-30
 
 

@@ -280,11 +280,13 @@ def test_dead_blocks_wide_logits_and_invalid_ids_together():
         P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW")
 
 
-@pytest.mark.parametrize("seed", range(32))
+@pytest.mark.parametrize("seed", list(range(32)) + [6007, 6036, 6076, 6086, 6088, 6109, 6157])
 def test_random_small_shapes(seed):
     """Seeded random shapes around the tile edges: hidden sizes that are and are not multiples of the K step and of
     the 256-wide column tile, vocabularies below and above one tile, row counts around one block, a random row
-    selection, some dead rows and blocks, one invalid id, chunked or not, accumulating or not."""
+    selection, some dead rows and blocks, one invalid id, chunked or not, accumulating or not.  The seeds from 6007
+    on are vocabularies of five tokens with rows whose taken token has probability 0.9998 .. 0.9999999: there the
+    float32 difference z_y - lse decides the taken token's entry of dz (see parity.bf16_gradient_bounds)."""
     rng = np.random.default_rng(1000 + seed)
     d = int(rng.choice([8, 64, 72, 128, 200, 264, 320]))
     V = int(rng.choice([5, 255, 256, 257, 700, 1030]))
@@ -332,7 +334,7 @@ def test_random_small_shapes(seed):
     # entry is held to the error bound that follows from the kernels' arithmetic (parity.bf16_gradient_bounds: one
     # bf16 rounding of the dense part of dz, one of the scaled hidden state for dW, one of the stored dH), the
     # arrays as a whole to the 1 % of the other tests.
-    bound_h, bound_w = P.bf16_gradient_bounds(H, W, P.oracle_dz(H, W, ids, lse_o, g_o, good), dH_o, dW_o, good)
+    bound_h, bound_w = P.bf16_gradient_bounds(H, W, P.oracle_dz(H, W, ids, lse_o, g_o, good), dH_o, dW_o, good, ids, lse_o, g_o)
     P.close_bounded(dH_g, dH_o, bound_h, 1e-2, "dH, " + what)
     # an accumulated gradient is compared on what was added to it; the sum was rounded to float32 once more
     if dW0 is not None:
