@@ -7,6 +7,7 @@ fingerprints of the seeded inputs they belong to.  It calls nothing but `oracle/
     python tests/golden/make_fullsize_golden.py 1        # every scored row; about 12 minutes on 8 cores
     python tests/golden/make_fullsize_golden.py 4 4096   # a seeded sample of 4096 scored rows per model
     python tests/golden/make_fullsize_golden.py 4 0 4    # every scored row, four worker processes
+    python tests/golden/make_fullsize_golden.py 4r3 4096 2  # configuration 4 with three fixed rounds (245 760 tokens), a sample
 
 The optional third argument runs the oracle in that many worker processes, each on its own blocks of
 rows (the oracle's element-wise passes are single-threaded; its matrix product is a library call).
@@ -55,9 +56,11 @@ def _score_block(rr):
     return rr, a[rr].astype(np.float32), b[rr].astype(np.float32), c[rr].astype(np.float32)
 
 
-def main(cfg, n_sample=0, procs=1):
+def main(name, n_sample=0, procs=1):
+    """name: a configuration number, or `4r3` for configuration 4 with every trajectory running three rounds."""
     global _T
-    w = wl.make_workload(cfg)
+    cfg = int(name.split("r")[0])
+    w = wl.make_workload(cfg, fixed_rounds=int(name.split("r")[1])) if "r" in name else wl.make_workload(cfg)
     st = orc.route(w.n_models, w.role_to_model, w.traj_turn_off, w.turn_role, w.turn_tok_off, w.tok_mask)
     out = {}
     for m in range(w.n_models):
@@ -90,10 +93,10 @@ def main(cfg, n_sample=0, procs=1):
                 print(f"cfg {cfg} model {m}: {rr[-1]}/{len(rows)} rows, {time.time() - t0:.0f} s", flush=True)
         out[f"logp_{m}"], out[f"lse_{m}"], out[f"entropy_{m}"] = logp, lse, ent
         out[f"fingerprint_{m}"] = fingerprint(t)
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"fullsize_cfg{cfg}.npz")
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"fullsize_cfg{name}.npz")
     np.savez_compressed(path, **out)
     print("wrote", path)
 
 
 if __name__ == "__main__":
-    main(int(sys.argv[1]), int(sys.argv[2]) if len(sys.argv) > 2 else 0, int(sys.argv[3]) if len(sys.argv) > 3 else 1)
+    main(sys.argv[1], int(sys.argv[2]) if len(sys.argv) > 2 else 0, int(sys.argv[3]) if len(sys.argv) > 3 else 1)

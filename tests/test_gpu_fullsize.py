@@ -41,12 +41,12 @@ def spread(idx, n, seed):
     return np.sort(np.concatenate([idx[:e], mid[pick], idx[len(idx) - e:]]))
 
 
-def run_fullsize(cfg):
-    path = os.path.join(GOLDEN, f"fullsize_cfg{cfg}.npz")
+def run_fullsize(cfg, fixed_rounds=None):
+    path = os.path.join(GOLDEN, f"fullsize_cfg{cfg}.npz" if fixed_rounds is None else f"fullsize_cfg{cfg}r{fixed_rounds}.npz")
     if not os.path.exists(path):
         pytest.skip(f"{os.path.basename(path)} has not been generated")
     gold = np.load(path)
-    w = wl.make_workload(cfg)
+    w = wl.make_workload(cfg) if fixed_rounds is None else wl.make_workload(cfg, fixed_rounds=fixed_rounds)
     rho, st, r, adv_o, ret_o = P.oracle_front(w)
     s, adv, ret = P.gpu_front(w)
     P.check_front(w, s, adv, ret, rho, st, r, adv_o, ret_o)
@@ -143,6 +143,13 @@ def run_fullsize(cfg):
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4])
 def test_full_size(cfg):
     run_fullsize(cfg)
+
+
+def test_full_size_cfg4_with_three_fixed_rounds():
+    """The other reading of configuration 4 (every trajectory runs all three rounds: 245 760 tokens, two chunks of the
+    backward at the recommended workspace): routing, rewards and advantages on the whole batch, log-probs, logsumexps
+    and entropies on a stored sample of 4096 rows, dH on 128 of them, dW summing to zero over the vocabulary."""
+    run_fullsize(4, fixed_rounds=3)
 
 
 def test_full_size_single_pass_backward_agrees_with_recomputing_backward():
