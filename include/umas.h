@@ -28,6 +28,12 @@
  *     HIP graph as long as profiling (umas_profile_enable) is off.
  *   - Every call returns a umas_status.  Argument errors are found on the host before any
  *     launch, leave outputs untouched and set a thread-local message (umas_last_error).
+ *     What the host can see is checked: scalars, host arrays, pointers and their alignment.
+ *     The contents of DEVICE arrays are the caller's responsibility: a token id outside [0,V)
+ *     is tolerated (counted, the row contributes nothing) and so is a role outside
+ *     [0, n_roles) (the row or token joins no per-role statistic), but an entry of a row
+ *     selection outside [0, n_rows), or streams that do not come from
+ *     umas_assign_token_rewards, make kernels read or write out of bounds.
  *   - Workspace sizes come from the umas_*_workspace_bytes queries; workspace must be
  *     256-byte aligned.  Passing less than the required size returns UMAS_EWORKSPACE.
  *   - One GPU, one process; calls on different streams may run concurrently only with
@@ -109,6 +115,8 @@ typedef struct {
  * umas_assign_token_rewards).  Stream m is the buffer B_m of the model-local worker group
  * (Section "Model-Local Buffers"): tokens of all turns with phi(role) = m, turns in ascending
  * global id, streams stored back to back.  "model-local order" below means this order.
+ * The arrays of n_tokens entries must be 16-byte aligned (rowsel 4-byte); a stream holds at most
+ * 2^31 - 1 tokens (UMAS_ESHAPE otherwise), n_tokens as a whole may be larger.
  * ------------------------------------------------------------------------------------------ */
 typedef struct {
   int64_t* model_tok_off;     /* [n_models+1]  stream m = positions [off[m], off[m+1]) */

@@ -757,11 +757,17 @@ umas_status validate(const umas_graph* g, const umas_rewards* r, const umas_stre
     UMAS_REQUIRE(g->traj_turn_off[b] <= g->traj_turn_off[b + 1], UMAS_EINVAL, "traj_turn_off decreases at %d", b);
   UMAS_REQUIRE(g->turn_tok_off[0] == 0 && g->turn_tok_off[g->n_turns] == g->n_tokens, UMAS_EINVAL,
                "turn_tok_off must run from 0 to n_tokens");
+  int64_t stream_tokens[UMAS_MAX_MODELS] = {};
   for (int u = 0; u < g->n_turns; ++u) {
     UMAS_REQUIRE(g->turn_tok_off[u] <= g->turn_tok_off[u + 1], UMAS_EINVAL, "turn_tok_off decreases at %d", u);
     UMAS_REQUIRE(g->turn_role[u] >= 0 && g->turn_role[u] < g->n_roles, UMAS_EINVAL,
                  "turn_role[%d]=%d is not a role in [0,%d)", u, g->turn_role[u], g->n_roles);
+    stream_tokens[g->role_to_model[g->turn_role[u]]] += g->turn_tok_off[u + 1] - g->turn_tok_off[u];
   }
+  // rowsel holds positions relative to the stream's start as int32
+  for (int m = 0; m < g->n_models; ++m)
+    UMAS_REQUIRE(stream_tokens[m] <= INT32_MAX, UMAS_ESHAPE, "the stream of model %d would hold %lld tokens, more than 2^31 - 1", m,
+                 static_cast<long long>(stream_tokens[m]));
   if (g->turn_pred_off) {
     UMAS_REQUIRE(g->turn_pred || g->turn_pred_off[g->n_turns] == 0, UMAS_EINVAL, "turn_pred is NULL");
     UMAS_REQUIRE(g->turn_pred_off[0] == 0, UMAS_EINVAL, "turn_pred_off must start at 0");
@@ -785,6 +791,11 @@ umas_status validate(const umas_graph* g, const umas_rewards* r, const umas_stre
                    o->model_trajrun_off && o->rowsel && o->model_rowsel_off && o->turn_scalar && o->turn_step &&
                    o->tok_flags,
                UMAS_EINVAL, "every pointer of the output streams must be set");
+  // the token kernel writes four tokens of every per-token array in one store
+  auto aligned16 = [](const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; };
+  UMAS_REQUIRE(aligned16(o->perm) && aligned16(o->tok_turn) && aligned16(o->tok_role) && aligned16(o->tok_mask) &&
+                   aligned16(o->tok_flags) && aligned16(o->tok_reward),
+               UMAS_EINVAL, "perm, tok_turn, tok_role, tok_mask, tok_flags and tok_reward must be 16-byte aligned");
   return UMAS_OK;
 }
 

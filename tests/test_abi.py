@@ -77,6 +77,8 @@ def graph(**kw):
     (dict(n_models=9, role_to_model=[0, 1]), -2, "n_models"),
     (dict(turn_pred_off=[0, 0, 1], turn_pred=[1]), -1, "predecessor"),
     (dict(traj_group=[-1]), -1, "traj_group"),
+    (dict(turn_tok_off=[0, 2 ** 31 + 5, 2 ** 31 + 9]), -2, "stream of model 0"),
+    (dict(), -1, "16-byte aligned"),          # a well-formed graph: the dummy output pointers (address 1) are what is refused
 ])
 def test_malformed_graphs_are_rejected_before_any_launch(lib, kw, code, needle):
     from paper_2605_26646_amd import binding as b
