@@ -572,3 +572,55 @@ def test_random_graphs_around_the_update(seed):
         # float32 rounding of the values and of the mean divided by the group's deviation
         bound = P.whiten_bounds(a_in, st["tok_mask"], st["tok_role"], st["model_tok_off"], w.n_roles, oscope == orc.WHITEN_MODEL_ROLE)
         P.close_bounded(wh.cpu().numpy(), wh_o, bound + 1e-30, 1e-5, f"whitened advantages, scope {scope}")
+
+
+def test_roles_outside_the_range_join_no_per_role_statistic():
+    """Role ids are device data the host cannot check: a row or token whose role lies outside [0, n_roles) still counts
+    in the model's totals and gradients and joins no role's statistics, in the policy update, the value update and
+    the per-role whitening (where it keeps 0).  The oracle's per-role selections leave such rows out by themselves."""
+    w = wl.make_workload(1, n_traj=6, tokens_per_turn=40, models=[(64, 300, "bf16")])
+    t = w.model_tensors(0)
+    n, R = len(t["ids"]), 3
+    rng = np.random.default_rng(41)
+    role = rng.integers(0, R, n).astype(np.int32)
+    stray = rng.choice(n, 40, replace=False)
+    role[stray] = rng.choice(np.array([-1, -7, R, R + 5, 10 ** 6], np.int32), len(stray))
+    rows = np.arange(n, dtype=np.int32)
+    logp_o, lse_o, ent_o = orc.score(t["H"], t["W"], t["ids"], rows)
+    logp_old = (logp_o + t["noise"]).astype(np.float32)
+    adv = rng.normal(size=n).astype(np.float32)
+    st_o, g_o = orc.ppo_loss(logp_o, logp_old, adv, ent_o, rows, role, R, 0.2)
+    assert st_o[1:, 4].sum() == n - len(stray)
+    H, W = P.to_dev(t["H"], torch.bfloat16), P.to_dev(t["W"], torch.bfloat16)
+    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(H, W, P.to_dev(t["ids"]), None, P.to_dev(logp_old), P.to_dev(adv),
+                                                        P.to_dev(role), R, 0.2)
+    sg = umas.read_stats(stats)
+    for k in range(1 + R):
+        assert int(sg["n_scored"][k]) == int(st_o[k, 4])
+        assert abs(float(sg["loss"][k]) - st_o[k, 0]) <= 1e-2 * max(abs(st_o[k, 0]), float(np.abs(adv).mean()))
+        assert abs(float(sg["entropy_mean"][k]) - st_o[k, 2]) <= 2e-2 and abs(float(sg["approx_kl"][k]) - st_o[k, 3]) <= 2e-2
+    dH_o, dW_o = orc.lm_head_backward(t["H"], t["W"], t["ids"], lse_o, g_o, rows)
+    P.close(dH.float().cpu().numpy(), dH_o, 1e-2, "dH")
+    P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW")
+    # value head
+    wv = (rng.normal(size=64) * 0.1).astype(np.float32)
+    wv_b = torch.from_numpy(wv).bfloat16()
+    V_o = orc.value_head(t["H"], wv_b.float().numpy(), 0.1, rows)
+    v_old = (V_o + 0.05 * rng.normal(size=n)).astype(np.float32)
+    ret = rng.normal(size=n).astype(np.float32)
+    sv_o, gv_o = orc.value_loss(V_o, v_old, ret, rows, role, R, 0.2)
+    stats_v, V_new, dHv, dw, db = umas.umas_value_loss_fwd_bwd(H, wv_b.cuda(), 0.1, None, P.to_dev(v_old), P.to_dev(ret),
+                                                             P.to_dev(role), R, 0.2)
+    sv = umas.read_value_stats(stats_v)
+    for k in range(1 + R):
+        assert int(sv["n_scored"][k]) == int(sv_o[k, 3])
+        assert abs(float(sv["loss"][k]) - sv_o[k, 0]) <= 1e-2 * max(abs(sv_o[k, 0]), 1e-3)
+        assert abs(float(sv["value_mean"][k]) - sv_o[k, 2]) <= 1e-2 * max(abs(sv_o[k, 2]), float(np.abs(V_o).mean()))
+    # whitening per (model, role): the stray tokens keep 0 on both sides
+    mask = (rng.random(n) < 0.8).astype(np.uint8)
+    a_in = rng.normal(size=n).astype(np.float32)
+    off = np.array([0, n], np.int64)
+    wh_o = orc.whiten_advantages(a_in, mask, role, off, R, orc.WHITEN_MODEL_ROLE)
+    wh = umas.umas_whiten_advantages(P.to_dev(a_in), P.to_dev(mask), P.to_dev(role), off, R, umas.WHITEN_MODEL_ROLE).cpu().numpy()
+    assert not wh[stray].any() and not wh_o[stray].any()
+    P.close(wh, wh_o, 1e-5, "whitened advantages")
