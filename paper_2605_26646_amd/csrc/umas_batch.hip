@@ -149,10 +149,9 @@ k_mb_scan(int n_models, int n_traj, int ntile, int n_minibatch, int balance_rows
   const int64_t n_kept = *n_kept_p;
   for (int t = blockIdx.x; t < n_all; t += gridDim.x) {
     const int m = t / ntile, tile0 = (t % ntile) * kScanTile;
-    int64_t before_row, in_row_before, unused;
+    int64_t before_row, in_row_before;
     const int64_t row_total = sum_published(part + static_cast<size_t>(m) * ntile, ntile, t % ntile, smem, &in_row_before);
     (void)sum_published(part, m * ntile, m * ntile, smem, &before_row);   // the rows of the models before m
-    (void)unused;
     int64_t* row = data + static_cast<size_t>(m) * n_traj;
     const int base = tile0 + tid * kScanItems;
     int64_t v[kScanItems];

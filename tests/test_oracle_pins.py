@@ -612,3 +612,56 @@ def test_workload_shapes_follow_the_configurations():
     t = wl.make_workload(1, n_traj=2, models=[(64, 300, "bf16")]).model_tensors(0)
     assert np.array_equal(wl.round_to_bf16(t["H"]), t["H"]) and t["ids"].max() < 300
     assert np.allclose((t["H"].astype(np.float64) ** 2).mean(axis=1), 1.0, atol=2e-2)
+
+
+def test_array_wise_restatement_agrees_with_the_sequential_oracle_on_random_graphs():
+    """tests/arraywise.py states steps a1-a4 with sorts, prefix sums and gathers; the oracle walks turns and tokens
+    one by one.  Two implementations written separately from the same definitions: on seeded random workflow graphs
+    (empty turns and trajectories, models that receive nothing, every mask density, all reward levels) every stream,
+    the flags, the composed and the placed rewards must be identical, and the oracle's advantages must satisfy the
+    recurrence token by token."""
+    from tests import arraywise as aw
+    from tests import parity as P
+    done = 0
+    for seed in range(400):
+        w, kw = wl.random_graph(seed)
+        if w.n_tokens > 20000:
+            continue
+        done += 1
+        rho, st, r, adv_o, ret_o = P.oracle_front(w, **kw)
+        sa = aw.streams(w)
+        n_runs = int(st["model_trajrun_off"][-1])
+        assert sa["n_runs"] == n_runs
+        for f in ("model_tok_off", "perm", "tok_turn", "tok_role", "tok_mask", "turn_seg_off", "seg_turn", "model_turn_off",
+                  "model_trajrun_off", "rowsel", "model_rowsel_off", "traj_seg_off"):
+            assert np.array_equal(sa[f], st[f]), f"seed {seed}: {f}"
+        if w.n_turns:
+            assert np.array_equal(sa["tok_flags"], P.expected_flags(w, st, sa["turn_step"])), f"seed {seed}: flags"
+        rho_a = aw.composed_rewards(w)
+        if w.traj_group is None:
+            assert np.array_equal(rho_a.view(np.uint32), rho.view(np.uint32)), f"seed {seed}: rho"
+        else:
+            assert np.allclose(rho_a, rho, rtol=1e-6, atol=1e-7), f"seed {seed}: rho"
+        r_a = aw.placed_rewards(sa, rho, kw["place_mode"])
+        assert np.array_equal(r_a.view(np.uint32), r.view(np.uint32)), f"seed {seed}: placed rewards"
+        value = w.value
+        worst = aw.recurrence_check(sa, r, value, adv_o, ret_o, kw["gamma"], kw["lam"], kw["gamma_turn"], kw["seg_mode"], tol=1e-12)
+        assert worst <= 1.0, f"seed {seed}: recurrence residual {worst:.3g} x its allowance"
+        # a wrong carry must not pass: the same check with another discount fails wherever something is carried
+        if n_runs and kw["lam"] > 0 and np.abs(adv_o).max() > 0:
+            cur = np.flatnonzero(st["tok_mask"])
+            seg = sa["tok_slot"] if kw["seg_mode"] == wl.SEG_TURN else sa["run_of_slot"][sa["tok_slot"]]
+            carried = (seg[cur[1:]] == seg[cur[:-1]]) & (adv_o[cur[1:]] != 0)
+            if carried.any():
+                assert aw.recurrence_check(sa, r, value, adv_o, ret_o, kw["gamma"], 0.5 * kw["lam"], kw["gamma_turn"], kw["seg_mode"], tol=1e-12) > 1.0
+        # the ready batch, both cuts
+        rng = np.random.default_rng(seed)
+        order = rng.permutation(w.n_traj).astype(np.int32) if rng.random() < 0.8 else None
+        keep = (rng.random(w.n_traj) < 0.8).astype(np.uint8) if rng.random() < 0.8 else None
+        M = int(rng.integers(1, 6))
+        for balanced in (False, True):
+            rows_o, off_o = orc.ready_batch(st, w.traj_turn_off, np.ones(w.n_traj, np.uint8) if keep is None else keep,
+                                            np.arange(w.n_traj) if order is None else order, M, balance_rows=balanced)
+            rows_a, off_a = aw.ready_batch(w, sa, keep, order, M, balanced)
+            assert np.array_equal(rows_a, rows_o) and np.array_equal(off_a, off_o), f"seed {seed}: ready batch, balanced={balanced}"
+    assert done >= 150
