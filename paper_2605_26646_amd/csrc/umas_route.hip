@@ -659,7 +659,7 @@ constexpr int kSelWords = kSelPerThread / 4;
 __global__ void __launch_bounds__(kTokThreads)
 k_rowsel(SelArgs A) {
   __shared__ int64_t smem[32];
-  __shared__ uint16_t s_out[kSelBlock];             // the block's scored positions, block-relative, compacted
+  __shared__ __attribute__((aligned(8))) uint16_t s_out[kSelBlock + 4];   // the block's scored positions, block-relative, compacted
   __shared__ int64_t moff[UMAS_MAX_MODELS + 1];
   __shared__ int32_t s_mro[UMAS_MAX_MODELS + 1];    // scored tokens of the block in front of a stream that starts in it, -1
   const int tid = threadIdx.x;
@@ -694,11 +694,16 @@ k_rowsel(SelArgs A) {
   for (int k = 0; k < kSelWords; ++k) c += __popc(w4[k]);
   int32_t block_count;
   int o = block_excl_scan<int32_t>(c, reinterpret_cast<int32_t*>(smem), &block_count);
+  // The entries leave single up to the first 16-byte boundary of rowsel, four to a store from there; they are staged
+  // `pad` places further on so that every such group of four starts at an 8-byte boundary of s_out.
+  int32_t* const dst = A.rowsel + prefix;
+  const int to_boundary = static_cast<int>((4 - ((reinterpret_cast<uintptr_t>(dst) >> 2) & 3)) & 3);
+  const int pad = (4 - to_boundary) & 3;
   // a stream may start inside the block: the scored tokens in front of its first token give its place in rowsel
   const int e = o;
 #pragma unroll
   for (int k = 0; k < kSelPerThread; ++k)
-    if ((w4[k >> 2] >> (8 * (k & 3))) & 1u) s_out[o++] = static_cast<uint16_t>(tid * kSelPerThread + k);
+    if ((w4[k >> 2] >> (8 * (k & 3))) & 1u) s_out[pad + o++] = static_cast<uint16_t>(tid * kSelPerThread + k);
   for (int j = 0; j <= A.n_models; ++j) {
     const int64_t q = moff[j] - p0;
     if (q >= 0 && q < kSelPerThread && moff[j] < A.n_tokens) {
@@ -714,20 +719,25 @@ k_rowsel(SelArgs A) {
   int m0 = 0;                                        // the stream of the block's first token
   while (m0 < A.n_models && moff[m0 + 1] <= blk0) ++m0;
   auto entry = [&](int i) -> int32_t {               // compacted entry i of the block, stream-relative
-    const int64_t p = blk0 + s_out[i];
+    const int64_t p = blk0 + s_out[pad + i];
     int m = m0;
     while (m < A.n_models && moff[m + 1] <= p) ++m;
     return static_cast<int32_t>(p - moff[m]);
   };
-  // coalesced: single entries up to the first 16-byte boundary of rowsel, four at a time from there, single ones at the end
-  int32_t* const dst = A.rowsel + prefix;
-  const int to_boundary = static_cast<int>((4 - ((reinterpret_cast<uintptr_t>(dst) >> 2) & 3)) & 3);
+  const bool one_stream = moff[m0 + 1] >= blk_end;   // the usual case: every entry is relative to the same start
+  const int32_t rel0 = static_cast<int32_t>(blk0 - moff[m0]);
   const int head = to_boundary < block_count ? to_boundary : block_count;
   const int n_vec = (block_count - head) / 4;
   if (tid < head) dst[tid] = entry(tid);
   for (int v = tid; v < n_vec; v += kTokThreads) {
     const int i = head + 4 * v;
-    *reinterpret_cast<int4*>(dst + i) = make_int4(entry(i), entry(i + 1), entry(i + 2), entry(i + 3));
+    if (one_stream) {
+      const uint2 q = *reinterpret_cast<const uint2*>(s_out + pad + i);
+      *reinterpret_cast<int4*>(dst + i) = make_int4(rel0 + static_cast<int32_t>(q.x & 0xffffu), rel0 + static_cast<int32_t>(q.x >> 16),
+                                                   rel0 + static_cast<int32_t>(q.y & 0xffffu), rel0 + static_cast<int32_t>(q.y >> 16));
+    } else {
+      *reinterpret_cast<int4*>(dst + i) = make_int4(entry(i), entry(i + 1), entry(i + 2), entry(i + 3));
+    }
   }
   {
     const int i = head + 4 * n_vec + tid;
