@@ -161,14 +161,16 @@ def test_full_size_single_pass_backward_agrees_with_recomputing_backward():
     s, adv, ret = P.gpu_front(w)
     spec = w.models[0]
     t = w.model_tensors(0)
-    n_sel = int(s.rowsel.numel())
+    n_sel = int(s.model_rowsel_off[-1].item())           # rowsel is allocated for every token; only the scored ones are written
+    assert n_sel == int(w.tok_mask.sum())
+    rowsel = s.rowsel[:n_sel]
     H, W, ids = P.to_dev(t["H"], torch.bfloat16), P.to_dev(t["W"], torch.bfloat16), P.to_dev(t["ids"])
-    logp, _, _ = umas.umas_policy_logprobs(H, W, ids, s.rowsel)
+    logp, _, _ = umas.umas_policy_logprobs(H, W, ids, rowsel)
     logp_old = logp + P.to_dev(t["noise"].astype(np.float32))
     ws = torch.empty(umas.ppo_workspace_bytes(n_sel, spec.d, spec.V, torch.bfloat16, w.n_roles), dtype=torch.uint8, device="cuda")
     out = []
     for coef in (0.0, 1e-30):
-        stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(H, W, ids, s.rowsel, logp_old, adv, s.tok_role, w.n_roles,
+        stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv, s.tok_role, w.n_roles,
                                                             w.clip_eps, entropy_coef=coef, workspace=ws)
         torch.cuda.synchronize()
         out.append((umas.read_stats(stats), logp_new.cpu().numpy(), dH.float().cpu().numpy(), dW.cpu().numpy()))
@@ -177,7 +179,7 @@ def test_full_size_single_pass_backward_agrees_with_recomputing_backward():
     # over the chunks, everything else is per row
     part = umas.ppo_workspace_bytes((n_sel + 2) // 3, spec.d, spec.V, torch.bfloat16, w.n_roles)
     assert umas.ppo_workspace_bytes(n_sel, spec.d, spec.V, torch.bfloat16, w.n_roles, minimum=True) < part < ws.numel() // 2
-    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(H, W, ids, s.rowsel, logp_old, adv, s.tok_role, w.n_roles,
+    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv, s.tok_role, w.n_roles,
                                                         w.clip_eps, workspace=ws[:part])
     torch.cuda.synchronize()
     sc_, lc, dHc, dWc = umas.read_stats(stats), logp_new.cpu().numpy(), dH.float().cpu().numpy(), dW.cpu().numpy()
