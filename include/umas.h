@@ -179,7 +179,8 @@ size_t umas_policy_logprobs_workspace_bytes(int64_t n_sel, int32_t d, int32_t V,
  * paragraph "Advantage computation and policy evaluation").  Logits are never written out.
  *   H       DEVICE [n_rows, d] row-major, dtype;  W  DEVICE [V, d] row-major, dtype
  *   ids     DEVICE int32 [n_rows]; a row whose id is outside [0,V) gets logp = entropy = 0
- *   rowsel  DEVICE int32 [n_sel] ascending rows to score, or NULL with n_sel = n_rows (all)
+ *   rowsel  DEVICE int32 [n_sel] rows to score, distinct, each in [0, n_rows), in any order (ascending as
+ *           umas_assign_token_rewards writes them, or a part of a ready batch); NULL with n_sel = n_rows = all
  *   logp, lse, entropy  DEVICE float [n_rows]; rows not selected are set to 0; entropy may be NULL
  * bf16 needs d % 8 == 0. */
 umas_status umas_policy_logprobs(const void* H, const void* W, umas_dtype dtype, int64_t n_rows,

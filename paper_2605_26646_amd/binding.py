@@ -165,6 +165,21 @@ def _stream():
     return torch.cuda.current_stream().cuda_stream
 
 
+# Row selections are device data that the library cannot check.  With CHECK_ROWS on (the test suite switches it on)
+# every call that takes one first reads its range back and refuses entries outside [0, n_rows): a mistake in a caller
+# then raises here instead of sending a kernel out of bounds.  It waits for the stream, so it stays off by default
+# and is skipped under graph capture.
+CHECK_ROWS = False
+
+
+def _check_rows(rowsel: Optional[torch.Tensor], n_rows: int):
+    if not CHECK_ROWS or rowsel is None or rowsel.numel() == 0 or torch.cuda.is_current_stream_capturing():
+        return
+    lo, hi = int(rowsel.min().item()), int(rowsel.max().item())
+    if lo < 0 or hi >= n_rows:
+        raise UmasError(-1, f"row selection holds entries from {lo} to {hi}, outside [0, {n_rows})")
+
+
 def _workspace(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
@@ -245,6 +260,7 @@ def umas_policy_logprobs(H: torch.Tensor, W: torch.Tensor, ids: torch.Tensor, ro
     lse = torch.empty(n_rows, dtype=torch.float32, device=dev)
     ent = torch.empty(n_rows, dtype=torch.float32, device=dev) if want_entropy else None
     ws = workspace if workspace is not None else _workspace(lib.umas_policy_logprobs_workspace_bytes(n_sel, d, V, dt), dev)
+    _check_rows(rowsel, n_rows)
     _keep, sel = _sel_ptr(rowsel)
     _check(lib, lib.umas_policy_logprobs(H.data_ptr(), W.data_ptr(), dt, n_rows, d, V, ids.data_ptr(), sel,
                                          n_sel, logp.data_ptr(), lse.data_ptr(), _ptr(ent), ws.data_ptr(), ws.numel(),
@@ -274,6 +290,7 @@ def umas_policy_logprobs_static(H: torch.Tensor, W: torch.Tensor, ids: torch.Ten
         lse = torch.empty(n_rows, dtype=torch.float32, device=dev)
     if entropy is None:
         entropy = torch.empty(n_rows, dtype=torch.float32, device=dev)
+    _check_rows(rowsel, n_rows)
     _keep, sel = _sel_ptr(rowsel)
     _check(lib, lib.umas_policy_logprobs_static(H.data_ptr(), W.data_ptr(), _dtype_code(H), n_rows, d, V, ids.data_ptr(),
                                                 sel, n_sel, logp.data_ptr(), lse.data_ptr(), entropy.data_ptr(), _stream()))
@@ -306,6 +323,7 @@ def umas_ppo_loss_fwd_bwd(H, W, ids, rowsel, logp_old, adv, tok_role, n_roles, c
         stats = torch.empty((1 + n_roles) * STATS_DTYPE.itemsize, dtype=torch.uint8, device=dev)
     ws = workspace if workspace is not None else _workspace(
         lib.umas_ppo_loss_workspace_bytes(n_sel, d, V, dt, n_roles), dev)
+    _check_rows(rowsel, n_rows)
     _keep, sel = _sel_ptr(rowsel)
     _check(lib, lib.umas_ppo_loss_fwd_bwd(H.data_ptr(), W.data_ptr(), dt, n_rows, d, V, ids.data_ptr(), sel,
                                           n_sel, _ptr(logp_old), adv.data_ptr(), _ptr(tok_role), n_roles,
@@ -329,6 +347,7 @@ def umas_values(H, w, bias=0.0, rowsel=None, value=None):
     n_sel = n_rows if rowsel is None else int(rowsel.numel())
     if value is None:
         value = torch.empty(n_rows, dtype=torch.float32, device=H.device)
+    _check_rows(rowsel, n_rows)
     _keep, sel = _sel_ptr(rowsel)
     _check(lib, lib.umas_values(_ptr(H), w.data_ptr(), bias, _dtype_code(H), n_rows, d, sel, n_sel, _ptr(value), _stream()))
     return value
@@ -360,6 +379,7 @@ def umas_value_loss_fwd_bwd(H, w, bias, rowsel, value_old, ret, tok_role, n_role
     if stats is None:
         stats = torch.empty((1 + n_roles) * VALUE_STATS_DTYPE.itemsize, dtype=torch.uint8, device=dev)
     ws = workspace if workspace is not None else _workspace(lib.umas_value_workspace_bytes(n_sel, d, dt, n_roles), dev)
+    _check_rows(rowsel, n_rows)
     _keep, sel = _sel_ptr(rowsel)
     _check(lib, lib.umas_value_loss_fwd_bwd(_ptr(H), w.data_ptr(), bias, dt, n_rows, d, sel, n_sel, _ptr(value_old),
                                             _ptr(ret), _ptr(tok_role), n_roles, clip_eps_v, 1 if accumulate_dH else 0,

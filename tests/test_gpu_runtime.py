@@ -130,3 +130,24 @@ def test_results_do_not_depend_on_scheduling():
         # a frequent token's row of dW is a float32 sum of hundreds of one-hot terms in arrival order: up to about
         # sqrt(terms) 2^-24 of their magnitudes apart between runs, two orders of magnitude inside the gradient bar
         P.close(dW2.cpu().numpy(), dW1.cpu().numpy().astype(np.float64), 1e-4, "dW of the second run against the first")
+
+
+def test_binding_refuses_a_row_selection_out_of_range():
+    """Row selections are device data the library cannot check; the binding's optional check (on for the tests)
+    reads the range back and raises before anything is launched."""
+    from paper_2605_26646_amd import binding
+    assert binding.CHECK_ROWS
+    H = torch.zeros((8, 64), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((300, 64), dtype=torch.bfloat16, device="cuda")
+    ids = torch.zeros(8, dtype=torch.int32, device="cuda")
+    z = torch.zeros(8, device="cuda")
+    for bad in ([0, 3, 8], [-1, 2]):
+        sel = torch.tensor(bad, dtype=torch.int32, device="cuda")
+        with pytest.raises(umas.UmasError, match="outside"):
+            umas.umas_policy_logprobs(H, W, ids, sel)
+        with pytest.raises(umas.UmasError, match="outside"):
+            umas.umas_ppo_loss_fwd_bwd(H, W, ids, sel, z, z, None, 0, 0.2)
+        with pytest.raises(umas.UmasError, match="outside"):
+            umas.umas_values(H, torch.ones(64, dtype=torch.bfloat16, device="cuda"), 0.0, sel)
+        with pytest.raises(umas.UmasError, match="outside"):
+            umas.umas_value_loss_fwd_bwd(H, torch.ones(64, dtype=torch.bfloat16, device="cuda"), 0.0, sel, z, z, None, 0, 0.2)
