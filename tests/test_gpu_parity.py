@@ -665,3 +665,34 @@ def test_on_policy_update_without_old_logprobs(dtype):
     assert abs(float(sg["loss"][0]) - st_o[0, 0]) <= tol * max(abs(st_o[0, 0]), term)
     P.close(dH.float().cpu().numpy(), dH_o, tol, "dH")
     P.close(dW.cpu().numpy(), dW_o, tol, "dW")
+
+
+def test_row_selections_in_any_order():
+    """A row selection need not be ascending (a part of a ready batch lists its rows trajectory by trajectory in
+    shuffled order): scoring and the update give every row the same results as with the ascending selection, up to
+    the last float32 bits (about one row in a hundred differs by one or two units in the last place, depending on
+    where in its tile it sits) and one bf16 rounding of dH; dW, a sum over the rows, is added up in another order."""
+    w = wl.make_workload(1, n_traj=5, tokens_per_turn=60, models=[(128, 1000, "bf16")])
+    t = w.model_tensors(0)
+    n = len(t["ids"])
+    rng = np.random.default_rng(9)
+    rows = np.sort(rng.choice(n, 700, replace=False)).astype(np.int32)
+    shuffled = rng.permutation(rows).astype(np.int32)
+    H, W, ids = P.to_dev(t["H"], torch.bfloat16), P.to_dev(t["W"], torch.bfloat16), P.to_dev(t["ids"])
+    a = umas.umas_policy_logprobs(H, W, ids, P.to_dev(rows))
+    b = umas.umas_policy_logprobs(H, W, ids, P.to_dev(shuffled))
+    for x, y in zip(a, b):
+        assert float((x - y).abs().max()) <= 4e-6          # values around 7: a few units in the last place
+        assert torch.equal(x == 0, y == 0)
+    logp_old = a[0] + P.to_dev(t["noise"].astype(np.float32))
+    adv = P.to_dev(rng.normal(size=n).astype(np.float32))
+    role = P.to_dev(rng.integers(0, 3, n).astype(np.int32))
+    sa, la, dHa, dWa = umas.umas_ppo_loss_fwd_bwd(H, W, ids, P.to_dev(rows), logp_old, adv, role, 3, 0.2)
+    sb, lb, dHb, dWb = umas.umas_ppo_loss_fwd_bwd(H, W, ids, P.to_dev(shuffled), logp_old, adv, role, 3, 0.2)
+    assert float((la - lb).abs().max()) <= 4e-6
+    P.close(dHb.float().cpu().numpy(), dHa.float().cpu().numpy().astype(np.float64), 1e-2, "dH, shuffled against ascending rows")
+    assert float((dHa.float() != dHb.float()).float().mean()) < 0.05
+    ga, gb = umas.read_stats(sa), umas.read_stats(sb)
+    assert np.array_equal(ga["n_scored"], gb["n_scored"])
+    assert np.allclose(ga["loss"], gb["loss"], rtol=1e-5, atol=1e-7)
+    P.close(dWb.cpu().numpy(), dWa.cpu().numpy().astype(np.float64), 1e-3, "dW, shuffled against ascending rows")
