@@ -95,6 +95,33 @@ def test_front_end_on_big_random_multi_model_graphs(seed, n_models, n_roles, pla
     check_ready_batch_arraywise(w, s, aw.streams(w), keep, order, 8)
 
 
+def test_front_end_on_many_random_graphs():
+    """400 small random workflow graphs (workloads.random_graph) and 40 of up to 700 trajectories on up to 8 models
+    and 19 roles: streams, flags, rewards, advantages and both cuts of the ready batch against the array-wise
+    restatement.  (The same loop has been run over 60 000 and 1500 of them.)"""
+    for seed in range(50000, 50400):
+        w, kw = wl.random_graph(seed)
+        s, adv, ret = P.gpu_front(w, **kw)
+        sa = check_front_arraywise(w, s, adv, ret, kw["place_mode"], kw["seg_mode"], kw["gamma"], kw["lam"], kw["gamma_turn"])
+        rng = np.random.default_rng(seed)
+        check_ready_batch_arraywise(w, s, sa, (rng.random(w.n_traj) < 0.8).astype(np.uint8), rng.permutation(w.n_traj).astype(np.int32),
+                                    int(rng.integers(1, 6)))
+    for seed in range(40):
+        rng = np.random.default_rng([77, seed])
+        K, R = int(rng.integers(1, 9)), int(rng.integers(1, 20))
+        w = big_random_graph(1000 + seed, int(rng.integers(1, 700)), K, R)
+        if rng.random() < 0.3:
+            w.traj_group = None
+        if rng.random() < 0.3:
+            w.value = None
+        kw = dict(seg_mode=int(rng.integers(0, 2)), gamma_turn=float(rng.choice([1.0, 0.8])), place_mode=int(rng.integers(0, 2)),
+                  gamma=float(rng.choice([1.0, 0.97])), lam=float(rng.choice([1.0, 0.9])))
+        s, adv, ret = P.gpu_front(w, **kw)
+        sa = check_front_arraywise(w, s, adv, ret, kw["place_mode"], kw["seg_mode"], kw["gamma"], kw["lam"], kw["gamma_turn"])
+        check_ready_batch_arraywise(w, s, sa, (rng.random(w.n_traj) < 0.8).astype(np.uint8), rng.permutation(w.n_traj).astype(np.int32),
+                                    int(rng.integers(1, 9)))
+
+
 def check_ready_batch_arraywise(w, s, sa, keep, order, M):
     for balanced in (False, True):
         want_rows, want_off = aw.ready_batch(w, sa, keep, order, M, balanced)
