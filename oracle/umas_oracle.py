@@ -556,3 +556,46 @@ def ready_batch(streams, traj_turn_off, traj_keep, traj_order, n_minibatch, bala
                     out.extend(rows_of.get(b, []))
         off[m, n_minibatch] = len(out)
     return np.array(out, dtype=np.int32), off
+
+
+def ready_batch_packed(streams, traj_turn_off, traj_keep, traj_order, max_rows):
+    """The ready batch cut into micro-batches under a budget of scored rows (sequence packing: whole sequences
+    laid end to end in a flat batch until it is full; the paper says only that batches are matched to the worker
+    group's configuration).  Per model, going through the kept trajectories in shuffled order: a trajectory's rows
+    join the open part unless that part already holds rows and would then hold more than max_rows, in which case
+    the part is closed and the trajectory opens the next one.  Trajectories are never split, so a trajectory with
+    more than max_rows rows has a part to itself; trajectories without rows in the model open or close nothing,
+    so no part is empty.  The rows and their order are those of ready_batch.
+    Returns (mb_rowsel int32, mb_off int64 [n_models, n_traj + 1], n_parts int32 [n_models]): part k < n_parts[m]
+    of model m is mb_rowsel[mb_off[m, k] : mb_off[m, k + 1]]; the entries past n_parts[m] repeat the model's end."""
+    n_traj = len(traj_turn_off) - 1
+    n_models = len(streams["model_tok_off"]) - 1
+    turn_traj = {}
+    for b in range(n_traj):
+        for u in range(int(traj_turn_off[b]), int(traj_turn_off[b + 1])):
+            turn_traj[u] = b
+    kept = [int(b) for b in traj_order if traj_keep[int(b)]]
+    out = []
+    off = np.zeros((n_models, n_traj + 1), dtype=np.int64)
+    n_parts = np.zeros(n_models, dtype=np.int32)
+    for m in range(n_models):
+        a = int(streams["model_tok_off"][m])
+        ra, re = int(streams["model_rowsel_off"][m]), int(streams["model_rowsel_off"][m + 1])
+        rows_of = {}
+        for row in streams["rowsel"][ra:re]:
+            rows_of.setdefault(turn_traj[int(streams["tok_turn"][a + int(row)])], []).append(int(row))
+        starts, in_part = [len(out)], 0
+        for b in kept:
+            mine = rows_of.get(b, [])
+            if not mine:
+                continue
+            if in_part > 0 and in_part + len(mine) > max_rows:
+                starts.append(len(out))
+                in_part = 0
+            out.extend(mine)
+            in_part += len(mine)
+        k = len(starts) if in_part > 0 else 0          # no rows at all: no part
+        n_parts[m] = k
+        off[m, :] = len(out)
+        off[m, :len(starts)] = starts
+    return np.array(out, dtype=np.int32), off, n_parts

@@ -346,3 +346,69 @@ def test_ready_batch_balanced_by_rows_properties(seed):
             sizes = np.diff(off_b[m])
             biggest = max(n_rows.values())
             assert sizes.max() <= -(-T // M) + biggest and sizes.min() >= T // M - biggest
+
+
+def test_ready_batch_packed_hand_example():
+    # 5 trajectories of one turn each with 3, 2, 4, 1, 2 valid tokens, one model, identity order, budget 5:
+    # 3 + 2 = 5 fits | 4 + 1 = 5 fits | 2 -> parts of 5, 5, 2 rows.  Budget 4: 3 | 2 | 4 | 1 + 2.  Budget 3: 3 | 2 | 4 alone
+    # (more than the budget, never split) | 1 + 2.
+    tto = np.arange(6)
+    st = orc.route(1, np.array([0]), tto, np.zeros(5, np.int32), np.array([0, 3, 5, 9, 10, 12]), np.ones(12, np.uint8))
+    rows, off, n = orc.ready_batch_packed(st, tto, np.ones(5), np.arange(5), 5)
+    assert rows.tolist() == list(range(12)) and n.tolist() == [3] and off.tolist() == [[0, 5, 10, 12, 12, 12]]
+    _, off, n = orc.ready_batch_packed(st, tto, np.ones(5), np.arange(5), 4)
+    assert n.tolist() == [4] and off.tolist() == [[0, 3, 5, 9, 12, 12]]
+    _, off, n = orc.ready_batch_packed(st, tto, np.ones(5), np.arange(5), 3)
+    assert n.tolist() == [4] and off.tolist() == [[0, 3, 5, 9, 12, 12]]
+    # a budget of one row: every trajectory with rows by itself; a budget of everything: one part
+    _, off, n = orc.ready_batch_packed(st, tto, np.ones(5), np.arange(5), 1)
+    assert n.tolist() == [5] and off.tolist() == [[0, 3, 5, 9, 10, 12]]
+    _, off, n = orc.ready_batch_packed(st, tto, np.ones(5), np.arange(5), 12)
+    assert n.tolist() == [1] and off.tolist() == [[0, 12, 12, 12, 12, 12]]
+    # shuffled and filtered: order 4, 2, 0, 3, 1 without trajectory 3 -> rows 2, 4, 3, 2; budget 6: 2 + 4 | 3 + 2
+    rows, off, n = orc.ready_batch_packed(st, tto, np.array([1, 1, 1, 0, 1]), np.array([4, 2, 0, 3, 1]), 6)
+    assert rows.tolist() == [10, 11, 5, 6, 7, 8, 0, 1, 2, 3, 4] and n.tolist() == [2] and off.tolist() == [[0, 6, 11, 11, 11, 11]]
+    # nothing kept: no part
+    rows, off, n = orc.ready_batch_packed(st, tto, np.zeros(5), np.arange(5), 6)
+    assert len(rows) == 0 and n.tolist() == [0] and not off.any()
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4, 5, 6])
+def test_ready_batch_packed_properties(seed):
+    """What fixes a next-fit packing: the rows and their order are those of the plain ready batch; cuts lie between
+    trajectories; no part is empty; a part is over the budget only if it is one trajectory; and no cut could have come
+    later (a part together with the first trajectory of the next one is over the budget).  With trajectory sizes that
+    all fit, the number of parts is at least ceil(T / budget) and less than 2 T / budget + 1 (two neighbouring parts
+    together always exceed the budget)."""
+    st, tto, turn_traj = _routed(seed, n_traj=11)
+    n_traj = len(tto) - 1
+    rng = np.random.default_rng(300 + seed)
+    keep = (rng.random(n_traj) < 0.85).astype(np.uint8)
+    order = rng.permutation(n_traj)
+    budget = int(rng.integers(1, 12))
+    rows, off, n_parts = orc.ready_batch_packed(st, tto, keep, order, budget)
+    rows1, off1 = orc.ready_batch(st, tto, keep, order, 1)
+    assert np.array_equal(rows, rows1)
+    for m in range(len(st["model_tok_off"]) - 1):
+        a = int(st["model_tok_off"][m])
+        k = int(n_parts[m])
+        assert off[m, 0] == off1[m, 0] and (off[m, k:] == off1[m, 1]).all()
+        sizes = np.diff(off[m, :k + 1])
+        assert (sizes > 0).all()
+        base = int(off[m, 0])
+        traj_of = [int(turn_traj[st["tok_turn"][a + r]]) for r in rows[base:int(off1[m, 1])]]   # of the model's rows
+        for p in range(k):
+            lo, hi = int(off[m, p]) - base, int(off[m, p + 1]) - base
+            trajs = traj_of[lo:hi]
+            if p + 1 < k:
+                assert trajs[-1] != traj_of[hi]                                    # the cut lies between two trajectories
+                first_next = traj_of[hi]
+                size_next = sum(1 for t in traj_of[hi:int(off[m, p + 2]) - base] if t == first_next)
+                assert sizes[p] + size_next > budget                             # the next trajectory did not fit
+            if sizes[p] > budget:
+                assert len(set(trajs)) == 1
+        T = len(traj_of)
+        assert T == int(off[m, k] - off[m, 0])
+        biggest = max([traj_of.count(t) for t in set(traj_of)], default=0)
+        if T and biggest <= budget:
+            assert -(-T // budget) <= k < 2 * T / budget + 1
