@@ -378,6 +378,24 @@ umas_status umas_ready_batch_balanced(const umas_streams* streams, int32_t n_mod
                                       const int32_t* traj_order, int32_t n_minibatch, int32_t* mb_rowsel,
                                       int64_t* mb_off, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same list of rows cut into micro-batches under a budget of scored rows: sequence packing, i.e. whole sequences
+ * laid end to end in a flat batch until it is full (Section "Model-Local Buffers": a ready batch is matched to the worker
+ * group's configuration; the paper prints no rule).  Per model, going through the kept trajectories in shuffled order, a
+ * trajectory's rows join the open part unless that part already holds rows and would then hold more than max_rows;
+ * then the part is closed and the trajectory opens the next one.  Trajectories are never split: one with more than
+ * max_rows rows has a part to itself.  No part is empty; a model without kept rows has no part.
+ *   max_rows  >= 1 (UMAS_EINVAL otherwise)
+ *   mb_off    DEVICE int64 [n_models * (n_traj + 1)]: part k < n_parts[m] of model m is
+ *             mb_rowsel[mb_off[m*(n_traj+1) + k] .. mb_off[m*(n_traj+1) + k + 1]); entries past n_parts[m] repeat the end
+ *   n_parts   DEVICE int32 [n_models]
+ * Other arguments, workspace and errors as umas_ready_batch.  The cuts are found part after part by one wavefront
+ * per model (one search per part): meant for budgets that give tens to thousands of parts, not one per trajectory. */
+umas_status umas_ready_batch_packed(const umas_streams* streams, int32_t n_models, int32_t n_turns,
+                                    const int32_t* traj_turn_off, int32_t n_traj, const uint8_t* traj_keep,
+                                    const int32_t* traj_order, int64_t max_rows, int32_t* mb_rowsel,
+                                    int64_t* mb_off, int32_t* n_parts, void* workspace, size_t workspace_bytes,
+                                    void* hip_stream);
+
 /* Kernel timing aid for benchmarks (not part of the method).  While enabled, every kernel launch
  * of the library is followed by a HIP event on its stream and the time between consecutive events
  * of one call is booked to the kernel launched in between.  umas_profile_enable(on) discards earlier

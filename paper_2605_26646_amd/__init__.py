@@ -11,6 +11,6 @@ from .binding import (  # noqa: F401
     umas_policy_logprobs_static, STATIC_SCRATCH_BYTES,
     ppo_workspace_bytes, read_stats, profile_enable, profile_read,
     umas_values, umas_value_loss_fwd_bwd, read_value_stats, umas_kl_rewards, umas_whiten_advantages,
-    WHITEN_MODEL, WHITEN_MODEL_ROLE, umas_ready_batch,
+    WHITEN_MODEL, WHITEN_MODEL_ROLE, umas_ready_batch, umas_ready_batch_packed,
     PLACE_LAST, PLACE_ALL, SEG_TURN, SEG_TRAJ,
 )

@@ -457,6 +457,31 @@ def umas_ready_batch(streams: Streams, traj_turn_off, n_minibatch, traj_keep=Non
     return mb_rowsel, mb_off
 
 
+def umas_ready_batch_packed(streams: Streams, traj_turn_off, max_rows, traj_keep=None, traj_order=None):
+    """Returns (mb_rowsel device int32, mb_off device int64 [n_models, n_traj + 1], n_parts device int32 [n_models]):
+    micro-batches of whole trajectories under a budget of max_rows scored rows."""
+    lib = load_library()
+    lib.umas_ready_batch_workspace_bytes.restype = C.c_size_t
+    lib.umas_ready_batch_workspace_bytes.argtypes = [C.c_int32, C.c_int32]
+    fn = lib.umas_ready_batch_packed
+    fn.restype = C.c_int
+    fn.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                   C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    dev = streams.rowsel.device
+    tto_keep, tto = _host(traj_turn_off, np.int32)
+    n_traj = len(tto_keep) - 1
+    keep_keep, keep = _host(traj_keep, np.uint8)
+    order_keep, order = _host(traj_order, np.int32)
+    mb_rowsel = torch.empty(max(int(streams.rowsel.numel()), 1), dtype=torch.int32, device=dev)
+    mb_off = torch.empty((streams.n_models, n_traj + 1), dtype=torch.int64, device=dev)
+    n_parts = torch.empty(streams.n_models, dtype=torch.int32, device=dev)
+    ws = _workspace(lib.umas_ready_batch_workspace_bytes(n_traj, streams.n_models), dev)
+    cs = streams._c()
+    _check(lib, fn(C.addressof(cs), streams.n_models, streams.n_turns, tto, n_traj, keep, order, int(max_rows),
+                   mb_rowsel.data_ptr(), mb_off.data_ptr(), n_parts.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+    return mb_rowsel, mb_off, n_parts
+
+
 def read_value_stats(stats: torch.Tensor) -> np.ndarray:
     return stats.cpu().numpy().view(VALUE_STATS_DTYPE)
 

@@ -227,6 +227,40 @@ k_mb_copy(int n_models, int n_traj, const int64_t* __restrict__ n_kept_p, const 
   }
 }
 
+// Parts under a budget of scored rows, one wavefront per model: starting from the model's first row, a part ends at
+// the last trajectory boundary within max_rows rows of its start, or, when not even the first trajectory fits, behind
+// that trajectory.  scan_mq holds the model's rows before each kept trajectory (kept rank order), so a boundary is found
+// by one wavefront-wide search per part; every part holds at least one row, so the walk ends after at most as many
+// steps as the model has rows.  Entries of the offsets past the last part repeat the model's end.
+__global__ void __launch_bounds__(kWave)
+k_mb_pack(int n_traj, int64_t max_rows, const int64_t* __restrict__ n_kept_p, const int64_t* __restrict__ scan_mq,
+          const int64_t* __restrict__ totals, int64_t* __restrict__ mb_off, int32_t* __restrict__ n_parts) {
+  const int m = blockIdx.x, lane = threadIdx.x;
+  const int n_kept = static_cast<int>(*n_kept_p);
+  const int64_t* row = scan_mq + static_cast<size_t>(m) * n_traj;
+  const int64_t total = totals[m];
+  int64_t base = 0;
+  for (int mm = 0; mm < m; ++mm) base += totals[mm];
+  int64_t* out = mb_off + static_cast<size_t>(m) * (static_cast<size_t>(n_traj) + 1);
+  if (lane == 0) out[0] = base;
+  int k = 0;
+  int64_t at = 0;                                    // first row of the open part, relative to the model's first
+  while (at < total) {                               // n_kept >= 1 here
+    const int64_t limit = at + max_rows;
+    int64_t end = total;
+    if (total > limit) {
+      const int j = wave_last_le(row, n_kept - 1, limit);     // row[0] = 0 <= limit
+      end = row[j];
+      if (end == at) end = j + 1 < n_kept ? row[j + 1] : total;   // the trajectory at the part's start is over the budget by itself
+    }
+    ++k;
+    if (lane == 0) out[k] = base + end;
+    at = end;
+  }
+  if (lane == 0) n_parts[m] = k;
+  for (int64_t i = k + 1 + lane; i <= n_traj; i += kWave) out[i] = base + total;
+}
+
 struct BatchWs {
   int32_t* traj_turn_off;
   int32_t* order;
@@ -238,6 +272,7 @@ struct BatchWs {
   int64_t* cnt_mq;   // [n_models][n_traj], scanned in place
   int64_t* src_mq;   // [n_models][n_traj]
   int64_t* totals;   // [n_models]
+  int64_t* one_off;  // [n_models][2] the scan kernel's offsets when the parts are cut by k_mb_pack
 };
 inline int scan_tiles(int n_traj) { return static_cast<int>(cdiv(n_traj > 0 ? n_traj : 1, kScanTile)); }
 size_t carve_batch(Carver& c, BatchWs& w, int n_traj, int n_models) {
@@ -251,6 +286,7 @@ size_t carve_batch(Carver& c, BatchWs& w, int n_traj, int n_models) {
   w.cnt_mq = c.take<int64_t>(static_cast<size_t>(n_models) * n_traj);
   w.src_mq = c.take<int64_t>(static_cast<size_t>(n_models) * n_traj);
   w.totals = c.take<int64_t>(n_models);
+  w.one_off = c.take<int64_t>(2 * static_cast<size_t>(n_models));
   return c.off;
 }
 
@@ -269,7 +305,10 @@ extern "C" size_t umas_ready_batch_workspace_bytes(int32_t n_traj, int32_t n_mod
 namespace {
 umas_status ready_batch(const umas_streams* s, int32_t n_models, int32_t n_turns, const int32_t* traj_turn_off, int32_t n_traj,
                         const uint8_t* traj_keep, const int32_t* traj_order, int32_t n_minibatch, int balance_rows,
-                        int32_t* mb_rowsel, int64_t* mb_off, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                        int64_t max_rows, int32_t* n_parts, int32_t* mb_rowsel, int64_t* mb_off, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  const bool packed = n_parts != nullptr;           // parts under a row budget instead of n_minibatch parts
+  UMAS_REQUIRE(!packed || max_rows >= 1, UMAS_EINVAL, "max_rows=%lld must be at least 1", static_cast<long long>(max_rows));
   UMAS_REQUIRE(s && s->traj_seg_off && s->model_trajrun_off && s->model_tok_off && s->model_rowsel_off && s->rowsel && s->tok_turn,
                UMAS_EINVAL, "streams lacks traj_seg_off, model_trajrun_off, model_tok_off, model_rowsel_off, rowsel or tok_turn");
   UMAS_REQUIRE(n_models >= 1 && n_models <= UMAS_MAX_MODELS, UMAS_ESHAPE, "n_models=%d outside [1,%d]", n_models, UMAS_MAX_MODELS);
@@ -328,9 +367,13 @@ umas_status ready_batch(const umas_streams* s, int32_t n_models, int32_t n_turns
                        w.rank, w.cnt_mq, w.src_mq);
     UMAS_LAUNCHED("k_run_slices");
   }
-  hipLaunchKernelGGL(k_mb_scan, dim3(std::min(n_models * ntile, kPerCu * n_cu)), dim3(256), 0, st, n_models, n_traj, ntile, n_minibatch,
-                     balance_rows, w.n_kept, w.cnt_mq, w.part_mq, w.totals, mb_off);
+  hipLaunchKernelGGL(k_mb_scan, dim3(std::min(n_models * ntile, kPerCu * n_cu)), dim3(256), 0, st, n_models, n_traj, ntile,
+                     packed ? 1 : n_minibatch, balance_rows, w.n_kept, w.cnt_mq, w.part_mq, w.totals, packed ? w.one_off : mb_off);
   UMAS_LAUNCHED("k_mb_scan");
+  if (packed) {
+    hipLaunchKernelGGL(k_mb_pack, dim3(n_models), dim3(kWave), 0, st, n_traj, max_rows, w.n_kept, w.cnt_mq, w.totals, mb_off, n_parts);
+    UMAS_LAUNCHED("k_mb_pack");
+  }
   if (n_mq > 0) {
     hipLaunchKernelGGL(k_mb_copy, dim3(cdiv(n_mq, 4)), dim3(256), 0, st, n_models, n_traj, w.n_kept, w.cnt_mq, w.src_mq,
                        w.totals, s->rowsel, mb_rowsel);
@@ -344,14 +387,24 @@ extern "C" umas_status umas_ready_batch(const umas_streams* s, int32_t n_models,
                                         const int32_t* traj_turn_off, int32_t n_traj, const uint8_t* traj_keep,
                                         const int32_t* traj_order, int32_t n_minibatch, int32_t* mb_rowsel,
                                         int64_t* mb_off, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return ready_batch(s, n_models, n_turns, traj_turn_off, n_traj, traj_keep, traj_order, n_minibatch, 0, mb_rowsel, mb_off, workspace,
-                     workspace_bytes, hip_stream);
+  return ready_batch(s, n_models, n_turns, traj_turn_off, n_traj, traj_keep, traj_order, n_minibatch, 0, 0, nullptr, mb_rowsel, mb_off,
+                     workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" umas_status umas_ready_batch_balanced(const umas_streams* s, int32_t n_models, int32_t n_turns,
                                                  const int32_t* traj_turn_off, int32_t n_traj, const uint8_t* traj_keep,
                                                  const int32_t* traj_order, int32_t n_minibatch, int32_t* mb_rowsel,
                                                  int64_t* mb_off, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return ready_batch(s, n_models, n_turns, traj_turn_off, n_traj, traj_keep, traj_order, n_minibatch, 1, mb_rowsel, mb_off, workspace,
-                     workspace_bytes, hip_stream);
+  return ready_batch(s, n_models, n_turns, traj_turn_off, n_traj, traj_keep, traj_order, n_minibatch, 1, 0, nullptr, mb_rowsel, mb_off,
+                     workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" umas_status umas_ready_batch_packed(const umas_streams* s, int32_t n_models, int32_t n_turns,
+                                               const int32_t* traj_turn_off, int32_t n_traj, const uint8_t* traj_keep,
+                                               const int32_t* traj_order, int64_t max_rows, int32_t* mb_rowsel,
+                                               int64_t* mb_off, int32_t* n_parts, void* workspace, size_t workspace_bytes,
+                                               void* hip_stream) {
+  UMAS_REQUIRE(n_parts, UMAS_EINVAL, "n_parts must not be NULL");
+  return ready_batch(s, n_models, n_turns, traj_turn_off, n_traj, traj_keep, traj_order, 1, 0, max_rows, n_parts, mb_rowsel, mb_off,
+                     workspace, workspace_bytes, hip_stream);
 }

@@ -167,3 +167,40 @@ def ready_batch(w, st, keep, order, M, balanced):
         off[m] = base + np.concatenate([[0], np.cumsum(per_part)])
         base += total
     return rows, off
+
+
+def ready_batch_packed(w, st, keep, order, max_rows):
+    """Micro-batches under a budget of scored rows: the rows of ready_batch; per model, from the prefix sums of the
+    kept trajectories' row counts, a part ends at the last trajectory boundary within max_rows rows of its start, or
+    behind the trajectory at its start when that one alone is over the budget (a search per part).
+    Returns (rows, off [n_models, n_traj + 1], n_parts)."""
+    K, B = w.n_models, w.n_traj
+    rows, off1 = ready_batch(w, st, keep, order, 1, False)
+    _, traj_of_turn = turn_steps(w)
+    scored = np.flatnonzero(st["tok_mask"])
+    model_of = np.searchsorted(st["model_tok_off"], scored, side="right") - 1
+    traj_of = traj_of_turn[st["tok_turn"][scored]]
+    order = np.arange(B) if order is None else np.asarray(order, np.int64)
+    kept = order if keep is None else order[np.asarray(keep)[order] != 0]
+    rank = np.full(B, -1, np.int64)
+    rank[kept] = np.arange(len(kept))
+    sel = rank[traj_of] >= 0 if len(scored) else np.zeros(0, bool)
+    cnt = np.zeros((K, len(kept)), np.int64)
+    np.add.at(cnt, (model_of[sel], rank[traj_of[sel]]), 1)
+    off = np.zeros((K, B + 1), np.int64)
+    n_parts = np.zeros(K, np.int32)
+    for m in range(K):
+        bounds = np.concatenate([[0], np.cumsum(cnt[m])])        # row boundaries between the kept trajectories
+        bounds = np.unique(bounds)                                # trajectories without rows add no boundary
+        total, at, cuts = int(bounds[-1]), 0, [0]
+        while at < total:
+            j = int(np.searchsorted(bounds, at + max_rows, side="right")) - 1
+            end = int(bounds[j])
+            if end == at:
+                end = int(bounds[j + 1])
+            cuts.append(end)
+            at = end
+        n_parts[m] = len(cuts) - 1
+        off[m, :] = off1[m, 0] + total
+        off[m, :len(cuts)] = off1[m, 0] + np.array(cuts)
+    return rows, off, n_parts

@@ -182,6 +182,12 @@ def test_entry_points_around_the_update_reject_bad_arguments(lib):
     assert st == -1 and "permutation" in lib.umas_last_error().decode()
     assert lib.umas_ready_batch(C.addressof(s), 1, 2, tto.ctypes.data, 2, None, None, 0, 256, 256, 256, 1 << 20, None) == -1
     assert lib.umas_ready_batch(C.addressof(s), 1, 3, tto.ctypes.data, 2, None, None, 1, 256, 256, 256, 1 << 20, None) == -1
+    lib.umas_ready_batch_packed.restype = C.c_int
+    lib.umas_ready_batch_packed.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                            C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    assert lib.umas_ready_batch_packed(C.addressof(s), 1, 2, tto.ctypes.data, 2, None, None, 0, 256, 256, 256, 256, 1 << 20, None) == -1
+    assert "max_rows" in lib.umas_last_error().decode()
+    assert lib.umas_ready_batch_packed(C.addressof(s), 1, 2, tto.ctypes.data, 2, None, None, 5, 256, 256, None, 256, 1 << 20, None) == -1
 
 
 def test_benchmark_refuses_more_than_one_gpu():

@@ -128,6 +128,14 @@ def check_ready_batch_arraywise(w, s, sa, keep, order, M):
         rows, mb_off = umas.umas_ready_batch(s, w.traj_turn_off, M, keep, order, balance_rows=balanced)
         assert np.array_equal(mb_off.cpu().numpy(), want_off), f"part offsets, balanced={balanced}"
         assert np.array_equal(rows.cpu().numpy()[:len(want_rows)], want_rows), f"rows, balanced={balanced}"
+    # packed under a budget of rows: a budget that gives about 3 M parts per model
+    total = int(sa["model_rowsel_off"][-1])
+    budget = max(total // (3 * M * w.n_models), 1)
+    want_rows, want_off, want_n = aw.ready_batch_packed(w, sa, keep, order, budget)
+    rows, mb_off, n_parts = umas.umas_ready_batch_packed(s, w.traj_turn_off, budget, keep, order)
+    assert np.array_equal(n_parts.cpu().numpy(), want_n), f"numbers of parts, budget {budget}"
+    assert np.array_equal(mb_off.cpu().numpy(), want_off), f"part offsets, budget {budget}"
+    assert np.array_equal(rows.cpu().numpy()[:len(want_rows)], want_rows), f"rows, budget {budget}"
 
 
 def test_shaping_and_ready_batch_at_bandwidth_sizes():

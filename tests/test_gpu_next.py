@@ -271,7 +271,20 @@ def ready_case(cfg, n_minibatch, seed, drop=0.25, **kw):
     rows_b, off_b = umas.umas_ready_batch(s, w.traj_turn_off, n_minibatch, keep, order, balance_rows=True)
     assert np.array_equal(off_b.cpu().numpy(), off_bo), "minibatch offsets differ (cut by rows)"
     assert np.array_equal(rows_b.cpu().numpy()[:len(rows_bo)], rows_bo), "minibatch rows differ (cut by rows)"
+    biggest = int(np.diff(off_o[:, [0, -1]]).max())
+    for budget in (1, 7, max(biggest // 9, 1), max(biggest // 2, 1), biggest + 5):
+        check_packed(w, st, s, keep, order, budget)
     return w, st, s, adv_o, adv, rows, off, off_o, rows_o
+
+
+def check_packed(w, st, s, keep, order, budget):
+    """The ready batch packed under a budget of scored rows against the oracle, bit for bit."""
+    rows_o, off_o, n_o = orc.ready_batch_packed(st, w.traj_turn_off, np.ones(w.n_traj, np.uint8) if keep is None else keep,
+                                                np.arange(w.n_traj) if order is None else order, budget)
+    rows, off, n = umas.umas_ready_batch_packed(s, w.traj_turn_off, budget, keep, order)
+    assert np.array_equal(n.cpu().numpy(), n_o), f"numbers of parts differ, budget {budget}"
+    assert np.array_equal(off.cpu().numpy(), off_o), f"part offsets differ, budget {budget}"
+    assert np.array_equal(rows.cpu().numpy()[:len(rows_o)], rows_o), f"packed rows differ, budget {budget}"
 
 
 def test_ready_batch_index_work_is_exact():
@@ -294,6 +307,9 @@ def test_ready_batch_index_work_is_exact():
     assert np.array_equal(off.cpu().numpy()[:, 0], st["model_rowsel_off"][:-1])
     with pytest.raises(umas.UmasError):
         umas.umas_ready_batch(s, w.traj_turn_off, 2, None, np.zeros(w.n_traj, np.int32))   # not a permutation
+    check_packed(w, st, s, None, None, 3000)                       # defaults: keep all, identity order
+    with pytest.raises(umas.UmasError):
+        umas.umas_ready_batch_packed(s, w.traj_turn_off, 0)
 
 
 def test_minibatch_gradients_accumulate():
@@ -558,6 +574,7 @@ def test_random_graphs_around_the_update(seed):
     _, off_bo = orc.ready_batch(st, w.traj_turn_off, keep, order, n_parts, balance_rows=True)
     _, off_b = umas.umas_ready_batch(s, w.traj_turn_off, n_parts, keep, order, balance_rows=True)
     assert np.array_equal(off_b.cpu().numpy(), off_bo), "minibatch offsets differ (cut by rows)"
+    check_packed(w, st, s, keep, order, int(rng.choice([1, 3, 40, 700, 10 ** 6])))
     logp = (-3.0 * rng.random(n)).astype(np.float32)
     logp_ref = (logp + 0.1 * rng.normal(size=n)).astype(np.float32)
     r_o, kl_o = orc.kl_penalised_rewards(r, logp, logp_ref, st["tok_mask"], 0.05)

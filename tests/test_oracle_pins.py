@@ -664,4 +664,9 @@ def test_array_wise_restatement_agrees_with_the_sequential_oracle_on_random_grap
                                             np.arange(w.n_traj) if order is None else order, M, balance_rows=balanced)
             rows_a, off_a = aw.ready_batch(w, sa, keep, order, M, balanced)
             assert np.array_equal(rows_a, rows_o) and np.array_equal(off_a, off_o), f"seed {seed}: ready batch, balanced={balanced}"
+        budget = int(rng.choice([1, 2, 9, 70, 2000, 10 ** 7]))
+        rows_o, off_o, n_o = orc.ready_batch_packed(st, w.traj_turn_off, np.ones(w.n_traj, np.uint8) if keep is None else keep,
+                                                    np.arange(w.n_traj) if order is None else order, budget)
+        rows_a, off_a, n_a = aw.ready_batch_packed(w, sa, keep, order, budget)
+        assert np.array_equal(rows_a, rows_o) and np.array_equal(off_a, off_o) and np.array_equal(n_a, n_o), f"seed {seed}: packed, budget {budget}"
     assert done >= 150
