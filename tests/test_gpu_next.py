@@ -388,6 +388,45 @@ def test_micro_batches_add_up_to_the_minibatch(dtype, entropy_coef):
                                    s.tok_role[:n].contiguous(), w.n_roles, w.clip_eps, norm_rows=sizes[0] - 1)
 
 
+def test_packed_micro_batches_add_up_to_the_batch():
+    """A ready batch packed under a row budget: as many micro-batches as the device says, each call normalised by the
+    batch's row count, offsets and counts read back from the device; loss, dH and the accumulated dW equal the oracle's
+    on all kept rows."""
+    w, st, s, adv_o, adv, rows_g, off_g, off_o, rows_o = ready_case(2, 1, 23, n_traj=9, tokens_per_turn=48, models=[(200, 1000, "bf16")])
+    rng = np.random.default_rng(23)                      # the same keep and order as ready_case drew
+    keep = (rng.random(w.n_traj) >= 0.25).astype(np.uint8)
+    keep[int(rng.integers(0, w.n_traj))] = 1
+    order = rng.permutation(w.n_traj).astype(np.int32)
+    S = int(off_o[0, 1] - off_o[0, 0])
+    budget = S // 4
+    rows, off, n_parts = umas.umas_ready_batch_packed(s, w.traj_turn_off, budget, keep, order)
+    k_parts = int(n_parts[0].item())
+    off = off.cpu().numpy()[0]
+    assert k_parts >= 4 and off[0] == 0 and off[k_parts] == S
+    assert np.array_equal(rows.cpu().numpy()[:S], rows_o[:S])
+    t = w.model_tensors(0)
+    H, W, ids = P.to_dev(t["H"], torch.bfloat16), P.to_dev(t["W"], torch.bfloat16), P.to_dev(t["ids"])
+    n = w.model_ntok[0]
+    rr_all = rows_o[:S]
+    logp_o, lse_o, ent_o = orc.score(t["H"], t["W"], t["ids"], rr_all)
+    logp_old = (logp_o + t["noise"]).astype(np.float32)
+    stats_o, g_o = orc.ppo_loss(logp_o, logp_old, adv_o[:n], ent_o, rr_all, st["tok_role"][:n], w.n_roles, w.clip_eps)
+    dH_o, dW_o = orc.lm_head_backward(t["H"], t["W"], t["ids"], lse_o, g_o, rr_all)
+    dW = torch.empty((1000, 200), dtype=torch.float32, device="cuda")
+    dH_sum, loss_sum = np.zeros(t["H"].shape), 0.0
+    for k in range(k_parts):
+        a, e = int(off[k]), int(off[k + 1])
+        assert 0 < e - a
+        stats, _, dH, _ = umas.umas_ppo_loss_fwd_bwd(H, W, ids, rows[a:e], P.to_dev(logp_old), adv[:n].contiguous(),
+                                                     s.tok_role[:n].contiguous(), w.n_roles, w.clip_eps,
+                                                     accumulate_dW=(k > 0), norm_rows=S, dW=dW)
+        loss_sum += float(umas.read_stats(stats)["loss"][0])
+        dH_sum += dH.float().cpu().numpy().astype(np.float64)
+    assert abs(loss_sum - stats_o[0, 0]) <= 1e-2 * max(abs(stats_o[0, 0]), 1e-3)
+    P.close(dH_sum, dH_o, 1e-2, "dH over the packed micro-batches")
+    P.close(dW.cpu().numpy(), dW_o, 1e-2, "dW accumulated over the packed micro-batches")
+
+
 def test_critic_micro_batches_add_up_to_the_minibatch():
     w, st, s, adv_o, adv, rows, off, off_o, rows_o = ready_case(2, 3, 19, n_traj=7, tokens_per_turn=48, models=[(200, 1000, "bf16")])
     rho, st2, r, adv2, ret_o = P.oracle_front(w)
