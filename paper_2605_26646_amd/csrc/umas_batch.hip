@@ -232,33 +232,38 @@ k_mb_copy(int n_models, int n_traj, const int64_t* __restrict__ n_kept_p, const 
 // that trajectory.  scan_mq holds the model's rows before each kept trajectory (kept rank order), so a boundary is found
 // by one wavefront-wide search per part; every part holds at least one row, so the walk ends after at most as many
 // steps as the model has rows.  Entries of the offsets past the last part repeat the model's end.
-__global__ void __launch_bounds__(kWave)
+constexpr int kPackThreads = 1024;
+__global__ void __launch_bounds__(kPackThreads)
 k_mb_pack(int n_traj, int64_t max_rows, const int64_t* __restrict__ n_kept_p, const int64_t* __restrict__ scan_mq,
           const int64_t* __restrict__ totals, int64_t* __restrict__ mb_off, int32_t* __restrict__ n_parts) {
-  const int m = blockIdx.x, lane = threadIdx.x;
+  __shared__ int s_parts;
+  const int m = blockIdx.x, tid = threadIdx.x;
   const int n_kept = static_cast<int>(*n_kept_p);
   const int64_t* row = scan_mq + static_cast<size_t>(m) * n_traj;
   const int64_t total = totals[m];
   int64_t base = 0;
   for (int mm = 0; mm < m; ++mm) base += totals[mm];
   int64_t* out = mb_off + static_cast<size_t>(m) * (static_cast<size_t>(n_traj) + 1);
-  if (lane == 0) out[0] = base;
-  int k = 0;
-  int64_t at = 0;                                    // first row of the open part, relative to the model's first
-  while (at < total) {                               // n_kept >= 1 here
-    const int64_t limit = at + max_rows;
-    int64_t end = total;
-    if (total > limit) {
-      const int j = wave_last_le(row, n_kept - 1, limit);     // row[0] = 0 <= limit
-      end = row[j];
-      if (end == at) end = j + 1 < n_kept ? row[j + 1] : total;   // the trajectory at the part's start is over the budget by itself
+  if (tid < kWave) {                                 // the walk is one wavefront's; the others help with the tail afterwards
+    if (tid == 0) out[0] = base;
+    int k = 0;
+    int64_t at = 0;                                  // first row of the open part, relative to the model's first
+    while (at < total) {                             // n_kept >= 1 here
+      const int64_t limit = at + max_rows;
+      int64_t end = total;
+      if (total > limit) {
+        const int j = wave_last_le(row, n_kept - 1, limit);     // row[0] = 0 <= limit
+        end = row[j];
+        if (end == at) end = j + 1 < n_kept ? row[j + 1] : total;   // the trajectory at the part's start is over the budget by itself
+      }
+      ++k;
+      if (tid == 0) out[k] = base + end;
+      at = end;
     }
-    ++k;
-    if (lane == 0) out[k] = base + end;
-    at = end;
+    if (tid == 0) { n_parts[m] = k; s_parts = k; }
   }
-  if (lane == 0) n_parts[m] = k;
-  for (int64_t i = k + 1 + lane; i <= n_traj; i += kWave) out[i] = base + total;
+  __syncthreads();
+  for (int64_t i = s_parts + 1 + tid; i <= n_traj; i += kPackThreads) out[i] = base + total;
 }
 
 struct BatchWs {
@@ -371,7 +376,7 @@ umas_status ready_batch(const umas_streams* s, int32_t n_models, int32_t n_turns
                      packed ? 1 : n_minibatch, balance_rows, w.n_kept, w.cnt_mq, w.part_mq, w.totals, packed ? w.one_off : mb_off);
   UMAS_LAUNCHED("k_mb_scan");
   if (packed) {
-    hipLaunchKernelGGL(k_mb_pack, dim3(n_models), dim3(kWave), 0, st, n_traj, max_rows, w.n_kept, w.cnt_mq, w.totals, mb_off, n_parts);
+    hipLaunchKernelGGL(k_mb_pack, dim3(n_models), dim3(kPackThreads), 0, st, n_traj, max_rows, w.n_kept, w.cnt_mq, w.totals, mb_off, n_parts);
     UMAS_LAUNCHED("k_mb_pack");
   }
   if (n_mq > 0) {
