@@ -231,6 +231,18 @@ def hbm_kernels(umas, wl, torch, cfg, n_traj, iters=5, shaping=False, traj_scan=
         rb = [k for k in p2 if k not in used]
         extra["ready_batch"] = entry(sum(p2[k][0] for k in rb) / iters, 8 * kept_scored)
         extra["ready_batch"]["kernels_ms"] = {k: p2[k][0] / iters for k in rb}
+        # the same rows cut under a budget of scored rows that gives about 64 micro-batches
+        budget = max(int(kept_scored) // 64, 1)
+        umas.umas_ready_batch_packed(s, w.traj_turn_off, budget, keep, order)
+        torch.cuda.synchronize()
+        umas.profile_enable(True)
+        for _ in range(iters):
+            _, _, n_parts = umas.umas_ready_batch_packed(s, w.traj_turn_off, budget, keep, order)
+        torch.cuda.synchronize()
+        p4 = umas.profile_read()
+        umas.profile_enable(False)
+        extra["ready_batch_packed"] = {"max_rows": budget, "parts": int(n_parts[0].item()), "ms": sum(v[0] for v in p4.values()) / iters,
+                                       "kernels_ms": {k: v[0] / iters for k, v in p4.items()}}
     return {"workload": f"{w.name} x{n_traj} trajectories", "tokens": N, **extra,
             "scan": entry(scan_ms, scan_bytes), "route_place": entry(route_ms, route_bytes),
             "kernels_ms": {k: v[0] / iters for k, v in prof.items()}}
