@@ -230,7 +230,7 @@ k_mb_copy(int n_models, int n_traj, const int64_t* __restrict__ n_kept_p, const 
 // Parts under a budget of scored rows, one wavefront per model: starting from the model's first row, a part ends at
 // the last trajectory boundary within max_rows rows of its start, or, when not even the first trajectory fits, behind
 // that trajectory.  scan_mq holds the model's rows before each kept trajectory (kept rank order), so a boundary is found
-// by one wavefront-wide search per part; every part holds at least one row, so the walk ends after at most as many
+// by one wavefront-wide search per part (one trip to memory when the part spans fewer than 256 trajectories); every part holds at least one row, so the walk ends after at most as many
 // steps as the model has rows.  Entries of the offsets past the last part repeat the model's end.
 constexpr int kPackThreads = 1024;
 __global__ void __launch_bounds__(kPackThreads)
@@ -248,13 +248,40 @@ k_mb_pack(int n_traj, int64_t max_rows, const int64_t* __restrict__ n_kept_p, co
     if (tid == 0) out[0] = base;
     int k = 0;
     int64_t at = 0;                                  // first row of the open part, relative to the model's first
+    int j0 = 0;                                      // a kept trajectory with row[j0] == at
+    // parts that span fewer than about 200 trajectories on average are looked for among the next 256 entries first
+    const bool near = static_cast<double>(max_rows) * n_kept < 200.0 * static_cast<double>(total);
     while (at < total) {                             // n_kept >= 1 here
       const int64_t limit = at + max_rows;
       int64_t end = total;
       if (total > limit) {
-        const int j = wave_last_le(row, n_kept - 1, limit);     // row[0] = 0 <= limit
-        end = row[j];
-        if (end == at) end = j + 1 < n_kept ? row[j + 1] : total;   // the trajectory at the part's start is over the budget by itself
+        // largest j with row[j] <= limit: with short parts first among the 256 entries from j0 on (one trip;
+        // row[j0] = at <= limit), and only if all of those hold, by the general search behind them
+        const int avail = n_kept - 1 - j0;           // entries j0 .. j0 + avail exist
+        int64_t v[4] = {0, 0, 0, 0};
+        int c = 4 * kWave;
+        if (near) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) v[q] = tid + q * kWave <= avail ? row[j0 + tid + q * kWave] : INT64_MAX;
+          c = 0;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) c += __popcll(__ballot(v[q] <= limit));
+        }
+        int j;
+        if (c < 4 * kWave) {
+          j = j0 + c - 1;
+          const int64_t mine = (c - 1) >> 6 == 0 ? v[0] : (c - 1) >> 6 == 1 ? v[1] : (c - 1) >> 6 == 2 ? v[2] : v[3];
+          end = __shfl(mine, (c - 1) & (kWave - 1), kWave);
+        } else {
+          const int from = near ? 4 * kWave - 1 : 0;   // row[j0 + from] <= limit either way
+          j = j0 + from + wave_last_le(row + j0 + from, avail - from, limit);
+          end = row[j];
+        }
+        if (end == at) {                             // the trajectory at the part's start is over the budget by itself
+          ++j;
+          end = j < n_kept ? row[j] : total;
+        }
+        j0 = j;
       }
       ++k;
       if (tid == 0) out[k] = base + end;
@@ -314,6 +341,7 @@ umas_status ready_batch(const umas_streams* s, int32_t n_models, int32_t n_turns
                         size_t workspace_bytes, void* hip_stream) {
   const bool packed = n_parts != nullptr;           // parts under a row budget instead of n_minibatch parts
   UMAS_REQUIRE(!packed || max_rows >= 1, UMAS_EINVAL, "max_rows=%lld must be at least 1", static_cast<long long>(max_rows));
+  if (max_rows > (int64_t{1} << 62)) max_rows = int64_t{1} << 62;   // more than any batch holds; keeps start + budget inside int64
   UMAS_REQUIRE(s && s->traj_seg_off && s->model_trajrun_off && s->model_tok_off && s->model_rowsel_off && s->rowsel && s->tok_turn,
                UMAS_EINVAL, "streams lacks traj_seg_off, model_trajrun_off, model_tok_off, model_rowsel_off, rowsel or tok_turn");
   UMAS_REQUIRE(n_models >= 1 && n_models <= UMAS_MAX_MODELS, UMAS_ESHAPE, "n_models=%d outside [1,%d]", n_models, UMAS_MAX_MODELS);
