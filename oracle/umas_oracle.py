@@ -14,8 +14,9 @@ the arithmetic open (it names PPO but prints no loss; it does not say which
 token carries a delayed reward) the reading taken is stated in the docstring.
 
 Parity pins (tests/test_oracle_pins.py, tests/test_oracle_pins_next.py): every function below is pinned against
-hand-worked workflow examples, closed forms, invariants or brute force, except
-the end-to-end composition of all steps, which is "parity unpinned" beyond the
+hand-worked workflow examples, closed forms, invariants or brute force.  The
+end-to-end composition of all steps is pinned by one closed form (a uniform
+policy, on-policy, gamma = lam = 1) and is otherwise "parity unpinned" beyond the
 composition of its pinned parts (the paper prints no end-to-end numbers).
 """
 from __future__ import annotations

@@ -696,3 +696,37 @@ def test_row_selections_in_any_order():
     assert np.array_equal(ga["n_scored"], gb["n_scored"])
     assert np.allclose(ga["loss"], gb["loss"], rtol=1e-5, atol=1e-7)
     P.close(dWb.cpu().numpy(), dWa.cpu().numpy().astype(np.float64), 1e-3, "dW, shuffled against ascending rows")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_end_to_end_closed_form_for_a_uniform_policy(dtype):
+    """The whole path on the GPU against the closed form of tests/test_oracle_pins.py (W = 0: a uniform policy; on-policy;
+    gamma = lam = 1, no critic): advantages, log-probs, loss, dH = 0 and dW from the inputs alone, no oracle in between."""
+    from tests.test_oracle_pins import end_to_end_closed_form
+    models = [(64, 512, "f32")] if dtype == "f32" else [(128, 1000, "bf16")]
+    w = wl.make_workload(0, n_traj=6, tokens_per_turn=50, models=models)
+    rng = np.random.default_rng(5)
+    w.tok_mask = (rng.random(w.n_tokens) < 0.7).astype(np.uint8)
+    w.tok_mask[:50] = 0                                           # a turn without any valid token
+    w.turn_reward = rng.normal(size=w.n_turns).astype(np.float32)
+    w.value = None
+    t = w.model_tensors(0)
+    d, V = models[0][0], models[0][1]
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    tol = 1e-5 if dtype == "f32" else 1e-2
+    A, loss, g, dW_c = end_to_end_closed_form(w, t["H"], t["ids"], V)
+    s, adv, ret = P.gpu_front(w, gamma=1.0, lam=1.0, seg_mode=wl.SEG_TURN, place_mode=wl.PLACE_LAST)
+    P.close(adv.cpu().numpy(), A, 1e-5, "advantages")
+    S = int(s.model_rowsel_off[-1].item())
+    assert S == int(w.tok_mask.sum())
+    rows = s.rowsel[:S]
+    H, W0, ids = P.to_dev(t["H"], tdt), torch.zeros((V, d), dtype=tdt, device="cuda"), P.to_dev(t["ids"])
+    stats, logp_new, dH, dW = umas.umas_ppo_loss_fwd_bwd(H, W0, ids, rows, None, adv, s.tok_role, w.n_roles, 0.2)   # on-policy
+    sg = umas.read_stats(stats)
+    lp = logp_new.cpu().numpy()
+    valid = w.tok_mask != 0
+    assert np.abs(lp[valid] + np.log(V)).max() <= (1e-5 if dtype == "f32" else 2e-2) and not lp[~valid].any()
+    assert abs(float(sg["loss"][0]) - loss) <= tol * abs(loss) and float(sg["clip_frac"][0]) == 0 and int(sg["n_scored"][0]) == S
+    assert abs(float(sg["entropy_mean"][0]) - np.log(V)) <= (1e-5 * np.log(V) if dtype == "f32" else 2e-2)
+    assert float(dH.float().abs().max()) == 0.0
+    P.close(dW.cpu().numpy(), dW_c, tol, "dW")

@@ -670,3 +670,59 @@ def test_array_wise_restatement_agrees_with_the_sequential_oracle_on_random_grap
         rows_a, off_a, n_a = aw.ready_batch_packed(w, sa, keep, order, budget)
         assert np.array_equal(rows_a, rows_o) and np.array_equal(off_a, off_o) and np.array_equal(n_a, n_o), f"seed {seed}: packed, budget {budget}"
     assert done >= 150
+
+
+def end_to_end_closed_form(w, H, ids, V):
+    """What the whole path must give for a policy with W = 0 (uniform over the vocabulary), ratio 1, gamma = lam = 1,
+    no critic, turn segments and the reward on a turn's last valid token - written from the inputs alone:
+    every valid token of a turn carries the turn's composed reward as its advantage (the suffix sum of a single
+    reward), log-prob = -ln V, loss = -mean A, g = -A / S, dH = 0 (every row of W is the same), and
+    dW[v] = sum_i g_i (1[v = y_i] - 1/V) h_i.  One model holding all roles: stream order = global order."""
+    f64 = np.float64
+    traj = np.repeat(np.arange(w.n_traj), np.diff(w.traj_turn_off))
+    rho = np.zeros(w.n_turns)
+    if w.role_reward is not None:
+        rho += w.role_reward.astype(f64)[traj * w.n_roles + w.turn_role]
+    if w.turn_reward is not None:
+        rho += w.turn_reward.astype(f64)
+    if w.traj_reward is not None:
+        rho += w.traj_reward.astype(f64)[traj]
+    tok_turn = np.repeat(np.arange(w.n_turns), np.diff(w.turn_tok_off))
+    valid = w.tok_mask != 0
+    A = np.where(valid, rho[tok_turn], 0.0)
+    S = int(valid.sum())
+    g = np.where(valid, -A / S, 0.0)
+    gh = g[:, None] * H.astype(f64)
+    dW = np.zeros((V, H.shape[1]))
+    np.add.at(dW, ids[valid], gh[valid])
+    dW -= gh.sum(axis=0)[None, :] / V
+    return A, -A[valid].mean(), g, dW
+
+
+def test_end_to_end_closed_form_for_a_uniform_policy():
+    """The composition of all steps (rewards -> routing -> placement -> scan -> scoring -> surrogate -> backward) against
+    a closed form that uses none of the oracle's functions: a plausible mistake in how the steps are joined (advantages
+    in the wrong order, the mean over the wrong count, a gradient with the wrong sign) changes the loss or dW."""
+    from tests import parity as P
+    w = wl.make_workload(0)
+    rng = np.random.default_rng(5)
+    w.tok_mask = (rng.random(w.n_tokens) < 0.7).astype(np.uint8)
+    w.tok_mask[:40] = 0                                           # a turn without any valid token
+    w.turn_reward = rng.normal(size=w.n_turns).astype(np.float32)
+    w.value = None
+    t = w.model_tensors(0)
+    V, d = w.models[0].V, w.models[0].d
+    W0 = np.zeros((V, d), np.float32)
+    rho, st, r, adv, ret = P.oracle_front(w, gamma=1.0, lam=1.0, seg_mode=wl.SEG_TURN, place_mode=wl.PLACE_LAST)
+    assert np.array_equal(st["perm"], np.arange(w.n_tokens))
+    A, loss, g, dW = end_to_end_closed_form(w, t["H"], t["ids"], V)
+    assert np.allclose(adv, A, rtol=1e-6, atol=1e-7) and np.allclose(ret, A, rtol=1e-6, atol=1e-7)
+    rows = st["rowsel"]
+    logp, lse, ent = orc.score(t["H"], W0, t["ids"], rows)
+    assert np.allclose(logp[rows], -math.log(V), atol=1e-12) and np.allclose(ent[rows], math.log(V), atol=1e-12)
+    stats, g_o = orc.ppo_loss(logp, logp, adv, ent, rows, st["tok_role"], w.n_roles, 0.2)
+    assert abs(stats[0, 0] - loss) <= 1e-6 * abs(loss) and stats[0, 1] == 0 and stats[0, 4] == len(rows)   # composed rewards are float32
+    assert np.allclose(g_o, g, rtol=1e-6, atol=1e-12)
+    dH_o, dW_o = orc.lm_head_backward(t["H"], W0, t["ids"], lse, g_o, rows)
+    assert not np.abs(dH_o).max() > 1e-15
+    assert np.allclose(dW_o, dW, rtol=1e-6, atol=1e-9)
