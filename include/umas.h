@@ -39,9 +39,10 @@
  *   - One GPU, one process; calls on different streams may run concurrently only with
  *     disjoint outputs and workspaces.  Some kernels of umas_assign_token_rewards,
  *     umas_ready_batch and umas_advantages have workgroups that wait for words published by
- *     their other workgroups; their grids are a fraction of what the device holds at once, so
- *     two or three such calls fit side by side.  Do not run more of them concurrently when
- *     each carries more than 65536 trajectories (or segments of more than 16384 tokens).
+ *     their other workgroups; their grids are at most half of what the device holds at once (a
+ *     quarter with four models or fewer), so two such calls fit side by side (three or four with
+ *     four models or fewer).  Do not run more of them concurrently when each carries more than
+ *     65536 trajectories (or segments of more than 16384 tokens).
  */
 #ifndef UMAS_H
 #define UMAS_H

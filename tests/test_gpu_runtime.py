@@ -151,3 +151,42 @@ def test_binding_refuses_a_row_selection_out_of_range():
             umas.umas_values(H, torch.ones(64, dtype=torch.bfloat16, device="cuda"), 0.0, sel)
         with pytest.raises(umas.UmasError, match="outside"):
             umas.umas_value_loss_fwd_bwd(H, torch.ones(64, dtype=torch.bfloat16, device="cuda"), 0.0, sel, z, z, None, 0, 0.2)
+
+
+def test_two_pipelines_on_two_streams_at_once():
+    """Routing, the scan and the ready batch have kernels whose workgroups wait for words that their other workgroups
+    publish; their grids are a fraction of what the device holds, so two such pipelines on different streams (disjoint
+    outputs and workspaces) run side by side.  Both must give what they give alone."""
+    ws = [wl.make_workload(1, n_traj=20000, tokens_per_turn=64), wl.make_workload(4, n_traj=200, tokens_per_turn=8192)]      # trajectory runs of up to 30 720 tokens: cut inside
+    masks = [P.to_dev(w.tok_mask) for w in ws]
+    values = [None if w.value is None else P.to_dev(w.value) for w in ws]
+    rngs = [np.random.default_rng(50 + i) for i in range(2)]
+    orders = [r.permutation(w.n_traj).astype(np.int32) for r, w in zip(rngs, ws)]
+    keeps = [(r.random(w.n_traj) < 0.9).astype(np.uint8) for r, w in zip(rngs, ws)]
+
+    def pipeline(i):
+        w = ws[i]
+        s = umas.umas_assign_token_rewards(**assign_kwargs(w, masks[i]))
+        adv, ret = umas.umas_advantages(s, values[i], w.gamma, w.lam, 0.97, wl.SEG_TRAJ)
+        rows, off = umas.umas_ready_batch(s, w.traj_turn_off, 8, keeps[i], orders[i])
+        return s, adv, ret, rows, off
+
+    alone = [pipeline(0), pipeline(1)]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]        # default priority
+    got = [None, None]
+    for rep in range(6):                                         # interleaved issue: the two pipelines overlap on the device
+        for i in range(2):
+            with torch.cuda.stream(streams[i]):
+                got[i] = pipeline(i)
+    torch.cuda.synchronize()
+    for i in range(2):
+        (s0, a0, r0, rows0, off0), (s1, a1, r1, rows1, off1) = alone[i], got[i]
+        n_scored = int(s0.model_rowsel_off[-1].item())
+        for f in ("perm", "tok_turn", "tok_flags", "tok_reward", "turn_seg_off", "model_rowsel_off"):
+            assert torch.equal(getattr(s0, f), getattr(s1, f)), f
+        assert torch.equal(s0.rowsel[:n_scored], s1.rowsel[:n_scored])
+        assert torch.equal(a0, a1) and torch.equal(r0, r1)
+        assert torch.equal(off0, off1)
+        n_kept = int(off0[-1, -1].item())
+        assert torch.equal(rows0[:n_kept], rows1[:n_kept])
